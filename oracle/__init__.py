@@ -1,0 +1,234 @@
+"""CPU oracle for the Winograd-aware convolution forward path (Python face).
+
+TEST INFRASTRUCTURE, NOT PRODUCT.  Only the tests, the smoke check and the
+CPU-baseline leg of the benchmark may import this package.  It never imports the
+HIP library or its binding, and the library never imports it.
+
+The arithmetic lives in ``wino_oracle.cpp`` (plain C++, compiled with g++ into
+``liboracle.so`` next to this file) and in ``cook_toom.py`` (exact rationals).
+This module only marshals numpy arrays across ctypes and strings the stages of
+the quantized pipeline together in the order of the paper's Fig. 2 / Sec. 3.2:
+quantize input -> B^T d B -> quantize ; G g G^T -> quantize ; Hadamard product
+summed over input channels -> (optional quantizer) ; A^T M A -> quantize.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+from .cook_toom import DEFAULT_POINTS, cook_toom, cook_toom_exact  # noqa: F401
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "wino_oracle.cpp")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with g++ (no fast-math, no contraction)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["g++", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC",
+           "-o", _LIB, _SRC]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.oracle_q_output.restype = ctypes.c_int64
+        L.oracle_num_threads.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def num_threads():
+    return int(lib().oracle_num_threads())
+
+
+def set_num_threads(nt):
+    lib().oracle_set_num_threads(ctypes.c_int(int(nt)))
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def geometry(N, H, W, pad, m):
+    """Ho, Wo, TH, TW, T, n, P for stride-1 F(m x m, 3 x 3)."""
+    Ho, Wo = H + 2 * pad - 2, W + 2 * pad - 2
+    TH, TW = -(-Ho // m), -(-Wo // m)
+    n = m + 2
+    return dict(Ho=Ho, Wo=Wo, TH=TH, TW=TW, T=N * TH * TW, n=n, P=n * n)
+
+
+# ------------------------------------------------------------------ O1 -----
+def conv2d_direct_f64(X, g, stride=1, pad=1):
+    X = _c(X, np.float64)
+    g = _c(g, np.float64)
+    N, C, H, W = X.shape
+    K = g.shape[0]
+    assert g.shape == (K, C, 3, 3)
+    Ho = (H + 2 * pad - 3) // stride + 1
+    Wo = (W + 2 * pad - 3) // stride + 1
+    Y = np.zeros((N, K, Ho, Wo), np.float64)
+    rc = lib().oracle_conv2d_direct_f64(N, C, K, H, W, stride, pad, _p(X), _p(g), _p(Y))
+    assert rc == 0
+    return Y
+
+
+def conv2d_direct_q(Xq, gq, r_y, qmax=127, stride=1, pad=1):
+    """Integer direct convolution + one requantization; returns (acc int64, y int32)."""
+    Xq = _c(Xq, np.int32)
+    gq = _c(gq, np.int32)
+    N, C, H, W = Xq.shape
+    K = gq.shape[0]
+    assert gq.shape == (K, C, 3, 3)
+    Ho = (H + 2 * pad - 3) // stride + 1
+    Wo = (W + 2 * pad - 3) // stride + 1
+    acc = np.zeros((N, K, Ho, Wo), np.int64)
+    Yq = np.zeros((N, K, Ho, Wo), np.int32)
+    rc = lib().oracle_conv2d_direct_q(N, C, K, H, W, stride, pad, _p(Xq), _p(gq),
+                                      ctypes.c_float(r_y), int(qmax), _p(acc), _p(Yq))
+    assert rc == 0
+    return acc, Yq
+
+
+# ------------------------------------------------------------------ O2 -----
+def winograd_f64(X, g, BT, G, AT, pad=1):
+    X = _c(X, np.float64)
+    g = _c(g, np.float64)
+    BT = _c(BT, np.float64)
+    G = _c(G, np.float64)
+    AT = _c(AT, np.float64)
+    N, C, H, W = X.shape
+    K = g.shape[0]
+    m = AT.shape[0]
+    n = m + 2
+    assert BT.shape == (n, n) and G.shape == (n, 3) and AT.shape == (m, n)
+    Y = np.zeros((N, K, H + 2 * pad - 2, W + 2 * pad - 2), np.float64)
+    rc = lib().oracle_winograd_f64(N, C, K, H, W, pad, m, _p(BT), _p(G), _p(AT),
+                                   _p(X), _p(g), _p(Y))
+    assert rc == 0
+    return Y
+
+
+# ------------------------------------------------------------------ O3 -----
+def q_scalars(s_x, s_v, s_u, s_y, s_m=0.0):
+    out = [ctypes.c_float() for _ in range(4)]
+    lib().oracle_q_scalars(ctypes.c_float(s_x), ctypes.c_float(s_v), ctypes.c_float(s_u),
+                           ctypes.c_float(s_y), ctypes.c_float(s_m),
+                           *[ctypes.byref(o) for o in out])
+    r_u, r_v, r_m, r_y = [np.float32(o.value) for o in out]
+    return dict(r_u=r_u, r_v=r_v, r_m=r_m, r_y=r_y)
+
+
+def q_weights(g, G, r_u=1.0, qmax=127, want_f32=True, want_q=True):
+    """U = G g G^T in pinned fp32; returns (U_f32 [P,K,C] or None, Uq int32 or None)."""
+    g = _c(g, np.float32)
+    G = _c(G, np.float32)
+    K, C = g.shape[:2]
+    n = G.shape[0]
+    m = n - 2
+    P = n * n
+    Uf = np.zeros((P, K, C), np.float32) if want_f32 else None
+    Uq = np.zeros((P, K, C), np.int32) if want_q else None
+    rc = lib().oracle_q_weights(K, C, m, _p(G), _p(g), ctypes.c_float(r_u), int(qmax),
+                                _p(Uf), _p(Uq))
+    assert rc == 0
+    return Uf, Uq
+
+
+def q_input(xq, BT, pad=1, r_v=1.0, qmax=127, want_f32=True, want_q=True):
+    """V = B^T d B per tile in pinned fp32; returns (V_f32 [P,T,C] or None, Vq or None)."""
+    xq = _c(xq, np.int32)
+    BT = _c(BT, np.float32)
+    N, C, H, W = xq.shape
+    n = BT.shape[0]
+    m = n - 2
+    geo = geometry(N, H, W, pad, m)
+    Vf = np.zeros((geo["P"], geo["T"], C), np.float32) if want_f32 else None
+    Vq = np.zeros((geo["P"], geo["T"], C), np.int32) if want_q else None
+    rc = lib().oracle_q_input(N, C, H, W, pad, m, _p(BT), _p(xq), ctypes.c_float(r_v),
+                              int(qmax), _p(Vf), _p(Vq))
+    assert rc == 0
+    return Vf, Vq
+
+
+def q_hadamard(Vq, Uq):
+    """M[p,t,k] = sum_c Vq[p,t,c] Uq[p,k,c], exact int64."""
+    Vq = _c(Vq, np.int32)
+    Uq = _c(Uq, np.int32)
+    P, T, C = Vq.shape
+    K = Uq.shape[1]
+    assert Uq.shape == (P, K, C)
+    M = np.zeros((P, T, K), np.int64)
+    rc = lib().oracle_q_hadamard(P, ctypes.c_int64(T), C, K, _p(Vq), _p(Uq), _p(M))
+    assert rc == 0
+    return M
+
+
+def q_output(M, AT, N, H, W, pad=1, r_m=0.0, r_y=1.0, qmax=127, want_f32=True, want_q=True):
+    """Y tile = A^T M A in pinned fp32; returns (Y_f32 unscaled or None, Yq or None, inexact)."""
+    M = _c(M, np.int64)
+    AT = _c(AT, np.float32)
+    m, n = AT.shape
+    geo = geometry(N, H, W, pad, m)
+    P, T, K = M.shape
+    assert P == geo["P"] and T == geo["T"]
+    Yf = np.zeros((N, K, geo["Ho"], geo["Wo"]), np.float32) if want_f32 else None
+    Yq = np.zeros((N, K, geo["Ho"], geo["Wo"]), np.int32) if want_q else None
+    inexact = lib().oracle_q_output(N, K, H, W, pad, m, _p(AT), _p(M), ctypes.c_float(r_m),
+                                    ctypes.c_float(r_y), int(qmax), _p(Yf), _p(Yq))
+    assert inexact >= 0
+    return Yf, Yq, int(inexact)
+
+
+def quantize_tensor(x, scale, qmax=127):
+    """Per-tensor symmetric quantizer of Sec. 5.1: sat(rne(x / scale)), in fp32."""
+    v = np.asarray(x, np.float32) / np.float32(scale)
+    return np.clip(np.rint(v), -qmax, qmax).astype(np.int32)
+
+
+def calibrate(X, g, BT, G, AT, pad=1, qmax=127):
+    """Static max-abs scales for the four quantizers (stand-in for the paper's
+    warmed-up moving averages, Table 1 caption).  Each scale is the max-abs of the
+    stage's value range divided by qmax, over the whole tensor (per-layer scale,
+    Sec. 5.1), computed with the pipeline's own arithmetic, stage after stage."""
+    f32 = np.float32
+    s_x = f32(np.abs(np.asarray(X, f32)).max() / f32(qmax))
+    xq = quantize_tensor(X, s_x, qmax)
+    Vf, _ = q_input(xq, BT, pad=pad, want_q=False)
+    s_v = f32(s_x * f32(np.abs(Vf).max()) / f32(qmax))
+    Uf, _ = q_weights(g, G, want_q=False)
+    s_u = f32(np.abs(Uf).max() / f32(qmax))
+    sc = q_scalars(s_x, s_v, s_u, 1.0)
+    _, Vq = q_input(xq, BT, pad=pad, r_v=sc["r_v"], qmax=qmax, want_f32=False)
+    _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qmax, want_f32=False)
+    M = q_hadamard(Vq, Uq)
+    N, _, H, W = xq.shape
+    Yf, _, _ = q_output(M, AT, N, H, W, pad=pad, want_q=False)
+    s_y = f32(f32(s_u * s_v) * f32(np.abs(Yf).max()) / f32(qmax))
+    return dict(s_x=float(s_x), s_v=float(s_v), s_u=float(s_u), s_y=float(s_y), s_m=0.0)
+
+
+def winograd_q(xq, g, BT, G, AT, scales, pad=1, qmax=127):
+    """The whole quantized forward, every tap returned.  xq: int input at scale s_x."""
+    sc = q_scalars(scales["s_x"], scales["s_v"], scales["s_u"], scales["s_y"],
+                   scales.get("s_m", 0.0))
+    _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qmax, want_f32=False)
+    _, Vq = q_input(xq, BT, pad=pad, r_v=sc["r_v"], qmax=qmax, want_f32=False)
+    M = q_hadamard(Vq, Uq)
+    N, _, H, W = np.asarray(xq).shape
+    _, Yq, inexact = q_output(M, AT, N, H, W, pad=pad, r_m=sc["r_m"], r_y=sc["r_y"],
+                              qmax=qmax, want_f32=False)
+    return dict(Uq=Uq, Vq=Vq, M=M, Yq=Yq, inexact=inexact, scalars=sc)

@@ -1,0 +1,442 @@
+"""Pins for the CPU oracle: everything here runs without a GPU and checks the
+oracle against things that are NOT the oracle -- exact identities, closed forms,
+brute force, library routines, and the counts the paper prints.
+
+Parity status that these tests cannot provide: with perturbed ("flex")
+transform matrices Eq. 1 no longer equals a direct convolution, so the literal
+Winograd (O2) and the quantized pipeline (O3) with such matrices are "parity
+unpinned" beyond (a) the limit noise -> 0 and (b) the exact-rational emulation
+of the fused chains on tiny cases below.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy.signal import correlate2d
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "paper_counts.txt")
+
+
+def _golden():
+    out = {}
+    for line in open(GOLD):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            out[k.strip()] = float(v)
+    return out
+
+
+def _rel(a, b):
+    return np.abs(a - b).max() / np.abs(b).max()
+
+
+# ---------------------------------------------------------------- P2 / P3 / P6
+@pytest.mark.parametrize("m", [2, 4, 6])
+def test_cook_toom_exact_bilinear_identity(oracle, m):
+    """sum_i A^T[a,i] G[i,b] B^T[i,c] == [c == a+b] exactly (the algebra of Eq. 1:
+    y_a = sum_b d_{a+b} g_b), in rationals -- independent of any convolution code."""
+    BT, G, AT = oracle.cook_toom_exact(m)
+    n = m + 2
+    for a in range(m):
+        for b in range(3):
+            for c in range(n):
+                s = sum(AT[a][i] * G[i][b] * BT[i][c] for i in range(n))
+                assert s == (1 if c == a + b else 0), (m, a, b, c, s)
+
+
+def test_cook_toom_custom_points_identity(oracle):
+    pts = [Fraction(0), Fraction(1), Fraction(-1), Fraction(2), Fraction(-2)]
+    BT, G, AT = oracle.cook_toom_exact(4, pts)
+    for a in range(4):
+        for b in range(3):
+            for c in range(6):
+                s = sum(AT[a][i] * G[i][b] * BT[i][c] for i in range(6))
+                assert s == (1 if c == a + b else 0)
+
+
+def test_f23_textbook_four_multiplies(oracle):
+    """1-D F(2,3): the textbook minimal algorithm
+        m1=(d0-d2)g0, m2=(d1+d2)(g0+g1+g2)/2, m3=(d2-d1)(g0-g1+g2)/2, m4=(d1-d3)g2,
+        y0=m1+m2+m3, y1=m2-m3-m4.
+    The row scaling is a free choice, so compare the rank-1 terms
+    A^T[:,i] (x) G[i,:] (x) B^T[i,:], which are not."""
+    BT, G, AT = oracle.cook_toom(2)
+    tb_BT = np.array([[1, 0, -1, 0], [0, 1, 1, 0], [0, -1, 1, 0], [0, 1, 0, -1]], float)
+    tb_G = np.array([[1, 0, 0], [.5, .5, .5], [.5, -.5, .5], [0, 0, 1]], float)
+    tb_AT = np.array([[1, 1, 1, 0], [0, 1, -1, -1]], float)
+    for i in range(4):
+        ours = np.einsum("a,b,c->abc", AT[:, i], G[i], BT[i])
+        text = np.einsum("a,b,c->abc", tb_AT[:, i], tb_G[i], tb_BT[i])
+        assert np.array_equal(ours, text), i
+    # and the textbook algorithm really is the FIR filter, with 4 multiplies
+    rng = np.random.default_rng(1)
+    d, g = rng.integers(-9, 9, 4).astype(float), rng.integers(-9, 9, 3).astype(float)
+    prod = (tb_G @ g) * (tb_BT @ d)
+    assert prod.shape == (4,)
+    y = tb_AT @ prod
+    assert np.array_equal(y, [d[0] * g[0] + d[1] * g[1] + d[2] * g[2],
+                              d[1] * g[0] + d[2] * g[1] + d[3] * g[2]])
+    assert np.array_equal(AT @ ((G @ g) * (BT @ d)), y)
+
+
+def test_default_matrices_literal_values(oracle):
+    """Spot values that follow from the construction by hand."""
+    BT, G, AT = oracle.cook_toom_exact(4)
+    assert BT[0] == [Fraction(1, 4), 0, Fraction(-5, 4), 0, 1, 0]
+    assert [list(r) for r in G] == [
+        [4, 0, 0], [Fraction(2, 3)] * 3, [Fraction(2, 3), Fraction(-2, 3), Fraction(2, 3)],
+        [Fraction(8, 3), Fraction(4, 3), Fraction(2, 3)],
+        [Fraction(8, 3), Fraction(-4, 3), Fraction(2, 3)], [0, 0, 1]]
+    pts = [0, 1, -1, Fraction(1, 2), Fraction(-1, 2)]
+    for a in range(4):
+        assert AT[a][:5] == [p ** a for p in pts]
+    mx = lambda M: max(abs(v) for r in M for v in r)
+    assert (mx(BT), mx(G), mx(AT)) == (Fraction(5, 4), 4, 1)
+    BT6, G6, AT6 = oracle.cook_toom_exact(6)
+    assert (mx(BT6), mx(G6), mx(AT6)) == (Fraction(21, 4), 1, 32)
+
+
+def test_zero_fractions_match_paper(oracle):
+    gold = _golden()
+    zf = lambda M: sum(v == 0 for r in M for v in r) / sum(len(r) for r in M)
+    BT, G, AT = oracle.cook_toom_exact(2)
+    assert zf(BT) == gold["zero_fraction_F2_BT"]
+    assert round(zf(G), 2) == gold["zero_fraction_F2_G"]
+    assert zf(AT) == gold["zero_fraction_F2_AT"]
+    BT, G, AT = oracle.cook_toom_exact(4)
+    assert round(zf(G), 2) == gold["zero_fraction_F4_G"]
+    assert zf(AT) == gold["zero_fraction_F4_AT"]
+
+
+def test_fp32_rounding_of_matrices_is_correct(oracle):
+    BTx, Gx, ATx = oracle.cook_toom_exact(6)
+    BT, G, AT = oracle.cook_toom(6, dtype=np.float32)
+    for ex, fl in ((BTx, BT), (Gx, G), (ATx, AT)):
+        for i, row in enumerate(ex):
+            for j, v in enumerate(row):
+                f = np.float32(fl[i, j])
+                lo, hi = np.nextafter(f, np.float32(-np.inf)), np.nextafter(f, np.float32(np.inf))
+                e = abs(Fraction(float(f)) - v)
+                assert e <= abs(Fraction(float(lo)) - v) and e <= abs(Fraction(float(hi)) - v)
+
+
+# ---------------------------------------------------------------- P5 counts
+def test_paper_counts(oracle):
+    gold = _golden()
+    assert gold["mults_per_output_direct"] == 9
+    for m, key in ((2, "mults_per_output_F2"), (4, "mults_per_output_F4")):
+        n = m + 2
+        assert n * n / (m * m) == gold[key]
+    # dense (valid) convolution of a 32x32 input: 30x30 outputs
+    geo = oracle.geometry(1, 32, 32, 0, 2)
+    assert (geo["Ho"], geo["Wo"], geo["n"]) == (30, 30, gold["patch_F2"])
+    assert geo["Ho"] * geo["Wo"] * 9 == gold["mults_32x32_direct"]
+    assert geo["T"] * geo["P"] == gold["mults_32x32_winograd_4x4_tile"]
+    assert round(16 / 9, 2) == gold["weight_memory_growth_F2"]
+    assert 36 / 9 == gold["weight_memory_growth_F4"]
+    # the U tensor really has that many entries
+    Uf, _ = oracle.q_weights(np.ones((2, 3, 3, 3), np.float32), oracle.cook_toom(4, dtype=np.float32)[1],
+                             want_q=False)
+    assert Uf.size == 4 * 2 * 3 * 9
+
+
+# ---------------------------------------------------------------- P4 brute force for O1
+def _direct_bruteforce(X, g, stride, pad):
+    N, C, H, W = X.shape
+    K = g.shape[0]
+    Ho, Wo = (H + 2 * pad - 3) // stride + 1, (W + 2 * pad - 3) // stride + 1
+    Xp = np.zeros((N, C, H + 2 * pad, W + 2 * pad), X.dtype)
+    Xp[:, :, pad:pad + H, pad:pad + W] = X
+    Y = np.zeros((N, K, Ho, Wo), X.dtype)
+    for i in range(3):
+        for j in range(3):
+            win = Xp[:, :, i:i + stride * (Ho - 1) + 1:stride, j:j + stride * (Wo - 1) + 1:stride]
+            Y += np.einsum("nchw,kc->nkhw", win, g[:, :, i, j])
+    return Y
+
+
+@pytest.mark.parametrize("stride,pad,H,W", [(1, 1, 5, 7), (1, 0, 6, 4), (2, 1, 8, 8), (2, 1, 7, 5)])
+def test_direct_conv_bruteforce_integers(oracle, stride, pad, H, W):
+    rng = np.random.default_rng(3)
+    X = rng.integers(-5, 6, (2, 3, H, W)).astype(np.float64)
+    g = rng.integers(-4, 5, (4, 3, 3, 3)).astype(np.float64)
+    assert np.array_equal(oracle.conv2d_direct_f64(X, g, stride, pad), _direct_bruteforce(X, g, stride, pad))
+
+
+def test_direct_conv_single_channel_nine_terms(oracle):
+    X = np.arange(1, 26, dtype=np.float64).reshape(1, 1, 5, 5)
+    g = np.array([[1, 2, 3], [4, 5, 6], [7, 8, 9]], np.float64).reshape(1, 1, 3, 3)
+    Y = oracle.conv2d_direct_f64(X, g, 1, 0)
+    # hand-written 9-term sum for the top-left output: no filter flip
+    exp00 = (1 * 1 + 2 * 2 + 3 * 3 + 6 * 4 + 7 * 5 + 8 * 6 + 11 * 7 + 12 * 8 + 13 * 9)
+    assert Y[0, 0, 0, 0] == exp00
+    assert np.array_equal(Y[0, 0], correlate2d(X[0, 0], g[0, 0], mode="valid"))
+    Y1 = oracle.conv2d_direct_f64(X, g, 1, 1)
+    assert np.array_equal(Y1[0, 0], correlate2d(X[0, 0], g[0, 0], mode="same"))
+
+
+def test_direct_conv_q_matches_integer_bruteforce(oracle):
+    rng = np.random.default_rng(5)
+    Xq = rng.integers(-127, 128, (2, 5, 6, 6))
+    gq = rng.integers(-127, 128, (3, 5, 3, 3))
+    for stride in (1, 2):
+        acc, Yq = oracle.conv2d_direct_q(Xq, gq, r_y=np.float32(3e-4), stride=stride, pad=1)
+        ref = _direct_bruteforce(Xq.astype(np.int64), gq.astype(np.int64), stride, 1)
+        assert np.array_equal(acc, ref)
+        exp = np.clip(np.rint(ref.astype(np.float32) * np.float32(3e-4)), -127, 127)
+        assert np.array_equal(Yq, exp.astype(np.int32))
+        assert np.abs(Yq).max() == 127 or np.abs(exp).max() < 127
+
+
+# ---------------------------------------------------------------- P1 Winograd == direct in fp64
+@pytest.mark.parametrize("m", [2, 4, 6])
+@pytest.mark.parametrize("H,W,pad", [(4, 4, 1), (5, 7, 1), (7, 5, 1), (8, 8, 1), (8, 6, 0), (9, 16, 1)])
+def test_winograd_f64_equals_direct(oracle, m, H, W, pad):
+    """Sec. 3.1: F2/F4 (and in fp64 also F6) introduce only marginal numerical
+    error; Table 1's 32-bit column.  Non-symmetric random data so a transposed
+    operand or a swapped index anywhere fails."""
+    rng = np.random.default_rng(100 * m + H + W)
+    X = rng.standard_normal((2, 3, H, W))
+    g = rng.standard_normal((4, 3, 3, 3))
+    BT, G, AT = oracle.cook_toom(m)
+    Yw = oracle.winograd_f64(X, g, BT, G, AT, pad)
+    Yd = oracle.conv2d_direct_f64(X, g, 1, pad)
+    assert Yw.shape == Yd.shape
+    assert _rel(Yw, Yd) <= 1e-9
+
+
+def test_winograd_f64_detects_a_planted_transpose(oracle):
+    """The pin above is sharp: feeding B instead of B^T breaks it."""
+    rng = np.random.default_rng(0)
+    X, g = rng.standard_normal((1, 2, 8, 8)), rng.standard_normal((2, 2, 3, 3))
+    BT, G, AT = oracle.cook_toom(4)
+    Yd = oracle.conv2d_direct_f64(X, g, 1, 1)
+    assert _rel(oracle.winograd_f64(X, g, BT.T.copy(), G, AT, 1), Yd) > 1e-3
+
+
+# ---------------------------------------------------------------- P7 quantized pipeline
+def test_hadamard_matches_einsum(oracle):
+    rng = np.random.default_rng(7)
+    Vq = rng.integers(-127, 128, (16, 10, 7))
+    Uq = rng.integers(-127, 128, (16, 5, 7))
+    M = oracle.q_hadamard(Vq, Uq)
+    assert np.array_equal(M, np.einsum("ptc,pkc->ptk", Vq.astype(np.int64), Uq.astype(np.int64)))
+
+
+def _patches(xq, m, pad):
+    """All n x n patches as an integer array [T, C, n, n] (index bookkeeping only)."""
+    N, C, H, W = xq.shape
+    n = m + 2
+    Ho, Wo = H + 2 * pad - 2, W + 2 * pad - 2
+    TH, TW = -(-Ho // m), -(-Wo // m)
+    Xp = np.zeros((N, C, pad + TH * m + 2 + n, pad + TW * m + 2 + n), xq.dtype)
+    Xp[:, :, pad:pad + H, pad:pad + W] = xq
+    out = np.zeros((N, TH, TW, C, n, n), xq.dtype)
+    for th in range(TH):
+        for tw in range(TW):
+            out[:, th, tw] = Xp[:, :, th * m:th * m + n, tw * m:tw * m + n]
+    return out.reshape(N * TH * TW, C, n, n), TH, TW
+
+
+def test_f2_stages_are_exact_integers(oracle):
+    """With the default F2 matrices (entries 0, +-1, 1/2) and integer data every
+    intermediate is exactly representable, so each stage must equal plain integer
+    matrix algebra done by numpy, whatever the fp32 evaluation order."""
+    rng = np.random.default_rng(11)
+    BT, G, AT = oracle.cook_toom(2, dtype=np.float32)
+    N, C, K, H, W = 2, 3, 4, 7, 6
+    xq = rng.integers(-127, 128, (N, C, H, W))
+    g4 = (4 * rng.integers(-7, 8, (K, C, 3, 3))).astype(np.float32)  # multiples of 4: G g G^T integral
+    Vf, Vq = oracle.q_input(xq, BT, pad=1, r_v=1.0, qmax=10 ** 6)
+    d, TH, TW = _patches(xq, 2, 1)
+    BTi = BT.astype(np.int64)
+    Vexp = np.einsum("ij,tcjl,kl->iktc", BTi, d.astype(np.int64), BTi).reshape(16, -1, C)
+    assert np.array_equal(Vq, Vexp) and np.array_equal(Vf, Vexp.astype(np.float32))
+    Uf, Uq = oracle.q_weights(g4, G, r_u=1.0, qmax=10 ** 6)
+    G2 = (2 * G).astype(np.int64)
+    Uexp = (np.einsum("ia,kcab,jb->ijkc", G2, g4.astype(np.int64), G2) // 4).reshape(16, K, C)
+    assert np.array_equal(Uq, Uexp)
+    M = oracle.q_hadamard(Vq, Uq)
+    Yf, Yq, inexact = oracle.q_output(M, AT, N, H, W, pad=1, r_y=1.0, qmax=2 ** 30)
+    ATi = AT.astype(np.int64)
+    Mt = M.reshape(4, 4, N, TH, TW, K)
+    Yt = np.einsum("ai,ijnhwk,bj->nkhawb", ATi, Mt, ATi).reshape(N, K, TH * 2, TW * 2)[:, :, :H, :W]
+    assert inexact == 0 and np.abs(Yt).max() < 2 ** 24
+    assert np.array_equal(Yq, Yt)
+    # and, being exact, the whole thing is the integer direct convolution
+    acc, _ = oracle.conv2d_direct_q(xq, g4.astype(np.int64), 1.0, qmax=2 ** 30)
+    assert np.array_equal(Yq, acc)
+
+
+def _fma32(a, b, c):
+    """Correctly rounded fp32 fma via exact rationals."""
+    v = Fraction(float(a)) * Fraction(float(b)) + Fraction(float(c))
+    return _round32(v)
+
+
+def _round32(v):
+    f = np.float32(float(v))
+    best = None
+    for x in (f, np.nextafter(f, np.float32(np.inf)), np.nextafter(f, np.float32(-np.inf))):
+        key = (abs(Fraction(float(x)) - v), int(x.view(np.uint32)) & 1)
+        if best is None or key < best[0]:
+            best = (key, x)
+    return best[1]
+
+
+def _rne_sat(v, qmax):
+    return int(min(max(np.rint(np.float32(v)), -qmax), qmax))
+
+
+def test_fused_chain_order_on_dense_matrices(oracle):
+    """The pinned arithmetic (ascending fused chains from +0, fp32 multiply by the
+    scale, round-half-even, saturate) emulated with exact rationals on a tiny case
+    with dense random matrices, where the evaluation order does change bits."""
+    rng = np.random.default_rng(13)
+    m, n = 2, 4
+    BT = rng.standard_normal((n, n)).astype(np.float32)
+    G = rng.standard_normal((n, 3)).astype(np.float32)
+    AT = rng.standard_normal((m, n)).astype(np.float32)
+    xq = rng.integers(-127, 128, (1, 2, 4, 4))
+    g = rng.standard_normal((2, 2, 3, 3)).astype(np.float32)
+    r_v, r_u, r_y = np.float32(0.37), np.float32(41.3), np.float32(2.1e-3)
+    f0 = np.float32(0)
+    # input stage, tile (0,0) .. all tiles of a 4x4 image with pad 1 (2x2 tiles)
+    Vf, Vq = oracle.q_input(xq, BT, pad=1, r_v=r_v)
+    d, TH, TW = _patches(xq, m, 1)
+    for t in range(d.shape[0]):
+        for c in range(2):
+            w = [[f0] * n for _ in range(n)]
+            for i in range(n):
+                for l in range(n):
+                    acc = f0
+                    for j in range(n):
+                        acc = _fma32(BT[i, j], np.float32(d[t, c, j, l]), acc)
+                    w[i][l] = acc
+            for i in range(n):
+                for k in range(n):
+                    acc = f0
+                    for l in range(n):
+                        acc = _fma32(w[i][l], BT[k, l], acc)
+                    assert Vf[i * n + k, t, c] == acc
+                    assert Vq[i * n + k, t, c] == _rne_sat(_round32(Fraction(float(acc)) * Fraction(float(r_v))), 127)
+    Uf, Uq = oracle.q_weights(g, G, r_u=r_u)
+    for k in range(2):
+        for c in range(2):
+            tt = [[f0] * 3 for _ in range(n)]
+            for i in range(n):
+                for b in range(3):
+                    acc = f0
+                    for a in range(3):
+                        acc = _fma32(G[i, a], g[k, c, a, b], acc)
+                    tt[i][b] = acc
+            for i in range(n):
+                for j in range(n):
+                    acc = f0
+                    for b in range(3):
+                        acc = _fma32(tt[i][b], G[j, b], acc)
+                    assert Uf[i * n + j, k, c] == acc
+                    assert Uq[i * n + j, k, c] == _rne_sat(_round32(Fraction(float(acc)) * Fraction(float(r_u))), 127)
+    M = oracle.q_hadamard(Vq, Uq)
+    Yf, Yq, _ = oracle.q_output(M, AT, 1, 4, 4, pad=1, r_y=r_y)
+    for t in range(4):
+        th, tw = divmod(t, 2)
+        for k in range(2):
+            z = [[f0] * n for _ in range(m)]
+            for a in range(m):
+                for j in range(n):
+                    acc = f0
+                    for i in range(n):
+                        acc = _fma32(AT[a, i], np.float32(M[i * n + j, t, k]), acc)
+                    z[a][j] = acc
+            for a in range(m):
+                for b in range(m):
+                    acc = f0
+                    for j in range(n):
+                        acc = _fma32(z[a][j], AT[b, j], acc)
+                    assert Yf[0, k, th * m + a, tw * m + b] == acc
+                    assert Yq[0, k, th * m + a, tw * m + b] == _rne_sat(
+                        _round32(Fraction(float(acc)) * Fraction(float(r_y))), 127)
+
+
+def test_q_scalars(oracle):
+    f = np.float32
+    s = oracle.q_scalars(0.031, 0.77, 0.0042, 0.19)
+    assert s["r_u"] == f(1) / f(0.0042) and s["r_v"] == f(0.031) / f(0.77)
+    assert s["r_y"] == (f(0.0042) * f(0.77)) / f(0.19) and s["r_m"] == 0
+    s = oracle.q_scalars(0.031, 0.77, 0.0042, 0.19, 0.05)
+    assert s["r_m"] == (f(0.0042) * f(0.77)) / f(0.05) and s["r_y"] == f(0.05) / f(0.19)
+
+
+def test_rounding_is_half_to_even_and_saturation_symmetric(oracle):
+    """Sec. 5.1 (per-layer symmetric quantization): range [-127, 127], never -128."""
+    G = oracle.cook_toom(2, dtype=np.float32)[1]
+    g = np.zeros((1, 1, 3, 3), np.float32)
+    for val, exp in ((0.5, 0), (1.5, 2), (2.5, 2), (-0.5, 0), (-1.5, -2), (-2.5, -2), (300.0, 127), (-300.0, -127)):
+        g[0, 0, 0, 0] = val  # U[0][0] = G[0,0]^2 g00 = g00 for the default F2 G
+        _, Uq = oracle.q_weights(g, G, r_u=1.0)
+        assert Uq[0, 0, 0] == exp, (val, Uq[0, 0, 0])
+    rng = np.random.default_rng(17)
+    xq = rng.integers(-127, 128, (1, 4, 8, 8))
+    BT, G, AT = oracle.cook_toom(4, dtype=np.float32)
+    _, Vq = oracle.q_input(xq, BT, r_v=np.float32(0.5))
+    assert Vq.max() == 127 and Vq.min() == -127
+    M = oracle.q_hadamard(Vq, Vq[:, :3, :])          # any int8-range "weights" will do
+    _, Yq, _ = oracle.q_output(M, AT, 1, 8, 8, pad=1, r_y=np.float32(1.0))
+    assert Yq.max() == 127 and Yq.min() == -127
+
+
+def test_quantized_pipeline_converges_to_fp64_winograd(oracle):
+    """As the quantization steps shrink (qmax large) the dequantized output of the
+    quantized pipeline approaches the fp64 Winograd of the same (fake-quantized) data."""
+    rng = np.random.default_rng(19)
+    N, C, K, H, W, m = 1, 3, 2, 8, 8, 4
+    BT, G, AT = oracle.cook_toom(m, dtype=np.float32)
+    X = np.maximum(rng.standard_normal((N, C, H, W)), 0).astype(np.float32)
+    g = (rng.standard_normal((K, C, 3, 3)) * 0.3).astype(np.float32)
+    errs = []
+    for qmax in (127, 2 ** 12, 2 ** 20):
+        sc = oracle.calibrate(X, g, BT, G, AT, qmax=qmax)
+        xq = oracle.quantize_tensor(X, sc["s_x"], qmax)
+        out = oracle.winograd_q(xq, g, BT, G, AT, sc, qmax=qmax)
+        Yd = out["Yq"].astype(np.float64) * sc["s_y"]
+        ref = oracle.winograd_f64(xq.astype(np.float64) * sc["s_x"], g, BT, G, AT)
+        errs.append(_rel(Yd, ref))
+    assert errs[0] > errs[1] > errs[2]
+    assert errs[2] < 1e-4 and errs[1] < 2e-2 and errs[0] > 20 * errs[1]
+
+
+def test_static_int8_error_grows_with_tile_size(oracle):
+    """Table 1: with static transforms 8-bit F2 is harmless, F4 and F6 are far from
+    the direct convolution.  This is why int8 parity is taken against the quantized
+    pipeline and never against the direct convolution."""
+    from paper_2002_10711_amd import workloads
+    L = workloads.Layer("t", 2, 32, 16, 12, 12, seed=23)
+    X, g = workloads.make_inputs(L)
+    errs = {}
+    for m in (2, 4, 6):
+        BT, G, AT = oracle.cook_toom(m, dtype=np.float32)
+        sc = oracle.calibrate(X, g, BT, G, AT)
+        xq = oracle.quantize_tensor(X, sc["s_x"])
+        out = oracle.winograd_q(xq, g, BT, G, AT, sc)
+        assert np.abs(out["Yq"]).max() == 127 and out["inexact"] == 0
+        ref = oracle.conv2d_direct_f64(xq.astype(np.float64) * sc["s_x"], g)
+        errs[m] = _rel(out["Yq"] * np.float64(sc["s_y"]), ref)
+    assert errs[2] < 0.06 and errs[4] > 2 * errs[2] and errs[6] > errs[4]
+
+
+def test_flex_limit_noise_to_zero(oracle):
+    """Perturbed matrices: only the limit is pinned -- as the noise shrinks the
+    literal Winograd returns to the direct convolution, linearly in sigma."""
+    from paper_2002_10711_amd import workloads
+    rng = np.random.default_rng(29)
+    X, g = rng.standard_normal((1, 3, 12, 12)), rng.standard_normal((2, 3, 3, 3))
+    Yd = oracle.conv2d_direct_f64(X, g)
+    errs = []
+    for sigma in (1e-2, 1e-4, 1e-6):
+        BT, G, AT = oracle.cook_toom(6)
+        BTp, Gp, ATp = [a.astype(np.float64) for a in workloads.perturb_transforms(BT, G, AT, sigma, 5)]
+        errs.append(_rel(oracle.winograd_f64(X, g, BTp, Gp, ATp), Yd))
+    assert errs[0] > 10 * errs[1] > 100 * errs[2] and errs[2] < 1e-3
