@@ -1,0 +1,149 @@
+/*
+ * wino.h -- C ABI of libwino: the forward path of a Winograd-aware 3x3
+ * convolution layer, F(m x m, 3 x 3) with m in {2, 4, 6}, on one AMD MI355X
+ * (gfx950).  Every step runs in hand-written HIP kernels; there is no CPU
+ * fallback.
+ *
+ * The operation (paper, Sec. 3.1, Eq. 1, applied to every patch of the
+ * activations as Sec. 3.2 describes, channels summed in the Winograd domain as
+ * in the GEMM formulation of Sec. 5.3):
+ *
+ *     Y = A^T [ sum_c (G g G^T) (.) (B^T d B) ] A
+ *
+ * with a per-layer symmetric quantizer after every stage in the int8 mode
+ * (Sec. 3.2, Fig. 2; Sec. 5.1).  B^T, G and A^T are arguments of every call, so
+ * fixed Cook-Toom matrices and learned ("flex", Sec. 3.2) ones take the same
+ * path.
+ *
+ * Conventions common to all entry points
+ *   - Pointers named *_dev are DEVICE pointers, everything else is HOST memory.
+ *   - The caller owns all buffers.  The library allocates and frees nothing on
+ *     the device and keeps no state between calls.
+ *   - Matrices in a wino_desc are read on the host during the call and passed to
+ *     the kernels by value; the caller may change them as soon as the call
+ *     returns.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream).  No entry point synchronises.
+ *   - Every argument check happens before the first HIP call, so error paths
+ *     never touch the GPU.  Errors are returned, never thrown or aborted on.
+ *   - Tensors: X[N][C][H][W], g[K][C][3][3], Y[N][K][Ho][Wo] with
+ *     Ho = H + 2 pad - 2 (stride is 1 by definition of the Winograd path),
+ *     row-major, last index fastest.  dtype WINO_I8: X and Y hold int8 codes
+ *     (x = s_x * code); dtype WINO_F32: float, no quantizer anywhere.
+ *   - Tiling: n = m + 2, P = n*n Winograd positions p = i*n + j,
+ *     TH = ceil(Ho/m), TW = ceil(Wo/m), T = N*TH*TW tiles,
+ *     t = (img*TH + th)*TW + tw.  Tile (th,tw) reads input rows
+ *     th*m - pad + j and columns tw*m - pad + l (zero outside the image) and
+ *     writes output rows th*m + a, columns tw*m + b (dropped outside).
+ */
+#ifndef WINO_H_
+#define WINO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  WINO_OK = 0,
+  WINO_E_NULL = -1,       /* a required pointer is NULL                          */
+  WINO_E_BAD_M = -2,      /* m is not 2, 4 or 6                                  */
+  WINO_E_BAD_SHAPE = -3,  /* a dimension is < 1, pad not in {0,1}, output empty,
+                             or a size overflows the 31-bit index range          */
+  WINO_E_BAD_DTYPE = -4,  /* dtype is neither WINO_F32 nor WINO_I8               */
+  WINO_E_BAD_SCALE = -5,  /* int8 mode: a scale is not finite and > 0, qmax not
+                             in [1,127], quant missing; or a matrix entry is not
+                             finite                                              */
+  WINO_E_WORKSPACE = -6,  /* workspace smaller than wino_workspace_bytes()       */
+  WINO_E_HIP = -7,        /* a HIP call or kernel launch failed                  */
+  WINO_E_BAD_ARG = -8     /* other invalid argument (stride, tap selector, ...)  */
+} wino_status;
+
+typedef enum { WINO_F32 = 0, WINO_I8 = 1 } wino_dtype;
+
+/* One layer problem.  BT is n x n, G is n x 3, AT is m x n, row-major, HOST. */
+typedef struct {
+  int N, C, K, H, W;
+  int pad;          /* 0 or 1 */
+  int m;            /* 2, 4 or 6 */
+  wino_dtype dtype;
+  const float* BT;
+  const float* G;
+  const float* AT;
+} wino_desc;
+
+/* Scales of the quantizers (Sec. 3.2: one after each stage; Sec. 5.1: one
+ * symmetric scale per layer and stage).  real value = scale * code.
+ *   s_x input, s_v transformed input B^T d B, s_u transformed weights G g G^T,
+ *   s_y output, s_m Hadamard/GEMM result (0 = that quantizer is off).
+ * Codes saturate to [-qmax, qmax]; rounding is half-to-even. */
+typedef struct {
+  float s_x, s_v, s_u, s_y, s_m;
+  int qmax;         /* 1..127 */
+} wino_quant;
+
+const char* wino_status_string(wino_status s);
+
+/* Bytes of the transformed-weight buffer U / of the workspace (transformed input
+ * V followed by the Hadamard/GEMM result M) for this problem; 0 if the
+ * descriptor is invalid.  Both layouts are private to the library. */
+size_t wino_weights_bytes(const wino_desc* d);
+size_t wino_workspace_bytes(const wino_desc* d);
+
+/* Weight stage of Eq. 1: U = G g G^T for every (k, c) (Sec. 3.1; amortised over
+ * inferences).  int8 mode: Uq = sat(rne(U / s_u)) with one scale for the whole
+ * tensor; `q` may be NULL only for WINO_F32.
+ *   g_dev  in   DEVICE float [K][C][3][3] (weights always enter as fp32)
+ *   U_dev  out  DEVICE, wino_weights_bytes(d) bytes, 256-byte aligned        */
+wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q,
+                                   const float* g_dev, void* U_dev, void* stream);
+
+/* Forward of the layer (Sec. 3.2): input transform B^T d B on every
+ * overlapping patch (+ quantizer), one GEMM per Winograd position summing over
+ * input channels (+ optional quantizer), output transform A^T M A (+ quantizer)
+ * and scatter to NCHW.
+ *   x_dev          in   DEVICE X, int8 codes or float
+ *   U_dev          in   DEVICE, produced by wino_transform_weights for the same d
+ *   y_dev          out  DEVICE Y, int8 codes or float
+ *   workspace_dev       DEVICE scratch, >= wino_workspace_bytes(d), 256-byte
+ *                       aligned; holds V and M afterwards (see wino_debug_export) */
+wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                            const void* U_dev, void* y_dev, void* workspace_dev,
+                            size_t workspace_bytes, void* stream);
+
+/* Parity taps: copy one intermediate out of the private layout into the
+ * canonical dense order.
+ *   which = WINO_TAP_U : src_dev = U buffer      -> out [P][K][C] int8 | float
+ *   which = WINO_TAP_V : src_dev = workspace     -> out [P][T][C] int8 | float
+ *   which = WINO_TAP_M : src_dev = workspace     -> out [P][T][K] int32 | float */
+enum { WINO_TAP_U = 0, WINO_TAP_V = 1, WINO_TAP_M = 2 };
+wino_status wino_debug_export(const wino_desc* d, int which, const void* src_dev,
+                              void* out_dev, void* stream);
+
+/* Cook-Toom matrices for F(m,3) from m+1 distinct finite points (NULL = the
+ * usual 0, 1, -1, 1/2, -1/2, 2, -2 prefix) plus the point at infinity
+ * (Sec. 3.1).  HOST outputs: BT n*n, G n*3, AT m*n floats. */
+wino_status wino_cook_toom(int m, const double* points, float* BT, float* G, float* AT);
+
+/* Baseline the paper compares against: im2row 3x3 convolution (Sec. 5.3),
+ * stride 1 or 2: gather rows of 9*C taps, one GEMM, requantize/scatter.
+ * Weights are packed once with conv2d_ref_pack_weights.
+ * int8 mode: y = sat(rne(acc * (s_x*s_w/s_y))), codes in [-qmax,qmax]. */
+size_t conv2d_ref_packed_weights_bytes(int C, int K, wino_dtype dtype);
+size_t conv2d_ref_workspace_bytes(int N, int C, int K, int H, int W, int stride, int pad,
+                                  wino_dtype dtype);
+/*   w_dev   in  DEVICE [K][C][3][3], int8 codes or float
+ *   wp_dev  out DEVICE packed weights                                         */
+wino_status conv2d_ref_pack_weights(int C, int K, wino_dtype dtype, const void* w_dev,
+                                    void* wp_dev, void* stream);
+wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pad,
+                           wino_dtype dtype, const void* x_dev, const void* wp_dev,
+                           void* y_dev, float s_x, float s_w, float s_y, int qmax,
+                           void* workspace_dev, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WINO_H_ */

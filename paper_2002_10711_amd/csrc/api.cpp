@@ -1,0 +1,313 @@
+// Host side of libwino: argument validation, geometry, scalar derivation and
+// kernel sequencing for the entry points declared in wino.h.  No device memory is
+// allocated here and nothing synchronises.
+#include <math.h>
+#include <string.h>
+
+#include "wino_internal.h"
+
+using namespace wino;
+
+namespace {
+
+bool finite_all(const float* p, int n) {
+  for (int i = 0; i < n; ++i)
+    if (!isfinite(p[i])) return false;
+  return true;
+}
+
+// Validates the descriptor and fills the derived geometry.
+wino_status make_geom(const wino_desc* d, Geom* g) {
+  if (!d) return WINO_E_NULL;
+  if (d->m != 2 && d->m != 4 && d->m != 6) return WINO_E_BAD_M;
+  if (d->dtype != WINO_F32 && d->dtype != WINO_I8) return WINO_E_BAD_DTYPE;
+  if (d->N < 1 || d->C < 1 || d->K < 1 || d->H < 1 || d->W < 1) return WINO_E_BAD_SHAPE;
+  if (d->pad != 0 && d->pad != 1) return WINO_E_BAD_SHAPE;
+  g->N = d->N; g->C = d->C; g->K = d->K; g->H = d->H; g->W = d->W;
+  g->pad = d->pad; g->m = d->m; g->n = d->m + 2; g->P = g->n * g->n;
+  g->Ho = d->H + 2 * d->pad - 2;
+  g->Wo = d->W + 2 * d->pad - 2;
+  if (g->Ho < 1 || g->Wo < 1) return WINO_E_BAD_SHAPE;
+  g->TH = (g->Ho + d->m - 1) / d->m;
+  g->TW = (g->Wo + d->m - 1) / d->m;
+  g->i8 = d->dtype == WINO_I8;
+  const long long T = (long long)d->N * g->TH * g->TW;
+  const long long limit = 0x7fffffffLL;
+  if (T > limit - 64) return WINO_E_BAD_SHAPE;
+  g->T = (int)T;
+  g->Tp = round_up(g->T, 64);
+  g->Cp = round_up(d->C, g->i8 ? 64 : 16);
+  g->Kp = round_up(d->K, 64);
+  // every tensor must be indexable with 31-bit element offsets
+  const long long e = g->i8 ? 1 : 4;
+  if ((long long)g->P * g->Tp * g->Cp > limit || (long long)g->P * g->Tp * g->Kp > limit ||
+      (long long)g->P * g->Kp * g->Cp > limit ||
+      (long long)d->N * d->C * d->H * d->W * e > limit * e ||
+      (long long)d->N * d->K * g->Ho * g->Wo > limit)
+    return WINO_E_BAD_SHAPE;
+  return WINO_OK;
+}
+
+size_t align256(size_t b) { return (b + 255) / 256 * 256; }
+size_t v_bytes(const Geom& g) { return align256((size_t)g.P * g.Tp * g.Cp * (g.i8 ? 1 : 4)); }
+size_t m_bytes(const Geom& g) { return align256((size_t)g.P * g.Tp * g.Kp * 4); }
+size_t u_bytes(const Geom& g) { return align256((size_t)g.P * g.Kp * g.Cp * (g.i8 ? 1 : 4)); }
+
+wino_status check_quant(const Geom& g, const wino_quant* q) {
+  if (!g.i8) return WINO_OK;
+  if (!q) return WINO_E_BAD_SCALE;
+  const float s[4] = {q->s_x, q->s_v, q->s_u, q->s_y};
+  for (float v : s)
+    if (!isfinite(v) || !(v > 0.0f)) return WINO_E_BAD_SCALE;
+  if (!isfinite(q->s_m) || q->s_m < 0.0f) return WINO_E_BAD_SCALE;
+  if (q->qmax < 1 || q->qmax > 127) return WINO_E_BAD_SCALE;
+  return WINO_OK;
+}
+
+// fp32 multipliers of the quantized pipeline, derived on the host:
+//   r_u = 1/s_u, r_v = s_x/s_v, r_m = (s_u s_v)/s_m, r_y = (s_u s_v)/s_y  (s_m/s_y if the
+//   quantizer after the Hadamard stage is on).
+struct Scalars { float r_u, r_v, r_m, r_y, qmax; };
+Scalars make_scalars(const Geom& g, const wino_quant* q) {
+  Scalars s = {1.0f, 1.0f, 0.0f, 1.0f, 127.0f};
+  if (!g.i8) return s;
+  volatile float suv = q->s_u * q->s_v;  // one rounded fp32 product, never contracted
+  s.r_u = 1.0f / q->s_u;
+  s.r_v = q->s_x / q->s_v;
+  if (q->s_m > 0.0f) {
+    s.r_m = suv / q->s_m;
+    s.r_y = q->s_m / q->s_y;
+  } else {
+    s.r_y = suv / q->s_y;
+  }
+  s.qmax = (float)q->qmax;
+  return s;
+}
+
+bool aligned256(const void* p) { return ((uintptr_t)p & 255) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char* wino_status_string(wino_status s) {
+  switch (s) {
+    case WINO_OK: return "ok";
+    case WINO_E_NULL: return "null pointer";
+    case WINO_E_BAD_M: return "m must be 2, 4 or 6";
+    case WINO_E_BAD_SHAPE: return "bad shape";
+    case WINO_E_BAD_DTYPE: return "bad dtype";
+    case WINO_E_BAD_SCALE: return "bad quantizer scale, qmax or matrix entry";
+    case WINO_E_WORKSPACE: return "workspace too small or misaligned";
+    case WINO_E_HIP: return "HIP error";
+    case WINO_E_BAD_ARG: return "bad argument";
+  }
+  return "unknown status";
+}
+
+size_t wino_weights_bytes(const wino_desc* d) {
+  Geom g;
+  if (make_geom(d, &g) != WINO_OK) return 0;
+  return u_bytes(g);
+}
+
+size_t wino_workspace_bytes(const wino_desc* d) {
+  Geom g;
+  if (make_geom(d, &g) != WINO_OK) return 0;
+  return v_bytes(g) + m_bytes(g);
+}
+
+wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, const float* g_dev,
+                                   void* U_dev, void* stream) {
+  Geom g;
+  wino_status st = make_geom(d, &g);
+  if (st != WINO_OK) return st;
+  if (!d->G || !g_dev || !U_dev) return WINO_E_NULL;
+  if (!finite_all(d->G, g.n * 3)) return WINO_E_BAD_SCALE;
+  if ((st = check_quant(g, q)) != WINO_OK) return st;
+  if (!aligned256(U_dev)) return WINO_E_WORKSPACE;
+  MatG mg;
+  memset(&mg, 0, sizeof mg);
+  memcpy(mg.v, d->G, sizeof(float) * g.n * 3);
+  const Scalars s = make_scalars(g, q);
+  if (launch_weight_transform(g, mg, g_dev, U_dev, s.r_u, s.qmax, (hipStream_t)stream) !=
+      hipSuccess)
+    return WINO_E_HIP;
+  return WINO_OK;
+}
+
+wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                            const void* U_dev, void* y_dev, void* workspace_dev,
+                            size_t workspace_bytes, void* stream) {
+  Geom g;
+  wino_status st = make_geom(d, &g);
+  if (st != WINO_OK) return st;
+  if (!d->BT || !d->AT || !x_dev || !U_dev || !y_dev || !workspace_dev) return WINO_E_NULL;
+  if (!finite_all(d->BT, g.n * g.n) || !finite_all(d->AT, g.m * g.n)) return WINO_E_BAD_SCALE;
+  if ((st = check_quant(g, q)) != WINO_OK) return st;
+  if (workspace_bytes < v_bytes(g) + m_bytes(g) || !aligned256(workspace_dev) ||
+      !aligned256(U_dev))
+    return WINO_E_WORKSPACE;
+  MatBT bt;
+  MatAT at;
+  memset(&bt, 0, sizeof bt);
+  memset(&at, 0, sizeof at);
+  memcpy(bt.v, d->BT, sizeof(float) * g.n * g.n);
+  memcpy(at.v, d->AT, sizeof(float) * g.m * g.n);
+  const Scalars s = make_scalars(g, q);
+  hipStream_t hs = (hipStream_t)stream;
+  void* V = workspace_dev;
+  void* M = (char*)workspace_dev + v_bytes(g);
+  if (launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs) != hipSuccess) return WINO_E_HIP;
+  if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
+  if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+    return WINO_E_HIP;
+  return WINO_OK;
+}
+
+wino_status wino_debug_export(const wino_desc* d, int which, const void* src_dev, void* out_dev,
+                              void* stream) {
+  Geom g;
+  wino_status st = make_geom(d, &g);
+  if (st != WINO_OK) return st;
+  if (!src_dev || !out_dev) return WINO_E_NULL;
+  if (which != WINO_TAP_U && which != WINO_TAP_V && which != WINO_TAP_M) return WINO_E_BAD_ARG;
+  const void* src = src_dev;
+  if (which == WINO_TAP_M) src = (const char*)src_dev + v_bytes(g);
+  if (launch_export(g, which, src, out_dev, (hipStream_t)stream) != hipSuccess) return WINO_E_HIP;
+  return WINO_OK;
+}
+
+// Cook-Toom / Lagrange construction of a minimal F(m,3) algorithm (Sec. 3.1).
+// For finite point p_i:  M_i(x) = prod_{j!=i}(x - p_j), N_i = M_i(p_i),
+//   BT[i,:] = sign(N_i) coeffs(M_i),  G[i,b] = p_i^b / |N_i|,  AT[a,i] = p_i^a;
+// point at infinity: BT[n-1,:] = coeffs(prod_j (x - p_j)), G[n-1,:] = (0,0,1),
+//   AT[m-1,n-1] = 1.
+wino_status wino_cook_toom(int m, const double* points, float* BT, float* G, float* AT) {
+  if (m != 2 && m != 4 && m != 6) return WINO_E_BAD_M;
+  if (!BT || !G || !AT) return WINO_E_NULL;
+  static const double kDefault[7] = {0.0, 1.0, -1.0, 0.5, -0.5, 2.0, -2.0};
+  const int n = m + 2, np = n - 1;
+  const double* pts = points ? points : kDefault;
+  for (int i = 0; i < np; ++i) {
+    if (!isfinite(pts[i])) return WINO_E_BAD_ARG;
+    for (int j = 0; j < i; ++j)
+      if (pts[i] == pts[j]) return WINO_E_BAD_ARG;
+  }
+  for (int i = 0; i < n * n; ++i) BT[i] = 0.0f;
+  for (int i = 0; i < n * 3; ++i) G[i] = 0.0f;
+  for (int i = 0; i < m * n; ++i) AT[i] = 0.0f;
+  long double poly[9];
+  for (int i = 0; i <= np; ++i) {      // i == np builds the full product (infinity row)
+    int deg = 0;
+    poly[0] = 1.0L;
+    for (int j = 0; j < np; ++j) {
+      if (j == i) continue;
+      poly[deg + 1] = 0.0L;            // multiply by (x - p_j)
+      for (int k = deg + 1; k >= 1; --k) poly[k] = poly[k - 1] - poly[k] * (long double)pts[j];
+      poly[0] = -poly[0] * (long double)pts[j];
+      ++deg;
+    }
+    if (i == np) {
+      for (int k = 0; k <= deg; ++k) BT[(n - 1) * n + k] = (float)poly[k];
+      G[(n - 1) * 3 + 2] = 1.0f;
+      AT[(m - 1) * n + (n - 1)] = 1.0f;
+      break;
+    }
+    const long double p = (long double)pts[i];
+    long double Ni = 0.0L, pw = 1.0L;
+    for (int k = 0; k <= deg; ++k) { Ni += poly[k] * pw; pw *= p; }
+    const long double sgn = Ni < 0 ? -1.0L : 1.0L, aN = Ni < 0 ? -Ni : Ni;
+    for (int k = 0; k <= deg; ++k) BT[i * n + k] = (float)(sgn * poly[k]);
+    pw = 1.0L;
+    for (int b = 0; b < 3; ++b) { G[i * 3 + b] = (float)(pw / aN); pw *= p; }
+    pw = 1.0L;
+    for (int a = 0; a < m; ++a) { AT[a * n + i] = (float)pw; pw *= p; }
+  }
+  return WINO_OK;
+}
+
+// ------------------------------------------------------------ im2row baseline
+static wino_status make_ref_geom(int N, int C, int K, int H, int W, int stride, int pad,
+                                 wino_dtype dtype, RefGeom* g) {
+  if (dtype != WINO_F32 && dtype != WINO_I8) return WINO_E_BAD_DTYPE;
+  if (N < 1 || C < 1 || K < 1 || H < 1 || W < 1) return WINO_E_BAD_SHAPE;
+  if (stride != 1 && stride != 2) return WINO_E_BAD_ARG;
+  if (pad != 0 && pad != 1) return WINO_E_BAD_SHAPE;
+  if (H + 2 * pad < 3 || W + 2 * pad < 3) return WINO_E_BAD_SHAPE;
+  g->N = N; g->C = C; g->K = K; g->H = H; g->W = W; g->stride = stride; g->pad = pad;
+  g->Ho = (H + 2 * pad - 3) / stride + 1;
+  g->Wo = (W + 2 * pad - 3) / stride + 1;
+  g->i8 = dtype == WINO_I8;
+  const long long T = (long long)N * g->Ho * g->Wo, limit = 0x7fffffffLL;
+  if (T > limit - 64) return WINO_E_BAD_SHAPE;
+  g->T = (int)T;
+  g->Tp = round_up(g->T, 64);
+  g->Cp = round_up(C, g->i8 ? 64 : 16);
+  g->Kp = round_up(K, 64);
+  if ((long long)g->Tp * 9 * g->Cp > limit || (long long)g->Tp * g->Kp > limit ||
+      (long long)N * C * H * W > limit || (long long)g->Kp * 9 * g->Cp > limit)
+    return WINO_E_BAD_SHAPE;
+  return WINO_OK;
+}
+
+size_t conv2d_ref_packed_weights_bytes(int C, int K, wino_dtype dtype) {
+  if (C < 1 || K < 1 || (dtype != WINO_F32 && dtype != WINO_I8)) return 0;
+  const int i8 = dtype == WINO_I8;
+  return align256((size_t)round_up(K, 64) * 9 * round_up(C, i8 ? 64 : 16) * (i8 ? 1 : 4));
+}
+
+size_t conv2d_ref_workspace_bytes(int N, int C, int K, int H, int W, int stride, int pad,
+                                  wino_dtype dtype) {
+  RefGeom g;
+  if (make_ref_geom(N, C, K, H, W, stride, pad, dtype, &g) != WINO_OK) return 0;
+  return align256((size_t)g.Tp * 9 * g.Cp * (g.i8 ? 1 : 4)) + align256((size_t)g.Tp * g.Kp * 4);
+}
+
+wino_status conv2d_ref_pack_weights(int C, int K, wino_dtype dtype, const void* w_dev, void* wp_dev,
+                                    void* stream) {
+  if (dtype != WINO_F32 && dtype != WINO_I8) return WINO_E_BAD_DTYPE;
+  if (C < 1 || K < 1) return WINO_E_BAD_SHAPE;
+  if (!w_dev || !wp_dev) return WINO_E_NULL;
+  if (!aligned256(wp_dev)) return WINO_E_WORKSPACE;
+  const int i8 = dtype == WINO_I8;
+  if ((long long)round_up(K, 64) * 9 * round_up(C, i8 ? 64 : 16) > 0x7fffffffLL)
+    return WINO_E_BAD_SHAPE;
+  if (launch_ref_pack_weights(C, K, round_up(C, i8 ? 64 : 16), round_up(K, 64), i8, w_dev, wp_dev,
+                              (hipStream_t)stream) != hipSuccess)
+    return WINO_E_HIP;
+  return WINO_OK;
+}
+
+wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pad, wino_dtype dtype,
+                           const void* x_dev, const void* wp_dev, void* y_dev, float s_x, float s_w,
+                           float s_y, int qmax, void* workspace_dev, size_t workspace_bytes,
+                           void* stream) {
+  RefGeom g;
+  wino_status st = make_ref_geom(N, C, K, H, W, stride, pad, dtype, &g);
+  if (st != WINO_OK) return st;
+  if (!x_dev || !wp_dev || !y_dev || !workspace_dev) return WINO_E_NULL;
+  float r_y = 1.0f;
+  if (g.i8) {
+    const float s[3] = {s_x, s_w, s_y};
+    for (float v : s)
+      if (!isfinite(v) || !(v > 0.0f)) return WINO_E_BAD_SCALE;
+    if (qmax < 1 || qmax > 127) return WINO_E_BAD_SCALE;
+    volatile float sxw = s_x * s_w;
+    r_y = sxw / s_y;
+  }
+  const size_t rows_b = align256((size_t)g.Tp * 9 * g.Cp * (g.i8 ? 1 : 4));
+  if (workspace_bytes < rows_b + align256((size_t)g.Tp * g.Kp * 4) || !aligned256(workspace_dev) ||
+      !aligned256(wp_dev))
+    return WINO_E_WORKSPACE;
+  hipStream_t hs = (hipStream_t)stream;
+  void* rows = workspace_dev;
+  void* M = (char*)workspace_dev + rows_b;
+  if (launch_im2row(g, x_dev, rows, hs) != hipSuccess) return WINO_E_HIP;
+  if (launch_gemm(1, g.Tp, g.Kp, 9 * g.Cp, g.i8, rows, wp_dev, M, hs) != hipSuccess)
+    return WINO_E_HIP;
+  if (launch_ref_epilogue(g, M, y_dev, r_y, (float)qmax, hs) != hipSuccess) return WINO_E_HIP;
+  return WINO_OK;
+}
+
+}  // extern "C"

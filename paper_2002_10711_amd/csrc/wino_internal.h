@@ -1,0 +1,53 @@
+// Internal declarations shared by the host API and the kernel files of libwino.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "wino.h"
+
+namespace wino {
+
+// Derived sizes of one layer problem.  Private device layouts:
+//   V [P][Tp][Cp]   transformed input, int8 or float, channel fastest
+//   U [P][Kp][Cp]   transformed weights, int8 or float, channel fastest
+//   M [P][Tp][Kp]   Hadamard/GEMM result, int32 or float
+// with Tp, Kp rounded up to 64 and Cp rounded up to 64 (int8) / 16 (float).
+// Padding channels are written as zero by the transform kernels; padding tiles
+// and padding output channels are computed on and never read back.
+struct Geom {
+  int N, C, K, H, W, pad, m, n, P;
+  int Ho, Wo, TH, TW, T;
+  int Tp, Cp, Kp;
+  int i8;
+};
+
+struct MatBT { float v[64]; };   // n x n, row-major, n <= 8
+struct MatG  { float v[24]; };   // n x 3
+struct MatAT { float v[48]; };   // m x n, m <= 6
+
+inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
+
+// Kernel launchers (each enqueues on `s` and returns hipGetLastError()).
+hipError_t launch_input_transform(const Geom& g, const MatBT& bt, const void* x, void* V,
+                                  float r_v, float qmax, hipStream_t s);
+hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w, void* U,
+                                   float r_u, float qmax, hipStream_t s);
+// Batched GEMM  M[p][t][k] = sum_c A[p][t][c] * B[p][k][c]; rows padded as above.
+// Used with P = n*n for the Winograd domain and P = 1 for the im2row baseline.
+hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, const void* A, const void* B,
+                       void* M, hipStream_t s);
+hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M, void* y,
+                                   float r_m, float r_y, float qmax, hipStream_t s);
+hipError_t launch_export(const Geom& g, int which, const void* src, void* out, hipStream_t s);
+
+// im2row baseline pieces.
+struct RefGeom {
+  int N, C, K, H, W, stride, pad, Ho, Wo, T, Tp, Cp, Kp, i8;
+};
+hipError_t launch_ref_pack_weights(int C, int K, int Cp, int Kp, int i8, const void* w, void* wp,
+                                   hipStream_t s);
+hipError_t launch_im2row(const RefGeom& g, const void* x, void* rows, hipStream_t s);
+hipError_t launch_ref_epilogue(const RefGeom& g, const void* M, void* y, float r_y, float qmax,
+                               hipStream_t s);
+
+}  // namespace wino

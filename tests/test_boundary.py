@@ -1,0 +1,146 @@
+"""Host-side tests of the C ABI: the library loads, exports every symbol the header
+declares, and every error path is reachable without a GPU (argument checks happen
+before the first HIP call).  No compute is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2002_10711_amd import binding as wb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(wb.LIB_PATH):
+        from paper_2002_10711_amd import build
+        build.build()
+    return wb.lib()
+
+
+def _declared_functions():
+    txt = open(os.path.join(ROOT, "include", "wino.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:wino|conv2d_ref)_[a-z0-9_]+)\s*\(", txt)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = _declared_functions()
+    assert set(names) == set(wb.EXPORTS), (names, wb.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def _desc(**kw):
+    d = dict(N=1, C=16, K=16, H=8, W=8, pad=1, m=2, dtype=wb.WINO_F32)
+    d.update(kw)
+    m = d["m"] if d["m"] in (2, 4, 6) else 2
+    n = m + 2
+    return wb.Desc(d["N"], d["C"], d["K"], d["H"], d["W"], d["pad"], d["m"], d["dtype"],
+                   BT=np.eye(n, dtype=np.float32), G=np.ones((n, 3), np.float32),
+                   AT=np.ones((m, n), np.float32))
+
+
+def test_sizes(L):
+    d = _desc()
+    # F2, T=16 -> Tp=64, C=16 -> Cp=16 (float), K -> Kp=64, P=16
+    assert wb.wino_weights_bytes(d) == 16 * 64 * 16 * 4
+    assert wb.wino_workspace_bytes(d) == 16 * 64 * 16 * 4 + 16 * 64 * 64 * 4
+    d = _desc(N=64, C=64, K=64, H=32, W=32, m=4, dtype=wb.WINO_I8)
+    assert wb.wino_weights_bytes(d) == 36 * 64 * 64
+    assert wb.wino_workspace_bytes(d) == 36 * 4096 * 64 + 36 * 4096 * 64 * 4
+    for bad in (dict(m=3), dict(N=0), dict(pad=2), dict(dtype=7), dict(H=1, W=1, pad=0)):
+        assert wb.wino_weights_bytes(_desc(**bad)) == 0
+        assert wb.wino_workspace_bytes(_desc(**bad)) == 0
+
+
+def _fwd(L, d, q, x=0x1000, U=0x1000, y=0x1000, ws=0x1000, nbytes=1 << 40):
+    qp = ctypes.byref(q) if q is not None else None
+    return L.wino_conv2d_fwd(d.ref, qp, x, U, y, ws, nbytes, None)
+
+
+def test_error_codes_without_gpu(L):
+    q = wb.make_quant(0.1, 0.1, 0.1, 0.1)
+    assert L.wino_conv2d_fwd(None, None, 1, 1, 1, 1, 0, None) == -1
+    assert _fwd(L, _desc(m=3), None) == -2
+    assert _fwd(L, _desc(m=8), None) == -2
+    assert _fwd(L, _desc(C=0), None) == -3
+    assert _fwd(L, _desc(pad=2), None) == -3
+    assert _fwd(L, _desc(H=2, W=2, pad=0), None) == -3
+    assert _fwd(L, _desc(N=1 << 20, C=1 << 10, H=64, W=64), None) == -3     # index range
+    assert _fwd(L, _desc(dtype=5), None) == -4
+    assert _fwd(L, _desc(), None, x=None) == -1
+    assert _fwd(L, _desc(), None, ws=None) == -1
+    d = _desc()
+    d.c.BT = None
+    assert _fwd(L, d, None) == -1
+    assert _fwd(L, _desc(dtype=wb.WINO_I8), None) == -5                     # quant missing
+    for bad in (dict(s_x=0.0), dict(s_v=-1.0), dict(s_u=float("nan")), dict(s_y=float("inf")),
+                dict(s_m=-0.5), dict(qmax=0), dict(qmax=128)):
+        kw = dict(s_x=0.1, s_v=0.1, s_u=0.1, s_y=0.1, s_m=0.0, qmax=127)
+        kw.update(bad)
+        assert _fwd(L, _desc(dtype=wb.WINO_I8), wb.make_quant(**kw)) == -5, bad
+    d = _desc()
+    d._keep[0][1, 1] = np.inf
+    assert _fwd(L, d, None) == -5
+    assert _fwd(L, _desc(), None, nbytes=100) == -6
+    assert _fwd(L, _desc(), None, ws=0x1010) == -6                           # misaligned
+    # weights entry point
+    assert L.wino_transform_weights(_desc().ref, None, None, 0x1000, None) == -1
+    assert L.wino_transform_weights(_desc(dtype=wb.WINO_I8).ref, None, 0x1000, 0x1000, None) == -5
+    assert L.wino_transform_weights(_desc(m=5).ref, None, 0x1000, 0x1000, None) == -2
+    assert L.wino_transform_weights(_desc().ref, None, 0x1000, 0x1004, None) == -6
+    # taps
+    assert L.wino_debug_export(_desc().ref, 9, 0x1000, 0x1000, None) == -8
+    assert L.wino_debug_export(_desc().ref, 0, None, 0x1000, None) == -1
+    assert q.qmax == 127
+    for s in range(-8, 1):
+        assert len(wb.status_string(s)) > 1
+
+
+def test_ref_conv_error_codes_without_gpu(L):
+    f = lambda **kw: L.conv2d_ref_gpu(*[kw.get(k, v) for k, v in (
+        ("N", 1), ("C", 8), ("K", 8), ("H", 8), ("W", 8), ("stride", 1), ("pad", 1),
+        ("dtype", wb.WINO_I8), ("x", 0x1000), ("wp", 0x1000), ("y", 0x1000), ("s_x", 0.1),
+        ("s_w", 0.1), ("s_y", 0.1), ("qmax", 127), ("ws", 0x1000), ("nbytes", 1 << 40),
+        ("stream", None))])
+    assert f(stride=3) == -8
+    assert f(dtype=3) == -4
+    assert f(N=0) == -3
+    assert f(pad=3) == -3
+    assert f(H=1, W=1, pad=0) == -3
+    assert f(x=None) == -1
+    assert f(s_w=0.0) == -5
+    assert f(qmax=200) == -5
+    assert f(nbytes=10) == -6
+    assert wb.conv2d_ref_workspace_bytes(1, 8, 8, 8, 8, 1, 1, wb.WINO_I8) == 64 * 9 * 64 + 64 * 64 * 4
+    assert wb.conv2d_ref_workspace_bytes(1, 8, 8, 8, 8, 2, 1, wb.WINO_F32) == 64 * 9 * 16 * 4 + 64 * 64 * 4
+    assert wb.conv2d_ref_packed_weights_bytes(8, 8, wb.WINO_I8) == 64 * 9 * 64
+    assert wb.conv2d_ref_packed_weights_bytes(0, 8, wb.WINO_I8) == 0
+    assert L.conv2d_ref_pack_weights(8, 8, wb.WINO_I8, None, 0x1000, None) == -1
+    assert L.conv2d_ref_pack_weights(8, 8, 9, 0x1000, 0x1000, None) == -4
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+def test_library_cook_toom_matches_oracle(L, oracle, m):
+    """The library's own generator (host code, independent implementation) gives the
+    correctly rounded fp32 matrices of the exact construction."""
+    BT, G, AT = wb.wino_cook_toom(m)
+    oBT, oG, oAT = oracle.cook_toom(m, dtype=np.float32)
+    assert np.array_equal(BT, oBT) and np.array_equal(G, oG) and np.array_equal(AT, oAT)
+
+
+def test_library_cook_toom_custom_points_and_errors(L, oracle):
+    from fractions import Fraction
+    pts = [0.0, 1.0, -1.0, 2.0, -2.0]
+    BT, G, AT = wb.wino_cook_toom(4, pts)
+    oBT, oG, oAT = oracle.cook_toom(4, [Fraction(p) for p in pts], dtype=np.float32)
+    assert np.array_equal(BT, oBT) and np.array_equal(G, oG) and np.array_equal(AT, oAT)
+    assert L.wino_cook_toom(3, None, 1, 1, 1) == -2
+    assert L.wino_cook_toom(2, None, None, 1, 1) == -1
+    dup = np.array([0.0, 1.0, 1.0])
+    b = np.zeros(64, np.float32)
+    assert L.wino_cook_toom(2, dup.ctypes.data, b.ctypes.data, b.ctypes.data, b.ctypes.data) == -8

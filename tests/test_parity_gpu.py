@@ -1,0 +1,132 @@
+"""GPU-vs-oracle parity through the C ABI.  int8: every tap (transformed weights,
+transformed input, int32 accumulators, int8 output) bit-exact against the pinned
+quantized pipeline of the oracle.  fp32: max |diff| / max |ref| against the fp64
+direct convolution <= 1e-4 (m = 2, 4) or 1e-3 (m = 6); with perturbed matrices the
+reference is the fp64 literal Winograd with the same matrices."""
+import numpy as np
+import pytest
+
+from paper_2002_10711_amd import workloads
+from paper_2002_10711_amd.workloads import Layer
+
+from helpers import make_case, max_rel, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+FP32_TOL = {2: 1e-4, 4: 1e-4, 6: 1e-3}
+
+
+def _check_i8(case, out):
+    ref = case["ref"]
+    assert ref["inexact"] == 0
+    for tap, key in (("U", "Uq"), ("V", "Vq"), ("M", "M"), ("Y", "Yq")):
+        a, b = out[tap].astype(np.int64), ref[key].astype(np.int64)
+        assert a.shape == b.shape, (tap, a.shape, b.shape)
+        bad = int((a != b).sum())
+        assert bad == 0, "%s: %d of %d differ, first at %s" % (
+            tap, bad, a.size, np.argwhere(a != b)[:3].tolist())
+
+
+def _check_f32(oracle, case, out):
+    L = case["layer"]
+    if L.flex_sigma > 0:
+        ref = oracle.winograd_f64(case["X"], case["g"], case["BT"], case["G"], case["AT"], L.pad)
+    else:
+        ref = oracle.conv2d_direct_f64(case["X"], case["g"], 1, L.pad)
+    assert out["Y"].shape == ref.shape
+    err = max_rel(out["Y"], ref)
+    assert err <= FP32_TOL[L.m], err
+    return err
+
+
+def test_config1_fp32_f2(oracle):
+    case = make_case(oracle, workloads.config1()[0])
+    _check_f32(oracle, case, run_gpu(case))
+
+
+# Small shapes spanning several 64-row blocks, ragged tiles (m does not divide
+# Ho), C and K that are not multiples of the padding granules, pad 0 and 1.
+SMALL = [
+    Layer("s_f2", 3, 20, 24, 9, 11, m=2, seed=101),
+    Layer("s_f4", 2, 70, 33, 13, 10, m=4, seed=102),
+    Layer("s_f6", 2, 12, 65, 16, 16, m=6, seed=103),
+    Layer("s_f6_tiny", 5, 5, 3, 4, 4, m=6, seed=104),
+    Layer("s_f4_pad0", 2, 16, 16, 10, 12, m=4, pad=0, seed=105),
+    Layer("s_f2_1x1out", 1, 3, 2, 3, 3, m=2, pad=0, seed=106),
+    Layer("s_f4_wide", 1, 130, 70, 6, 40, m=4, seed=107),
+]
+
+
+@pytest.mark.parametrize("layer", SMALL, ids=lambda l: l.name)
+def test_small_int8_all_taps(oracle, layer):
+    case = make_case(oracle, layer)
+    _check_i8(case, run_gpu(case))
+
+
+@pytest.mark.parametrize("layer", SMALL, ids=lambda l: l.name)
+def test_small_fp32(oracle, layer):
+    from dataclasses import replace
+    case = make_case(oracle, replace(layer, dtype="f32"))
+    _check_f32(oracle, case, run_gpu(case))
+
+
+def test_flex_small_int8_and_fp32(oracle):
+    from dataclasses import replace
+    L = Layer("flex_small", 2, 24, 40, 10, 10, m=6, flex_sigma=0.01, seed=108)
+    case = make_case(oracle, L)
+    _check_i8(case, run_gpu(case))
+    case = make_case(oracle, replace(L, dtype="f32"))
+    _check_f32(oracle, case, run_gpu(case))
+    L4 = Layer("flex_small4", 2, 24, 40, 10, 10, m=4, flex_sigma=0.05, seed=109)
+    case = make_case(oracle, L4)
+    _check_i8(case, run_gpu(case))
+
+
+def test_saturation_and_m_quantizer(oracle):
+    """Deliberately small scales drive every stage into saturation; the optional
+    quantizer after the Hadamard stage is switched on."""
+    L = Layer("sat", 2, 32, 16, 12, 12, m=4, seed=110)
+    case = make_case(oracle, L, with_oracle=False)
+    sc = dict(case["scales"])
+    sc["s_v"] *= 0.25
+    sc["s_u"] *= 0.5
+    sc["s_y"] *= 0.3
+    sc["s_m"] = sc["s_u"] * sc["s_v"] * 400.0
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc)
+    out = run_gpu(case, scales=sc)
+    for tap, key in (("U", "Uq"), ("V", "Vq"), ("Y", "Yq")):
+        assert np.abs(case["ref"][key]).max() == 127 and case["ref"][key].min() >= -127
+    _check_i8(case, out)
+    sc["qmax"] = 7                                  # a 4-bit-ish quantizer through the same path
+    case["ref"] = oracle.winograd_q(case["xq"].astype(np.int32) // 19, case["g"], case["BT"],
+                                    case["G"], case["AT"], sc, qmax=7)
+    case["xq"] = (case["xq"].astype(np.int32) // 19).astype(np.int8)
+    _check_i8(case, run_gpu(case, scales=sc))
+
+
+def test_config2_int8_full(oracle):
+    case = make_case(oracle, workloads.config2("i8")[0])
+    _check_i8(case, run_gpu(case))
+
+
+def test_config2_fp32_full(oracle):
+    case = make_case(oracle, workloads.config2("f32")[0])
+    _check_f32(oracle, case, run_gpu(case))
+
+
+@pytest.mark.parametrize("layer", workloads.config3(), ids=lambda l: l.name)
+def test_config3_int8_full(oracle, layer):
+    case = make_case(oracle, layer)
+    _check_i8(case, run_gpu(case))
+
+
+def test_config4_flex_int8_full(oracle):
+    case = make_case(oracle, workloads.config4()[0])
+    _check_i8(case, run_gpu(case))
+
+
+def test_determinism(oracle):
+    case = make_case(oracle, Layer("det", 4, 64, 64, 16, 16, m=4, seed=111), with_oracle=False)
+    a, b = run_gpu(case), run_gpu(case)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k

@@ -1,0 +1,56 @@
+"""The im2row baseline against the oracle's direct convolution: int8 bit-exact
+(integer accumulation, one requantization), fp32 within 1e-5 of fp64."""
+import numpy as np
+import pytest
+
+from paper_2002_10711_amd.workloads import Layer, make_inputs
+
+from helpers import max_rel
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    Layer("r1", 2, 20, 24, 9, 11, stride=1, seed=201),
+    Layer("r2", 3, 64, 128, 16, 16, stride=2, seed=202),
+    Layer("r3", 2, 7, 5, 7, 5, stride=2, seed=203),
+    Layer("r4", 1, 130, 70, 6, 10, stride=1, pad=0, seed=204),
+    Layer("r5", 8, 64, 64, 32, 32, stride=1, seed=205),
+]
+
+
+def _run(L, x_np, w_np, i8, s=(1.0, 1.0, 1.0)):
+    import torch
+    from paper_2002_10711_amd import binding as wb
+    dev = torch.device("cuda:0")
+    dt = wb.WINO_I8 if i8 else wb.WINO_F32
+    x, w = torch.from_numpy(x_np).to(dev), torch.from_numpy(w_np).to(dev)
+    wp = torch.empty(wb.conv2d_ref_packed_weights_bytes(L.C, L.K, dt), dtype=torch.uint8, device=dev)
+    ws = torch.empty(wb.conv2d_ref_workspace_bytes(L.N, L.C, L.K, L.H, L.W, L.stride, L.pad, dt),
+                     dtype=torch.uint8, device=dev)
+    y = torch.full((L.N, L.K, L.Ho, L.Wo), 77, dtype=torch.int8 if i8 else torch.float32, device=dev)
+    wb.conv2d_ref_pack_weights(L.C, L.K, dt, w, wp)
+    wb.conv2d_ref_gpu(L.N, L.C, L.K, L.H, L.W, L.stride, L.pad, dt, x, wp, y, s[0], s[1], s[2], 127, ws)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+@pytest.mark.parametrize("L", CASES, ids=lambda l: l.name)
+def test_ref_conv_int8(oracle, L):
+    X, g = make_inputs(L)
+    s_x, s_w = np.float32(np.abs(X).max() / 127), np.float32(np.abs(g).max() / 127)
+    xq, wq = oracle.quantize_tensor(X, s_x), oracle.quantize_tensor(g, s_w)
+    acc, _ = oracle.conv2d_direct_q(xq, wq, 1.0, stride=L.stride, pad=L.pad)
+    s_y = np.float32(s_x * s_w * np.abs(acc).max() / 127 * 0.8)      # a little saturation
+    r_y = np.float32(np.float32(s_x * s_w) / s_y)
+    _, Yq = oracle.conv2d_direct_q(xq, wq, r_y, stride=L.stride, pad=L.pad)
+    y = _run(L, xq.astype(np.int8), wq.astype(np.int8), True, (float(s_x), float(s_w), float(s_y)))
+    assert np.abs(Yq).max() == 127
+    assert np.array_equal(y.astype(np.int32), Yq)
+
+
+@pytest.mark.parametrize("L", CASES, ids=lambda l: l.name)
+def test_ref_conv_fp32(oracle, L):
+    X, g = make_inputs(L)
+    ref = oracle.conv2d_direct_f64(X, g, L.stride, L.pad)
+    y = _run(L, X, g, False)
+    assert y.shape == ref.shape and max_rel(y, ref) <= 1e-5
