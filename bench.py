@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the Winograd-aware convolution forward path on one MI355X.
+
+A step is one pass of the whole hot path over one batch: weight transform
+G g G^T, input transform B^T d B, the per-position GEMMs and the output transform
+A^T M A, int8 with a quantizer after every stage.  The default workload is the
+CIFAR ResNet-18 stage-1 convolution (batch 64, 32x32, 64->64 channels,
+F(4x4,3x3)); inputs are synthetic (seeded ReLU(N(0,1)) activations, Kaiming
+weights) and resident in HBM before the timed region starts.
+
+Prints ONE JSON line: direct-convolution-equivalent TOPS of the whole step, the
+roofline of the dominant kernel (per-kernel durations measured with events on the
+launch stream), the speedup over the im2row baseline, and the CPU oracle timed on
+the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2002_10711_amd import workloads  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK = {"int8": 5000.0, "f32": 157.3}   # dense TOP/s, TFLOP/s
+HBM_TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def pick_workload(name):
+    table = {}
+    for L in (workloads.config2("i8") + workloads.config2("f32") + workloads.config3() +
+              workloads.config4() + workloads.config5()):
+        table[L.name] = L
+    if name not in table:
+        raise SystemExit("unknown workload %r; choose from %s" % (name, sorted(table)))
+    return table[name]
+
+
+def algorithmic(L):
+    """Bytes / operations the method itself must move / do, per kernel launch."""
+    e = 1 if L.dtype == "i8" else 4
+    n = L.m + 2
+    P = n * n
+    TH, TW = -(-L.Ho // L.m), -(-L.Wo // L.m)
+    T = L.N * TH * TW
+    x_b, y_b = L.N * L.C * L.H * L.W * e, L.N * L.K * L.Ho * L.Wo * e
+    v_b, u_b, m_b = P * T * L.C * e, P * L.C * L.K * e, 4 * P * T * L.K
+    return {
+        "weight_transform": dict(bytes=9 * L.C * L.K * 4 + u_b, ops=0),
+        "input_transform": dict(bytes=x_b + v_b, ops=0),
+        "gemm": dict(bytes=v_b + u_b + m_b, ops=2 * P * T * L.C * L.K),
+        "output_transform": dict(bytes=m_b + y_b, ops=0),
+    }
+
+
+def roofline_entry(name, alg, us, dtype, traffic):
+    ridge = MFMA_PEAK["int8" if dtype == "i8" else "f32"] * 1e12 / (HBM_PEAK_GBS * 1e9)
+    intensity = alg["ops"] / alg["bytes"] if alg["bytes"] else 0.0
+    if alg["ops"] and intensity >= ridge:
+        peak = MFMA_PEAK["int8" if dtype == "i8" else "f32"]
+        ach = alg["ops"] / (us * 1e-6) / 1e12
+        ent = dict(bound="mfma", achieved=ach, peak=peak,
+                   unit="TOP/s" if dtype == "i8" else "TFLOP/s")
+    else:
+        ach = alg["bytes"] / (us * 1e-6) / 1e9
+        ent = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s")
+    ent.update(kernel=name, frac=ent["achieved"] / ent["peak"], avg_us=us,
+               algorithmic_bytes=alg["bytes"], algorithmic_ops=alg["ops"], traffic=traffic)
+    return ent
+
+
+def gpu_leg(L, steps, warmup, use_graph):
+    import torch
+    from paper_2002_10711_amd import binding as wb
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (no CPU fallback exists)")
+    wb.lib()
+    dev = torch.device("cuda:0")
+    i8 = L.dtype == "i8"
+    scales = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[
+        L.name.replace("_f32", "_i8")]
+    X, g = workloads.make_inputs(L)
+    BT, G, AT = wb.wino_cook_toom(L.m)
+    if L.flex_sigma > 0:
+        BT, G, AT = workloads.perturb_transforms(BT, G, AT, L.flex_sigma, L.seed)
+    dt = wb.WINO_I8 if i8 else wb.WINO_F32
+    desc = wb.Desc(L.N, L.C, L.K, L.H, L.W, L.pad, L.m, dt, BT=BT, G=G, AT=AT)
+    quant = None
+    if i8:
+        quant = wb.make_quant(scales["s_x"], scales["s_v"], scales["s_u"], scales["s_y"])
+        # input codes of the previous layer's quantizer (input preparation, not the path)
+        xh = np.clip(np.rint(X / np.float32(scales["s_x"])), -127, 127).astype(np.int8)
+    else:
+        xh = X
+    x = torch.from_numpy(xh).to(dev)
+    gd = torch.from_numpy(g).to(dev)
+    U = torch.empty(wb.wino_weights_bytes(desc), dtype=torch.uint8, device=dev)
+    ws = torch.empty(wb.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    y = torch.empty((L.N, L.K, L.Ho, L.Wo), dtype=torch.int8 if i8 else torch.float32, device=dev)
+    stream = torch.cuda.Stream()          # default priority
+
+    def step():
+        wb.wino_transform_weights(desc, quant, gd, U, stream=stream)
+        wb.wino_conv2d_fwd(desc, quant, x, U, y, ws, stream=stream)
+
+    def fwd_only():
+        wb.wino_conv2d_fwd(desc, quant, x, U, y, ws, stream=stream)
+
+    def timed(fn, k, w):
+        with torch.cuda.stream(stream):
+            runner = fn
+            if use_graph:
+                for _ in range(3):
+                    fn()
+                stream.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=stream):
+                    fn()
+                runner = graph.replay
+            for _ in range(w):
+                runner()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for _ in range(k):
+                runner()
+            e1.record(stream)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / k       # ms per call
+
+    ms_step = timed(step, steps, warmup)
+    ms_fwd = timed(fwd_only, steps, warmup)
+
+    # per-kernel durations: the same step, with events between the kernels
+    stages = [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
+              ("gemm", wb.WINO_STAGE_GEMM), ("output_transform", wb.WINO_STAGE_OUTPUT)]
+    ksteps = max(20, min(steps, 200))
+    acc = {n: 0.0 for n, _ in stages}
+    with torch.cuda.stream(stream):
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)]
+               for _ in range(ksteps)]
+        for it in range(ksteps + 5):
+            row = evs[max(it - 5, 0)]
+            row[0].record(stream)
+            for si, (name, mask) in enumerate(stages):
+                if mask is None:
+                    wb.wino_transform_weights(desc, quant, gd, U, stream=stream)
+                else:
+                    wb.wino_conv2d_fwd_stages(desc, quant, x, U, y, ws, mask, stream=stream)
+                row[si + 1].record(stream)
+        torch.cuda.synchronize()
+        for row in evs:
+            for si, (name, _) in enumerate(stages):
+                acc[name] += row[si].elapsed_time(row[si + 1]) * 1e3 / ksteps   # us
+
+    # im2row baseline on the same layer, forward only (weights packed once)
+    s_w = scales.get("s_w", 1.0)
+    if i8:
+        wq = np.clip(np.rint(g / np.float32(s_w)), -127, 127).astype(np.int8)
+    else:
+        wq = g
+    wdev = torch.from_numpy(wq).to(dev)
+    wp = torch.empty(wb.conv2d_ref_packed_weights_bytes(L.C, L.K, dt), dtype=torch.uint8, device=dev)
+    rws = torch.empty(wb.conv2d_ref_workspace_bytes(L.N, L.C, L.K, L.H, L.W, 1, L.pad, dt),
+                      dtype=torch.uint8, device=dev)
+    with torch.cuda.stream(stream):
+        wb.conv2d_ref_pack_weights(L.C, L.K, dt, wdev, wp, stream=stream)
+
+    def ref_fwd():
+        wb.conv2d_ref_gpu(L.N, L.C, L.K, L.H, L.W, 1, L.pad, dt, x, wp, y, scales["s_x"], s_w,
+                          scales["s_y"], 127, rws, stream=stream)
+
+    ms_ref = timed(ref_fwd, max(10, steps // 4), max(2, warmup // 4))
+    return dict(ms_step=ms_step, ms_fwd=ms_fwd, ms_ref=ms_ref, kernel_us=acc)
+
+
+def cpu_leg(L):
+    """The oracle as it stands, on the host cores, whole quantized forward
+    (weight stage included) on the first images of the same workload."""
+    import oracle
+    oracle.build()
+    n_img = min(L.N, 16)
+    from dataclasses import replace
+    Ls = replace(L, N=n_img)
+    X, g = workloads.make_inputs(L)
+    X = X[:n_img]
+    BT, G, AT = oracle.cook_toom(L.m, dtype=np.float32)
+    if L.flex_sigma > 0:
+        BT, G, AT = workloads.perturb_transforms(BT, G, AT, L.flex_sigma, L.seed)
+    if L.dtype == "i8":
+        sc = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[L.name]
+        xq = oracle.quantize_tensor(X, sc["s_x"])
+        fn = lambda: oracle.winograd_q(xq, g, BT, G, AT, sc, pad=L.pad)
+    else:
+        fn = lambda: oracle.winograd_f64(X, g, BT, G, AT, L.pad)
+    fn()
+    t0 = time.perf_counter()
+    reps = 0
+    while time.perf_counter() - t0 < 10.0 or reps < 3:
+        fn()
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
+    return dict(value=Ls.direct_ops / dt / 1e12, unit="TOPS (direct-conv-equivalent)",
+                cores=oracle.num_threads(), kind="oracle",
+                sample="first %d of %d images of %s, %d repetitions, %.3f s each; quantized "
+                       "pipeline incl. weight stage, OpenMP over tiles" % (n_img, L.N, L.name, reps, dt))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="cfg2_i8")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step from the host "
+                    "instead of replaying a captured HIP graph of one step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU only (the path needs no exchange "
+                         "step; see DESIGN.md for how it would shard); got --gpus %d" % a.gpus)
+    L = pick_workload(a.workload)
+    if L.stride != 1:
+        raise SystemExit("workload %s is an im2row (stride-2) layer, not a Winograd one" % L.name)
+    r = gpu_leg(L, a.steps, a.warmup, not a.no_graph)
+    alg = algorithmic(L)
+    traffic = {}
+    if os.path.exists(HBM_TRAFFIC_FILE):
+        traffic = json.load(open(HBM_TRAFFIC_FILE)).get(L.name, {})
+    kernels = [roofline_entry(k, alg[k], us, L.dtype, traffic.get(k)) for k, us in r["kernel_us"].items()]
+    dominant = max(kernels, key=lambda e: e["avg_us"])
+    out = {
+        "metric": "direct-conv-equiv TOPS, int8 F(4x4,3x3) ResNet-18 layer (whole path incl. weight transform)"
+                  if L.name == "cfg2_i8" else "direct-conv-equiv TOPS, whole Winograd path incl. weight transform",
+        "value": L.direct_ops / (r["ms_step"] * 1e-3) / 1e12,
+        "unit": "TOPS",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": r["ms_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8" if L.dtype == "i8" else "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: N=%d C=%d K=%d %dx%d pad=%d F(%dx%d,3x3) %s" % (
+            L.name, L.N, L.C, L.K, L.H, L.W, L.pad, L.m, L.m, L.dtype),
+            "launch": "hip-graph replay of one step" if not a.no_graph else "host launches"},
+        "fwd_only_ms": r["ms_fwd"],
+        "fwd_only_tops": L.direct_ops / (r["ms_fwd"] * 1e-3) / 1e12,
+        "im2row_baseline_ms": r["ms_ref"],
+        "speedup_vs_im2row": r["ms_ref"] / r["ms_fwd"],
+        "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
+                                               "kernel", "avg_us")},
+        "kernels": kernels,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_leg(L)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -113,6 +113,16 @@ wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void*
                             const void* U_dev, void* y_dev, void* workspace_dev,
                             size_t workspace_bytes, void* stream);
 
+/* The same forward, restricted to the stages named in `stages` (a mask of
+ * WINO_STAGE_*), for per-kernel timing and for tests: a stage reads what the
+ * previous one left in the workspace.  WINO_STAGE_ALL is wino_conv2d_fwd.
+ * Pointers a selected stage does not touch may be NULL (x_dev without INPUT,
+ * U_dev without GEMM, y_dev without OUTPUT). */
+enum { WINO_STAGE_INPUT = 1, WINO_STAGE_GEMM = 2, WINO_STAGE_OUTPUT = 4, WINO_STAGE_ALL = 7 };
+wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                                   const void* U_dev, void* y_dev, void* workspace_dev,
+                                   size_t workspace_bytes, int stages, void* stream);
+
 /* Parity taps: copy one intermediate out of the private layout into the
  * canonical dense order.
  *   which = WINO_TAP_U : src_dev = U buffer      -> out [P][K][C] int8 | float

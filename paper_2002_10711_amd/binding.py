@@ -13,10 +13,11 @@ LIB_PATH = os.path.join(_HERE, "libwino.so")
 
 WINO_F32, WINO_I8 = 0, 1
 WINO_TAP_U, WINO_TAP_V, WINO_TAP_M = 0, 1, 2
+WINO_STAGE_INPUT, WINO_STAGE_GEMM, WINO_STAGE_OUTPUT, WINO_STAGE_ALL = 1, 2, 4, 7
 
 EXPORTS = [
     "wino_status_string", "wino_weights_bytes", "wino_workspace_bytes",
-    "wino_transform_weights", "wino_conv2d_fwd", "wino_debug_export", "wino_cook_toom",
+    "wino_transform_weights", "wino_conv2d_fwd", "wino_conv2d_fwd_stages", "wino_debug_export", "wino_cook_toom",
     "conv2d_ref_packed_weights_bytes", "conv2d_ref_workspace_bytes",
     "conv2d_ref_pack_weights", "conv2d_ref_gpu",
 ]
@@ -63,6 +64,10 @@ def lib():
         L.wino_conv2d_fwd.argtypes = [ctypes.POINTER(WinoDesc), ctypes.POINTER(WinoQuant),
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.wino_conv2d_fwd_stages.argtypes = [ctypes.POINTER(WinoDesc), ctypes.POINTER(WinoQuant),
+                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
+                                             ctypes.c_void_p]
         L.wino_debug_export.argtypes = [ctypes.POINTER(WinoDesc), ctypes.c_int, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_void_p]
         L.wino_cook_toom.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
@@ -149,6 +154,16 @@ def wino_conv2d_fwd(desc, quant, x_dev, U_dev, y_dev, workspace_dev, workspace_b
     _check(lib().wino_conv2d_fwd(desc.ref, q, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev),
                                  _ptr(workspace_dev), workspace_bytes, _stream(stream)),
            "wino_conv2d_fwd")
+
+
+def wino_conv2d_fwd_stages(desc, quant, x_dev, U_dev, y_dev, workspace_dev, stages,
+                           workspace_bytes=None, stream=None):
+    q = ctypes.byref(quant) if quant is not None else None
+    if workspace_bytes is None:
+        workspace_bytes = workspace_dev.numel() * workspace_dev.element_size()
+    _check(lib().wino_conv2d_fwd_stages(desc.ref, q, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev),
+                                        _ptr(workspace_dev), workspace_bytes, stages,
+                                        _stream(stream)), "wino_conv2d_fwd_stages")
 
 
 def wino_debug_export(desc, which, src_dev, out_dev, stream=None):

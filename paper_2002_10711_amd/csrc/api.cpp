@@ -136,33 +136,52 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, cons
   return WINO_OK;
 }
 
-wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void* x_dev,
-                            const void* U_dev, void* y_dev, void* workspace_dev,
-                            size_t workspace_bytes, void* stream) {
+wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                                   const void* U_dev, void* y_dev, void* workspace_dev,
+                                   size_t workspace_bytes, int stages, void* stream) {
   Geom g;
   wino_status st = make_geom(d, &g);
   if (st != WINO_OK) return st;
-  if (!d->BT || !d->AT || !x_dev || !U_dev || !y_dev || !workspace_dev) return WINO_E_NULL;
-  if (!finite_all(d->BT, g.n * g.n) || !finite_all(d->AT, g.m * g.n)) return WINO_E_BAD_SCALE;
+  if (stages < 1 || stages > WINO_STAGE_ALL) return WINO_E_BAD_ARG;
+  const bool s_in = stages & WINO_STAGE_INPUT, s_mm = stages & WINO_STAGE_GEMM,
+             s_out = stages & WINO_STAGE_OUTPUT;
+  if (!workspace_dev || (s_in && (!d->BT || !x_dev)) || (s_mm && !U_dev) ||
+      (s_out && (!d->AT || !y_dev)))
+    return WINO_E_NULL;
+  if ((s_in && !finite_all(d->BT, g.n * g.n)) || (s_out && !finite_all(d->AT, g.m * g.n)))
+    return WINO_E_BAD_SCALE;
   if ((st = check_quant(g, q)) != WINO_OK) return st;
   if (workspace_bytes < v_bytes(g) + m_bytes(g) || !aligned256(workspace_dev) ||
-      !aligned256(U_dev))
+      (s_mm && !aligned256(U_dev)))
     return WINO_E_WORKSPACE;
-  MatBT bt;
-  MatAT at;
-  memset(&bt, 0, sizeof bt);
-  memset(&at, 0, sizeof at);
-  memcpy(bt.v, d->BT, sizeof(float) * g.n * g.n);
-  memcpy(at.v, d->AT, sizeof(float) * g.m * g.n);
   const Scalars s = make_scalars(g, q);
   hipStream_t hs = (hipStream_t)stream;
   void* V = workspace_dev;
   void* M = (char*)workspace_dev + v_bytes(g);
-  if (launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs) != hipSuccess) return WINO_E_HIP;
-  if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
-  if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+  if (s_in) {
+    MatBT bt;
+    memset(&bt, 0, sizeof bt);
+    memcpy(bt.v, d->BT, sizeof(float) * g.n * g.n);
+    if (launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs) != hipSuccess)
+      return WINO_E_HIP;
+  }
+  if (s_mm && launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, V, U_dev, M, hs) != hipSuccess)
     return WINO_E_HIP;
+  if (s_out) {
+    MatAT at;
+    memset(&at, 0, sizeof at);
+    memcpy(at.v, d->AT, sizeof(float) * g.m * g.n);
+    if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+      return WINO_E_HIP;
+  }
   return WINO_OK;
+}
+
+wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                            const void* U_dev, void* y_dev, void* workspace_dev,
+                            size_t workspace_bytes, void* stream) {
+  return wino_conv2d_fwd_stages(d, q, x_dev, U_dev, y_dev, workspace_dev, workspace_bytes,
+                                WINO_STAGE_ALL, stream);
 }
 
 wino_status wino_debug_export(const wino_desc* d, int which, const void* src_dev, void* out_dev,
