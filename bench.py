@@ -55,6 +55,10 @@ def algorithmic(L):
         "input_transform": dict(bytes=x_b + v_b, ops=0),
         "gemm": dict(bytes=v_b + u_b + m_b, ops=2 * P * T * L.C * L.K),
         "output_transform": dict(bytes=m_b + y_b, ops=0),
+        # GEMM and output transform in one kernel: M is never stored
+        "gemm_output": dict(bytes=v_b + u_b + y_b, ops=2 * P * T * L.C * L.K),
+        # the whole forward in one kernel: neither V nor M is stored
+        "fused_forward": dict(bytes=x_b + u_b + y_b, ops=2 * P * T * L.C * L.K),
     }
 
 
@@ -137,8 +141,11 @@ def gpu_leg(L, steps, warmup, use_graph):
     ms_fwd = timed(fwd_only, steps, warmup)
 
     # per-kernel durations: the same step, with events between the kernels
-    stages = [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
-              ("gemm", wb.WINO_STAGE_GEMM), ("output_transform", wb.WINO_STAGE_OUTPUT)]
+    if wb.wino_fwd_num_kernels(desc) == 1:
+        stages = [("weight_transform", None), ("fused_forward", wb.WINO_STAGE_ALL)]
+    else:
+        stages = [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
+                  ("gemm_output", wb.WINO_STAGE_GEMM | wb.WINO_STAGE_OUTPUT)]
     ksteps = max(20, min(steps, 200))
     acc = {n: 0.0 for n, _ in stages}
     with torch.cuda.stream(stream):

@@ -113,6 +113,12 @@ wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void*
                             const void* U_dev, void* y_dev, void* workspace_dev,
                             size_t workspace_bytes, void* stream);
 
+/* How many kernels wino_conv2d_fwd launches for this problem (0 if the descriptor is
+ * invalid): 1 = input transform, GEMM and output transform in one kernel (small int8
+ * layers; V and M never reach memory), 2 = input transform, then GEMM fused with the
+ * output transform (M never reaches memory). */
+int wino_fwd_num_kernels(const wino_desc* d);
+
 /* The same forward, restricted to the stages named in `stages` (a mask of
  * WINO_STAGE_*), for per-kernel timing and for tests: a stage reads what the
  * previous one left in the workspace.  WINO_STAGE_ALL is wino_conv2d_fwd.

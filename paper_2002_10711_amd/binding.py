@@ -17,7 +17,8 @@ WINO_STAGE_INPUT, WINO_STAGE_GEMM, WINO_STAGE_OUTPUT, WINO_STAGE_ALL = 1, 2, 4, 
 
 EXPORTS = [
     "wino_status_string", "wino_weights_bytes", "wino_workspace_bytes",
-    "wino_transform_weights", "wino_conv2d_fwd", "wino_conv2d_fwd_stages", "wino_debug_export", "wino_cook_toom",
+    "wino_transform_weights", "wino_conv2d_fwd", "wino_conv2d_fwd_stages", "wino_fwd_num_kernels",
+    "wino_debug_export", "wino_cook_toom",
     "conv2d_ref_packed_weights_bytes", "conv2d_ref_workspace_bytes",
     "conv2d_ref_pack_weights", "conv2d_ref_gpu",
 ]
@@ -58,6 +59,7 @@ def lib():
                   "conv2d_ref_packed_weights_bytes", "conv2d_ref_workspace_bytes"):
             getattr(L, f).restype = ctypes.c_size_t
         L.wino_weights_bytes.argtypes = [ctypes.POINTER(WinoDesc)]
+        L.wino_fwd_num_kernels.argtypes = [ctypes.POINTER(WinoDesc)]
         L.wino_workspace_bytes.argtypes = [ctypes.POINTER(WinoDesc)]
         L.wino_transform_weights.argtypes = [ctypes.POINTER(WinoDesc), ctypes.POINTER(WinoQuant),
                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -154,6 +156,10 @@ def wino_conv2d_fwd(desc, quant, x_dev, U_dev, y_dev, workspace_dev, workspace_b
     _check(lib().wino_conv2d_fwd(desc.ref, q, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev),
                                  _ptr(workspace_dev), workspace_bytes, _stream(stream)),
            "wino_conv2d_fwd")
+
+
+def wino_fwd_num_kernels(desc):
+    return int(lib().wino_fwd_num_kernels(desc.ref))
 
 
 def wino_conv2d_fwd_stages(desc, quant, x_dev, U_dev, y_dev, workspace_dev, stages,

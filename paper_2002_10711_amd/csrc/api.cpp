@@ -136,6 +136,12 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, cons
   return WINO_OK;
 }
 
+int wino_fwd_num_kernels(const wino_desc* d) {
+  Geom g;
+  if (make_geom(d, &g) != WINO_OK) return 0;
+  return fused_fwd_supported(g) ? 1 : 2;
+}
+
 wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
                                    const void* U_dev, void* y_dev, void* workspace_dev,
                                    size_t workspace_bytes, int stages, void* stream) {
@@ -158,19 +164,32 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
   hipStream_t hs = (hipStream_t)stream;
   void* V = workspace_dev;
   void* M = (char*)workspace_dev + v_bytes(g);
+  MatBT bt;
+  MatAT at;
   if (s_in) {
-    MatBT bt;
     memset(&bt, 0, sizeof bt);
     memcpy(bt.v, d->BT, sizeof(float) * g.n * g.n);
-    if (launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs) != hipSuccess)
-      return WINO_E_HIP;
   }
-  if (s_mm && launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, V, U_dev, M, hs) != hipSuccess)
-    return WINO_E_HIP;
   if (s_out) {
-    MatAT at;
     memset(&at, 0, sizeof at);
     memcpy(at.v, d->AT, sizeof(float) * g.m * g.n);
+  }
+  if (stages == WINO_STAGE_ALL && fused_fwd_supported(g)) {
+    // the whole forward in one kernel: V and M stay on chip, the workspace is untouched
+    if (launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs) !=
+        hipSuccess)
+      return WINO_E_HIP;
+    return WINO_OK;
+  }
+  if (s_in && launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs) != hipSuccess)
+    return WINO_E_HIP;
+  if (s_mm && s_out) {
+    // both stages requested together: M stays in registers and is never written
+    if (launch_gemm_out(g, at, V, U_dev, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+      return WINO_E_HIP;
+  } else if (s_mm) {
+    if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
+  } else if (s_out) {
     if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;
   }

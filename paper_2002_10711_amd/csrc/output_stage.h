@@ -1,0 +1,102 @@
+// Output side shared by the fused kernels: MFMA accumulator types, the lane-local
+// output transform of the four (tile, k) pairs a lane holds after the last Winograd
+// position, and the NCHW store of one m x m tile (Eq. 1, Sec. 3.1; quantizer of
+// Sec. 3.2).
+#pragma once
+#include "transform_math.h"
+
+namespace wino {
+
+#if defined(__HIPCC__)
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <bool I8> struct Acc { typedef v4i type; };
+template <> struct Acc<false> { typedef v4f type; };
+
+// Stores one m x m output tile of channel k; (h0, w0) is its top-left corner.
+template <int M, bool I8>
+__device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv, size_t plane,
+                                           int h0, int w0, const float (&Y)[M][M], float r_y,
+                                           float lo, float hi) {
+  if (I8) {
+    int8_t* y = (int8_t*)yv + plane;
+    uint32_t q[M][M];
+#pragma unroll
+    for (int a = 0; a < M; ++a)
+#pragma unroll
+      for (int b = 0; b < M; ++b) q[a][b] = quantize_bits(Y[a][b], r_y, lo, hi);
+    const bool full = h0 + M <= g.Ho && w0 + M <= g.Wo;
+    if (full && (g.Wo & 1) == 0) {
+      // rows start at even addresses (w0 = tw*m is even): 2-byte stores, or one
+      // dword per row when m == 4 and the row pitch keeps it aligned
+#pragma unroll
+      for (int a = 0; a < M; ++a) {
+        int8_t* row = y + (size_t)(h0 + a) * g.Wo + w0;
+        if (M == 4 && (g.Wo & 3) == 0) {
+          uint32_t lo16 = __builtin_amdgcn_perm(q[a][1], q[a][0], 0x0c0c0400u);
+          uint32_t hi16 = __builtin_amdgcn_perm(q[a][3], q[a][2], 0x04000c0cu);
+          *(uint32_t*)row = lo16 | hi16;
+        } else {
+#pragma unroll
+          for (int b = 0; b < M; b += 2)
+            *(uint16_t*)(row + b) =
+                (uint16_t)__builtin_amdgcn_perm(q[a][b + 1], q[a][b], 0x0c0c0400u);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int a = 0; a < M; ++a)
+#pragma unroll
+        for (int b = 0; b < M; ++b)
+          if (h0 + a < g.Ho && w0 + b < g.Wo)
+            y[(size_t)(h0 + a) * g.Wo + w0 + b] = (int8_t)(q[a][b] & 0xff);
+    }
+  } else {
+    float* y = (float*)yv + plane;
+#pragma unroll
+    for (int a = 0; a < M; ++a)
+#pragma unroll
+      for (int b = 0; b < M; ++b)
+        if (h0 + a < g.Ho && w0 + b < g.Wo) y[(size_t)(h0 + a) * g.Wo + w0 + b] = Y[a][b];
+  }
+}
+
+
+// A lane of the 16x16 MFMA result holds, for one tile, the accumulators of four
+// consecutive output channels k0..k0+3 (vector components) of every position:
+// transform each of the four n x n matrices and store its tile.
+// kMQ: the optional quantizer after the Hadamard stage is on (r_m > 0).
+template <int M, bool I8, bool kSparse, bool kMQ>
+__device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
+                                            const typename Acc<I8>::type (&acc)[(M + 2) * (M + 2)],
+                                            void* __restrict__ yv, int img, int th, int tw, int k0,
+                                            float r_m, float r_y, float qmax) {
+  constexpr int n = M + 2;
+  const float lo = kMagic - qmax, hi = kMagic + qmax;
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const int k = k0 + rr;
+    if (k >= g.K) continue;
+    float Mt[n][n], Y[M][M];
+#pragma unroll
+    for (int i = 0; i < n; ++i)
+#pragma unroll
+      for (int j = 0; j < n; ++j) {
+        if constexpr (I8) {
+          float f = (float)acc[i * n + j][rr];
+          if constexpr (kMQ) f = (float)quantize(f, r_m, qmax);
+          Mt[i][j] = f;
+        } else {
+          Mt[i][j] = acc[i * n + j][rr];
+        }
+      }
+    transform_result<M, kSparse>(Mt, at, Y);
+    store_tile<M, I8>(g, yv, ((size_t)img * g.K + k) * g.Ho * g.Wo, th * M, tw * M, Y, r_y, lo, hi);
+  }
+}
+
+#endif  // __HIPCC__
+
+}  // namespace wino

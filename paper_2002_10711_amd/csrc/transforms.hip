@@ -12,96 +12,47 @@
 //
 // The matrices arrive by value in the kernel arguments (scalar registers), never
 // as compiled-in constants, so learned transforms use the same code.
-#include "wino_internal.h"
+#include "input_stage.h"
 
 namespace wino {
 namespace {
 
-__device__ __forceinline__ int quantize(float v, float r, float qmax) {
-  float s = v * r;
-  s = __builtin_rintf(s);
-  s = fminf(fmaxf(s, -qmax), qmax);
-  return (int)s;
-}
-
 // ------------------------------------------------------------------ input --
-// V = B^T d B for one n x n patch held in registers.
-template <int n>
-__device__ __forceinline__ void transform_patch(const float (&d)[n][n], const MatBT& bt,
-                                                float (&V)[n][n]) {
-  float w[n][n];
-#pragma unroll
-  for (int i = 0; i < n; ++i)
-#pragma unroll
-    for (int l = 0; l < n; ++l) {
-      float acc = 0.0f;
-#pragma unroll
-      for (int j = 0; j < n; ++j) acc = __builtin_fmaf(bt.v[i * n + j], d[j][l], acc);
-      w[i][l] = acc;
-    }
-#pragma unroll
-  for (int i = 0; i < n; ++i)
-#pragma unroll
-    for (int k = 0; k < n; ++k) {
-      float acc = 0.0f;
-#pragma unroll
-      for (int l = 0; l < n; ++l) acc = __builtin_fmaf(w[i][l], bt.v[k * n + l], acc);
-      V[i][k] = acc;
-    }
-}
-
-// int8: one thread per (tile, group of 4 channels); the four int8 results of a
-// Winograd position are packed into one dword so that a wavefront writes 256
-// contiguous bytes per position.
-template <int M>
+// Stand-alone int8 input transform (see input_stage.h): V[p][t][c] to global memory,
+// a wavefront storing 256 contiguous bytes per position.
+template <int M, bool kSparse, bool kWide>
 __global__ __launch_bounds__(256) void input_transform_i8(Geom g, MatBT bt,
                                                           const int8_t* __restrict__ x,
                                                           uint32_t* __restrict__ V, float r_v,
-                                                          float qmax) {
-  constexpr int n = M + 2, P = n * n;
+                                                          float qmax, int RB, int TWB) {
+  constexpr int n = M + 2, P = n * n, CBQ = InCfg<M>::kCBQ;
+  extern __shared__ uint32_t lds[];
+  const int Wc = stage_cols(M, TWB);
+  const int ntwb = (g.TW + TWB - 1) / TWB;
+  const int twb = blockIdx.x % ntwb, rb = blockIdx.x / ntwb;
+  const int r0 = rb * RB, tw0 = twb * TWB, c0 = blockIdx.y * 64;
+  const int R = g.N * g.TH;
+  stage_strips<M, kWide>(g, x, lds, c0, r0, tw0, RB, TWB);
+  __syncthreads();
+  const float lo = kMagic - qmax, hi = kMagic + qmax;
   const int cq_per = g.Cp >> 2;
-  const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
-  const int t = (int)(item / cq_per), cq = (int)(item % cq_per);
-  if (t >= g.Tp) return;
-  uint32_t out[P];
-#pragma unroll
-  for (int p = 0; p < P; ++p) out[p] = 0u;
-  if (t < g.T) {
-    const int tw = t % g.TW, th = (t / g.TW) % g.TH, img = t / (g.TW * g.TH);
-    const int h0 = th * M - g.pad, w0 = tw * M - g.pad;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int c = cq * 4 + e;
-      if (c < g.C) {
-        const int8_t* xp = x + ((size_t)img * g.C + c) * g.H * g.W;
-        float d[n][n], Vt[n][n];
-#pragma unroll
-        for (int j = 0; j < n; ++j)
-#pragma unroll
-          for (int l = 0; l < n; ++l) {
-            const int h = h0 + j, w = w0 + l;
-            const bool in = h >= 0 && h < g.H && w >= 0 && w < g.W;
-            d[j][l] = in ? (float)xp[h * g.W + w] : 0.0f;
-          }
-        transform_patch<n>(d, bt, Vt);
-#pragma unroll
-        for (int i = 0; i < n; ++i)
-#pragma unroll
-          for (int k = 0; k < n; ++k) {
-            const int q = quantize(Vt[i][k], r_v, qmax);
-            out[i * n + k] |= (uint32_t)(q & 0xff) << (8 * e);
-          }
-      }
-    }
-  }
   const size_t pstride = (size_t)g.Tp * cq_per;
-  uint32_t* vp = V + (size_t)t * cq_per + cq;
+  const int nitem = RB * TWB * 16;
+  for (int it = threadIdx.x; it < nitem; it += blockDim.x) {
+    const int cq = it & 15, twl = (it >> 4) % TWB, rs = (it >> 4) / TWB;
+    const int r = r0 + rs, tw = tw0 + twl;
+    if (r >= R || tw >= g.TW) continue;
+    uint32_t out[P];
+    transform_quad<M, kSparse>(lds + ((size_t)rs * n * Wc + twl * M) * CBQ + cq, Wc, bt, r_v, lo,
+                               hi, out);
+    uint32_t* vp = V + ((size_t)r * g.TW + tw) * cq_per + (c0 >> 2) + cq;
 #pragma unroll
-  for (int p = 0; p < P; ++p) vp[p * pstride] = out[p];
+    for (int p = 0; p < P; ++p) vp[p * pstride] = out[p];
+  }
 }
 
-// fp32: one thread per (tile, channel).
-template <int M>
+// fp32: one thread per (tile, channel), patch gathered straight from global memory.
+template <int M, bool kSparse>
 __global__ __launch_bounds__(256) void input_transform_f32(Geom g, MatBT bt,
                                                            const float* __restrict__ x,
                                                            float* __restrict__ V) {
@@ -127,7 +78,7 @@ __global__ __launch_bounds__(256) void input_transform_f32(Geom g, MatBT bt,
         const bool in = h >= 0 && h < g.H && w >= 0 && w < g.W;
         d[j][l] = in ? xp[h * g.W + w] : 0.0f;
       }
-    transform_patch<n>(d, bt, Vt);
+    transform_patch<M, kSparse>(d, bt, Vt);
   }
   const size_t pstride = (size_t)g.Tp * g.Cp;
   float* vp = V + (size_t)t * g.Cp + c;
@@ -136,70 +87,54 @@ __global__ __launch_bounds__(256) void input_transform_f32(Geom g, MatBT bt,
 }
 
 // ----------------------------------------------------------------- weights --
-// U = G g G^T for one (k, c).
-template <int n>
-__device__ __forceinline__ void transform_filter(const float (&gk)[3][3], const MatG& mg,
-                                                 float (&U)[n][n]) {
-  float t[n][3];
-#pragma unroll
-  for (int i = 0; i < n; ++i)
-#pragma unroll
-    for (int b = 0; b < 3; ++b) {
-      float acc = 0.0f;
-#pragma unroll
-      for (int a = 0; a < 3; ++a) acc = __builtin_fmaf(mg.v[i * 3 + a], gk[a][b], acc);
-      t[i][b] = acc;
-    }
-#pragma unroll
-  for (int i = 0; i < n; ++i)
-#pragma unroll
-    for (int j = 0; j < n; ++j) {
-      float acc = 0.0f;
-#pragma unroll
-      for (int b = 0; b < 3; ++b) acc = __builtin_fmaf(t[i][b], mg.v[j * 3 + b], acc);
-      U[i][j] = acc;
-    }
-}
-
 template <int M>
 __global__ __launch_bounds__(256) void weight_transform_i8(Geom g, MatG mg,
                                                            const float* __restrict__ w,
                                                            uint32_t* __restrict__ U, float r_u,
                                                            float qmax) {
-  constexpr int n = M + 2, P = n * n;
+  // One thread per (row i of U, k, channel quad); i is uniform per block (blockIdx.y)
+  // so the matrix entries stay in scalar registers.  Splitting the rows over threads
+  // gives this small, latency-bound kernel n times more wavefronts.
+  constexpr int n = M + 2;
   const int cq_per = g.Cp >> 2;
+  const int i = blockIdx.y;
   const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
   const int k = (int)(item / cq_per), cq = (int)(item % cq_per);
   if (k >= g.Kp) return;
-  uint32_t out[P];
+  uint32_t out[n];
 #pragma unroll
-  for (int p = 0; p < P; ++p) out[p] = 0u;
+  for (int j = 0; j < n; ++j) out[j] = 0u;
   if (k < g.K) {
+    const float gi0 = mg.v[i * 3 + 0], gi1 = mg.v[i * 3 + 1], gi2 = mg.v[i * 3 + 2];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int c = cq * 4 + e;
       if (c < g.C) {
         const float* wp = w + ((size_t)k * g.C + c) * 9;
-        float gk[3][3], Ut[n][n];
+        float t[3];
 #pragma unroll
-        for (int a = 0; a < 3; ++a)
+        for (int b = 0; b < 3; ++b) {        // t[b] = (G g)[i][b]
+          float acc = 0.0f;
+          acc = __builtin_fmaf(gi0, wp[0 * 3 + b], acc);
+          acc = __builtin_fmaf(gi1, wp[1 * 3 + b], acc);
+          acc = __builtin_fmaf(gi2, wp[2 * 3 + b], acc);
+          t[b] = acc;
+        }
 #pragma unroll
-          for (int b = 0; b < 3; ++b) gk[a][b] = wp[a * 3 + b];
-        transform_filter<n>(gk, mg, Ut);
+        for (int j = 0; j < n; ++j) {        // U[i][j] = sum_b t[b] G[j][b]
+          float acc = 0.0f;
 #pragma unroll
-        for (int i = 0; i < n; ++i)
-#pragma unroll
-          for (int j = 0; j < n; ++j) {
-            const int q = quantize(Ut[i][j], r_u, qmax);
-            out[i * n + j] |= (uint32_t)(q & 0xff) << (8 * e);
-          }
+          for (int b = 0; b < 3; ++b) acc = __builtin_fmaf(t[b], mg.v[j * 3 + b], acc);
+          const int q = quantize(acc, r_u, qmax);
+          out[j] |= (uint32_t)(q & 0xff) << (8 * e);
+        }
       }
     }
   }
   const size_t pstride = (size_t)g.Kp * cq_per;
-  uint32_t* up = U + (size_t)k * cq_per + cq;
+  uint32_t* up = U + (size_t)i * n * pstride + (size_t)k * cq_per + cq;
 #pragma unroll
-  for (int p = 0; p < P; ++p) up[p * pstride] = out[p];
+  for (int j = 0; j < n; ++j) up[j * pstride] = out[j];
 }
 
 template <int M>
@@ -231,35 +166,10 @@ __global__ __launch_bounds__(256) void weight_transform_f32(Geom g, MatG mg,
 }
 
 // ------------------------------------------------------------------ output --
-// Yt = A^T Mt A for one (tile, output channel).
-template <int M>
-__device__ __forceinline__ void transform_result(const float (&Mt)[M + 2][M + 2], const MatAT& at,
-                                                 float (&Y)[M][M]) {
-  constexpr int n = M + 2;
-  float z[M][n];
-#pragma unroll
-  for (int a = 0; a < M; ++a)
-#pragma unroll
-    for (int j = 0; j < n; ++j) {
-      float acc = 0.0f;
-#pragma unroll
-      for (int i = 0; i < n; ++i) acc = __builtin_fmaf(at.v[a * n + i], Mt[i][j], acc);
-      z[a][j] = acc;
-    }
-#pragma unroll
-  for (int a = 0; a < M; ++a)
-#pragma unroll
-    for (int b = 0; b < M; ++b) {
-      float acc = 0.0f;
-#pragma unroll
-      for (int j = 0; j < n; ++j) acc = __builtin_fmaf(z[a][j], at.v[b * n + j], acc);
-      Y[a][b] = acc;
-    }
-}
-
-// One thread per (tile, output channel); lanes run along k so that the reads of M
-// are contiguous.
-template <int M, bool I8>
+// Stand-alone output transform (used when M is materialised: per-stage calls and
+// the parity tap).  One thread per (tile, output channel); lanes run along k so
+// that the reads of M are contiguous.
+template <int M, bool I8, bool kSparse>
 __global__ __launch_bounds__(256) void output_transform(Geom g, MatAT at,
                                                         const void* __restrict__ Mv,
                                                         void* __restrict__ yv, float r_m,
@@ -283,7 +193,7 @@ __global__ __launch_bounds__(256) void output_transform(Geom g, MatAT at,
         Mt[i][j] = ((const float*)Mv)[(i * n + j) * pstride + base];
       }
     }
-  transform_result<M>(Mt, at, Y);
+  transform_result<M, kSparse>(Mt, at, Y);
   const int tw = t % g.TW, th = (t / g.TW) % g.TH, img = t / (g.TW * g.TH);
   const size_t ybase = ((size_t)img * g.K + k) * g.Ho * g.Wo;
 #pragma unroll
@@ -318,30 +228,66 @@ __global__ __launch_bounds__(256) void export_kernel(const T* __restrict__ src,
 
 unsigned blocks_for(long long items) { return (unsigned)((items + 255) / 256); }
 
+// Block shape of the int8 input transform: TWB tiles of RB tile rows per workgroup,
+// about 16 tiles (256 threads x 1 item), LDS kept under 64 KB.
+template <int M, bool kSparse>
+hipError_t launch_input_i8(const Geom& g, const MatBT& bt, const int8_t* x, uint32_t* V, float r_v,
+                           float qmax, hipStream_t s) {
+  constexpr int n = M + 2;
+  const int R = g.N * g.TH;
+  // 16, 8 or 4 tiles per workgroup: the largest that still gives every CU several
+  // workgroups to overlap one's loads with another's math.
+  const long long tc = (long long)R * g.TW * (g.Cp / 64);      // tiles x channel blocks
+  int tiles = 16;
+  while (tiles > 4 && tc / tiles < 1024) tiles >>= 1;
+  int TWB = g.TW < tiles ? g.TW : tiles;
+  int RB = tiles / TWB;
+  if (RB > R) RB = R;
+  if (RB < 1) RB = 1;
+  auto lds_bytes = [&](int rb, int twb) { return (size_t)stage_dwords<M>(rb, twb) * 4; };
+  while (lds_bytes(RB, TWB) > 65536 && RB > 1) --RB;
+  while (lds_bytes(RB, TWB) > 65536 && TWB > 1) --TWB;
+  const int ntwb = (g.TW + TWB - 1) / TWB, nrb = (R + RB - 1) / RB;
+  if ((long long)ntwb * nrb > 0x7fffffffLL || g.Cp / 64 > 65535) return hipErrorInvalidValue;
+  dim3 grid((unsigned)(ntwb * nrb), (unsigned)(g.Cp / 64));
+  int threads = RB * TWB * 16;
+  threads = threads <= 64 ? 64 : threads <= 128 ? 128 : 256;
+  const int strip = n * (stage_cols(M, TWB) / 4);          // staging lanes one strip needs
+  while (threads < strip) threads *= 2;
+  if (threads > 256) return hipErrorInvalidValue;          // cannot happen for TWB <= 16
+  const size_t lb = lds_bytes(RB, TWB);
+  if (g.W >= 4)
+    input_transform_i8<M, kSparse, true><<<grid, threads, lb, s>>>(g, bt, x, V, r_v, qmax, RB, TWB);
+  else
+    input_transform_i8<M, kSparse, false><<<grid, threads, lb, s>>>(g, bt, x, V, r_v, qmax, RB, TWB);
+  return hipGetLastError();
+}
+
+template <int M>
+hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
+                          float qmax, hipStream_t s) {
+  const bool sparse = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt);
+  if (g.i8) {
+    return sparse ? launch_input_i8<M, true>(g, bt, (const int8_t*)x, (uint32_t*)V, r_v, qmax, s)
+                  : launch_input_i8<M, false>(g, bt, (const int8_t*)x, (uint32_t*)V, r_v, qmax, s);
+  }
+  const unsigned nb = blocks_for((long long)g.Tp * g.Cp);
+  if (sparse)
+    input_transform_f32<M, true><<<nb, 256, 0, s>>>(g, bt, (const float*)x, (float*)V);
+  else
+    input_transform_f32<M, false><<<nb, 256, 0, s>>>(g, bt, (const float*)x, (float*)V);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_input_transform(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
                                   float qmax, hipStream_t s) {
-  if (g.i8) {
-    const unsigned nb = blocks_for((long long)g.Tp * (g.Cp / 4));
-    const int8_t* xi = (const int8_t*)x;
-    uint32_t* Vo = (uint32_t*)V;
-    switch (g.m) {
-      case 2: input_transform_i8<2><<<nb, 256, 0, s>>>(g, bt, xi, Vo, r_v, qmax); break;
-      case 4: input_transform_i8<4><<<nb, 256, 0, s>>>(g, bt, xi, Vo, r_v, qmax); break;
-      default: input_transform_i8<6><<<nb, 256, 0, s>>>(g, bt, xi, Vo, r_v, qmax); break;
-    }
-  } else {
-    const unsigned nb = blocks_for((long long)g.Tp * g.Cp);
-    const float* xf = (const float*)x;
-    float* Vo = (float*)V;
-    switch (g.m) {
-      case 2: input_transform_f32<2><<<nb, 256, 0, s>>>(g, bt, xf, Vo); break;
-      case 4: input_transform_f32<4><<<nb, 256, 0, s>>>(g, bt, xf, Vo); break;
-      default: input_transform_f32<6><<<nb, 256, 0, s>>>(g, bt, xf, Vo); break;
-    }
+  switch (g.m) {
+    case 2: return launch_input_m<2>(g, bt, x, V, r_v, qmax, s);
+    case 4: return launch_input_m<4>(g, bt, x, V, r_v, qmax, s);
+    default: return launch_input_m<6>(g, bt, x, V, r_v, qmax, s);
   }
-  return hipGetLastError();
 }
 
 hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w, void* U, float r_u,
@@ -350,9 +296,9 @@ hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w
     const unsigned nb = blocks_for((long long)g.Kp * (g.Cp / 4));
     uint32_t* Uo = (uint32_t*)U;
     switch (g.m) {
-      case 2: weight_transform_i8<2><<<nb, 256, 0, s>>>(g, mg, w, Uo, r_u, qmax); break;
-      case 4: weight_transform_i8<4><<<nb, 256, 0, s>>>(g, mg, w, Uo, r_u, qmax); break;
-      default: weight_transform_i8<6><<<nb, 256, 0, s>>>(g, mg, w, Uo, r_u, qmax); break;
+      case 2: weight_transform_i8<2><<<dim3(nb, 4), 256, 0, s>>>(g, mg, w, Uo, r_u, qmax); break;
+      case 4: weight_transform_i8<4><<<dim3(nb, 6), 256, 0, s>>>(g, mg, w, Uo, r_u, qmax); break;
+      default: weight_transform_i8<6><<<dim3(nb, 8), 256, 0, s>>>(g, mg, w, Uo, r_u, qmax); break;
     }
   } else {
     const unsigned nb = blocks_for((long long)g.Kp * g.Cp);
@@ -366,23 +312,33 @@ hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w
   return hipGetLastError();
 }
 
+namespace {
+template <int M, bool I8>
+hipError_t launch_output_m(const Geom& g, const MatAT& at, const void* Mv, void* y, float r_m,
+                           float r_y, float qmax, hipStream_t s) {
+  const unsigned nb = blocks_for((long long)g.T * g.Kp);
+  if (fits_mask(at.v, g.m * g.n, CookToomMask<M>::at))
+    output_transform<M, I8, true><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  else
+    output_transform<M, I8, false><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  return hipGetLastError();
+}
+}  // namespace
+
 hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M, void* y, float r_m,
                                    float r_y, float qmax, hipStream_t s) {
-  const unsigned nb = blocks_for((long long)g.T * g.Kp);
   if (g.i8) {
     switch (g.m) {
-      case 2: output_transform<2, true><<<nb, 256, 0, s>>>(g, at, M, y, r_m, r_y, qmax); break;
-      case 4: output_transform<4, true><<<nb, 256, 0, s>>>(g, at, M, y, r_m, r_y, qmax); break;
-      default: output_transform<6, true><<<nb, 256, 0, s>>>(g, at, M, y, r_m, r_y, qmax); break;
-    }
-  } else {
-    switch (g.m) {
-      case 2: output_transform<2, false><<<nb, 256, 0, s>>>(g, at, M, y, r_m, r_y, qmax); break;
-      case 4: output_transform<4, false><<<nb, 256, 0, s>>>(g, at, M, y, r_m, r_y, qmax); break;
-      default: output_transform<6, false><<<nb, 256, 0, s>>>(g, at, M, y, r_m, r_y, qmax); break;
+      case 2: return launch_output_m<2, true>(g, at, M, y, r_m, r_y, qmax, s);
+      case 4: return launch_output_m<4, true>(g, at, M, y, r_m, r_y, qmax, s);
+      default: return launch_output_m<6, true>(g, at, M, y, r_m, r_y, qmax, s);
     }
   }
-  return hipGetLastError();
+  switch (g.m) {
+    case 2: return launch_output_m<2, false>(g, at, M, y, r_m, r_y, qmax, s);
+    case 4: return launch_output_m<4, false>(g, at, M, y, r_m, r_y, qmax, s);
+    default: return launch_output_m<6, false>(g, at, M, y, r_m, r_y, qmax, s);
+  }
 }
 
 hipError_t launch_export(const Geom& g, int which, const void* src, void* out, hipStream_t s) {

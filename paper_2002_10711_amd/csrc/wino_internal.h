@@ -38,6 +38,14 @@ hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, const void* A, con
                        void* M, hipStream_t s);
 hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M, void* y,
                                    float r_m, float r_y, float qmax, hipStream_t s);
+// GEMM and output transform in one kernel (M stays in registers).
+hipError_t launch_gemm_out(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
+                           float r_m, float r_y, float qmax, hipStream_t s);
+// Whole int8 forward in one kernel (neither V nor M stored); only where supported.
+bool fused_fwd_supported(const Geom& g);
+hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                            const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
+                            hipStream_t s);
 hipError_t launch_export(const Geom& g, int which, const void* src, void* out, hipStream_t s);
 
 // im2row baseline pieces.

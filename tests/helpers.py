@@ -41,9 +41,17 @@ def run_gpu(case, taps=True, scales=None):
     Ho, Wo = L.H + 2 * L.pad - 2, L.W + 2 * L.pad - 2
     y = torch.full((L.N, L.K, Ho, Wo), 77, dtype=torch.int8 if i8 else torch.float32, device=dev)
     wb.wino_transform_weights(desc, quant, g, U)
+    # the whole forward in one call (GEMM and output transform fused, M never stored)
     wb.wino_conv2d_fwd(desc, quant, x, U, y, ws)
     torch.cuda.synchronize()
     out = dict(Y=y.cpu().numpy())
+    # stage by stage, which materialises V and M for the taps
+    y2 = torch.full_like(y, 55)
+    ws.zero_()
+    for stage in (wb.WINO_STAGE_INPUT, wb.WINO_STAGE_GEMM, wb.WINO_STAGE_OUTPUT):
+        wb.wino_conv2d_fwd_stages(desc, quant, x, U, y2, ws, stage)
+    torch.cuda.synchronize()
+    out["Y_staged"] = y2.cpu().numpy()
     if taps:
         n = L.m + 2
         P = n * n
