@@ -176,10 +176,11 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
   }
   if (stages == WINO_STAGE_ALL && fused_fwd_supported(g)) {
     // the whole forward in one kernel: V and M stay on chip, the workspace is untouched
-    if (launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs) !=
-        hipSuccess)
-      return WINO_E_HIP;
-    return WINO_OK;
+    const hipError_t e =
+        fused_fwd_exact_supported(g, bt)
+            ? launch_fused_fwd_exact(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs)
+            : launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs);
+    return e == hipSuccess ? WINO_OK : WINO_E_HIP;
   }
   if (s_in && launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs) != hipSuccess)
     return WINO_E_HIP;

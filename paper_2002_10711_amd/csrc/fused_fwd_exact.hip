@@ -1,0 +1,356 @@
+// Single-kernel int8 forward for F(4x4,3x3) when the input transform is EXACT, with
+// the input transform itself on the matrix cores.
+//
+// If 2^s B^T is an integer matrix (s <= 3; true for Cook-Toom points 0, +-1, +-1/2:
+// 4 B^T has entries 0, +-1, +-2, +-4, +-5) and the input holds int8 codes, then every
+// partial sum of B^T d B is a small dyadic rational that fp32 represents exactly, so
+// the order of evaluation cannot change a bit of it.  The transform of a whole patch
+// is then one integer matrix-vector product
+//
+//     4^s V[(i,k)] = sum_{(j,l)} (2^s B^T[i][j] * 2^s B^T[k][l]) * d[(j,l)]
+//
+// with int8 factors: a 36 x 64 int8 matrix W (the Kronecker square of 2^s B^T, patch
+// index (j,l) padded to 8 x 8) times the 8 x 8 byte window of the image that starts
+// at the tile's top-left corner.  v_mfma_i32_16x16x64_i8 does 16 such windows
+// (16 channels of one tile) per instruction, three instructions for the 36 positions.
+// Window bytes outside the 6 x 6 patch meet zero columns of W, so they need not be
+// cleared; only pixels outside the image must be zero.
+// The quantizer keeps its definition: V * r_v = (4^s V) * (r_v / 4^s), both exact
+// scalings, then round-half-even and saturate (Sec. 3.2, Sec. 5.1).
+//
+// The rest is the fused forward of fused_fwd.hip: quantized V goes to LDS as the
+// channel-contiguous operand of the per-position GEMMs, whose accumulators stay in
+// registers for the lane-local output transform.  Per 64 input channels:
+//   1. stage n rows x (4 TWB + 4) bytes per channel and tile row into LDS, plain
+//      copy in image order (coalesced loads, conflict-free LDS stores);
+//   2. every lane gathers its window operands (two 8-byte row pieces per window)
+//      into registers; barrier; the staging area is now free and is reused as Vl;
+//   3. per window group: 3 MFMAs against W (held in registers, built by the host),
+//      windows as the "A" operand so that a lane receives four consecutive channels
+//      of one position: quantize, pack into a dword, store into Vl[p][tile][channel];
+//   4. barrier; wave w: one MFMA per position against U[p][16 k of w][64 c].
+#include "input_stage.h"
+#include "output_stage.h"
+
+// Development aid, compiled only with -DWINO_PROFILE_PHASES: every wavefront records the
+// shader clock at its phase boundaries; wino_debug_read_phases() copies them out.
+#ifdef WINO_PROFILE_PHASES
+__device__ unsigned long long wino_phase_ts[4096 * 8];
+#define WINO_TS(slot)                                                                     \
+  if ((threadIdx.x & 63) == 0 && blockIdx.y == 0 && blockIdx.x < 1024)                      \
+    wino_phase_ts[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (slot)] = __builtin_amdgcn_s_memtime()
+extern "C" int wino_debug_read_phases(unsigned long long* host, size_t count) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(wino_phase_ts), count * sizeof(unsigned long long));
+}
+#else
+#define WINO_TS(slot)
+#endif
+
+namespace wino {
+namespace {
+
+constexpr int kXM = 4, kXN = 6, kXP = 36;   // this file is F(4x4,3x3) only
+
+// LDS geometry of the staged input: a row is TWB + 1 dwords (image columns
+// tw0*4 - pad .. + 4 TWB + 3), a channel plane is n rows plus one dword so that the 16
+// channels of a window group fall into 16 different banks.
+__host__ __device__ inline int xs_row_dw(int TWB) { return TWB + 1; }
+__host__ __device__ inline int xs_plane_dw(int TWB) { return (kXN * xs_row_dw(TWB)) | 1; }
+
+// Vl: quantized transformed input, [position][tile][64 channels]; the position pitch is
+// padded by 4 dwords so that the 16 positions a wavefront stores at once fall into
+// different banks.
+constexpr int kVlPitch = 16 * 16 + 4;
+
+// The Kronecker matrix W[p][(j,l)] = (2^s B^T)[i][j] * (2^s B^T)[k][l], p = i*6 + k, laid out
+// by the host as MFMA operand registers: w[(blk*64 + lane)*4 .. +3] are the 16 bytes
+// (j, l) = (2*(lane/16) + b/8, b%8), b = 0..15, of row p = blk*16 + lane%16 (zero for
+// p >= 36 and for j, l >= 6).
+struct KronW { uint32_t v[3 * 64 * 4]; };
+
+struct __attribute__((packed, aligned(4))) U64A4 { uint32_t lo, hi; };   // 8 bytes, dword aligned
+
+// kLoad: 0 = byte loads (W < 4), 1 = one dword per lane at any byte address,
+// 2 = 8 bytes per lane from a dword-aligned address (W % 4 == 0, W >= 8, x aligned).
+template <int kLoad>
+__device__ __forceinline__ void stage_planes(const Geom& g, const int8_t* __restrict__ x,
+                                             uint32_t* Xs, int c0, int r0, int tw0, int RB,
+                                             int TWB) {
+  // Same lane mapping and branch-free batched loads as stage_strips (input_stage.h);
+  // the dwords are stored as they are: Xs[(rs*64 + c)*plane + j*row + lq].
+  constexpr int n = kXN, M = kXM;
+  const int WQ = xs_row_dw(TWB), plane = xs_plane_dw(TWB);
+  const int R = g.N * g.TH;
+  const int wbase = tw0 * M - g.pad;
+  const int nthr = blockDim.x, tid = threadIdx.x;
+  const int strip = WQ * n;
+  const int slots = nthr / strip;
+  const int sidx = tid / strip, rem = tid - sidx * strip;
+  const int j = rem / WQ, lq = rem - j * WQ;
+  const bool lane_on = sidx < slots;
+  const int w = wbase + lq * 4;                    // first of the lane's four image columns
+  // wl: column the lane really loads from; the wanted bytes are the loaded ones shifted
+  // by (w - wl) bytes (right if positive, left if negative, zero fill).
+  int wl = 0, lsh = 0, rsh = 0;
+  bool overlap = true;
+  if (kLoad == 1) {
+    wl = w < 0 ? 0 : (w > g.W - 4 ? g.W - 4 : w);
+    overlap = w - wl > -4 && w - wl < 4;
+  } else if (kLoad == 2) {
+    const int wa = w & ~3;
+    wl = wa < 0 ? 0 : (wa > g.W - 8 ? g.W - 8 : wa);
+    overlap = w - wl > -4 && w - wl < 8;
+  }
+  if (kLoad != 0 && overlap) {
+    lsh = w < wl ? 8 * (wl - w) : 0;
+    rsh = w > wl ? 8 * (w - wl) : 0;
+  }
+  const int chs = g.H * g.W;
+  const int npass = (16 + slots - 1) / slots;
+  constexpr int kBatch = 8;
+  uint32_t* dump = Xs + RB * 64 * plane;          // 4 dwords nobody reads
+  for (int rs = 0; rs < RB; ++rs) {
+    const int r = r0 + rs;
+    const int rc = r < R ? r : R - 1;
+    const int img = rc / g.TH, th = rc - img * g.TH;
+    const int h = th * M - g.pad + j;
+    const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
+    const bool rowok = lane_on && r < R && h == hc && overlap;
+    const int8_t* base = x + ((size_t)img * g.C + c0) * chs + (size_t)hc * g.W + wl;
+    uint32_t* xrow = Xs + (rs * 64) * plane + j * WQ + lq;
+    for (int ps0 = 0; ps0 < npass; ps0 += kBatch) {
+      uint64_t q[kBatch][4];
+      int off[kBatch][4];
+      uint32_t msk[kBatch][4];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int cq = (ps0 + u) * slots + sidx;
+        const bool ok = rowok && cq < 16;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int cl = cq * 4 + e;
+          const bool cok = ok && c0 + cl < g.C;
+          msk[u][e] = 0u - (uint32_t)cok;
+          off[u][e] = (cl * chs) & (int)msk[u][e];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if constexpr (kLoad == 2) {
+            const U64A4 t = *(const U64A4*)(base + off[u][e]);
+            q[u][e] = ((uint64_t)t.hi << 32) | t.lo;
+          } else if constexpr (kLoad == 1) {
+            q[u][e] = ((const UnalignedU32*)(base + off[u][e]))->v;
+          } else {
+            q[u][e] = load_quad_guarded(base + off[u][e], w, g.W);
+          }
+        }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int cq = (ps0 + u) * slots + sidx;
+        const bool live = lane_on && cq < 16;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t v = (uint32_t)((q[u][e] << lsh) >> rsh) & msk[u][e];
+          uint32_t* dst = live ? xrow + (cq * 4 + e) * plane : dump;
+          *dst = v;
+        }
+      }
+    }
+  }
+}
+
+template <bool kSparseA, int kLoad, bool kMQ>
+__global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
+    Geom g, MatAT at, KronW kw, const int8_t* __restrict__ x, const int8_t* __restrict__ U,
+    void* __restrict__ y, float r_vs, float r_m, float r_y, float qmax, int RB, int TWB) {
+  constexpr int n = kXN, P = kXP, M = kXM;
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  uint32_t* Xs = lds;
+  uint32_t* Vl = lds;                                  // aliases Xs
+  const int WQ = xs_row_dw(TWB), plane = xs_plane_dw(TWB);
+  const int ntwb = (g.TW + TWB - 1) / TWB;
+  const int twb = blockIdx.x % ntwb, rb = blockIdx.x / ntwb;
+  const int r0 = rb * RB, tw0 = twb * TWB, kb = blockIdx.y * 64;
+  const int R = g.N * g.TH;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  const float lo = kMagic - qmax, hi = kMagic + qmax;
+
+  WINO_TS(0);
+  const int8_t* urow = U + ((size_t)(kb + wave * 16 + r) * g.Cp) + grp * 16;
+  const size_t up = (size_t)g.Kp * g.Cp;
+  v4i acc[P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) acc[p] = v4i{0, 0, 0, 0};
+
+  const int nblk = g.Cp >> 6;
+  for (int cb = 0; cb < nblk; ++cb) {
+    if (cb) __syncthreads();                           // previous block's Vl fully consumed
+    WINO_TS(1);
+    stage_planes<kLoad>(g, x, Xs, cb * 64, r0, tw0, RB, TWB);
+    // the lane's slice of W, as MFMA operand registers (three 16-position blocks)
+    v4i Wb[3];
+#pragma unroll
+    for (int blk = 0; blk < 3; ++blk) Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
+    __syncthreads();
+    WINO_TS(2);
+
+    // Window group gi of this wave: tile tl = wave*4 + gi/4, channels (gi%4)*16 .. +15.
+    // "A" operand row = channel (gi%4)*16 + r: rows 2 grp and 2 grp + 1 of its window,
+    // 8 bytes each (rows 6 and 7 meet zero entries of W: any staged row will do).
+    v4i Aw[16];
+    {
+      const int j0 = 2 * grp < n ? 2 * grp : 0, j1 = 2 * grp + 1 < n ? 2 * grp + 1 : 0;
+#pragma unroll
+      for (int gi = 0; gi < 16; ++gi) {
+        const int tl = wave * 4 + (gi >> 2), c = (gi & 3) * 16 + r;
+        int rs = tl / TWB;
+        const int twl = tl - rs * TWB;
+        rs = rs < RB ? rs : 0;                         // tiles beyond RB*TWB: results unused
+        const uint32_t* p0 = Xs + (rs * 64 + c) * plane + twl;
+        Aw[gi] = v4i{(int)p0[j0 * WQ], (int)p0[j0 * WQ + 1], (int)p0[j1 * WQ], (int)p0[j1 * WQ + 1]};
+      }
+    }
+    // first operands of the per-position GEMMs, so that they arrive during the transform
+    constexpr int kDepth = 9;
+    const int8_t* ub = urow + (size_t)cb * 64;
+    v4i bufU[kDepth];
+#pragma unroll
+    for (int p = 0; p < kDepth; ++p) bufU[p] = *(const v4i*)(ub + p * up);
+    __syncthreads();                                   // Xs is free: Vl may overwrite it
+    WINO_TS(3);
+
+    // D[channel][position]: a lane gets positions p = blk*16 + r of channels
+    // (gi%4)*16 + 4 grp .. + 3, i.e. one dword of Vl per MFMA.
+#pragma unroll
+    for (int gi = 0; gi < 16; ++gi) {
+      const int tl = wave * 4 + (gi >> 2);
+#pragma unroll
+      for (int blk = 0; blk < 3; ++blk) {
+        // every lane takes part in the MFMA; only the stores are predicated
+        const v4i v = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[gi], Wb[blk], v4i{0, 0, 0, 0}, 0, 0, 0);
+        uint32_t packed = 0u;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+          packed = __builtin_amdgcn_perm(quantize_bits((float)v[rr], r_vs, lo, hi), packed, 0x04030201u);
+        const int p = blk * 16 + r;
+        if (p < P) Vl[p * kVlPitch + tl * 16 + (gi & 3) * 4 + grp] = packed;
+      }
+    }
+    __syncthreads();
+    WINO_TS(4);
+
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      const v4i au = bufU[p % kDepth];
+      if (p + kDepth < P) bufU[p % kDepth] = *(const v4i*)(ub + (p + kDepth) * up);
+      const v4i bv = *(const v4i*)(Vl + p * kVlPitch + r * 16 + grp * 4);
+      acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, acc[p], 0, 0, 0);
+    }
+  }
+
+  WINO_TS(5);
+  const int rs = r / TWB, twl = r - rs * TWB;
+  const int rr_ = r0 + rs, tw = tw0 + twl;
+  if (rs < RB && rr_ < R && tw < g.TW) {
+    const int img = rr_ / g.TH, th = rr_ - img * g.TH;
+    finish_lane<M, true, kSparseA, kMQ>(g, at, acc, y, img, th, tw, kb + wave * 16 + grp * 4, r_m,
+                                        r_y, qmax);
+  }
+  WINO_TS(6);
+}
+
+}  // namespace
+
+// Host: smallest s <= 3 with 2^s B^T integral, all pairwise products within int8, and
+// every intermediate of the fp32 evaluation exactly representable (so that integer and
+// float evaluation agree bit for bit); -1 if there is none.
+int exact_input_shift(const Geom& g, const MatBT& bt) {
+  if (!g.i8 || g.m != kXM) return -1;
+  for (int s = 0; s <= 3; ++s) {
+    const float sc = (float)(1 << s);
+    bool ok = true;
+    float amax = 0.0f, rowmax = 0.0f;
+    for (int i = 0; i < g.n && ok; ++i) {
+      float rowsum = 0.0f;
+      for (int j = 0; j < g.n; ++j) {
+        const float v = bt.v[i * g.n + j] * sc;
+        if (!(v <= 127.0f && v >= -127.0f) || v != (float)(int)v) { ok = false; break; }
+        const float a = v < 0 ? -v : v;
+        amax = a > amax ? a : amax;
+        rowsum += a;
+      }
+      rowmax = rowsum > rowmax ? rowsum : rowmax;
+    }
+    if (!ok) continue;
+    if (amax * amax > 127.0f) return -1;
+    // |4^s V| <= 128 * rowmax^2 must stay below 2^24 (fp32 exact integers)
+    if (128.0f * rowmax * rowmax >= 16777216.0f) return -1;
+    return s;
+  }
+  return -1;
+}
+
+bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
+  return g.Kp <= 128 && exact_input_shift(g, bt) >= 0;
+}
+
+hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                                  const void* U, void* y, float r_v, float r_m, float r_y,
+                                  float qmax, hipStream_t s) {
+  const int sft = exact_input_shift(g, bt);
+  if (sft < 0 || g.Kp > 128) return hipErrorInvalidValue;
+  const float bt_scale = (float)(1 << sft);
+  const float r_vs = r_v / (float)(1 << (2 * sft));      // exact power-of-two scaling
+  if (!(r_vs * (float)(1 << (2 * sft)) == r_v)) return hipErrorInvalidValue;   // underflow
+  // W in MFMA register order (see KronW)
+  KronW kw;
+  int bi[8][8] = {};
+  for (int i = 0; i < kXN; ++i)
+    for (int j = 0; j < kXN; ++j) bi[i][j] = (int)(bt.v[i * kXN + j] * bt_scale);
+  for (int blk = 0; blk < 3; ++blk)
+    for (int lane = 0; lane < 64; ++lane) {
+      const int p = blk * 16 + (lane & 15), kgrp = lane >> 4;
+      const int i = p < kXP ? p / kXN : 7, k = p < kXP ? p % kXN : 7;     // row 7 of bi is zero
+      for (int d = 0; d < 4; ++d) {
+        uint32_t word = 0;
+        for (int e = 0; e < 4; ++e) {
+          const int b = d * 4 + e, j = 2 * kgrp + b / 8, l = b % 8;
+          word |= (uint32_t)((bi[i][j] * bi[k][l]) & 0xff) << (8 * e);
+        }
+        kw.v[(blk * 64 + lane) * 4 + d] = word;
+      }
+    }
+  const int R = g.N * g.TH;
+  int TWB = g.TW < 16 ? g.TW : 16;
+  int RB = 16 / TWB;
+  if (RB > R) RB = R;
+  const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(TWB) + 4) * 4, vl_b = (size_t)kXP * kVlPitch * 4;
+  const size_t lb = xs_b > vl_b ? xs_b : vl_b;
+  const int ntwb = (g.TW + TWB - 1) / TWB, nrb = (R + RB - 1) / RB;
+  if (lb > 65536 || (long long)ntwb * nrb > 0x7fffffffLL || kXN * xs_row_dw(TWB) > 256)
+    return hipErrorInvalidValue;
+  dim3 grid((unsigned)(ntwb * nrb), (unsigned)(g.Kp / 64));
+  const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<kXM>::at);
+  const int8_t* xi = (const int8_t*)x;
+  const int8_t* Ui = (const int8_t*)U;
+  const int load = g.W < 4 ? 0 : (g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0) ? 2 : 1;
+  const bool mq = r_m > 0.0f;
+#define WINO_LAUNCH_X(SA, LOAD, MQ)                                                        \
+  fused_fwd_exact_kernel<SA, LOAD, MQ><<<grid, 256, lb, s>>>(g, at, kw, xi, Ui, y, r_vs, r_m, \
+                                                             r_y, qmax, RB, TWB)
+#define WINO_LAUNCH_X2(SA, LOAD) \
+  do { if (mq) WINO_LAUNCH_X(SA, LOAD, true); else WINO_LAUNCH_X(SA, LOAD, false); } while (0)
+#define WINO_LAUNCH_X3(SA)                                                                 \
+  do { if (load == 2) WINO_LAUNCH_X2(SA, 2); else if (load == 1) WINO_LAUNCH_X2(SA, 1);    \
+       else WINO_LAUNCH_X2(SA, 0); } while (0)
+  if (sa) WINO_LAUNCH_X3(true); else WINO_LAUNCH_X3(false);
+#undef WINO_LAUNCH_X3
+#undef WINO_LAUNCH_X2
+#undef WINO_LAUNCH_X
+  return hipGetLastError();
+}
+
+}  // namespace wino

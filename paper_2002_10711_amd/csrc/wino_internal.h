@@ -46,6 +46,11 @@ bool fused_fwd_supported(const Geom& g);
 hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                             const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
                             hipStream_t s);
+// The same for F(4x4,3x3) with an exact (dyadic) B^T: input transform on the matrix cores.
+bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt);
+hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                                  const void* U, void* y, float r_v, float r_m, float r_y,
+                                  float qmax, hipStream_t s);
 hipError_t launch_export(const Geom& g, int which, const void* src, void* out, hipStream_t s);
 
 // im2row baseline pieces.
