@@ -146,8 +146,12 @@ def gpu_leg(L, steps, warmup, use_graph):
     ms_fwd = timed(fwd_only, steps, warmup)
 
     # per-kernel durations: the same step, with events between the kernels
-    if wb.wino_fwd_num_kernels(desc) == 1:
+    nk = wb.wino_fwd_num_kernels(desc)
+    if nk == 1:
         stages = [("weight_transform", None), ("fused_forward", wb.WINO_STAGE_ALL)]
+    elif nk == 3:
+        stages = [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
+                  ("gemm", wb.WINO_STAGE_GEMM), ("output_transform", wb.WINO_STAGE_OUTPUT)]
     else:
         stages = [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
                   ("gemm_output", wb.WINO_STAGE_GEMM | wb.WINO_STAGE_OUTPUT)]

@@ -116,7 +116,8 @@ wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void*
 /* How many kernels wino_conv2d_fwd launches for this problem (0 if the descriptor is
  * invalid): 1 = input transform, GEMM and output transform in one kernel (small int8
  * layers; V and M never reach memory), 2 = input transform, then GEMM fused with the
- * output transform (M never reaches memory). */
+ * output transform (M never reaches memory), 3 = input transform, tiled GEMM, output
+ * transform (long reductions, F(6x6,3x3)). */
 int wino_fwd_num_kernels(const wino_desc* d);
 
 /* The same forward, restricted to the stages named in `stages` (a mask of

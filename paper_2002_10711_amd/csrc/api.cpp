@@ -139,7 +139,7 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, cons
 int wino_fwd_num_kernels(const wino_desc* d) {
   Geom g;
   if (make_geom(d, &g) != WINO_OK) return 0;
-  return fused_fwd_supported(g) ? 1 : 2;
+  return fused_fwd_supported(g) ? 1 : gemm_out_preferred(g) ? 2 : 3;
 }
 
 wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
@@ -184,9 +184,13 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
   }
   if (s_in && launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs) != hipSuccess)
     return WINO_E_HIP;
-  if (s_mm && s_out) {
-    // both stages requested together: M stays in registers and is never written
+  if (s_mm && s_out && gemm_out_preferred(g)) {
+    // short reductions: GEMM and output transform in one kernel, M stays in registers
     if (launch_gemm_out(g, at, V, U_dev, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+      return WINO_E_HIP;
+  } else if (s_mm && s_out) {
+    if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
+    if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;
   } else if (s_mm) {
     if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;

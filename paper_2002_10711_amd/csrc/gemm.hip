@@ -4,10 +4,23 @@
 //     M[p][t][k] = sum_c A[p][t][c] * B[p][k][c]
 //
 // Both operands are channel-contiguous, which is the operand order the gfx950
-// matrix cores want: a lane of v_mfma_i32_16x16x64_i8 supplies 16 consecutive
-// bytes of the reduction axis for one row.  int8 x int8 -> int32 is exact;
-// the float variant accumulates in fp32.  The same kernels serve the im2row
-// baseline with P = 1 and a reduction length of 9*C.
+// matrix cores want: a lane of v_mfma_i32_16x16x64_i8 supplies 16 consecutive bytes
+// of the reduction axis for one row (v_mfma_f32_16x16x4_f32: 4 consecutive floats,
+// fed one at a time).  int8 x int8 -> int32 is exact; the float variant accumulates
+// in fp32.  This stand-alone GEMM (M goes to memory) serves the layers whose
+// accumulators do not fit the fused kernels, the per-stage calls and parity taps, and
+// the im2row baseline with P = 1 and a reduction length of 9*C.
+//
+// Tiling: workgroup = 2 x 2 wavefronts; a wavefront owns WT x WK MFMA tiles of
+// 16 x 16, so the block is (32 WT) tiles x (32 WK) output channels.  The reduction
+// runs in steps of 64 bytes per row: the block's A rows and B rows of a step are
+// copied to LDS once (16 bytes per thread and row piece, double buffered, the next
+// step's global loads in flight during the MFMAs) and every wave reads its
+// operands from there with 16-byte LDS reads, each reused WK (resp. WT) times from
+// registers.  The weights are the MFMA "A" operand (rows = k) and the activations
+// the "B" operand (columns = t), so a lane ends up with four consecutive k of one
+// tile and stores 16 bytes at once.  Whatever order the instruction assigns to the
+// reduction elements inside a lane group, it is the same for both operands.
 #include "wino_internal.h"
 
 namespace wino {
@@ -16,67 +29,103 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-// Block = 4 wavefronts = 64 tiles x 64 output channels of one position.
-// Wave w owns tiles [16w, 16w+16) and four 16x16 MFMA accumulators along k.
-// The weights are the MFMA "A" operand (rows = k) and the activations the "B"
-// operand (columns = t), so a lane ends up with four consecutive k of one tile
-// and stores 16 bytes at once.  Whatever order the instruction assigns to the 64
-// reduction elements inside a lane group, it is the same for both operands, so
-// the sum is over matching channels.
-__global__ __launch_bounds__(256) void gemm_i8_kernel(const int8_t* __restrict__ A,
-                                                      const int8_t* __restrict__ B,
-                                                      int32_t* __restrict__ M, int Tp, int Kp,
-                                                      int Cp) {
-  const int p = blockIdx.z, tb = blockIdx.x * 64, kb = blockIdx.y * 64;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, grp = lane >> 4;
-  const int t = tb + wave * 16 + r;
-  const int8_t* vrow = A + ((size_t)p * Tp + t) * Cp + grp * 16;
-  const int8_t* urow = B + ((size_t)p * Kp + kb + r) * Cp + grp * 16;
-  v4i acc[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) acc[j] = (v4i){0, 0, 0, 0};
-  for (int c0 = 0; c0 < Cp; c0 += 64) {
-    const v4i bv = *(const v4i*)(vrow + c0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const v4i au = *(const v4i*)(urow + (size_t)j * 16 * Cp + c0);
-      acc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, acc[j], 0, 0, 0);
-    }
-  }
-  int32_t* mrow = M + ((size_t)p * Tp + t) * Kp + kb + grp * 4;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) *(v4i*)(mrow + j * 16) = acc[j];
-}
+template <bool I8> struct AccT { typedef v4i type; };
+template <> struct AccT<false> { typedef v4f type; };
 
-// Same blocking with v_mfma_f32_16x16x4_f32: a lane loads four consecutive
-// channels and feeds them to four MFMA steps; the step order permutes the
-// channels inside a chunk of 16, identically for both operands.
-__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A,
-                                                       const float* __restrict__ B,
-                                                       float* __restrict__ M, int Tp, int Kp,
-                                                       int Cp) {
-  const int p = blockIdx.z, tb = blockIdx.x * 64, kb = blockIdx.y * 64;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, grp = lane >> 4;
-  const int t = tb + wave * 16 + r;
-  const float* vrow = A + ((size_t)p * Tp + t) * Cp + grp * 4;
-  const float* urow = B + ((size_t)p * Kp + kb + r) * Cp + grp * 4;
-  v4f acc[4];
+template <int WT, int WK, bool I8>
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(const char* __restrict__ A,
+                                                         const char* __restrict__ B,
+                                                         char* __restrict__ M, int Tp, int Kp,
+                                                         int row_bytes) {
+  constexpr int BT = 32 * WT, BK = 32 * WK;            // block tile
+  constexpr int LA = BT * 4 / 256, LB = BK * 4 / 256;  // 16-byte pieces per thread and step
+  typedef typename AccT<I8>::type acc_t;
+  __shared__ __attribute__((aligned(16))) char As[2][BT * 64];
+  __shared__ __attribute__((aligned(16))) char Bs[2][BK * 64];
+  const int p = blockIdx.z, tb = blockIdx.x * BT, kb = blockIdx.y * BK;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  const int wt = wave >> 1, wk = wave & 1;             // position of the wave in the block
+  const char* Ag = A + ((size_t)p * Tp + tb) * row_bytes;
+  const char* Bg = B + ((size_t)p * Kp + kb) * row_bytes;
+  const int nstep = row_bytes >> 6;
+
+  acc_t acc[WT][WK];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
-  for (int c0 = 0; c0 < Cp; c0 += 16) {
-    const v4f bv = *(const v4f*)(vrow + c0);
+  for (int i = 0; i < WT; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const v4f au = *(const v4f*)(urow + (size_t)j * 16 * Cp + c0);
-      acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(au.x, bv.x, acc[j], 0, 0, 0);
-      acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(au.y, bv.y, acc[j], 0, 0, 0);
-      acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(au.z, bv.z, acc[j], 0, 0, 0);
-      acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(au.w, bv.w, acc[j], 0, 0, 0);
-    }
+    for (int j = 0; j < WK; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
+
+  // piece q of a tile: row q / 4, bytes (q % 4) * 16 .. + 15 of the step
+  v4i ra[LA], rb[LB];
+#pragma unroll
+  for (int u = 0; u < LA; ++u) {
+    const int q = tid + u * 256;
+    ra[u] = *(const v4i*)(Ag + (size_t)(q >> 2) * row_bytes + (q & 3) * 16);
   }
-  float* mrow = M + ((size_t)p * Tp + t) * Kp + kb + grp * 4;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) *(v4f*)(mrow + j * 16) = acc[j];
+  for (int u = 0; u < LB; ++u) {
+    const int q = tid + u * 256;
+    rb[u] = *(const v4i*)(Bg + (size_t)(q >> 2) * row_bytes + (q & 3) * 16);
+  }
+#pragma unroll
+  for (int u = 0; u < LA; ++u) *(v4i*)(As[0] + (tid + u * 256) * 16) = ra[u];
+#pragma unroll
+  for (int u = 0; u < LB; ++u) *(v4i*)(Bs[0] + (tid + u * 256) * 16) = rb[u];
+  __syncthreads();
+
+  for (int st = 0; st < nstep; ++st) {
+    const int cur = st & 1;
+    const bool more = st + 1 < nstep;
+    if (more) {
+      const size_t co = (size_t)(st + 1) * 64;
+#pragma unroll
+      for (int u = 0; u < LA; ++u) {
+        const int q = tid + u * 256;
+        ra[u] = *(const v4i*)(Ag + (size_t)(q >> 2) * row_bytes + co + (q & 3) * 16);
+      }
+#pragma unroll
+      for (int u = 0; u < LB; ++u) {
+        const int q = tid + u * 256;
+        rb[u] = *(const v4i*)(Bg + (size_t)(q >> 2) * row_bytes + co + (q & 3) * 16);
+      }
+    }
+    acc_t va[WT], vb[WK];
+#pragma unroll
+    for (int i = 0; i < WT; ++i)
+      va[i] = *(const acc_t*)(As[cur] + ((wt * WT + i) * 16 + r) * 64 + grp * 16);
+#pragma unroll
+    for (int j = 0; j < WK; ++j)
+      vb[j] = *(const acc_t*)(Bs[cur] + ((wk * WK + j) * 16 + r) * 64 + grp * 16);
+#pragma unroll
+    for (int i = 0; i < WT; ++i)
+#pragma unroll
+      for (int j = 0; j < WK; ++j) {
+        if constexpr (I8) {
+          acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vb[j], va[i], acc[i][j], 0, 0, 0);
+        } else {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[j].x, va[i].x, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[j].y, va[i].y, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[j].z, va[i].z, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(vb[j].w, va[i].w, acc[i][j], 0, 0, 0);
+        }
+      }
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < LA; ++u) *(v4i*)(As[cur ^ 1] + (tid + u * 256) * 16) = ra[u];
+#pragma unroll
+      for (int u = 0; u < LB; ++u) *(v4i*)(Bs[cur ^ 1] + (tid + u * 256) * 16) = rb[u];
+    }
+    __syncthreads();
+  }
+
+  // lane holds, per tile (i, j): t = tb + (wt*WT + i)*16 + r, k = kb + (wk*WK + j)*16 + grp*4 .. +3
+#pragma unroll
+  for (int i = 0; i < WT; ++i) {
+    const int t = tb + (wt * WT + i) * 16 + r;
+    char* mrow = M + (((size_t)p * Tp + t) * Kp + kb + wk * WK * 16 + grp * 4) * 4;
+#pragma unroll
+    for (int j = 0; j < WK; ++j) *(acc_t*)(mrow + j * 64) = acc[i][j];
+  }
 }
 
 }  // namespace
@@ -84,14 +133,28 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, const void* A, const void* B, void* M,
                        hipStream_t s) {
   // Tp, Kp are multiples of 64; Cp of 64 (int8) or 16 (float): the host API rounds them.
-  if (Tp % 64 || Kp % 64 || Cp % (i8 ? 64 : 16) || P < 1 || P > 65535 || Kp / 64 > 65535)
-    return hipErrorInvalidValue;
-  dim3 grid(Tp / 64, Kp / 64, P);
-  if (i8)
-    gemm_i8_kernel<<<grid, 256, 0, s>>>((const int8_t*)A, (const int8_t*)B, (int32_t*)M, Tp, Kp,
-                                        Cp);
-  else
-    gemm_f32_kernel<<<grid, 256, 0, s>>>((const float*)A, (const float*)B, (float*)M, Tp, Kp, Cp);
+  if (Tp % 64 || Kp % 64 || Cp % (i8 ? 64 : 16) || P < 1 || P > 65535) return hipErrorInvalidValue;
+  const int row_bytes = Cp * (i8 ? 1 : 4);
+  const char* a = (const char*)A;
+  const char* b = (const char*)B;
+  char* m = (char*)M;
+  // 128 x 128 blocks when both extents allow it and the grid still fills the chip
+  const bool big = Tp % 128 == 0 && Kp % 128 == 0 && (long long)(Tp / 128) * (Kp / 128) * P >= 512;
+  if (big) {
+    if (Kp / 128 > 65535) return hipErrorInvalidValue;
+    dim3 grid(Tp / 128, Kp / 128, P);
+    if (i8)
+      gemm_tiled_kernel<4, 4, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
+    else
+      gemm_tiled_kernel<4, 4, false><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
+  } else {
+    if (Kp / 64 > 65535) return hipErrorInvalidValue;
+    dim3 grid(Tp / 64, Kp / 64, P);
+    if (i8)
+      gemm_tiled_kernel<2, 2, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
+    else
+      gemm_tiled_kernel<2, 2, false><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
+  }
   return hipGetLastError();
 }
 

@@ -13,6 +13,7 @@
 // The matrices arrive by value in the kernel arguments (scalar registers), never
 // as compiled-in constants, so learned transforms use the same code.
 #include "input_stage.h"
+#include "output_stage.h"
 
 namespace wino {
 namespace {
@@ -166,10 +167,10 @@ __global__ __launch_bounds__(256) void weight_transform_f32(Geom g, MatG mg,
 }
 
 // ------------------------------------------------------------------ output --
-// Stand-alone output transform (used when M is materialised: per-stage calls and
-// the parity tap).  One thread per (tile, output channel); lanes run along k so
-// that the reads of M are contiguous.
-template <int M, bool I8, bool kSparse>
+// Stand-alone output transform, used when M is materialised (layers whose accumulators
+// do not fit the fused kernels, per-stage calls, the parity tap).  One thread per
+// (tile, output channel); lanes run along k so that the reads of M are contiguous.
+template <int M, bool I8, bool kSparse, bool kMQ>
 __global__ __launch_bounds__(256) void output_transform(Geom g, MatAT at,
                                                         const void* __restrict__ Mv,
                                                         void* __restrict__ yv, float r_m,
@@ -187,7 +188,7 @@ __global__ __launch_bounds__(256) void output_transform(Geom g, MatAT at,
     for (int j = 0; j < n; ++j) {
       if (I8) {
         float f = (float)((const int32_t*)Mv)[(i * n + j) * pstride + base];
-        if (r_m > 0.0f) f = (float)quantize(f, r_m, qmax);
+        if constexpr (kMQ) f = (float)quantize(f, r_m, qmax);
         Mt[i][j] = f;
       } else {
         Mt[i][j] = ((const float*)Mv)[(i * n + j) * pstride + base];
@@ -195,19 +196,8 @@ __global__ __launch_bounds__(256) void output_transform(Geom g, MatAT at,
     }
   transform_result<M, kSparse>(Mt, at, Y);
   const int tw = t % g.TW, th = (t / g.TW) % g.TH, img = t / (g.TW * g.TH);
-  const size_t ybase = ((size_t)img * g.K + k) * g.Ho * g.Wo;
-#pragma unroll
-  for (int a = 0; a < M; ++a)
-#pragma unroll
-    for (int b = 0; b < M; ++b) {
-      const int h = th * M + a, w = tw * M + b;
-      if (h < g.Ho && w < g.Wo) {
-        if (I8)
-          ((int8_t*)yv)[ybase + (size_t)h * g.Wo + w] = (int8_t)quantize(Y[a][b], r_y, qmax);
-        else
-          ((float*)yv)[ybase + (size_t)h * g.Wo + w] = Y[a][b];
-      }
-    }
+  store_tile<M, I8>(g, yv, ((size_t)img * g.K + k) * g.Ho * g.Wo, th * M, tw * M, Y, r_y,
+                    kMagic - qmax, kMagic + qmax);
 }
 
 // ------------------------------------------------------------------- taps --
@@ -317,10 +307,18 @@ template <int M, bool I8>
 hipError_t launch_output_m(const Geom& g, const MatAT& at, const void* Mv, void* y, float r_m,
                            float r_y, float qmax, hipStream_t s) {
   const unsigned nb = blocks_for((long long)g.T * g.Kp);
-  if (fits_mask(at.v, g.m * g.n, CookToomMask<M>::at))
-    output_transform<M, I8, true><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
-  else
-    output_transform<M, I8, false><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  if (I8 && r_m > 0.0f) {
+    if (sparse)
+      output_transform<M, I8, true, I8><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+    else
+      output_transform<M, I8, false, I8><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  } else {
+    if (sparse)
+      output_transform<M, I8, true, false><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+    else
+      output_transform<M, I8, false, false><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  }
   return hipGetLastError();
 }
 }  // namespace
