@@ -41,40 +41,59 @@ def pick_workload(name):
     return table[name]
 
 
-def algorithmic(L):
-    """Bytes / operations the method itself must move / do, per kernel launch."""
+ALU_PEAK_TFLOPS = 78.6         # fp32 vector without packed ops: 256 CU x 64 lanes x 2 x 2.4 GHz
+
+
+def algorithmic(L, BT, AT):
+    """Bytes / operations the method itself must move / do, per kernel launch.
+    `ops` are the GEMM's multiply-adds (x2); `alu` are the transforms' fp32 operations:
+    one fused multiply-add (2 flops) per nonzero matrix entry and vector element, one
+    int->float conversion per accumulator, four operations per quantized element
+    (scale, round, saturate, convert)."""
     e = 1 if L.dtype == "i8" else 4
+    qops = 4 if L.dtype == "i8" else 0
     n = L.m + 2
     P = n * n
     TH, TW = -(-L.Ho // L.m), -(-L.Wo // L.m)
     T = L.N * TH * TW
+    nzb, nza = int(np.count_nonzero(BT)), int(np.count_nonzero(AT))
     x_b, y_b = L.N * L.C * L.H * L.W * e, L.N * L.K * L.Ho * L.Wo * e
     v_b, u_b, m_b = P * T * L.C * e, P * L.C * L.K * e, 4 * P * T * L.K
+    mm = 2 * P * T * L.C * L.K
+    alu_in = T * L.C * (2 * 2 * n * nzb + qops * P)
+    alu_out = T * L.K * (2 * (n + L.m) * nza + (P if L.dtype == "i8" else 0) + qops * L.m * L.m)
+    alu_w = L.K * L.C * (2 * (3 * 3 * n + 3 * n * n) + qops * P)
     return {
-        "weight_transform": dict(bytes=9 * L.C * L.K * 4 + u_b, ops=0),
-        "input_transform": dict(bytes=x_b + v_b, ops=0),
-        "gemm": dict(bytes=v_b + u_b + m_b, ops=2 * P * T * L.C * L.K),
-        "output_transform": dict(bytes=m_b + y_b, ops=0),
+        "weight_transform": dict(bytes=9 * L.C * L.K * 4 + u_b, ops=0, alu=alu_w),
+        "input_transform": dict(bytes=x_b + v_b, ops=0, alu=alu_in),
+        "gemm": dict(bytes=v_b + u_b + m_b, ops=mm, alu=0),
+        "output_transform": dict(bytes=m_b + y_b, ops=0, alu=alu_out),
         # GEMM and output transform in one kernel: M is never stored
-        "gemm_output": dict(bytes=v_b + u_b + y_b, ops=2 * P * T * L.C * L.K),
+        "gemm_output": dict(bytes=v_b + u_b + y_b, ops=mm, alu=alu_out),
         # the whole forward in one kernel: neither V nor M is stored
-        "fused_forward": dict(bytes=x_b + u_b + y_b, ops=2 * P * T * L.C * L.K),
+        "fused_forward": dict(bytes=x_b + u_b + y_b, ops=mm, alu=alu_in + alu_out),
     }
 
 
 def roofline_entry(name, alg, us, dtype, traffic):
-    ridge = MFMA_PEAK["int8" if dtype == "i8" else "f32"] * 1e12 / (HBM_PEAK_GBS * 1e9)
-    intensity = alg["ops"] / alg["bytes"] if alg["bytes"] else 0.0
-    if alg["ops"] and intensity >= ridge:
-        peak = MFMA_PEAK["int8" if dtype == "i8" else "f32"]
-        ach = alg["ops"] / (us * 1e-6) / 1e12
-        ent = dict(bound="mfma", achieved=ach, peak=peak,
+    """The bound is whichever of HBM, MFMA and vector-ALU peak needs the longest time
+    for the kernel's algorithmic bytes / GEMM operations / transform operations."""
+    mf = MFMA_PEAK["int8" if dtype == "i8" else "f32"]
+    t = {"hbm": alg["bytes"] / (HBM_PEAK_GBS * 1e9), "mfma": alg["ops"] / (mf * 1e12),
+         "alu": alg["alu"] / (ALU_PEAK_TFLOPS * 1e12)}
+    bound = max(t, key=t.get)
+    sec = us * 1e-6
+    if bound == "hbm":
+        ent = dict(bound="hbm", achieved=alg["bytes"] / sec / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
+    elif bound == "mfma":
+        ent = dict(bound="mfma", achieved=alg["ops"] / sec / 1e12, peak=mf,
                    unit="TOP/s" if dtype == "i8" else "TFLOP/s")
     else:
-        ach = alg["bytes"] / (us * 1e-6) / 1e9
-        ent = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s")
+        ent = dict(bound="alu", achieved=alg["alu"] / sec / 1e12, peak=ALU_PEAK_TFLOPS, unit="TFLOP/s")
     ent.update(kernel=name, frac=ent["achieved"] / ent["peak"], avg_us=us,
-               algorithmic_bytes=alg["bytes"], algorithmic_ops=alg["ops"], traffic=traffic)
+               algorithmic_bytes=alg["bytes"], algorithmic_ops=alg["ops"],
+               algorithmic_alu_ops=alg["alu"], hbm_frac=alg["bytes"] / sec / 1e9 / HBM_PEAK_GBS,
+               traffic=traffic)
     return ent
 
 
@@ -192,7 +211,7 @@ def gpu_leg(L, steps, warmup, use_graph):
                           scales["s_y"], 127, rws, stream=stream)
 
     ms_ref = timed(ref_fwd, max(10, steps // 4), max(2, warmup // 4))
-    return dict(ms_step=ms_step, ms_fwd=ms_fwd, ms_ref=ms_ref, kernel_us=acc)
+    return dict(ms_step=ms_step, ms_fwd=ms_fwd, ms_ref=ms_ref, kernel_us=acc, BT=BT, AT=AT)
 
 
 def cpu_leg(L):
@@ -244,7 +263,7 @@ def main():
     if L.stride != 1:
         raise SystemExit("workload %s is an im2row (stride-2) layer, not a Winograd one" % L.name)
     r = gpu_leg(L, a.steps, a.warmup, not a.no_graph)
-    alg = algorithmic(L)
+    alg = algorithmic(L, r["BT"], r["AT"])
     traffic = {}
     if os.path.exists(HBM_TRAFFIC_FILE):
         traffic = json.load(open(HBM_TRAFFIC_FILE)).get(L.name, {})
