@@ -35,10 +35,10 @@
 // Development aid, compiled only with -DWINO_PROFILE_PHASES: every wavefront records the
 // shader clock at its phase boundaries; wino_debug_read_phases() copies them out.
 #ifdef WINO_PROFILE_PHASES
-__device__ unsigned long long wino_phase_ts[4096 * 8];
+__device__ unsigned long long wino_phase_ts[4096 * 16];
 #define WINO_TS(slot)                                                                     \
   if ((threadIdx.x & 63) == 0 && blockIdx.y == 0 && blockIdx.x < 1024)                      \
-    wino_phase_ts[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (slot)] = __builtin_amdgcn_s_memtime()
+    wino_phase_ts[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + (slot)] = __builtin_amdgcn_s_memtime()
 extern "C" int wino_debug_read_phases(unsigned long long* host, size_t count) {
   return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(wino_phase_ts), count * sizeof(unsigned long long));
 }
@@ -70,23 +70,43 @@ struct KronW { uint32_t v[3 * 64 * 4]; };
 
 struct __attribute__((packed, aligned(4))) U64A4 { uint32_t lo, hi; };   // 8 bytes, dword aligned
 
+// Launch plan computed by the host.  The reciprocals turn the kernel's few integer
+// divisions into one multiply-high each: inv(d) = ceil(2^32 / d) (0 stands for d == 1),
+// exact whenever numerator * d < 2^32, which the host checks for every use.
+struct XPlan {
+  int RB, TWB;               // tile rows and tiles per row of a workgroup (RB * TWB <= 16)
+  uint32_t inv_twb;          // numerators < 16
+  uint32_t inv_strip, inv_wq;   // numerators < 256
+  uint32_t inv_th;           // numerators < N * TH
+};
+
+__host__ __device__ inline uint32_t make_inv(uint32_t d) {
+  return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d);
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t inv) {
+  return inv ? __umulhi(n, inv) : n;
+}
+
 // kLoad: 0 = byte loads (W < 4), 1 = one dword per lane at any byte address,
 // 2 = 8 bytes per lane from a dword-aligned address (W % 4 == 0, W >= 8, x aligned).
-template <int kLoad>
-__device__ __forceinline__ void stage_planes(const Geom& g, const int8_t* __restrict__ x,
-                                             uint32_t* Xs, int c0, int r0, int tw0, int RB,
-                                             int TWB) {
+// kTWB > 0: the workgroup shape (TWB, RB) = (kTWB, 16 / kTWB) is a compile-time constant,
+// which folds the index arithmetic; 0 = taken from the plan at run time.
+template <int kLoad, int kTWB>
+__device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
+                                             const int8_t* __restrict__ x, uint32_t* Xs, int c0,
+                                             int r0, int tw0) {
   // Same lane mapping and branch-free batched loads as stage_strips (input_stage.h);
   // the dwords are stored as they are: Xs[(rs*64 + c)*plane + j*row + lq].
   constexpr int n = kXN, M = kXM;
+  const int RB = kTWB ? 16 / kTWB : pl.RB, TWB = kTWB ? kTWB : pl.TWB;
   const int WQ = xs_row_dw(TWB), plane = xs_plane_dw(TWB);
   const int R = g.N * g.TH;
   const int wbase = tw0 * M - g.pad;
-  const int nthr = blockDim.x, tid = threadIdx.x;
+  const int nthr = 256, tid = threadIdx.x;
   const int strip = WQ * n;
-  const int slots = nthr / strip;
-  const int sidx = tid / strip, rem = tid - sidx * strip;
-  const int j = rem / WQ, lq = rem - j * WQ;
+  const int slots = kTWB ? nthr / strip : (int)fast_div(nthr, pl.inv_strip);
+  const int sidx = kTWB ? tid / strip : (int)fast_div(tid, pl.inv_strip), rem = tid - sidx * strip;
+  const int j = kTWB ? rem / WQ : (int)fast_div(rem, pl.inv_wq), lq = rem - j * WQ;
   const bool lane_on = sidx < slots;
   const int w = wbase + lq * 4;                    // first of the lane's four image columns
   // wl: column the lane really loads from; the wanted bytes are the loaded ones shifted
@@ -106,90 +126,97 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const int8_t* __rest
     rsh = w > wl ? 8 * (w - wl) : 0;
   }
   const int chs = g.H * g.W;
-  const int npass = (16 + slots - 1) / slots;
+  const int npass = (16 + slots - 1) / slots;      // slots is uniform: scalar division
+  const int lane_c = sidx * 4 * chs;               // byte offset of the lane's first channel
+  const int pass_c = slots * 4 * chs;              // ... added per pass (uniform)
   constexpr int kBatch = 8;
-  uint32_t* dump = Xs + RB * 64 * plane;          // 4 dwords nobody reads
+  uint32_t* dump = Xs + RB * 64 * plane;           // 4 dwords nobody reads
   for (int rs = 0; rs < RB; ++rs) {
     const int r = r0 + rs;
     const int rc = r < R ? r : R - 1;
-    const int img = rc / g.TH, th = rc - img * g.TH;
+    const int img = (int)fast_div(rc, pl.inv_th), th = rc - img * g.TH;
     const int h = th * M - g.pad + j;
     const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
     const bool rowok = lane_on && r < R && h == hc && overlap;
-    const int8_t* base = x + ((size_t)img * g.C + c0) * chs + (size_t)hc * g.W + wl;
+    // uniform base of (image, channel block) + the lane's 32-bit offset inside it
+    const int8_t* ibase = x + ((size_t)img * g.C + c0) * chs;
+    const int loff = hc * g.W + wl;
     uint32_t* xrow = Xs + (rs * 64) * plane + j * WQ + lq;
     for (int ps0 = 0; ps0 < npass; ps0 += kBatch) {
       uint64_t q[kBatch][4];
-      int off[kBatch][4];
       uint32_t msk[kBatch][4];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const int cq = (ps0 + u) * slots + sidx;
         const bool ok = rowok && cq < 16;
+        const int coff = lane_c + (ps0 + u) * pass_c;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int cl = cq * 4 + e;
-          const bool cok = ok && c0 + cl < g.C;
+          const bool cok = ok && c0 + cq * 4 + e < g.C;
           msk[u][e] = 0u - (uint32_t)cok;
-          off[u][e] = (cl * chs) & (int)msk[u][e];
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
+          const int off = loff + ((coff + e * chs) & (int)msk[u][e]);
           if constexpr (kLoad == 2) {
-            const U64A4 t = *(const U64A4*)(base + off[u][e]);
+            const U64A4 t = *(const U64A4*)(ibase + off);
             q[u][e] = ((uint64_t)t.hi << 32) | t.lo;
           } else if constexpr (kLoad == 1) {
-            q[u][e] = ((const UnalignedU32*)(base + off[u][e]))->v;
+            q[u][e] = ((const UnalignedU32*)(ibase + off))->v;
           } else {
-            q[u][e] = load_quad_guarded(base + off[u][e], w, g.W);
+            q[u][e] = load_quad_guarded(ibase + off, w, g.W);
           }
         }
+      }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const int cq = (ps0 + u) * slots + sidx;
         const bool live = lane_on && cq < 16;
+        uint32_t* dst = live ? xrow + cq * 4 * plane : dump;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const uint32_t v = (uint32_t)((q[u][e] << lsh) >> rsh) & msk[u][e];
-          uint32_t* dst = live ? xrow + (cq * 4 + e) * plane : dump;
-          *dst = v;
-        }
+        for (int e = 0; e < 4; ++e)
+          dst[live ? e * plane : 0] = (uint32_t)((q[u][e] << lsh) >> rsh) & msk[u][e];
       }
     }
   }
 }
 
-template <bool kSparseA, int kLoad, bool kMQ>
+// Grid: x = blocks of RB tile rows, y = blocks of TWB tiles along a row, z = blocks of 64
+// output channels.
+// kOneBlock: C <= 64, a single channel block; the accumulators then start life at the
+// first per-position MFMA (zero "C" operand) instead of occupying 144 registers during
+// staging and transform.
+template <bool kSparseA, int kLoad, bool kMQ, bool kOneBlock, int kTWB>
 __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
-    Geom g, MatAT at, KronW kw, const int8_t* __restrict__ x, const int8_t* __restrict__ U,
-    void* __restrict__ y, float r_vs, float r_m, float r_y, float qmax, int RB, int TWB) {
+    const int8_t* __restrict__ x, const int8_t* __restrict__ U, void* __restrict__ y, float r_vs,
+    float r_m, float r_y, float qmax, Geom g, XPlan pl, MatAT at, KronW kw) {
+  // (pointers and scalars first: they sit next to the geometry in the argument block,
+  // so one batch of scalar loads at kernel start brings in everything staging needs)
   constexpr int n = kXN, P = kXP, M = kXM;
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   uint32_t* Xs = lds;
   uint32_t* Vl = lds;                                  // aliases Xs
+  const int RB = kTWB ? 16 / kTWB : pl.RB, TWB = kTWB ? kTWB : pl.TWB;
   const int WQ = xs_row_dw(TWB), plane = xs_plane_dw(TWB);
-  const int ntwb = (g.TW + TWB - 1) / TWB;
-  const int twb = blockIdx.x % ntwb, rb = blockIdx.x / ntwb;
-  const int r0 = rb * RB, tw0 = twb * TWB, kb = blockIdx.y * 64;
+  const int r0 = blockIdx.x * RB, tw0 = blockIdx.y * TWB, kb = blockIdx.z * 64;
   const int R = g.N * g.TH;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps tile math scalar
   const float lo = kMagic - qmax, hi = kMagic + qmax;
 
   WINO_TS(0);
-  const int8_t* urow = U + ((size_t)(kb + wave * 16 + r) * g.Cp) + grp * 16;
-  const size_t up = (size_t)g.Kp * g.Cp;
+  // U rows of this wave: output channels kb + wave*16 + r, 16 bytes at channel grp*16;
+  // 32-bit offsets from the (uniform) base pointer
+  const uint32_t uoff = (uint32_t)(kb + wave * 16 + r) * (uint32_t)g.Cp + (uint32_t)grp * 16u;
+  const uint32_t up = (uint32_t)g.Kp * (uint32_t)g.Cp;
   v4i acc[P];
+  if constexpr (!kOneBlock) {
 #pragma unroll
-  for (int p = 0; p < P; ++p) acc[p] = v4i{0, 0, 0, 0};
+    for (int p = 0; p < P; ++p) acc[p] = v4i{0, 0, 0, 0};
+  }
 
-  const int nblk = g.Cp >> 6;
+  const int nblk = kOneBlock ? 1 : (g.Cp >> 6);
   for (int cb = 0; cb < nblk; ++cb) {
     if (cb) __syncthreads();                           // previous block's Vl fully consumed
     WINO_TS(1);
-    stage_planes<kLoad>(g, x, Xs, cb * 64, r0, tw0, RB, TWB);
+    stage_planes<kLoad, kTWB>(g, pl, x, Xs, cb * 64, r0, tw0);
     // the lane's slice of W, as MFMA operand registers (three 16-position blocks)
     v4i Wb[3];
 #pragma unroll
@@ -203,27 +230,34 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     v4i Aw[16];
     {
       const int j0 = 2 * grp < n ? 2 * grp : 0, j1 = 2 * grp + 1 < n ? 2 * grp + 1 : 0;
+      const uint32_t* lane_x = Xs + r * plane + j0 * WQ;       // per lane; the rest is uniform
+      const int dj = (j1 - j0) * WQ;
 #pragma unroll
-      for (int gi = 0; gi < 16; ++gi) {
-        const int tl = wave * 4 + (gi >> 2), c = (gi & 3) * 16 + r;
-        int rs = tl / TWB;
+      for (int t4 = 0; t4 < 4; ++t4) {
+        const int tl = wave * 4 + t4;
+        int rs = kTWB ? tl / kTWB : (int)fast_div(tl, pl.inv_twb);
         const int twl = tl - rs * TWB;
         rs = rs < RB ? rs : 0;                         // tiles beyond RB*TWB: results unused
-        const uint32_t* p0 = Xs + (rs * 64 + c) * plane + twl;
-        Aw[gi] = v4i{(int)p0[j0 * WQ], (int)p0[j0 * WQ + 1], (int)p0[j1 * WQ], (int)p0[j1 * WQ + 1]};
+        const uint32_t* p0 = lane_x + rs * 64 * plane + twl;
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg) {
+          const uint32_t* p1 = p0 + cg * 16 * plane;
+          Aw[t4 * 4 + cg] = v4i{(int)p1[0], (int)p1[1], (int)p1[dj], (int)p1[dj + 1]};
+        }
       }
     }
     // first operands of the per-position GEMMs, so that they arrive during the transform
-    constexpr int kDepth = 9;
-    const int8_t* ub = urow + (size_t)cb * 64;
+    constexpr int kDepth = 12;
+    const uint32_t ub = uoff + (uint32_t)cb * 64u;
     v4i bufU[kDepth];
 #pragma unroll
-    for (int p = 0; p < kDepth; ++p) bufU[p] = *(const v4i*)(ub + p * up);
+    for (int p = 0; p < kDepth; ++p) bufU[p] = *(const v4i*)(U + (ub + (uint32_t)p * up));
     __syncthreads();                                   // Xs is free: Vl may overwrite it
     WINO_TS(3);
 
     // D[channel][position]: a lane gets positions p = blk*16 + r of channels
     // (gi%4)*16 + 4 grp .. + 3, i.e. one dword of Vl per MFMA.
+    uint32_t* lane_v = Vl + r * kVlPitch + grp;
 #pragma unroll
     for (int gi = 0; gi < 16; ++gi) {
       const int tl = wave * 4 + (gi >> 2);
@@ -235,27 +269,31 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr)
           packed = __builtin_amdgcn_perm(quantize_bits((float)v[rr], r_vs, lo, hi), packed, 0x04030201u);
-        const int p = blk * 16 + r;
-        if (p < P) Vl[p * kVlPitch + tl * 16 + (gi & 3) * 4 + grp] = packed;
+        if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
       }
     }
     __syncthreads();
     WINO_TS(4);
 
+    const uint32_t* lane_b = Vl + r * 16 + grp * 4;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
       const v4i au = bufU[p % kDepth];
-      if (p + kDepth < P) bufU[p % kDepth] = *(const v4i*)(ub + (p + kDepth) * up);
-      const v4i bv = *(const v4i*)(Vl + p * kVlPitch + r * 16 + grp * 4);
-      acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, acc[p], 0, 0, 0);
+      if (p + kDepth < P)
+        bufU[p % kDepth] = *(const v4i*)(U + (ub + (uint32_t)(p + kDepth) * up));
+      const v4i bv = *(const v4i*)(lane_b + p * kVlPitch);
+      if constexpr (kOneBlock)
+        acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, v4i{0, 0, 0, 0}, 0, 0, 0);
+      else
+        acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, acc[p], 0, 0, 0);
     }
   }
 
   WINO_TS(5);
-  const int rs = r / TWB, twl = r - rs * TWB;
+  const int rs = kTWB ? r / kTWB : (int)fast_div(r, pl.inv_twb), twl = r - rs * TWB;
   const int rr_ = r0 + rs, tw = tw0 + twl;
   if (rs < RB && rr_ < R && tw < g.TW) {
-    const int img = rr_ / g.TH, th = rr_ - img * g.TH;
+    const int img = (int)fast_div(rr_, pl.inv_th), th = rr_ - img * g.TH;
     finish_lane<M, true, kSparseA, kMQ>(g, at, acc, y, img, th, tw, kb + wave * 16 + grp * 4, r_m,
                                         r_y, qmax);
   }
@@ -294,14 +332,17 @@ int exact_input_shift(const Geom& g, const MatBT& bt) {
 }
 
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
-  return g.Kp <= 128 && exact_input_shift(g, bt) >= 0;
+  // the reciprocal of TH must be exact for every tile row index (see XPlan)
+  const unsigned long long R = (unsigned long long)g.N * g.TH;
+  return g.Kp <= 128 && R * (unsigned long long)g.TH < 0x100000000ull &&
+         exact_input_shift(g, bt) >= 0;
 }
 
 hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                                   const void* U, void* y, float r_v, float r_m, float r_y,
                                   float qmax, hipStream_t s) {
   const int sft = exact_input_shift(g, bt);
-  if (sft < 0 || g.Kp > 128) return hipErrorInvalidValue;
+  if (sft < 0 || !fused_fwd_exact_supported(g, bt)) return hipErrorInvalidValue;
   const float bt_scale = (float)(1 << sft);
   const float r_vs = r_v / (float)(1 << (2 * sft));      // exact power-of-two scaling
   if (!(r_vs * (float)(1 << (2 * sft)) == r_v)) return hipErrorInvalidValue;   // underflow
@@ -330,26 +371,44 @@ hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& a
   const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(TWB) + 4) * 4, vl_b = (size_t)kXP * kVlPitch * 4;
   const size_t lb = xs_b > vl_b ? xs_b : vl_b;
   const int ntwb = (g.TW + TWB - 1) / TWB, nrb = (R + RB - 1) / RB;
-  if (lb > 65536 || (long long)ntwb * nrb > 0x7fffffffLL || kXN * xs_row_dw(TWB) > 256)
-    return hipErrorInvalidValue;
-  dim3 grid((unsigned)(ntwb * nrb), (unsigned)(g.Kp / 64));
+  const int strip = kXN * xs_row_dw(TWB);
+  if (lb > 65536 || ntwb > 65535 || g.Kp / 64 > 65535 || strip > 256) return hipErrorInvalidValue;
+  dim3 grid((unsigned)nrb, (unsigned)ntwb, (unsigned)(g.Kp / 64));
+  XPlan pl;
+  pl.RB = RB;
+  pl.TWB = TWB;
+  pl.inv_twb = make_inv(TWB);
+  pl.inv_strip = make_inv(strip);
+  pl.inv_wq = make_inv(xs_row_dw(TWB));
+  pl.inv_th = make_inv(g.TH);
   const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<kXM>::at);
   const int8_t* xi = (const int8_t*)x;
   const int8_t* Ui = (const int8_t*)U;
   const int load = g.W < 4 ? 0 : (g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0) ? 2 : 1;
   const bool mq = r_m > 0.0f;
-#define WINO_LAUNCH_X(SA, LOAD, MQ)                                                        \
-  fused_fwd_exact_kernel<SA, LOAD, MQ><<<grid, 256, lb, s>>>(g, at, kw, xi, Ui, y, r_vs, r_m, \
-                                                             r_y, qmax, RB, TWB)
+  const bool one = g.Cp == 64;
+  // compile-time workgroup shapes for the common image widths (32, 16 pixels)
+  const int shape = (TWB == 8 && RB == 2) ? 8 : (TWB == 4 && RB == 4) ? 4 : 0;
+#define WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, TWBC)                                            \
+  fused_fwd_exact_kernel<SA, LOAD, MQ, ONE, TWBC><<<grid, 256, lb, s>>>(                     \
+      xi, Ui, y, r_vs, r_m, r_y, qmax, g, pl, at, kw)
+#define WINO_LAUNCH_X(SA, LOAD, MQ, ONE)                                                   \
+  do { if (shape == 8) WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, 8);                               \
+       else if (shape == 4) WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, 4);                          \
+       else WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, 0); } while (0)
+#define WINO_LAUNCH_X1(SA, LOAD, MQ) \
+  do { if (one) WINO_LAUNCH_X(SA, LOAD, MQ, true); else WINO_LAUNCH_X(SA, LOAD, MQ, false); } while (0)
 #define WINO_LAUNCH_X2(SA, LOAD) \
-  do { if (mq) WINO_LAUNCH_X(SA, LOAD, true); else WINO_LAUNCH_X(SA, LOAD, false); } while (0)
+  do { if (mq) WINO_LAUNCH_X1(SA, LOAD, true); else WINO_LAUNCH_X1(SA, LOAD, false); } while (0)
 #define WINO_LAUNCH_X3(SA)                                                                 \
   do { if (load == 2) WINO_LAUNCH_X2(SA, 2); else if (load == 1) WINO_LAUNCH_X2(SA, 1);    \
        else WINO_LAUNCH_X2(SA, 0); } while (0)
   if (sa) WINO_LAUNCH_X3(true); else WINO_LAUNCH_X3(false);
 #undef WINO_LAUNCH_X3
 #undef WINO_LAUNCH_X2
+#undef WINO_LAUNCH_X1
 #undef WINO_LAUNCH_X
+#undef WINO_LAUNCH_X0
   return hipGetLastError();
 }
 
