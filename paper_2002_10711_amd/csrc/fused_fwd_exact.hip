@@ -257,20 +257,25 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 
     // D[channel][position]: a lane gets positions p = blk*16 + r of channels
     // (gi%4)*16 + 4 grp .. + 3, i.e. one dword of Vl per MFMA.
+    // Software pipeline over the 48 (group, block) steps: the MFMA of step s + 1 is issued
+    // before the results of step s are quantized, so the matrix pipe works while the
+    // vector ALU rounds and packs.
     uint32_t* lane_v = Vl + r * kVlPitch + grp;
+    v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], v4i{0, 0, 0, 0}, 0, 0, 0);
 #pragma unroll
-    for (int gi = 0; gi < 16; ++gi) {
+    for (int st = 0; st < 48; ++st) {
+      const int gi = st / 3, blk = st % 3;
+      v4i nxt = cur;
+      if (st + 1 < 48)      // every lane takes part in the MFMA; only the stores are predicated
+        nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / 3], Wb[(st + 1) % 3],
+                                                    v4i{0, 0, 0, 0}, 0, 0, 0);
+      uint32_t packed = 0u;
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr)
+        packed = __builtin_amdgcn_perm(quantize_bits((float)cur[rr], r_vs, lo, hi), packed, 0x04030201u);
       const int tl = wave * 4 + (gi >> 2);
-#pragma unroll
-      for (int blk = 0; blk < 3; ++blk) {
-        // every lane takes part in the MFMA; only the stores are predicated
-        const v4i v = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[gi], Wb[blk], v4i{0, 0, 0, 0}, 0, 0, 0);
-        uint32_t packed = 0u;
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr)
-          packed = __builtin_amdgcn_perm(quantize_bits((float)v[rr], r_vs, lo, hi), packed, 0x04030201u);
-        if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
-      }
+      if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
+      cur = nxt;
     }
     __syncthreads();
     WINO_TS(4);
