@@ -255,6 +255,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host "
                     "instead of replaying a captured HIP graph of one step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true", help="also run a plain 256 MiB device "
+                    "copy a few times: the reference kernel against which rocprofv3's "
+                    "FETCH_SIZE / WRITE_SIZE counters are scaled")
     a = ap.parse_args()
     if a.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (the path needs no exchange "
@@ -262,6 +265,14 @@ def main():
     L = pick_workload(a.workload)
     if L.stride != 1:
         raise SystemExit("workload %s is an im2row (stride-2) layer, not a Winograd one" % L.name)
+    if a.copy_probe:
+        import torch
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     r = gpu_leg(L, a.steps, a.warmup, not a.no_graph)
     alg = algorithmic(L, r["BT"], r["AT"])
     traffic = {}
