@@ -54,6 +54,11 @@ SMALL = [
     Layer("s_f4_pad0", 2, 16, 16, 10, 12, m=4, pad=0, seed=105),
     Layer("s_f2_1x1out", 1, 3, 2, 3, 3, m=2, pad=0, seed=106),
     Layer("s_f4_wide", 1, 130, 70, 6, 40, m=4, seed=107),
+    Layer("s_f4_16px", 3, 64, 64, 16, 16, m=4, seed=112),       # 4 x 4 tiles per workgroup row block
+    Layer("s_f4_narrow", 2, 8, 8, 5, 3, m=4, seed=113),         # image narrower than a dword
+    Layer("s_f4_c128k128", 2, 128, 128, 8, 8, m=4, seed=114),   # two channel blocks, two k blocks
+    Layer("s_f2_32px", 2, 64, 32, 32, 32, m=2, seed=115),
+    Layer("s_f6_32px", 1, 64, 64, 32, 32, m=6, seed=116),
 ]
 
 
