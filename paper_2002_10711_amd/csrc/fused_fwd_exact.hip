@@ -183,7 +183,8 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
 // kOneBlock: C <= 64, a single channel block; the accumulators then start life at the
 // first per-position MFMA (zero "C" operand) instead of occupying 144 registers during
 // staging and transform.
-template <bool kSparseA, int kLoad, bool kMQ, bool kOneBlock, int kTWB>
+// kFast: whole tiles, K % 4 == 0 (see output_stage.h).
+template <bool kSparseA, int kLoad, bool kMQ, bool kOneBlock, int kTWB, bool kFast>
 __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     const int8_t* __restrict__ x, const int8_t* __restrict__ U, void* __restrict__ y, float r_vs,
     float r_m, float r_y, float qmax, Geom g, XPlan pl, MatAT at, KronW kw) {
@@ -246,12 +247,13 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
         }
       }
     }
-    // first operands of the per-position GEMMs, so that they arrive during the transform
-    constexpr int kDepth = 12;
+    // All 36 "A" operands of the per-position GEMMs are fetched during the transform
+    // below, one load per pipeline step: that phase is bound by the vector ALU and leaves
+    // the memory pipe idle, while the loads (36 KB per wavefront through the L1) would
+    // otherwise stall the MFMA loop.
+    constexpr int kDepth = P;
     const uint32_t ub = uoff + (uint32_t)cb * 64u;
     v4i bufU[kDepth];
-#pragma unroll
-    for (int p = 0; p < kDepth; ++p) bufU[p] = *(const v4i*)(U + (ub + (uint32_t)p * up));
     __syncthreads();                                   // Xs is free: Vl may overwrite it
     WINO_TS(3);
 
@@ -265,6 +267,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 #pragma unroll
     for (int st = 0; st < 48; ++st) {
       const int gi = st / 3, blk = st % 3;
+      if (st < kDepth) bufU[st] = *(const v4i*)(U + (ub + (uint32_t)st * up));
       v4i nxt = cur;
       if (st + 1 < 48)      // every lane takes part in the MFMA; only the stores are predicated
         nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / 3], Wb[(st + 1) % 3],
@@ -283,9 +286,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     const uint32_t* lane_b = Vl + r * 16 + grp * 4;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-      const v4i au = bufU[p % kDepth];
-      if (p + kDepth < P)
-        bufU[p % kDepth] = *(const v4i*)(U + (ub + (uint32_t)(p + kDepth) * up));
+      const v4i au = bufU[p];
       const v4i bv = *(const v4i*)(lane_b + p * kVlPitch);
       if constexpr (kOneBlock)
         acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, v4i{0, 0, 0, 0}, 0, 0, 0);
@@ -299,8 +300,8 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
   const int rr_ = r0 + rs, tw = tw0 + twl;
   if (rs < RB && rr_ < R && tw < g.TW) {
     const int img = (int)fast_div(rr_, pl.inv_th), th = rr_ - img * g.TH;
-    finish_lane<M, true, kSparseA, kMQ>(g, at, acc, y, img, th, tw, kb + wave * 16 + grp * 4, r_m,
-                                        r_y, qmax);
+    finish_lane<M, true, kSparseA, kMQ, kFast>(g, at, acc, y, img, th, tw,
+                                               kb + wave * 16 + grp * 4, r_m, r_y, qmax);
   }
   WINO_TS(6);
 }
@@ -394,9 +395,15 @@ hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& a
   const bool one = g.Cp == 64;
   // compile-time workgroup shapes for the common image widths (32, 16 pixels)
   const int shape = (TWB == 8 && RB == 2) ? 8 : (TWB == 4 && RB == 4) ? 4 : 0;
-#define WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, TWBC)                                            \
-  fused_fwd_exact_kernel<SA, LOAD, MQ, ONE, TWBC><<<grid, 256, lb, s>>>(                     \
+  // the common case gets the branch-free output side: whole tiles, K % 4 == 0, default
+  // A^T pattern, no quantizer on M, aligned 8-byte staging loads
+  const bool fast = g.Ho % kXM == 0 && g.Wo % kXM == 0 && g.K % 4 == 0;
+#define WINO_LAUNCH_XF(SA, LOAD, MQ, ONE, TWBC, FAST)                                      \
+  fused_fwd_exact_kernel<SA, LOAD, MQ, ONE, TWBC, FAST><<<grid, 256, lb, s>>>(               \
       xi, Ui, y, r_vs, r_m, r_y, qmax, g, pl, at, kw)
+#define WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, TWBC)                                            \
+  do { if (fast && SA && LOAD == 2 && !MQ) WINO_LAUNCH_XF(SA, LOAD, MQ, ONE, TWBC, true);  \
+       else WINO_LAUNCH_XF(SA, LOAD, MQ, ONE, TWBC, false); } while (0)
 #define WINO_LAUNCH_X(SA, LOAD, MQ, ONE)                                                   \
   do { if (shape == 8) WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, 8);                               \
        else if (shape == 4) WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, 4);                          \
@@ -414,6 +421,7 @@ hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& a
 #undef WINO_LAUNCH_X1
 #undef WINO_LAUNCH_X
 #undef WINO_LAUNCH_X0
+#undef WINO_LAUNCH_XF
   return hipGetLastError();
 }
 

@@ -16,7 +16,9 @@ template <bool I8> struct Acc { typedef v4i type; };
 template <> struct Acc<false> { typedef v4f type; };
 
 // Stores one m x m output tile of channel k; (h0, w0) is its top-left corner.
-template <int M, bool I8>
+// kFast: the host has checked that m divides Ho and Wo (every tile is whole and every
+// row keeps the alignment of the vector stores), so no per-lane decisions are left.
+template <int M, bool I8, bool kFast = false>
 __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv, size_t plane,
                                            int h0, int w0, const float (&Y)[M][M], float r_y,
                                            float lo, float hi) {
@@ -27,14 +29,14 @@ __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv,
     for (int a = 0; a < M; ++a)
 #pragma unroll
       for (int b = 0; b < M; ++b) q[a][b] = quantize_bits(Y[a][b], r_y, lo, hi);
-    const bool full = h0 + M <= g.Ho && w0 + M <= g.Wo;
-    if (full && (g.Wo & 1) == 0) {
+    const bool full = kFast || (h0 + M <= g.Ho && w0 + M <= g.Wo);
+    if (kFast || (full && (g.Wo & 1) == 0)) {
       // rows start at even addresses (w0 = tw*m is even): 2-byte stores, or one
       // dword per row when m == 4 and the row pitch keeps it aligned
 #pragma unroll
       for (int a = 0; a < M; ++a) {
         int8_t* row = y + (size_t)(h0 + a) * g.Wo + w0;
-        if (M == 4 && (g.Wo & 3) == 0) {
+        if (M == 4 && (kFast || (g.Wo & 3) == 0)) {
           uint32_t lo16 = __builtin_amdgcn_perm(q[a][1], q[a][0], 0x0c0c0400u);
           uint32_t hi16 = __builtin_amdgcn_perm(q[a][3], q[a][2], 0x04000c0cu);
           *(uint32_t*)row = lo16 | hi16;
@@ -68,7 +70,8 @@ __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv,
 // consecutive output channels k0..k0+3 (vector components) of every position:
 // transform each of the four n x n matrices and store its tile.
 // kMQ: the optional quantizer after the Hadamard stage is on (r_m > 0).
-template <int M, bool I8, bool kSparse, bool kMQ>
+// kFast: whole tiles only (see store_tile) and K a multiple of 4 (no channel guard).
+template <int M, bool I8, bool kSparse, bool kMQ, bool kFast = false>
 __device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
                                             const typename Acc<I8>::type (&acc)[(M + 2) * (M + 2)],
                                             void* __restrict__ yv, int img, int th, int tw, int k0,
@@ -78,7 +81,7 @@ __device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
 #pragma unroll
   for (int rr = 0; rr < 4; ++rr) {
     const int k = k0 + rr;
-    if (k >= g.K) continue;
+    if (!kFast && k >= g.K) continue;
     float Mt[n][n], Y[M][M];
 #pragma unroll
     for (int i = 0; i < n; ++i)
@@ -93,7 +96,8 @@ __device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
         }
       }
     transform_result<M, kSparse>(Mt, at, Y);
-    store_tile<M, I8>(g, yv, ((size_t)img * g.K + k) * g.Ho * g.Wo, th * M, tw * M, Y, r_y, lo, hi);
+    store_tile<M, I8, kFast>(g, yv, ((size_t)img * g.K + k) * g.Ho * g.Wo, th * M, tw * M, Y, r_y,
+                             lo, hi);
   }
 }
 
