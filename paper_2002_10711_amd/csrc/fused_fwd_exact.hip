@@ -1,5 +1,5 @@
-// Single-kernel int8 forward for F(4x4,3x3) when the input transform is EXACT, with
-// the input transform itself on the matrix cores.
+// Single-kernel int8 forward for F(2x2,3x3) and F(4x4,3x3) when the input transform is
+// EXACT, with the input transform itself on the matrix cores.
 //
 // If 2^s B^T is an integer matrix (s <= 3; true for Cook-Toom points 0, +-1, +-1/2:
 // 4 B^T has entries 0, +-1, +-2, +-4, +-5) and the input holds int8 codes, then every
@@ -29,6 +29,8 @@
 //      windows as the "A" operand so that a lane receives four consecutive channels
 //      of one position: quantize, pack into a dword, store into Vl[p][tile][channel];
 //   4. barrier; wave w: one MFMA per position against U[p][16 k of w][64 c].
+#include <string.h>
+
 #include "input_stage.h"
 #include "output_stage.h"
 
@@ -49,13 +51,17 @@ extern "C" int wino_debug_read_phases(unsigned long long* host, size_t count) {
 namespace wino {
 namespace {
 
-constexpr int kXM = 4, kXN = 6, kXP = 36;   // this file is F(4x4,3x3) only
+// F(2x2,3x3) and F(4x4,3x3): the n x n patch fits the 8 x 8 window and the products of
+// the usual matrices fit int8; F(6x6,3x3) does not (4 B^T reaches 21, products 441).
 
-// LDS geometry of the staged input: a row is TWB + 1 dwords (image columns
-// tw0*4 - pad .. + 4 TWB + 3), a channel plane is n rows plus one dword so that the 16
-// channels of a window group fall into 16 different banks.
-__host__ __device__ inline int xs_row_dw(int TWB) { return TWB + 1; }
-__host__ __device__ inline int xs_plane_dw(int TWB) { return (kXN * xs_row_dw(TWB)) | 1; }
+// LDS geometry of the staged input: a row holds the image columns from tw0*m - pad on,
+// up to the second dword of the last tile's window (which starts at byte (TWB-1)*m); a
+// channel plane is n rows, made odd so that the 16 channels of a window group fall into
+// 16 different banks.
+__host__ __device__ inline int xs_row_dw(int M, int TWB) { return (((TWB - 1) * M) >> 2) + 2; }
+__host__ __device__ inline int xs_plane_dw(int M, int TWB) {
+  return ((M + 2) * xs_row_dw(M, TWB)) | 1;
+}
 
 // Vl: quantized transformed input, [position][tile][64 channels]; the position pitch is
 // padded by 4 dwords so that the 16 positions a wavefront stores at once fall into
@@ -91,15 +97,15 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t inv) {
 // 2 = 8 bytes per lane from a dword-aligned address (W % 4 == 0, W >= 8, x aligned).
 // kTWB > 0: the workgroup shape (TWB, RB) = (kTWB, 16 / kTWB) is a compile-time constant,
 // which folds the index arithmetic; 0 = taken from the plan at run time.
-template <int kLoad, int kTWB>
+template <int M, int kLoad, int kTWB>
 __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
                                              const int8_t* __restrict__ x, uint32_t* Xs, int c0,
                                              int r0, int tw0) {
   // Same lane mapping and branch-free batched loads as stage_strips (input_stage.h);
   // the dwords are stored as they are: Xs[(rs*64 + c)*plane + j*row + lq].
-  constexpr int n = kXN, M = kXM;
-  const int RB = kTWB ? 16 / kTWB : pl.RB, TWB = kTWB ? kTWB : pl.TWB;
-  const int WQ = xs_row_dw(TWB), plane = xs_plane_dw(TWB);
+  constexpr int n = M + 2;
+  const int RB = kTWB ? 16 / (kTWB ? kTWB : 1) : pl.RB, TWB = kTWB ? kTWB : pl.TWB;
+  const int WQ = xs_row_dw(M, TWB), plane = xs_plane_dw(M, TWB);
   const int R = g.N * g.TH;
   const int wbase = tw0 * M - g.pad;
   const int nthr = 256, tid = threadIdx.x;
@@ -184,18 +190,20 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
 // first per-position MFMA (zero "C" operand) instead of occupying 144 registers during
 // staging and transform.
 // kFast: whole tiles, K % 4 == 0 (see output_stage.h).
-template <bool kSparseA, int kLoad, bool kMQ, bool kOneBlock, int kTWB, bool kFast>
+template <int M, bool kSparseA, int kLoad, bool kMQ, bool kOneBlock, int kTWB, bool kFast>
 __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     const int8_t* __restrict__ x, const int8_t* __restrict__ U, void* __restrict__ y, float r_vs,
     float r_m, float r_y, float qmax, Geom g, XPlan pl, MatAT at, KronW kw) {
   // (pointers and scalars first: they sit next to the geometry in the argument block,
   // so one batch of scalar loads at kernel start brings in everything staging needs)
-  constexpr int n = kXN, P = kXP, M = kXM;
+  constexpr int n = M + 2, P = n * n;
+  constexpr int NBLK = (P + 15) / 16;                  // 16-position blocks of the transform
+  constexpr int NSTEP = 16 * NBLK;                     // (window group, block) steps per wave
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   uint32_t* Xs = lds;
   uint32_t* Vl = lds;                                  // aliases Xs
-  const int RB = kTWB ? 16 / kTWB : pl.RB, TWB = kTWB ? kTWB : pl.TWB;
-  const int WQ = xs_row_dw(TWB), plane = xs_plane_dw(TWB);
+  const int RB = kTWB ? 16 / (kTWB ? kTWB : 1) : pl.RB, TWB = kTWB ? kTWB : pl.TWB;
+  const int WQ = xs_row_dw(M, TWB), plane = xs_plane_dw(M, TWB);
   const int r0 = blockIdx.x * RB, tw0 = blockIdx.y * TWB, kb = blockIdx.z * 64;
   const int R = g.N * g.TH;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
@@ -217,17 +225,19 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
   for (int cb = 0; cb < nblk; ++cb) {
     if (cb) __syncthreads();                           // previous block's Vl fully consumed
     WINO_TS(1);
-    stage_planes<kLoad, kTWB>(g, pl, x, Xs, cb * 64, r0, tw0);
-    // the lane's slice of W, as MFMA operand registers (three 16-position blocks)
-    v4i Wb[3];
+    stage_planes<M, kLoad, kTWB>(g, pl, x, Xs, cb * 64, r0, tw0);
+    // the lane's slice of W, as MFMA operand registers (one per 16-position block)
+    v4i Wb[NBLK];
 #pragma unroll
-    for (int blk = 0; blk < 3; ++blk) Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
+    for (int blk = 0; blk < NBLK; ++blk) Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
     __syncthreads();
     WINO_TS(2);
 
     // Window group gi of this wave: tile tl = wave*4 + gi/4, channels (gi%4)*16 .. +15.
     // "A" operand row = channel (gi%4)*16 + r: rows 2 grp and 2 grp + 1 of its window,
-    // 8 bytes each (rows 6 and 7 meet zero entries of W: any staged row will do).
+    // 8 bytes each (rows and columns beyond the n x n patch meet zero entries of W: any
+    // staged bytes will do).  The window starts at byte twl*m of the staged row: dword
+    // aligned for m = 4, possibly in mid-dword for m = 2 (funnel shift).
     v4i Aw[16];
     {
       const int j0 = 2 * grp < n ? 2 * grp : 0, j1 = 2 * grp + 1 < n ? 2 * grp + 1 : 0;
@@ -236,18 +246,25 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 #pragma unroll
       for (int t4 = 0; t4 < 4; ++t4) {
         const int tl = wave * 4 + t4;
-        int rs = kTWB ? tl / kTWB : (int)fast_div(tl, pl.inv_twb);
+        int rs = kTWB ? tl / (kTWB ? kTWB : 1) : (int)fast_div(tl, pl.inv_twb);
         const int twl = tl - rs * TWB;
         rs = rs < RB ? rs : 0;                         // tiles beyond RB*TWB: results unused
-        const uint32_t* p0 = lane_x + rs * 64 * plane + twl;
+        const uint32_t* p0 = lane_x + rs * 64 * plane + ((twl * M) >> 2);
+        const int sh = (twl * M) & 3;                  // uniform
 #pragma unroll
         for (int cg = 0; cg < 4; ++cg) {
           const uint32_t* p1 = p0 + cg * 16 * plane;
-          Aw[t4 * 4 + cg] = v4i{(int)p1[0], (int)p1[1], (int)p1[dj], (int)p1[dj + 1]};
+          if constexpr (M == 4) {
+            Aw[t4 * 4 + cg] = v4i{(int)p1[0], (int)p1[1], (int)p1[dj], (int)p1[dj + 1]};
+          } else {
+            const uint32_t a0 = __builtin_amdgcn_alignbyte(p1[1], p1[0], sh);
+            const uint32_t a1 = __builtin_amdgcn_alignbyte(p1[dj + 1], p1[dj], sh);
+            Aw[t4 * 4 + cg] = v4i{(int)a0, (int)p1[1], (int)a1, (int)p1[dj + 1]};
+          }
         }
       }
     }
-    // All 36 "A" operands of the per-position GEMMs are fetched during the transform
+    // All P "A" operands of the per-position GEMMs are fetched during the transform
     // below, one load per pipeline step: that phase is bound by the vector ALU and leaves
     // the memory pipe idle, while the loads (36 KB per wavefront through the L1) would
     // otherwise stall the MFMA loop.
@@ -259,18 +276,19 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 
     // D[channel][position]: a lane gets positions p = blk*16 + r of channels
     // (gi%4)*16 + 4 grp .. + 3, i.e. one dword of Vl per MFMA.
-    // Software pipeline over the 48 (group, block) steps: the MFMA of step s + 1 is issued
+    // Software pipeline over the (group, block) steps: the MFMA of step s + 1 is issued
     // before the results of step s are quantized, so the matrix pipe works while the
     // vector ALU rounds and packs.
     uint32_t* lane_v = Vl + r * kVlPitch + grp;
     v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], v4i{0, 0, 0, 0}, 0, 0, 0);
+    static_assert(NSTEP >= P, "one U load per step must cover all positions");
 #pragma unroll
-    for (int st = 0; st < 48; ++st) {
-      const int gi = st / 3, blk = st % 3;
+    for (int st = 0; st < NSTEP; ++st) {
+      const int gi = st / NBLK, blk = st % NBLK;
       if (st < kDepth) bufU[st] = *(const v4i*)(U + (ub + (uint32_t)st * up));
       v4i nxt = cur;
-      if (st + 1 < 48)      // every lane takes part in the MFMA; only the stores are predicated
-        nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / 3], Wb[(st + 1) % 3],
+      if (st + 1 < NSTEP)   // every lane takes part in the MFMA; only the stores are predicated
+        nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
                                                     v4i{0, 0, 0, 0}, 0, 0, 0);
       uint32_t packed = 0u;
 #pragma unroll
@@ -296,12 +314,13 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
   }
 
   WINO_TS(5);
-  const int rs = kTWB ? r / kTWB : (int)fast_div(r, pl.inv_twb), twl = r - rs * TWB;
-  const int rr_ = r0 + rs, tw = tw0 + twl;
-  if (rs < RB && rr_ < R && tw < g.TW) {
+  const int rs = kTWB ? r / (kTWB ? kTWB : 1) : (int)fast_div(r, pl.inv_twb), twl = r - rs * TWB;
+  const int rr_ = r0 + rs, tw = tw0 + twl, k0 = kb + wave * 16 + grp * 4;
+  // k0 < K: the channel block is padded to 64, so whole lanes may lie beyond K (the
+  // per-channel guard inside finish_lane is compiled out when kFast)
+  if (rs < RB && rr_ < R && tw < g.TW && k0 < g.K) {
     const int img = (int)fast_div(rr_, pl.inv_th), th = rr_ - img * g.TH;
-    finish_lane<M, true, kSparseA, kMQ, kFast>(g, at, acc, y, img, th, tw,
-                                               kb + wave * 16 + grp * 4, r_m, r_y, qmax);
+    finish_lane<M, true, kSparseA, kMQ, kFast>(g, at, acc, y, img, th, tw, k0, r_m, r_y, qmax);
   }
   WINO_TS(6);
 }
@@ -312,7 +331,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 // every intermediate of the fp32 evaluation exactly representable (so that integer and
 // float evaluation agree bit for bit); -1 if there is none.
 int exact_input_shift(const Geom& g, const MatBT& bt) {
-  if (!g.i8 || g.m != kXM) return -1;
+  if (!g.i8 || (g.m != 2 && g.m != 4)) return -1;
   for (int s = 0; s <= 3; ++s) {
     const float sc = (float)(1 << s);
     bool ok = true;
@@ -344,9 +363,13 @@ bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
          exact_input_shift(g, bt) >= 0;
 }
 
-hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
-                                  const void* U, void* y, float r_v, float r_m, float r_y,
-                                  float qmax, hipStream_t s) {
+namespace {
+
+template <int M>
+hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                          const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
+                          hipStream_t s) {
+  constexpr int n = M + 2, P = n * n, NBLK = (P + 15) / 16;
   const int sft = exact_input_shift(g, bt);
   if (sft < 0 || !fused_fwd_exact_supported(g, bt)) return hipErrorInvalidValue;
   const float bt_scale = (float)(1 << sft);
@@ -354,13 +377,14 @@ hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& a
   if (!(r_vs * (float)(1 << (2 * sft)) == r_v)) return hipErrorInvalidValue;   // underflow
   // W in MFMA register order (see KronW)
   KronW kw;
+  memset(&kw, 0, sizeof kw);
   int bi[8][8] = {};
-  for (int i = 0; i < kXN; ++i)
-    for (int j = 0; j < kXN; ++j) bi[i][j] = (int)(bt.v[i * kXN + j] * bt_scale);
-  for (int blk = 0; blk < 3; ++blk)
+  for (int i = 0; i < n; ++i)
+    for (int j = 0; j < n; ++j) bi[i][j] = (int)(bt.v[i * n + j] * bt_scale);
+  for (int blk = 0; blk < NBLK; ++blk)
     for (int lane = 0; lane < 64; ++lane) {
       const int p = blk * 16 + (lane & 15), kgrp = lane >> 4;
-      const int i = p < kXP ? p / kXN : 7, k = p < kXP ? p % kXN : 7;     // row 7 of bi is zero
+      const int i = p < P ? p / n : 7, k = p < P ? p % n : 7;     // row 7 of bi is zero
       for (int d = 0; d < 4; ++d) {
         uint32_t word = 0;
         for (int e = 0; e < 4; ++e) {
@@ -374,10 +398,10 @@ hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& a
   int TWB = g.TW < 16 ? g.TW : 16;
   int RB = 16 / TWB;
   if (RB > R) RB = R;
-  const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(TWB) + 4) * 4, vl_b = (size_t)kXP * kVlPitch * 4;
+  const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(M, TWB) + 4) * 4, vl_b = (size_t)P * kVlPitch * 4;
   const size_t lb = xs_b > vl_b ? xs_b : vl_b;
   const int ntwb = (g.TW + TWB - 1) / TWB, nrb = (R + RB - 1) / RB;
-  const int strip = kXN * xs_row_dw(TWB);
+  const int strip = n * xs_row_dw(M, TWB);
   if (lb > 65536 || ntwb > 65535 || g.Kp / 64 > 65535 || strip > 256) return hipErrorInvalidValue;
   dim3 grid((unsigned)nrb, (unsigned)ntwb, (unsigned)(g.Kp / 64));
   XPlan pl;
@@ -385,44 +409,56 @@ hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& a
   pl.TWB = TWB;
   pl.inv_twb = make_inv(TWB);
   pl.inv_strip = make_inv(strip);
-  pl.inv_wq = make_inv(xs_row_dw(TWB));
+  pl.inv_wq = make_inv(xs_row_dw(M, TWB));
   pl.inv_th = make_inv(g.TH);
-  const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<kXM>::at);
+  const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
   const int8_t* xi = (const int8_t*)x;
   const int8_t* Ui = (const int8_t*)U;
   const int load = g.W < 4 ? 0 : (g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0) ? 2 : 1;
-  const bool mq = r_m > 0.0f;
-  const bool one = g.Cp == 64;
-  // compile-time workgroup shapes for the common image widths (32, 16 pixels)
-  const int shape = (TWB == 8 && RB == 2) ? 8 : (TWB == 4 && RB == 4) ? 4 : 0;
-  // the common case gets the branch-free output side: whole tiles, K % 4 == 0, default
-  // A^T pattern, no quantizer on M, aligned 8-byte staging loads
-  const bool fast = g.Ho % kXM == 0 && g.Wo % kXM == 0 && g.K % 4 == 0;
-#define WINO_LAUNCH_XF(SA, LOAD, MQ, ONE, TWBC, FAST)                                      \
-  fused_fwd_exact_kernel<SA, LOAD, MQ, ONE, TWBC, FAST><<<grid, 256, lb, s>>>(               \
+  const bool mq = r_m > 0.0f, one = g.Cp == 64;
+#define WINO_LAUNCH_XK(SA, LOAD, MQ, ONE, TWBC, FAST)                                      \
+  fused_fwd_exact_kernel<M, SA, LOAD, MQ, ONE, TWBC, FAST><<<grid, 256, lb, s>>>(            \
       xi, Ui, y, r_vs, r_m, r_y, qmax, g, pl, at, kw)
-#define WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, TWBC)                                            \
-  do { if (fast && SA && LOAD == 2 && !MQ) WINO_LAUNCH_XF(SA, LOAD, MQ, ONE, TWBC, true);  \
-       else WINO_LAUNCH_XF(SA, LOAD, MQ, ONE, TWBC, false); } while (0)
-#define WINO_LAUNCH_X(SA, LOAD, MQ, ONE)                                                   \
-  do { if (shape == 8) WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, 8);                               \
-       else if (shape == 4) WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, 4);                          \
-       else WINO_LAUNCH_X0(SA, LOAD, MQ, ONE, 0); } while (0)
-#define WINO_LAUNCH_X1(SA, LOAD, MQ) \
-  do { if (one) WINO_LAUNCH_X(SA, LOAD, MQ, true); else WINO_LAUNCH_X(SA, LOAD, MQ, false); } while (0)
-#define WINO_LAUNCH_X2(SA, LOAD) \
-  do { if (mq) WINO_LAUNCH_X1(SA, LOAD, true); else WINO_LAUNCH_X1(SA, LOAD, false); } while (0)
-#define WINO_LAUNCH_X3(SA)                                                                 \
-  do { if (load == 2) WINO_LAUNCH_X2(SA, 2); else if (load == 1) WINO_LAUNCH_X2(SA, 1);    \
-       else WINO_LAUNCH_X2(SA, 0); } while (0)
-  if (sa) WINO_LAUNCH_X3(true); else WINO_LAUNCH_X3(false);
-#undef WINO_LAUNCH_X3
-#undef WINO_LAUNCH_X2
-#undef WINO_LAUNCH_X1
-#undef WINO_LAUNCH_X
-#undef WINO_LAUNCH_X0
-#undef WINO_LAUNCH_XF
+  // The common case -- whole tiles, K % 4 == 0, Cook-Toom A^T pattern, no quantizer on M,
+  // aligned 8-byte staging loads, a power-of-two workgroup shape (16, 8, 4 or 2 tiles
+  // per row: 32 .. 8 pixel images) -- gets compile-time shapes and a branch-free output side.
+  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && sa && load == 2 && !mq &&
+                    RB * TWB == 16;
+  if (fast && (TWB == 16 || TWB == 8 || TWB == 4 || TWB == 2)) {
+#define WINO_LAUNCH_FAST(TWBC) \
+  do { if (one) WINO_LAUNCH_XK(true, 2, false, true, TWBC, true);  \
+       else WINO_LAUNCH_XK(true, 2, false, false, TWBC, true); } while (0)
+    if (TWB == 16) WINO_LAUNCH_FAST(16);
+    else if (TWB == 8) WINO_LAUNCH_FAST(8);
+    else if (TWB == 4) WINO_LAUNCH_FAST(4);
+    else WINO_LAUNCH_FAST(2);
+#undef WINO_LAUNCH_FAST
+    return hipGetLastError();
+  }
+#define WINO_LAUNCH_G1(SA, LOAD, MQ) \
+  do { if (one) WINO_LAUNCH_XK(SA, LOAD, MQ, true, 0, false);      \
+       else WINO_LAUNCH_XK(SA, LOAD, MQ, false, 0, false); } while (0)
+#define WINO_LAUNCH_G2(SA, LOAD) \
+  do { if (mq) WINO_LAUNCH_G1(SA, LOAD, true); else WINO_LAUNCH_G1(SA, LOAD, false); } while (0)
+#define WINO_LAUNCH_G3(SA)                                                                 \
+  do { if (load == 2) WINO_LAUNCH_G2(SA, 2); else if (load == 1) WINO_LAUNCH_G2(SA, 1);    \
+       else WINO_LAUNCH_G2(SA, 0); } while (0)
+  if (sa) WINO_LAUNCH_G3(true); else WINO_LAUNCH_G3(false);
+#undef WINO_LAUNCH_G3
+#undef WINO_LAUNCH_G2
+#undef WINO_LAUNCH_G1
+#undef WINO_LAUNCH_XK
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                                  const void* U, void* y, float r_v, float r_m, float r_y,
+                                  float qmax, hipStream_t s) {
+  if (g.m == 2) return launch_exact_m<2>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, s);
+  if (g.m == 4) return launch_exact_m<4>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, s);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace wino

@@ -36,11 +36,16 @@ __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv,
 #pragma unroll
       for (int a = 0; a < M; ++a) {
         int8_t* row = y + (size_t)(h0 + a) * g.Wo + w0;
-        if (M == 4 && (kFast || (g.Wo & 3) == 0)) {
-          uint32_t lo16 = __builtin_amdgcn_perm(q[a][1], q[a][0], 0x0c0c0400u);
-          uint32_t hi16 = __builtin_amdgcn_perm(q[a][3], q[a][2], 0x04000c0cu);
-          *(uint32_t*)row = lo16 | hi16;
-        } else {
+        bool dword_row = false;
+        if constexpr (M == 4) {
+          dword_row = kFast || (g.Wo & 3) == 0;
+          if (dword_row) {
+            uint32_t lo16 = __builtin_amdgcn_perm(q[a][1], q[a][0], 0x0c0c0400u);
+            uint32_t hi16 = __builtin_amdgcn_perm(q[a][3], q[a][2], 0x04000c0cu);
+            *(uint32_t*)row = lo16 | hi16;
+          }
+        }
+        if (!dword_row) {
 #pragma unroll
           for (int b = 0; b < M; b += 2)
             *(uint16_t*)(row + b) =
@@ -70,7 +75,8 @@ __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv,
 // consecutive output channels k0..k0+3 (vector components) of every position:
 // transform each of the four n x n matrices and store its tile.
 // kMQ: the optional quantizer after the Hadamard stage is on (r_m > 0).
-// kFast: whole tiles only (see store_tile) and K a multiple of 4 (no channel guard).
+// kFast: whole tiles only (see store_tile), K a multiple of 4 and k0 < K checked by the
+// caller (no channel guard here).
 template <int M, bool I8, bool kSparse, bool kMQ, bool kFast = false>
 __device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
                                             const typename Acc<I8>::type (&acc)[(M + 2) * (M + 2)],

@@ -59,6 +59,13 @@ SMALL = [
     Layer("s_f4_c128k128", 2, 128, 128, 8, 8, m=4, seed=114),   # two channel blocks, two k blocks
     Layer("s_f2_32px", 2, 64, 32, 32, 32, m=2, seed=115),
     Layer("s_f6_32px", 1, 64, 64, 32, 32, m=6, seed=116),
+    Layer("s_f2_16px_c128", 2, 128, 128, 16, 16, m=2, seed=117),  # F2, two channel and k blocks
+    Layer("s_f2_8px", 5, 64, 64, 8, 8, m=2, seed=118),            # 4 tiles per row
+    Layer("s_f2_14px", 3, 48, 36, 14, 14, m=2, seed=119),         # 7 tiles per row: odd window offsets
+    Layer("s_f4_8px", 9, 64, 64, 8, 8, m=4, seed=120),            # 2 tiles per row, ragged row blocks
+    Layer("s_f4_64px", 1, 64, 64, 64, 64, m=4, seed=121),         # 16 tiles per row
+    Layer("s_f4_k32", 3, 64, 32, 16, 16, m=4, seed=122),          # K below the 64-channel block
+    Layer("s_f4_k100", 2, 64, 100, 16, 16, m=4, seed=123),        # K = 64 + 36
 ]
 
 
