@@ -37,9 +37,14 @@ __global__ __launch_bounds__(256) void gemm_out_kernel(Geom g, MatAT at,
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, grp = lane >> 4;
   const int t = tb + r;
   const int krow = kb + wave * 16 + r;
+  // Addresses = uniform 64-bit base (position, channel chunk: scalar registers) + a
+  // 32-bit per-lane offset (row, lane group): no per-position 64-bit vector pointers,
+  // which would not fit next to n*n accumulator sets.  The host checks the 32-bit range.
   const size_t vp = (size_t)g.Tp * g.Cp * ESZ, up = (size_t)g.Kp * g.Cp * ESZ;
-  const char* vrow = (const char*)Vv + ((size_t)t * g.Cp) * ESZ + grp * 16;
-  const char* urow = (const char*)Uv + ((size_t)krow * g.Cp) * ESZ + grp * 16;
+  const uint32_t voff = (uint32_t)t * (uint32_t)(g.Cp * ESZ) + (uint32_t)grp * 16u;
+  const uint32_t uoff = (uint32_t)krow * (uint32_t)(g.Cp * ESZ) + (uint32_t)grp * 16u;
+  const char* vrow = (const char*)Vv;
+  const char* urow = (const char*)Uv;
   const int nchunk = g.Cp / CHUNK;
 
   // Operand stream: step (ch, p) needs 16 bytes of V and 16 bytes of U per lane.  With
@@ -52,24 +57,41 @@ __global__ __launch_bounds__(256) void gemm_out_kernel(Geom g, MatAT at,
   op_t bufV[kDepth], bufU[kDepth];
 #pragma unroll
   for (int p = 0; p < kDepth; ++p) {
-    bufV[p] = *(const op_t*)(vrow + p * vp);
-    bufU[p] = *(const op_t*)(urow + p * up);
+    bufV[p] = *(const op_t*)(vrow + p * vp + voff);
+    bufU[p] = *(const op_t*)(urow + p * up + uoff);
   }
   acc_t acc[P];
 #pragma unroll
   for (int p = 0; p < P; ++p) acc[p] = acc_t{0, 0, 0, 0};
+  // Running (uniform) load pointers, advanced by one position per step and wrapped to
+  // the next channel chunk after the last position: a loop-carried pair of scalar
+  // registers each, instead of one precomputed base per position.
+  const char* vchunk = vrow;
+  const char* uchunk = urow;
+  const char* vld = vrow + kDepth * vp;
+  const char* uld = urow + kDepth * up;
   for (int ch = 0; ch < nchunk; ++ch) {
 #pragma unroll
     for (int p = 0; p < P; ++p) {
       const op_t bv = bufV[p % kDepth], au = bufU[p % kDepth];
-      // refill the slot with the operands of step p + kDepth
-      if (p + kDepth < P) {
-        bufV[p % kDepth] = *(const op_t*)(vrow + (p + kDepth) * vp + (size_t)ch * 64);
-        bufU[p % kDepth] = *(const op_t*)(urow + (p + kDepth) * up + (size_t)ch * 64);
-      } else if (ch + 1 < nchunk) {
-        bufV[p % kDepth] = *(const op_t*)(vrow + (p + kDepth - P) * vp + (size_t)(ch + 1) * 64);
-        bufU[p % kDepth] = *(const op_t*)(urow + (p + kDepth - P) * up + (size_t)(ch + 1) * 64);
+      // refill the slot with the operands of step p + kDepth (of the next chunk, if any,
+      // once the positions of this one are all on their way)
+      if (p + kDepth < P || ch + 1 < nchunk) {
+        bufV[p % kDepth] = *(const op_t*)(vld + voff);
+        bufU[p % kDepth] = *(const op_t*)(uld + uoff);
       }
+      if (p + kDepth + 1 == P) {
+        vchunk += 64;
+        uchunk += 64;
+        vld = vchunk;
+        uld = uchunk;
+      } else {
+        vld += vp;
+        uld += up;
+      }
+      // (empty statement: keeps the two pointers in scalar registers as they are; without
+      // it the optimiser rewrites the chain as one 64-bit vector pointer per position)
+      asm volatile("" : "+s"(vld), "+s"(uld));
       if constexpr (I8) {
         acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, acc[p], 0, 0, 0);
       } else {
@@ -90,7 +112,10 @@ __global__ __launch_bounds__(256) void gemm_out_kernel(Geom g, MatAT at,
 template <int M, bool I8>
 hipError_t launch_m(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                     float r_m, float r_y, float qmax, hipStream_t s) {
-  if (g.Kp / 64 > 65535) return hipErrorInvalidValue;
+  const size_t esz = I8 ? 1 : 4;
+  if (g.Kp / 64 > 65535 || (size_t)g.Tp * g.Cp * esz >= 0xffffffffull ||
+      (size_t)g.Kp * g.Cp * esz >= 0xffffffffull)
+    return hipErrorInvalidValue;
   dim3 grid(g.Tp / 16, g.Kp / 64);
   const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
   if (I8 && r_m > 0.0f) {

@@ -41,7 +41,11 @@ hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M
 // GEMM and output transform in one kernel (M stays in registers, operands straight
 // from global memory): preferred while the reduction is short and the n*n accumulator
 // sets leave room for two wavefronts per SIMD.
-inline bool gemm_out_preferred(const Geom& g) { return g.Cp * (g.i8 ? 1 : 4) <= 128 && g.m != 6; }
+inline bool gemm_out_preferred(const Geom& g) {
+  // (8 x 8 accumulator sets fill the register file: one wavefront per SIMD, so the
+  // operand stream must be short to stay ahead)
+  return g.Cp * (g.i8 ? 1 : 4) <= (g.m == 6 ? 64 : 128);
+}
 hipError_t launch_gemm_out(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                            float r_m, float r_y, float qmax, hipStream_t s);
 // Whole int8 forward in one kernel (neither V nor M stored); only where supported.
