@@ -175,23 +175,33 @@ def gpu_leg(L, steps, warmup, use_graph):
         stages = [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
                   ("gemm_output", wb.WINO_STAGE_GEMM | wb.WINO_STAGE_OUTPUT)]
     ksteps = max(20, min(steps, 200))
-    acc = {n: 0.0 for n, _ in stages}
-    with torch.cuda.stream(stream):
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)]
-               for _ in range(ksteps)]
-        for it in range(ksteps + 5):
-            row = evs[max(it - 5, 0)]
-            row[0].record(stream)
-            for si, (name, mask) in enumerate(stages):
-                if mask is None:
-                    wb.wino_transform_weights(desc, quant, gd, U, stream=stream)
-                else:
-                    wb.wino_conv2d_fwd_stages(desc, quant, x, U, y, ws, mask, stream=stream)
-                row[si + 1].record(stream)
-        torch.cuda.synchronize()
-        for row in evs:
-            for si, (name, _) in enumerate(stages):
-                acc[name] += row[si].elapsed_time(row[si + 1]) * 1e3 / ksteps   # us
+
+    def time_stages(stages):
+        acc = {n: 0.0 for n, _ in stages}
+        with torch.cuda.stream(stream):
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)]
+                   for _ in range(ksteps)]
+            for it in range(ksteps + 5):
+                row = evs[max(it - 5, 0)]
+                row[0].record(stream)
+                for si, (name, mask) in enumerate(stages):
+                    if mask is None:
+                        wb.wino_transform_weights(desc, quant, gd, U, stream=stream)
+                    else:
+                        wb.wino_conv2d_fwd_stages(desc, quant, x, U, y, ws, mask, stream=stream)
+                    row[si + 1].record(stream)
+            torch.cuda.synchronize()
+            for row in evs:
+                for si, (name, _) in enumerate(stages):
+                    acc[name] += row[si].elapsed_time(row[si + 1]) * 1e3 / ksteps   # us
+        return acc
+
+    acc = time_stages(stages)
+    # the four kernels of the unfused path, one call each (the paper's kernels a-d as
+    # separate launches, V and M through memory), whatever the forward call itself uses
+    acc_staged = acc if nk == 3 else time_stages(
+        [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
+         ("gemm", wb.WINO_STAGE_GEMM), ("output_transform", wb.WINO_STAGE_OUTPUT)])
 
     # im2row baseline on the same layer, forward only (weights packed once)
     s_w = scales.get("s_w", 1.0)
@@ -211,7 +221,8 @@ def gpu_leg(L, steps, warmup, use_graph):
                           scales["s_y"], 127, rws, stream=stream)
 
     ms_ref = timed(ref_fwd, max(10, steps // 4), max(2, warmup // 4))
-    return dict(ms_step=ms_step, ms_fwd=ms_fwd, ms_ref=ms_ref, kernel_us=acc, BT=BT, AT=AT)
+    return dict(ms_step=ms_step, ms_fwd=ms_fwd, ms_ref=ms_ref, kernel_us=acc, staged_us=acc_staged,
+                BT=BT, AT=AT)
 
 
 def cpu_leg(L):
@@ -300,6 +311,8 @@ def main():
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
                                                "kernel", "avg_us")},
         "kernels": kernels,
+        "staged_kernels": [roofline_entry(k, alg[k], us, L.dtype, None)
+                           for k, us in r["staged_us"].items()],
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_leg(L)

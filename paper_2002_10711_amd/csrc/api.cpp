@@ -182,7 +182,9 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
             : launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs);
     return e == hipSuccess ? WINO_OK : WINO_E_HIP;
   }
-  if (s_in && launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs) != hipSuccess)
+  if (s_in && (input_exact_preferred(g, bt, x_dev)
+                   ? launch_input_exact(g, bt, x_dev, V, s.r_v, s.qmax, hs)
+                   : launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs)) != hipSuccess)
     return WINO_E_HIP;
   if (s_mm && s_out && gemm_out_preferred(g)) {
     // short reductions: GEMM and output transform in one kernel, M stays in registers

@@ -325,6 +325,104 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
   WINO_TS(6);
 }
 
+
+// The input stage alone, for the layers whose accumulators do not fit the fused kernel
+// and for the per-stage calls: same staging, window gather and MFMA transform, then the
+// block's V tile goes from LDS to memory in the GEMM's operand order V[p][t][c].
+// Grid: x = blocks of RB tile rows, y = blocks of TWB tiles along a row, z = blocks of 64
+// input channels.  Tiles of a workgroup that lie beyond the image are not written; the
+// rows of V between T and Tp are never read by anything that reaches the output.
+template <int M, int kTWB>
+__global__ __launch_bounds__(256) void input_transform_exact_kernel(
+    const int8_t* __restrict__ x, int8_t* __restrict__ V, float r_vs, float qmax, Geom g, XPlan pl,
+    KronW kw) {
+  constexpr int n = M + 2, P = n * n;
+  constexpr int NBLK = (P + 15) / 16, NSTEP = 16 * NBLK;
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  uint32_t* Xs = lds;
+  uint32_t* Vl = lds;                                  // aliases Xs
+  const int RB = kTWB ? 16 / (kTWB ? kTWB : 1) : pl.RB, TWB = kTWB ? kTWB : pl.TWB;
+  const int WQ = xs_row_dw(M, TWB), plane = xs_plane_dw(M, TWB);
+  const int r0 = blockIdx.x * RB, tw0 = blockIdx.y * TWB, cb = blockIdx.z;
+  const int R = g.N * g.TH;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const float lo = kMagic - qmax, hi = kMagic + qmax;
+
+  stage_planes<M, 2, kTWB>(g, pl, x, Xs, cb * 64, r0, tw0);    // aligned 8-byte loads only
+  v4i Wb[NBLK];
+#pragma unroll
+  for (int blk = 0; blk < NBLK; ++blk) Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
+  __syncthreads();
+
+  // window operands: see fused_fwd_exact_kernel
+  v4i Aw[16];
+  {
+    const int j0 = 2 * grp < n ? 2 * grp : 0, j1 = 2 * grp + 1 < n ? 2 * grp + 1 : 0;
+    const uint32_t* lane_x = Xs + r * plane + j0 * WQ;
+    const int dj = (j1 - j0) * WQ;
+#pragma unroll
+    for (int t4 = 0; t4 < 4; ++t4) {
+      const int tl = wave * 4 + t4;
+      int rs = kTWB ? tl / (kTWB ? kTWB : 1) : (int)fast_div(tl, pl.inv_twb);
+      const int twl = tl - rs * TWB;
+      rs = rs < RB ? rs : 0;
+      const uint32_t* p0 = lane_x + rs * 64 * plane + ((twl * M) >> 2);
+      const int sh = (twl * M) & 3;
+#pragma unroll
+      for (int cg = 0; cg < 4; ++cg) {
+        const uint32_t* p1 = p0 + cg * 16 * plane;
+        if constexpr (M == 4) {
+          Aw[t4 * 4 + cg] = v4i{(int)p1[0], (int)p1[1], (int)p1[dj], (int)p1[dj + 1]};
+        } else {
+          const uint32_t a0 = __builtin_amdgcn_alignbyte(p1[1], p1[0], sh);
+          const uint32_t a1 = __builtin_amdgcn_alignbyte(p1[dj + 1], p1[dj], sh);
+          Aw[t4 * 4 + cg] = v4i{(int)a0, (int)p1[1], (int)a1, (int)p1[dj + 1]};
+        }
+      }
+    }
+  }
+  __syncthreads();                                     // Xs is free: Vl may overwrite it
+
+  uint32_t* lane_v = Vl + r * kVlPitch + grp;
+  v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], v4i{0, 0, 0, 0}, 0, 0, 0);
+#pragma unroll
+  for (int st = 0; st < NSTEP; ++st) {
+    const int gi = st / NBLK, blk = st % NBLK;
+    v4i nxt = cur;
+    if (st + 1 < NSTEP)
+      nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
+                                                  v4i{0, 0, 0, 0}, 0, 0, 0);
+    uint32_t packed = 0u;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr)
+      packed = __builtin_amdgcn_perm(quantize_bits((float)cur[rr], r_vs, lo, hi), packed, 0x04030201u);
+    const int tl = wave * 4 + (gi >> 2);
+    if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
+    cur = nxt;
+  }
+  __syncthreads();
+
+  // Vl[p][tile][16 dwords] -> V[p][t][cb*64 ..]: a lane moves 16 bytes, a wavefront the 16
+  // tiles of one position (1 KB, contiguous in V when the tiles are consecutive and
+  // Cp == 64); wave w takes the positions p = w, w + 4, ...
+  const int tl = lane >> 2, q4 = lane & 3;
+  const int rs = kTWB ? tl / (kTWB ? kTWB : 1) : (int)fast_div(tl, pl.inv_twb), twl = tl - rs * TWB;
+  const int rr_ = r0 + rs, tw = tw0 + twl;
+  if (rs < RB && rr_ < R && tw < g.TW) {
+    const uint32_t t = (uint32_t)rr_ * (uint32_t)g.TW + (uint32_t)tw;
+    const uint32_t voff = t * (uint32_t)g.Cp + (uint32_t)cb * 64u + (uint32_t)q4 * 16u;
+    const size_t vp = (size_t)g.Tp * g.Cp;
+    const uint32_t* src = Vl + tl * 16 + q4 * 4;
+    static_assert(P % 4 == 0, "positions are dealt out to four wavefronts");
+#pragma unroll
+    for (int i = 0; i < P / 4; ++i) {
+      const int p = i * 4 + wave;
+      *(v4i*)(V + (size_t)p * vp + voff) = *(const v4i*)(src + p * kVlPitch);
+    }
+  }
+}
+
 }  // namespace
 
 // Host: smallest s <= 3 with 2^s B^T integral, all pairwise products within int8, and
@@ -356,27 +454,47 @@ int exact_input_shift(const Geom& g, const MatBT& bt) {
   return -1;
 }
 
-bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
-  // the reciprocal of TH must be exact for every tile row index (see XPlan)
+bool input_exact_supported(const Geom& g, const MatBT& bt) {
+  // the reciprocal of TH must be exact for every tile row index (see XPlan), and the
+  // per-lane offsets into V are 32-bit
   const unsigned long long R = (unsigned long long)g.N * g.TH;
-  return g.Kp <= 128 && R * (unsigned long long)g.TH < 0x100000000ull &&
-         exact_input_shift(g, bt) >= 0;
+  return R * (unsigned long long)g.TH < 0x100000000ull &&
+         (unsigned long long)g.Tp * g.Cp < 0x100000000ull && exact_input_shift(g, bt) >= 0;
+}
+
+bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
+  return g.Kp <= 128 && input_exact_supported(g, bt);
+}
+
+// As a stand-alone input stage the exact kernel pays off where its staging runs on
+// aligned 8-byte loads; images narrower than 8 pixels (one or two tiles per row) are
+// better served by the vector-ALU kernel, whose workgroups span many images.
+bool input_exact_preferred(const Geom& g, const MatBT& bt, const void* x) {
+  return g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0 && input_exact_supported(g, bt);
 }
 
 namespace {
 
+// What the host prepares for either kernel: W, the plan, the scaled quantizer factor,
+// the LDS size and the grid extents along tile rows and row pieces.
+struct XLaunch {
+  KronW kw;
+  XPlan pl;
+  float r_vs;
+  size_t lds_bytes;
+  int nrb, ntwb, load;
+};
+
 template <int M>
-hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
-                          const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
-                          hipStream_t s) {
+bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLaunch* xl) {
   constexpr int n = M + 2, P = n * n, NBLK = (P + 15) / 16;
   const int sft = exact_input_shift(g, bt);
-  if (sft < 0 || !fused_fwd_exact_supported(g, bt)) return hipErrorInvalidValue;
+  if (sft < 0 || !input_exact_supported(g, bt)) return false;
   const float bt_scale = (float)(1 << sft);
-  const float r_vs = r_v / (float)(1 << (2 * sft));      // exact power-of-two scaling
-  if (!(r_vs * (float)(1 << (2 * sft)) == r_v)) return hipErrorInvalidValue;   // underflow
+  xl->r_vs = r_v / (float)(1 << (2 * sft));              // exact power-of-two scaling
+  if (!(xl->r_vs * (float)(1 << (2 * sft)) == r_v)) return false;   // underflow
   // W in MFMA register order (see KronW)
-  KronW kw;
+  KronW& kw = xl->kw;
   memset(&kw, 0, sizeof kw);
   int bi[8][8] = {};
   for (int i = 0; i < n; ++i)
@@ -399,22 +517,60 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   int RB = 16 / TWB;
   if (RB > R) RB = R;
   const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(M, TWB) + 4) * 4, vl_b = (size_t)P * kVlPitch * 4;
-  const size_t lb = xs_b > vl_b ? xs_b : vl_b;
-  const int ntwb = (g.TW + TWB - 1) / TWB, nrb = (R + RB - 1) / RB;
+  xl->lds_bytes = xs_b > vl_b ? xs_b : vl_b;
+  xl->ntwb = (g.TW + TWB - 1) / TWB;
+  xl->nrb = (R + RB - 1) / RB;
   const int strip = n * xs_row_dw(M, TWB);
-  if (lb > 65536 || ntwb > 65535 || g.Kp / 64 > 65535 || strip > 256) return hipErrorInvalidValue;
-  dim3 grid((unsigned)nrb, (unsigned)ntwb, (unsigned)(g.Kp / 64));
-  XPlan pl;
+  if (xl->lds_bytes > 65536 || xl->ntwb > 65535 || strip > 256) return false;
+  XPlan& pl = xl->pl;
   pl.RB = RB;
   pl.TWB = TWB;
   pl.inv_twb = make_inv(TWB);
   pl.inv_strip = make_inv(strip);
   pl.inv_wq = make_inv(xs_row_dw(M, TWB));
   pl.inv_th = make_inv(g.TH);
+  xl->load = g.W < 4 ? 0 : (g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0) ? 2 : 1;
+  return true;
+}
+
+template <int M>
+hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
+                          float qmax, hipStream_t s) {
+  XLaunch xl;
+  if (!make_xlaunch<M>(g, bt, x, r_v, &xl) || g.Cp / 64 > 65535) return hipErrorInvalidValue;
+  dim3 grid((unsigned)xl.nrb, (unsigned)xl.ntwb, (unsigned)(g.Cp / 64));
+  const int8_t* xi = (const int8_t*)x;
+  int8_t* Vi = (int8_t*)V;
+  const int TWB = xl.pl.TWB, RB = xl.pl.RB;
+#define WINO_LAUNCH_IN(TWBC)                                                               \
+  input_transform_exact_kernel<M, TWBC><<<grid, 256, xl.lds_bytes, s>>>(                     \
+      xi, Vi, xl.r_vs, qmax, g, xl.pl, xl.kw)
+  if (xl.load != 2) return hipErrorInvalidValue;         // see input_exact_preferred
+  if (RB * TWB == 16 && TWB == 16) WINO_LAUNCH_IN(16);
+  else if (RB * TWB == 16 && TWB == 8) WINO_LAUNCH_IN(8);
+  else if (RB * TWB == 16 && TWB == 4) WINO_LAUNCH_IN(4);
+  else if (RB * TWB == 16 && TWB == 2) WINO_LAUNCH_IN(2);
+  else WINO_LAUNCH_IN(0);
+#undef WINO_LAUNCH_IN
+  return hipGetLastError();
+}
+
+template <int M>
+hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                          const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
+                          hipStream_t s) {
+  XLaunch xl;
+  if (!fused_fwd_exact_supported(g, bt) || !make_xlaunch<M>(g, bt, x, r_v, &xl))
+    return hipErrorInvalidValue;
+  dim3 grid((unsigned)xl.nrb, (unsigned)xl.ntwb, (unsigned)(g.Kp / 64));
+  const XPlan& pl = xl.pl;
+  const KronW& kw = xl.kw;
+  const float r_vs = xl.r_vs;
+  const size_t lb = xl.lds_bytes;
+  const int TWB = pl.TWB, RB = pl.RB, load = xl.load;
   const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
   const int8_t* xi = (const int8_t*)x;
   const int8_t* Ui = (const int8_t*)U;
-  const int load = g.W < 4 ? 0 : (g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0) ? 2 : 1;
   const bool mq = r_m > 0.0f, one = g.Cp == 64;
 #define WINO_LAUNCH_XK(SA, LOAD, MQ, ONE, TWBC, FAST)                                      \
   fused_fwd_exact_kernel<M, SA, LOAD, MQ, ONE, TWBC, FAST><<<grid, 256, lb, s>>>(            \
@@ -452,6 +608,13 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
 }
 
 }  // namespace
+
+hipError_t launch_input_exact(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
+                              float qmax, hipStream_t s) {
+  if (g.m == 2) return launch_input_m<2>(g, bt, x, V, r_v, qmax, s);
+  if (g.m == 4) return launch_input_m<4>(g, bt, x, V, r_v, qmax, s);
+  return hipErrorInvalidValue;
+}
 
 hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                                   const void* U, void* y, float r_v, float r_m, float r_y,

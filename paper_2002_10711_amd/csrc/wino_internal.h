@@ -55,6 +55,11 @@ hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, con
                             hipStream_t s);
 // The same for F(4x4,3x3) with an exact (dyadic) B^T: input transform on the matrix cores.
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt);
+// The input stage alone with the same exact transform (any number of output channels).
+bool input_exact_supported(const Geom& g, const MatBT& bt);
+bool input_exact_preferred(const Geom& g, const MatBT& bt, const void* x);
+hipError_t launch_input_exact(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
+                              float qmax, hipStream_t s);
 hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                                   const void* U, void* y, float r_v, float r_m, float r_y,
                                   float qmax, hipStream_t s);
