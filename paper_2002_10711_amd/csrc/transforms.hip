@@ -303,6 +303,58 @@ hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w
 }
 
 namespace {
+// Output transform, four channels per lane: the lane layout of the MFMA result (lane =
+// tile r of 16, channel quad grp; wavefront w = channels 16 w .. 16 w + 15 of a 64-channel
+// block), so every load moves 16 bytes per lane, the four wavefronts of a workgroup read
+// 256 contiguous bytes per tile and position, and the lane-local transform and the tile
+// stores are the ones of the fused kernels (16 consecutive tiles store side by side).
+// For m = 2 and 4; the 8 x 8 accumulator sets of m = 6 do not fit beside the temporaries.
+template <int M, bool I8, bool kSparse, bool kMQ, bool kFast>
+__global__ __launch_bounds__(256) void output_transform_quad(Geom g, MatAT at,
+                                                             const void* __restrict__ Mv,
+                                                             void* __restrict__ yv, float r_m,
+                                                             float r_y, float qmax) {
+  constexpr int n = M + 2, P = n * n;
+  typedef typename Acc<I8>::type acc_t;
+  const int lane = threadIdx.x & 63, r = lane & 15, grp = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int t = blockIdx.x * 16 + r, k0 = blockIdx.y * 64 + wave * 16 + grp * 4;
+  // uniform base per position + one 32-bit lane offset (the host checks the range);
+  // rows t < Tp and channels k0 + 3 < Kp exist in M whatever T and K are
+  const size_t pstride = (size_t)g.Tp * g.Kp * 4;
+  const uint32_t off = ((uint32_t)t * (uint32_t)g.Kp + (uint32_t)k0) * 4u;
+  const char* Mb = (const char*)Mv;
+  acc_t acc[P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) acc[p] = *(const acc_t*)(Mb + p * pstride + off);
+  if (t >= g.T || k0 >= g.K) return;
+  const int tw = t % g.TW, th = (t / g.TW) % g.TH, img = t / (g.TW * g.TH);
+  finish_lane<M, I8, kSparse, kMQ, kFast>(g, at, acc, yv, img, th, tw, k0, r_m, r_y, qmax);
+}
+
+template <int M, bool I8>
+hipError_t launch_output_quad(const Geom& g, const MatAT& at, const void* Mv, void* y, float r_m,
+                              float r_y, float qmax, hipStream_t s) {
+  if (g.Kp / 64 > 65535) return hipErrorInvalidValue;
+  dim3 grid(g.Tp / 16, g.Kp / 64);
+  const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool mq = I8 && r_m > 0.0f;
+  const bool fast = I8 && !mq && sparse && g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
+  if (fast)
+    output_transform_quad<M, I8, true, false, I8><<<grid, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  else if (mq && sparse)
+    output_transform_quad<M, I8, true, I8, false><<<grid, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  else if (mq)
+    output_transform_quad<M, I8, false, I8, false><<<grid, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  else if (sparse)
+    output_transform_quad<M, I8, true, false, false><<<grid, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  else
+    output_transform_quad<M, I8, false, false, false><<<grid, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  return hipGetLastError();
+}
+}  // namespace
+
+namespace {
 template <int M, bool I8>
 hipError_t launch_output_m(const Geom& g, const MatAT& at, const void* Mv, void* y, float r_m,
                            float r_y, float qmax, hipStream_t s) {
@@ -325,16 +377,25 @@ hipError_t launch_output_m(const Geom& g, const MatAT& at, const void* Mv, void*
 
 hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M, void* y, float r_m,
                                    float r_y, float qmax, hipStream_t s) {
+  // four channels per lane: needs 32-bit lane offsets, and enough workgroups (16 tiles x
+  // 64 channels each) for one per compute unit; below that the thread-per-(tile,
+  // channel) kernel spreads the work further
+  const bool quad = (unsigned long long)g.Tp * g.Kp * 4 < 0x100000000ull &&
+                    (long long)(g.Tp / 16) * (g.Kp / 64) >= 256;
   if (g.i8) {
     switch (g.m) {
-      case 2: return launch_output_m<2, true>(g, at, M, y, r_m, r_y, qmax, s);
-      case 4: return launch_output_m<4, true>(g, at, M, y, r_m, r_y, qmax, s);
+      case 2: return quad ? launch_output_quad<2, true>(g, at, M, y, r_m, r_y, qmax, s)
+                          : launch_output_m<2, true>(g, at, M, y, r_m, r_y, qmax, s);
+      case 4: return quad ? launch_output_quad<4, true>(g, at, M, y, r_m, r_y, qmax, s)
+                          : launch_output_m<4, true>(g, at, M, y, r_m, r_y, qmax, s);
       default: return launch_output_m<6, true>(g, at, M, y, r_m, r_y, qmax, s);
     }
   }
   switch (g.m) {
-    case 2: return launch_output_m<2, false>(g, at, M, y, r_m, r_y, qmax, s);
-    case 4: return launch_output_m<4, false>(g, at, M, y, r_m, r_y, qmax, s);
+    case 2: return quad ? launch_output_quad<2, false>(g, at, M, y, r_m, r_y, qmax, s)
+                        : launch_output_m<2, false>(g, at, M, y, r_m, r_y, qmax, s);
+    case 4: return quad ? launch_output_quad<4, false>(g, at, M, y, r_m, r_y, qmax, s)
+                        : launch_output_m<4, false>(g, at, M, y, r_m, r_y, qmax, s);
     default: return launch_output_m<6, false>(g, at, M, y, r_m, r_y, qmax, s);
   }
 }

@@ -116,6 +116,27 @@ def test_saturation_and_m_quantizer(oracle):
     _check_i8(case, run_gpu(case, scales=sc))
 
 
+@pytest.mark.parametrize("m", [2, 4])
+def test_many_tiles_ragged_flex_and_m_quantizer(oracle, m):
+    """Few channels, many tiles: large enough (>= 256 workgroups of 16 tiles x 64 output
+    channels) for the kernels that are only chosen on big grids, with ragged tiles
+    (30 = 7.5 tiles of 4), K not a multiple of 4, dense (perturbed) matrices, and the
+    optional quantizer after the Hadamard stage; then the same with the default
+    matrices in fp32."""
+    from dataclasses import replace
+    L = Layer("many_tiles_m%d" % m, 32 if m == 4 else 10, 16, 70, 30, 30, m=m, flex_sigma=0.02,
+              seed=124 + m)
+    case = make_case(oracle, L, with_oracle=False)
+    sc = dict(case["scales"])
+    sc["s_m"] = sc["s_u"] * sc["s_v"] * 3.0
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc)
+    _check_i8(case, run_gpu(case, scales=sc))
+    case = make_case(oracle, replace(L, flex_sigma=0.0))          # Cook-Toom pattern, no s_m
+    _check_i8(case, run_gpu(case))
+    case = make_case(oracle, replace(L, flex_sigma=0.0, dtype="f32"))
+    _check_f32(oracle, case, run_gpu(case))
+
+
 def test_config2_int8_full(oracle):
     case = make_case(oracle, workloads.config2("i8")[0])
     _check_i8(case, run_gpu(case))
