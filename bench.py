@@ -311,7 +311,7 @@ def main():
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
                                                "kernel", "avg_us")},
         "kernels": kernels,
-        "staged_kernels": [roofline_entry(k, alg[k], us, L.dtype, None)
+        "staged_kernels": [roofline_entry(k, alg[k], us, L.dtype, traffic.get(k))
                            for k, us in r["staged_us"].items()],
     }
     if not a.no_cpu_baseline:
