@@ -139,7 +139,7 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, cons
 int wino_fwd_num_kernels(const wino_desc* d) {
   Geom g;
   if (make_geom(d, &g) != WINO_OK) return 0;
-  return fused_fwd_supported(g) ? 1 : gemm_out_preferred(g) ? 2 : 3;
+  return (fused_fwd_supported(g) || fused_fwd_f32_supported(g)) ? 1 : gemm_out_preferred(g) ? 2 : 3;
 }
 
 wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
@@ -182,6 +182,9 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
             : launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs);
     return e == hipSuccess ? WINO_OK : WINO_E_HIP;
   }
+  if (stages == WINO_STAGE_ALL && fused_fwd_f32_supported(g))
+    return launch_fused_fwd_f32(g, bt, at, x_dev, U_dev, y_dev, hs) == hipSuccess ? WINO_OK
+                                                                                  : WINO_E_HIP;
   if (s_in && (input_exact_preferred(g, bt, x_dev)
                    ? launch_input_exact(g, bt, x_dev, V, s.r_v, s.qmax, hs)
                    : launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs)) != hipSuccess)

@@ -31,6 +31,7 @@
 //   4. barrier; wave w: one MFMA per position against U[p][16 k of w][64 c].
 #include <string.h>
 
+#include "fastdiv.h"
 #include "input_stage.h"
 #include "output_stage.h"
 
@@ -76,22 +77,14 @@ struct KronW { uint32_t v[3 * 64 * 4]; };
 
 struct __attribute__((packed, aligned(4))) U64A4 { uint32_t lo, hi; };   // 8 bytes, dword aligned
 
-// Launch plan computed by the host.  The reciprocals turn the kernel's few integer
-// divisions into one multiply-high each: inv(d) = ceil(2^32 / d) (0 stands for d == 1),
-// exact whenever numerator * d < 2^32, which the host checks for every use.
+// Launch plan computed by the host.  The reciprocals (fastdiv.h) turn the kernel's few
+// integer divisions into one multiply-high each.
 struct XPlan {
   int RB, TWB;               // tile rows and tiles per row of a workgroup (RB * TWB <= 16)
   uint32_t inv_twb;          // numerators < 16
   uint32_t inv_strip, inv_wq;   // numerators < 256
   uint32_t inv_th;           // numerators < N * TH
 };
-
-__host__ __device__ inline uint32_t make_inv(uint32_t d) {
-  return d <= 1 ? 0u : (uint32_t)((0x100000000ull + d - 1) / d);
-}
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t inv) {
-  return inv ? __umulhi(n, inv) : n;
-}
 
 // kLoad: 0 = byte loads (W < 4), 1 = one dword per lane at any byte address,
 // 2 = 8 bytes per lane from a dword-aligned address (W % 4 == 0, W >= 8, x aligned).

@@ -53,6 +53,10 @@ bool fused_fwd_supported(const Geom& g);
 hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                             const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
                             hipStream_t s);
+// Whole fp32 forward in one kernel; only where supported.
+bool fused_fwd_f32_supported(const Geom& g);
+hipError_t launch_fused_fwd_f32(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                                const void* U, void* y, hipStream_t s);
 // The same for F(4x4,3x3) with an exact (dyadic) B^T: input transform on the matrix cores.
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt);
 // The input stage alone with the same exact transform (any number of output channels).
