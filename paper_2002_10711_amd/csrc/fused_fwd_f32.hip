@@ -3,21 +3,25 @@
 // per-position GEMM over the input channels on v_mfma_f32_16x16x4_f32, output transform
 // A^T M A, NCHW store.  V and M never go to memory.
 //
-// Workgroup = 256 threads = 16 tiles x (4 waves x 16 output channels).  For every block of
-// 16 input channels:
-//   1. the input rows of the 16 tiles are staged in LDS as floats, Xs[channel][row][col],
-//      with coalesced loads along the image rows (zero outside the image);
-//   2. thread (tile, channel) takes its n x n patch to registers, transforms it with the
-//      pinned fmaf chains and writes V to LDS as Vl[p][tile][16 channels] -- a lane of the
-//      MFMA then reads four consecutive channels (16 bytes) and feeds them to four MFMAs;
-//      Vl reuses the staging area (every patch is in registers before anyone writes);
-//   3. wave w multiplies: per position four MFMAs with U[p][16 k of w][4 x 4 channels] as
-//      the "A" operand, streamed from global memory / L2 through a register ring.
-// Whatever order the instruction gives the four reduction elements of a lane group, it is
-// the same for both operands.  After the last block a lane holds M[., tile, 4 consecutive k]
-// and finishes with the lane-local output transform.
-//
-// The matrix pipe bounds this kernel: fp32 MFMA peak is 1/32 of the int8 one.
+// The fp32 matrix pipe is slow (1/32 of the int8 rate) and every wavefront streams its
+// own slice of U from L2 once per 16 tiles (8 flop per operand byte), so the MFMAs and
+// their operand stream bound this kernel and everything else is arranged to run beside them.  A workgroup (16 tiles x 64 output
+// channels) has EIGHT wavefronts in two roles, one of each per SIMD:
+//   * wavefronts 0-3, "consumers": wave w owns output channels 16 w .. 16 w + 15; for every
+//     block of 16 input channels and every position, four MFMAs with U[p][k][4 x 4
+//     channels] (streamed from global memory / L2 through a register ring) as the "A"
+//     operand and V (from LDS) as the "B" operand.  After the last block a lane holds
+//     M[., tile, 4 consecutive k] and finishes with the lane-local output transform.
+//   * wavefronts 4-7, "producers": while block s is multiplied they prepare block s + 1:
+//     the input rows of the 16 tiles, staged in LDS as Xs[channel][row][col] with coalesced
+//     loads along the image rows (issued a whole block ahead), then thread (tile, channel)
+//     transforms its n x n patch with the pinned fmaf chains and writes it to the other
+//     half of the double-buffered Vl[2][p][tile][16 channels].
+// Both roles meet at two barriers per block (the consumers' first one sits a third of the
+// way into their MFMA loop): every wavefront executes exactly 3 + 2 * (number of blocks)
+// barriers, whatever its role.  A lane of the MFMA reads four consecutive channels
+// (16 bytes) of V and of U and feeds them to four MFMAs: whatever order the instruction
+// gives the four reduction elements of a lane group, it is the same for both operands.
 #include "fastdiv.h"
 #include "output_stage.h"
 
@@ -25,8 +29,8 @@
 // Development build only: shader-clock timestamps per wavefront and phase.
 __device__ unsigned long long wino_phase_ts_f32[4096 * 16];
 #define WINO_TSF(slot)                                                                    \
-  if ((threadIdx.x & 63) == 0 && blockIdx.y == 0 && blockIdx.z == 0 && blockIdx.x < 1024)   \
-    wino_phase_ts_f32[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + (slot)] = __builtin_amdgcn_s_memtime()
+  if ((threadIdx.x & 63) == 0 && blockIdx.y == 0 && blockIdx.z == 0 && blockIdx.x < 512)    \
+    wino_phase_ts_f32[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (slot)] = __builtin_amdgcn_s_memtime()
 extern "C" int wino_debug_read_phases_f32(unsigned long long* host, size_t count) {
   return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(wino_phase_ts_f32), count * sizeof(unsigned long long));
 }
@@ -46,24 +50,35 @@ struct FPlan {
   uint32_t inv_twb, inv_wc, inv_rows, inv_th;
 };
 
-template <int M, bool kSparseB, bool kSparseA>
-__global__ __launch_bounds__(256) void fused_fwd_f32_kernel(const float* __restrict__ x,
+// Workgroup barrier that orders LDS traffic only: the writers' LDS stores are complete
+// before anyone passes, while global loads stay in flight across it (a full
+// __syncthreads() would also wait for them, which is the latency this kernel hides).
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// kSparse: B^T and A^T both have the Cook-Toom zero pattern.
+// kFast: whole tiles, K % 4 == 0, y 16-byte aligned (vector stores, no guards).
+// kIters: staged elements per producer thread and block (>= ceil(total / 256)).
+template <int M, bool kSparse, bool kFast, int kIters>
+__global__ __launch_bounds__(512) void fused_fwd_f32_kernel(const float* __restrict__ x,
                                                             const float* __restrict__ U,
                                                             float* __restrict__ y, Geom g, FPlan pl,
                                                             MatBT bt, MatAT at) {
   constexpr int n = M + 2, P = n * n, CB = 16;
-  constexpr int kMaxIters = 32;                        // staged elements per thread and block
   extern __shared__ __attribute__((aligned(16))) float ldsf[];
-  float* Xs = ldsf;
-  float* Vl = ldsf;                                    // aliases Xs
-  const int area = CB * pl.plane > P * 256 ? CB * pl.plane : P * 256;
-  // ldsf[area .. area + 3]: 4 floats nobody reads (target of surplus staging lanes)
-  int* rowinfo = (int*)(ldsf + area + 4);              // [rows]
+  float* Vl = ldsf;                                    // [2][P][16 tiles][16 channels]
+  float* Xs = ldsf + 2 * P * 256;                      // [16 channels][plane]
+  const int dumpi = 2 * P * 256 + CB * pl.plane;       // 4 floats nobody reads
+  int* rowinfo = (int*)(ldsf + dumpi + 4);             // [rows]
   const int RB = pl.RB, TWB = pl.TWB, Wc = pl.Wc, rows = pl.rows, plane = pl.plane;
   const int r0 = blockIdx.x * RB, tw0 = blockIdx.y * TWB, kb = blockIdx.z * 64;
   const int R = g.N * g.TH, HW = g.H * g.W;
-  const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nblk = g.Cp / CB;
 
   // Row table: element offset of (image, channel 0, row h, column 0) for every staged row
   // of the workgroup, or -1 for rows outside the image / beyond the last tile row.
@@ -75,130 +90,194 @@ __global__ __launch_bounds__(256) void fused_fwd_f32_kernel(const float* __restr
     const int h = th * M - g.pad + j;
     rowinfo[tid] = (rr < R && h >= 0 && h < g.H) ? (img * g.C * g.H + h) * g.W : -1;
   }
+  lds_barrier();                                       // barrier 0: row table complete
 
-  // phase-2 role: tile tl of the workgroup, channel c2 of the block
-  const int c2 = tid & 15, tl = tid >> 4;
-  const int rs2 = (int)fast_div(tl, pl.inv_twb), twl2 = tl - rs2 * TWB;
-  const float* patch = Xs + c2 * plane + ((rs2 < RB ? rs2 : 0) * n) * Wc + twl2 * M;
+  if (wave >= 4) {
+    // ------------------------------------------------------------------ producers
+    const int ptid = tid - 256;
+    const int c2 = ptid & 15, tl = ptid >> 4;          // transform role: (tile, channel)
+    const int rs2 = (int)fast_div(tl, pl.inv_twb), twl2 = tl - rs2 * TWB;
+    const float* patch = Xs + c2 * plane + ((rs2 < RB ? rs2 : 0) * n) * Wc + twl2 * M;
+    // Staging plan of this thread, the same for every channel block: element
+    // e = ptid + 256 i of the block's [16 channels][rows][Wc] array -> element offset in x
+    // relative to the block's first channel, LDS index, channel.  Elements outside the
+    // image are zero in every block: their Xs slots are cleared once, here, and from then
+    // on such lanes load x[0] (any valid address) and store to the dump area, so the
+    // per-block work is one address add, one load and one LDS store per element, with no
+    // decisions.  The loads of block 0 go out as soon as their offsets are known.
+    const int wbase = tw0 * M - g.pad;
+    const bool full_c = g.C % CB == 0;                 // no ragged last channel block
+    int goff[kIters];
+    uint32_t lpk[kIters];
+    float xv[kIters];
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) {
+      const int e = ptid + i * 256;
+      const int ec = e < pl.total ? e : pl.total - 1;
+      const int rowidx = (int)fast_div(ec, pl.inv_wc), col = ec - rowidx * Wc;
+      const int c = (int)fast_div(rowidx, pl.inv_rows), rj = rowidx - c * rows;
+      const int info = rowinfo[rj];
+      const int w = wbase + col;
+      const bool inside = info >= 0 && w >= 0 && w < g.W;
+      const bool ok = e < pl.total && inside && c < g.C;          // (c < C: block 0)
+      const int xs = 2 * P * 256 + c * plane + rj * Wc + col;
+      goff[i] = ok ? info + c * HW + w : 0;
+      xv[i] = x[goff[i]];
+      if (e < pl.total && !ok) ldsf[xs] = 0.0f;
+      lpk[i] = ((uint32_t)c << 16) | (uint32_t)(ok ? xs : dumpi + (ptid & 3));
+    }
+    // every block but a ragged last one: channel c of the block exists
+    auto issue_loads = [&](int cbase) {
+      const float* xb = x + (size_t)cbase * HW;
+#pragma unroll
+      for (int i = 0; i < kIters; ++i) xv[i] = xb[goff[i]];
+    };
+    // ragged last block: channels beyond C read x[0] and are stored as zero
+    auto issue_loads_ragged = [&](int cbase) {
+      const float* xb = x + (size_t)cbase * HW;
+#pragma unroll
+      for (int i = 0; i < kIters; ++i) {
+        const bool ok = cbase + (int)(lpk[i] >> 16) < g.C;
+        xv[i] = ok ? xb[goff[i]] : 0.0f;
+      }
+    };
+    for (int nb = 0; nb < nblk; ++nb) {                // prepares block nb during step nb - 1
+      const int cbase = nb * CB;
+      if (nb == 1) WINO_TSF(6);
+      // phase A: X of block nb into Xs (last read before the previous step's barrier 2)
+#pragma unroll
+      for (int i = 0; i < kIters; ++i) ldsf[lpk[i] & 0xffffu] = xv[i];
+      if (nb == 1) WINO_TSF(7);
+      lds_barrier();                                   // barrier 1 of step nb - 1
+      if (nb == 1) WINO_TSF(8);
+      // phase B: patch to registers, loads of the block after, transform, V to
+      // Vl[nb & 1] (last read by the consumers before the previous step's barrier 2)
+      float d[n][n];
+#pragma unroll
+      for (int j = 0; j < n; ++j)
+#pragma unroll
+        for (int l = 0; l < n; ++l) d[j][l] = patch[j * Wc + l];
+      if (nb == 1) WINO_TSF(9);
+      if (nb + 1 < nblk) {
+        if (full_c || nb + 2 < nblk) issue_loads(cbase + CB);
+        else issue_loads_ragged(cbase + CB);
+      }
+      if (nb == 1) WINO_TSF(10);
+      {
+        float Vt[n][n];
+        transform_patch<M, kSparse>(d, bt, Vt);
+        float* vdst = Vl + (nb & 1) * P * 256 + tl * 16 + c2;
+#pragma unroll
+        for (int p = 0; p < P; ++p) vdst[p * 256] = Vt[p / n][p % n];
+      }
+      if (nb == 1) WINO_TSF(11);
+      lds_barrier();                                   // barrier 2 of step nb - 1
+      if (nb == 1) WINO_TSF(12);
+    }
+    // the consumers' last step: nothing left to prepare
+    lds_barrier();
+    lds_barrier();
+    return;
+  }
 
-  // MFMA role: "A" rows = output channels kb + wave*16 + r, 4 floats at channel grp*4
-  const uint32_t uoff = ((uint32_t)(kb + wave * 16 + r) * (uint32_t)g.Cp + (uint32_t)grp * 4u) * 4u;
+  // -------------------------------------------------------------------- consumers
+  const int lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  // "A" rows = output channels kb + wave*16 + r, 4 floats at channel grp*4: in the blocked
+  // layout of the fp32 weights (u_f32_index) the wavefront's 16 x 16 block of a channel
+  // block is 1 KB of consecutive bytes, this lane's piece at (grp*16 + r) * 16
+  const uint32_t uoff = (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)(g.Cp >> 4) * 1024u +
+                        (uint32_t)(grp * 16 + r) * 16u;
   const size_t up = (size_t)g.Kp * g.Cp * 4;
-  const char* Ub = (const char*)U;
-
   v4f acc[P];
 #pragma unroll
   for (int p = 0; p < P; ++p) acc[p] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
-  // Staging plan of this thread, the same for every channel block: element e = tid + 256 i
-  // of the block's [16 channels][rows][Wc] array -> element offset in x relative to the
-  // block's first channel (-1: outside the image) and (channel << 16 | LDS index).
-  const int wbase = tw0 * M - g.pad;
-  int goff[kMaxIters];
-  uint32_t lpk[kMaxIters];
-  __syncthreads();                                     // row table complete
+  // U through a register ring kDepth positions deep that runs on across the channel
+  // blocks (uniform running byte offset, one position per step; the empty statement keeps
+  // it in scalar registers instead of one precomputed 64-bit base per position)
+  constexpr int kDepth = M == 4 ? 12 : 8;
+  static_assert(P % kDepth == 0, "ring depth must divide the number of positions");
+  v4f bufU[kDepth];
+  const char* Ub = (const char*)U;
+  size_t ublk = 0;                                     // byte offset of position 0, current block
+  size_t uld = 0;
 #pragma unroll
-  for (int i = 0; i < kMaxIters; ++i) {
-    const int e = tid + i * 256;
-    const int ec = e < pl.total ? e : pl.total - 1;
-    const int rowidx = (int)fast_div(ec, pl.inv_wc), col = ec - rowidx * Wc;
-    const int c = (int)fast_div(rowidx, pl.inv_rows), rj = rowidx - c * rows;
-    const int info = rowinfo[rj];
-    const int w = wbase + col;
-    const bool ok = e < pl.total && info >= 0 && w >= 0 && w < g.W;
-    goff[i] = ok ? info + c * HW + w : -1;
-    lpk[i] = ((uint32_t)c << 16) | (uint32_t)(e < pl.total ? c * plane + rj * Wc + col : area + (tid & 3));
+  for (int p = 0; p < kDepth; ++p) {
+    bufU[p] = *(const v4f*)(Ub + uld + uoff);
+    uld += up;
+    asm volatile("" : "+s"(uld));
   }
-  // The loads of a block are all issued at once, one block ahead of its use: they are in
-  // flight during the transform and the MFMAs of the block before.
-  // (validity travels as one bit per element in a vector register: 32 lane masks kept
-  // alive across the load latency would not fit the scalar registers)
-  float xv[kMaxIters];
-  uint32_t okbits = 0u;
-  auto issue_loads = [&](int cbase) {
-    okbits = 0u;
-#pragma unroll
-    for (int i = 0; i < kMaxIters; ++i) {
-      if (i < pl.iters) {
-        const bool ok = goff[i] >= 0 && cbase + (int)(lpk[i] >> 16) < g.C;
-        xv[i] = x[ok ? goff[i] + cbase * HW : 0];
-        okbits |= ok ? (1u << i) : 0u;
-      }
-    }
-  };
   WINO_TSF(0);
-  issue_loads(0);
+  lds_barrier();                                       // step -1: the producers prepare block 0
+  lds_barrier();
   WINO_TSF(1);
 
-  const int nblk = g.Cp / CB;
-  for (int cb = 0; cb < nblk; ++cb) {
-    if (cb) __syncthreads();                           // previous block's Vl consumed
-    if (cb == 1) WINO_TSF(2);
-    const int cbase = cb * CB;
+  constexpr int kVRing = 4;                            // V operands: LDS reads 4 positions ahead
+  static_assert(P % kVRing == 0 && P % 2 == 0, "ring depths must divide the number of positions");
+  constexpr int kSplit = (P / 3) & ~1;                 // barrier 1 after this many positions
+  for (int s = 0; s < nblk; ++s) {
+    const float* vb = Vl + (s & 1) * P * 256 + r * 16 + grp * 4;
+    v4f bufV[kVRing];
 #pragma unroll
-    for (int i = 0; i < kMaxIters; ++i)
-      if (i < pl.iters) ldsf[lpk[i] & 0xffffu] = (okbits & (1u << i)) ? xv[i] : 0.0f;
-    __syncthreads();
-    if (cb == 1) WINO_TSF(3);
-    float d[n][n];
+    for (int p = 0; p < kVRing; ++p) bufV[p] = *(const v4f*)(vb + p * 256);
+    __builtin_amdgcn_sched_group_barrier(0x100, kVRing, 0);
 #pragma unroll
-    for (int j = 0; j < n; ++j)
+    for (int p0 = 0; p0 < P; p0 += 2) {
+      if (p0 == kSplit) {
+        if (s == 0) WINO_TSF(13);
+        lds_barrier();                                 // barrier 1 of step s
+        if (s == 0) WINO_TSF(14);
+      }
+      v4f au[2], bv[2];
 #pragma unroll
-      for (int l = 0; l < n; ++l) d[j][l] = patch[j * Wc + l];
-    __syncthreads();                                   // staging area is free: Vl may overwrite it
-    if (cb == 1) WINO_TSF(4);
-    if (cb + 1 < nblk) issue_loads(cbase + CB);
-    if (cb == 1) WINO_TSF(5);
-    {
-      float Vt[n][n];
-      transform_patch<M, kSparseB>(d, bt, Vt);
-#pragma unroll
-      for (int p = 0; p < P; ++p) Vl[(p * 16 + tl) * 16 + c2] = Vt[p / n][p % n];
-    }
-    __syncthreads();
-    if (cb == 1) WINO_TSF(6);
-
-    // four MFMAs per position; U through a register ring kDepth positions deep
-    constexpr int kDepth = M == 4 ? 9 : 8;
-    static_assert(P % kDepth == 0, "ring depth must divide the number of positions");
-    const uint32_t ub = uoff + (uint32_t)cbase * 4u;
-    v4f bufU[kDepth];
-    // (uniform running pointer, one position per step; the empty statement keeps it in
-    // scalar registers instead of one precomputed 64-bit base per position)
-    const char* uld = Ub;
-#pragma unroll
-    for (int p = 0; p < kDepth; ++p) {
-      bufU[p] = *(const v4f*)(uld + ub);
-      uld += up;
-      asm volatile("" : "+s"(uld));
-    }
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-      const v4f au = bufU[p % kDepth];
-      if (p + kDepth < P) {
-        bufU[p % kDepth] = *(const v4f*)(uld + ub);
-        uld += up;
+      for (int q = 0; q < 2; ++q) {
+        const int p = p0 + q;
+        au[q] = bufU[p % kDepth];
+        bv[q] = bufV[p % kVRing];
+        if (p + kVRing < P) bufV[p % kVRing] = *(const v4f*)(vb + (p + kVRing) * 256);
+        // refill the U slot with position p + kDepth (of the next block, if any, once the
+        // positions of this one are all on their way)
+        if (p + kDepth < P || s + 1 < nblk) bufU[p % kDepth] = *(const v4f*)(Ub + uld + uoff);
+        if (p + kDepth + 1 == P) {
+          ublk += 1024;                                // next 16-channel block of U
+          uld = ublk;
+        } else {
+          uld += up;
+        }
         asm volatile("" : "+s"(uld));
       }
-      const v4f bv = *(const v4f*)(Vl + (p * 16 + r) * 16 + grp * 4);
-      acc[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(au.x, bv.x, acc[p], 0, 0, 0);
-      acc[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(au.y, bv.y, acc[p], 0, 0, 0);
-      acc[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(au.z, bv.z, acc[p], 0, 0, 0);
-      acc[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(au.w, bv.w, acc[p], 0, 0, 0);
+      // two positions interleaved: consecutive MFMAs never wait for each other's result
+      acc[p0] = __builtin_amdgcn_mfma_f32_16x16x4f32(au[0].x, bv[0].x, acc[p0], 0, 0, 0);
+      acc[p0 + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(au[1].x, bv[1].x, acc[p0 + 1], 0, 0, 0);
+      acc[p0] = __builtin_amdgcn_mfma_f32_16x16x4f32(au[0].y, bv[0].y, acc[p0], 0, 0, 0);
+      acc[p0 + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(au[1].y, bv[1].y, acc[p0 + 1], 0, 0, 0);
+      acc[p0] = __builtin_amdgcn_mfma_f32_16x16x4f32(au[0].z, bv[0].z, acc[p0], 0, 0, 0);
+      acc[p0 + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(au[1].z, bv[1].z, acc[p0 + 1], 0, 0, 0);
+      acc[p0] = __builtin_amdgcn_mfma_f32_16x16x4f32(au[0].w, bv[0].w, acc[p0], 0, 0, 0);
+      acc[p0 + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(au[1].w, bv[1].w, acc[p0 + 1], 0, 0, 0);
+      // Scheduling groups, in this order: the two LDS reads and the two U loads issued
+      // above (operands of later positions), then this pair's eight MFMAs.  Left to
+      // itself the scheduler sinks every operand load to just before its use, which
+      // undoes the rings and leaves the matrix pipe idle for each load's latency.
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
-    if (cb == 1) WINO_TSF(7);
+    if (s == 0) WINO_TSF(15);
+    lds_barrier();                                     // barrier 2 of step s
+    if (s == 0) WINO_TSF(2);
+    if (s == 1) WINO_TSF(3);
   }
+  WINO_TSF(4);
 
-  WINO_TSF(8);
   // lane holds M[., tile r, k] for k = kb + wave*16 + grp*4 + rr
   const int rs = (int)fast_div(r, pl.inv_twb), twl = r - rs * TWB;
-  const int rr_ = r0 + rs, tw = tw0 + twl;
-  if (rs < RB && rr_ < R && tw < g.TW) {
+  const int rr_ = r0 + rs, tw = tw0 + twl, k0 = kb + wave * 16 + grp * 4;
+  if (rs < RB && rr_ < R && tw < g.TW && k0 < g.K) {
     const int img = (int)fast_div(rr_, pl.inv_th), th = rr_ - img * g.TH;
-    finish_lane<M, false, kSparseA, false>(g, at, acc, y, img, th, tw, kb + wave * 16 + grp * 4,
-                                           0.0f, 0.0f, 0.0f);
+    finish_lane<M, false, kSparse, false, kFast>(g, at, acc, y, img, th, tw, k0, 0.0f, 0.0f, 0.0f);
   }
-  WINO_TSF(9);
+  WINO_TSF(5);
 }
 
 // Launch plan and dynamic LDS size; false if the shape does not fit the kernel's limits.
@@ -218,13 +297,28 @@ bool make_fplan(const Geom& g, FPlan* plp, size_t* lds_bytes, int* nrb, int* ntw
   pl.inv_wc = make_inv(pl.Wc);
   pl.inv_rows = make_inv(pl.rows);
   pl.inv_th = make_inv(g.TH);
-  const size_t area = (size_t)(16 * pl.plane > P * 256 ? 16 * pl.plane : P * 256);
-  *lds_bytes = (area + 4 + pl.rows) * 4;
+  const size_t lds_floats = (size_t)2 * P * 256 + (size_t)16 * pl.plane + 4 + pl.rows;
+  *lds_bytes = lds_floats * 4;
   *ntwb = (g.TW + pl.TWB - 1) / pl.TWB;
   *nrb = (R + pl.RB - 1) / pl.RB;
-  // 32 = kMaxIters of the kernel; 65536 floats: the packed LDS index has 16 bits
-  return *lds_bytes <= 65536 && *ntwb <= 65535 && g.Kp / 64 <= 65535 && pl.rows <= 256 &&
-         pl.iters <= 32;
+  // 32 = kMaxIters of the kernel; the packed LDS index has 16 bits; 160 KB of LDS per
+  // workgroup on gfx950
+  return lds_floats <= 65536 && *lds_bytes <= 160 * 1024 && *ntwb <= 65535 &&
+         g.Kp / 64 <= 65535 && pl.rows <= 256 && pl.iters <= 32;
+}
+
+template <int M, bool kSparse, bool kFast, int kIters>
+hipError_t launch_k(const Geom& g, const FPlan& pl, size_t lb, dim3 grid, const MatBT& bt,
+                    const MatAT& at, const float* x, const float* U, float* y, hipStream_t s) {
+  if (lb > 65536) {
+    // more dynamic LDS than the default limit: raise it for this kernel (cheap, idempotent)
+    const hipError_t e =
+        hipFuncSetAttribute((const void*)fused_fwd_f32_kernel<M, kSparse, kFast, kIters>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lb);
+    if (e != hipSuccess) return e;
+  }
+  fused_fwd_f32_kernel<M, kSparse, kFast, kIters><<<grid, 512, lb, s>>>(x, U, y, g, pl, bt, at);
+  return hipGetLastError();
 }
 
 template <int M>
@@ -235,25 +329,38 @@ hipError_t launch_m(const Geom& g, const MatBT& bt, const MatAT& at, const float
   int nrb, ntwb;
   if (!make_fplan(g, &pl, &lb, &nrb, &ntwb)) return hipErrorInvalidValue;
   dim3 grid((unsigned)nrb, (unsigned)ntwb, (unsigned)(g.Kp / 64));
-  const bool sb = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt);
-  const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
-#define WINO_LAUNCH_F32(SB, SA) \
-  fused_fwd_f32_kernel<M, SB, SA><<<grid, 256, lb, s>>>(x, U, y, g, pl, bt, at)
-  if (sb && sa) WINO_LAUNCH_F32(true, true);
-  else if (sb) WINO_LAUNCH_F32(true, false);
-  else if (sa) WINO_LAUNCH_F32(false, true);
-  else WINO_LAUNCH_F32(false, false);
+  const bool sparse = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt) &&
+                      fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && ((uintptr_t)y & 15) == 0;
+  // The common case (Cook-Toom pattern, whole tiles) gets the staging loop sized to the
+  // shape, in steps of 4 elements per thread; everything else the full 32.
+#define WINO_LAUNCH_F32(SP, FA, IT) \
+  return launch_k<M, SP, FA, IT>(g, pl, lb, grid, bt, at, x, U, y, s)
+  if (sparse && fast) {
+    switch ((pl.iters + 3) / 4) {
+      case 1: WINO_LAUNCH_F32(true, true, 4);
+      case 2: WINO_LAUNCH_F32(true, true, 8);
+      case 3: WINO_LAUNCH_F32(true, true, 12);
+      case 4: WINO_LAUNCH_F32(true, true, 16);
+      case 5: WINO_LAUNCH_F32(true, true, 20);
+      case 6: WINO_LAUNCH_F32(true, true, 24);
+      case 7: WINO_LAUNCH_F32(true, true, 28);
+      default: WINO_LAUNCH_F32(true, true, 32);
+    }
+  }
+  if (sparse) WINO_LAUNCH_F32(true, false, 32);
+  if (fast) WINO_LAUNCH_F32(false, true, 32);
+  WINO_LAUNCH_F32(false, false, 32);
 #undef WINO_LAUNCH_F32
-  return hipGetLastError();
 }
 
 }  // namespace
 
 bool fused_fwd_f32_supported(const Geom& g) {
-  // fp32, F2 or F4 (the 8 x 8 accumulator sets of F6 leave no room for the transforms), few
-  // enough output-channel blocks that repeating the input transform per block is cheaper
-  // than a round trip of V through memory; 32-bit element offsets into X and U, and exact
-  // reciprocals (fastdiv.h) for the tile row index.
+  // fp32, F2 or F4 (the 8 x 8 accumulator sets of F6 leave no room beside the operand
+  // rings), few enough output-channel blocks that repeating the input transform per block
+  // is cheaper than a round trip of V through memory; 32-bit element offsets into X and
+  // byte offsets into U, and exact reciprocals (fastdiv.h) for the tile row index.
   const unsigned long long R = (unsigned long long)g.N * g.TH;
   FPlan pl;
   size_t lb;

@@ -32,7 +32,11 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 template <bool I8> struct AccT { typedef v4i type; };
 template <> struct AccT<false> { typedef v4f type; };
 
-template <int WT, int WK, bool I8>
+// kBlockedB: B is in the fp32 block layout of u_f32_index (1 KB blocks of 16 rows x 64
+// bytes, piece (16-byte segment seg, row kr) at piece index seg*16 + kr): a thread's
+// pieces are then taken in block order, so the global reads stay contiguous, and are put
+// into the same LDS places as in the plain layout.
+template <int WT, int WK, bool I8, bool kBlockedB = false>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(const char* __restrict__ A,
                                                          const char* __restrict__ B,
                                                          char* __restrict__ M, int Tp, int Kp,
@@ -48,6 +52,19 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const char* __restrict_
   const char* Ag = A + ((size_t)p * Tp + tb) * row_bytes;
   const char* Bg = B + ((size_t)p * Kp + kb) * row_bytes;
   const int nstep = row_bytes >> 6;
+  // piece q of the block's B tile at reduction step st: where it comes from, where it goes
+  auto b_src = [&](int q, int st) -> const char* {
+    if constexpr (kBlockedB)
+      return Bg + ((size_t)(q >> 6) * nstep + st) * 1024 + (q & 63) * 16;   // block q/64 of 16 rows
+    else
+      return Bg + (size_t)(q >> 2) * row_bytes + (size_t)st * 64 + (q & 3) * 16;
+  };
+  auto b_dst = [&](int q) -> int {
+    if constexpr (kBlockedB)
+      return (((q >> 6) * 16 + (q & 15)) * 4 + ((q >> 4) & 3)) * 16;        // row, segment
+    else
+      return q * 16;
+  };
 
   acc_t acc[WT][WK];
 #pragma unroll
@@ -63,14 +80,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const char* __restrict_
     ra[u] = *(const v4i*)(Ag + (size_t)(q >> 2) * row_bytes + (q & 3) * 16);
   }
 #pragma unroll
-  for (int u = 0; u < LB; ++u) {
-    const int q = tid + u * 256;
-    rb[u] = *(const v4i*)(Bg + (size_t)(q >> 2) * row_bytes + (q & 3) * 16);
-  }
+  for (int u = 0; u < LB; ++u) rb[u] = *(const v4i*)b_src(tid + u * 256, 0);
 #pragma unroll
   for (int u = 0; u < LA; ++u) *(v4i*)(As[0] + (tid + u * 256) * 16) = ra[u];
 #pragma unroll
-  for (int u = 0; u < LB; ++u) *(v4i*)(Bs[0] + (tid + u * 256) * 16) = rb[u];
+  for (int u = 0; u < LB; ++u) *(v4i*)(Bs[0] + b_dst(tid + u * 256)) = rb[u];
   __syncthreads();
 
   for (int st = 0; st < nstep; ++st) {
@@ -84,10 +98,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const char* __restrict_
         ra[u] = *(const v4i*)(Ag + (size_t)(q >> 2) * row_bytes + co + (q & 3) * 16);
       }
 #pragma unroll
-      for (int u = 0; u < LB; ++u) {
-        const int q = tid + u * 256;
-        rb[u] = *(const v4i*)(Bg + (size_t)(q >> 2) * row_bytes + co + (q & 3) * 16);
-      }
+      for (int u = 0; u < LB; ++u) rb[u] = *(const v4i*)b_src(tid + u * 256, st + 1);
     }
     acc_t va[WT], vb[WK];
 #pragma unroll
@@ -113,7 +124,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const char* __restrict_
 #pragma unroll
       for (int u = 0; u < LA; ++u) *(v4i*)(As[cur ^ 1] + (tid + u * 256) * 16) = ra[u];
 #pragma unroll
-      for (int u = 0; u < LB; ++u) *(v4i*)(Bs[cur ^ 1] + (tid + u * 256) * 16) = rb[u];
+      for (int u = 0; u < LB; ++u) *(v4i*)(Bs[cur ^ 1] + b_dst(tid + u * 256)) = rb[u];
     }
     __syncthreads();
   }
@@ -130,10 +141,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const char* __restrict_
 
 }  // namespace
 
-hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, const void* A, const void* B, void* M,
-                       hipStream_t s) {
+hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, int b_blocked, const void* A,
+                       const void* B, void* M, hipStream_t s) {
   // Tp, Kp are multiples of 64; Cp of 64 (int8) or 16 (float): the host API rounds them.
-  if (Tp % 64 || Kp % 64 || Cp % (i8 ? 64 : 16) || P < 1 || P > 65535) return hipErrorInvalidValue;
+  if (Tp % 64 || Kp % 64 || Cp % (i8 ? 64 : 16) || P < 1 || P > 65535 || (i8 && b_blocked))
+    return hipErrorInvalidValue;
   const int row_bytes = Cp * (i8 ? 1 : 4);
   const char* a = (const char*)A;
   const char* b = (const char*)B;
@@ -145,6 +157,8 @@ hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, const void* A, con
     dim3 grid(Tp / 128, Kp / 128, P);
     if (i8)
       gemm_tiled_kernel<4, 4, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
+    else if (b_blocked)
+      gemm_tiled_kernel<4, 4, false, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
     else
       gemm_tiled_kernel<4, 4, false><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
   } else {
@@ -152,6 +166,8 @@ hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, const void* A, con
     dim3 grid(Tp / 64, Kp / 64, P);
     if (i8)
       gemm_tiled_kernel<2, 2, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
+    else if (b_blocked)
+      gemm_tiled_kernel<2, 2, false, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
     else
       gemm_tiled_kernel<2, 2, false><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
   }

@@ -42,7 +42,12 @@ __global__ __launch_bounds__(256) void gemm_out_kernel(Geom g, MatAT at,
   // which would not fit next to n*n accumulator sets.  The host checks the 32-bit range.
   const size_t vp = (size_t)g.Tp * g.Cp * ESZ, up = (size_t)g.Kp * g.Cp * ESZ;
   const uint32_t voff = (uint32_t)t * (uint32_t)(g.Cp * ESZ) + (uint32_t)grp * 16u;
-  const uint32_t uoff = (uint32_t)krow * (uint32_t)(g.Cp * ESZ) + (uint32_t)grp * 16u;
+  // (fp32 weights are in the blocked layout of u_f32_index: the wavefront's 16 channels x
+  // 16 input channels of a chunk are 1 KB of consecutive bytes, lane piece grp*16 + r)
+  const uint32_t uoff =
+      I8 ? (uint32_t)krow * (uint32_t)(g.Cp * ESZ) + (uint32_t)grp * 16u
+         : (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)(g.Cp >> 4) * 1024u + (uint32_t)(grp * 16 + r) * 16u;
+  constexpr int kUChunk = I8 ? 64 : 1024;             // bytes from one chunk of U to the next
   const char* vrow = (const char*)Vv;
   const char* urow = (const char*)Uv;
   const int nchunk = g.Cp / CHUNK;
@@ -60,16 +65,15 @@ __global__ __launch_bounds__(256) void gemm_out_kernel(Geom g, MatAT at,
     bufV[p] = *(const op_t*)(vrow + p * vp + voff);
     bufU[p] = *(const op_t*)(urow + p * up + uoff);
   }
+  static_assert(CHUNK * ESZ == 64, "V advances 64 bytes per chunk");
   acc_t acc[P];
 #pragma unroll
   for (int p = 0; p < P; ++p) acc[p] = acc_t{0, 0, 0, 0};
-  // Running (uniform) load pointers, advanced by one position per step and wrapped to
-  // the next channel chunk after the last position: a loop-carried pair of scalar
-  // registers each, instead of one precomputed base per position.
-  const char* vchunk = vrow;
-  const char* uchunk = urow;
-  const char* vld = vrow + kDepth * vp;
-  const char* uld = urow + kDepth * up;
+  // Running (uniform) byte offsets of the next loads, advanced by one position per step
+  // and wrapped to the next channel chunk after the last position: a loop-carried scalar
+  // each, instead of one precomputed base per position.
+  size_t vchunk = 0, uchunk = 0;
+  size_t vld = kDepth * vp, uld = kDepth * up;
   for (int ch = 0; ch < nchunk; ++ch) {
 #pragma unroll
     for (int p = 0; p < P; ++p) {
@@ -77,19 +81,19 @@ __global__ __launch_bounds__(256) void gemm_out_kernel(Geom g, MatAT at,
       // refill the slot with the operands of step p + kDepth (of the next chunk, if any,
       // once the positions of this one are all on their way)
       if (p + kDepth < P || ch + 1 < nchunk) {
-        bufV[p % kDepth] = *(const op_t*)(vld + voff);
-        bufU[p % kDepth] = *(const op_t*)(uld + uoff);
+        bufV[p % kDepth] = *(const op_t*)(vrow + vld + voff);
+        bufU[p % kDepth] = *(const op_t*)(urow + uld + uoff);
       }
       if (p + kDepth + 1 == P) {
         vchunk += 64;
-        uchunk += 64;
+        uchunk += kUChunk;
         vld = vchunk;
         uld = uchunk;
       } else {
         vld += vp;
         uld += up;
       }
-      // (empty statement: keeps the two pointers in scalar registers as they are; without
+      // (empty statement: keeps the two offsets in scalar registers as they are; without
       // it the optimiser rewrites the chain as one 64-bit vector pointer per position)
       asm volatile("" : "+s"(vld), "+s"(uld));
       if constexpr (I8) {

@@ -17,7 +17,8 @@ template <> struct Acc<false> { typedef v4f type; };
 
 // Stores one m x m output tile of channel k; (h0, w0) is its top-left corner.
 // kFast: the host has checked that m divides Ho and Wo (every tile is whole and every
-// row keeps the alignment of the vector stores), so no per-lane decisions are left.
+// row keeps the alignment of the vector stores; for fp32 also that y itself is 16-byte
+// aligned), so no per-lane decisions are left.
 template <int M, bool I8, bool kFast = false>
 __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv, size_t plane,
                                            int h0, int w0, const float (&Y)[M][M], float r_y,
@@ -62,11 +63,26 @@ __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv,
     }
   } else {
     float* y = (float*)yv + plane;
+    if constexpr (kFast && (M == 2 || M == 4)) {
+      // whole tiles, and the host has checked that y is 16-byte aligned: one vector store
+      // per tile row (rows start at multiples of m floats)
 #pragma unroll
-    for (int a = 0; a < M; ++a)
+      for (int a = 0; a < M; ++a) {
+        float* row = y + (size_t)(h0 + a) * g.Wo + w0;
+        if constexpr (M == 4) {
+          *(v4f*)row = v4f{Y[a][0], Y[a][1], Y[a][2], Y[a][3]};
+        } else {
+          typedef float v2f __attribute__((ext_vector_type(2)));
+          *(v2f*)row = v2f{Y[a][0], Y[a][1]};
+        }
+      }
+    } else {
 #pragma unroll
-      for (int b = 0; b < M; ++b)
-        if (h0 + a < g.Ho && w0 + b < g.Wo) y[(size_t)(h0 + a) * g.Wo + w0 + b] = Y[a][b];
+      for (int a = 0; a < M; ++a)
+#pragma unroll
+        for (int b = 0; b < M; ++b)
+          if (h0 + a < g.Ho && w0 + b < g.Wo) y[(size_t)(h0 + a) * g.Wo + w0 + b] = Y[a][b];
+    }
   }
 }
 

@@ -27,6 +27,17 @@ struct MatAT { float v[48]; };   // m x n, m <= 6
 
 inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
 
+// Private layout of the fp32 transformed weights (the int8 ones are plain U[p][k][c]):
+// [p][Kp/16][Cp/16] blocks of 16 output channels x 16 input channels, each block (1 KB)
+// in the order in which an MFMA wavefront loads it -- the 16-byte piece (channel quad q,
+// output channel k) sits at piece index q*16 + k, which is the lane that needs it.  A
+// wavefront's operand load is then 1 KB of consecutive bytes instead of 16 bytes from
+// each of 64 cache lines.  Element index of U[p][k][c]:
+__host__ __device__ inline size_t u_f32_index(int Kp, int Cp, int p, int k, int c) {
+  const size_t blk = ((size_t)p * (Kp >> 4) + (k >> 4)) * (Cp >> 4) + (c >> 4);
+  return (blk * 64 + (size_t)(((c & 15) >> 2) * 16 + (k & 15))) * 4 + (c & 3);
+}
+
 // Kernel launchers (each enqueues on `s` and returns hipGetLastError()).
 hipError_t launch_input_transform(const Geom& g, const MatBT& bt, const void* x, void* V,
                                   float r_v, float qmax, hipStream_t s);
@@ -34,8 +45,9 @@ hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w
                                    float r_u, float qmax, hipStream_t s);
 // Batched GEMM  M[p][t][k] = sum_c A[p][t][c] * B[p][k][c]; rows padded as above.
 // Used with P = n*n for the Winograd domain and P = 1 for the im2row baseline.
-hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, const void* A, const void* B,
-                       void* M, hipStream_t s);
+// b_blocked: B is in the fp32 block layout of u_f32_index (fp32 only).
+hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, int b_blocked, const void* A,
+                       const void* B, void* M, hipStream_t s);
 hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M, void* y,
                                    float r_m, float r_y, float qmax, hipStream_t s);
 // GEMM and output transform in one kernel (M stays in registers, operands straight
