@@ -194,11 +194,11 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
     if (launch_gemm_out(g, at, V, U_dev, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;
   } else if (s_mm && s_out) {
-    if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, !g.i8, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
+    if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, 1, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
     if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;
   } else if (s_mm) {
-    if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, !g.i8, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
+    if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, 1, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
   } else if (s_out) {
     if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;

@@ -48,8 +48,10 @@ __global__ __launch_bounds__(256) void fused_fwd_i8_kernel(
   const int rs2 = tl / TWB, twl2 = tl - rs2 * TWB;
   const bool has_tile = rs2 < RB;                      // RB * TWB may be less than 16
 
-  // MFMA role: "A" rows = output channels kb + wave*16 + r, 16 bytes at channel grp*16
-  const int8_t* urow = U + ((size_t)(kb + wave * 16 + r) * g.Cp) + grp * 16;
+  // MFMA role: "A" rows = output channels kb + wave*16 + r, 16 bytes at channel grp*16: in
+  // the blocked layout of the weights (u_byte_index) the wavefront's 16 x 64 block of a
+  // channel block is 1 KB of consecutive bytes, this lane's piece at (grp*16 + r) * 16
+  const int8_t* urow = U + (size_t)((kb + wave * 16) >> 4) * (g.Cp >> 6) * 1024 + (grp * 16 + r) * 16;
   const size_t up = (size_t)g.Kp * g.Cp;
 
   v4i acc[P];
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(256) void fused_fwd_i8_kernel(
     // one MFMA per position; U through a register ring kDepth positions deep
     constexpr int kDepth = M == 4 ? 9 : 8;
     static_assert(P % kDepth == 0, "ring depth must divide the number of positions");
-    const int8_t* ub = urow + (size_t)cb * 64;
+    const int8_t* ub = urow + (size_t)cb * 1024;
     v4i bufU[kDepth];
 #pragma unroll
     for (int p = 0; p < kDepth; ++p) bufU[p] = *(const v4i*)(ub + p * up);

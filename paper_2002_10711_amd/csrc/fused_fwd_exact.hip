@@ -204,9 +204,11 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
   const float lo = kMagic - qmax, hi = kMagic + qmax;
 
   WINO_TS(0);
-  // U rows of this wave: output channels kb + wave*16 + r, 16 bytes at channel grp*16;
-  // 32-bit offsets from the (uniform) base pointer
-  const uint32_t uoff = (uint32_t)(kb + wave * 16 + r) * (uint32_t)g.Cp + (uint32_t)grp * 16u;
+  // U rows of this wave: output channels kb + wave*16 + r, 16 bytes at channel grp*16 -- in
+  // the blocked layout of the weights (u_byte_index) 1 KB of consecutive bytes per
+  // wavefront and channel block; 32-bit offsets from the (uniform) base pointer
+  const uint32_t uoff = (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)(g.Cp >> 6) * 1024u +
+                        (uint32_t)(grp * 16 + r) * 16u;
   const uint32_t up = (uint32_t)g.Kp * (uint32_t)g.Cp;
   v4i acc[P];
   if constexpr (!kOneBlock) {
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     // the memory pipe idle, while the loads (36 KB per wavefront through the L1) would
     // otherwise stall the MFMA loop.
     constexpr int kDepth = P;
-    const uint32_t ub = uoff + (uint32_t)cb * 64u;
+    const uint32_t ub = uoff + (uint32_t)cb * 1024u;
     v4i bufU[kDepth];
     __syncthreads();                                   // Xs is free: Vl may overwrite it
     WINO_TS(3);

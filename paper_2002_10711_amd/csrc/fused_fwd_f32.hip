@@ -183,7 +183,7 @@ __global__ __launch_bounds__(512) void fused_fwd_f32_kernel(const float* __restr
   // -------------------------------------------------------------------- consumers
   const int lane = tid & 63, r = lane & 15, grp = lane >> 4;
   // "A" rows = output channels kb + wave*16 + r, 4 floats at channel grp*4: in the blocked
-  // layout of the fp32 weights (u_f32_index) the wavefront's 16 x 16 block of a channel
+  // layout of the fp32 weights (u_byte_index) the wavefront's 16 x 16 block of a channel
   // block is 1 KB of consecutive bytes, this lane's piece at (grp*16 + r) * 16
   const uint32_t uoff = (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)(g.Cp >> 4) * 1024u +
                         (uint32_t)(grp * 16 + r) * 16u;

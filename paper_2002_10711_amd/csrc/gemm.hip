@@ -32,7 +32,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 template <bool I8> struct AccT { typedef v4i type; };
 template <> struct AccT<false> { typedef v4f type; };
 
-// kBlockedB: B is in the fp32 block layout of u_f32_index (1 KB blocks of 16 rows x 64
+// kBlockedB: B is in the block layout of u_byte_index (1 KB blocks of 16 rows x 64
 // bytes, piece (16-byte segment seg, row kr) at piece index seg*16 + kr): a thread's
 // pieces are then taken in block order, so the global reads stay contiguous, and are put
 // into the same LDS places as in the plain layout.
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const char* __restrict_
 hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, int b_blocked, const void* A,
                        const void* B, void* M, hipStream_t s) {
   // Tp, Kp are multiples of 64; Cp of 64 (int8) or 16 (float): the host API rounds them.
-  if (Tp % 64 || Kp % 64 || Cp % (i8 ? 64 : 16) || P < 1 || P > 65535 || (i8 && b_blocked))
+  if (Tp % 64 || Kp % 64 || Cp % (i8 ? 64 : 16) || P < 1 || P > 65535)
     return hipErrorInvalidValue;
   const int row_bytes = Cp * (i8 ? 1 : 4);
   const char* a = (const char*)A;
@@ -155,7 +155,9 @@ hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, int b_blocked, con
   if (big) {
     if (Kp / 128 > 65535) return hipErrorInvalidValue;
     dim3 grid(Tp / 128, Kp / 128, P);
-    if (i8)
+    if (i8 && b_blocked)
+      gemm_tiled_kernel<4, 4, true, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
+    else if (i8)
       gemm_tiled_kernel<4, 4, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
     else if (b_blocked)
       gemm_tiled_kernel<4, 4, false, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
@@ -164,7 +166,9 @@ hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, int b_blocked, con
   } else {
     if (Kp / 64 > 65535) return hipErrorInvalidValue;
     dim3 grid(Tp / 64, Kp / 64, P);
-    if (i8)
+    if (i8 && b_blocked)
+      gemm_tiled_kernel<2, 2, true, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
+    else if (i8)
       gemm_tiled_kernel<2, 2, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);
     else if (b_blocked)
       gemm_tiled_kernel<2, 2, false, true><<<grid, 256, 0, s>>>(a, b, m, Tp, Kp, row_bytes);

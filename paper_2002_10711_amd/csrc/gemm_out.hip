@@ -36,18 +36,16 @@ __global__ __launch_bounds__(256) void gemm_out_kernel(Geom g, MatAT at,
   const int tb = blockIdx.x * 16, kb = blockIdx.y * 64;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, grp = lane >> 4;
   const int t = tb + r;
-  const int krow = kb + wave * 16 + r;
   // Addresses = uniform 64-bit base (position, channel chunk: scalar registers) + a
   // 32-bit per-lane offset (row, lane group): no per-position 64-bit vector pointers,
   // which would not fit next to n*n accumulator sets.  The host checks the 32-bit range.
   const size_t vp = (size_t)g.Tp * g.Cp * ESZ, up = (size_t)g.Kp * g.Cp * ESZ;
   const uint32_t voff = (uint32_t)t * (uint32_t)(g.Cp * ESZ) + (uint32_t)grp * 16u;
-  // (fp32 weights are in the blocked layout of u_f32_index: the wavefront's 16 channels x
-  // 16 input channels of a chunk are 1 KB of consecutive bytes, lane piece grp*16 + r)
-  const uint32_t uoff =
-      I8 ? (uint32_t)krow * (uint32_t)(g.Cp * ESZ) + (uint32_t)grp * 16u
-         : (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)(g.Cp >> 4) * 1024u + (uint32_t)(grp * 16 + r) * 16u;
-  constexpr int kUChunk = I8 ? 64 : 1024;             // bytes from one chunk of U to the next
+  // (the weights are in the blocked layout of u_byte_index: the wavefront's 16 channels x
+  // 64 bytes of a chunk are 1 KB of consecutive bytes, this lane's piece at grp*16 + r)
+  const uint32_t uoff = (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)((g.Cp * ESZ) >> 6) * 1024u +
+                        (uint32_t)(grp * 16 + r) * 16u;
+  constexpr int kUChunk = 1024;                        // bytes from one chunk of U to the next
   const char* vrow = (const char*)Vv;
   const char* urow = (const char*)Uv;
   const int nchunk = g.Cp / CHUNK;

@@ -132,8 +132,9 @@ __global__ __launch_bounds__(256) void weight_transform_i8(Geom g, MatG mg,
       }
     }
   }
-  const size_t pstride = (size_t)g.Kp * cq_per;
-  uint32_t* up = U + (size_t)i * n * pstride + (size_t)k * cq_per + cq;
+  // blocked layout (see u_byte_index): same place in every position's slab
+  const size_t pstride = (size_t)g.Kp * cq_per;        // dwords per position
+  uint32_t* up = U + (size_t)i * n * pstride + u_byte_index(g.Kp, g.Cp, 1, 0, k, cq * 4) / 4;
 #pragma unroll
   for (int j = 0; j < n; ++j) up[j * pstride] = out[j];
 }
@@ -160,9 +161,9 @@ __global__ __launch_bounds__(256) void weight_transform_f32(Geom g, MatG mg,
       for (int b = 0; b < 3; ++b) gk[a][b] = wp[a * 3 + b];
     transform_filter<n>(gk, mg, Ut);
   }
-  // blocked layout (see u_f32_index): same place in every position's slab
+  // blocked layout (see u_byte_index): same place in every position's slab
   const size_t pstride = (size_t)g.Kp * g.Cp;
-  float* up = U + u_f32_index(g.Kp, g.Cp, 0, k, c);
+  float* up = U + u_byte_index(g.Kp, g.Cp, 4, 0, k, c) / 4;
 #pragma unroll
   for (int p = 0; p < P; ++p) up[p * pstride] = Ut[p / n][p % n];
 }
@@ -217,17 +218,18 @@ __global__ __launch_bounds__(256) void export_kernel(const T* __restrict__ src,
   }
 }
 
-// The same for the fp32 transformed weights, which live in the blocked layout.
-__global__ __launch_bounds__(256) void export_u_f32_kernel(const float* __restrict__ src,
-                                                           float* __restrict__ out, int P, int K,
-                                                           int C, int Kp, int Cp) {
+// The same for the transformed weights, which live in the blocked layout.
+template <typename T>
+__global__ __launch_bounds__(256) void export_u_kernel(const T* __restrict__ src,
+                                                       T* __restrict__ out, int P, int K, int C,
+                                                       int Kp, int Cp) {
   const long long total = (long long)P * K * C;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total;
        i += (long long)gridDim.x * 256) {
     const int c = (int)(i % C);
     const long long pk = i / C;
     const int k = (int)(pk % K), p = (int)(pk / K);
-    out[i] = src[u_f32_index(Kp, Cp, p, k, c)];
+    out[i] = src[u_byte_index(Kp, Cp, (int)sizeof(T), p, k, c) / sizeof(T)];
   }
 }
 
@@ -426,8 +428,10 @@ hipError_t launch_export(const Geom& g, int which, const void* src, void* out, h
   }
   const long long total = (long long)g.P * rows * cols;
   const unsigned nb = (unsigned)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
-  if (which == WINO_TAP_U && !g.i8)
-    export_u_f32_kernel<<<nb, 256, 0, s>>>((const float*)src, (float*)out, g.P, g.K, g.C, g.Kp, g.Cp);
+  if (which == WINO_TAP_U && g.i8)
+    export_u_kernel<int8_t><<<nb, 256, 0, s>>>((const int8_t*)src, (int8_t*)out, g.P, g.K, g.C, g.Kp, g.Cp);
+  else if (which == WINO_TAP_U)
+    export_u_kernel<uint32_t><<<nb, 256, 0, s>>>((const uint32_t*)src, (uint32_t*)out, g.P, g.K, g.C, g.Kp, g.Cp);
   else if (esz == 1)
     export_kernel<int8_t><<<nb, 256, 0, s>>>((const int8_t*)src, (int8_t*)out, g.P, rows, cols,
                                               rowsP, colsP);

@@ -27,15 +27,17 @@ struct MatAT { float v[48]; };   // m x n, m <= 6
 
 inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
 
-// Private layout of the fp32 transformed weights (the int8 ones are plain U[p][k][c]):
-// [p][Kp/16][Cp/16] blocks of 16 output channels x 16 input channels, each block (1 KB)
-// in the order in which an MFMA wavefront loads it -- the 16-byte piece (channel quad q,
-// output channel k) sits at piece index q*16 + k, which is the lane that needs it.  A
-// wavefront's operand load is then 1 KB of consecutive bytes instead of 16 bytes from
-// each of 64 cache lines.  Element index of U[p][k][c]:
-__host__ __device__ inline size_t u_f32_index(int Kp, int Cp, int p, int k, int c) {
-  const size_t blk = ((size_t)p * (Kp >> 4) + (k >> 4)) * (Cp >> 4) + (c >> 4);
-  return (blk * 64 + (size_t)(((c & 15) >> 2) * 16 + (k & 15))) * 4 + (c & 3);
+// Private layout of the transformed weights U: per position, blocks of 16 output channels
+// x 64 bytes of the reduction axis (64 int8 or 16 fp32 input channels), [p][Kp/16][row
+// bytes/64] blocks of 1 KB, each in the order in which an MFMA wavefront loads it -- the
+// 16-byte piece (segment q of the 64 bytes, output channel k) sits at piece index
+// q*16 + k, which is the lane that needs it.  A wavefront's operand load is then 1 KB of
+// consecutive bytes (8 cache lines) instead of 16 bytes from each of up to 64 lines.
+// Byte offset of element U[p][k][c], esz = bytes per element:
+__host__ __device__ inline size_t u_byte_index(int Kp, int Cp, int esz, int p, int k, int c) {
+  const int cb = c * esz;                               // byte position in the row
+  const size_t blk = ((size_t)p * (Kp >> 4) + (k >> 4)) * ((Cp * esz) >> 6) + (cb >> 6);
+  return (blk * 64 + (size_t)(((cb & 63) >> 4) * 16 + (k & 15))) * 16 + (cb & 15);
 }
 
 // Kernel launchers (each enqueues on `s` and returns hipGetLastError()).
@@ -45,7 +47,7 @@ hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w
                                    float r_u, float qmax, hipStream_t s);
 // Batched GEMM  M[p][t][k] = sum_c A[p][t][c] * B[p][k][c]; rows padded as above.
 // Used with P = n*n for the Winograd domain and P = 1 for the im2row baseline.
-// b_blocked: B is in the fp32 block layout of u_f32_index (fp32 only).
+// b_blocked: B is in the block layout of u_byte_index.
 hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, int b_blocked, const void* A,
                        const void* B, void* M, hipStream_t s);
 hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M, void* y,
