@@ -458,7 +458,9 @@ bool input_exact_supported(const Geom& g, const MatBT& bt) {
 }
 
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
-  return g.Kp <= 128 && input_exact_supported(g, bt);
+  // (images narrower than 8 pixels or with ragged rows would need the byte / unaligned
+  // staging of one or two tiles per row, where the vector-ALU kernel is the faster one)
+  return g.Kp <= 128 && g.W % 4 == 0 && g.W >= 8 && input_exact_supported(g, bt);
 }
 
 // As a stand-alone input stage the exact kernel pays off where its staging runs on
@@ -592,8 +594,8 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
 #define WINO_LAUNCH_G2(SA, LOAD) \
   do { if (mq) WINO_LAUNCH_G1(SA, LOAD, true); else WINO_LAUNCH_G1(SA, LOAD, false); } while (0)
 #define WINO_LAUNCH_G3(SA)                                                                 \
-  do { if (load == 2) WINO_LAUNCH_G2(SA, 2); else if (load == 1) WINO_LAUNCH_G2(SA, 1);    \
-       else WINO_LAUNCH_G2(SA, 0); } while (0)
+  do { if (load == 2) WINO_LAUNCH_G2(SA, 2); else WINO_LAUNCH_G2(SA, 1); } while (0)
+  if (load == 0) return hipErrorInvalidValue;            // W < 4: see fused_fwd_exact_supported
   if (sa) WINO_LAUNCH_G3(true); else WINO_LAUNCH_G3(false);
 #undef WINO_LAUNCH_G3
 #undef WINO_LAUNCH_G2
