@@ -97,7 +97,7 @@ def roofline_entry(name, alg, us, dtype, traffic):
     return ent
 
 
-def gpu_leg(L, steps, warmup, use_graph):
+def gpu_leg(L, steps, warmup, use_graph, cold=False):
     import torch
     from paper_2002_10711_amd import binding as wb
     if not torch.cuda.is_available():
@@ -221,7 +221,50 @@ def gpu_leg(L, steps, warmup, use_graph):
                           scales["s_y"], 127, rws, stream=stream)
 
     ms_ref = timed(ref_fwd, max(10, steps // 4), max(2, warmup // 4))
-    return dict(ms_step=ms_step, ms_fwd=ms_fwd, ms_ref=ms_ref, kernel_us=acc, staged_us=acc_staged,
+    extra = {}
+    if cold:
+        # cold: every call finds neither X, U nor anything else in L2 / Infinity Cache
+        # (256 MB): a 1 GiB fill runs between the calls, outside the event pairs
+        big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        n = 30
+        with torch.cuda.stream(stream):
+            def event_timed(flush):
+                ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                      for _ in range(n)]
+                for a, b in ev:
+                    if flush:
+                        big.fill_(1)
+                    a.record(stream)
+                    fwd_only()
+                    b.record(stream)
+                torch.cuda.synchronize()
+                ts = sorted(a.elapsed_time(b) for a, b in ev)
+                return ts[len(ts) // 2]
+            event_timed(True)
+            extra["cold_fwd_ms"] = event_timed(True)
+            extra["warm_fwd_host_launch_ms"] = event_timed(False)
+            # plain device copy of 1 GiB (reads + writes counted): the HBM rate a kernel sees
+            dst = torch.empty_like(big)
+            for _ in range(2):
+                dst.copy_(big)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(5):
+                dst.copy_(big)
+            b.record(stream)
+            torch.cuda.synchronize()
+            extra["measured_copy_GBps"] = 5 * 2 * (1 << 30) / (a.elapsed_time(b) * 1e-3) / 1e9
+            # matrix-core probe: independent MFMAs only, 8 workgroups per compute unit
+            probe = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
+            for name, pdt in (("measured_mfma_int8_TOPS", wb.WINO_I8), ("measured_mfma_f32_TFLOPS", wb.WINO_F32)):
+                wb.wino_debug_mfma_loop(pdt, 2048, 2000, probe, stream=stream)
+                a.record(stream)
+                ops = wb.wino_debug_mfma_loop(pdt, 2048, 2000, probe, stream=stream)
+                b.record(stream)
+                torch.cuda.synchronize()
+                extra[name] = ops / (a.elapsed_time(b) * 1e-3) / 1e12
+        del big, dst
+    return dict(extra=extra, ms_step=ms_step, ms_fwd=ms_fwd, ms_ref=ms_ref, kernel_us=acc, staged_us=acc_staged,
                 BT=BT, AT=AT)
 
 
@@ -266,6 +309,11 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host "
                     "instead of replaying a captured HIP graph of one step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold", action="store_true", help="also time the forward with L2 and "
+                    "Infinity Cache evicted before every call (a 1 GiB buffer is overwritten in "
+                    "between) and measure the plain-copy HBM rate; adds cold_fwd_ms, "
+                    "warm_fwd_host_launch_ms, measured_copy_GBps and the measured matrix-core "
+                    "rates (MFMA-only loop) to the JSON line")
     ap.add_argument("--copy-probe", action="store_true", help="also run a plain 256 MiB device "
                     "copy a few times: the reference kernel against which rocprofv3's "
                     "FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -284,7 +332,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    r = gpu_leg(L, a.steps, a.warmup, not a.no_graph)
+    r = gpu_leg(L, a.steps, a.warmup, not a.no_graph, a.cold)
     alg = algorithmic(L, r["BT"], r["AT"])
     traffic = {}
     if os.path.exists(HBM_TRAFFIC_FILE):
@@ -314,6 +362,7 @@ def main():
         "staged_kernels": [roofline_entry(k, alg[k], us, L.dtype, traffic.get(k))
                            for k, us in r["staged_us"].items()],
     }
+    out.update(r["extra"])
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_leg(L)
     print(json.dumps(out))

@@ -139,6 +139,16 @@ enum { WINO_TAP_U = 0, WINO_TAP_V = 1, WINO_TAP_M = 2 };
 wino_status wino_debug_export(const wino_desc* d, int which, const void* src_dev,
                               void* out_dev, void* stream);
 
+/* Matrix-core peak probe for the roofline figures (measurement infrastructure, not part
+ * of the paper's method): launches `workgroups` x 256 threads, every wavefront issuing
+ * 8 * iters independent MFMAs of the path's instruction (v_mfma_i32_16x16x64_i8 for
+ * WINO_I8, v_mfma_f32_16x16x4_f32 for WINO_F32) and nothing else.
+ *   out_dev         out  DEVICE, workgroups * 256 floats (checksums, ignore)
+ *   ops_per_launch  out  HOST, may be NULL: multiply-adds x 2 the launch performs
+ * Time it with events on `stream`; ops / time is the achievable matrix rate. */
+wino_status wino_debug_mfma_loop(wino_dtype dtype, int workgroups, int iters, float* out_dev,
+                                 double* ops_per_launch, void* stream);
+
 /* Cook-Toom matrices for F(m,3) from m+1 distinct finite points (NULL = the
  * usual 0, 1, -1, 1/2, -1/2, 2, -2 prefix) plus the point at infinity
  * (Sec. 3.1).  HOST outputs: BT n*n, G n*3, AT m*n floats. */

@@ -18,7 +18,7 @@ WINO_STAGE_INPUT, WINO_STAGE_GEMM, WINO_STAGE_OUTPUT, WINO_STAGE_ALL = 1, 2, 4, 
 EXPORTS = [
     "wino_status_string", "wino_weights_bytes", "wino_workspace_bytes",
     "wino_transform_weights", "wino_conv2d_fwd", "wino_conv2d_fwd_stages", "wino_fwd_num_kernels",
-    "wino_debug_export", "wino_cook_toom",
+    "wino_debug_export", "wino_debug_mfma_loop", "wino_cook_toom",
     "conv2d_ref_packed_weights_bytes", "conv2d_ref_workspace_bytes",
     "conv2d_ref_pack_weights", "conv2d_ref_gpu",
 ]
@@ -72,6 +72,8 @@ def lib():
                                              ctypes.c_void_p]
         L.wino_debug_export.argtypes = [ctypes.POINTER(WinoDesc), ctypes.c_int, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_void_p]
+        L.wino_debug_mfma_loop.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                           ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
         L.wino_cook_toom.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_void_p]
         L.conv2d_ref_packed_weights_bytes.argtypes = [ctypes.c_int] * 3
@@ -175,6 +177,14 @@ def wino_conv2d_fwd_stages(desc, quant, x_dev, U_dev, y_dev, workspace_dev, stag
 def wino_debug_export(desc, which, src_dev, out_dev, stream=None):
     _check(lib().wino_debug_export(desc.ref, which, _ptr(src_dev), _ptr(out_dev), _stream(stream)),
            "wino_debug_export")
+
+
+def wino_debug_mfma_loop(dtype, workgroups, iters, out_dev, stream=None):
+    """Launches the matrix-core peak probe; returns the operations one launch performs."""
+    ops = ctypes.c_double(0.0)
+    _check(lib().wino_debug_mfma_loop(dtype, workgroups, iters, _ptr(out_dev), ctypes.byref(ops),
+                                      _stream(stream)), "wino_debug_mfma_loop")
+    return ops.value
 
 
 def wino_cook_toom(m, points=None):

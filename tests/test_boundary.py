@@ -144,3 +144,16 @@ def test_library_cook_toom_custom_points_and_errors(L, oracle):
     dup = np.array([0.0, 1.0, 1.0])
     b = np.zeros(64, np.float32)
     assert L.wino_cook_toom(2, dup.ctypes.data, b.ctypes.data, b.ctypes.data, b.ctypes.data) == -8
+
+
+def test_mfma_probe_argument_checks():
+    """Argument errors of the matrix-core probe come back before any HIP call."""
+    from paper_2002_10711_amd import binding as wb
+    L = wb.lib()
+    import ctypes
+    assert L.wino_debug_mfma_loop(wb.WINO_I8, 8, 10, None, None, None) == -1        # WINO_E_NULL
+    buf = (ctypes.c_float * 4)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    assert L.wino_debug_mfma_loop(wb.WINO_I8, 0, 10, p, None, None) == -3           # bad shape
+    assert L.wino_debug_mfma_loop(wb.WINO_I8, 8, 0, p, None, None) == -3
+    assert L.wino_debug_mfma_loop(7, 8, 10, p, None, None) == -4                    # bad dtype

@@ -54,3 +54,17 @@ def test_ref_conv_fp32(oracle, L):
     ref = oracle.conv2d_direct_f64(X, g, L.stride, L.pad)
     y = _run(L, X, g, False)
     assert y.shape == ref.shape and max_rel(y, ref) <= 1e-5
+
+
+@pytest.mark.gpu
+def test_mfma_probe_runs_and_counts_its_operations():
+    import torch
+    from paper_2002_10711_amd import binding as wb
+    out = torch.zeros(64 * 256, dtype=torch.float32, device="cuda:0")
+    ops = wb.wino_debug_mfma_loop(wb.WINO_I8, 64, 10, out)
+    torch.cuda.synchronize()
+    assert ops == 2.0 * 16 * 16 * 64 * 8 * 10 * 4 * 64
+    ops = wb.wino_debug_mfma_loop(wb.WINO_F32, 64, 10, out)
+    torch.cuda.synchronize()
+    assert ops == 2.0 * 16 * 16 * 4 * 8 * 10 * 4 * 64
+    assert torch.isfinite(out).all()
