@@ -157,3 +157,16 @@ def test_mfma_probe_argument_checks():
     assert L.wino_debug_mfma_loop(wb.WINO_I8, 0, 10, p, None, None) == -3           # bad shape
     assert L.wino_debug_mfma_loop(wb.WINO_I8, 8, 0, p, None, None) == -3
     assert L.wino_debug_mfma_loop(7, 8, 10, p, None, None) == -4                    # bad dtype
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: any other --gpus value ends with a message, before
+    anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
