@@ -42,6 +42,7 @@ def lib():
         build()
         L = ctypes.CDLL(_LIB)
         L.oracle_q_output.restype = ctypes.c_int64
+        L.oracle_q_output_pos.restype = ctypes.c_int64
         L.oracle_num_threads.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -132,8 +133,29 @@ def q_scalars(s_x, s_v, s_u, s_y, s_m=0.0):
     return dict(r_u=r_u, r_v=r_v, r_m=r_m, r_y=r_y)
 
 
+def q_scalars_pos(s_x, s_v_pos, s_u_pos, s_y, s_m=0.0):
+    """Host scalars of the per-position variant: arrays r_u, r_v, w (one entry per
+    Winograd position) and the two scalars r_m, r_y."""
+    sv = _c(s_v_pos, np.float32)
+    su = _c(s_u_pos, np.float32)
+    P = sv.size
+    assert su.size == P
+    r_u, r_v, w = (np.zeros(P, np.float32) for _ in range(3))
+    r_m, r_y = ctypes.c_float(), ctypes.c_float()
+    lib().oracle_q_scalars_pos(P, ctypes.c_float(s_x), _p(sv), _p(su), ctypes.c_float(s_y),
+                               ctypes.c_float(s_m), _p(r_u), _p(r_v), _p(w),
+                               ctypes.byref(r_m), ctypes.byref(r_y))
+    return dict(r_u=r_u, r_v=r_v, w=w, r_m=np.float32(r_m.value), r_y=np.float32(r_y.value))
+
+
+def _per_position(r, P):
+    a = np.asarray(r, np.float32)
+    return np.ascontiguousarray(np.broadcast_to(a, (P,)) if a.ndim == 0 else a.reshape(P))
+
+
 def q_weights(g, G, r_u=1.0, qmax=127, want_f32=True, want_q=True):
-    """U = G g G^T in pinned fp32; returns (U_f32 [P,K,C] or None, Uq int32 or None)."""
+    """U = G g G^T in pinned fp32; returns (U_f32 [P,K,C] or None, Uq int32 or None).
+    r_u: one factor, or one per Winograd position."""
     g = _c(g, np.float32)
     G = _c(G, np.float32)
     K, C = g.shape[:2]
@@ -142,14 +164,19 @@ def q_weights(g, G, r_u=1.0, qmax=127, want_f32=True, want_q=True):
     P = n * n
     Uf = np.zeros((P, K, C), np.float32) if want_f32 else None
     Uq = np.zeros((P, K, C), np.int32) if want_q else None
-    rc = lib().oracle_q_weights(K, C, m, _p(G), _p(g), ctypes.c_float(r_u), int(qmax),
-                                _p(Uf), _p(Uq))
+    if np.ndim(r_u) == 0:
+        rc = lib().oracle_q_weights(K, C, m, _p(G), _p(g), ctypes.c_float(r_u), int(qmax),
+                                    _p(Uf), _p(Uq))
+    else:
+        rc = lib().oracle_q_weights_pos(K, C, m, _p(G), _p(g), _p(_per_position(r_u, P)),
+                                        int(qmax), _p(Uf), _p(Uq))
     assert rc == 0
     return Uf, Uq
 
 
 def q_input(xq, BT, pad=1, r_v=1.0, qmax=127, want_f32=True, want_q=True):
-    """V = B^T d B per tile in pinned fp32; returns (V_f32 [P,T,C] or None, Vq or None)."""
+    """V = B^T d B per tile in pinned fp32; returns (V_f32 [P,T,C] or None, Vq or None).
+    r_v: one factor, or one per Winograd position."""
     xq = _c(xq, np.int32)
     BT = _c(BT, np.float32)
     N, C, H, W = xq.shape
@@ -158,8 +185,12 @@ def q_input(xq, BT, pad=1, r_v=1.0, qmax=127, want_f32=True, want_q=True):
     geo = geometry(N, H, W, pad, m)
     Vf = np.zeros((geo["P"], geo["T"], C), np.float32) if want_f32 else None
     Vq = np.zeros((geo["P"], geo["T"], C), np.int32) if want_q else None
-    rc = lib().oracle_q_input(N, C, H, W, pad, m, _p(BT), _p(xq), ctypes.c_float(r_v),
-                              int(qmax), _p(Vf), _p(Vq))
+    if np.ndim(r_v) == 0:
+        rc = lib().oracle_q_input(N, C, H, W, pad, m, _p(BT), _p(xq), ctypes.c_float(r_v),
+                                  int(qmax), _p(Vf), _p(Vq))
+    else:
+        rc = lib().oracle_q_input_pos(N, C, H, W, pad, m, _p(BT), _p(xq),
+                                      _p(_per_position(r_v, geo["P"])), int(qmax), _p(Vf), _p(Vq))
     assert rc == 0
     return Vf, Vq
 
@@ -177,8 +208,10 @@ def q_hadamard(Vq, Uq):
     return M
 
 
-def q_output(M, AT, N, H, W, pad=1, r_m=0.0, r_y=1.0, qmax=127, want_f32=True, want_q=True):
-    """Y tile = A^T M A in pinned fp32; returns (Y_f32 unscaled or None, Yq or None, inexact)."""
+def q_output(M, AT, N, H, W, pad=1, r_m=0.0, r_y=1.0, qmax=127, want_f32=True, want_q=True,
+             w_pos=None):
+    """Y tile = A^T M A in pinned fp32; returns (Y_f32 unscaled or None, Yq or None, inexact).
+    w_pos: per-position factors that bring M to real units first (per-position scales)."""
     M = _c(M, np.int64)
     AT = _c(AT, np.float32)
     m, n = AT.shape
@@ -187,8 +220,13 @@ def q_output(M, AT, N, H, W, pad=1, r_m=0.0, r_y=1.0, qmax=127, want_f32=True, w
     assert P == geo["P"] and T == geo["T"]
     Yf = np.zeros((N, K, geo["Ho"], geo["Wo"]), np.float32) if want_f32 else None
     Yq = np.zeros((N, K, geo["Ho"], geo["Wo"]), np.int32) if want_q else None
-    inexact = lib().oracle_q_output(N, K, H, W, pad, m, _p(AT), _p(M), ctypes.c_float(r_m),
-                                    ctypes.c_float(r_y), int(qmax), _p(Yf), _p(Yq))
+    if w_pos is None:
+        inexact = lib().oracle_q_output(N, K, H, W, pad, m, _p(AT), _p(M), ctypes.c_float(r_m),
+                                        ctypes.c_float(r_y), int(qmax), _p(Yf), _p(Yq))
+    else:
+        inexact = lib().oracle_q_output_pos(N, K, H, W, pad, m, _p(AT), _p(M),
+                                            _p(_per_position(w_pos, P)), ctypes.c_float(r_m),
+                                            ctypes.c_float(r_y), int(qmax), _p(Yf), _p(Yq))
     assert inexact >= 0
     return Yf, Yq, int(inexact)
 
@@ -221,8 +259,43 @@ def calibrate(X, g, BT, G, AT, pad=1, qmax=127):
     return dict(s_x=float(s_x), s_v=float(s_v), s_u=float(s_u), s_y=float(s_y), s_m=0.0)
 
 
+def calibrate_pos(X, g, BT, G, AT, pad=1, qmax=127):
+    """As calibrate, with one max-abs scale per Winograd position for the transformed
+    input and the transformed weights ("s_v_pos", "s_u_pos"; a position that is zero
+    everywhere gets the scale 1)."""
+    f32 = np.float32
+    s_x = f32(np.abs(np.asarray(X, f32)).max() / f32(qmax))
+    xq = quantize_tensor(X, s_x, qmax)
+    Vf, _ = q_input(xq, BT, pad=pad, want_q=False)
+    Uf, _ = q_weights(g, G, want_q=False)
+    P = Vf.shape[0]
+    vmax = np.abs(Vf).reshape(P, -1).max(axis=1).astype(f32)
+    umax = np.abs(Uf).reshape(P, -1).max(axis=1).astype(f32)
+    s_v = np.where(vmax > 0, s_x * vmax / f32(qmax), f32(1)).astype(f32)
+    s_u = np.where(umax > 0, umax / f32(qmax), f32(1)).astype(f32)
+    sc = q_scalars_pos(s_x, s_v, s_u, 1.0)
+    _, Vq = q_input(xq, BT, pad=pad, r_v=sc["r_v"], qmax=qmax, want_f32=False)
+    _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qmax, want_f32=False)
+    M = q_hadamard(Vq, Uq)
+    N, _, H, W = xq.shape
+    Yf, _, _ = q_output(M, AT, N, H, W, pad=pad, want_q=False, w_pos=sc["w"])
+    s_y = f32(f32(np.abs(Yf).max()) / f32(qmax))
+    return dict(s_x=float(s_x), s_v_pos=s_v, s_u_pos=s_u, s_y=float(s_y), s_m=0.0)
+
+
 def winograd_q(xq, g, BT, G, AT, scales, pad=1, qmax=127):
-    """The whole quantized forward, every tap returned.  xq: int input at scale s_x."""
+    """The whole quantized forward, every tap returned.  xq: int input at scale s_x.
+    With "s_v_pos" / "s_u_pos" in scales: the per-position variant."""
+    if "s_v_pos" in scales:
+        sc = q_scalars_pos(scales["s_x"], scales["s_v_pos"], scales["s_u_pos"], scales["s_y"],
+                           scales.get("s_m", 0.0))
+        _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qmax, want_f32=False)
+        _, Vq = q_input(xq, BT, pad=pad, r_v=sc["r_v"], qmax=qmax, want_f32=False)
+        M = q_hadamard(Vq, Uq)
+        N, _, H, W = np.asarray(xq).shape
+        _, Yq, inexact = q_output(M, AT, N, H, W, pad=pad, r_m=sc["r_m"], r_y=sc["r_y"],
+                                  qmax=qmax, want_f32=False, w_pos=sc["w"])
+        return dict(Uq=Uq, Vq=Vq, M=M, Yq=Yq, inexact=inexact, scalars=sc)
     sc = q_scalars(scales["s_x"], scales["s_v"], scales["s_u"], scales["s_y"],
                    scales.get("s_m", 0.0))
     _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qmax, want_f32=False)

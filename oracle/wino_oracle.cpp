@@ -229,9 +229,13 @@ void oracle_q_scalars(float s_x, float s_v, float s_u, float s_y, float s_m,
 // Weight stage:  t = G g (n x 3), U = t G^T (n x n), Uq = sat(rne(U * r_u)).
 // U_f32 (optional) receives the unscaled fp32 U, Uq (optional) the integers;
 // both in the order [p][k][c].
-int oracle_q_weights(int K, int C, int m, const float* G, const float* g, float r_u, int qmax,
-                     float* U_f32, int32_t* Uq) {
-  if (K < 1 || C < 1 || m < 1 || m > 6) return -1;
+// Per-position variant (Sec. 6 names "other types of quantization" as the way to recover
+// F4/F6 accuracy; one scale per Winograd position is the smallest step from the paper's
+// one scale per tensor): r_u_pos[p] multiplies position p = i*n + j.  The per-tensor entry
+// point below is this one with all factors equal.
+int oracle_q_weights_pos(int K, int C, int m, const float* G, const float* g,
+                         const float* r_u_pos, int qmax, float* U_f32, int32_t* Uq) {
+  if (K < 1 || C < 1 || m < 1 || m > 6 || !r_u_pos) return -1;
   const int n = m + 2;
 #pragma omp parallel for schedule(static)
   for (int k = 0; k < K; ++k)
@@ -250,18 +254,27 @@ int oracle_q_weights(int K, int C, int m, const float* G, const float* g, float 
           for (int b = 0; b < 3; ++b) acc = fmaf(t[i][b], G[j * 3 + b], acc);
           const size_t o = ((size_t)(i * n + j) * K + k) * C + c;
           if (U_f32) U_f32[o] = acc;
-          if (Uq) Uq[o] = quantize(acc * r_u, (float)qmax);
+          if (Uq) Uq[o] = quantize(acc * r_u_pos[i * n + j], (float)qmax);
         }
     }
   return 0;
 }
 
+int oracle_q_weights(int K, int C, int m, const float* G, const float* g, float r_u, int qmax,
+                     float* U_f32, int32_t* Uq) {
+  float r[64];
+  for (int p = 0; p < 64; ++p) r[p] = r_u;
+  return oracle_q_weights_pos(K, C, m, G, g, r, qmax, U_f32, Uq);
+}
+
 // Input stage:  d = patch of x_q as floats (+0 outside the image),
 //   w = B^T d (n x n), V = w B (n x n), Vq = sat(rne(V * r_v)).
 // V_f32 / Vq in the order [p][t][c].
-int oracle_q_input(int N, int C, int H, int W, int pad, int m, const float* BT,
-                   const int32_t* xq, float r_v, int qmax, float* V_f32, int32_t* Vq) {
-  if (N < 1 || C < 1 || H < 1 || W < 1 || pad < 0 || m < 1 || m > 6) return -1;
+// r_v_pos[p]: one factor per Winograd position p = i*n + k (see oracle_q_weights_pos).
+int oracle_q_input_pos(int N, int C, int H, int W, int pad, int m, const float* BT,
+                       const int32_t* xq, const float* r_v_pos, int qmax, float* V_f32,
+                       int32_t* Vq) {
+  if (N < 1 || C < 1 || H < 1 || W < 1 || pad < 0 || m < 1 || m > 6 || !r_v_pos) return -1;
   const int n = m + 2;
   const int Ho = H + 2 * pad - 2, Wo = W + 2 * pad - 2;
   if (Ho < 1 || Wo < 1) return -1;
@@ -293,11 +306,18 @@ int oracle_q_input(int N, int C, int H, int W, int pad, int m, const float* BT,
               for (int l = 0; l < n; ++l) acc = fmaf(w[i][l], BT[k * n + l], acc);
               const size_t o = ((size_t)(i * n + k) * T + t) * C + c;
               if (V_f32) V_f32[o] = acc;
-              if (Vq) Vq[o] = quantize(acc * r_v, (float)qmax);
+              if (Vq) Vq[o] = quantize(acc * r_v_pos[i * n + k], (float)qmax);
             }
         }
       }
   return 0;
+}
+
+int oracle_q_input(int N, int C, int H, int W, int pad, int m, const float* BT,
+                   const int32_t* xq, float r_v, int qmax, float* V_f32, int32_t* Vq) {
+  float r[64];
+  for (int p = 0; p < 64; ++p) r[p] = r_v;
+  return oracle_q_input_pos(N, C, H, W, pad, m, BT, xq, r, qmax, V_f32, Vq);
 }
 
 // Hadamard stage written as one GEMM per Winograd position (exact integers):
@@ -323,9 +343,12 @@ int oracle_q_hadamard(int P, int64_t T, int C, int K, const int32_t* Vq, const i
 // Y_f32 (optional) receives Yt before the multiplication by r_y.
 // Returns the number of accumulators with |M| >= 2^24 (whose float conversion
 // is not exact); 0 in every int8 workload (127^2 * 512 < 2^23).
-int64_t oracle_q_output(int N, int K, int H, int W, int pad, int m, const float* AT,
-                        const int64_t* M, float r_m, float r_y, int qmax, float* Y_f32,
-                        int32_t* Yq) {
+// w_pos (optional): with per-position scales the accumulators of different positions are
+// in different units, so each is first brought to real units, Mf = (float)M * w_pos[p]
+// (w_pos[p] = s_u[p] * s_v[p]); r_m and r_y then no longer contain s_u * s_v.
+int64_t oracle_q_output_pos(int N, int K, int H, int W, int pad, int m, const float* AT,
+                            const int64_t* M, const float* w_pos, float r_m, float r_y, int qmax,
+                            float* Y_f32, int32_t* Yq) {
   if (N < 1 || K < 1 || H < 1 || W < 1 || pad < 0 || m < 1 || m > 6) return -1;
   const int n = m + 2;
   const int Ho = H + 2 * pad - 2, Wo = W + 2 * pad - 2;
@@ -345,6 +368,7 @@ int64_t oracle_q_output(int N, int K, int H, int W, int pad, int m, const float*
               const int64_t v = M[((size_t)(i * n + j) * T + t) * K + k];
               if (v >= (1 << 24) || v <= -(1 << 24)) ++inexact;
               float f = (float)v;
+              if (w_pos) f = f * w_pos[i * n + j];
               if (r_m > 0.0f) f = (float)quantize(f * r_m, (float)qmax);
               Mf[i][j] = f;
             }
@@ -368,6 +392,32 @@ int64_t oracle_q_output(int N, int K, int H, int W, int pad, int m, const float*
         }
       }
   return inexact;
+}
+
+int64_t oracle_q_output(int N, int K, int H, int W, int pad, int m, const float* AT,
+                        const int64_t* M, float r_m, float r_y, int qmax, float* Y_f32,
+                        int32_t* Yq) {
+  return oracle_q_output_pos(N, K, H, W, pad, m, AT, M, nullptr, r_m, r_y, qmax, Y_f32, Yq);
+}
+
+// Host scalars of the per-position variant, each one fp32 operation:
+//   r_u[p] = 1 / s_u[p];  r_v[p] = s_x / s_v[p];  w[p] = s_u[p] * s_v[p];
+//   s_m > 0:  r_m = 1 / s_m, r_y = s_m / s_y;   else  r_m = 0, r_y = 1 / s_y.
+void oracle_q_scalars_pos(int P, float s_x, const float* s_v_pos, const float* s_u_pos, float s_y,
+                          float s_m, float* r_u_pos, float* r_v_pos, float* w_pos, float* r_m,
+                          float* r_y) {
+  for (int p = 0; p < P; ++p) {
+    r_u_pos[p] = 1.0f / s_u_pos[p];
+    r_v_pos[p] = s_x / s_v_pos[p];
+    w_pos[p] = s_u_pos[p] * s_v_pos[p];
+  }
+  if (s_m > 0.0f) {
+    *r_m = 1.0f / s_m;
+    *r_y = s_m / s_y;
+  } else {
+    *r_m = 0.0f;
+    *r_y = 1.0f / s_y;
+  }
 }
 
 // Number of OpenMP threads the loops above will use (for reporting).

@@ -440,3 +440,94 @@ def test_flex_limit_noise_to_zero(oracle):
         BTp, Gp, ATp = [a.astype(np.float64) for a in workloads.perturb_transforms(BT, G, AT, sigma, 5)]
         errs.append(_rel(oracle.winograd_f64(X, g, BTp, Gp, ATp), Yd))
     assert errs[0] > 10 * errs[1] > 100 * errs[2] and errs[2] < 1e-3
+
+
+# ------------------------------------------------------------ per-position scales --
+def test_per_position_f2_stages_are_exact_integers(oracle):
+    """Per-position variant with power-of-two factors on exact F2 data: every stage equals
+    integer algebra with the factor applied per Winograd position, and the real-unit
+    output equals the integer direct convolution (Sec. 6: finer quantization granularity
+    as the way to recover the larger tiles' accuracy)."""
+    rng = np.random.default_rng(31)
+    BT, G, AT = oracle.cook_toom(2, dtype=np.float32)
+    N, C, K, H, W = 2, 3, 4, 6, 7
+    xq = rng.integers(-127, 128, (N, C, H, W))
+    g4 = (4 * rng.integers(-7, 8, (K, C, 3, 3))).astype(np.float32)
+    d, TH, TW = _patches(xq, 2, 1)
+    BTi = BT.astype(np.int64)
+    Vexp = np.einsum("ij,tcjl,kl->iktc", BTi, d.astype(np.int64), BTi).reshape(16, -1, C)
+    G2 = (2 * G).astype(np.int64)
+    Uexp = (np.einsum("ia,kcab,jb->ijkc", G2, g4.astype(np.int64), G2) // 4).reshape(16, K, C)
+    # factors 2^e, e >= 0, so that quantized values stay integers of the exact ones
+    ev = rng.integers(0, 3, 16)
+    eu = rng.integers(0, 3, 16)
+    r_v = (2.0 ** ev).astype(np.float32)
+    r_u = (2.0 ** eu).astype(np.float32)
+    _, Vq = oracle.q_input(xq, BT, pad=1, r_v=r_v, qmax=10 ** 7, want_f32=False)
+    _, Uq = oracle.q_weights(g4, G, r_u=r_u, qmax=10 ** 7, want_f32=False)
+    assert np.array_equal(Vq, Vexp * (2 ** ev)[:, None, None])
+    assert np.array_equal(Uq, Uexp * (2 ** eu)[:, None, None])
+    M = oracle.q_hadamard(Vq, Uq)
+    w = (2.0 ** (-(ev + eu))).astype(np.float32)          # brings every position back
+    Yf, Yq, inexact = oracle.q_output(M, AT, N, H, W, pad=1, r_y=1.0, qmax=2 ** 30, w_pos=w)
+    acc, _ = oracle.conv2d_direct_q(xq, g4.astype(np.int64), 1.0, qmax=2 ** 30)
+    assert inexact == 0 and np.array_equal(Yq, acc)
+    # a factor applied to the wrong position (transposed index) must show
+    if not np.array_equal(ev.reshape(4, 4), ev.reshape(4, 4).T):
+        _, Vbad = oracle.q_input(xq, BT, pad=1, r_v=r_v.reshape(4, 4).T.ravel(), qmax=10 ** 7,
+                                 want_f32=False)
+        assert not np.array_equal(Vbad, Vq)
+
+
+def test_per_position_scalars(oracle):
+    f32 = np.float32
+    sv = np.array([0.3, 0.7, 1.1, 0.05], f32)
+    su = np.array([0.01, 0.2, 0.4, 3.0], f32)
+    sc = oracle.q_scalars_pos(0.1, sv, su, 0.9)
+    assert np.array_equal(sc["r_u"], f32(1) / su) and np.array_equal(sc["r_v"], f32(0.1) / sv)
+    assert np.array_equal(sc["w"], su * sv) and sc["r_m"] == 0 and sc["r_y"] == f32(1) / f32(0.9)
+    sc = oracle.q_scalars_pos(0.1, sv, su, 0.9, 0.25)
+    assert sc["r_m"] == f32(1) / f32(0.25) and sc["r_y"] == f32(0.25) / f32(0.9)
+
+
+def test_per_position_equals_per_tensor_when_all_factors_agree(oracle):
+    """With one common factor per stage the per-position quantizers of U and V are the
+    per-tensor ones, bit for bit."""
+    rng = np.random.default_rng(37)
+    BT, G, AT = oracle.cook_toom(4, dtype=np.float32)
+    xq = rng.integers(-127, 128, (1, 5, 9, 8))
+    g = (rng.standard_normal((3, 5, 3, 3)) * 0.2).astype(np.float32)
+    _, Vq1 = oracle.q_input(xq, BT, r_v=0.037, want_f32=False)
+    _, Vq2 = oracle.q_input(xq, BT, r_v=np.full(36, 0.037, np.float32), want_f32=False)
+    _, Uq1 = oracle.q_weights(g, G, r_u=41.5, want_f32=False)
+    _, Uq2 = oracle.q_weights(g, G, r_u=np.full(36, 41.5, np.float32), want_f32=False)
+    assert np.array_equal(Vq1, Vq2) and np.array_equal(Uq1, Uq2)
+
+
+def test_per_position_scales_reduce_the_static_int8_error(oracle):
+    """The motivation (Sec. 6; Table 1): one scale for all positions wastes most of the
+    int8 range on F4 / F6; one scale per position brings the error against the direct
+    convolution down, and converges like the per-tensor pipeline as qmax grows."""
+    from paper_2002_10711_amd import workloads
+    L = workloads.Layer("t", 2, 32, 16, 12, 12, seed=23)
+    X, g = workloads.make_inputs(L)
+    for m in (4, 6):
+        BT, G, AT = oracle.cook_toom(m, dtype=np.float32)
+        sc = oracle.calibrate(X, g, BT, G, AT)
+        xq = oracle.quantize_tensor(X, sc["s_x"])
+        ref = oracle.conv2d_direct_f64(xq.astype(np.float64) * sc["s_x"], g)
+        e_tensor = _rel(oracle.winograd_q(xq, g, BT, G, AT, sc)["Yq"] * np.float64(sc["s_y"]), ref)
+        scp = oracle.calibrate_pos(X, g, BT, G, AT)
+        out = oracle.winograd_q(xq, g, BT, G, AT, scp)
+        assert out["inexact"] == 0 and np.abs(out["Yq"]).max() == 127
+        e_pos = _rel(out["Yq"] * np.float64(scp["s_y"]), ref)
+        assert e_pos < 0.75 * e_tensor, (m, e_pos, e_tensor)
+    BT, G, AT = oracle.cook_toom(4, dtype=np.float32)
+    errs = []
+    for qmax in (127, 2 ** 12, 2 ** 20):
+        scp = oracle.calibrate_pos(X, g, BT, G, AT, qmax=qmax)
+        xq = oracle.quantize_tensor(X, scp["s_x"], qmax)
+        out = oracle.winograd_q(xq, g, BT, G, AT, scp, qmax=qmax)
+        ref = oracle.winograd_f64(xq.astype(np.float64) * scp["s_x"], g, BT, G, AT)
+        errs.append(_rel(out["Yq"].astype(np.float64) * scp["s_y"], ref))
+    assert errs[0] > errs[1] > errs[2] and errs[2] < 1e-4
