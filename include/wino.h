@@ -82,6 +82,16 @@ typedef struct {
 typedef struct {
   float s_x, s_v, s_u, s_y, s_m;
   int qmax;         /* 1..127 */
+  /* Optional finer granularity (Sec. 6: "other types of quantization would likely help"):
+   * one scale per Winograd position p = i*n + j for the transformed input and the
+   * transformed weights, HOST arrays of n*n floats, both or neither (NULL).  When given,
+   * s_v and s_u are ignored, Vq[p] = sat(rne(V[p] * s_x / s_v_pos[p])),
+   * Uq[p] = sat(rne(U[p] / s_u_pos[p])), and every accumulator is brought to real units
+   * before the output transform, Mf[p] = (float)M[p] * (s_u_pos[p] * s_v_pos[p]), so that
+   * y_q = sat(rne(Yt / s_y)) (with the Hadamard-stage quantizer: Mq = sat(rne(Mf / s_m)),
+   * y_q = sat(rne(Yt * s_m / s_y))).  The forward then runs as three kernels. */
+  const float* s_v_pos;
+  const float* s_u_pos;
 } wino_quant;
 
 const char* wino_status_string(wino_status s);

@@ -33,7 +33,8 @@ class WinoDesc(ctypes.Structure):
 
 class WinoQuant(ctypes.Structure):
     _fields_ = [("s_x", ctypes.c_float), ("s_v", ctypes.c_float), ("s_u", ctypes.c_float),
-                ("s_y", ctypes.c_float), ("s_m", ctypes.c_float), ("qmax", ctypes.c_int)]
+                ("s_y", ctypes.c_float), ("s_m", ctypes.c_float), ("qmax", ctypes.c_int),
+                ("s_v_pos", ctypes.c_void_p), ("s_u_pos", ctypes.c_void_p)]
 
 
 class WinoError(RuntimeError):
@@ -132,8 +133,16 @@ class Desc:
         return ctypes.byref(self.c)
 
 
-def make_quant(s_x, s_v, s_u, s_y, s_m=0.0, qmax=127):
-    return WinoQuant(s_x, s_v, s_u, s_y, s_m, qmax)
+def make_quant(s_x, s_v, s_u, s_y, s_m=0.0, qmax=127, s_v_pos=None, s_u_pos=None):
+    """wino_quant; with s_v_pos / s_u_pos (one scale per Winograd position, host arrays)
+    s_v and s_u are ignored.  The arrays are kept alive by the returned object."""
+    q = WinoQuant(s_x, s_v, s_u, s_y, s_m, qmax, None, None)
+    if s_v_pos is not None or s_u_pos is not None:
+        q._sv = np.ascontiguousarray(s_v_pos, dtype=np.float32)
+        q._su = np.ascontiguousarray(s_u_pos, dtype=np.float32)
+        q.s_v_pos = q._sv.ctypes.data
+        q.s_u_pos = q._su.ctypes.data
+    return q
 
 
 def wino_weights_bytes(desc):

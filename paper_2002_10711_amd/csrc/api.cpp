@@ -56,9 +56,20 @@ size_t u_bytes(const Geom& g) { return align256((size_t)g.P * g.Kp * g.Cp * (g.i
 wino_status check_quant(const Geom& g, const wino_quant* q) {
   if (!g.i8) return WINO_OK;
   if (!q) return WINO_E_BAD_SCALE;
-  const float s[4] = {q->s_x, q->s_v, q->s_u, q->s_y};
-  for (float v : s)
-    if (!isfinite(v) || !(v > 0.0f)) return WINO_E_BAD_SCALE;
+  if ((q->s_v_pos != nullptr) != (q->s_u_pos != nullptr)) return WINO_E_BAD_SCALE;
+  if (q->s_v_pos) {
+    // per-position scales replace s_v and s_u
+    if (!isfinite(q->s_x) || !(q->s_x > 0.0f) || !isfinite(q->s_y) || !(q->s_y > 0.0f))
+      return WINO_E_BAD_SCALE;
+    for (int p = 0; p < g.P; ++p)
+      if (!isfinite(q->s_v_pos[p]) || !(q->s_v_pos[p] > 0.0f) || !isfinite(q->s_u_pos[p]) ||
+          !(q->s_u_pos[p] > 0.0f))
+        return WINO_E_BAD_SCALE;
+  } else {
+    const float s[4] = {q->s_x, q->s_v, q->s_u, q->s_y};
+    for (float v : s)
+      if (!isfinite(v) || !(v > 0.0f)) return WINO_E_BAD_SCALE;
+  }
   if (!isfinite(q->s_m) || q->s_m < 0.0f) return WINO_E_BAD_SCALE;
   if (q->qmax < 1 || q->qmax > 127) return WINO_E_BAD_SCALE;
   return WINO_OK;
@@ -67,10 +78,38 @@ wino_status check_quant(const Geom& g, const wino_quant* q) {
 // fp32 multipliers of the quantized pipeline, derived on the host:
 //   r_u = 1/s_u, r_v = s_x/s_v, r_m = (s_u s_v)/s_m, r_y = (s_u s_v)/s_y  (s_m/s_y if the
 //   quantizer after the Hadamard stage is on).
-struct Scalars { float r_u, r_v, r_m, r_y, qmax; };
+// With per-position scales (pos): r_u[p] = 1/s_u[p], r_v[p] = s_x/s_v[p],
+//   w[p] = s_u[p] s_v[p] (applied to the accumulators), r_m = 1/s_m, r_y = 1/s_y (s_m/s_y).
+struct Scalars {
+  float r_u, r_v, r_m, r_y, qmax;
+  bool pos;
+  PosScale ru_pos, rv_pos, w_pos;
+};
 Scalars make_scalars(const Geom& g, const wino_quant* q) {
-  Scalars s = {1.0f, 1.0f, 0.0f, 1.0f, 127.0f};
+  Scalars s;
+  memset(&s, 0, sizeof s);
+  s.r_u = s.r_v = s.r_y = 1.0f;
+  s.qmax = 127.0f;
   if (!g.i8) return s;
+  if (q->s_v_pos) {
+    s.pos = true;
+    s.qmax = (float)q->qmax;
+    for (int p = 0; p < g.P; ++p) {
+      volatile float w = q->s_u_pos[p] * q->s_v_pos[p];   // one rounded fp32 product
+      s.ru_pos.r[p] = 1.0f / q->s_u_pos[p];
+      s.rv_pos.r[p] = q->s_x / q->s_v_pos[p];
+      s.w_pos.r[p] = w;
+    }
+    if (q->s_m > 0.0f) {
+      s.r_m = 1.0f / q->s_m;
+      s.r_y = q->s_m / q->s_y;
+    } else {
+      s.r_y = 1.0f / q->s_y;
+    }
+    s.r_u = s.ru_pos.r[0];
+    s.r_v = s.rv_pos.r[0];
+    return s;
+  }
   volatile float suv = q->s_u * q->s_v;  // one rounded fp32 product, never contracted
   s.r_u = 1.0f / q->s_u;
   s.r_v = q->s_x / q->s_v;
@@ -130,8 +169,8 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, cons
   memset(&mg, 0, sizeof mg);
   memcpy(mg.v, d->G, sizeof(float) * g.n * 3);
   const Scalars s = make_scalars(g, q);
-  if (launch_weight_transform(g, mg, g_dev, U_dev, s.r_u, s.qmax, (hipStream_t)stream) !=
-      hipSuccess)
+  if (launch_weight_transform(g, mg, g_dev, U_dev, s.r_u, s.qmax, (hipStream_t)stream,
+                              s.pos ? &s.ru_pos : nullptr) != hipSuccess)
     return WINO_E_HIP;
   return WINO_OK;
 }
@@ -174,7 +213,7 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
     memset(&at, 0, sizeof at);
     memcpy(at.v, d->AT, sizeof(float) * g.m * g.n);
   }
-  if (stages == WINO_STAGE_ALL && fused_fwd_supported(g)) {
+  if (stages == WINO_STAGE_ALL && !s.pos && fused_fwd_supported(g)) {
     // the whole forward in one kernel: V and M stay on chip, the workspace is untouched
     const hipError_t e =
         fused_fwd_exact_supported(g, bt)
@@ -185,22 +224,26 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
   if (stages == WINO_STAGE_ALL && fused_fwd_f32_supported(g))
     return launch_fused_fwd_f32(g, bt, at, x_dev, U_dev, y_dev, hs) == hipSuccess ? WINO_OK
                                                                                   : WINO_E_HIP;
+  const PosScale* rvp = s.pos ? &s.rv_pos : nullptr;
+  const PosScale* wp = s.pos ? &s.w_pos : nullptr;
   if (s_in && (input_exact_preferred(g, bt, x_dev)
-                   ? launch_input_exact(g, bt, x_dev, V, s.r_v, s.qmax, hs)
-                   : launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs)) != hipSuccess)
+                   ? launch_input_exact(g, bt, x_dev, V, s.r_v, s.qmax, hs, rvp)
+                   : launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs, rvp)) != hipSuccess)
     return WINO_E_HIP;
-  if (s_mm && s_out && gemm_out_preferred(g)) {
+  // (per-position scales: the accumulators need their factors before the output
+  // transform, which only the stand-alone output kernel applies)
+  if (s_mm && s_out && !s.pos && gemm_out_preferred(g)) {
     // short reductions: GEMM and output transform in one kernel, M stays in registers
     if (launch_gemm_out(g, at, V, U_dev, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;
   } else if (s_mm && s_out) {
     if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, 1, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
-    if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+    if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs, wp) != hipSuccess)
       return WINO_E_HIP;
   } else if (s_mm) {
     if (launch_gemm(g.P, g.Tp, g.Kp, g.Cp, g.i8, 1, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
   } else if (s_out) {
-    if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+    if (launch_output_transform(g, at, M, y_dev, s.r_m, s.r_y, s.qmax, hs, wp) != hipSuccess)
       return WINO_E_HIP;
   }
   return WINO_OK;

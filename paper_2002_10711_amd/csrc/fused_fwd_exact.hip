@@ -329,8 +329,8 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 // rows of V between T and Tp are never read by anything that reaches the output.
 template <int M, int kTWB>
 __global__ __launch_bounds__(256) void input_transform_exact_kernel(
-    const int8_t* __restrict__ x, int8_t* __restrict__ V, float r_vs, float qmax, Geom g, XPlan pl,
-    KronW kw) {
+    const int8_t* __restrict__ x, int8_t* __restrict__ V, PosScale rvs, float qmax, Geom g,
+    XPlan pl, KronW kw) {
   constexpr int n = M + 2, P = n * n;
   constexpr int NBLK = (P + 15) / 16, NSTEP = 16 * NBLK;
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
@@ -345,6 +345,11 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
   const float lo = kMagic - qmax, hi = kMagic + qmax;
 
   stage_planes<M, 2, kTWB>(g, pl, x, Xs, cb * 64, r0, tw0);    // aligned 8-byte loads only
+  // quantizer factor of the positions this lane produces (p = blk*16 + r): one per
+  // position, all equal for a per-tensor scale
+  float rq[NBLK];
+#pragma unroll
+  for (int blk = 0; blk < NBLK; ++blk) rq[blk] = rvs.r[blk * 16 + r < P ? blk * 16 + r : P - 1];
   v4i Wb[NBLK];
 #pragma unroll
   for (int blk = 0; blk < NBLK; ++blk) Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
@@ -391,7 +396,7 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
     uint32_t packed = 0u;
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr)
-      packed = __builtin_amdgcn_perm(quantize_bits((float)cur[rr], r_vs, lo, hi), packed, 0x04030201u);
+      packed = __builtin_amdgcn_perm(quantize_bits((float)cur[rr], rq[blk], lo, hi), packed, 0x04030201u);
     const int tl = wave * 4 + (gi >> 2);
     if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
     cur = nxt;
@@ -532,16 +537,23 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
 
 template <int M>
 hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
-                          float qmax, hipStream_t s) {
+                          float qmax, hipStream_t s, const PosScale* rv_pos) {
   XLaunch xl;
   if (!make_xlaunch<M>(g, bt, x, r_v, &xl) || g.Cp / 64 > 65535) return hipErrorInvalidValue;
+  // per-position factors, each scaled by 4^-s like the per-tensor one (exact, or refuse)
+  PosScale rvs;
+  const float sc = r_v / xl.r_vs;                        // 4^s, exactly
+  for (int p = 0; p < 64; ++p) {
+    rvs.r[p] = rv_pos ? rv_pos->r[p] / sc : xl.r_vs;
+    if (rv_pos && p < (M + 2) * (M + 2) && !(rvs.r[p] * sc == rv_pos->r[p])) return hipErrorInvalidValue;
+  }
   dim3 grid((unsigned)xl.nrb, (unsigned)xl.ntwb, (unsigned)(g.Cp / 64));
   const int8_t* xi = (const int8_t*)x;
   int8_t* Vi = (int8_t*)V;
   const int TWB = xl.pl.TWB, RB = xl.pl.RB;
 #define WINO_LAUNCH_IN(TWBC)                                                               \
   input_transform_exact_kernel<M, TWBC><<<grid, 256, xl.lds_bytes, s>>>(                     \
-      xi, Vi, xl.r_vs, qmax, g, xl.pl, xl.kw)
+      xi, Vi, rvs, qmax, g, xl.pl, xl.kw)
   if (xl.load != 2) return hipErrorInvalidValue;         // see input_exact_preferred
   if (RB * TWB == 16 && TWB == 16) WINO_LAUNCH_IN(16);
   else if (RB * TWB == 16 && TWB == 8) WINO_LAUNCH_IN(8);
@@ -607,9 +619,9 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
 }  // namespace
 
 hipError_t launch_input_exact(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
-                              float qmax, hipStream_t s) {
-  if (g.m == 2) return launch_input_m<2>(g, bt, x, V, r_v, qmax, s);
-  if (g.m == 4) return launch_input_m<4>(g, bt, x, V, r_v, qmax, s);
+                              float qmax, hipStream_t s, const PosScale* rv_pos) {
+  if (g.m == 2) return launch_input_m<2>(g, bt, x, V, r_v, qmax, s, rv_pos);
+  if (g.m == 4) return launch_input_m<4>(g, bt, x, V, r_v, qmax, s, rv_pos);
   return hipErrorInvalidValue;
 }
 

@@ -156,10 +156,12 @@ __device__ __forceinline__ void load_quad_patch(const uint32_t* src, int Wc,
     for (int l = 0; l < n; ++l) raw[j][l] = src[(j * Wc + l) * CBQ];
 }
 
-template <int M, bool kSparse>
+// kPos: one quantizer factor per Winograd position (rvp.r[p]) instead of r_v.
+template <int M, bool kSparse, bool kPos = false>
 __device__ __forceinline__ void transform_raw(uint32_t (&raw)[M + 2][M + 2], const MatBT& bt,
                                               float r_v, float lo, float hi,
-                                              uint32_t (&out)[(M + 2) * (M + 2)]) {
+                                              uint32_t (&out)[(M + 2) * (M + 2)],
+                                              const PosScale* rvp = nullptr) {
   constexpr int n = M + 2, P = n * n;
 #pragma unroll
   for (int p = 0; p < P; ++p) out[p] = 0u;
@@ -182,19 +184,20 @@ __device__ __forceinline__ void transform_raw(uint32_t (&raw)[M + 2][M + 2], con
     for (int i = 0; i < n; ++i)
 #pragma unroll
       for (int k = 0; k < n; ++k) {
-        const uint32_t bits = quantize_bits(Vt[i][k], r_v, lo, hi);
+        const uint32_t bits = quantize_bits(Vt[i][k], kPos ? rvp->r[i * n + k] : r_v, lo, hi);
         out[i * n + k] = __builtin_amdgcn_perm(bits, out[i * n + k], 0x04030201u);
       }
   }
 }
 
-template <int M, bool kSparse>
+template <int M, bool kSparse, bool kPos = false>
 __device__ __forceinline__ void transform_quad(const uint32_t* src, int Wc, const MatBT& bt,
                                                float r_v, float lo, float hi,
-                                               uint32_t (&out)[(M + 2) * (M + 2)]) {
+                                               uint32_t (&out)[(M + 2) * (M + 2)],
+                                               const PosScale* rvp = nullptr) {
   uint32_t raw[M + 2][M + 2];
   load_quad_patch<M>(src, Wc, raw);
-  transform_raw<M, kSparse>(raw, bt, r_v, lo, hi, out);
+  transform_raw<M, kSparse, kPos>(raw, bt, r_v, lo, hi, out, rvp);
 }
 
 #endif  // __HIPCC__

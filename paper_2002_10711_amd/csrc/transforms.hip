@@ -12,6 +12,8 @@
 //
 // The matrices arrive by value in the kernel arguments (scalar registers), never
 // as compiled-in constants, so learned transforms use the same code.
+#include <string.h>
+
 #include "input_stage.h"
 #include "output_stage.h"
 
@@ -21,11 +23,13 @@ namespace {
 // ------------------------------------------------------------------ input --
 // Stand-alone int8 input transform (see input_stage.h): V[p][t][c] to global memory,
 // a wavefront storing 256 contiguous bytes per position.
-template <int M, bool kSparse, bool kWide>
+// kPos: per-position quantizer factors rvp (else the one factor r_v).
+template <int M, bool kSparse, bool kWide, bool kPos>
 __global__ __launch_bounds__(256) void input_transform_i8(Geom g, MatBT bt,
                                                           const int8_t* __restrict__ x,
                                                           uint32_t* __restrict__ V, float r_v,
-                                                          float qmax, int RB, int TWB) {
+                                                          float qmax, int RB, int TWB,
+                                                          PosScale rvp) {
   constexpr int n = M + 2, P = n * n, CBQ = InCfg<M>::kCBQ;
   extern __shared__ uint32_t lds[];
   const int Wc = stage_cols(M, TWB);
@@ -44,8 +48,8 @@ __global__ __launch_bounds__(256) void input_transform_i8(Geom g, MatBT bt,
     const int r = r0 + rs, tw = tw0 + twl;
     if (r >= R || tw >= g.TW) continue;
     uint32_t out[P];
-    transform_quad<M, kSparse>(lds + ((size_t)rs * n * Wc + twl * M) * CBQ + cq, Wc, bt, r_v, lo,
-                               hi, out);
+    transform_quad<M, kSparse, kPos>(lds + ((size_t)rs * n * Wc + twl * M) * CBQ + cq, Wc, bt, r_v,
+                                     lo, hi, out, &rvp);
     uint32_t* vp = V + ((size_t)r * g.TW + tw) * cq_per + (c0 >> 2) + cq;
 #pragma unroll
     for (int p = 0; p < P; ++p) vp[p * pstride] = out[p];
@@ -91,7 +95,7 @@ __global__ __launch_bounds__(256) void input_transform_f32(Geom g, MatBT bt,
 template <int M>
 __global__ __launch_bounds__(256) void weight_transform_i8(Geom g, MatG mg,
                                                            const float* __restrict__ w,
-                                                           uint32_t* __restrict__ U, float r_u,
+                                                           uint32_t* __restrict__ U, PosScale ru,
                                                            float qmax) {
   // One thread per (row i of U, k, channel quad); i is uniform per block (blockIdx.y)
   // so the matrix entries stay in scalar registers.  Splitting the rows over threads
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(256) void weight_transform_i8(Geom g, MatG mg,
           float acc = 0.0f;
 #pragma unroll
           for (int b = 0; b < 3; ++b) acc = __builtin_fmaf(t[b], mg.v[j * 3 + b], acc);
-          const int q = quantize(acc, r_u, qmax);
+          const int q = quantize(acc, ru.r[i * n + j], qmax);   // one factor per position
           out[j] |= (uint32_t)(q & 0xff) << (8 * e);
         }
       }
@@ -172,11 +176,13 @@ __global__ __launch_bounds__(256) void weight_transform_f32(Geom g, MatG mg,
 // Stand-alone output transform, used when M is materialised (layers whose accumulators
 // do not fit the fused kernels, per-stage calls, the parity tap).  One thread per
 // (tile, output channel); lanes run along k so that the reads of M are contiguous.
-template <int M, bool I8, bool kSparse, bool kMQ>
+// kPos: per-position scales -- every accumulator is first brought to real units,
+// (float)M * wp.r[p], before the optional quantizer and the transform.
+template <int M, bool I8, bool kSparse, bool kMQ, bool kPos = false>
 __global__ __launch_bounds__(256) void output_transform(Geom g, MatAT at,
                                                         const void* __restrict__ Mv,
                                                         void* __restrict__ yv, float r_m,
-                                                        float r_y, float qmax) {
+                                                        float r_y, float qmax, PosScale wp) {
   constexpr int n = M + 2;
   const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
   const int t = (int)(item / g.Kp), k = (int)(item % g.Kp);
@@ -190,6 +196,7 @@ __global__ __launch_bounds__(256) void output_transform(Geom g, MatAT at,
     for (int j = 0; j < n; ++j) {
       if (I8) {
         float f = (float)((const int32_t*)Mv)[(i * n + j) * pstride + base];
+        if constexpr (kPos) f = f * wp.r[i * n + j];
         if constexpr (kMQ) f = (float)quantize(f, r_m, qmax);
         Mt[i][j] = f;
       } else {
@@ -239,7 +246,7 @@ unsigned blocks_for(long long items) { return (unsigned)((items + 255) / 256); }
 // about 16 tiles (256 threads x 1 item), LDS kept under 64 KB.
 template <int M, bool kSparse>
 hipError_t launch_input_i8(const Geom& g, const MatBT& bt, const int8_t* x, uint32_t* V, float r_v,
-                           float qmax, hipStream_t s) {
+                           float qmax, hipStream_t s, const PosScale* rv_pos) {
   constexpr int n = M + 2;
   const int R = g.N * g.TH;
   // 16, 8 or 4 tiles per workgroup: the largest that still gives every CU several
@@ -263,20 +270,29 @@ hipError_t launch_input_i8(const Geom& g, const MatBT& bt, const int8_t* x, uint
   while (threads < strip) threads *= 2;
   if (threads > 256) return hipErrorInvalidValue;          // cannot happen for TWB <= 16
   const size_t lb = lds_bytes(RB, TWB);
-  if (g.W >= 4)
-    input_transform_i8<M, kSparse, true><<<grid, threads, lb, s>>>(g, bt, x, V, r_v, qmax, RB, TWB);
-  else
-    input_transform_i8<M, kSparse, false><<<grid, threads, lb, s>>>(g, bt, x, V, r_v, qmax, RB, TWB);
+  PosScale none;
+  memset(&none, 0, sizeof none);
+#define WINO_LAUNCH_IN(WIDE, POS)                                                          \
+  input_transform_i8<M, kSparse, WIDE, POS><<<grid, threads, lb, s>>>(g, bt, x, V, r_v, qmax, RB, \
+                                                                       TWB, POS ? *rv_pos : none)
+  if (g.W >= 4) {
+    if (rv_pos) WINO_LAUNCH_IN(true, true); else WINO_LAUNCH_IN(true, false);
+  } else {
+    if (rv_pos) WINO_LAUNCH_IN(false, true); else WINO_LAUNCH_IN(false, false);
+  }
+#undef WINO_LAUNCH_IN
   return hipGetLastError();
 }
 
 template <int M>
 hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
-                          float qmax, hipStream_t s) {
+                          float qmax, hipStream_t s, const PosScale* rv_pos) {
   const bool sparse = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt);
   if (g.i8) {
-    return sparse ? launch_input_i8<M, true>(g, bt, (const int8_t*)x, (uint32_t*)V, r_v, qmax, s)
-                  : launch_input_i8<M, false>(g, bt, (const int8_t*)x, (uint32_t*)V, r_v, qmax, s);
+    return sparse ? launch_input_i8<M, true>(g, bt, (const int8_t*)x, (uint32_t*)V, r_v, qmax, s,
+                                             rv_pos)
+                  : launch_input_i8<M, false>(g, bt, (const int8_t*)x, (uint32_t*)V, r_v, qmax, s,
+                                              rv_pos);
   }
   const unsigned nb = blocks_for((long long)g.Tp * g.Cp);
   if (sparse)
@@ -289,23 +305,25 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
 }  // namespace
 
 hipError_t launch_input_transform(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
-                                  float qmax, hipStream_t s) {
+                                  float qmax, hipStream_t s, const PosScale* rv_pos) {
   switch (g.m) {
-    case 2: return launch_input_m<2>(g, bt, x, V, r_v, qmax, s);
-    case 4: return launch_input_m<4>(g, bt, x, V, r_v, qmax, s);
-    default: return launch_input_m<6>(g, bt, x, V, r_v, qmax, s);
+    case 2: return launch_input_m<2>(g, bt, x, V, r_v, qmax, s, rv_pos);
+    case 4: return launch_input_m<4>(g, bt, x, V, r_v, qmax, s, rv_pos);
+    default: return launch_input_m<6>(g, bt, x, V, r_v, qmax, s, rv_pos);
   }
 }
 
 hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w, void* U, float r_u,
-                                   float qmax, hipStream_t s) {
+                                   float qmax, hipStream_t s, const PosScale* ru_pos) {
   if (g.i8) {
+    PosScale ru;                                       // per-tensor: the same factor everywhere
+    for (int p = 0; p < 64; ++p) ru.r[p] = ru_pos ? ru_pos->r[p] : r_u;
     const unsigned nb = blocks_for((long long)g.Kp * (g.Cp / 4));
     uint32_t* Uo = (uint32_t*)U;
     switch (g.m) {
-      case 2: weight_transform_i8<2><<<dim3(nb, 4), 256, 0, s>>>(g, mg, w, Uo, r_u, qmax); break;
-      case 4: weight_transform_i8<4><<<dim3(nb, 6), 256, 0, s>>>(g, mg, w, Uo, r_u, qmax); break;
-      default: weight_transform_i8<6><<<dim3(nb, 8), 256, 0, s>>>(g, mg, w, Uo, r_u, qmax); break;
+      case 2: weight_transform_i8<2><<<dim3(nb, 4), 256, 0, s>>>(g, mg, w, Uo, ru, qmax); break;
+      case 4: weight_transform_i8<4><<<dim3(nb, 6), 256, 0, s>>>(g, mg, w, Uo, ru, qmax); break;
+      default: weight_transform_i8<6><<<dim3(nb, 8), 256, 0, s>>>(g, mg, w, Uo, ru, qmax); break;
     }
   } else {
     const unsigned nb = blocks_for((long long)g.Kp * g.Cp);
@@ -374,46 +392,50 @@ hipError_t launch_output_quad(const Geom& g, const MatAT& at, const void* Mv, vo
 namespace {
 template <int M, bool I8>
 hipError_t launch_output_m(const Geom& g, const MatAT& at, const void* Mv, void* y, float r_m,
-                           float r_y, float qmax, hipStream_t s) {
+                           float r_y, float qmax, hipStream_t s, const PosScale* w_pos) {
   const unsigned nb = blocks_for((long long)g.T * g.Kp);
   const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
-  if (I8 && r_m > 0.0f) {
-    if (sparse)
-      output_transform<M, I8, true, I8><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
-    else
-      output_transform<M, I8, false, I8><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+  const bool mq = I8 && r_m > 0.0f;
+  PosScale none;
+  memset(&none, 0, sizeof none);
+#define WINO_LAUNCH_OUT(SP, MQ, POS)                                                         \
+  output_transform<M, I8, SP, MQ, POS><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax,        \
+                                                          POS ? *w_pos : none)
+  if (I8 && w_pos) {
+    if (mq) { if (sparse) WINO_LAUNCH_OUT(true, I8, I8); else WINO_LAUNCH_OUT(false, I8, I8); }
+    else    { if (sparse) WINO_LAUNCH_OUT(true, false, I8); else WINO_LAUNCH_OUT(false, false, I8); }
+  } else if (mq) {
+    if (sparse) WINO_LAUNCH_OUT(true, I8, false); else WINO_LAUNCH_OUT(false, I8, false);
   } else {
-    if (sparse)
-      output_transform<M, I8, true, false><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
-    else
-      output_transform<M, I8, false, false><<<nb, 256, 0, s>>>(g, at, Mv, y, r_m, r_y, qmax);
+    if (sparse) WINO_LAUNCH_OUT(true, false, false); else WINO_LAUNCH_OUT(false, false, false);
   }
+#undef WINO_LAUNCH_OUT
   return hipGetLastError();
 }
 }  // namespace
 
 hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M, void* y, float r_m,
-                                   float r_y, float qmax, hipStream_t s) {
+                                   float r_y, float qmax, hipStream_t s, const PosScale* w_pos) {
   // four channels per lane: needs 32-bit lane offsets, and enough workgroups (16 tiles x
   // 64 channels each) for one per compute unit; below that the thread-per-(tile,
   // channel) kernel spreads the work further
-  const bool quad = (unsigned long long)g.Tp * g.Kp * 4 < 0x100000000ull &&
+  const bool quad = !w_pos && (unsigned long long)g.Tp * g.Kp * 4 < 0x100000000ull &&
                     (long long)(g.Tp / 16) * (g.Kp / 64) >= 256;
   if (g.i8) {
     switch (g.m) {
       case 2: return quad ? launch_output_quad<2, true>(g, at, M, y, r_m, r_y, qmax, s)
-                          : launch_output_m<2, true>(g, at, M, y, r_m, r_y, qmax, s);
+                          : launch_output_m<2, true>(g, at, M, y, r_m, r_y, qmax, s, w_pos);
       case 4: return quad ? launch_output_quad<4, true>(g, at, M, y, r_m, r_y, qmax, s)
-                          : launch_output_m<4, true>(g, at, M, y, r_m, r_y, qmax, s);
-      default: return launch_output_m<6, true>(g, at, M, y, r_m, r_y, qmax, s);
+                          : launch_output_m<4, true>(g, at, M, y, r_m, r_y, qmax, s, w_pos);
+      default: return launch_output_m<6, true>(g, at, M, y, r_m, r_y, qmax, s, w_pos);
     }
   }
   switch (g.m) {
     case 2: return quad ? launch_output_quad<2, false>(g, at, M, y, r_m, r_y, qmax, s)
-                        : launch_output_m<2, false>(g, at, M, y, r_m, r_y, qmax, s);
+                        : launch_output_m<2, false>(g, at, M, y, r_m, r_y, qmax, s, w_pos);
     case 4: return quad ? launch_output_quad<4, false>(g, at, M, y, r_m, r_y, qmax, s)
-                        : launch_output_m<4, false>(g, at, M, y, r_m, r_y, qmax, s);
-    default: return launch_output_m<6, false>(g, at, M, y, r_m, r_y, qmax, s);
+                        : launch_output_m<4, false>(g, at, M, y, r_m, r_y, qmax, s, w_pos);
+    default: return launch_output_m<6, false>(g, at, M, y, r_m, r_y, qmax, s, w_pos);
   }
 }
 

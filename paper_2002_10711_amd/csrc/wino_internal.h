@@ -24,6 +24,7 @@ struct Geom {
 struct MatBT { float v[64]; };   // n x n, row-major, n <= 8
 struct MatG  { float v[24]; };   // n x 3
 struct MatAT { float v[48]; };   // m x n, m <= 6
+struct PosScale { float r[64]; };   // one factor per Winograd position (n*n <= 64)
 
 inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
 
@@ -41,17 +42,22 @@ __host__ __device__ inline size_t u_byte_index(int Kp, int Cp, int esz, int p, i
 }
 
 // Kernel launchers (each enqueues on `s` and returns hipGetLastError()).
+// (the optional PosScale arguments switch a stage to per-position factors: r_v[p], r_u[p],
+// and w[p] = s_u[p] * s_v[p] applied to the accumulators before the output transform)
 hipError_t launch_input_transform(const Geom& g, const MatBT& bt, const void* x, void* V,
-                                  float r_v, float qmax, hipStream_t s);
+                                  float r_v, float qmax, hipStream_t s,
+                                  const PosScale* rv_pos = nullptr);
 hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w, void* U,
-                                   float r_u, float qmax, hipStream_t s);
+                                   float r_u, float qmax, hipStream_t s,
+                                   const PosScale* ru_pos = nullptr);
 // Batched GEMM  M[p][t][k] = sum_c A[p][t][c] * B[p][k][c]; rows padded as above.
 // Used with P = n*n for the Winograd domain and P = 1 for the im2row baseline.
 // b_blocked: B is in the block layout of u_byte_index.
 hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, int b_blocked, const void* A,
                        const void* B, void* M, hipStream_t s);
 hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M, void* y,
-                                   float r_m, float r_y, float qmax, hipStream_t s);
+                                   float r_m, float r_y, float qmax, hipStream_t s,
+                                   const PosScale* w_pos = nullptr);
 // GEMM and output transform in one kernel (M stays in registers, operands straight
 // from global memory): preferred while the reduction is short and the n*n accumulator
 // sets leave room for two wavefronts per SIMD.
@@ -77,7 +83,7 @@ bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt);
 bool input_exact_supported(const Geom& g, const MatBT& bt);
 bool input_exact_preferred(const Geom& g, const MatBT& bt, const void* x);
 hipError_t launch_input_exact(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
-                              float qmax, hipStream_t s);
+                              float qmax, hipStream_t s, const PosScale* rv_pos = nullptr);
 hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                                   const void* U, void* y, float r_v, float r_m, float r_y,
                                   float qmax, hipStream_t s);

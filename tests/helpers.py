@@ -32,8 +32,9 @@ def run_gpu(case, taps=True, scales=None):
     quant = None
     if i8:
         sc = scales or case["scales"]
-        quant = wb.make_quant(sc["s_x"], sc["s_v"], sc["s_u"], sc["s_y"], sc.get("s_m", 0.0),
-                              sc.get("qmax", 127))
+        quant = wb.make_quant(sc["s_x"], sc.get("s_v", 1.0), sc.get("s_u", 1.0), sc["s_y"],
+                              sc.get("s_m", 0.0), sc.get("qmax", 127),
+                              s_v_pos=sc.get("s_v_pos"), s_u_pos=sc.get("s_u_pos"))
     x = torch.from_numpy(case["xq"] if i8 else case["X"]).to(dev)
     g = torch.from_numpy(case["g"]).to(dev)
     U = torch.empty(wb.wino_weights_bytes(desc), dtype=torch.uint8, device=dev)

@@ -170,3 +170,25 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in (r.stderr + r.stdout)
+
+
+def test_per_position_scale_argument_checks(L):
+    """Both per-position arrays or neither; every entry finite and positive -- checked
+    before any HIP call."""
+    import ctypes
+    import numpy as np
+    from paper_2002_10711_amd import binding as wb
+    BT, G, AT = wb.wino_cook_toom(4)
+    d = wb.Desc(1, 8, 8, 8, 8, 1, 4, wb.WINO_I8, BT=BT, G=G, AT=AT)
+    fake = ctypes.c_void_p(256)          # never dereferenced: the checks come first
+    ok = np.full(36, 0.5, np.float32)
+    q = wb.make_quant(0.1, 1.0, 1.0, 0.2, s_v_pos=ok, s_u_pos=ok)
+    q.s_u_pos = None                                      # only one of the two
+    assert L.wino_transform_weights(d.ref, ctypes.byref(q), fake, fake, None) == -5
+    bad = ok.copy()
+    bad[7] = 0.0
+    q = wb.make_quant(0.1, 1.0, 1.0, 0.2, s_v_pos=ok, s_u_pos=bad)
+    assert L.wino_transform_weights(d.ref, ctypes.byref(q), fake, fake, None) == -5
+    bad[7] = np.inf
+    q = wb.make_quant(0.1, 1.0, 1.0, 0.2, s_v_pos=bad, s_u_pos=ok)
+    assert L.wino_transform_weights(d.ref, ctypes.byref(q), fake, fake, None) == -5

@@ -137,6 +137,28 @@ def test_many_tiles_ragged_flex_and_m_quantizer(oracle, m):
     _check_f32(oracle, case, run_gpu(case))
 
 
+@pytest.mark.parametrize("layer", [
+    Layer("pos_f4", 3, 40, 70, 16, 16, m=4, seed=131),            # matrix-core input stage
+    Layer("pos_f2_ragged", 2, 20, 24, 9, 11, m=2, seed=132),      # vector-ALU input stage
+    Layer("pos_f6", 2, 12, 33, 14, 14, m=6, seed=133),
+    Layer("pos_f4_flex", 2, 24, 40, 10, 10, m=4, flex_sigma=0.05, seed=134),
+], ids=lambda l: l.name)
+def test_per_position_scales_all_taps(oracle, layer):
+    """One quantizer scale per Winograd position for V and U (Sec. 6), calibrated by the
+    oracle; every tap bit-exact; then the same with the Hadamard-stage quantizer on."""
+    case = make_case(oracle, layer, with_oracle=False)
+    sc = oracle.calibrate_pos(case["X"], case["g"], case["BT"], case["G"], case["AT"], pad=layer.pad)
+    case["xq"] = oracle.quantize_tensor(case["X"], sc["s_x"]).astype(np.int8)
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc,
+                                    pad=layer.pad)
+    assert np.abs(case["ref"]["Vq"]).reshape(case["ref"]["Vq"].shape[0], -1).max(axis=1).min() >= 100
+    _check_i8(case, run_gpu(case, scales=sc))
+    sc = dict(sc, s_m=float(np.abs(case["ref"]["M"] * case["ref"]["scalars"]["w"][:, None, None]).max()) / 100.0)
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc,
+                                    pad=layer.pad)
+    _check_i8(case, run_gpu(case, scales=sc))
+
+
 def test_config2_int8_full(oracle):
     case = make_case(oracle, workloads.config2("i8")[0])
     _check_i8(case, run_gpu(case))
