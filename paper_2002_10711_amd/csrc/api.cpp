@@ -228,6 +228,8 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
   const PosScale* wp = s.pos ? &s.w_pos : nullptr;
   if (s_in && (input_exact_preferred(g, bt, x_dev)
                    ? launch_input_exact(g, bt, x_dev, V, s.r_v, s.qmax, hs, rvp)
+               : input_f32_staged_supported(g)
+                   ? launch_input_f32_staged(g, bt, x_dev, V, hs)
                    : launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs, rvp)) != hipSuccess)
     return WINO_E_HIP;
   // (per-position scales: the accumulators need their factors before the output

@@ -280,6 +280,70 @@ __global__ __launch_bounds__(512) void fused_fwd_f32_kernel(const float* __restr
   WINO_TSF(5);
 }
 
+// The fp32 input stage alone (V to memory, for the unfused sequences): the same staging
+// and per-(tile, channel) transform as the producers above, one 16-channel block per
+// workgroup.  Grid: x = blocks of RB tile rows, y = blocks of TWB tiles, z = Cp / 16.
+template <int M, bool kSparse>
+__global__ __launch_bounds__(256) void input_transform_f32_staged(const float* __restrict__ x,
+                                                                  float* __restrict__ V, Geom g,
+                                                                  FPlan pl, MatBT bt) {
+  constexpr int n = M + 2, P = n * n, CB = 16;
+  extern __shared__ __attribute__((aligned(16))) float ldsf[];
+  float* Xs = ldsf;                                    // [16 channels][plane]
+  int* rowinfo = (int*)(ldsf + CB * pl.plane);         // [rows]
+  const int RB = pl.RB, TWB = pl.TWB, Wc = pl.Wc, rows = pl.rows, plane = pl.plane;
+  const int r0 = blockIdx.x * RB, tw0 = blockIdx.y * TWB, cbase = blockIdx.z * CB;
+  const int R = g.N * g.TH, HW = g.H * g.W;
+  const int tid = threadIdx.x;
+  if (tid < rows) {
+    const int rs = tid / n, j = tid - rs * n;
+    const int rr = r0 + rs;
+    const int rc = rr < R ? rr : R - 1;
+    const int img = (int)fast_div(rc, pl.inv_th), th = rc - img * g.TH;
+    const int h = th * M - g.pad + j;
+    rowinfo[tid] = (rr < R && h >= 0 && h < g.H) ? (img * g.C * g.H + h) * g.W : -1;
+  }
+  __syncthreads();
+  const int wbase = tw0 * M - g.pad;
+  const float* xb = x + (size_t)cbase * HW;
+  constexpr int kBatch = 8;
+  for (int i0 = 0; i0 < pl.iters; i0 += kBatch) {
+    float v[kBatch];
+    int dst[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int e = tid + (i0 + u) * 256;
+      const int ec = e < pl.total ? e : pl.total - 1;
+      const int rowidx = (int)fast_div(ec, pl.inv_wc), col = ec - rowidx * Wc;
+      const int c = (int)fast_div(rowidx, pl.inv_rows), rj = rowidx - c * rows;
+      const int info = rowinfo[rj];
+      const int w = wbase + col;
+      const bool ok = info >= 0 && w >= 0 && w < g.W && cbase + c < g.C;
+      const float f = xb[ok ? info + c * HW + w : 0];
+      v[u] = ok ? f : 0.0f;
+      dst[u] = c * plane + rj * Wc + col;              // surplus lanes repeat the last element
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) Xs[dst[u]] = v[u];
+  }
+  __syncthreads();
+  const int c2 = tid & 15, tl = tid >> 4;
+  const int rs2 = (int)fast_div(tl, pl.inv_twb), twl2 = tl - rs2 * TWB;
+  const int rr = r0 + rs2, tw = tw0 + twl2;
+  if (rs2 >= RB || rr >= R || tw >= g.TW) return;
+  const float* patch = Xs + c2 * plane + (rs2 * n) * Wc + twl2 * M;
+  float d[n][n], Vt[n][n];
+#pragma unroll
+  for (int j = 0; j < n; ++j)
+#pragma unroll
+    for (int l = 0; l < n; ++l) d[j][l] = patch[j * Wc + l];
+  transform_patch<M, kSparse>(d, bt, Vt);
+  const size_t pstride = (size_t)g.Tp * g.Cp;
+  float* vp = V + ((size_t)rr * g.TW + tw) * g.Cp + cbase + c2;
+#pragma unroll
+  for (int p = 0; p < P; ++p) vp[p * pstride] = Vt[p / n][p % n];
+}
+
 // Launch plan and dynamic LDS size; false if the shape does not fit the kernel's limits.
 bool make_fplan(const Geom& g, FPlan* plp, size_t* lds_bytes, int* nrb, int* ntwb) {
   FPlan& pl = *plp;
@@ -301,10 +365,27 @@ bool make_fplan(const Geom& g, FPlan* plp, size_t* lds_bytes, int* nrb, int* ntw
   *lds_bytes = lds_floats * 4;
   *ntwb = (g.TW + pl.TWB - 1) / pl.TWB;
   *nrb = (R + pl.RB - 1) / pl.RB;
-  // 32 = kMaxIters of the kernel; the packed LDS index has 16 bits; 160 KB of LDS per
-  // workgroup on gfx950
+  // 32 = the largest kIters of the fused kernel; its packed LDS index has 16 bits;
+  // 160 KB of LDS per workgroup on gfx950
   return lds_floats <= 65536 && *lds_bytes <= 160 * 1024 && *ntwb <= 65535 &&
          g.Kp / 64 <= 65535 && pl.rows <= 256 && pl.iters <= 32;
+}
+
+template <int M>
+hipError_t launch_input_staged_m(const Geom& g, const MatBT& bt, const float* x, float* V,
+                                 hipStream_t s) {
+  FPlan pl;
+  size_t lb_fused;
+  int nrb, ntwb;
+  make_fplan(g, &pl, &lb_fused, &nrb, &ntwb);            // the plan itself; limits checked here
+  const size_t lb = ((size_t)16 * pl.plane + pl.rows) * 4;
+  if (lb > 65536 || ntwb > 65535 || g.Cp / 16 > 65535 || pl.rows > 256) return hipErrorInvalidValue;
+  dim3 grid((unsigned)nrb, (unsigned)ntwb, (unsigned)(g.Cp / 16));
+  if (fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt))
+    input_transform_f32_staged<M, true><<<grid, 256, lb, s>>>(x, V, g, pl, bt);
+  else
+    input_transform_f32_staged<M, false><<<grid, 256, lb, s>>>(x, V, g, pl, bt);
+  return hipGetLastError();
 }
 
 template <int M, bool kSparse, bool kFast, int kIters>
@@ -368,6 +449,30 @@ bool fused_fwd_f32_supported(const Geom& g) {
   return !g.i8 && (g.m == 2 || g.m == 4) && g.Kp <= 128 && make_fplan(g, &pl, &lb, &nrb, &ntwb) &&
          (unsigned long long)g.N * g.C * g.H * g.W < 0x7fffffffull &&
          (unsigned long long)g.Kp * g.Cp * 4 < 0xffffffffull && R * g.TH < 0x100000000ull;
+}
+
+bool input_f32_staged_supported(const Geom& g) {
+  // 32-bit element offsets into X, exact reciprocal for the tile row index, LDS within the
+  // default limit (checked again by the launcher)
+  const unsigned long long R = (unsigned long long)g.N * g.TH;
+  FPlan pl;
+  size_t lb;
+  int nrb, ntwb;
+  make_fplan(g, &pl, &lb, &nrb, &ntwb);
+  return !g.i8 && (unsigned long long)g.N * g.C * g.H * g.W < 0x7fffffffull &&
+         R * g.TH < 0x100000000ull && ((size_t)16 * pl.plane + pl.rows) * 4 <= 65536 &&
+         ntwb <= 65535 && g.Cp / 16 <= 65535 && pl.rows <= 256 &&
+         (unsigned long long)pl.total * pl.Wc < 0x100000000ull;
+}
+
+hipError_t launch_input_f32_staged(const Geom& g, const MatBT& bt, const void* x, void* V,
+                                   hipStream_t s) {
+  if (!input_f32_staged_supported(g)) return hipErrorInvalidValue;
+  switch (g.m) {
+    case 2: return launch_input_staged_m<2>(g, bt, (const float*)x, (float*)V, s);
+    case 4: return launch_input_staged_m<4>(g, bt, (const float*)x, (float*)V, s);
+    default: return launch_input_staged_m<6>(g, bt, (const float*)x, (float*)V, s);
+  }
 }
 
 hipError_t launch_fused_fwd_f32(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,

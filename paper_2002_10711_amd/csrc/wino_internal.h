@@ -77,6 +77,10 @@ hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, con
 bool fused_fwd_f32_supported(const Geom& g);
 hipError_t launch_fused_fwd_f32(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                                 const void* U, void* y, hipStream_t s);
+// The fp32 input stage alone, LDS-staged (coalesced row loads); only where supported.
+bool input_f32_staged_supported(const Geom& g);
+hipError_t launch_input_f32_staged(const Geom& g, const MatBT& bt, const void* x, void* V,
+                                   hipStream_t s);
 // The same for F(4x4,3x3) with an exact (dyadic) B^T: input transform on the matrix cores.
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt);
 // The input stage alone with the same exact transform (any number of output channels).
