@@ -309,6 +309,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host "
                     "instead of replaying a captured HIP graph of one step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--flex", type=float, default=0.0, help="perturb the Cook-Toom matrices by "
+                    "seeded N(0, FLEX) noise (dense 'learned' transforms, paper Sec. 3.2): a timing "
+                    "option, the stored scales are not recalibrated")
     ap.add_argument("--cold", action="store_true", help="also time the forward with L2 and "
                     "Infinity Cache evicted before every call (a 1 GiB buffer is overwritten in "
                     "between) and measure the plain-copy HBM rate; adds cold_fwd_ms, "
@@ -322,6 +325,9 @@ def main():
         raise SystemExit("bench.py: this build runs on ONE GPU only (the path needs no exchange "
                          "step; see DESIGN.md for how it would shard); got --gpus %d" % a.gpus)
     L = pick_workload(a.workload)
+    if a.flex > 0:
+        from dataclasses import replace
+        L = replace(L, flex_sigma=a.flex)
     if L.stride != 1:
         raise SystemExit("workload %s is an im2row (stride-2) layer, not a Winograd one" % L.name)
     if a.copy_probe:

@@ -26,11 +26,12 @@ FLAGS = [
 ]
 
 
-# Per-file additions.  The exact fused forward keeps its MFMA results in VGPRs: its
+# Per-file additions.  The int8 fused forwards keep their MFMA results in VGPRs: the
 # accumulators are consumed by VALU code right away, and the AGPR form costs an extra
-# v_accvgpr_read per value.
+# v_accvgpr_read / v_accvgpr_write per value.
 EXTRA_FLAGS = {
     "fused_fwd_exact.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "fused_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

@@ -28,8 +28,13 @@
 namespace wino {
 namespace {
 
-template <int M, bool kSparseB, bool kSparseA, bool kWide, bool kMQ>
-__global__ __launch_bounds__(256) void fused_fwd_i8_kernel(
+// kFast: whole tiles and K % 4 == 0 (branch-free output side, see output_stage.h).
+// kOneBlock: C <= 64, a single channel block; the accumulators then start life at the
+// MFMAs (zero "C" operand) instead of occupying registers during staging and transform.
+// That variant is held to 256 registers per lane, i.e. at least two workgroups per compute
+// unit: one's memory and LDS latencies hide behind the other's arithmetic.
+template <int M, bool kSparseB, bool kSparseA, bool kWide, bool kMQ, bool kFast, bool kOneBlock>
+__global__ __launch_bounds__(256, kOneBlock ? 2 : 1) void fused_fwd_i8_kernel(
     Geom g, MatBT bt, MatAT at, const int8_t* __restrict__ x, const int8_t* __restrict__ U,
     void* __restrict__ y, float r_v, float r_m, float r_y, float qmax, int RB, int TWB) {
   constexpr int n = M + 2, P = n * n, CBQ = InCfg<M>::kCBQ;
@@ -55,10 +60,12 @@ __global__ __launch_bounds__(256) void fused_fwd_i8_kernel(
   const size_t up = (size_t)g.Kp * g.Cp;
 
   v4i acc[P];
+  if constexpr (!kOneBlock) {
 #pragma unroll
-  for (int p = 0; p < P; ++p) acc[p] = v4i{0, 0, 0, 0};
+    for (int p = 0; p < P; ++p) acc[p] = v4i{0, 0, 0, 0};
+  }
 
-  const int nblk = g.Cp >> 6;
+  const int nblk = kOneBlock ? 1 : (g.Cp >> 6);
   for (int cb = 0; cb < nblk; ++cb) {
     if (cb) __syncthreads();                           // previous block's Vl fully consumed
     stage_strips<M, kWide>(g, x, lds, cb * 64, r0, tw0, RB, TWB);
@@ -93,17 +100,20 @@ __global__ __launch_bounds__(256) void fused_fwd_i8_kernel(
       const v4i au = bufU[p % kDepth];
       if (p + kDepth < P) bufU[p % kDepth] = *(const v4i*)(ub + (p + kDepth) * up);
       const v4i bv = *(const v4i*)(Vl + (p * 16 + r) * 16 + grp * 4);
-      acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, acc[p], 0, 0, 0);
+      if constexpr (kOneBlock)
+        acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, v4i{0, 0, 0, 0}, 0, 0, 0);
+      else
+        acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, acc[p], 0, 0, 0);
     }
   }
 
   // lane holds M[., tile r, k] for k = kb + wave*16 + grp*4 + rr
   const int rs = r / TWB, twl = r - rs * TWB;
   const int rr_ = r0 + rs, tw = tw0 + twl;
-  if (rs >= RB || rr_ >= R || tw >= g.TW) return;
+  const int k0 = kb + wave * 16 + grp * 4;
+  if (rs >= RB || rr_ >= R || tw >= g.TW || k0 >= g.K) return;
   const int img = rr_ / g.TH, th = rr_ - img * g.TH;
-  finish_lane<M, true, kSparseA, kMQ>(g, at, acc, y, img, th, tw, kb + wave * 16 + grp * 4, r_m, r_y,
-                                 qmax);
+  finish_lane<M, true, kSparseA, kMQ, kFast>(g, at, acc, y, img, th, tw, k0, r_m, r_y, qmax);
 }
 
 template <int M, bool kSparseB, bool kSparseA>
@@ -122,15 +132,23 @@ hipError_t launch_k(const Geom& g, const MatBT& bt, const MatAT& at, const int8_
       n * (stage_cols(M, TWB) / 4) > 256)
     return hipErrorInvalidValue;
   dim3 grid((unsigned)(ntwb * nrb), (unsigned)(g.Kp / 64));
-#define WINO_LAUNCH_FUSED(WIDE, MQ)                                                   \
-  fused_fwd_i8_kernel<M, kSparseB, kSparseA, WIDE, MQ><<<grid, 256, lb, s>>>(           \
+#define WINO_LAUNCH_FUSED1(WIDE, MQ, FAST, ONE)                                       \
+  fused_fwd_i8_kernel<M, kSparseB, kSparseA, WIDE, MQ, FAST, ONE><<<grid, 256, lb, s>>>( \
       g, bt, at, x, U, y, r_v, r_m, r_y, qmax, RB, TWB)
+#define WINO_LAUNCH_FUSED(WIDE, MQ, FAST)                                             \
+  do { if (g.Cp == 64) WINO_LAUNCH_FUSED1(WIDE, MQ, FAST, true);                      \
+       else WINO_LAUNCH_FUSED1(WIDE, MQ, FAST, false); } while (0)
+  // whole tiles and K % 4 == 0 (and no quantizer on M): no guards on the output side
+  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && !(r_m > 0.0f);
   if (g.W >= 4) {
-    if (r_m > 0.0f) WINO_LAUNCH_FUSED(true, true); else WINO_LAUNCH_FUSED(true, false);
+    if (fast) WINO_LAUNCH_FUSED(true, false, true);
+    else if (r_m > 0.0f) WINO_LAUNCH_FUSED(true, true, false);
+    else WINO_LAUNCH_FUSED(true, false, false);
   } else {
-    if (r_m > 0.0f) WINO_LAUNCH_FUSED(false, true); else WINO_LAUNCH_FUSED(false, false);
+    if (r_m > 0.0f) WINO_LAUNCH_FUSED(false, true, false); else WINO_LAUNCH_FUSED(false, false, false);
   }
 #undef WINO_LAUNCH_FUSED
+#undef WINO_LAUNCH_FUSED1
   return hipGetLastError();
 }
 
