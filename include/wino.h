@@ -123,11 +123,12 @@ wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void*
                             const void* U_dev, void* y_dev, void* workspace_dev,
                             size_t workspace_bytes, void* stream);
 
-/* How many kernels wino_conv2d_fwd launches for this problem (0 if the descriptor is
- * invalid): 1 = input transform, GEMM and output transform in one kernel (small int8
- * layers; V and M never reach memory), 2 = input transform, then GEMM fused with the
- * output transform (M never reaches memory), 3 = input transform, tiled GEMM, output
- * transform (long reductions, F(6x6,3x3)). */
+/* How many kernels wino_conv2d_fwd launches for this problem with per-tensor scales (0 if
+ * the descriptor is invalid): 1 = input transform, GEMM and output transform in one
+ * kernel (small layers; V and M never reach memory), 2 = input transform, then GEMM fused
+ * with the output transform (M never reaches memory), 3 = input transform, tiled GEMM,
+ * output transform (long reductions, F(6x6,3x3); always with per-position scales).  Reads
+ * d->BT (HOST) if it is not NULL: which single-kernel variant applies depends on it. */
 int wino_fwd_num_kernels(const wino_desc* d);
 
 /* The same forward, restricted to the stages named in `stages` (a mask of

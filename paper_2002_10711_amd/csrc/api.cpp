@@ -178,7 +178,20 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, cons
 int wino_fwd_num_kernels(const wino_desc* d) {
   Geom g;
   if (make_geom(d, &g) != WINO_OK) return 0;
-  return (fused_fwd_supported(g) || fused_fwd_f32_supported(g)) ? 1 : gemm_out_preferred(g) ? 2 : 3;
+  if (fused_fwd_f32_supported(g)) return 1;
+  if (fused_fwd_supported(g)) {
+    // as in wino_conv2d_fwd: the matrix-core variant whenever B^T allows it, the
+    // vector-ALU one for a single block of output channels
+    bool exact = false;
+    if (d->BT && finite_all(d->BT, g.n * g.n)) {
+      MatBT bt;
+      memset(&bt, 0, sizeof bt);
+      memcpy(bt.v, d->BT, sizeof(float) * g.n * g.n);
+      exact = fused_fwd_exact_supported(g, bt);
+    }
+    if (exact || fused_fwd_generic_preferred(g)) return 1;
+  }
+  return gemm_out_preferred(g) ? 2 : 3;
 }
 
 wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
@@ -215,11 +228,13 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
   }
   if (stages == WINO_STAGE_ALL && !s.pos && fused_fwd_supported(g)) {
     // the whole forward in one kernel: V and M stay on chip, the workspace is untouched
-    const hipError_t e =
-        fused_fwd_exact_supported(g, bt)
-            ? launch_fused_fwd_exact(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs)
-            : launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs);
-    return e == hipSuccess ? WINO_OK : WINO_E_HIP;
+    const bool exact = fused_fwd_exact_supported(g, bt);
+    if (exact || fused_fwd_generic_preferred(g)) {
+      const hipError_t e =
+          exact ? launch_fused_fwd_exact(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs)
+                : launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs);
+      return e == hipSuccess ? WINO_OK : WINO_E_HIP;
+    }
   }
   if (stages == WINO_STAGE_ALL && fused_fwd_f32_supported(g))
     return launch_fused_fwd_f32(g, bt, at, x_dev, U_dev, y_dev, hs) == hipSuccess ? WINO_OK

@@ -70,6 +70,9 @@ hipError_t launch_gemm_out(const Geom& g, const MatAT& at, const void* V, const 
                            float r_m, float r_y, float qmax, hipStream_t s);
 // Whole int8 forward in one kernel (neither V nor M stored); only where supported.
 bool fused_fwd_supported(const Geom& g);
+// ... and worth it with the vector-ALU input transform, which a second block of output
+// channels would have to repeat in full.
+inline bool fused_fwd_generic_preferred(const Geom& g) { return g.Kp <= 64; }
 hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                             const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
                             hipStream_t s);
