@@ -87,7 +87,11 @@ struct XPlan {
 };
 
 // kLoad: 0 = byte loads (W < 4), 1 = one dword per lane at any byte address,
-// 2 = 8 bytes per lane from a dword-aligned address (W % 4 == 0, W >= 8, x aligned).
+// 2 = 8 bytes per lane from a dword-aligned address (W % 4 == 0, W >= 8, x aligned),
+// 3 = whole image rows: the workgroup spans the full width (TW == kTWB, W == kTWB * m,
+// pad == 1, x aligned to min(W, 16) bytes), a lane loads one row of one channel (W bytes,
+// consecutive lanes consecutive rows) and shifts it by one byte into its staged form --
+// one funnel shift per staged dword instead of a dozen operations.
 // kTWB > 0: the workgroup shape (TWB, RB) = (kTWB, 16 / kTWB) is a compile-time constant,
 // which folds the index arithmetic; 0 = taken from the plan at run time.
 template <int M, int kLoad, int kTWB>
@@ -100,6 +104,62 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
   const int RB = kTWB ? 16 / (kTWB ? kTWB : 1) : pl.RB, TWB = kTWB ? kTWB : pl.TWB;
   const int WQ = xs_row_dw(M, TWB), plane = xs_plane_dw(M, TWB);
   const int R = g.N * g.TH;
+  if constexpr (kLoad == 3) {
+    static_assert(kLoad != 3 || kTWB > 0, "whole-row staging needs a compile-time shape");
+    constexpr int RW = (kTWB ? kTWB : 1) * M;          // bytes per image row
+    constexpr int ND = RW / 4;                         // dwords per image row; WQ == ND + 1
+    constexpr int RBc = 16 / (kTWB ? kTWB : 1);
+    constexpr int nrows = RBc * n * 64;                // rows to stage: (rs, channel, j), j fastest
+    constexpr int per = (nrows + 255) / 256;
+    uint32_t rw[per][ND];
+    uint32_t* dst[per];
+    uint32_t* dump = Xs + RB * 64 * plane;             // WQ dwords nobody reads
+#pragma unroll
+    for (int i = 0; i < per; ++i) {
+      const int id = (int)threadIdx.x + i * 256;
+      const int idc = (nrows % 256 == 0 || id < nrows) ? id : nrows - 1;
+      const int cj = idc % (n * 64), rs = idc / (n * 64);
+      const int c = cj / n, j = cj - c * n;
+      const int r = r0 + rs;
+      const int rc = r < R ? r : R - 1;
+      const int img = (int)fast_div(rc, pl.inv_th), th = rc - img * g.TH;
+      const int h = th * M - 1 + j;
+      const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
+      const bool ok = r < R && h == hc && c0 + c < g.C;
+      const int cc = c0 + c < g.C ? c0 + c : c0;       // a channel that exists
+      const int8_t* src = x + (((size_t)img * g.C + cc) * g.H + hc) * RW;
+      if constexpr (RW % 16 == 0) {
+#pragma unroll
+        for (int q = 0; q < RW / 16; ++q) {
+          const v4i t = *(const v4i*)(src + 16 * q);
+          rw[i][4 * q + 0] = ok ? (uint32_t)t.x : 0u;
+          rw[i][4 * q + 1] = ok ? (uint32_t)t.y : 0u;
+          rw[i][4 * q + 2] = ok ? (uint32_t)t.z : 0u;
+          rw[i][4 * q + 3] = ok ? (uint32_t)t.w : 0u;
+        }
+      } else if constexpr (RW == 8) {
+        typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+        const v2u t = *(const v2u*)src;
+        rw[i][0] = ok ? t.x : 0u;
+        rw[i][1] = ok ? t.y : 0u;
+      } else {
+        static_assert(RW % 16 == 0 || RW == 8 || RW == 4, "row widths: 4, 8, 16, 32, 64 bytes");
+        const uint32_t t = *(const uint32_t*)src;
+        rw[i][0] = ok ? t : 0u;
+      }
+      dst[i] = (nrows % 256 == 0 || id < nrows) ? Xs + (rs * 64 + c) * plane + j * WQ : dump;
+    }
+#pragma unroll
+    for (int i = 0; i < per; ++i) {
+      // staged dword k = image bytes 4k-1 .. 4k+2 (zero outside the row)
+#pragma unroll
+      for (int k = 0; k <= ND; ++k) {
+        const uint32_t hi = k < ND ? rw[i][k] : 0u, lo = k > 0 ? rw[i][k - 1] : 0u;
+        dst[i][k] = __builtin_amdgcn_alignbyte(hi, lo, 3);
+      }
+    }
+    return;
+  }
   const int wbase = tw0 * M - g.pad;
   const int nthr = 256, tid = threadIdx.x;
   const int strip = WQ * n;
@@ -327,7 +387,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 // Grid: x = blocks of RB tile rows, y = blocks of TWB tiles along a row, z = blocks of 64
 // input channels.  Tiles of a workgroup that lie beyond the image are not written; the
 // rows of V between T and Tp are never read by anything that reaches the output.
-template <int M, int kTWB>
+template <int M, int kLoad, int kTWB>
 __global__ __launch_bounds__(256) void input_transform_exact_kernel(
     const int8_t* __restrict__ x, int8_t* __restrict__ V, PosScale rvs, float qmax, Geom g,
     XPlan pl, KronW kw) {
@@ -344,7 +404,7 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const float lo = kMagic - qmax, hi = kMagic + qmax;
 
-  stage_planes<M, 2, kTWB>(g, pl, x, Xs, cb * 64, r0, tw0);    // aligned 8-byte loads only
+  stage_planes<M, kLoad, kTWB>(g, pl, x, Xs, cb * 64, r0, tw0);   // kLoad 2 or 3 only
   // quantizer factor of the positions this lane produces (p = blk*16 + r): one per
   // position, all equal for a per-tensor scale
   float rq[NBLK];
@@ -518,7 +578,8 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   int TWB = g.TW < 16 ? g.TW : 16;
   int RB = 16 / TWB;
   if (RB > R) RB = R;
-  const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(M, TWB) + 4) * 4, vl_b = (size_t)P * kVlPitch * 4;
+  // (+ 20 dwords: the dump area of surplus staging lanes, up to one staged row)
+  const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(M, TWB) + 20) * 4, vl_b = (size_t)P * kVlPitch * 4;
   xl->lds_bytes = xs_b > vl_b ? xs_b : vl_b;
   xl->ntwb = (g.TW + TWB - 1) / TWB;
   xl->nrb = (R + RB - 1) / RB;
@@ -532,6 +593,11 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   pl.inv_wq = make_inv(xs_row_dw(M, TWB));
   pl.inv_th = make_inv(g.TH);
   xl->load = g.W < 4 ? 0 : (g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0) ? 2 : 1;
+  // whole-row staging: the workgroup spans the image width, rows are 8, 16, 32 or 64 bytes
+  if (xl->load == 2 && g.pad == 1 && g.TW == TWB && g.W == TWB * M && RB * TWB == 16 &&
+      (TWB == 16 || TWB == 8 || TWB == 4 || TWB == 2) && g.W >= 8 &&
+      ((uintptr_t)x & (g.W >= 16 ? 15 : 7)) == 0)
+    xl->load = 3;
   return true;
 }
 
@@ -551,15 +617,24 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
   const int8_t* xi = (const int8_t*)x;
   int8_t* Vi = (int8_t*)V;
   const int TWB = xl.pl.TWB, RB = xl.pl.RB;
-#define WINO_LAUNCH_IN(TWBC)                                                               \
-  input_transform_exact_kernel<M, TWBC><<<grid, 256, xl.lds_bytes, s>>>(                     \
+#define WINO_LAUNCH_IN(LOAD, TWBC)                                                         \
+  input_transform_exact_kernel<M, LOAD, TWBC><<<grid, 256, xl.lds_bytes, s>>>(               \
       xi, Vi, rvs, qmax, g, xl.pl, xl.kw)
-  if (xl.load != 2) return hipErrorInvalidValue;         // see input_exact_preferred
-  if (RB * TWB == 16 && TWB == 16) WINO_LAUNCH_IN(16);
-  else if (RB * TWB == 16 && TWB == 8) WINO_LAUNCH_IN(8);
-  else if (RB * TWB == 16 && TWB == 4) WINO_LAUNCH_IN(4);
-  else if (RB * TWB == 16 && TWB == 2) WINO_LAUNCH_IN(2);
-  else WINO_LAUNCH_IN(0);
+  if (xl.load < 2) return hipErrorInvalidValue;          // see input_exact_preferred
+  const bool shaped = RB * TWB == 16 && (TWB == 16 || TWB == 8 || TWB == 4 || TWB == 2);
+  if (xl.load == 3) {
+    if (TWB == 16) WINO_LAUNCH_IN(3, 16);
+    else if (TWB == 8) WINO_LAUNCH_IN(3, 8);
+    else if (TWB == 4) WINO_LAUNCH_IN(3, 4);
+    else WINO_LAUNCH_IN(3, 2);
+  } else if (shaped) {
+    if (TWB == 16) WINO_LAUNCH_IN(2, 16);
+    else if (TWB == 8) WINO_LAUNCH_IN(2, 8);
+    else if (TWB == 4) WINO_LAUNCH_IN(2, 4);
+    else WINO_LAUNCH_IN(2, 2);
+  } else {
+    WINO_LAUNCH_IN(2, 0);
+  }
 #undef WINO_LAUNCH_IN
   return hipGetLastError();
 }
@@ -587,17 +662,20 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   // The common case -- whole tiles, K % 4 == 0, Cook-Toom A^T pattern, no quantizer on M,
   // aligned 8-byte staging loads, a power-of-two workgroup shape (16, 8, 4 or 2 tiles
   // per row: 32 .. 8 pixel images) -- gets compile-time shapes and a branch-free output side.
-  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && sa && load == 2 && !mq &&
+  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && sa && load >= 2 && !mq &&
                     RB * TWB == 16;
   if (fast && (TWB == 16 || TWB == 8 || TWB == 4 || TWB == 2)) {
+#define WINO_LAUNCH_FAST1(LOAD, TWBC) \
+  do { if (one) WINO_LAUNCH_XK(true, LOAD, false, true, TWBC, true);  \
+       else WINO_LAUNCH_XK(true, LOAD, false, false, TWBC, true); } while (0)
 #define WINO_LAUNCH_FAST(TWBC) \
-  do { if (one) WINO_LAUNCH_XK(true, 2, false, true, TWBC, true);  \
-       else WINO_LAUNCH_XK(true, 2, false, false, TWBC, true); } while (0)
+  do { if (load == 3) WINO_LAUNCH_FAST1(3, TWBC); else WINO_LAUNCH_FAST1(2, TWBC); } while (0)
     if (TWB == 16) WINO_LAUNCH_FAST(16);
     else if (TWB == 8) WINO_LAUNCH_FAST(8);
     else if (TWB == 4) WINO_LAUNCH_FAST(4);
     else WINO_LAUNCH_FAST(2);
 #undef WINO_LAUNCH_FAST
+#undef WINO_LAUNCH_FAST1
     return hipGetLastError();
   }
 #define WINO_LAUNCH_G1(SA, LOAD, MQ) \
@@ -606,7 +684,7 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
 #define WINO_LAUNCH_G2(SA, LOAD) \
   do { if (mq) WINO_LAUNCH_G1(SA, LOAD, true); else WINO_LAUNCH_G1(SA, LOAD, false); } while (0)
 #define WINO_LAUNCH_G3(SA)                                                                 \
-  do { if (load == 2) WINO_LAUNCH_G2(SA, 2); else WINO_LAUNCH_G2(SA, 1); } while (0)
+  do { if (load >= 2) WINO_LAUNCH_G2(SA, 2); else WINO_LAUNCH_G2(SA, 1); } while (0)
   if (load == 0) return hipErrorInvalidValue;            // W < 4: see fused_fwd_exact_supported
   if (sa) WINO_LAUNCH_G3(true); else WINO_LAUNCH_G3(false);
 #undef WINO_LAUNCH_G3
