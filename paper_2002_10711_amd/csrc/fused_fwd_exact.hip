@@ -575,9 +575,12 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
       }
     }
   const int R = g.N * g.TH;
-  int TWB = g.TW < 16 ? g.TW : 16;
-  int RB = 16 / TWB;
-  if (RB > R) RB = R;
+  // Workgroup shape: 16 tiles as RB tile rows x TWB tiles per row, TWB the power of two
+  // that covers the tile row (16 at most).  Tile slots beyond the image (TWB > TW, tile
+  // rows beyond N * TH) are masked everywhere, so every shape is one of four, all known
+  // at compile time.
+  const int TWB = g.TW > 8 ? 16 : g.TW > 4 ? 8 : g.TW > 2 ? 4 : 2;
+  const int RB = 16 / TWB;
   // (+ 20 dwords: the dump area of surplus staging lanes, up to one staged row)
   const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(M, TWB) + 20) * 4, vl_b = (size_t)P * kVlPitch * 4;
   xl->lds_bytes = xs_b > vl_b ? xs_b : vl_b;
@@ -594,8 +597,7 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   pl.inv_th = make_inv(g.TH);
   xl->load = g.W < 4 ? 0 : (g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0) ? 2 : 1;
   // whole-row staging: the workgroup spans the image width, rows are 8, 16, 32 or 64 bytes
-  if (xl->load == 2 && g.pad == 1 && g.TW == TWB && g.W == TWB * M && RB * TWB == 16 &&
-      (TWB == 16 || TWB == 8 || TWB == 4 || TWB == 2) && g.W >= 8 &&
+  if (xl->load == 2 && g.pad == 1 && g.TW == TWB && g.W == TWB * M && g.W >= 8 &&
       ((uintptr_t)x & (g.W >= 16 ? 15 : 7)) == 0)
     xl->load = 3;
   return true;
@@ -616,25 +618,18 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
   dim3 grid((unsigned)xl.nrb, (unsigned)xl.ntwb, (unsigned)(g.Cp / 64));
   const int8_t* xi = (const int8_t*)x;
   int8_t* Vi = (int8_t*)V;
-  const int TWB = xl.pl.TWB, RB = xl.pl.RB;
+  const int TWB = xl.pl.TWB;
 #define WINO_LAUNCH_IN(LOAD, TWBC)                                                         \
   input_transform_exact_kernel<M, LOAD, TWBC><<<grid, 256, xl.lds_bytes, s>>>(               \
       xi, Vi, rvs, qmax, g, xl.pl, xl.kw)
   if (xl.load < 2) return hipErrorInvalidValue;          // see input_exact_preferred
-  const bool shaped = RB * TWB == 16 && (TWB == 16 || TWB == 8 || TWB == 4 || TWB == 2);
-  if (xl.load == 3) {
-    if (TWB == 16) WINO_LAUNCH_IN(3, 16);
-    else if (TWB == 8) WINO_LAUNCH_IN(3, 8);
-    else if (TWB == 4) WINO_LAUNCH_IN(3, 4);
-    else WINO_LAUNCH_IN(3, 2);
-  } else if (shaped) {
-    if (TWB == 16) WINO_LAUNCH_IN(2, 16);
-    else if (TWB == 8) WINO_LAUNCH_IN(2, 8);
-    else if (TWB == 4) WINO_LAUNCH_IN(2, 4);
-    else WINO_LAUNCH_IN(2, 2);
-  } else {
-    WINO_LAUNCH_IN(2, 0);
-  }
+#define WINO_LAUNCH_IN2(TWBC) \
+  do { if (xl.load == 3) WINO_LAUNCH_IN(3, TWBC); else WINO_LAUNCH_IN(2, TWBC); } while (0)
+  if (TWB == 16) WINO_LAUNCH_IN2(16);
+  else if (TWB == 8) WINO_LAUNCH_IN2(8);
+  else if (TWB == 4) WINO_LAUNCH_IN2(4);
+  else WINO_LAUNCH_IN2(2);
+#undef WINO_LAUNCH_IN2
 #undef WINO_LAUNCH_IN
   return hipGetLastError();
 }
@@ -651,7 +646,7 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   const KronW& kw = xl.kw;
   const float r_vs = xl.r_vs;
   const size_t lb = xl.lds_bytes;
-  const int TWB = pl.TWB, RB = pl.RB, load = xl.load;
+  const int TWB = pl.TWB, load = xl.load;
   const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
   const int8_t* xi = (const int8_t*)x;
   const int8_t* Ui = (const int8_t*)U;
@@ -659,25 +654,28 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
 #define WINO_LAUNCH_XK(SA, LOAD, MQ, ONE, TWBC, FAST)                                      \
   fused_fwd_exact_kernel<M, SA, LOAD, MQ, ONE, TWBC, FAST><<<grid, 256, lb, s>>>(            \
       xi, Ui, y, r_vs, r_m, r_y, qmax, g, pl, at, kw)
-  // The common case -- whole tiles, K % 4 == 0, Cook-Toom A^T pattern, no quantizer on M,
-  // aligned 8-byte staging loads, a power-of-two workgroup shape (16, 8, 4 or 2 tiles
-  // per row: 32 .. 8 pixel images) -- gets compile-time shapes and a branch-free output side.
-  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && sa && load >= 2 && !mq &&
-                    RB * TWB == 16;
-  if (fast && (TWB == 16 || TWB == 8 || TWB == 4 || TWB == 2)) {
-#define WINO_LAUNCH_FAST1(LOAD, TWBC) \
-  do { if (one) WINO_LAUNCH_XK(true, LOAD, false, true, TWBC, true);  \
-       else WINO_LAUNCH_XK(true, LOAD, false, false, TWBC, true); } while (0)
-#define WINO_LAUNCH_FAST(TWBC) \
-  do { if (load == 3) WINO_LAUNCH_FAST1(3, TWBC); else WINO_LAUNCH_FAST1(2, TWBC); } while (0)
-    if (TWB == 16) WINO_LAUNCH_FAST(16);
-    else if (TWB == 8) WINO_LAUNCH_FAST(8);
-    else if (TWB == 4) WINO_LAUNCH_FAST(4);
-    else WINO_LAUNCH_FAST(2);
-#undef WINO_LAUNCH_FAST
-#undef WINO_LAUNCH_FAST1
+  // The common case -- Cook-Toom A^T pattern, no quantizer on M, aligned staging loads --
+  // gets the compile-time workgroup shapes and, with whole tiles and K % 4 == 0, a
+  // branch-free output side.
+  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
+  if (sa && load >= 2 && !mq) {
+#define WINO_LAUNCH_C1(LOAD, TWBC, FAST) \
+  do { if (one) WINO_LAUNCH_XK(true, LOAD, false, true, TWBC, FAST);  \
+       else WINO_LAUNCH_XK(true, LOAD, false, false, TWBC, FAST); } while (0)
+#define WINO_LAUNCH_C2(LOAD, TWBC) \
+  do { if (fast) WINO_LAUNCH_C1(LOAD, TWBC, true); else WINO_LAUNCH_C1(LOAD, TWBC, false); } while (0)
+#define WINO_LAUNCH_C3(TWBC) \
+  do { if (load == 3) WINO_LAUNCH_C2(3, TWBC); else WINO_LAUNCH_C2(2, TWBC); } while (0)
+    if (TWB == 16) WINO_LAUNCH_C3(16);
+    else if (TWB == 8) WINO_LAUNCH_C3(8);
+    else if (TWB == 4) WINO_LAUNCH_C3(4);
+    else WINO_LAUNCH_C3(2);
+#undef WINO_LAUNCH_C3
+#undef WINO_LAUNCH_C2
+#undef WINO_LAUNCH_C1
     return hipGetLastError();
   }
+  // everything else: the same kernel with the shape read from the plan
 #define WINO_LAUNCH_G1(SA, LOAD, MQ) \
   do { if (one) WINO_LAUNCH_XK(SA, LOAD, MQ, true, 0, false);      \
        else WINO_LAUNCH_XK(SA, LOAD, MQ, false, 0, false); } while (0)
