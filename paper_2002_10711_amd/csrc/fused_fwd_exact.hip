@@ -404,7 +404,7 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const float lo = kMagic - qmax, hi = kMagic + qmax;
 
-  stage_planes<M, kLoad, kTWB>(g, pl, x, Xs, cb * 64, r0, tw0);   // kLoad 2 or 3 only
+  stage_planes<M, kLoad, kTWB>(g, pl, x, Xs, cb * 64, r0, tw0);
   // quantizer factor of the positions this lane produces (p = blk*16 + r): one per
   // position, all equal for a per-tensor scale
   float rq[NBLK];
@@ -523,16 +523,15 @@ bool input_exact_supported(const Geom& g, const MatBT& bt) {
 }
 
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
-  // (images narrower than 8 pixels or with ragged rows would need the byte / unaligned
-  // staging of one or two tiles per row, where the vector-ALU kernel is the faster one)
-  return g.Kp <= 128 && g.W % 4 == 0 && g.W >= 8 && input_exact_supported(g, bt);
+  // (W < 4 would need byte-wise staging: such images take the unfused path)
+  return g.Kp <= 128 && g.W >= 4 && input_exact_supported(g, bt);
 }
 
-// As a stand-alone input stage the exact kernel pays off where its staging runs on
-// aligned 8-byte loads; images narrower than 8 pixels (one or two tiles per row) are
-// better served by the vector-ALU kernel, whose workgroups span many images.
+// As a stand-alone input stage: wherever the staging can load dwords (W >= 4); only
+// narrower images go to the vector-ALU kernel.
 bool input_exact_preferred(const Geom& g, const MatBT& bt, const void* x) {
-  return g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0 && input_exact_supported(g, bt);
+  (void)x;
+  return g.W >= 4 && input_exact_supported(g, bt);
 }
 
 namespace {
@@ -622,9 +621,10 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
 #define WINO_LAUNCH_IN(LOAD, TWBC)                                                         \
   input_transform_exact_kernel<M, LOAD, TWBC><<<grid, 256, xl.lds_bytes, s>>>(               \
       xi, Vi, rvs, qmax, g, xl.pl, xl.kw)
-  if (xl.load < 2) return hipErrorInvalidValue;          // see input_exact_preferred
+  if (xl.load < 1) return hipErrorInvalidValue;          // see input_exact_preferred
 #define WINO_LAUNCH_IN2(TWBC) \
-  do { if (xl.load == 3) WINO_LAUNCH_IN(3, TWBC); else WINO_LAUNCH_IN(2, TWBC); } while (0)
+  do { if (xl.load == 3) WINO_LAUNCH_IN(3, TWBC); else if (xl.load == 2) WINO_LAUNCH_IN(2, TWBC); \
+       else WINO_LAUNCH_IN(1, TWBC); } while (0)
   if (TWB == 16) WINO_LAUNCH_IN2(16);
   else if (TWB == 8) WINO_LAUNCH_IN2(8);
   else if (TWB == 4) WINO_LAUNCH_IN2(4);
@@ -658,14 +658,15 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   // gets the compile-time workgroup shapes and, with whole tiles and K % 4 == 0, a
   // branch-free output side.
   const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
-  if (sa && load >= 2 && !mq) {
+  if (sa && load >= 1 && !mq) {
 #define WINO_LAUNCH_C1(LOAD, TWBC, FAST) \
   do { if (one) WINO_LAUNCH_XK(true, LOAD, false, true, TWBC, FAST);  \
        else WINO_LAUNCH_XK(true, LOAD, false, false, TWBC, FAST); } while (0)
 #define WINO_LAUNCH_C2(LOAD, TWBC) \
   do { if (fast) WINO_LAUNCH_C1(LOAD, TWBC, true); else WINO_LAUNCH_C1(LOAD, TWBC, false); } while (0)
 #define WINO_LAUNCH_C3(TWBC) \
-  do { if (load == 3) WINO_LAUNCH_C2(3, TWBC); else WINO_LAUNCH_C2(2, TWBC); } while (0)
+  do { if (load == 3) WINO_LAUNCH_C2(3, TWBC); else if (load == 2) WINO_LAUNCH_C2(2, TWBC); \
+       else WINO_LAUNCH_C2(1, TWBC); } while (0)
     if (TWB == 16) WINO_LAUNCH_C3(16);
     else if (TWB == 8) WINO_LAUNCH_C3(8);
     else if (TWB == 4) WINO_LAUNCH_C3(4);
