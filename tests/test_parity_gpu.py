@@ -64,6 +64,10 @@ SMALL = [
     Layer("s_f2_14px", 3, 48, 36, 14, 14, m=2, seed=119),         # 7 tiles per row: odd window offsets
     Layer("s_f4_8px", 9, 64, 64, 8, 8, m=4, seed=120),            # 2 tiles per row, ragged row blocks
     Layer("s_f4_64px", 1, 64, 64, 64, 64, m=4, seed=121),         # 16 tiles per row
+    Layer("s_f4_7px", 5, 24, 20, 7, 7, m=4, seed=141),            # 2 x 2 ragged tiles, odd width
+    Layer("s_f2_4px", 9, 64, 64, 4, 4, m=2, seed=142),            # rows of one dword
+    Layer("s_f4_4px", 17, 70, 33, 4, 4, m=4, seed=143),           # one tile per image, ragged row blocks
+    Layer("s_f2_36px", 1, 16, 16, 36, 36, m=2, seed=144),         # 18 tiles per row: two row pieces
     Layer("s_f4_k32", 3, 64, 32, 16, 16, m=4, seed=122),          # K below the 64-channel block
     Layer("s_f4_k100", 2, 64, 100, 16, 16, m=4, seed=123),        # K = 64 + 36
 ]
@@ -157,6 +161,35 @@ def test_per_position_scales_all_taps(oracle, layer):
     case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc,
                                     pad=layer.pad)
     _check_i8(case, run_gpu(case, scales=sc))
+
+
+def test_input_at_an_odd_address(oracle):
+    """x need not be aligned: the staging falls back to unaligned dword loads."""
+    import torch
+    from paper_2002_10711_amd import binding as wb
+    L = Layer("odd_x", 2, 64, 64, 16, 16, m=4, seed=145)
+    case = make_case(oracle, L)
+    sc = case["scales"]
+    dev = torch.device("cuda:0")
+    desc = wb.Desc(L.N, L.C, L.K, L.H, L.W, L.pad, L.m, wb.WINO_I8, BT=case["BT"], G=case["G"],
+                   AT=case["AT"])
+    quant = wb.make_quant(sc["s_x"], sc["s_v"], sc["s_u"], sc["s_y"])
+    buf = torch.zeros(case["xq"].size + 3, dtype=torch.int8, device=dev)
+    for shift in (1, 2):
+        x = buf[shift:shift + case["xq"].size].view(case["xq"].shape)
+        x.copy_(torch.from_numpy(case["xq"]))
+        assert x.data_ptr() % 4 == shift
+        U = torch.empty(wb.wino_weights_bytes(desc), dtype=torch.uint8, device=dev)
+        ws = torch.empty(wb.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        y = torch.zeros((L.N, L.K, 16, 16), dtype=torch.int8, device=dev)
+        wb.wino_transform_weights(desc, quant, torch.from_numpy(case["g"]).to(dev), U)
+        wb.wino_conv2d_fwd(desc, quant, x, U, y, ws)
+        y2 = torch.zeros_like(y)
+        for stage in (wb.WINO_STAGE_INPUT, wb.WINO_STAGE_GEMM, wb.WINO_STAGE_OUTPUT):
+            wb.wino_conv2d_fwd_stages(desc, quant, x, U, y2, ws, stage)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), case["ref"]["Yq"])
+        assert np.array_equal(y2.cpu().numpy(), case["ref"]["Yq"])
 
 
 def test_config2_int8_full(oracle):
