@@ -323,7 +323,8 @@ def main():
     a = ap.parse_args()
     if a.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (the path needs no exchange "
-                         "step; see DESIGN.md for how it would shard); got --gpus %d" % a.gpus)
+                         "step: tiles are independent, so more GPUs would each take a share of the batch); "
+                         "got --gpus %d" % a.gpus)
     L = pick_workload(a.workload)
     if a.flex > 0:
         from dataclasses import replace
