@@ -163,6 +163,33 @@ def test_per_position_scales_all_taps(oracle, layer):
     _check_i8(case, run_gpu(case, scales=sc))
 
 
+def _random_layers(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        m = int(rng.choice([2, 4, 6]))
+        pad = int(rng.integers(0, 2))
+        H, W = int(rng.integers(3, 41)), int(rng.integers(3, 41))
+        if H + 2 * pad - 2 < 1 or W + 2 * pad - 2 < 1:
+            continue
+        out.append(Layer("rnd%d" % len(out), int(rng.integers(1, 5)), int(rng.integers(1, 141)),
+                         int(rng.integers(1, 141)), H, W, m=m, pad=pad,
+                         flex_sigma=float(rng.choice([0.0, 0.0, 0.03])), seed=1000 + len(out)))
+    return out
+
+
+@pytest.mark.parametrize("layer", _random_layers(36, 7), ids=lambda l: "%s_%dx%dx%dx%dx%d_m%d_p%d%s" % (
+    l.name, l.N, l.C, l.K, l.H, l.W, l.m, l.pad, "_flex" if l.flex_sigma else ""))
+def test_random_shapes_int8_and_fp32(oracle, layer):
+    """Seeded random shapes across every dispatch path: all int8 taps bit-exact, fp32 within
+    tolerance."""
+    from dataclasses import replace
+    case = make_case(oracle, layer)
+    _check_i8(case, run_gpu(case))
+    case = make_case(oracle, replace(layer, dtype="f32"))
+    _check_f32(oracle, case, run_gpu(case))
+
+
 def test_input_at_an_odd_address(oracle):
     """x need not be aligned: the staging falls back to unaligned dword loads."""
     import torch
