@@ -94,7 +94,8 @@ struct XPlan {
 // one funnel shift per staged dword instead of a dozen operations.
 // kTWB > 0: the workgroup shape (TWB, RB) = (kTWB, 16 / kTWB) is a compile-time constant,
 // which folds the index arithmetic; 0 = taken from the plan at run time.
-template <int M, int kLoad, int kTWB>
+// kThreads: threads of the workgroup (256, or 512 for the 128-output-channel kernel).
+template <int M, int kLoad, int kTWB, int kThreads = 256>
 __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
                                              const int8_t* __restrict__ x, uint32_t* Xs, int c0,
                                              int r0, int tw0) {
@@ -110,14 +111,14 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
     constexpr int ND = RW / 4;                         // dwords per image row; WQ == ND + 1
     constexpr int RBc = 16 / (kTWB ? kTWB : 1);
     constexpr int nrows = RBc * n * 64;                // rows to stage: (rs, channel, j), j fastest
-    constexpr int per = (nrows + 255) / 256;
+    constexpr int per = (nrows + kThreads - 1) / kThreads;
     uint32_t rw[per][ND];
     uint32_t* dst[per];
     uint32_t* dump = Xs + RB * 64 * plane;             // WQ dwords nobody reads
 #pragma unroll
     for (int i = 0; i < per; ++i) {
-      const int id = (int)threadIdx.x + i * 256;
-      const int idc = (nrows % 256 == 0 || id < nrows) ? id : nrows - 1;
+      const int id = (int)threadIdx.x + i * kThreads;
+      const int idc = (nrows % kThreads == 0 || id < nrows) ? id : nrows - 1;
       const int cj = idc % (n * 64), rs = idc / (n * 64);
       const int c = cj / n, j = cj - c * n;
       const int r = r0 + rs;
@@ -147,7 +148,7 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
         const uint32_t t = *(const uint32_t*)src;
         rw[i][0] = ok ? t : 0u;
       }
-      dst[i] = (nrows % 256 == 0 || id < nrows) ? Xs + (rs * 64 + c) * plane + j * WQ : dump;
+      dst[i] = (nrows % kThreads == 0 || id < nrows) ? Xs + (rs * 64 + c) * plane + j * WQ : dump;
     }
 #pragma unroll
     for (int i = 0; i < per; ++i) {
@@ -161,7 +162,7 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
     return;
   }
   const int wbase = tw0 * M - g.pad;
-  const int nthr = 256, tid = threadIdx.x;
+  const int nthr = kThreads, tid = threadIdx.x;
   const int strip = WQ * n;
   const int slots = kTWB ? nthr / strip : (int)fast_div(nthr, pl.inv_strip);
   const int sidx = kTWB ? tid / strip : (int)fast_div(tid, pl.inv_strip), rem = tid - sidx * strip;
@@ -380,6 +381,132 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
   WINO_TS(6);
 }
 
+
+// The same forward for 128 output channels in one workgroup of EIGHT wavefronts (two per
+// SIMD): wavefronts 0-3 own output channels 0..63 of the block, 4-7 channels 64..127, and
+// all eight share the staging and the transform (two tiles per wavefront), which the
+// 64-channel kernel would repeat per block of output channels.  One or two blocks of 64
+// input channels (kRegions), each transformed into an LDS region of its own, so that the
+// accumulators start life at the per-position MFMAs and the kernel stays within 256
+// registers per lane.  Cook-Toom A^T pattern, no quantizer on M, compile-time shape.
+// Grid: x = blocks of RB tile rows, y = blocks of TWB tiles along a row, z = blocks of 128
+// output channels.
+template <int M, int kLoad, int kTWB, int kRegions, bool kFast>
+__global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
+    const int8_t* __restrict__ x, const int8_t* __restrict__ U, void* __restrict__ y, float r_vs,
+    float r_y, float qmax, Geom g, XPlan pl, MatAT at, KronW kw) {
+  static_assert(kTWB > 0, "compile-time workgroup shape");
+  constexpr int n = M + 2, P = n * n;
+  constexpr int NBLK = (P + 15) / 16;
+  constexpr int NG = 8;                                // window groups per wavefront: 2 tiles x 4
+  constexpr int NSTEP = NG * NBLK;
+  constexpr int RB = 16 / kTWB, TWB = kTWB;
+  constexpr int WQ = (((kTWB - 1) * M) >> 2) + 2, plane = ((M + 2) * WQ) | 1;
+  constexpr int kXsDw = RB * 64 * plane + 20, kVlDw = P * kVlPitch;
+  constexpr int kRegionDw = kXsDw > kVlDw ? kXsDw : kVlDw;
+  static_assert(kRegionDw % 4 == 0, "regions keep the 16-byte alignment of the operand reads");
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  const int r0 = blockIdx.x * RB, tw0 = blockIdx.y * TWB, kb = blockIdx.z * 128;
+  const int R = g.N * g.TH;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // 0..7
+  const int kw16 = kb + (wave >> 2) * 64 + (wave & 3) * 16;    // first output channel of the wave
+  const float lo = kMagic - qmax, hi = kMagic + qmax;
+  const uint32_t uoff = (uint32_t)(kw16 >> 4) * (uint32_t)(g.Cp >> 6) * 1024u +
+                        (uint32_t)(grp * 16 + r) * 16u;
+  const uint32_t up = (uint32_t)g.Kp * (uint32_t)g.Cp;
+
+  v4i Wb[NBLK];
+#pragma unroll
+  for (int blk = 0; blk < NBLK; ++blk) Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
+
+  // U operands of the per-position MFMAs, in the order (position, channel block), through
+  // a register ring; the first ring-full is fetched during the last transform phase
+  constexpr int Q = P * kRegions;
+  constexpr int kDepth = M == 4 ? 12 : 8;
+  static_assert(Q % kDepth == 0, "ring depth must divide the operand sequence");
+  v4i bufU[kDepth];
+
+#pragma unroll
+  for (int cb = 0; cb < kRegions; ++cb) {
+    uint32_t* Xs = lds + cb * kRegionDw;
+    uint32_t* Vl = Xs;                                 // the region's V overwrites its staging
+    stage_planes<M, kLoad, kTWB, 512>(g, pl, x, Xs, cb * 64, r0, tw0);
+    __syncthreads();
+    v4i Aw[NG];
+    {
+      const int j0 = 2 * grp < n ? 2 * grp : 0, j1 = 2 * grp + 1 < n ? 2 * grp + 1 : 0;
+      const uint32_t* lane_x = Xs + r * plane + j0 * WQ;
+      const int dj = (j1 - j0) * WQ;
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
+        const int tl = wave * 2 + t2;
+        const int rs = tl / kTWB, twl = tl - rs * kTWB;
+        const uint32_t* p0 = lane_x + rs * 64 * plane + ((twl * M) >> 2);
+        const int sh = (twl * M) & 3;
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg) {
+          const uint32_t* p1 = p0 + cg * 16 * plane;
+          if constexpr (M == 4) {
+            Aw[t2 * 4 + cg] = v4i{(int)p1[0], (int)p1[1], (int)p1[dj], (int)p1[dj + 1]};
+          } else {
+            const uint32_t a0 = __builtin_amdgcn_alignbyte(p1[1], p1[0], sh);
+            const uint32_t a1 = __builtin_amdgcn_alignbyte(p1[dj + 1], p1[dj], sh);
+            Aw[t2 * 4 + cg] = v4i{(int)a0, (int)p1[1], (int)a1, (int)p1[dj + 1]};
+          }
+        }
+      }
+    }
+    __syncthreads();                                   // the region's staging is free
+    if (cb == kRegions - 1) {
+#pragma unroll
+      for (int q = 0; q < kDepth; ++q)
+        bufU[q] = *(const v4i*)(U + (uoff + (uint32_t)(q % kRegions) * 1024u +
+                                     (uint32_t)(q / kRegions) * up));
+    }
+    uint32_t* lane_v = Vl + r * kVlPitch + grp;
+    v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], v4i{0, 0, 0, 0}, 0, 0, 0);
+#pragma unroll
+    for (int st = 0; st < NSTEP; ++st) {
+      const int gi = st / NBLK, blk = st % NBLK;
+      v4i nxt = cur;
+      if (st + 1 < NSTEP)
+        nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
+                                                    v4i{0, 0, 0, 0}, 0, 0, 0);
+      uint32_t packed = 0u;
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr)
+        packed = __builtin_amdgcn_perm(quantize_bits((float)cur[rr], r_vs, lo, hi), packed, 0x04030201u);
+      const int tl = wave * 2 + (gi >> 2);
+      if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
+      cur = nxt;
+    }
+  }
+  __syncthreads();
+
+  v4i acc[P];
+  const uint32_t* lane_b = lds + r * 16 + grp * 4;
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int p = q / kRegions, cb = q % kRegions;
+    const v4i au = bufU[q % kDepth];
+    if (q + kDepth < Q)
+      bufU[q % kDepth] = *(const v4i*)(U + (uoff + (uint32_t)((q + kDepth) % kRegions) * 1024u +
+                                            (uint32_t)((q + kDepth) / kRegions) * up));
+    const v4i bv = *(const v4i*)(lane_b + cb * kRegionDw + p * kVlPitch);
+    if (cb == 0)
+      acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, v4i{0, 0, 0, 0}, 0, 0, 0);
+    else
+      acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, acc[p], 0, 0, 0);
+  }
+
+  const int rs = r / kTWB, twl = r - rs * kTWB;
+  const int rr_ = r0 + rs, tw = tw0 + twl, k0 = kw16 + grp * 4;
+  if (rr_ < R && tw < g.TW && k0 < g.K) {
+    const int img = (int)fast_div(rr_, pl.inv_th), th = rr_ - img * g.TH;
+    finish_lane<M, true, true, false, kFast>(g, at, acc, y, img, th, tw, k0, 0.0f, r_y, qmax);
+  }
+}
 
 // The input stage alone, for the layers whose accumulators do not fit the fused kernel
 // and for the per-stage calls: same staging, window gather and MFMA transform, then the
@@ -658,6 +785,41 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   // gets the compile-time workgroup shapes and, with whole tiles and K % 4 == 0, a
   // branch-free output side.
   const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
+  // 128 output channels and at most 128 input channels: eight wavefronts share one
+  // transform (fused_fwd_exact_wide_kernel)
+  if (sa && load >= 2 && !mq && g.Kp == 128 && g.Cp <= 128) {
+    constexpr int n_ = M + 2, P_ = n_ * n_;
+    const int plane_ = xs_plane_dw(M, TWB);
+    const size_t xs_dw = (size_t)(16 / TWB) * 64 * plane_ + 20, vl_dw = (size_t)P_ * kVlPitch;
+    const int regions = g.Cp / 64;
+    const size_t lbw = regions * (xs_dw > vl_dw ? xs_dw : vl_dw) * 4;
+    dim3 gridw((unsigned)xl.nrb, (unsigned)xl.ntwb, 1u);
+#define WINO_LAUNCH_W(LOAD, TWBC, REG, FAST)                                               \
+  do {                                                                                     \
+    auto kern = fused_fwd_exact_wide_kernel<M, LOAD, TWBC, REG, FAST>;                      \
+    if (lbw > 65536) {                                                                     \
+      const hipError_t e = hipFuncSetAttribute(                                            \
+          (const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lbw);        \
+      if (e != hipSuccess) return e;                                                       \
+    }                                                                                      \
+    kern<<<gridw, 512, lbw, s>>>(xi, Ui, y, r_vs, r_y, qmax, g, pl, at, kw);                \
+  } while (0)
+#define WINO_LAUNCH_W1(LOAD, TWBC, REG) \
+  do { if (fast) WINO_LAUNCH_W(LOAD, TWBC, REG, true); else WINO_LAUNCH_W(LOAD, TWBC, REG, false); } while (0)
+#define WINO_LAUNCH_W2(LOAD, TWBC) \
+  do { if (regions == 2) WINO_LAUNCH_W1(LOAD, TWBC, 2); else WINO_LAUNCH_W1(LOAD, TWBC, 1); } while (0)
+#define WINO_LAUNCH_W3(TWBC) \
+  do { if (load == 3) WINO_LAUNCH_W2(3, TWBC); else WINO_LAUNCH_W2(2, TWBC); } while (0)
+    if (TWB == 16) WINO_LAUNCH_W3(16);
+    else if (TWB == 8) WINO_LAUNCH_W3(8);
+    else if (TWB == 4) WINO_LAUNCH_W3(4);
+    else WINO_LAUNCH_W3(2);
+#undef WINO_LAUNCH_W3
+#undef WINO_LAUNCH_W2
+#undef WINO_LAUNCH_W1
+#undef WINO_LAUNCH_W
+    return hipGetLastError();
+  }
   if (sa && load >= 1 && !mq) {
 #define WINO_LAUNCH_C1(LOAD, TWBC, FAST) \
   do { if (one) WINO_LAUNCH_XK(true, LOAD, false, true, TWBC, FAST);  \

@@ -70,6 +70,13 @@ SMALL = [
     Layer("s_f2_36px", 1, 16, 16, 36, 36, m=2, seed=144),         # 18 tiles per row: two row pieces
     Layer("s_f4_k32", 3, 64, 32, 16, 16, m=4, seed=122),          # K below the 64-channel block
     Layer("s_f4_k100", 2, 64, 100, 16, 16, m=4, seed=123),        # K = 64 + 36
+    # 65..128 output channels, at most 128 input channels: the eight-wavefront fused kernel
+    Layer("s_f4_c128_k128", 3, 128, 128, 16, 16, m=4, seed=145),  # two LDS regions
+    Layer("s_f4_c70_k100", 2, 70, 100, 8, 8, m=4, seed=146),      # ragged channels both ways
+    Layer("s_f4_c40_k128_7px", 5, 40, 128, 7, 7, m=4, seed=147),  # one region, ragged tiles
+    Layer("s_f2_c128_k72_32px", 1, 128, 72, 32, 32, m=2, seed=148),
+    Layer("s_f2_c100_k128_6px", 7, 100, 128, 6, 6, m=2, seed=149),
+    Layer("s_f4_c128_k128_64px", 1, 128, 128, 64, 64, m=4, seed=150),
 ]
 
 
