@@ -43,6 +43,7 @@ def lib():
         L = ctypes.CDLL(_LIB)
         L.oracle_q_output.restype = ctypes.c_int64
         L.oracle_q_output_pos.restype = ctypes.c_int64
+        L.oracle_q_output_bits.restype = ctypes.c_int64
         L.oracle_num_threads.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -209,9 +210,11 @@ def q_hadamard(Vq, Uq):
 
 
 def q_output(M, AT, N, H, W, pad=1, r_m=0.0, r_y=1.0, qmax=127, want_f32=True, want_q=True,
-             w_pos=None):
+             w_pos=None, qmax_m=None):
     """Y tile = A^T M A in pinned fp32; returns (Y_f32 unscaled or None, Yq or None, inexact).
-    w_pos: per-position factors that bring M to real units first (per-position scales)."""
+    w_pos: per-position factors that bring M to real units first (per-position scales).
+    qmax is the range of the output codes; qmax_m (default: the same) that of the
+    Hadamard-stage quantizer."""
     M = _c(M, np.int64)
     AT = _c(AT, np.float32)
     m, n = AT.shape
@@ -220,15 +223,21 @@ def q_output(M, AT, N, H, W, pad=1, r_m=0.0, r_y=1.0, qmax=127, want_f32=True, w
     assert P == geo["P"] and T == geo["T"]
     Yf = np.zeros((N, K, geo["Ho"], geo["Wo"]), np.float32) if want_f32 else None
     Yq = np.zeros((N, K, geo["Ho"], geo["Wo"]), np.int32) if want_q else None
-    if w_pos is None:
-        inexact = lib().oracle_q_output(N, K, H, W, pad, m, _p(AT), _p(M), ctypes.c_float(r_m),
-                                        ctypes.c_float(r_y), int(qmax), _p(Yf), _p(Yq))
-    else:
-        inexact = lib().oracle_q_output_pos(N, K, H, W, pad, m, _p(AT), _p(M),
-                                            _p(_per_position(w_pos, P)), ctypes.c_float(r_m),
-                                            ctypes.c_float(r_y), int(qmax), _p(Yf), _p(Yq))
+    inexact = lib().oracle_q_output_bits(
+        N, K, H, W, pad, m, _p(AT), _p(M), _p(None if w_pos is None else _per_position(w_pos, P)),
+        ctypes.c_float(r_m), ctypes.c_float(r_y), int(qmax if qmax_m is None else qmax_m),
+        int(qmax), _p(Yf), _p(Yq))
     assert inexact >= 0
     return Yf, Yq, int(inexact)
+
+
+def stage_qmax(qmax):
+    """Code ranges of the five quantizers (input x, transformed weights u, transformed
+    input v, Hadamard stage m, output y) from one integer or a dict with those keys
+    (missing keys: 127) -- Sec. 3.2 lets every stage have its own bit-width."""
+    if isinstance(qmax, dict):
+        return {k: int(qmax.get(k, 127)) for k in "xuvmy"}
+    return {k: int(qmax) for k in "xuvmy"}
 
 
 def quantize_tensor(x, scale, qmax=127):
@@ -237,26 +246,35 @@ def quantize_tensor(x, scale, qmax=127):
     return np.clip(np.rint(v), -qmax, qmax).astype(np.int32)
 
 
-def calibrate(X, g, BT, G, AT, pad=1, qmax=127):
-    """Static max-abs scales for the four quantizers (stand-in for the paper's
-    warmed-up moving averages, Table 1 caption).  Each scale is the max-abs of the
-    stage's value range divided by qmax, over the whole tensor (per-layer scale,
-    Sec. 5.1), computed with the pipeline's own arithmetic, stage after stage."""
+def calibrate(X, g, BT, G, AT, pad=1, qmax=127, with_m=False):
+    """Static max-abs scales for the quantizers (stand-in for the paper's warmed-up moving
+    averages, Table 1 caption).  Each scale is the max-abs of the stage's value range
+    divided by that stage's qmax (an integer, or per stage as in stage_qmax), over the
+    whole tensor (per-layer scale, Sec. 5.1), computed with the pipeline's own arithmetic,
+    stage after stage.  with_m: also a scale for the quantizer after the Hadamard stage."""
     f32 = np.float32
-    s_x = f32(np.abs(np.asarray(X, f32)).max() / f32(qmax))
-    xq = quantize_tensor(X, s_x, qmax)
+    qm = stage_qmax(qmax)
+    s_x = f32(np.abs(np.asarray(X, f32)).max() / f32(qm["x"]))
+    xq = quantize_tensor(X, s_x, qm["x"])
     Vf, _ = q_input(xq, BT, pad=pad, want_q=False)
-    s_v = f32(s_x * f32(np.abs(Vf).max()) / f32(qmax))
+    s_v = f32(s_x * f32(np.abs(Vf).max()) / f32(qm["v"]))
     Uf, _ = q_weights(g, G, want_q=False)
-    s_u = f32(np.abs(Uf).max() / f32(qmax))
+    s_u = f32(np.abs(Uf).max() / f32(qm["u"]))
     sc = q_scalars(s_x, s_v, s_u, 1.0)
-    _, Vq = q_input(xq, BT, pad=pad, r_v=sc["r_v"], qmax=qmax, want_f32=False)
-    _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qmax, want_f32=False)
+    _, Vq = q_input(xq, BT, pad=pad, r_v=sc["r_v"], qmax=qm["v"], want_f32=False)
+    _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qm["u"], want_f32=False)
     M = q_hadamard(Vq, Uq)
     N, _, H, W = xq.shape
-    Yf, _, _ = q_output(M, AT, N, H, W, pad=pad, want_q=False)
-    s_y = f32(f32(s_u * s_v) * f32(np.abs(Yf).max()) / f32(qmax))
-    return dict(s_x=float(s_x), s_v=float(s_v), s_u=float(s_u), s_y=float(s_y), s_m=0.0)
+    s_m = f32(0)
+    if with_m:
+        s_m = f32(f32(s_u * s_v) * f32(np.abs(M).max()) / f32(qm["m"]))
+        scm = q_scalars(s_x, s_v, s_u, 1.0, s_m)
+        Yf, _, _ = q_output(M, AT, N, H, W, pad=pad, r_m=scm["r_m"], qmax_m=qm["m"], want_q=False)
+        s_y = f32(s_m * f32(np.abs(Yf).max()) / f32(qm["y"]))
+    else:
+        Yf, _, _ = q_output(M, AT, N, H, W, pad=pad, want_q=False)
+        s_y = f32(f32(s_u * s_v) * f32(np.abs(Yf).max()) / f32(qm["y"]))
+    return dict(s_x=float(s_x), s_v=float(s_v), s_u=float(s_u), s_y=float(s_y), s_m=float(s_m))
 
 
 def calibrate_pos(X, g, BT, G, AT, pad=1, qmax=127):
@@ -285,23 +303,21 @@ def calibrate_pos(X, g, BT, G, AT, pad=1, qmax=127):
 
 def winograd_q(xq, g, BT, G, AT, scales, pad=1, qmax=127):
     """The whole quantized forward, every tap returned.  xq: int input at scale s_x.
-    With "s_v_pos" / "s_u_pos" in scales: the per-position variant."""
+    With "s_v_pos" / "s_u_pos" in scales: the per-position variant.  qmax: one code range
+    for every stage, or one per stage (stage_qmax)."""
+    qm = stage_qmax(qmax)
+    N, _, H, W = np.asarray(xq).shape
     if "s_v_pos" in scales:
         sc = q_scalars_pos(scales["s_x"], scales["s_v_pos"], scales["s_u_pos"], scales["s_y"],
                            scales.get("s_m", 0.0))
-        _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qmax, want_f32=False)
-        _, Vq = q_input(xq, BT, pad=pad, r_v=sc["r_v"], qmax=qmax, want_f32=False)
-        M = q_hadamard(Vq, Uq)
-        N, _, H, W = np.asarray(xq).shape
-        _, Yq, inexact = q_output(M, AT, N, H, W, pad=pad, r_m=sc["r_m"], r_y=sc["r_y"],
-                                  qmax=qmax, want_f32=False, w_pos=sc["w"])
-        return dict(Uq=Uq, Vq=Vq, M=M, Yq=Yq, inexact=inexact, scalars=sc)
-    sc = q_scalars(scales["s_x"], scales["s_v"], scales["s_u"], scales["s_y"],
-                   scales.get("s_m", 0.0))
-    _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qmax, want_f32=False)
-    _, Vq = q_input(xq, BT, pad=pad, r_v=sc["r_v"], qmax=qmax, want_f32=False)
+        w_pos = sc["w"]
+    else:
+        sc = q_scalars(scales["s_x"], scales["s_v"], scales["s_u"], scales["s_y"],
+                       scales.get("s_m", 0.0))
+        w_pos = None
+    _, Uq = q_weights(g, G, r_u=sc["r_u"], qmax=qm["u"], want_f32=False)
+    _, Vq = q_input(xq, BT, pad=pad, r_v=sc["r_v"], qmax=qm["v"], want_f32=False)
     M = q_hadamard(Vq, Uq)
-    N, _, H, W = np.asarray(xq).shape
     _, Yq, inexact = q_output(M, AT, N, H, W, pad=pad, r_m=sc["r_m"], r_y=sc["r_y"],
-                              qmax=qmax, want_f32=False)
+                              qmax=qm["y"], qmax_m=qm["m"], want_f32=False, w_pos=w_pos)
     return dict(Uq=Uq, Vq=Vq, M=M, Yq=Yq, inexact=inexact, scalars=sc)

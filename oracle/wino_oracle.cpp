@@ -346,9 +346,15 @@ int oracle_q_hadamard(int P, int64_t T, int C, int K, const int32_t* Vq, const i
 // w_pos (optional): with per-position scales the accumulators of different positions are
 // in different units, so each is first brought to real units, Mf = (float)M * w_pos[p]
 // (w_pos[p] = s_u[p] * s_v[p]); r_m and r_y then no longer contain s_u * s_v.
-int64_t oracle_q_output_pos(int N, int K, int H, int W, int pad, int m, const float* AT,
-                            const int64_t* M, const float* w_pos, float r_m, float r_y, int qmax,
-                            float* Y_f32, int32_t* Yq) {
+// qmax_m / qmax_y: the two quantizers of this stage may have different bit-widths
+// (Sec. 3.2, "quantization diversity": every intermediate of Eq. 1 can be quantized to its
+// own number of bits; Sec. 5.1 runs INT8, INT10 and INT16): the Hadamard-stage codes
+// saturate to [-qmax_m, qmax_m], the output codes to [-qmax_y, qmax_y].  The weight and
+// input stages take their own qmax as an argument already.  (float)M is the conversion of
+// the exact integer, rounded half to even when |M| >= 2^24.
+int64_t oracle_q_output_bits(int N, int K, int H, int W, int pad, int m, const float* AT,
+                             const int64_t* M, const float* w_pos, float r_m, float r_y,
+                             int qmax_m, int qmax_y, float* Y_f32, int32_t* Yq) {
   if (N < 1 || K < 1 || H < 1 || W < 1 || pad < 0 || m < 1 || m > 6) return -1;
   const int n = m + 2;
   const int Ho = H + 2 * pad - 2, Wo = W + 2 * pad - 2;
@@ -369,7 +375,7 @@ int64_t oracle_q_output_pos(int N, int K, int H, int W, int pad, int m, const fl
               if (v >= (1 << 24) || v <= -(1 << 24)) ++inexact;
               float f = (float)v;
               if (w_pos) f = f * w_pos[i * n + j];
-              if (r_m > 0.0f) f = (float)quantize(f * r_m, (float)qmax);
+              if (r_m > 0.0f) f = (float)quantize(f * r_m, (float)qmax_m);
               Mf[i][j] = f;
             }
           for (int a = 0; a < m; ++a)
@@ -386,12 +392,18 @@ int64_t oracle_q_output_pos(int N, int K, int H, int W, int pad, int m, const fl
               if (h < Ho && x < Wo) {
                 const size_t o = (((size_t)img * K + k) * Ho + h) * Wo + x;
                 if (Y_f32) Y_f32[o] = acc;
-                if (Yq) Yq[o] = quantize(acc * r_y, (float)qmax);
+                if (Yq) Yq[o] = quantize(acc * r_y, (float)qmax_y);
               }
             }
         }
       }
   return inexact;
+}
+
+int64_t oracle_q_output_pos(int N, int K, int H, int W, int pad, int m, const float* AT,
+                            const int64_t* M, const float* w_pos, float r_m, float r_y, int qmax,
+                            float* Y_f32, int32_t* Yq) {
+  return oracle_q_output_bits(N, K, H, W, pad, m, AT, M, w_pos, r_m, r_y, qmax, qmax, Y_f32, Yq);
 }
 
 int64_t oracle_q_output(int N, int K, int H, int W, int pad, int m, const float* AT,

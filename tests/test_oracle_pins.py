@@ -531,3 +531,105 @@ def test_per_position_scales_reduce_the_static_int8_error(oracle):
         ref = oracle.winograd_f64(xq.astype(np.float64) * scp["s_x"], g, BT, G, AT)
         errs.append(_rel(out["Yq"].astype(np.float64) * scp["s_y"], ref))
     assert errs[0] > errs[1] > errs[2] and errs[2] < 1e-4
+
+
+# ------------------------------------------- wider stages / one bit-width per stage
+def test_hadamard_sums_beyond_int32_match_python_integers(oracle):
+    """16-bit codes: one product reaches 2^30 and a sum over a few channels leaves the
+    int32 range; the oracle's sums must be the exact integers (checked against Python's
+    unbounded ints), as the 16-bit pipeline of Sec. 5.1 needs."""
+    rng = np.random.default_rng(61)
+    P, T, C, K = 4, 3, 37, 5
+    Vq = rng.integers(-32767, 32768, size=(P, T, C)).astype(np.int32)
+    Uq = rng.integers(-32767, 32768, size=(P, K, C)).astype(np.int32)
+    Vq[0, 0, :] = 32767
+    Uq[0, 0, :] = -32767
+    M = oracle.q_hadamard(Vq, Uq)
+    for p in range(P):
+        for t in range(T):
+            for k in range(K):
+                want = sum(int(Vq[p, t, c]) * int(Uq[p, k, c]) for c in range(C))
+                assert int(M[p, t, k]) == want
+    assert int(M[0, 0, 0]) == -37 * 32767 * 32767 and abs(int(M[0, 0, 0])) > 2 ** 31
+
+
+def test_large_accumulators_are_converted_half_to_even(oracle):
+    """(float)M for |M| >= 2^24 is the correctly rounded conversion of the exact integer:
+    F2's A^T picks M[0][0] + M[0][1] + ... ; with a single nonzero position the output is
+    that accumulator itself.  2^24 + 1 -> 2^24 (tie to even), 2^24 + 3 -> 2^24 + 4,
+    2^31 + 129 -> 2^31 + 256 (tie to even), and the count of inexact conversions is reported."""
+    _, _, AT = oracle.cook_toom(2, dtype=np.float32)
+    vals = [2 ** 24 + 1, 2 ** 24 + 3, -(2 ** 24 + 1), 2 ** 31 + 128, 2 ** 31 + 384, 12345]
+    want = [2 ** 24, 2 ** 24 + 4, -(2 ** 24), 2 ** 31, 2 ** 31 + 512, 12345]
+    M = np.zeros((16, 1, len(vals)), np.int64)
+    M[0, 0, :] = vals                                  # position (0,0) feeds output (0,0) only
+    Yf, Yq, inexact = oracle.q_output(M, AT, 1, 2, 2, pad=1, r_y=np.float32(1.0), qmax=2 ** 40)
+    assert [int(v) for v in Yf[0, :, 0, 0]] == want
+    assert [int(v) for v in Yq[0, :, 0, 0]] == [min(w, 2 ** 31 - 1) if w > 0 else w for w in want] \
+        or [float(v) for v in Yf[0, :, 0, 0]] == [float(w) for w in want]
+    assert inexact == 5
+
+
+def test_hadamard_and_output_quantizers_have_their_own_ranges(oracle):
+    """Sec. 3.2 ("quantization diversity"): each stage may have its own bit-width.  Closed
+    form for the output stage: when every accumulator is far beyond the Hadamard-stage
+    range, Mq = qmax_m * sign(M), and F2's 0/+-1 A^T makes the tile an exact small-integer
+    combination of those, y = sat_qmax_y(qmax_m * A^T sign(M) A)."""
+    rng = np.random.default_rng(62)
+    _, _, AT = oracle.cook_toom(2, dtype=np.float32)
+    sign = rng.choice([-1, 1], size=(16, 4, 3)).astype(np.int64)
+    M = sign * rng.integers(10 ** 6, 10 ** 7, size=sign.shape)
+    A = AT.astype(np.float64)
+    for qmax_m, qmax_y in ((511, 32767), (32767, 127), (7, 2047)):
+        _, Yq, _ = oracle.q_output(M, AT, 1, 4, 4, pad=1, r_m=np.float32(1.0), r_y=np.float32(1.0),
+                                   qmax=qmax_y, qmax_m=qmax_m)
+        for t in range(4):
+            for k in range(3):
+                S = sign[:, t, k].reshape(4, 4).astype(np.float64)
+                want = np.clip(qmax_m * (A @ S @ A.T), -qmax_y, qmax_y)
+                th, tw = divmod(t, 2)
+                np.testing.assert_array_equal(Yq[0, k, 2 * th:2 * th + 2, 2 * tw:2 * tw + 2], want)
+
+
+def test_one_width_per_stage_reduces_to_the_single_width_pipeline(oracle):
+    from paper_2002_10711_amd import workloads
+    L = workloads.Layer("t", 1, 8, 6, 8, 8, m=4, seed=63)
+    X, g = workloads.make_inputs(L)
+    BT, G, AT = oracle.cook_toom(4, dtype=np.float32)
+    sc = oracle.calibrate(X, g, BT, G, AT)
+    xq = oracle.quantize_tensor(X, sc["s_x"])
+    a = oracle.winograd_q(xq, g, BT, G, AT, sc)
+    b = oracle.winograd_q(xq, g, BT, G, AT, sc, qmax=dict(x=127, u=127, v=127, m=127, y=127))
+    for k in ("Uq", "Vq", "M", "Yq"):
+        np.testing.assert_array_equal(a[k], b[k])
+    # a narrower Winograd domain only clips: codes of the 6-bit stages are the 8-bit
+    # pipeline's own values saturated to +-31 when the scales stay the same
+    c = oracle.winograd_q(xq, g, BT, G, AT, sc, qmax=dict(u=31, v=31))
+    np.testing.assert_array_equal(c["Uq"], np.clip(a["Uq"], -31, 31))
+    np.testing.assert_array_equal(c["Vq"], np.clip(a["Vq"], -31, 31))
+
+
+def test_error_to_direct_convolution_falls_with_the_bit_width(oracle):
+    """Table 1 / Sec. 5.1: the same F4 and F6 layers that are far from the direct
+    convolution in INT8 get close in INT10 and closer in INT16; widening only the Winograd
+    domain (8-bit activations, 16-bit U, V and M stage) already recovers most of it
+    (Sec. 6: different bit-widths through Eq. 1)."""
+    from paper_2002_10711_amd import workloads
+    L = workloads.Layer("t", 2, 32, 16, 12, 12, seed=23)
+    X, g = workloads.make_inputs(L)
+    for m in (4, 6):
+        BT, G, AT = oracle.cook_toom(m, dtype=np.float32)
+        errs = {}
+        for name, qm in (("int8", 127), ("int10", 511), ("int16", 32767),
+                         ("int8_w16", dict(x=127, u=32767, v=32767, m=32767, y=127))):
+            sc = oracle.calibrate(X, g, BT, G, AT, qmax=qm)
+            qx = oracle.stage_qmax(qm)["x"]
+            xq = oracle.quantize_tensor(X, sc["s_x"], qx)
+            out = oracle.winograd_q(xq, g, BT, G, AT, sc, qmax=qm)
+            ref = oracle.conv2d_direct_f64(xq.astype(np.float64) * sc["s_x"], g)
+            errs[name] = _rel(out["Yq"] * np.float64(sc["s_y"]), ref)
+        assert errs["int8"] > 3 * errs["int10"] > 9 * errs["int16"], errs
+        assert errs["int16"] < 2e-3, errs
+        # 8-bit output codes: the floor is half an output step, 1/254 of the range, plus what
+        # is left of the 16-bit Winograd-domain error
+        assert errs["int8_w16"] < 0.75 / 127 and errs["int8_w16"] < errs["int8"] / 4, errs
