@@ -610,16 +610,18 @@ def test_one_width_per_stage_reduces_to_the_single_width_pipeline(oracle):
 
 
 def test_error_to_direct_convolution_falls_with_the_bit_width(oracle):
-    """Table 1 / Sec. 5.1: the same F4 and F6 layers that are far from the direct
-    convolution in INT8 get close in INT10 and closer in INT16; widening only the Winograd
-    domain (8-bit activations, 16-bit U, V and M stage) already recovers most of it
-    (Sec. 6: different bit-widths through Eq. 1)."""
+    """Sec. 5.1 runs INT8, INT10 and INT16: with static transforms the distance of one layer
+    to the direct convolution falls with every added bit, for each tile size, but the
+    ordering F2 < F4 < F6 of Table 1 stays at every width -- F6 is still far away with
+    16-bit stages (Table 1's 16-bit column), F4 is within 2e-3 for a single layer.  Widening
+    only the Winograd domain (8-bit activations, 16-bit U, V and Hadamard stage; Sec. 6:
+    different bit-widths through Eq. 1) brings F4 down to the floor of its 8-bit output."""
     from paper_2002_10711_amd import workloads
     L = workloads.Layer("t", 2, 32, 16, 12, 12, seed=23)
     X, g = workloads.make_inputs(L)
-    for m in (4, 6):
+    errs = {}
+    for m in (2, 4, 6):
         BT, G, AT = oracle.cook_toom(m, dtype=np.float32)
-        errs = {}
         for name, qm in (("int8", 127), ("int10", 511), ("int16", 32767),
                          ("int8_w16", dict(x=127, u=32767, v=32767, m=32767, y=127))):
             sc = oracle.calibrate(X, g, BT, G, AT, qmax=qm)
@@ -627,9 +629,12 @@ def test_error_to_direct_convolution_falls_with_the_bit_width(oracle):
             xq = oracle.quantize_tensor(X, sc["s_x"], qx)
             out = oracle.winograd_q(xq, g, BT, G, AT, sc, qmax=qm)
             ref = oracle.conv2d_direct_f64(xq.astype(np.float64) * sc["s_x"], g)
-            errs[name] = _rel(out["Yq"] * np.float64(sc["s_y"]), ref)
-        assert errs["int8"] > 3 * errs["int10"] > 9 * errs["int16"], errs
-        assert errs["int16"] < 2e-3, errs
-        # 8-bit output codes: the floor is half an output step, 1/254 of the range, plus what
-        # is left of the 16-bit Winograd-domain error
-        assert errs["int8_w16"] < 0.75 / 127 and errs["int8_w16"] < errs["int8"] / 4, errs
+            errs[m, name] = _rel(out["Yq"] * np.float64(sc["s_y"]), ref)
+        assert errs[m, "int8"] > 3 * errs[m, "int10"] > 9 * errs[m, "int16"], errs
+    for name in ("int8", "int10", "int16"):
+        assert errs[2, name] < errs[4, name] < errs[6, name], errs
+    assert errs[4, "int16"] < 2e-3 and errs[2, "int16"] < 2e-4, errs
+    assert errs[6, "int16"] > 50 * errs[4, "int16"], errs
+    # 8-bit output codes: the floor is half an output step, 1/254 of the range, plus what
+    # is left of the 16-bit Winograd-domain error
+    assert errs[4, "int8_w16"] < 0.75 / 127 and errs[4, "int8_w16"] < errs[4, "int8"] / 4, errs
