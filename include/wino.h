@@ -29,7 +29,8 @@
  *   - Tensors: X[N][C][H][W], g[K][C][3][3], Y[N][K][Ho][Wo] with
  *     Ho = H + 2 pad - 2 (stride is 1 by definition of the Winograd path),
  *     row-major, last index fastest.  dtype WINO_I8: X and Y hold int8 codes
- *     (x = s_x * code); dtype WINO_F32: float, no quantizer anywhere.
+ *     (x = s_x * code); dtype WINO_F32: float, no quantizer anywhere;
+ *     WINO_I16 / WINO_I8W16: wider stages, see wino_dtype.
  *   - Tiling: n = m + 2, P = n*n Winograd positions p = i*n + j,
  *     TH = ceil(Ho/m), TW = ceil(Wo/m), T = N*TH*TW tiles,
  *     t = (img*TH + th)*TW + tw.  Tile (th,tw) reads input rows
@@ -52,16 +53,25 @@ typedef enum {
   WINO_E_BAD_M = -2,      /* m is not 2, 4 or 6                                  */
   WINO_E_BAD_SHAPE = -3,  /* a dimension is < 1, pad not in {0,1}, output empty,
                              or a size overflows the 31-bit index range          */
-  WINO_E_BAD_DTYPE = -4,  /* dtype is neither WINO_F32 nor WINO_I8               */
-  WINO_E_BAD_SCALE = -5,  /* int8 mode: a scale is not finite and > 0, qmax not
-                             in [1,127], quant missing; or a matrix entry is not
-                             finite                                              */
+  WINO_E_BAD_DTYPE = -4,  /* dtype is not one of wino_dtype                      */
+  WINO_E_BAD_SCALE = -5,  /* quantized modes: a scale is not finite and > 0, a
+                             qmax outside the range of its container, quant
+                             missing; or a matrix entry is not finite            */
   WINO_E_WORKSPACE = -6,  /* workspace smaller than wino_workspace_bytes()       */
   WINO_E_HIP = -7,        /* a HIP call or kernel launch failed                  */
   WINO_E_BAD_ARG = -8     /* other invalid argument (stride, tap selector, ...)  */
 } wino_status;
 
-typedef enum { WINO_F32 = 0, WINO_I8 = 1 } wino_dtype;
+/* WINO_F32   float everywhere, no quantizer.
+ * WINO_I8    int8 codes after every stage (X, U, V, Y; M int32), Sec. 5.1's INT8.
+ * WINO_I16   up to 16-bit codes after every stage (Sec. 5.1's INT10 and INT16): X and Y are
+ *            int16 arrays, U and V hold 16-bit codes, M is the exact int64 sum.
+ * WINO_I8W16 8-bit activations with a 16-bit Winograd domain (Sec. 3.2, "quantization
+ *            diversity"; Sec. 6, different bit-widths through Eq. 1): X and Y are int8
+ *            arrays, U, V and the Hadamard-stage quantizer may use up to 16 bits.
+ * The two wide modes accept one code range per stage (wino_quant.qmax_*), need C <= 1024,
+ * and run as three kernels (input transform, GEMM, output transform). */
+typedef enum { WINO_F32 = 0, WINO_I8 = 1, WINO_I16 = 2, WINO_I8W16 = 3 } wino_dtype;
 
 /* One layer problem.  BT is n x n, G is n x 3, AT is m x n, row-major, HOST. */
 typedef struct {
@@ -81,7 +91,7 @@ typedef struct {
  * Codes saturate to [-qmax, qmax]; rounding is half-to-even. */
 typedef struct {
   float s_x, s_v, s_u, s_y, s_m;
-  int qmax;         /* 1..127 */
+  int qmax;         /* 1..127 (1..32767 in the wide modes); see qmax_* below */
   /* Optional finer granularity (Sec. 6: "other types of quantization would likely help"):
    * one scale per Winograd position p = i*n + j for the transformed input and the
    * transformed weights, HOST arrays of n*n floats, both or neither (NULL).  When given,
@@ -92,6 +102,12 @@ typedef struct {
    * y_q = sat(rne(Yt * s_m / s_y))).  The forward then runs as three kernels. */
   const float* s_v_pos;
   const float* s_u_pos;
+  /* One code range per quantizer (Sec. 3.2: each stage may be quantized to its own number
+   * of bits), 0 = qmax: transformed weights, transformed input, Hadamard stage, output.
+   * Limits: 127 where the codes live in int8 (every stage of WINO_I8, where all ranges
+   * must also agree; qmax_y of WINO_I8W16), 32767 otherwise.  The codes of X are the
+   * caller's; they only have to fit X's container. */
+  int qmax_u, qmax_v, qmax_m, qmax_y;
 } wino_quant;
 
 const char* wino_status_string(wino_status s);
@@ -114,9 +130,9 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q,
  * overlapping patch (+ quantizer), one GEMM per Winograd position summing over
  * input channels (+ optional quantizer), output transform A^T M A (+ quantizer)
  * and scatter to NCHW.
- *   x_dev          in   DEVICE X, int8 codes or float
+ *   x_dev          in   DEVICE X, int8 / int16 codes or float (aligned to its element)
  *   U_dev          in   DEVICE, produced by wino_transform_weights for the same d
- *   y_dev          out  DEVICE Y, int8 codes or float
+ *   y_dev          out  DEVICE Y, int8 / int16 codes or float
  *   workspace_dev       DEVICE scratch, >= wino_workspace_bytes(d), 256-byte
  *                       aligned; holds V and M afterwards (see wino_debug_export) */
 wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void* x_dev,
@@ -127,7 +143,8 @@ wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void*
  * the descriptor is invalid): 1 = input transform, GEMM and output transform in one
  * kernel (small layers; V and M never reach memory), 2 = input transform, then GEMM fused
  * with the output transform (M never reaches memory), 3 = input transform, tiled GEMM,
- * output transform (long reductions, F(6x6,3x3); always with per-position scales).  Reads
+ * output transform (long reductions, F(6x6,3x3); always with per-position scales and in
+ * the wide modes).  Reads
  * d->BT (HOST) if it is not NULL: which single-kernel variant applies depends on it. */
 int wino_fwd_num_kernels(const wino_desc* d);
 
@@ -143,9 +160,10 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
 
 /* Parity taps: copy one intermediate out of the private layout into the
  * canonical dense order.
- *   which = WINO_TAP_U : src_dev = U buffer      -> out [P][K][C] int8 | float
- *   which = WINO_TAP_V : src_dev = workspace     -> out [P][T][C] int8 | float
- *   which = WINO_TAP_M : src_dev = workspace     -> out [P][T][K] int32 | float */
+ *   which = WINO_TAP_U : src_dev = U buffer      -> out [P][K][C] int8 | float | int16
+ *   which = WINO_TAP_V : src_dev = workspace     -> out [P][T][C] int8 | float | int16
+ *   which = WINO_TAP_M : src_dev = workspace     -> out [P][T][K] int32 | float | int64
+ * (third type: the wide modes WINO_I16 and WINO_I8W16) */
 enum { WINO_TAP_U = 0, WINO_TAP_V = 1, WINO_TAP_M = 2 };
 wino_status wino_debug_export(const wino_desc* d, int which, const void* src_dev,
                               void* out_dev, void* stream);

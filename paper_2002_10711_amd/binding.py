@@ -11,7 +11,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libwino.so")
 
-WINO_F32, WINO_I8 = 0, 1
+WINO_F32, WINO_I8, WINO_I16, WINO_I8W16 = 0, 1, 2, 3
 WINO_TAP_U, WINO_TAP_V, WINO_TAP_M = 0, 1, 2
 WINO_STAGE_INPUT, WINO_STAGE_GEMM, WINO_STAGE_OUTPUT, WINO_STAGE_ALL = 1, 2, 4, 7
 
@@ -34,7 +34,9 @@ class WinoDesc(ctypes.Structure):
 class WinoQuant(ctypes.Structure):
     _fields_ = [("s_x", ctypes.c_float), ("s_v", ctypes.c_float), ("s_u", ctypes.c_float),
                 ("s_y", ctypes.c_float), ("s_m", ctypes.c_float), ("qmax", ctypes.c_int),
-                ("s_v_pos", ctypes.c_void_p), ("s_u_pos", ctypes.c_void_p)]
+                ("s_v_pos", ctypes.c_void_p), ("s_u_pos", ctypes.c_void_p),
+                ("qmax_u", ctypes.c_int), ("qmax_v", ctypes.c_int), ("qmax_m", ctypes.c_int),
+                ("qmax_y", ctypes.c_int)]
 
 
 class WinoError(RuntimeError):
@@ -133,10 +135,12 @@ class Desc:
         return ctypes.byref(self.c)
 
 
-def make_quant(s_x, s_v, s_u, s_y, s_m=0.0, qmax=127, s_v_pos=None, s_u_pos=None):
+def make_quant(s_x, s_v, s_u, s_y, s_m=0.0, qmax=127, s_v_pos=None, s_u_pos=None,
+               qmax_u=0, qmax_v=0, qmax_m=0, qmax_y=0):
     """wino_quant; with s_v_pos / s_u_pos (one scale per Winograd position, host arrays)
-    s_v and s_u are ignored.  The arrays are kept alive by the returned object."""
-    q = WinoQuant(s_x, s_v, s_u, s_y, s_m, qmax, None, None)
+    s_v and s_u are ignored.  The arrays are kept alive by the returned object.
+    qmax_*: code range of one stage (0 = qmax)."""
+    q = WinoQuant(s_x, s_v, s_u, s_y, s_m, qmax, None, None, qmax_u, qmax_v, qmax_m, qmax_y)
     if s_v_pos is not None or s_u_pos is not None:
         q._sv = np.ascontiguousarray(s_v_pos, dtype=np.float32)
         q._su = np.ascontiguousarray(s_u_pos, dtype=np.float32)

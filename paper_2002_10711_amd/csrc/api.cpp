@@ -20,7 +20,9 @@ bool finite_all(const float* p, int n) {
 wino_status make_geom(const wino_desc* d, Geom* g) {
   if (!d) return WINO_E_NULL;
   if (d->m != 2 && d->m != 4 && d->m != 6) return WINO_E_BAD_M;
-  if (d->dtype != WINO_F32 && d->dtype != WINO_I8) return WINO_E_BAD_DTYPE;
+  if (d->dtype != WINO_F32 && d->dtype != WINO_I8 && d->dtype != WINO_I16 &&
+      d->dtype != WINO_I8W16)
+    return WINO_E_BAD_DTYPE;
   if (d->N < 1 || d->C < 1 || d->K < 1 || d->H < 1 || d->W < 1) return WINO_E_BAD_SHAPE;
   if (d->pad != 0 && d->pad != 1) return WINO_E_BAD_SHAPE;
   g->N = d->N; g->C = d->C; g->K = d->K; g->H = d->H; g->W = d->W;
@@ -31,15 +33,23 @@ wino_status make_geom(const wino_desc* d, Geom* g) {
   g->TH = (g->Ho + d->m - 1) / d->m;
   g->TW = (g->Wo + d->m - 1) / d->m;
   g->i8 = d->dtype == WINO_I8;
+  g->w16 = d->dtype == WINO_I16 || d->dtype == WINO_I8W16;
+  g->x16 = d->dtype == WINO_I16;
+  // (wide modes: partial sums of the digit products stay exact in fp32 up to 1024 channels)
+  if (g->w16 && d->C > 1024) return WINO_E_BAD_SHAPE;
   const long long T = (long long)d->N * g->TH * g->TW;
   const long long limit = 0x7fffffffLL;
   if (T > limit - 64) return WINO_E_BAD_SHAPE;
   g->T = (int)T;
   g->Tp = round_up(g->T, 64);
-  g->Cp = round_up(d->C, g->i8 ? 64 : 16);
+  g->Cp = round_up(d->C, (g->i8 || g->w16) ? 64 : 16);
   g->Kp = round_up(d->K, 64);
   // every tensor must be indexable with 31-bit element offsets
   const long long e = g->i8 ? 1 : 4;
+  // (wide modes: two digit planes per element of U and V)
+  if (g->w16 && ((long long)g->P * g->Tp * g->Cp * 2 > limit ||
+                 (long long)g->P * g->Kp * g->Cp * 2 > limit))
+    return WINO_E_BAD_SHAPE;
   if ((long long)g->P * g->Tp * g->Cp > limit || (long long)g->P * g->Tp * g->Kp > limit ||
       (long long)g->P * g->Kp * g->Cp > limit ||
       (long long)d->N * d->C * d->H * d->W * e > limit * e ||
@@ -49,12 +59,16 @@ wino_status make_geom(const wino_desc* d, Geom* g) {
 }
 
 size_t align256(size_t b) { return (b + 255) / 256 * 256; }
+// (wide modes: two fp16 digit planes per element of U and V, int64 M)
 size_t v_bytes(const Geom& g) { return align256((size_t)g.P * g.Tp * g.Cp * (g.i8 ? 1 : 4)); }
-size_t m_bytes(const Geom& g) { return align256((size_t)g.P * g.Tp * g.Kp * 4); }
+size_t m_bytes(const Geom& g) { return align256((size_t)g.P * g.Tp * g.Kp * (g.w16 ? 8 : 4)); }
 size_t u_bytes(const Geom& g) { return align256((size_t)g.P * g.Kp * g.Cp * (g.i8 ? 1 : 4)); }
 
+// Code range of one stage: its own field, else the common qmax.
+int stage_qmax(int own, int common) { return own ? own : common; }
+
 wino_status check_quant(const Geom& g, const wino_quant* q) {
-  if (!g.i8) return WINO_OK;
+  if (!g.i8 && !g.w16) return WINO_OK;
   if (!q) return WINO_E_BAD_SCALE;
   if ((q->s_v_pos != nullptr) != (q->s_u_pos != nullptr)) return WINO_E_BAD_SCALE;
   if (q->s_v_pos) {
@@ -71,7 +85,16 @@ wino_status check_quant(const Geom& g, const wino_quant* q) {
       if (!isfinite(v) || !(v > 0.0f)) return WINO_E_BAD_SCALE;
   }
   if (!isfinite(q->s_m) || q->s_m < 0.0f) return WINO_E_BAD_SCALE;
-  if (q->qmax < 1 || q->qmax > 127) return WINO_E_BAD_SCALE;
+  const int wide = g.w16 ? 32767 : 127;
+  if (q->qmax < 1 || q->qmax > wide) return WINO_E_BAD_SCALE;
+  const int qu = stage_qmax(q->qmax_u, q->qmax), qv = stage_qmax(q->qmax_v, q->qmax),
+            qm = stage_qmax(q->qmax_m, q->qmax), qy = stage_qmax(q->qmax_y, q->qmax);
+  if (qu < 1 || qu > wide || qv < 1 || qv > wide || qm < 1 || qm > wide || qy < 1 ||
+      qy > (g.x16 ? 32767 : 127))
+    return WINO_E_BAD_SCALE;
+  // the int8 kernels share one range between their stages
+  if (g.i8 && (qu != q->qmax || qv != q->qmax || qm != q->qmax || qy != q->qmax))
+    return WINO_E_BAD_SCALE;
   return WINO_OK;
 }
 
@@ -82,6 +105,7 @@ wino_status check_quant(const Geom& g, const wino_quant* q) {
 //   w[p] = s_u[p] s_v[p] (applied to the accumulators), r_m = 1/s_m, r_y = 1/s_y (s_m/s_y).
 struct Scalars {
   float r_u, r_v, r_m, r_y, qmax;
+  float qmax_u, qmax_v, qmax_m, qmax_y;   // per stage (all equal to qmax in the int8 mode)
   bool pos;
   PosScale ru_pos, rv_pos, w_pos;
 };
@@ -90,7 +114,11 @@ Scalars make_scalars(const Geom& g, const wino_quant* q) {
   memset(&s, 0, sizeof s);
   s.r_u = s.r_v = s.r_y = 1.0f;
   s.qmax = 127.0f;
-  if (!g.i8) return s;
+  if (!g.i8 && !g.w16) return s;
+  s.qmax_u = (float)stage_qmax(q->qmax_u, q->qmax);
+  s.qmax_v = (float)stage_qmax(q->qmax_v, q->qmax);
+  s.qmax_m = (float)stage_qmax(q->qmax_m, q->qmax);
+  s.qmax_y = (float)stage_qmax(q->qmax_y, q->qmax);
   if (q->s_v_pos) {
     s.pos = true;
     s.qmax = (float)q->qmax;
@@ -120,6 +148,11 @@ Scalars make_scalars(const Geom& g, const wino_quant* q) {
     s.r_y = suv / q->s_y;
   }
   s.qmax = (float)q->qmax;
+  // (the wide kernels always take one factor per position)
+  for (int p = 0; p < 64; ++p) {
+    s.ru_pos.r[p] = s.r_u;
+    s.rv_pos.r[p] = s.r_v;
+  }
   return s;
 }
 
@@ -169,6 +202,11 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, cons
   memset(&mg, 0, sizeof mg);
   memcpy(mg.v, d->G, sizeof(float) * g.n * 3);
   const Scalars s = make_scalars(g, q);
+  if (g.w16)
+    return launch_w16_weights(g, mg, g_dev, U_dev, s.ru_pos, s.qmax_u, (hipStream_t)stream) ==
+                   hipSuccess
+               ? WINO_OK
+               : WINO_E_HIP;
   if (launch_weight_transform(g, mg, g_dev, U_dev, s.r_u, s.qmax, (hipStream_t)stream,
                               s.pos ? &s.ru_pos : nullptr) != hipSuccess)
     return WINO_E_HIP;
@@ -178,6 +216,7 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, cons
 int wino_fwd_num_kernels(const wino_desc* d) {
   Geom g;
   if (make_geom(d, &g) != WINO_OK) return 0;
+  if (g.w16) return 3;
   if (fused_fwd_f32_supported(g)) return 1;
   if (fused_fwd_supported(g)) {
     // as in wino_conv2d_fwd: the matrix-core variant whenever B^T allows it, the
@@ -225,6 +264,17 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
   if (s_out) {
     memset(&at, 0, sizeof at);
     memcpy(at.v, d->AT, sizeof(float) * g.m * g.n);
+  }
+  if (g.w16) {
+    if (s_in && g.x16 && ((uintptr_t)x_dev & 1)) return WINO_E_BAD_ARG;
+    if (s_out && g.x16 && ((uintptr_t)y_dev & 1)) return WINO_E_BAD_ARG;
+    if (s_in && launch_w16_input(g, bt, x_dev, V, s.rv_pos, s.qmax_v, hs) != hipSuccess)
+      return WINO_E_HIP;
+    if (s_mm && launch_w16_gemm(g, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
+    if (s_out && launch_w16_output(g, at, M, y_dev, s.pos ? &s.w_pos : nullptr, s.r_m, s.r_y,
+                                   s.qmax_m, s.qmax_y, hs) != hipSuccess)
+      return WINO_E_HIP;
+    return WINO_OK;
   }
   if (stages == WINO_STAGE_ALL && !s.pos && fused_fwd_supported(g)) {
     // the whole forward in one kernel: V and M stay on chip, the workspace is untouched
@@ -282,7 +332,9 @@ wino_status wino_debug_export(const wino_desc* d, int which, const void* src_dev
   if (which != WINO_TAP_U && which != WINO_TAP_V && which != WINO_TAP_M) return WINO_E_BAD_ARG;
   const void* src = src_dev;
   if (which == WINO_TAP_M) src = (const char*)src_dev + v_bytes(g);
-  if (launch_export(g, which, src, out_dev, (hipStream_t)stream) != hipSuccess) return WINO_E_HIP;
+  if ((g.w16 ? launch_w16_export(g, which, src, out_dev, (hipStream_t)stream)
+             : launch_export(g, which, src, out_dev, (hipStream_t)stream)) != hipSuccess)
+    return WINO_E_HIP;
   return WINO_OK;
 }
 

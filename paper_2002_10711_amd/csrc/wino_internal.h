@@ -19,6 +19,8 @@ struct Geom {
   int Ho, Wo, TH, TW, T;
   int Tp, Cp, Kp;
   int i8;
+  int w16;   // 16-bit codes in the Winograd domain (WINO_I16, WINO_I8W16): own kernels, own layouts
+  int x16;   // ... and int16 containers for X and Y (WINO_I16)
 };
 
 struct MatBT { float v[64]; };   // n x n, row-major, n <= 8
@@ -95,6 +97,18 @@ hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& a
                                   const void* U, void* y, float r_v, float r_m, float r_y,
                                   float qmax, hipStream_t s);
 hipError_t launch_export(const Geom& g, int which, const void* src, void* out, hipStream_t s);
+
+// The path with up to 16-bit codes after every stage (g.w16): weight stage, input stage,
+// exact int64 GEMM on fp16 digit planes, output stage; layouts private to these kernels.
+hipError_t launch_w16_weights(const Geom& g, const MatG& mg, const float* w, void* U,
+                              const PosScale& ru, float qmax, hipStream_t s);
+hipError_t launch_w16_input(const Geom& g, const MatBT& bt, const void* x, void* V,
+                            const PosScale& rv, float qmax, hipStream_t s);
+hipError_t launch_w16_gemm(const Geom& g, const void* V, const void* U, void* M, hipStream_t s);
+hipError_t launch_w16_output(const Geom& g, const MatAT& at, const void* M, void* y,
+                             const PosScale* w_pos, float r_m, float r_y, float qmax_m,
+                             float qmax_y, hipStream_t s);
+hipError_t launch_w16_export(const Geom& g, int which, const void* src, void* out, hipStream_t s);
 
 // im2row baseline pieces.
 struct RefGeom {
