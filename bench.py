@@ -27,13 +27,15 @@ sys.path.insert(0, ROOT)
 from paper_2002_10711_amd import workloads  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-MFMA_PEAK = {"int8": 5000.0, "f32": 157.3}   # dense TOP/s, TFLOP/s
+MFMA_PEAK = {"int8": 5000.0, "f32": 157.3, "f16": 2500.0}   # dense TOP/s, TFLOP/s
+WIDE = ("i16", "i8w16")    # dtypes with 16-bit codes in the Winograd domain
 HBM_TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 
 def pick_workload(name):
     table = {}
-    for L in (workloads.config2("i8") + workloads.config2("f32") + workloads.config3() +
+    for L in (workloads.config2("i8") + workloads.config2("f32") + workloads.config2("i16") +
+              workloads.config2("i8w16") + workloads.config3() +
               workloads.config4() + workloads.config5()):
         table[L.name] = L
     if name not in table:
@@ -50,18 +52,22 @@ def algorithmic(L, BT, AT):
     one fused multiply-add (2 flops) per nonzero matrix entry and vector element, one
     int->float conversion per accumulator, four operations per quantized element
     (scale, round, saturate, convert)."""
-    e = 1 if L.dtype == "i8" else 4
-    qops = 4 if L.dtype == "i8" else 0
+    wide = L.dtype in WIDE
+    e = 1 if L.dtype in ("i8", "i8w16") else 2 if L.dtype == "i16" else 4   # X, Y element
+    ew = 2 if wide else e                                                   # U, V element
+    quantized = L.dtype != "f32"
+    qops = 4 if quantized else 0
     n = L.m + 2
     P = n * n
     TH, TW = -(-L.Ho // L.m), -(-L.Wo // L.m)
     T = L.N * TH * TW
     nzb, nza = int(np.count_nonzero(BT)), int(np.count_nonzero(AT))
     x_b, y_b = L.N * L.C * L.H * L.W * e, L.N * L.K * L.Ho * L.Wo * e
-    v_b, u_b, m_b = P * T * L.C * e, P * L.C * L.K * e, 4 * P * T * L.K
-    mm = 2 * P * T * L.C * L.K
+    v_b, u_b, m_b = P * T * L.C * ew, P * L.C * L.K * ew, (8 if wide else 4) * P * T * L.K
+    # wide modes: a 16-bit product is four fp16 digit products on the matrix cores
+    mm = 2 * P * T * L.C * L.K * (4 if wide else 1)
     alu_in = T * L.C * (2 * 2 * n * nzb + qops * P)
-    alu_out = T * L.K * (2 * (n + L.m) * nza + (P if L.dtype == "i8" else 0) + qops * L.m * L.m)
+    alu_out = T * L.K * (2 * (n + L.m) * nza + (P if quantized else 0) + qops * L.m * L.m)
     alu_w = L.K * L.C * (2 * (3 * 3 * n + 3 * n * n) + qops * P)
     return {
         "weight_transform": dict(bytes=9 * L.C * L.K * 4 + u_b, ops=0, alu=alu_w),
@@ -78,7 +84,7 @@ def algorithmic(L, BT, AT):
 def roofline_entry(name, alg, us, dtype, traffic):
     """The bound is whichever of HBM, MFMA and vector-ALU peak needs the longest time
     for the kernel's algorithmic bytes / GEMM operations / transform operations."""
-    mf = MFMA_PEAK["int8" if dtype == "i8" else "f32"]
+    mf = MFMA_PEAK["int8" if dtype == "i8" else "f16" if dtype in WIDE else "f32"]
     t = {"hbm": alg["bytes"] / (HBM_PEAK_GBS * 1e9), "mfma": alg["ops"] / (mf * 1e12),
          "alu": alg["alu"] / (ALU_PEAK_TFLOPS * 1e12)}
     bound = max(t, key=t.get)
@@ -105,26 +111,32 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
     wb.lib()
     dev = torch.device("cuda:0")
     i8 = L.dtype == "i8"
+    wide = L.dtype in WIDE
+    qm = workloads.STAGE_QMAX.get(L.dtype)
     scales = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[
         L.name.replace("_f32", "_i8")]
     X, g = workloads.make_inputs(L)
     BT, G, AT = wb.wino_cook_toom(L.m)
     if L.flex_sigma > 0:
         BT, G, AT = workloads.perturb_transforms(BT, G, AT, L.flex_sigma, L.seed)
-    dt = wb.WINO_I8 if i8 else wb.WINO_F32
+    dt = {"i8": wb.WINO_I8, "f32": wb.WINO_F32, "i16": wb.WINO_I16, "i8w16": wb.WINO_I8W16}[L.dtype]
     desc = wb.Desc(L.N, L.C, L.K, L.H, L.W, L.pad, L.m, dt, BT=BT, G=G, AT=AT)
     quant = None
-    if i8:
-        quant = wb.make_quant(scales["s_x"], scales["s_v"], scales["s_u"], scales["s_y"])
+    ydt = torch.float32
+    if i8 or wide:
+        quant = wb.make_quant(scales["s_x"], scales["s_v"], scales["s_u"], scales["s_y"], 0.0, qm["y"],
+                              qmax_u=qm["u"], qmax_v=qm["v"], qmax_m=qm["m"], qmax_y=qm["y"])
         # input codes of the previous layer's quantizer (input preparation, not the path)
-        xh = np.clip(np.rint(X / np.float32(scales["s_x"])), -127, 127).astype(np.int8)
+        xh = np.clip(np.rint(X / np.float32(scales["s_x"])), -qm["x"], qm["x"]).astype(
+            np.int16 if L.dtype == "i16" else np.int8)
+        ydt = torch.int16 if L.dtype == "i16" else torch.int8
     else:
         xh = X
     x = torch.from_numpy(xh).to(dev)
     gd = torch.from_numpy(g).to(dev)
     U = torch.empty(wb.wino_weights_bytes(desc), dtype=torch.uint8, device=dev)
     ws = torch.empty(wb.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
-    y = torch.empty((L.N, L.K, L.Ho, L.Wo), dtype=torch.int8 if i8 else torch.float32, device=dev)
+    y = torch.empty((L.N, L.K, L.Ho, L.Wo), dtype=ydt, device=dev)
     stream = torch.cuda.Stream()          # default priority
 
     def step():
@@ -204,23 +216,28 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
          ("gemm", wb.WINO_STAGE_GEMM), ("output_transform", wb.WINO_STAGE_OUTPUT)])
 
     # im2row baseline on the same layer, forward only (weights packed once)
+    # (the baseline has int8 and fp32 forms: 8-bit activations are compared with the int8
+    # one, the int16 workload has no baseline)
     s_w = scales.get("s_w", 1.0)
-    if i8:
-        wq = np.clip(np.rint(g / np.float32(s_w)), -127, 127).astype(np.int8)
-    else:
-        wq = g
-    wdev = torch.from_numpy(wq).to(dev)
-    wp = torch.empty(wb.conv2d_ref_packed_weights_bytes(L.C, L.K, dt), dtype=torch.uint8, device=dev)
-    rws = torch.empty(wb.conv2d_ref_workspace_bytes(L.N, L.C, L.K, L.H, L.W, 1, L.pad, dt),
-                      dtype=torch.uint8, device=dev)
-    with torch.cuda.stream(stream):
-        wb.conv2d_ref_pack_weights(L.C, L.K, dt, wdev, wp, stream=stream)
+    rdt = wb.WINO_F32 if L.dtype == "f32" else wb.WINO_I8
+    ms_ref = None
+    if L.dtype != "i16":
+        if rdt == wb.WINO_I8:
+            wq = np.clip(np.rint(g / np.float32(s_w)), -127, 127).astype(np.int8)
+        else:
+            wq = g
+        wdev = torch.from_numpy(wq).to(dev)
+        wp = torch.empty(wb.conv2d_ref_packed_weights_bytes(L.C, L.K, rdt), dtype=torch.uint8, device=dev)
+        rws = torch.empty(wb.conv2d_ref_workspace_bytes(L.N, L.C, L.K, L.H, L.W, 1, L.pad, rdt),
+                          dtype=torch.uint8, device=dev)
+        with torch.cuda.stream(stream):
+            wb.conv2d_ref_pack_weights(L.C, L.K, rdt, wdev, wp, stream=stream)
 
-    def ref_fwd():
-        wb.conv2d_ref_gpu(L.N, L.C, L.K, L.H, L.W, 1, L.pad, dt, x, wp, y, scales["s_x"], s_w,
-                          scales["s_y"], 127, rws, stream=stream)
+        def ref_fwd():
+            wb.conv2d_ref_gpu(L.N, L.C, L.K, L.H, L.W, 1, L.pad, rdt, x, wp, y, scales["s_x"], s_w,
+                              scales["s_y"], 127, rws, stream=stream)
 
-    ms_ref = timed(ref_fwd, max(10, steps // 4), max(2, warmup // 4))
+        ms_ref = timed(ref_fwd, max(10, steps // 4), max(2, warmup // 4))
     extra = {}
     if cold:
         # cold: every call finds neither X, U nor anything else in L2 / Infinity Cache
@@ -281,10 +298,11 @@ def cpu_leg(L):
     BT, G, AT = oracle.cook_toom(L.m, dtype=np.float32)
     if L.flex_sigma > 0:
         BT, G, AT = workloads.perturb_transforms(BT, G, AT, L.flex_sigma, L.seed)
-    if L.dtype == "i8":
+    if L.dtype != "f32":
         sc = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[L.name]
-        xq = oracle.quantize_tensor(X, sc["s_x"])
-        fn = lambda: oracle.winograd_q(xq, g, BT, G, AT, sc, pad=L.pad)
+        qm = workloads.STAGE_QMAX[L.dtype]
+        xq = oracle.quantize_tensor(X, sc["s_x"], qm["x"])
+        fn = lambda: oracle.winograd_q(xq, g, BT, G, AT, sc, pad=L.pad, qmax=qm)
     else:
         fn = lambda: oracle.winograd_f64(X, g, BT, G, AT, L.pad)
     fn()
@@ -354,7 +372,7 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": r["ms_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8" if L.dtype == "i8" else "f32",
+        "dtype": {"i8": "int8", "f32": "f32", "i16": "int16", "i8w16": "int8 data, int16 Winograd domain"}[L.dtype],
         "data": "synthetic",
         "config": {"workload": "%s: N=%d C=%d K=%d %dx%d pad=%d F(%dx%d,3x3) %s" % (
             L.name, L.N, L.C, L.K, L.H, L.W, L.pad, L.m, L.m, L.dtype),
@@ -362,7 +380,7 @@ def main():
         "fwd_only_ms": r["ms_fwd"],
         "fwd_only_tops": L.direct_ops / (r["ms_fwd"] * 1e-3) / 1e12,
         "im2row_baseline_ms": r["ms_ref"],
-        "speedup_vs_im2row": r["ms_ref"] / r["ms_fwd"],
+        "speedup_vs_im2row": r["ms_ref"] / r["ms_fwd"] if r["ms_ref"] else None,
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
                                                "kernel", "avg_us")},
         "kernels": kernels,

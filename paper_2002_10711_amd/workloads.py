@@ -30,7 +30,7 @@ class Layer:
     m: int = 4            # Winograd output tile (ignored when stride == 2)
     stride: int = 1
     pad: int = 1
-    dtype: str = "i8"     # "i8" or "f32"
+    dtype: str = "i8"     # "i8", "f32", "i16" or "i8w16" (see STAGE_QMAX)
     relu_input: bool = True
     flex_sigma: float = 0.0   # std of the noise added to B^T, G, A^T ("flex" transforms)
     seed: int = 0
@@ -47,6 +47,17 @@ class Layer:
     def direct_ops(self):
         """Direct-convolution-equivalent operations: 2 N K Ho Wo C 9 (all nine taps counted)."""
         return 2 * self.N * self.K * self.Ho * self.Wo * self.C * 9
+
+
+# Code ranges per quantizer (input x, transformed weights u, transformed input v, Hadamard
+# stage m, output y) of the dtypes a Layer can name: "i8" is the paper's INT8 pipeline,
+# "i16" its INT16 one (Sec. 5.1), "i8w16" 8-bit activations around a 16-bit Winograd domain
+# (Sec. 3.2, one bit-width per stage).
+STAGE_QMAX = {
+    "i8": dict(x=127, u=127, v=127, m=127, y=127),
+    "i16": dict(x=32767, u=32767, v=32767, m=32767, y=32767),
+    "i8w16": dict(x=127, u=32767, v=32767, m=32767, y=127),
+}
 
 
 def _seed(config, layer):
