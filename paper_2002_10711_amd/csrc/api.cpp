@@ -216,7 +216,15 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q, cons
 int wino_fwd_num_kernels(const wino_desc* d) {
   Geom g;
   if (make_geom(d, &g) != WINO_OK) return 0;
-  if (g.w16) return 3;
+  if (g.w16) {
+    MatAT at;
+    memset(&at, 0, sizeof at);
+    if (d->AT && finite_all(d->AT, g.m * g.n)) {
+      memcpy(at.v, d->AT, sizeof(float) * g.m * g.n);
+      if (w16_gemm_out_supported(g, at)) return 2;
+    }
+    return 3;
+  }
   if (fused_fwd_f32_supported(g)) return 1;
   if (fused_fwd_supported(g)) {
     // as in wino_conv2d_fwd: the matrix-core variant whenever B^T allows it, the
@@ -270,6 +278,12 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
     if (s_out && g.x16 && ((uintptr_t)y_dev & 1)) return WINO_E_BAD_ARG;
     if (s_in && launch_w16_input(g, bt, x_dev, V, s.rv_pos, s.qmax_v, hs) != hipSuccess)
       return WINO_E_HIP;
+    const PosScale* wpw = s.pos ? &s.w_pos : nullptr;
+    if (s_mm && s_out && w16_gemm_out_supported(g, at))
+      return launch_w16_gemm_out(g, at, V, U_dev, y_dev, wpw, s.r_m, s.r_y, s.qmax_m, s.qmax_y,
+                                 hs) == hipSuccess
+                 ? WINO_OK
+                 : WINO_E_HIP;
     if (s_mm && launch_w16_gemm(g, V, U_dev, M, hs) != hipSuccess) return WINO_E_HIP;
     if (s_out && launch_w16_output(g, at, M, y_dev, s.pos ? &s.w_pos : nullptr, s.r_m, s.r_y,
                                    s.qmax_m, s.qmax_y, hs) != hipSuccess)

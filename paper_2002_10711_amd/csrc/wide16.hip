@@ -99,20 +99,35 @@ __global__ __launch_bounds__(256) void input_transform_w16(Geom g, MatBT bt,
   const int tid = threadIdx.x, r = tid & 15, cc = tid >> 4;
   const int t = blockIdx.x * 16 + r, c = blockIdx.y * 16 + cc;
   float d[n][n];
+  {
+    // branch-free: every lane loads from an address clamped into an image that exists and
+    // zeroes what fell outside (loads under a branch would be waited for one by one)
+    const bool live = t < g.T && c < g.C;
+    const int tc = t < g.T ? t : g.T - 1, ch = c < g.C ? c : g.C - 1;
+    const int tw = tc % g.TW, th = (tc / g.TW) % g.TH, img = tc / (g.TW * g.TH);
+    const XT* base = x + ((size_t)img * g.C + ch) * g.H * g.W;
+    XT raw[n][n];
 #pragma unroll
-  for (int j = 0; j < n; ++j)
-#pragma unroll
-    for (int l = 0; l < n; ++l) d[j][l] = 0.0f;
-  if (t < g.T && c < g.C) {
-    const int tw = t % g.TW, th = (t / g.TW) % g.TH, img = t / (g.TW * g.TH);
-    const XT* base = x + ((size_t)img * g.C + c) * g.H * g.W;
-#pragma unroll
-    for (int j = 0; j < n; ++j)
+    for (int j = 0; j < n; ++j) {
+      const int h = th * M - g.pad + j;
+      const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
 #pragma unroll
       for (int l = 0; l < n; ++l) {
-        const int h = th * M - g.pad + j, ww = tw * M - g.pad + l;
-        if (h >= 0 && h < g.H && ww >= 0 && ww < g.W) d[j][l] = (float)base[h * g.W + ww];
+        const int ww = tw * M - g.pad + l;
+        const int wc = ww < 0 ? 0 : (ww >= g.W ? g.W - 1 : ww);
+        raw[j][l] = base[hc * g.W + wc];
       }
+    }
+#pragma unroll
+    for (int j = 0; j < n; ++j) {
+      const int h = th * M - g.pad + j;
+      const bool hok = live && h >= 0 && h < g.H;
+#pragma unroll
+      for (int l = 0; l < n; ++l) {
+        const int ww = tw * M - g.pad + l;
+        d[j][l] = (hok && ww >= 0 && ww < g.W) ? (float)raw[j][l] : 0.0f;
+      }
+    }
   }
   float Vf[n][n];
   transform_patch<M, kSparse>(d, bt, Vf);
@@ -266,6 +281,128 @@ __global__ __launch_bounds__(256) void output_transform_w16(Geom g, MatAT at,
     }
 }
 
+// Hadamard/GEMM stage and output stage in one kernel: M never reaches memory.  A wavefront
+// owns 16 tiles x 16 output channels (the MFMA result: lane = tile, four channels); the
+// workgroup's four wavefronts share the tiles.  The Winograd positions are visited column
+// by column (j outer, i inner), which lets the output transform run along with them in
+// exactly the pinned order: z[a] = fma(A^T[a][i], M[i][j], z[a]) as the accumulators of
+// column j arrive (ascending i), then Y[a][b] = fma(z[a], A^T[b][j], Y[a][b]) once the
+// column is complete (ascending j).  A lane therefore keeps m + m*m floats per channel
+// instead of all n*n accumulators, which leaves room for the three digit-pair accumulators
+// and a ring of operands loaded kDepth steps ahead.  The column loop is a real loop (it
+// bounds how far the compiler may hoist loads); inside it everything is unrolled, so
+// NCH = Cp / 32 is a compile-time constant and the ring slots are static.  At most 512
+// channels, so the two middle digit sums may share an accumulator.  Entries of A^T that
+// are zero in the Cook-Toom pattern are skipped along i (compile time); along j they are
+// multiplied out (fma(z, 0, Y) == Y).
+template <int M, typename YT, int NCH>
+__global__ __launch_bounds__(256) void gemm_out_w16_kernel(Geom g, MatAT at,
+                                                           const half8* __restrict__ V,
+                                                           const half8* __restrict__ U,
+                                                           YT* __restrict__ y, PosScale w,
+                                                           int use_w, float r_m, float r_y,
+                                                           float qmax_m, float qmax_y) {
+  constexpr int n = M + 2;
+  constexpr int SJ = n * NCH;                          // steps per column
+  constexpr int kDepth = M == 4 ? 6 : M == 2 ? 8 : 4;
+  static_assert(SJ % kDepth == 0 && kDepth <= SJ, "ring depth must divide a column's steps");
+  const int tb = blockIdx.x * 16, kb = blockIdx.y * 64;
+  const int lane = threadIdx.x & 63, r = lane & 15, grp = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int t = tb + r;
+  // 16-byte pieces: U block pair of (position, 16 channels k, 32 channels c) = 128 pieces,
+  // digit planes 64 apart; V row piece = 8 channels
+  const uint32_t ubase = (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)NCH * 128u + (uint32_t)lane;
+  const uint32_t ustep_p = (uint32_t)(g.Kp >> 4) * (uint32_t)NCH * 128u;
+  const uint32_t vrow = (uint32_t)(g.Cp >> 3);
+  const uint32_t vbase = (uint32_t)t * vrow + (uint32_t)grp;
+  const uint32_t vplane = (uint32_t)g.Tp * vrow;
+
+  half8 ruh[kDepth], rul[kDepth], rvh[kDepth], rvl[kDepth];
+  // step sj of column j: position p = (sj / NCH) * n + j, channel step sj % NCH
+  auto fetch = [&](int sj, int j, int slot) {
+    const int p = (sj / NCH) * n + j, ch = sj % NCH;
+    const uint32_t uo = ubase + (uint32_t)p * ustep_p + (uint32_t)ch * 128u;
+    const uint32_t vo = vbase + (uint32_t)(2 * p) * vplane + (uint32_t)ch * 4u;
+    ruh[slot] = U[uo];
+    rul[slot] = U[uo + 64u];
+    rvh[slot] = V[vo];
+    rvl[slot] = V[vo + vplane];
+  };
+#pragma unroll
+  for (int s = 0; s < kDepth; ++s) fetch(s, 0, s);
+
+  float z[M][4], Y[M][M][4];
+#pragma unroll
+  for (int a = 0; a < M; ++a)
+#pragma unroll
+    for (int b = 0; b < M; ++b)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) Y[a][b][rr] = 0.0f;
+
+#pragma unroll 1
+  for (int j = 0; j < n; ++j) {
+    // (the last column prefetches the steps of column n - 1 again instead of branching
+    // around the loads)
+    const int jn = j + 1 < n ? j + 1 : j;
+#pragma unroll
+    for (int i = 0; i < n; ++i) {
+      v4f hh = v4f{0, 0, 0, 0}, mid = hh, ll = hh;
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        const int sj = i * NCH + ch, slot = sj % kDepth;
+        const half8 uh = ruh[slot], ul = rul[slot];
+        const half8 vh = rvh[slot], vl = rvl[slot];
+        if (sj + kDepth < SJ) fetch(sj + kDepth, j, slot);
+        else fetch(sj + kDepth - SJ, jn, slot);
+        hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vh, hh, 0, 0, 0);
+        mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vl, mid, 0, 0, 0);
+        mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vh, mid, 0, 0, 0);
+        ll = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vl, ll, 0, 0, 0);
+      }
+      const float wp = w.r[i * n + j];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        // exact in fp64 (below 2^53), one rounding to fp32: the conversion of the integer M
+        const double dm = __builtin_fma((double)hh[rr], 65536.0,
+                                        __builtin_fma((double)mid[rr], 256.0, (double)ll[rr]));
+        float f = (float)dm;
+        if (use_w) f = f * wp;
+        if (r_m > 0.0f) f = (float)quantize(f, r_m, qmax_m);
+#pragma unroll
+        for (int a = 0; a < M; ++a) {
+          if (i == 0) z[a][rr] = 0.0f;
+          if (at_nonzero<M, true>(a, i)) z[a][rr] = __builtin_fmaf(at.v[a * n + i], f, z[a][rr]);
+        }
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < M; ++b) {
+      const float abj = at.v[b * n + j];
+#pragma unroll
+      for (int a = 0; a < M; ++a)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) Y[a][b][rr] = __builtin_fmaf(z[a][rr], abj, Y[a][b][rr]);
+    }
+  }
+  if (t >= g.T) return;
+  const int tw = t % g.TW, th = (t / g.TW) % g.TH, img = t / (g.TW * g.TH);
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const int k = kb + wave * 16 + grp * 4 + rr;
+    if (k >= g.K) continue;
+    YT* plane = y + ((size_t)img * g.K + k) * g.Ho * g.Wo;
+#pragma unroll
+    for (int a = 0; a < M; ++a)
+#pragma unroll
+      for (int b = 0; b < M; ++b) {
+        const int h = th * M + a, x = tw * M + b;
+        if (h < g.Ho && x < g.Wo)
+          plane[(size_t)h * g.Wo + x] = (YT)quantize(Y[a][b][rr], r_y, qmax_y);
+      }
+  }
+}
+
 // Taps: canonical dense order, int16 codes (U, V) or the int64 accumulators (M).
 __global__ __launch_bounds__(256) void export_u_w16(const _Float16* __restrict__ U,
                                                     int16_t* __restrict__ out, Geom g) {
@@ -372,6 +509,59 @@ hipError_t launch_w16_output(const Geom& g, const MatAT& at, const void* M, void
     case 2: return output_m<2>(g, at, M, y, w_pos, r_m, r_y, qmax_m, qmax_y, s);
     case 4: return output_m<4>(g, at, M, y, w_pos, r_m, r_y, qmax_m, qmax_y, s);
     default: return output_m<6>(g, at, M, y, w_pos, r_m, r_y, qmax_m, qmax_y, s);
+  }
+}
+
+// GEMM + output in one kernel: Cook-Toom pattern of A^T, 64..512 padded channels in powers
+// of two, every offset in 32 bits.
+bool w16_gemm_out_supported(const Geom& g, const MatAT& at) {
+  const bool sparse = g.m == 2   ? fits_mask(at.v, g.m * g.n, CookToomMask<2>::at)
+                      : g.m == 4 ? fits_mask(at.v, g.m * g.n, CookToomMask<4>::at)
+                                 : fits_mask(at.v, g.m * g.n, CookToomMask<6>::at);
+  const bool nch_ok = g.Cp == 64 || g.Cp == 128 || g.Cp == 256 || g.Cp == 512;
+  return sparse && nch_ok && g.Kp / 64 <= 65535 &&
+         (size_t)g.P * 2 * g.Tp * g.Cp / 8 < 0xffffffffull &&
+         (size_t)g.P * 2 * g.Kp * g.Cp / 8 < 0xffffffffull;
+}
+
+namespace {
+template <int M, typename YT>
+hipError_t gemm_out_my(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
+                       const PosScale* w, float r_m, float r_y, float qmax_m, float qmax_y,
+                       hipStream_t s) {
+  dim3 grid(g.Tp / 16, g.Kp / 64);
+  PosScale one;
+  for (int p = 0; p < 64; ++p) one.r[p] = 1.0f;
+  const PosScale& ws = w ? *w : one;
+  const half8* Vh = (const half8*)V;
+  const half8* Uh = (const half8*)U;
+  YT* yo = (YT*)y;
+  const int use_w = w != nullptr;
+  switch (g.Cp) {
+    case 64: gemm_out_w16_kernel<M, YT, 2><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, use_w, r_m, r_y, qmax_m, qmax_y); break;
+    case 128: gemm_out_w16_kernel<M, YT, 4><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, use_w, r_m, r_y, qmax_m, qmax_y); break;
+    case 256: gemm_out_w16_kernel<M, YT, 8><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, use_w, r_m, r_y, qmax_m, qmax_y); break;
+    default: gemm_out_w16_kernel<M, YT, 16><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, use_w, r_m, r_y, qmax_m, qmax_y); break;
+  }
+  return hipGetLastError();
+}
+template <int M>
+hipError_t gemm_out_m(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
+                      const PosScale* w, float r_m, float r_y, float qmax_m, float qmax_y,
+                      hipStream_t s) {
+  return g.x16 ? gemm_out_my<M, int16_t>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s)
+               : gemm_out_my<M, int8_t>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s);
+}
+}  // namespace
+
+hipError_t launch_w16_gemm_out(const Geom& g, const MatAT& at, const void* V, const void* U,
+                               void* y, const PosScale* w_pos, float r_m, float r_y, float qmax_m,
+                               float qmax_y, hipStream_t s) {
+  if (!w16_gemm_out_supported(g, at)) return hipErrorInvalidValue;
+  switch (g.m) {
+    case 2: return gemm_out_m<2>(g, at, V, U, y, w_pos, r_m, r_y, qmax_m, qmax_y, s);
+    case 4: return gemm_out_m<4>(g, at, V, U, y, w_pos, r_m, r_y, qmax_m, qmax_y, s);
+    default: return gemm_out_m<6>(g, at, V, U, y, w_pos, r_m, r_y, qmax_m, qmax_y, s);
   }
 }
 

@@ -108,6 +108,11 @@ hipError_t launch_w16_gemm(const Geom& g, const void* V, const void* U, void* M,
 hipError_t launch_w16_output(const Geom& g, const MatAT& at, const void* M, void* y,
                              const PosScale* w_pos, float r_m, float r_y, float qmax_m,
                              float qmax_y, hipStream_t s);
+// GEMM and output stage in one kernel (M stays in registers); only where supported.
+bool w16_gemm_out_supported(const Geom& g, const MatAT& at);
+hipError_t launch_w16_gemm_out(const Geom& g, const MatAT& at, const void* V, const void* U,
+                               void* y, const PosScale* w_pos, float r_m, float r_y, float qmax_m,
+                               float qmax_y, hipStream_t s);
 hipError_t launch_w16_export(const Geom& g, int which, const void* src, void* out, hipStream_t s);
 
 // im2row baseline pieces.

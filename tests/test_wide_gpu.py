@@ -33,7 +33,7 @@ def run_wide(case, qm, sc):
                           sc.get("s_m", 0.0), qm["y"], s_v_pos=sc.get("s_v_pos"),
                           s_u_pos=sc.get("s_u_pos"), qmax_u=qm["u"], qmax_v=qm["v"],
                           qmax_m=qm["m"], qmax_y=qm["y"])
-    assert wb.wino_fwd_num_kernels(desc) == 3
+    assert wb.wino_fwd_num_kernels(desc) in (2, 3)
     x = torch.from_numpy(case["xq"].astype(np.int16 if x16 else np.int8)).to(dev)
     g = torch.from_numpy(case["g"]).to(dev)
     U = torch.empty(wb.wino_weights_bytes(desc), dtype=torch.uint8, device=dev)
