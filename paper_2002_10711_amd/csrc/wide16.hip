@@ -4,8 +4,8 @@
 // the way to recover F4/F6 accuracy).
 //
 // The matrix cores have no 16-bit integer instruction.  A code v in [-32767, 32767] is
-// split into two balanced base-256 digits, v = 256 a + b with b in [-128, 127] and
-// a in [-128, 128], both exact in fp16, and the per-position GEMM of Sec. 5.3 becomes four
+// split into two balanced base-256 digits, v = 256 a + b with |a| <= 128 and |b| <= 128,
+// both exact in fp16, and the per-position GEMM of Sec. 5.3 becomes four
 // fp16 MFMAs per 32 channels,
 //
 //     sum_c u v = 2^16 sum a_u a_v + 2^8 (sum a_u b_v + sum b_u a_v) + sum b_u b_v .
@@ -21,6 +21,8 @@
 //                      operand: lane = (c % 32 / 8) * 16 + k % 16 holds channels c % 8
 //   M [P][Tp][Kp]      int64
 // with Tp, Kp, Cp rounded up to 64; padding channels hold zero.
+#include <type_traits>
+
 #include "output_stage.h"
 
 namespace wino {
@@ -37,14 +39,62 @@ __host__ __device__ inline size_t v16_index(int Tp, int Cp, int p, int digit, in
   return (((size_t)p * 2 + digit) * Tp + t) * Cp + c;
 }
 
-// v = 256 a + b, b in [-128, 127]
-__device__ __forceinline__ void split_code(int v, _Float16& a, _Float16& b) {
-  const int lo = ((v + 128) & 255) - 128;
-  a = (_Float16)(float)((v - lo) >> 8);
-  b = (_Float16)(float)lo;
+// v = 256 a + b with |a|, |b| <= 128, on the code as a float (an integer, |v| <= 32767):
+// a = v / 256 rounded to the nearest integer (ties to even), b the exact remainder.
+__device__ __forceinline__ void split_code(float v, _Float16& a, _Float16& b) {
+  const float hi = __builtin_rintf(v * 0.00390625f);
+  a = (_Float16)hi;
+  b = (_Float16)__builtin_fmaf(hi, -256.0f, v);
+}
+// sat(rne(v * r)) as a float holding the integer code
+__device__ __forceinline__ float quantize_f(float v, float r, float qmax) {
+  return __builtin_amdgcn_fmed3f(__builtin_rintf(v * r), -qmax, qmax);
 }
 __device__ __forceinline__ int join_code(_Float16 a, _Float16 b) {
   return (int)(float)a * 256 + (int)(float)b;
+}
+
+// Stores one m x m tile of output codes; (h0, w0) is its top-left corner in the plane.
+// fast (uniform): m divides Ho and Wo and Y is 8-byte aligned, so every tile is whole and
+// every tile row is one aligned piece of m codes.
+template <int M, typename YT>
+__device__ __forceinline__ void store_codes(YT* __restrict__ plane, const Geom& g, int h0, int w0,
+                                            const int (&q)[M][M], bool fast) {
+  if (fast) {
+#pragma unroll
+    for (int a = 0; a < M; ++a) {
+      YT* row = plane + (size_t)(h0 + a) * g.Wo + w0;
+      if constexpr (sizeof(YT) == 2) {
+        uint32_t wd[M / 2];
+#pragma unroll
+        for (int e = 0; e < M / 2; ++e)
+          wd[e] = ((uint32_t)q[a][2 * e] & 0xffffu) | ((uint32_t)q[a][2 * e + 1] << 16);
+        if constexpr (M == 4) {
+          typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+          *(v2u*)row = v2u{wd[0], wd[1]};
+        } else {
+#pragma unroll
+          for (int e = 0; e < M / 2; ++e) ((uint32_t*)row)[e] = wd[e];
+        }
+      } else {
+        if constexpr (M == 4) {
+          *(uint32_t*)row = ((uint32_t)q[a][0] & 0xffu) | (((uint32_t)q[a][1] & 0xffu) << 8) |
+                            (((uint32_t)q[a][2] & 0xffu) << 16) | ((uint32_t)q[a][3] << 24);
+        } else {
+#pragma unroll
+          for (int e = 0; e < M / 2; ++e)
+            ((uint16_t*)row)[e] =
+                (uint16_t)(((uint32_t)q[a][2 * e] & 0xffu) | (((uint32_t)q[a][2 * e + 1] & 0xffu) << 8));
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int a = 0; a < M; ++a)
+#pragma unroll
+      for (int b = 0; b < M; ++b)
+        if (h0 + a < g.Ho && w0 + b < g.Wo) plane[(size_t)(h0 + a) * g.Wo + w0 + b] = (YT)q[a][b];
+  }
 }
 
 // Weight stage (Eq. 1: U = G g G^T; quantizer of Sec. 3.2): one thread per (k, c) of the
@@ -78,26 +128,27 @@ __global__ __launch_bounds__(256) void weight_transform_w16(Geom g, MatG mg,
     for (int j = 0; j < n; ++j) {
       const int p = i * n + j;
       _Float16 a, b;
-      split_code(quantize(Uf[i][j], ru.r[p], qmax), a, b);
+      split_code(quantize_f(Uf[i][j], ru.r[p], qmax), a, b);
       U[u16_index(g.Kp, g.Cp, p, 0, k, c)] = a;
       U[u16_index(g.Kp, g.Cp, p, 1, k, c)] = b;
     }
 }
 
-// Input stage (Eq. 1: V = B^T d B on every patch, Sec. 3.2): a workgroup owns 16
-// consecutive tiles x 16 channels, one (tile, channel) per thread with the tiles along the
-// lanes (neighbouring patches overlap: the loads of a wavefront fall into a few runs of
-// an image row).  The codes go through LDS so that the rows of V are written in pieces of
-// 32 bytes.
+// Input stage (Eq. 1: V = B^T d B on every patch, Sec. 3.2): a workgroup owns 8
+// consecutive tiles x 32 channels, one (tile, channel) per thread with the tiles along the
+// lanes: neighbouring patches overlap, so the eight lanes of a channel read one run of an
+// image row (one cache access instead of eight).  The codes go through LDS so that the
+// rows of V are written in pieces of 64 bytes.
 template <int M, typename XT, bool kSparse>
 __global__ __launch_bounds__(256) void input_transform_w16(Geom g, MatBT bt,
                                                            const XT* __restrict__ x,
                                                            _Float16* __restrict__ V, PosScale rv,
                                                            float qmax) {
   constexpr int n = M + 2, P = n * n;
-  __shared__ __attribute__((aligned(16))) _Float16 sm[P * 256];
-  const int tid = threadIdx.x, r = tid & 15, cc = tid >> 4;
-  const int t = blockIdx.x * 16 + r, c = blockIdx.y * 16 + cc;
+  constexpr int kPitch = 40;                           // halfs per staged row (32 used)
+  __shared__ __attribute__((aligned(16))) _Float16 sm[P * 8 * kPitch];
+  const int tid = threadIdx.x, r = tid & 7, cc = tid >> 3;
+  const int t = blockIdx.x * 8 + r, c = blockIdx.y * 32 + cc;
   float d[n][n];
   {
     // branch-free: every lane loads from an address clamped into an image that exists and
@@ -131,11 +182,11 @@ __global__ __launch_bounds__(256) void input_transform_w16(Geom g, MatBT bt,
   }
   float Vf[n][n];
   transform_patch<M, kSparse>(d, bt, Vf);
-  int code[P];
+  float code[P];
 #pragma unroll
   for (int i = 0; i < n; ++i)
 #pragma unroll
-    for (int k = 0; k < n; ++k) code[i * n + k] = quantize(Vf[i][k], rv.r[i * n + k], qmax);
+    for (int k = 0; k < n; ++k) code[i * n + k] = quantize_f(Vf[i][k], rv.r[i * n + k], qmax);
 #pragma unroll
   for (int digit = 0; digit < 2; ++digit) {
     if (digit) __syncthreads();                        // the first plane has left LDS
@@ -143,15 +194,15 @@ __global__ __launch_bounds__(256) void input_transform_w16(Geom g, MatBT bt,
     for (int p = 0; p < P; ++p) {
       _Float16 a, b;
       split_code(code[p], a, b);
-      sm[(p * 16 + r) * 16 + cc] = digit ? b : a;
+      sm[(p * 8 + r) * kPitch + cc] = digit ? b : a;
     }
     __syncthreads();
-    // P * 16 rows of 16 channels = P * 32 pieces of 16 bytes
+    // P * 8 rows of 32 channels = P * 32 pieces of 16 bytes
     for (int idx = tid; idx < P * 32; idx += 256) {
-      const int p = idx >> 5, row = (idx & 31) >> 1, piece = idx & 1;
-      *(v4u*)(V + v16_index(g.Tp, g.Cp, p, digit, blockIdx.x * 16 + row,
-                            blockIdx.y * 16 + piece * 8)) =
-          *(const v4u*)&sm[(p * 16 + row) * 16 + piece * 8];
+      const int p = idx >> 5, row = (idx & 31) >> 2, piece = idx & 3;
+      *(v4u*)(V + v16_index(g.Tp, g.Cp, p, digit, blockIdx.x * 8 + row,
+                            blockIdx.y * 32 + piece * 8)) =
+          *(const v4u*)&sm[(p * 8 + row) * kPitch + piece * 8];
     }
   }
 }
@@ -254,7 +305,7 @@ __global__ __launch_bounds__(256) void output_transform_w16(Geom g, MatAT at,
                                                             const long long* __restrict__ Mi,
                                                             YT* __restrict__ y, PosScale w,
                                                             float r_m, float r_y, float qmax_m,
-                                                            float qmax_y) {
+                                                            float qmax_y, int fast) {
   constexpr int n = M + 2;
   const int k = blockIdx.y * 64 + (threadIdx.x & 63), t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= g.T || k >= g.K) return;
@@ -271,14 +322,12 @@ __global__ __launch_bounds__(256) void output_transform_w16(Geom g, MatAT at,
     }
   transform_result<M, kSparse>(Mt, at, Y);
   const int tw = t % g.TW, th = (t / g.TW) % g.TH, img = t / (g.TW * g.TH);
-  YT* plane = y + ((size_t)img * g.K + k) * g.Ho * g.Wo;
+  int q[M][M];
 #pragma unroll
   for (int a = 0; a < M; ++a)
 #pragma unroll
-    for (int b = 0; b < M; ++b) {
-      const int h = th * M + a, x = tw * M + b;
-      if (h < g.Ho && x < g.Wo) plane[(size_t)h * g.Wo + x] = (YT)quantize(Y[a][b], r_y, qmax_y);
-    }
+    for (int b = 0; b < M; ++b) q[a][b] = quantize(Y[a][b], r_y, qmax_y);
+  store_codes<M, YT>(y + ((size_t)img * g.K + k) * g.Ho * g.Wo, g, th * M, tw * M, q, fast != 0);
 }
 
 // Hadamard/GEMM stage and output stage in one kernel: M never reaches memory.  A wavefront
@@ -292,16 +341,16 @@ __global__ __launch_bounds__(256) void output_transform_w16(Geom g, MatAT at,
 // and a ring of operands loaded kDepth steps ahead.  The column loop is a real loop (it
 // bounds how far the compiler may hoist loads); inside it everything is unrolled, so
 // NCH = Cp / 32 is a compile-time constant and the ring slots are static.  At most 512
-// channels, so the two middle digit sums may share an accumulator.  Entries of A^T that
-// are zero in the Cook-Toom pattern are skipped along i (compile time); along j they are
-// multiplied out (fma(z, 0, Y) == Y).
-template <int M, typename YT, int NCH>
+// channels, so the two middle digit sums may share an accumulator.  kSparse: entries of
+// A^T that are zero in the Cook-Toom pattern are skipped along i (compile time); along j
+// they are multiplied out (fma(z, 0, Y) == Y).
+template <int M, typename YT, int NCH, bool kSparse>
 __global__ __launch_bounds__(256) void gemm_out_w16_kernel(Geom g, MatAT at,
                                                            const half8* __restrict__ V,
                                                            const half8* __restrict__ U,
                                                            YT* __restrict__ y, PosScale w,
-                                                           int use_w, float r_m, float r_y,
-                                                           float qmax_m, float qmax_y) {
+                                                           float r_m, float r_y, float qmax_m,
+                                                           float qmax_y, int fast) {
   constexpr int n = M + 2;
   constexpr int SJ = n * NCH;                          // steps per column
   constexpr int kDepth = M == 4 ? 6 : M == 2 ? 8 : 4;
@@ -340,66 +389,71 @@ __global__ __launch_bounds__(256) void gemm_out_w16_kernel(Geom g, MatAT at,
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) Y[a][b][rr] = 0.0f;
 
+  // (one copy of the loop per setting of the Hadamard-stage quantizer: a test per
+  // accumulator would cut the loop body into pieces the scheduler cannot overlap)
+  auto columns = [&](auto mq_tag) {
+    constexpr bool kMQ = decltype(mq_tag)::value;
 #pragma unroll 1
-  for (int j = 0; j < n; ++j) {
-    // (the last column prefetches the steps of column n - 1 again instead of branching
-    // around the loads)
-    const int jn = j + 1 < n ? j + 1 : j;
+    for (int j = 0; j < n; ++j) {
+      // (the last column prefetches the steps of column n - 1 again instead of branching
+      // around the loads)
+      const int jn = j + 1 < n ? j + 1 : j;
 #pragma unroll
-    for (int i = 0; i < n; ++i) {
-      v4f hh = v4f{0, 0, 0, 0}, mid = hh, ll = hh;
+      for (int i = 0; i < n; ++i) {
+        v4f hh = v4f{0, 0, 0, 0}, mid = hh, ll = hh;
 #pragma unroll
-      for (int ch = 0; ch < NCH; ++ch) {
-        const int sj = i * NCH + ch, slot = sj % kDepth;
-        const half8 uh = ruh[slot], ul = rul[slot];
-        const half8 vh = rvh[slot], vl = rvl[slot];
-        if (sj + kDepth < SJ) fetch(sj + kDepth, j, slot);
-        else fetch(sj + kDepth - SJ, jn, slot);
-        hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vh, hh, 0, 0, 0);
-        mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vl, mid, 0, 0, 0);
-        mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vh, mid, 0, 0, 0);
-        ll = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vl, ll, 0, 0, 0);
-      }
-      const float wp = w.r[i * n + j];
+        for (int ch = 0; ch < NCH; ++ch) {
+          const int sj = i * NCH + ch, slot = sj % kDepth;
+          const half8 uh = ruh[slot], ul = rul[slot];
+          const half8 vh = rvh[slot], vl = rvl[slot];
+          if (sj + kDepth < SJ) fetch(sj + kDepth, j, slot);
+          else fetch(sj + kDepth - SJ, jn, slot);
+          hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vh, hh, 0, 0, 0);
+          mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vl, mid, 0, 0, 0);
+          mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vh, mid, 0, 0, 0);
+          ll = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vl, ll, 0, 0, 0);
+        }
+        const float wp = w.r[i * n + j];               // 1 with per-tensor scales: exact
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        // exact in fp64 (below 2^53), one rounding to fp32: the conversion of the integer M
-        const double dm = __builtin_fma((double)hh[rr], 65536.0,
-                                        __builtin_fma((double)mid[rr], 256.0, (double)ll[rr]));
-        float f = (float)dm;
-        if (use_w) f = f * wp;
-        if (r_m > 0.0f) f = (float)quantize(f, r_m, qmax_m);
+        for (int rr = 0; rr < 4; ++rr) {
+          // exact in fp64 (below 2^53), one rounding to fp32: the conversion of the integer M
+          const double dm = __builtin_fma((double)hh[rr], 65536.0,
+                                          __builtin_fma((double)mid[rr], 256.0, (double)ll[rr]));
+          float f = (float)dm * wp;
+          if constexpr (kMQ) f = (float)quantize(f, r_m, qmax_m);
 #pragma unroll
-        for (int a = 0; a < M; ++a) {
-          if (i == 0) z[a][rr] = 0.0f;
-          if (at_nonzero<M, true>(a, i)) z[a][rr] = __builtin_fmaf(at.v[a * n + i], f, z[a][rr]);
+          for (int a = 0; a < M; ++a) {
+            if (i == 0) z[a][rr] = 0.0f;
+            if (at_nonzero<M, kSparse>(a, i))
+              z[a][rr] = __builtin_fmaf(at.v[a * n + i], f, z[a][rr]);
+          }
         }
       }
+#pragma unroll
+      for (int b = 0; b < M; ++b) {
+        const float abj = at.v[b * n + j];
+#pragma unroll
+        for (int a = 0; a < M; ++a)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) Y[a][b][rr] = __builtin_fmaf(z[a][rr], abj, Y[a][b][rr]);
+      }
     }
-#pragma unroll
-    for (int b = 0; b < M; ++b) {
-      const float abj = at.v[b * n + j];
-#pragma unroll
-      for (int a = 0; a < M; ++a)
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) Y[a][b][rr] = __builtin_fmaf(z[a][rr], abj, Y[a][b][rr]);
-    }
-  }
+  };
+  if (r_m > 0.0f) columns(std::true_type{});
+  else columns(std::false_type{});
+
   if (t >= g.T) return;
   const int tw = t % g.TW, th = (t / g.TW) % g.TH, img = t / (g.TW * g.TH);
 #pragma unroll
   for (int rr = 0; rr < 4; ++rr) {
     const int k = kb + wave * 16 + grp * 4 + rr;
     if (k >= g.K) continue;
-    YT* plane = y + ((size_t)img * g.K + k) * g.Ho * g.Wo;
+    int q[M][M];
 #pragma unroll
     for (int a = 0; a < M; ++a)
 #pragma unroll
-      for (int b = 0; b < M; ++b) {
-        const int h = th * M + a, x = tw * M + b;
-        if (h < g.Ho && x < g.Wo)
-          plane[(size_t)h * g.Wo + x] = (YT)quantize(Y[a][b][rr], r_y, qmax_y);
-      }
+      for (int b = 0; b < M; ++b) q[a][b] = quantize(Y[a][b][rr], r_y, qmax_y);
+    store_codes<M, YT>(y + ((size_t)img * g.K + k) * g.Ho * g.Wo, g, th * M, tw * M, q, fast != 0);
   }
 }
 
@@ -431,7 +485,7 @@ __global__ __launch_bounds__(256) void export_m_w16(const long long* __restrict_
 template <int M>
 hipError_t input_m(const Geom& g, const MatBT& bt, const void* x, void* V, const PosScale& rv,
                    float qmax, hipStream_t s) {
-  dim3 grid(g.Tp / 16, g.Cp / 16);
+  dim3 grid(g.Tp / 8, g.Cp / 32);
   const bool sparse = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt);
   _Float16* Vh = (_Float16*)V;
   if (g.x16) {
@@ -453,12 +507,13 @@ hipError_t output_my(const Geom& g, const MatAT& at, const void* Mi, void* y, co
   for (int p = 0; p < 64; ++p) one.r[p] = 1.0f;
   const long long* Ml = (const long long*)Mi;
   YT* yo = (YT*)y;
+  const int fast = g.Ho % M == 0 && g.Wo % M == 0 && ((uintptr_t)y & 7) == 0;
   if (w) {
-    if (sparse) output_transform_w16<M, YT, true, true><<<grid, 256, 0, s>>>(g, at, Ml, yo, *w, r_m, r_y, qmax_m, qmax_y);
-    else output_transform_w16<M, YT, false, true><<<grid, 256, 0, s>>>(g, at, Ml, yo, *w, r_m, r_y, qmax_m, qmax_y);
+    if (sparse) output_transform_w16<M, YT, true, true><<<grid, 256, 0, s>>>(g, at, Ml, yo, *w, r_m, r_y, qmax_m, qmax_y, fast);
+    else output_transform_w16<M, YT, false, true><<<grid, 256, 0, s>>>(g, at, Ml, yo, *w, r_m, r_y, qmax_m, qmax_y, fast);
   } else {
-    if (sparse) output_transform_w16<M, YT, true, false><<<grid, 256, 0, s>>>(g, at, Ml, yo, one, r_m, r_y, qmax_m, qmax_y);
-    else output_transform_w16<M, YT, false, false><<<grid, 256, 0, s>>>(g, at, Ml, yo, one, r_m, r_y, qmax_m, qmax_y);
+    if (sparse) output_transform_w16<M, YT, true, false><<<grid, 256, 0, s>>>(g, at, Ml, yo, one, r_m, r_y, qmax_m, qmax_y, fast);
+    else output_transform_w16<M, YT, false, false><<<grid, 256, 0, s>>>(g, at, Ml, yo, one, r_m, r_y, qmax_m, qmax_y, fast);
   }
   return hipGetLastError();
 }
@@ -512,23 +567,19 @@ hipError_t launch_w16_output(const Geom& g, const MatAT& at, const void* M, void
   }
 }
 
-// GEMM + output in one kernel: Cook-Toom pattern of A^T, 64..512 padded channels in powers
-// of two, every offset in 32 bits.
-bool w16_gemm_out_supported(const Geom& g, const MatAT& at) {
-  const bool sparse = g.m == 2   ? fits_mask(at.v, g.m * g.n, CookToomMask<2>::at)
-                      : g.m == 4 ? fits_mask(at.v, g.m * g.n, CookToomMask<4>::at)
-                                 : fits_mask(at.v, g.m * g.n, CookToomMask<6>::at);
+// GEMM + output in one kernel: 64..512 padded channels in powers of two, every offset in
+// 32 bits.
+bool w16_gemm_out_supported(const Geom& g, const MatAT&) {
   const bool nch_ok = g.Cp == 64 || g.Cp == 128 || g.Cp == 256 || g.Cp == 512;
-  return sparse && nch_ok && g.Kp / 64 <= 65535 &&
-         (size_t)g.P * 2 * g.Tp * g.Cp / 8 < 0xffffffffull &&
+  return nch_ok && g.Kp / 64 <= 65535 && (size_t)g.P * 2 * g.Tp * g.Cp / 8 < 0xffffffffull &&
          (size_t)g.P * 2 * g.Kp * g.Cp / 8 < 0xffffffffull;
 }
 
 namespace {
-template <int M, typename YT>
-hipError_t gemm_out_my(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
-                       const PosScale* w, float r_m, float r_y, float qmax_m, float qmax_y,
-                       hipStream_t s) {
+template <int M, typename YT, bool kSparse>
+hipError_t gemm_out_mys(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
+                        const PosScale* w, float r_m, float r_y, float qmax_m, float qmax_y,
+                        hipStream_t s) {
   dim3 grid(g.Tp / 16, g.Kp / 64);
   PosScale one;
   for (int p = 0; p < 64; ++p) one.r[p] = 1.0f;
@@ -536,12 +587,12 @@ hipError_t gemm_out_my(const Geom& g, const MatAT& at, const void* V, const void
   const half8* Vh = (const half8*)V;
   const half8* Uh = (const half8*)U;
   YT* yo = (YT*)y;
-  const int use_w = w != nullptr;
+  const int fast = g.Ho % M == 0 && g.Wo % M == 0 && ((uintptr_t)y & 7) == 0;
   switch (g.Cp) {
-    case 64: gemm_out_w16_kernel<M, YT, 2><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, use_w, r_m, r_y, qmax_m, qmax_y); break;
-    case 128: gemm_out_w16_kernel<M, YT, 4><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, use_w, r_m, r_y, qmax_m, qmax_y); break;
-    case 256: gemm_out_w16_kernel<M, YT, 8><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, use_w, r_m, r_y, qmax_m, qmax_y); break;
-    default: gemm_out_w16_kernel<M, YT, 16><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, use_w, r_m, r_y, qmax_m, qmax_y); break;
+    case 64: gemm_out_w16_kernel<M, YT, 2, kSparse><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast); break;
+    case 128: gemm_out_w16_kernel<M, YT, 4, kSparse><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast); break;
+    case 256: gemm_out_w16_kernel<M, YT, 8, kSparse><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast); break;
+    default: gemm_out_w16_kernel<M, YT, 16, kSparse><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast); break;
   }
   return hipGetLastError();
 }
@@ -549,8 +600,12 @@ template <int M>
 hipError_t gemm_out_m(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                       const PosScale* w, float r_m, float r_y, float qmax_m, float qmax_y,
                       hipStream_t s) {
-  return g.x16 ? gemm_out_my<M, int16_t>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s)
-               : gemm_out_my<M, int8_t>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s);
+  const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  if (g.x16)
+    return sparse ? gemm_out_mys<M, int16_t, true>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s)
+                  : gemm_out_mys<M, int16_t, false>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s);
+  return sparse ? gemm_out_mys<M, int8_t, true>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s)
+                : gemm_out_mys<M, int8_t, false>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s);
 }
 }  // namespace
 
