@@ -187,25 +187,25 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
         stages = [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
                   ("gemm_output", wb.WINO_STAGE_GEMM | wb.WINO_STAGE_OUTPUT)]
     ksteps = max(20, min(steps, 200))
+    # (the forward once, so that every stage finds its predecessor's output)
+    wb.wino_transform_weights(desc, quant, gd, U, stream=stream)
+    for _, mask in stages[1:]:
+        wb.wino_conv2d_fwd_stages(desc, quant, x, U, y, ws, mask, stream=stream)
+    stream.synchronize()
 
     def time_stages(stages):
-        acc = {n: 0.0 for n, _ in stages}
-        with torch.cuda.stream(stream):
-            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)]
-                   for _ in range(ksteps)]
-            for it in range(ksteps + 5):
-                row = evs[max(it - 5, 0)]
-                row[0].record(stream)
-                for si, (name, mask) in enumerate(stages):
-                    if mask is None:
-                        wb.wino_transform_weights(desc, quant, gd, U, stream=stream)
-                    else:
-                        wb.wino_conv2d_fwd_stages(desc, quant, x, U, y, ws, mask, stream=stream)
-                    row[si + 1].record(stream)
-            torch.cuda.synchronize()
-            for row in evs:
-                for si, (name, _) in enumerate(stages):
-                    acc[name] += row[si].elapsed_time(row[si + 1]) * 1e3 / ksteps   # us
+        """us per launch of every stage: each stage on its own, 10 back-to-back calls per HIP
+        graph (host launches with --no-graph), events around the replays on the stream the
+        kernels run on.  A stage reads what the previous one left in the workspace, so
+        repeating it changes nothing."""
+        acc = {}
+        for name, mask in stages:
+            if mask is None:
+                fn = lambda: wb.wino_transform_weights(desc, quant, gd, U, stream=stream)
+            else:
+                fn = lambda mask=mask: wb.wino_conv2d_fwd_stages(desc, quant, x, U, y, ws, mask,
+                                                                 stream=stream)
+            acc[name] = timed(fn, ksteps - ksteps % 10, 10) * 1e3
         return acc
 
     acc = time_stages(stages)

@@ -192,3 +192,34 @@ def test_per_position_scale_argument_checks(L):
     bad[7] = np.inf
     q = wb.make_quant(0.1, 1.0, 1.0, 0.2, s_v_pos=bad, s_u_pos=ok)
     assert L.wino_transform_weights(d.ref, ctypes.byref(q), fake, fake, None) == -5
+
+
+def test_wide_mode_sizes_and_argument_checks(L):
+    """The modes with 16-bit codes in the Winograd domain: buffer sizes (two fp16 digit planes
+    per code of U and V, int64 M), the channel limit of the exact digit arithmetic, one code
+    range per quantizer with the limit of its container -- all checked before any HIP call."""
+    d = _desc(N=64, C=64, K=64, H=32, W=32, m=4, dtype=wb.WINO_I16)
+    assert wb.wino_weights_bytes(d) == 36 * 64 * 64 * 4
+    assert wb.wino_workspace_bytes(d) == 36 * 4096 * 64 * 4 + 36 * 4096 * 64 * 8
+    assert wb.wino_workspace_bytes(_desc(C=3, dtype=wb.WINO_I8W16)) == 16 * 64 * 64 * 4 + 16 * 64 * 64 * 8
+    assert wb.wino_weights_bytes(_desc(C=1024, dtype=wb.WINO_I16)) > 0
+    assert wb.wino_weights_bytes(_desc(C=1025, dtype=wb.WINO_I16)) == 0
+    assert _fwd(L, _desc(C=1025, dtype=wb.WINO_I8W16), wb.make_quant(1, 1, 1, 1)) == -3
+    assert _fwd(L, _desc(dtype=wb.WINO_I16), None) == -5                    # quant missing
+    kw = dict(s_x=0.1, s_v=0.1, s_u=0.1, s_y=0.1, s_m=0.0)
+    for dtype, q, want in (
+            (wb.WINO_I16, dict(qmax=32768), -5),
+            (wb.WINO_I16, dict(qmax=127, qmax_v=40000), -5),
+            (wb.WINO_I16, dict(qmax=127, qmax_m=-1), -5),
+            (wb.WINO_I8W16, dict(qmax=32767), -5),               # output codes live in int8
+            (wb.WINO_I8W16, dict(qmax=127, qmax_y=128), -5),
+            (wb.WINO_I8, dict(qmax=127, qmax_v=63), -5),         # int8 mode: one range for all
+            (wb.WINO_I8, dict(qmax=127, qmax_u=127, qmax_v=127, qmax_m=127, qmax_y=127), -6),
+            (wb.WINO_I8W16, dict(qmax=127, qmax_u=32767, qmax_v=511, qmax_m=8191), -6),
+            (wb.WINO_I16, dict(qmax=32767), -6)):
+        # (-6: every argument check passed, the 100-byte workspace is what is refused)
+        assert _fwd(L, _desc(dtype=dtype), wb.make_quant(**kw, **q), nbytes=100) == want, (dtype, q)
+    # int16 tensors must be 2-byte aligned
+    q = wb.make_quant(**kw, qmax=32767)
+    assert _fwd(L, _desc(dtype=wb.WINO_I16), q, x=0x1001) == -8
+    assert _fwd(L, _desc(dtype=wb.WINO_I16), q, y=0x1001) == -8
