@@ -32,6 +32,7 @@ FLAGS = [
 EXTRA_FLAGS = {
     "fused_fwd_exact.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "fused_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "wide16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

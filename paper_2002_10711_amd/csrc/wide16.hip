@@ -344,8 +344,11 @@ __global__ __launch_bounds__(256) void output_transform_w16(Geom g, MatAT at,
 // channels, so the two middle digit sums may share an accumulator.  kSparse: entries of
 // A^T that are zero in the Cook-Toom pattern are skipped along i (compile time); along j
 // they are multiplied out (fma(z, 0, Y) == Y).
-template <int M, typename YT, int NCH, bool kSparse>
-__global__ __launch_bounds__(256) void gemm_out_w16_kernel(Geom g, MatAT at,
+// kTG: groups of 16 tiles per workgroup (four wavefronts each).  The groups read the same
+// blocks of U at about the same time, so the second group finds them in the CU's L1 and
+// the stream of U through the L2 -- what bounds this kernel -- is halved.
+template <int M, typename YT, int NCH, bool kSparse, int kTG>
+__global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT at,
                                                            const half8* __restrict__ V,
                                                            const half8* __restrict__ U,
                                                            YT* __restrict__ y, PosScale w,
@@ -353,30 +356,38 @@ __global__ __launch_bounds__(256) void gemm_out_w16_kernel(Geom g, MatAT at,
                                                            float qmax_y, int fast) {
   constexpr int n = M + 2;
   constexpr int SJ = n * NCH;                          // steps per column
-  constexpr int kDepth = M == 4 ? 6 : M == 2 ? 8 : 4;
+  constexpr int kDepth = kTG == 1 ? (M == 4 ? (NCH == 2 ? 12 : 6) : M == 2 ? 8 : 4) : (M == 6 ? 2 : 4);
   static_assert(SJ % kDepth == 0 && kDepth <= SJ, "ring depth must divide a column's steps");
-  const int tb = blockIdx.x * 16, kb = blockIdx.y * 64;
   const int lane = threadIdx.x & 63, r = lane & 15, grp = lane >> 4;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wave_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wave = wave_id & 3;                        // block of 16 output channels
+  const int tb = (blockIdx.x * kTG + (wave_id >> 2)) * 16, kb = blockIdx.y * 64;
   const int t = tb + r;
-  // 16-byte pieces: U block pair of (position, 16 channels k, 32 channels c) = 128 pieces,
-  // digit planes 64 apart; V row piece = 8 channels
-  const uint32_t ubase = (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)NCH * 128u + (uint32_t)lane;
-  const uint32_t ustep_p = (uint32_t)(g.Kp >> 4) * (uint32_t)NCH * 128u;
-  const uint32_t vrow = (uint32_t)(g.Cp >> 3);
-  const uint32_t vbase = (uint32_t)t * vrow + (uint32_t)grp;
-  const uint32_t vplane = (uint32_t)g.Tp * vrow;
+  // Addresses = uniform byte offset (position, channel step: scalar registers, recomputed
+  // per load and hidden from the optimiser, which would otherwise keep one 64-bit vector
+  // pointer per load site of the unrolled column) + one 32-bit per-lane offset per tensor.
+  // U: block pair of (position, 16 channels k, 32 channels c) = 2 KB, digit planes 1 KB
+  // apart, the lane's piece at lane * 16; V: row piece of 8 channels = 16 bytes.
+  const char* Ub = (const char*)U;
+  const char* Vb = (const char*)V;
+  const size_t ublock = (size_t)((kb + wave * 16) >> 4) * NCH * 2048;
+  const size_t ustep_p = (size_t)(g.Kp >> 4) * NCH * 2048;
+  const size_t vplane = (size_t)g.Tp * g.Cp * 2;       // bytes of one digit plane of a position
+  const uint32_t ulane = (uint32_t)lane * 16u;
+  const uint32_t vlane = ((uint32_t)t * (uint32_t)(g.Cp >> 3) + (uint32_t)grp) * 16u;
 
   half8 ruh[kDepth], rul[kDepth], rvh[kDepth], rvl[kDepth];
   // step sj of column j: position p = (sj / NCH) * n + j, channel step sj % NCH
   auto fetch = [&](int sj, int j, int slot) {
     const int p = (sj / NCH) * n + j, ch = sj % NCH;
-    const uint32_t uo = ubase + (uint32_t)p * ustep_p + (uint32_t)ch * 128u;
-    const uint32_t vo = vbase + (uint32_t)(2 * p) * vplane + (uint32_t)ch * 4u;
-    ruh[slot] = U[uo];
-    rul[slot] = U[uo + 64u];
-    rvh[slot] = V[vo];
-    rvl[slot] = V[vo + vplane];
+    size_t uo = ublock + (size_t)p * ustep_p + (size_t)ch * 2048;
+    size_t vo = (size_t)(2 * p) * vplane + (size_t)ch * 64;
+    size_t vo2 = vo + vplane;
+    asm volatile("" : "+s"(uo), "+s"(vo), "+s"(vo2));
+    ruh[slot] = *(const half8*)(Ub + uo + ulane);
+    rul[slot] = *(const half8*)(Ub + uo + 1024 + ulane);
+    rvh[slot] = *(const half8*)(Vb + vo + vlane);
+    rvl[slot] = *(const half8*)(Vb + vo2 + vlane);
   };
 #pragma unroll
   for (int s = 0; s < kDepth; ++s) fetch(s, 0, s);
@@ -406,12 +417,16 @@ __global__ __launch_bounds__(256) void gemm_out_w16_kernel(Geom g, MatAT at,
           const int sj = i * NCH + ch, slot = sj % kDepth;
           const half8 uh = ruh[slot], ul = rul[slot];
           const half8 vh = rvh[slot], vl = rvl[slot];
-          if (sj + kDepth < SJ) fetch(sj + kDepth, j, slot);
-          else fetch(sj + kDepth - SJ, jn, slot);
           hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vh, hh, 0, 0, 0);
           mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vl, mid, 0, 0, 0);
           mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vh, mid, 0, 0, 0);
           ll = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vl, ll, 0, 0, 0);
+          // refill the slot once its operands have been issued (the loads may then land in
+          // the same registers); the compiler-level fence keeps later steps' loads behind
+          // this one, so that the ring, not the scheduler, decides what is in flight
+          if (sj + kDepth < SJ) fetch(sj + kDepth, j, slot);
+          else fetch(sj + kDepth - SJ, jn, slot);
+          asm volatile("" ::: "memory");
         }
         const float wp = w.r[i * n + j];               // 1 with per-tensor scales: exact
 #pragma unroll
@@ -576,11 +591,16 @@ bool w16_gemm_out_supported(const Geom& g, const MatAT&) {
 }
 
 namespace {
+// Two tile groups per workgroup pay (about 12 % on 64-channel layers of 16 k tiles) once
+// that still leaves two workgroups for every CU; not for m = 6, whose ring would shrink
+// to two steps.
+inline bool w16_two_groups(const Geom& g) {
+  return g.m != 6 && (long long)(g.Tp / 32) * (g.Kp / 64) >= 512;
+}
 template <int M, typename YT, bool kSparse>
 hipError_t gemm_out_mys(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                         const PosScale* w, float r_m, float r_y, float qmax_m, float qmax_y,
                         hipStream_t s) {
-  dim3 grid(g.Tp / 16, g.Kp / 64);
   PosScale one;
   for (int p = 0; p < 64; ++p) one.r[p] = 1.0f;
   const PosScale& ws = w ? *w : one;
@@ -588,12 +608,24 @@ hipError_t gemm_out_mys(const Geom& g, const MatAT& at, const void* V, const voi
   const half8* Uh = (const half8*)U;
   YT* yo = (YT*)y;
   const int fast = g.Ho % M == 0 && g.Wo % M == 0 && ((uintptr_t)y & 7) == 0;
+  // (Tp is a multiple of 64, so of 32)
+  const bool two = w16_two_groups(g);
+#define WINO_W16_GO(NCHV)                                                                     \
+  do {                                                                                        \
+    if (two)                                                                                  \
+      gemm_out_w16_kernel<M, YT, NCHV, kSparse, 2><<<dim3(g.Tp / 32, g.Kp / 64), 512, 0, s>>>( \
+          g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast);                             \
+    else                                                                                      \
+      gemm_out_w16_kernel<M, YT, NCHV, kSparse, 1><<<dim3(g.Tp / 16, g.Kp / 64), 256, 0, s>>>( \
+          g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast);                             \
+  } while (0)
   switch (g.Cp) {
-    case 64: gemm_out_w16_kernel<M, YT, 2, kSparse><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast); break;
-    case 128: gemm_out_w16_kernel<M, YT, 4, kSparse><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast); break;
-    case 256: gemm_out_w16_kernel<M, YT, 8, kSparse><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast); break;
-    default: gemm_out_w16_kernel<M, YT, 16, kSparse><<<grid, 256, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast); break;
+    case 64: WINO_W16_GO(2); break;
+    case 128: WINO_W16_GO(4); break;
+    case 256: WINO_W16_GO(8); break;
+    default: WINO_W16_GO(16); break;
   }
+#undef WINO_W16_GO
   return hipGetLastError();
 }
 template <int M>

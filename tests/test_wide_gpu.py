@@ -4,9 +4,13 @@ weights and input, the exact int64 accumulators, the output codes -- for one wid
 everywhere (WINO_I16) and for 8-bit activations around a 16-bit Winograd domain
 (WINO_I8W16), with and without the Hadamard-stage quantizer, per-position scales, learned
 ("flex") matrices, ragged shapes and the longest reduction the digit arithmetic allows."""
+import json
+import os
+
 import numpy as np
 import pytest
 
+from paper_2002_10711_amd import workloads
 from paper_2002_10711_amd.workloads import Layer
 
 from helpers import make_case
@@ -97,6 +101,7 @@ LAYERS = [
     Layer("w_f4_flex", 2, 40, 24, 12, 12, m=4, flex_sigma=0.03, seed=305),
     Layer("w_f4_c600", 1, 600, 40, 8, 8, m=4, seed=306),          # beyond 512 channels
     Layer("w_f2_1px", 5, 3, 5, 1, 1, m=2, seed=307),              # a single output pixel
+    Layer("w_f2_16k_tiles", 64, 16, 24, 32, 32, m=2, seed=309),   # two tile groups per workgroup
 ]
 
 
@@ -140,6 +145,21 @@ def test_every_code_saturated_over_1024_channels(oracle):
     ref = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc, qmax=INT16)
     assert np.abs(ref["M"]).max() >= 1000 * 32767 * 32767
     check(ref, run_wide(case, INT16, sc))
+
+
+@pytest.mark.parametrize("dtype", ["i16", "i8w16"])
+def test_config2_wide_full_size_as_benchmarked(oracle, dtype):
+    """The benchmark's wide workloads at full size, with the scales the benchmark reads
+    (written by tests/golden/make_bench_scales.py through the oracle): every tap."""
+    L = workloads.config2(dtype)[0]
+    qm = workloads.STAGE_QMAX[dtype]
+    sc = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "bench_scales.json")))[L.name]
+    case = make_case(oracle, L, with_oracle=False)
+    case["xq"] = oracle.quantize_tensor(case["X"], sc["s_x"], qm["x"])
+    ref = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc,
+                            pad=L.pad, qmax=qm)
+    assert np.abs(ref["Vq"]).max() == qm["v"] and np.abs(ref["Yq"]).max() == qm["y"]
+    check(ref, run_wide(case, qm, sc))
 
 
 def test_wide_argument_checks():
