@@ -356,39 +356,74 @@ __global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT a
                                                            float qmax_y, int fast) {
   constexpr int n = M + 2;
   constexpr int SJ = n * NCH;                          // steps per column
-  constexpr int kDepth = kTG == 1 ? (M == 4 ? (NCH == 2 ? 12 : 6) : M == 2 ? 8 : 4) : (M == 6 ? 2 : 4);
+  constexpr int kDepth = M == 4 ? (kTG == 1 ? 12 : 6) : 8;       // U ring, in steps
   static_assert(SJ % kDepth == 0 && kDepth <= SJ, "ring depth must divide a column's steps");
+  // V reaches the four wavefronts of a tile group through LDS: the group loads each
+  // position's operands once (16 tiles x Cp channels x 2 digits = NCH * 2 KB, 16 bytes per
+  // thread and 256 bytes of the row) instead of once per wavefront -- the L1's access
+  // rate, about 44 cycles per 16-byte-per-lane wavefront load, is what bounds this kernel.
+  // The loads run kPos positions ahead in registers; two LDS buffers alternate.
+  constexpr int kLd = NCH / 2;                          // 16-byte loads per thread and position
+  constexpr int kPos = NCH == 2 ? n : NCH == 4 ? n / 2 : NCH == 8 ? 2 : 1;
+  static_assert(n % kPos == 0 && n % 2 == 0, "position ring and buffer parity must be static");
+  constexpr int kBufPieces = NCH * 128;                 // 16-byte pieces of one position
+  __shared__ v4u vlds[kTG * 2 * kBufPieces];
   const int lane = threadIdx.x & 63, r = lane & 15, grp = lane >> 4;
   const int wave_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wave = wave_id & 3;                        // block of 16 output channels
-  const int tb = (blockIdx.x * kTG + (wave_id >> 2)) * 16, kb = blockIdx.y * 64;
+  const int group = wave_id >> 2;                      // tile group of the workgroup
+  const int tb = (blockIdx.x * kTG + group) * 16, kb = blockIdx.y * 64;
   const int t = tb + r;
+  const int tidg = threadIdx.x & 255;                  // thread of the tile group
   // Addresses = uniform byte offset (position, channel step: scalar registers, recomputed
   // per load and hidden from the optimiser, which would otherwise keep one 64-bit vector
   // pointer per load site of the unrolled column) + one 32-bit per-lane offset per tensor.
   // U: block pair of (position, 16 channels k, 32 channels c) = 2 KB, digit planes 1 KB
-  // apart, the lane's piece at lane * 16; V: row piece of 8 channels = 16 bytes.
+  // apart, the lane's piece at lane * 16.
   const char* Ub = (const char*)U;
   const char* Vb = (const char*)V;
   const size_t ublock = (size_t)((kb + wave * 16) >> 4) * NCH * 2048;
   const size_t ustep_p = (size_t)(g.Kp >> 4) * NCH * 2048;
   const size_t vplane = (size_t)g.Tp * g.Cp * 2;       // bytes of one digit plane of a position
   const uint32_t ulane = (uint32_t)lane * 16u;
-  const uint32_t vlane = ((uint32_t)t * (uint32_t)(g.Cp >> 3) + (uint32_t)grp) * 16u;
+  // V piece e = tidg + 256 k of a position, in operand order [channel step][digit][tile
+  // row][8 channels]: e & 3 = piece of the row, (e >> 2) & 15 = tile, (e >> 6) & 1 = digit,
+  // e >> 7 = channel step (its low bit from the thread, the rest from k)
+  const uint32_t vthr = (uint32_t)((tidg >> 6) & 1) * (uint32_t)vplane +
+                        (uint32_t)(tb + ((tidg >> 2) & 15)) * (uint32_t)(g.Cp * 2) +
+                        (uint32_t)(tidg >> 7) * 64u + (uint32_t)(tidg & 3) * 16u;
+  v4u* vbuf = vlds + group * 2 * kBufPieces;
 
-  half8 ruh[kDepth], rul[kDepth], rvh[kDepth], rvl[kDepth];
+  half8 ruh[kDepth], rul[kDepth];
+  v4u vst[kPos][kLd];
   // step sj of column j: position p = (sj / NCH) * n + j, channel step sj % NCH
   auto fetch = [&](int sj, int j, int slot) {
     const int p = (sj / NCH) * n + j, ch = sj % NCH;
     size_t uo = ublock + (size_t)p * ustep_p + (size_t)ch * 2048;
-    size_t vo = (size_t)(2 * p) * vplane + (size_t)ch * 64;
-    size_t vo2 = vo + vplane;
-    asm volatile("" : "+s"(uo), "+s"(vo), "+s"(vo2));
+    asm volatile("" : "+s"(uo));
     ruh[slot] = *(const half8*)(Ub + uo + ulane);
     rul[slot] = *(const half8*)(Ub + uo + 1024 + ulane);
-    rvh[slot] = *(const half8*)(Vb + vo + vlane);
-    rvl[slot] = *(const half8*)(Vb + vo2 + vlane);
   };
+  // the group's share of position (i, j) into ring slot `slot`
+  auto vfetch = [&](int i, int j, int slot) {
+    const int p = i * n + j;
+#pragma unroll
+    for (int k = 0; k < kLd; ++k) {
+      size_t vo = (size_t)(2 * p) * vplane + (size_t)k * 128;
+      asm volatile("" : "+s"(vo));
+      vst[slot][k] = *(const v4u*)(Vb + vo + vthr);
+    }
+  };
+  auto vstore = [&](int slot, int buf) {
+#pragma unroll
+    for (int k = 0; k < kLd; ++k) vbuf[buf * kBufPieces + tidg + 256 * k] = vst[slot][k];
+  };
+  // position 0 straight into buffer 0, positions 1 .. kPos into the ring (position x in
+  // slot x % kPos), the first kDepth steps of U into theirs
+  vfetch(0, 0, 0);
+  vstore(0, 0);
+#pragma unroll
+  for (int x = 1; x <= kPos; ++x) vfetch(x % n, x / n, x % kPos);
 #pragma unroll
   for (int s = 0; s < kDepth; ++s) fetch(s, 0, s);
 
@@ -408,15 +443,26 @@ __global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT a
     for (int j = 0; j < n; ++j) {
       // (the last column prefetches the steps of column n - 1 again instead of branching
       // around the loads)
-      const int jn = j + 1 < n ? j + 1 : j;
+      const int jn = j + 1 < n ? j + 1 : j, jnn = j + 2 < n ? j + 2 : n - 1;
 #pragma unroll
       for (int i = 0; i < n; ++i) {
+        // Every wavefront has finished the previous position, whose buffer the next
+        // position's operands may now overwrite; this position's buffer is complete.
+        __syncthreads();
+        vstore((i + 1) % kPos, (i + 1) & 1);
+        // position kPos + 1 ahead: in this column, the next one or the one after
+        // (columns past the last: any valid address, the data is never used)
+        constexpr int kAhead = 1 + kPos;
+        static_assert(kAhead <= n + 1, "at most two columns ahead");
+        vfetch((i + kAhead) % n, (i + kAhead) / n == 0 ? j : (i + kAhead) / n == 1 ? jn : jnn,
+               (i + 1) % kPos);
+        const half8* vops = (const half8*)(vbuf + (i & 1) * kBufPieces) + (r * 4 + grp);
         v4f hh = v4f{0, 0, 0, 0}, mid = hh, ll = hh;
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
           const int sj = i * NCH + ch, slot = sj % kDepth;
           const half8 uh = ruh[slot], ul = rul[slot];
-          const half8 vh = rvh[slot], vl = rvl[slot];
+          const half8 vh = vops[(ch * 2) * 64], vl = vops[(ch * 2 + 1) * 64];
           hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vh, hh, 0, 0, 0);
           mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vl, mid, 0, 0, 0);
           mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vh, mid, 0, 0, 0);
@@ -586,8 +632,8 @@ hipError_t launch_w16_output(const Geom& g, const MatAT& at, const void* M, void
 // 32 bits.
 bool w16_gemm_out_supported(const Geom& g, const MatAT&) {
   const bool nch_ok = g.Cp == 64 || g.Cp == 128 || g.Cp == 256 || g.Cp == 512;
-  return nch_ok && g.Kp / 64 <= 65535 && (size_t)g.P * 2 * g.Tp * g.Cp / 8 < 0xffffffffull &&
-         (size_t)g.P * 2 * g.Kp * g.Cp / 8 < 0xffffffffull;
+  // (the per-thread part of a V address, up to two digit planes, must fit 32 bits)
+  return nch_ok && g.Kp / 64 <= 65535 && (size_t)g.Tp * g.Cp * 4 < 0xffffffffull;
 }
 
 namespace {
@@ -595,7 +641,7 @@ namespace {
 // that still leaves two workgroups for every CU; not for m = 6, whose ring would shrink
 // to two steps.
 inline bool w16_two_groups(const Geom& g) {
-  return g.m != 6 && (long long)(g.Tp / 32) * (g.Kp / 64) >= 512;
+  return g.m != 6 && g.Cp <= 256 && (long long)(g.Tp / 32) * (g.Kp / 64) >= 512;
 }
 template <int M, typename YT, bool kSparse>
 hipError_t gemm_out_mys(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
