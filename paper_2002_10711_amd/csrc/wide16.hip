@@ -139,7 +139,11 @@ __global__ __launch_bounds__(256) void weight_transform_w16(Geom g, MatG mg,
 // lanes: neighbouring patches overlap, so the eight lanes of a channel read one run of an
 // image row (one cache access instead of eight).  The codes go through LDS so that the
 // rows of V are written in pieces of 64 bytes.
-template <int M, typename XT, bool kSparse>
+// kRow: every image row holds at least one load window (W >= 8 elements): a
+// lane fetches each of its n patch rows with ONE load of a window clamped into the row and
+// shifts the patch out of it, instead of n loads of one element -- the L1 spends its
+// cycles per lane and load, not per byte.
+template <int M, typename XT, bool kSparse, bool kRow>
 __global__ __launch_bounds__(256) void input_transform_w16(Geom g, MatBT bt,
                                                            const XT* __restrict__ x,
                                                            _Float16* __restrict__ V, PosScale rv,
@@ -157,26 +161,73 @@ __global__ __launch_bounds__(256) void input_transform_w16(Geom g, MatBT bt,
     const int tc = t < g.T ? t : g.T - 1, ch = c < g.C ? c : g.C - 1;
     const int tw = tc % g.TW, th = (tc / g.TW) % g.TH, img = tc / (g.TW * g.TH);
     const XT* base = x + ((size_t)img * g.C + ch) * g.H * g.W;
-    XT raw[n][n];
+    if constexpr (kRow) {
+      constexpr int NW = (sizeof(XT) == 2 && M == 2) ? 4 : 8;   // elements per window (>= n)
+      constexpr int EB = 8 * (int)sizeof(XT);          // bits per element
+      typedef uint32_t wdw __attribute__((ext_vector_type(NW * sizeof(XT) / 4)));
+      struct __attribute__((packed, aligned(sizeof(XT)))) Window { wdw v; };
+      const int c0 = tw * M - g.pad;                   // first patch column
+      const int ws = c0 < 0 ? 0 : (c0 > g.W - NW ? g.W - NW : c0);
+      const int sh = c0 - ws;                          // -1 at the left edge, > 0 at the right
+      Window raw[n];
 #pragma unroll
-    for (int j = 0; j < n; ++j) {
-      const int h = th * M - g.pad + j;
-      const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
-#pragma unroll
-      for (int l = 0; l < n; ++l) {
-        const int ww = tw * M - g.pad + l;
-        const int wc = ww < 0 ? 0 : (ww >= g.W ? g.W - 1 : ww);
-        raw[j][l] = base[hc * g.W + wc];
+      for (int j = 0; j < n; ++j) {
+        const int h = th * M - g.pad + j;
+        const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
+        raw[j] = *(const Window*)(base + hc * g.W + ws);
       }
-    }
+      const unsigned rs = sh > 0 ? (unsigned)sh * EB : 0u;          // right shift, bits
 #pragma unroll
-    for (int j = 0; j < n; ++j) {
-      const int h = th * M - g.pad + j;
-      const bool hok = live && h >= 0 && h < g.H;
+      for (int j = 0; j < n; ++j) {
+        const int h = th * M - g.pad + j;
+        const bool hok = live && h >= 0 && h < g.H;
+        // the window as one little-endian integer (64 or 128 bits), patch column l at
+        // element l + sh: shift right by sh elements (zero fill = columns >= W, because a
+        // positive sh means the window ends at the row's end), or left by one (column -1)
+        unsigned long long lo, hi = 0;
+        if constexpr (sizeof(wdw) == 8) {
+          lo = ((unsigned long long)raw[j].v[1] << 32) | raw[j].v[0];
+        } else {
+          lo = ((unsigned long long)raw[j].v[1] << 32) | raw[j].v[0];
+          hi = ((unsigned long long)raw[j].v[3] << 32) | raw[j].v[2];
+        }
+        const unsigned s1 = rs & 63u;
+        const unsigned long long a = rs >= 64 ? hi : lo, b = rs >= 64 ? 0ull : hi;
+        unsigned long long r0 = (a >> s1) | (s1 ? b << (64u - s1) : 0ull), r1 = b >> s1;
+        if (sh < 0) {
+          r1 = (hi << EB) | (lo >> (64 - EB));
+          r0 = lo << EB;
+        }
 #pragma unroll
-      for (int l = 0; l < n; ++l) {
-        const int ww = tw * M - g.pad + l;
-        d[j][l] = (hok && ww >= 0 && ww < g.W) ? (float)raw[j][l] : 0.0f;
+        for (int l = 0; l < n; ++l) {
+          const int bit = l * EB;
+          const unsigned long long word = bit < 64 ? r0 >> bit : r1 >> (bit - 64);
+          const int e = sizeof(XT) == 2 ? (int)(short)word : (int)(signed char)word;
+          d[j][l] = hok ? (float)e : 0.0f;
+        }
+      }
+    } else {
+      XT raw[n][n];
+#pragma unroll
+      for (int j = 0; j < n; ++j) {
+        const int h = th * M - g.pad + j;
+        const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
+#pragma unroll
+        for (int l = 0; l < n; ++l) {
+          const int ww = tw * M - g.pad + l;
+          const int wc = ww < 0 ? 0 : (ww >= g.W ? g.W - 1 : ww);
+          raw[j][l] = base[hc * g.W + wc];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < n; ++j) {
+        const int h = th * M - g.pad + j;
+        const bool hok = live && h >= 0 && h < g.H;
+#pragma unroll
+        for (int l = 0; l < n; ++l) {
+          const int ww = tw * M - g.pad + l;
+          d[j][l] = (hok && ww >= 0 && ww < g.W) ? (float)raw[j][l] : 0.0f;
+        }
       }
     }
   }
@@ -548,14 +599,18 @@ hipError_t input_m(const Geom& g, const MatBT& bt, const void* x, void* V, const
                    float qmax, hipStream_t s) {
   dim3 grid(g.Tp / 8, g.Cp / 32);
   const bool sparse = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt);
+  const bool row = g.W >= 8;
   _Float16* Vh = (_Float16*)V;
+#define WINO_W16_IN(XT, SP, RW) \
+  input_transform_w16<M, XT, SP, RW><<<grid, 256, 0, s>>>(g, bt, (const XT*)x, Vh, rv, qmax)
+#define WINO_W16_IN2(XT, SP) do { if (row) WINO_W16_IN(XT, SP, true); else WINO_W16_IN(XT, SP, false); } while (0)
   if (g.x16) {
-    if (sparse) input_transform_w16<M, int16_t, true><<<grid, 256, 0, s>>>(g, bt, (const int16_t*)x, Vh, rv, qmax);
-    else input_transform_w16<M, int16_t, false><<<grid, 256, 0, s>>>(g, bt, (const int16_t*)x, Vh, rv, qmax);
+    if (sparse) WINO_W16_IN2(int16_t, true); else WINO_W16_IN2(int16_t, false);
   } else {
-    if (sparse) input_transform_w16<M, int8_t, true><<<grid, 256, 0, s>>>(g, bt, (const int8_t*)x, Vh, rv, qmax);
-    else input_transform_w16<M, int8_t, false><<<grid, 256, 0, s>>>(g, bt, (const int8_t*)x, Vh, rv, qmax);
+    if (sparse) WINO_W16_IN2(int8_t, true); else WINO_W16_IN2(int8_t, false);
   }
+#undef WINO_W16_IN2
+#undef WINO_W16_IN
   return hipGetLastError();
 }
 
