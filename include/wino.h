@@ -70,7 +70,8 @@ typedef enum {
  *            diversity"; Sec. 6, different bit-widths through Eq. 1): X and Y are int8
  *            arrays, U, V and the Hadamard-stage quantizer may use up to 16 bits.
  * The two wide modes accept one code range per stage (wino_quant.qmax_*), need C <= 1024,
- * and run as three kernels (input transform, GEMM, output transform). */
+ * and run as two kernels (input transform; GEMM fused with the output transform) or, for
+ * channel counts whose padding is not 64/128/256/512, three. */
 typedef enum { WINO_F32 = 0, WINO_I8 = 1, WINO_I16 = 2, WINO_I8W16 = 3 } wino_dtype;
 
 /* One layer problem.  BT is n x n, G is n x 3, AT is m x n, row-major, HOST. */
@@ -99,7 +100,7 @@ typedef struct {
    * Uq[p] = sat(rne(U[p] / s_u_pos[p])), and every accumulator is brought to real units
    * before the output transform, Mf[p] = (float)M[p] * (s_u_pos[p] * s_v_pos[p]), so that
    * y_q = sat(rne(Yt / s_y)) (with the Hadamard-stage quantizer: Mq = sat(rne(Mf / s_m)),
-   * y_q = sat(rne(Yt * s_m / s_y))).  The forward then runs as three kernels. */
+   * y_q = sat(rne(Yt * s_m / s_y))).  The forward then runs as two or three kernels. */
   const float* s_v_pos;
   const float* s_u_pos;
   /* One code range per quantizer (Sec. 3.2: each stage may be quantized to its own number
@@ -143,9 +144,10 @@ wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void*
  * the descriptor is invalid): 1 = input transform, GEMM and output transform in one
  * kernel (small layers; V and M never reach memory), 2 = input transform, then GEMM fused
  * with the output transform (M never reaches memory), 3 = input transform, tiled GEMM,
- * output transform (long reductions, F(6x6,3x3); always with per-position scales and in
- * the wide modes).  Reads
- * d->BT (HOST) if it is not NULL: which single-kernel variant applies depends on it. */
+ * output transform (F(6x6,3x3) and F(4x4,3x3) with long reductions, channel counts whose
+ * padding is not 64/128/256/512).  Per-position scales and the wide modes run as 2 or 3
+ * kernels.  Reads d->BT / d->AT (HOST) if they are not NULL: which variant applies can
+ * depend on them. */
 int wino_fwd_num_kernels(const wino_desc* d);
 
 /* The same forward, restricted to the stages named in `stages` (a mask of

@@ -33,6 +33,7 @@ EXTRA_FLAGS = {
     "fused_fwd_exact.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "fused_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "wide16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "gemm_out_col.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

@@ -238,7 +238,7 @@ int wino_fwd_num_kernels(const wino_desc* d) {
     }
     if (exact || fused_fwd_generic_preferred(g)) return 1;
   }
-  return gemm_out_preferred(g) ? 2 : 3;
+  return (gemm_out_col_preferred(g) || gemm_out_preferred(g)) ? 2 : 3;
 }
 
 wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
@@ -313,7 +313,12 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
     return WINO_E_HIP;
   // (per-position scales: the accumulators need their factors before the output
   // transform, which only the stand-alone output kernel applies)
-  if (s_mm && s_out && !s.pos && gemm_out_preferred(g)) {
+  if (s_mm && s_out && gemm_out_col_preferred(g)) {
+    // GEMM and output transform in one kernel for any reduction length (and with
+    // per-position scales): M stays in registers
+    if (launch_gemm_out_col(g, at, V, U_dev, y_dev, wp, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+      return WINO_E_HIP;
+  } else if (s_mm && s_out && !s.pos && gemm_out_preferred(g)) {
     // short reductions: GEMM and output transform in one kernel, M stays in registers
     if (launch_gemm_out(g, at, V, U_dev, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;

@@ -123,6 +123,49 @@ __device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
   }
 }
 
+// Stores one m x m tile of output codes; (h0, w0) is its top-left corner in the plane.
+// fast (uniform): m divides Ho and Wo and Y is 8-byte aligned, so every tile is whole and
+// every tile row is one aligned piece of m codes.
+template <int M, typename YT>
+__device__ __forceinline__ void store_codes(YT* __restrict__ plane, const Geom& g, int h0, int w0,
+                                            const int (&q)[M][M], bool fast) {
+  if (fast) {
+#pragma unroll
+    for (int a = 0; a < M; ++a) {
+      YT* row = plane + (size_t)(h0 + a) * g.Wo + w0;
+      if constexpr (sizeof(YT) == 2) {
+        uint32_t wd[M / 2];
+#pragma unroll
+        for (int e = 0; e < M / 2; ++e)
+          wd[e] = ((uint32_t)q[a][2 * e] & 0xffffu) | ((uint32_t)q[a][2 * e + 1] << 16);
+        if constexpr (M == 4) {
+          typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+          *(v2u*)row = v2u{wd[0], wd[1]};
+        } else {
+#pragma unroll
+          for (int e = 0; e < M / 2; ++e) ((uint32_t*)row)[e] = wd[e];
+        }
+      } else {
+        if constexpr (M == 4) {
+          *(uint32_t*)row = ((uint32_t)q[a][0] & 0xffu) | (((uint32_t)q[a][1] & 0xffu) << 8) |
+                            (((uint32_t)q[a][2] & 0xffu) << 16) | ((uint32_t)q[a][3] << 24);
+        } else {
+#pragma unroll
+          for (int e = 0; e < M / 2; ++e)
+            ((uint16_t*)row)[e] =
+                (uint16_t)(((uint32_t)q[a][2 * e] & 0xffu) | (((uint32_t)q[a][2 * e + 1] & 0xffu) << 8));
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int a = 0; a < M; ++a)
+#pragma unroll
+      for (int b = 0; b < M; ++b)
+        if (h0 + a < g.Ho && w0 + b < g.Wo) plane[(size_t)(h0 + a) * g.Wo + w0 + b] = (YT)q[a][b];
+  }
+}
+
 #endif  // __HIPCC__
 
 }  // namespace wino

@@ -70,6 +70,18 @@ inline bool gemm_out_preferred(const Geom& g) {
 }
 hipError_t launch_gemm_out(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                            float r_m, float r_y, float qmax, hipStream_t s);
+// The same for long int8 reductions (64 .. 512 padded channels; per-tensor or per-position
+// scales): column-by-column output transform, V shared through LDS.
+bool gemm_out_col_supported(const Geom& g);
+// ... and faster than both alternatives (gemm_out_kernel; tiled GEMM + output transform):
+// measured for m = 2 at every supported reduction, for m = 4 up to 256 channels; with
+// 512 channels and for m = 6 the few, long workgroups lose to the LDS-tiled GEMM.
+inline bool gemm_out_col_preferred(const Geom& g) {
+  return gemm_out_col_supported(g) && (g.m == 2 || (g.m == 4 && g.Cp <= 256));
+}
+hipError_t launch_gemm_out_col(const Geom& g, const MatAT& at, const void* V, const void* U,
+                               void* y, const PosScale* w_pos, float r_m, float r_y, float qmax,
+                               hipStream_t s);
 // Whole int8 forward in one kernel (neither V nor M stored); only where supported.
 bool fused_fwd_supported(const Geom& g);
 // ... and worth it with the vector-ALU input transform, which a second block of output
