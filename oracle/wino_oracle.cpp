@@ -26,8 +26,9 @@
 //       stage with every intermediate exposed.  Arithmetic is pinned so that an
 //       integer result is well defined for arbitrary real matrices:
 //       IEEE fp32, every sum a chain acc = +0; acc = fmaf(a_j, b_j, acc) over
-//       ascending j; rounding to integer is round-half-to-even; saturation to
-//       [-qmax, qmax] happens in float before the integer conversion.
+//       ascending j; a quantizer rounds the EXACT product of its fp32 input and its
+//       fp32 reciprocal step once, to the nearest integer, ties to even, and then
+//       saturates to [-qmax, qmax].
 //
 // Canonical tensor orders (row-major, last index fastest):
 //   X[N][C][H][W], g[K][C][3][3], Y[N][K][Ho][Wo], Ho = H + 2 pad - 2,
@@ -77,11 +78,14 @@ void matmul_bt(const double* A, int ar, int ac, const double* B, int br, double*
     }
 }
 
-// Symmetric uniform quantizer: saturate in float, round half to even.
-inline int32_t quantize(float v, float qmax) {
-  float r = nearbyintf(v);
-  r = fminf(fmaxf(r, -qmax), qmax);
-  return (int32_t)r;
+// Symmetric uniform quantizer q = sat(rne(v * r)) (Sec. 5.1: per-layer symmetric uniform
+// quantization; r is the reciprocal step, an fp32 number from the host).  The product is
+// taken exactly -- two fp32 numbers multiply without error in fp64 -- and rounded once, to
+// the nearest integer, ties to even; then saturated to [-qmax, qmax].
+inline int32_t quantize(float v, float r, float qmax) {
+  double q = nearbyint((double)v * (double)r);
+  q = fmin(fmax(q, -(double)qmax), (double)qmax);
+  return (int32_t)q;
 }
 
 }  // namespace
@@ -141,7 +145,7 @@ int oracle_conv2d_direct_q(int N, int C, int K, int H, int W, int stride, int pa
               }
           const size_t o = (((size_t)n * K + k) * Ho + h) * Wo + w;
           if (acc_out) acc_out[o] = s;
-          Yq[o] = quantize((float)s * r_y, (float)qmax);
+          Yq[o] = quantize((float)s, r_y, (float)qmax);
         }
   return 0;
 }
@@ -254,7 +258,7 @@ int oracle_q_weights_pos(int K, int C, int m, const float* G, const float* g,
           for (int b = 0; b < 3; ++b) acc = fmaf(t[i][b], G[j * 3 + b], acc);
           const size_t o = ((size_t)(i * n + j) * K + k) * C + c;
           if (U_f32) U_f32[o] = acc;
-          if (Uq) Uq[o] = quantize(acc * r_u_pos[i * n + j], (float)qmax);
+          if (Uq) Uq[o] = quantize(acc, r_u_pos[i * n + j], (float)qmax);
         }
     }
   return 0;
@@ -306,7 +310,7 @@ int oracle_q_input_pos(int N, int C, int H, int W, int pad, int m, const float* 
               for (int l = 0; l < n; ++l) acc = fmaf(w[i][l], BT[k * n + l], acc);
               const size_t o = ((size_t)(i * n + k) * T + t) * C + c;
               if (V_f32) V_f32[o] = acc;
-              if (Vq) Vq[o] = quantize(acc * r_v_pos[i * n + k], (float)qmax);
+              if (Vq) Vq[o] = quantize(acc, r_v_pos[i * n + k], (float)qmax);
             }
         }
       }
@@ -375,7 +379,7 @@ int64_t oracle_q_output_bits(int N, int K, int H, int W, int pad, int m, const f
               if (v >= (1 << 24) || v <= -(1 << 24)) ++inexact;
               float f = (float)v;
               if (w_pos) f = f * w_pos[i * n + j];
-              if (r_m > 0.0f) f = (float)quantize(f * r_m, (float)qmax_m);
+              if (r_m > 0.0f) f = (float)quantize(f, r_m, (float)qmax_m);
               Mf[i][j] = f;
             }
           for (int a = 0; a < m; ++a)
@@ -392,7 +396,7 @@ int64_t oracle_q_output_bits(int N, int K, int H, int W, int pad, int m, const f
               if (h < Ho && x < Wo) {
                 const size_t o = (((size_t)img * K + k) * Ho + h) * Wo + x;
                 if (Y_f32) Y_f32[o] = acc;
-                if (Yq) Yq[o] = quantize(acc * r_y, (float)qmax_y);
+                if (Yq) Yq[o] = quantize(acc, r_y, (float)qmax_y);
               }
             }
         }

@@ -287,12 +287,17 @@ def _round32(v):
 
 
 def _rne_sat(v, qmax):
-    return int(min(max(np.rint(np.float32(v)), -qmax), qmax))
+    """Nearest integer to the exact rational v, ties to even, saturated."""
+    v = Fraction(v)
+    fl = v.numerator // v.denominator
+    rem = v - fl
+    q = fl + (1 if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1) else 0)
+    return int(min(max(q, -qmax), qmax))
 
 
 def test_fused_chain_order_on_dense_matrices(oracle):
-    """The pinned arithmetic (ascending fused chains from +0, fp32 multiply by the
-    scale, round-half-even, saturate) emulated with exact rationals on a tiny case
+    """The pinned arithmetic (ascending fused chains from +0; the quantizer rounds the
+    exact product with its reciprocal step half to even, then saturates) emulated with exact rationals on a tiny case
     with dense random matrices, where the evaluation order does change bits."""
     rng = np.random.default_rng(13)
     m, n = 2, 4
@@ -321,7 +326,7 @@ def test_fused_chain_order_on_dense_matrices(oracle):
                     for l in range(n):
                         acc = _fma32(w[i][l], BT[k, l], acc)
                     assert Vf[i * n + k, t, c] == acc
-                    assert Vq[i * n + k, t, c] == _rne_sat(_round32(Fraction(float(acc)) * Fraction(float(r_v))), 127)
+                    assert Vq[i * n + k, t, c] == _rne_sat(Fraction(float(acc)) * Fraction(float(r_v)), 127)
     Uf, Uq = oracle.q_weights(g, G, r_u=r_u)
     for k in range(2):
         for c in range(2):
@@ -338,7 +343,7 @@ def test_fused_chain_order_on_dense_matrices(oracle):
                     for b in range(3):
                         acc = _fma32(tt[i][b], G[j, b], acc)
                     assert Uf[i * n + j, k, c] == acc
-                    assert Uq[i * n + j, k, c] == _rne_sat(_round32(Fraction(float(acc)) * Fraction(float(r_u))), 127)
+                    assert Uq[i * n + j, k, c] == _rne_sat(Fraction(float(acc)) * Fraction(float(r_u)), 127)
     M = oracle.q_hadamard(Vq, Uq)
     Yf, Yq, _ = oracle.q_output(M, AT, 1, 4, 4, pad=1, r_y=r_y)
     for t in range(4):
@@ -358,7 +363,7 @@ def test_fused_chain_order_on_dense_matrices(oracle):
                         acc = _fma32(z[a][j], AT[b, j], acc)
                     assert Yf[0, k, th * m + a, tw * m + b] == acc
                     assert Yq[0, k, th * m + a, tw * m + b] == _rne_sat(
-                        _round32(Fraction(float(acc)) * Fraction(float(r_y))), 127)
+                        Fraction(float(acc)) * Fraction(float(r_y)), 127)
 
 
 def test_q_scalars(oracle):
@@ -638,3 +643,18 @@ def test_error_to_direct_convolution_falls_with_the_bit_width(oracle):
     # 8-bit output codes: the floor is half an output step, 1/254 of the range, plus what
     # is left of the 16-bit Winograd-domain error
     assert errs[4, "int8_w16"] < 0.75 / 127 and errs[4, "int8_w16"] < errs[4, "int8"] / 4, errs
+
+
+def test_quantizer_rounds_the_exact_product_once(oracle):
+    """q = rne(v * r) on the exact product: 3 * fl32(1/6) = 0.5000000149 lies above the tie
+    and rounds to 1 (an fp32 multiplication first would land on 0.5 exactly and a second
+    rounding would give 0); 3 * fl32(0.16666666) lies below it and rounds to 0; exact ties
+    go to even; large products saturate."""
+    _, _, AT = oracle.cook_toom(2, dtype=np.float32)
+    r_up, r_dn = np.float32(1.0) / np.float32(6.0), np.float32(0.16666666)
+    assert Fraction(float(r_up)) * 3 > Fraction(1, 2) > Fraction(float(r_dn)) * 3
+    M = np.zeros((16, 1, 4), np.int64)
+    M[0, 0, :] = [3, -3, 5, 10 ** 9]                 # position (0,0) feeds output (0,0) only
+    for r, want in ((r_up, [1, -1, 1, 127]), (r_dn, [0, 0, 1, 127]), (np.float32(0.5), [2, -2, 2, 127])):
+        _, Yq, _ = oracle.q_output(M, AT, 1, 2, 2, pad=1, r_y=r)
+        assert [int(v) for v in Yq[0, :, 0, 0]] == want, (r, Yq[0, :, 0, 0])
