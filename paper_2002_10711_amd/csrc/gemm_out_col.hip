@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void gemm_out_col_kernel(Geom g, MatAT at,
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
             float f = (float)acc[tk][rr] * wp;
-            if constexpr (kMQ) f = (float)quantize(f, r_m, qmax);
+            if constexpr (kMQ) f = quantize_f(f, r_m, qmax);
 #pragma unroll
             for (int a = 0; a < M; ++a) {
               if (i == 0) z[tk][a][rr] = 0.0f;

@@ -3,7 +3,7 @@
 // (tap-major, channel fastest), the filters become rows of the same order, one
 // GEMM multiplies them, and an epilogue requantizes and scatters to NCHW.
 // Stride 1 or 2, 3x3 filters, zero padding.
-#include "wino_internal.h"
+#include "transform_math.h"
 
 namespace wino {
 namespace {
@@ -62,10 +62,8 @@ __global__ __launch_bounds__(256) void ref_epilogue_kernel(RefGeom g, const void
   const int hw = g.Ho * g.Wo, img = t / hw, pix = t % hw;
   const size_t o = ((size_t)img * g.K + k) * hw + pix;
   if (I8) {
-    float s = (float)((const int32_t*)Mv)[(size_t)t * g.Kp + k] * r_y;
-    s = __builtin_rintf(s);
-    s = fminf(fmaxf(s, -qmax), qmax);
-    ((int8_t*)yv)[o] = (int8_t)(int)s;
+    ((int8_t*)yv)[o] =
+        (int8_t)quantize((float)((const int32_t*)Mv)[(size_t)t * g.Kp + k], r_y, qmax);
   } else {
     ((float*)yv)[o] = ((const float*)Mv)[(size_t)t * g.Kp + k];
   }
@@ -145,9 +143,7 @@ __global__ __launch_bounds__(256) void ref_epilogue_tiled_kernel(RefGeom g,
     float s = 0.0f;
     if (t < g.T) {
       if (I8) {
-        s = (float)((const int32_t*)Mv)[(size_t)t * g.Kp + k0 + k] * r_y;
-        s = __builtin_rintf(s);
-        s = fminf(fmaxf(s, -qmax), qmax);
+        s = quantize_f((float)((const int32_t*)Mv)[(size_t)t * g.Kp + k0 + k], r_y, qmax);
       } else {
         s = ((const float*)Mv)[(size_t)t * g.Kp + k0 + k];
       }

@@ -111,7 +111,7 @@ __device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
       for (int j = 0; j < n; ++j) {
         if constexpr (I8) {
           float f = (float)acc[i * n + j][rr];
-          if constexpr (kMQ) f = (float)quantize(f, r_m, qmax);
+          if constexpr (kMQ) f = quantize_f(f, r_m, qmax);
           Mt[i][j] = f;
         } else {
           Mt[i][j] = acc[i * n + j][rr];

@@ -4,9 +4,9 @@
 // Arithmetic contract of the int8 mode (what makes an integer result well defined
 // for arbitrary real matrices): IEEE fp32; every sum is the chain
 // acc = +0; acc = fma(a_j, b_j, acc) over ascending j; the left product of a
-// two-sided transform comes first (B^T d, G g, A^T M); the scale is applied by one
-// fp32 multiplication; rounding is half-to-even; saturation to [-qmax, qmax]
-// happens before the integer is taken.
+// two-sided transform comes first (B^T d, G g, A^T M); a quantizer rounds the exact
+// product of its input and its reciprocal step once, half to even, and saturates to
+// [-qmax, qmax].
 //
 // Terms whose matrix entry is exactly zero may be skipped: fma(0, x, acc) == acc
 // for finite x (a +0/-0 difference disappears when the integer is taken, and
@@ -52,24 +52,27 @@ inline bool fits_mask(const float* mat, int count, uint64_t mask) {
 
 #if defined(__HIPCC__)
 
-// sat(rne(v * r)) as an integer in [-qmax, qmax].
-__device__ __forceinline__ int quantize(float v, float r, float qmax) {
-  float s = v * r;
-  s = __builtin_rintf(s);
-  s = fminf(fmaxf(s, -qmax), qmax);
-  return (int)s;
-}
-
-// The same value, left in the low byte of a float's bit pattern: adding 1.5 * 2^23
-// rounds v * r to an integer, half to even (the sum lies in [2^23, 2^24) where the
-// spacing is 1, for |v r| < 2^22; beyond that the sum is past the clamp bounds
-// anyway), and the low mantissa bits then hold the two's-complement integer.
+// The stage quantizer q = sat(rne(v * r)), product taken exactly and rounded once: the
+// fused multiply-add v * r + 1.5 * 2^23 rounds the exact sum to fp32, and in [2^23, 2^24)
+// the fp32 numbers are the integers, so for |v r| < 2^22 the result is 1.5 * 2^23 plus the
+// integer nearest to v * r, ties to even (1.5 * 2^23 is even).  Beyond that range the sum
+// is past the clamp bounds anyway.  The low mantissa bits hold the two's-complement
+// integer: bits(1.5 * 2^23 + q) = 0x4B400000 + q.
 constexpr float kMagic = 12582912.0f;
+constexpr uint32_t kMagicBits = 0x4B400000u;
+// ... left in the low bits of a float's bit pattern (lo = kMagic - qmax, hi = kMagic + qmax)
 __device__ __forceinline__ uint32_t quantize_bits(float v, float r, float lo, float hi) {
-  float s = v * r;
-  float u = s + kMagic;
-  u = __builtin_amdgcn_fmed3f(u, lo, hi);   // lo = kMagic - qmax, hi = kMagic + qmax
+  float u = __builtin_fmaf(v, r, kMagic);
+  u = __builtin_amdgcn_fmed3f(u, lo, hi);
   return __float_as_uint(u);
+}
+// ... as an integer in [-qmax, qmax]
+__device__ __forceinline__ int quantize(float v, float r, float qmax) {
+  return (int)(quantize_bits(v, r, kMagic - qmax, kMagic + qmax) - kMagicBits);
+}
+// ... as a float holding that integer
+__device__ __forceinline__ float quantize_f(float v, float r, float qmax) {
+  return __uint_as_float(quantize_bits(v, r, kMagic - qmax, kMagic + qmax)) - kMagic;
 }
 
 // out with byte `e` replaced by the low byte of `bits` (v_perm_b32: selector

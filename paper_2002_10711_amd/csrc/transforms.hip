@@ -6,9 +6,9 @@
 // Arithmetic contract of the int8 mode (what makes an integer result well defined
 // for arbitrary real matrices): IEEE fp32; every sum is the chain
 // acc = +0; acc = fma(a_j, b_j, acc) over ascending j; the first product of a
-// two-sided transform is the left one (B^T d, G g, A^T M); the scale is applied
-// by one fp32 multiplication; rounding is half-to-even; saturation to
-// [-qmax, qmax] is done in float before the integer conversion.
+// two-sided transform is the left one (B^T d, G g, A^T M); a quantizer rounds the
+// exact product of its input and its reciprocal step once, half to even, and
+// saturates to [-qmax, qmax] (transform_math.h).
 //
 // The matrices arrive by value in the kernel arguments (scalar registers), never
 // as compiled-in constants, so learned transforms use the same code.
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void output_transform(Geom g, MatAT at,
       if (I8) {
         float f = (float)((const int32_t*)Mv)[(i * n + j) * pstride + base];
         if constexpr (kPos) f = f * wp.r[i * n + j];
-        if constexpr (kMQ) f = (float)quantize(f, r_m, qmax);
+        if constexpr (kMQ) f = quantize_f(f, r_m, qmax);
         Mt[i][j] = f;
       } else {
         Mt[i][j] = ((const float*)Mv)[(i * n + j) * pstride + base];

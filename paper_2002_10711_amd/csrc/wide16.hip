@@ -46,10 +46,7 @@ __device__ __forceinline__ void split_code(float v, _Float16& a, _Float16& b) {
   a = (_Float16)hi;
   b = (_Float16)__builtin_fmaf(hi, -256.0f, v);
 }
-// sat(rne(v * r)) as a float holding the integer code
-__device__ __forceinline__ float quantize_f(float v, float r, float qmax) {
-  return __builtin_amdgcn_fmed3f(__builtin_rintf(v * r), -qmax, qmax);
-}
+
 __device__ __forceinline__ int join_code(_Float16 a, _Float16 b) {
   return (int)(float)a * 256 + (int)(float)b;
 }
@@ -325,7 +322,7 @@ __global__ __launch_bounds__(256) void output_transform_w16(Geom g, MatAT at,
       const int p = i * n + j;
       float f = (float)Mi[((size_t)p * g.Tp + t) * g.Kp + k];   // correctly rounded
       if (kPos) f = f * w.r[p];
-      if (r_m > 0.0f) f = (float)quantize(f, r_m, qmax_m);
+      if (r_m > 0.0f) f = quantize_f(f, r_m, qmax_m);
       Mt[i][j] = f;
     }
   transform_result<M, kSparse>(Mt, at, Y);
@@ -489,7 +486,7 @@ __global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT a
           const double dm = __builtin_fma((double)hh[rr], 65536.0,
                                           __builtin_fma((double)mid[rr], 256.0, (double)ll[rr]));
           float f = (float)dm * wp;
-          if constexpr (kMQ) f = (float)quantize(f, r_m, qmax_m);
+          if constexpr (kMQ) f = quantize_f(f, r_m, qmax_m);
 #pragma unroll
           for (int a = 0; a < M; ++a) {
             if (i == 0) z[a][rr] = 0.0f;
