@@ -346,10 +346,11 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
       if (st + 1 < NSTEP)   // every lane takes part in the MFMA; only the stores are predicated
         nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
                                                     v4i{0, 0, 0, 0}, 0, 0, 0);
-      uint32_t packed = 0u;
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr)
-        packed = __builtin_amdgcn_perm(quantize_bits((float)cur[rr], r_vs, lo, hi), packed, 0x04030201u);
+      // four codes into one dword with three byte permutes
+      const uint32_t packed = pack_codes(quantize_bits((float)cur[0], r_vs, lo, hi),
+                                         quantize_bits((float)cur[1], r_vs, lo, hi),
+                                         quantize_bits((float)cur[2], r_vs, lo, hi),
+                                         quantize_bits((float)cur[3], r_vs, lo, hi));
       const int tl = wave * 4 + (gi >> 2);
       if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
       cur = nxt;
@@ -473,10 +474,11 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
       if (st + 1 < NSTEP)
         nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
                                                     v4i{0, 0, 0, 0}, 0, 0, 0);
-      uint32_t packed = 0u;
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr)
-        packed = __builtin_amdgcn_perm(quantize_bits((float)cur[rr], r_vs, lo, hi), packed, 0x04030201u);
+      // four codes into one dword with three byte permutes
+      const uint32_t packed = pack_codes(quantize_bits((float)cur[0], r_vs, lo, hi),
+                                         quantize_bits((float)cur[1], r_vs, lo, hi),
+                                         quantize_bits((float)cur[2], r_vs, lo, hi),
+                                         quantize_bits((float)cur[3], r_vs, lo, hi));
       const int tl = wave * 2 + (gi >> 2);
       if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
       cur = nxt;
@@ -580,10 +582,10 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
     if (st + 1 < NSTEP)
       nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
                                                   v4i{0, 0, 0, 0}, 0, 0, 0);
-    uint32_t packed = 0u;
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr)
-      packed = __builtin_amdgcn_perm(quantize_bits((float)cur[rr], rq[blk], lo, hi), packed, 0x04030201u);
+    const uint32_t packed = pack_codes(quantize_bits((float)cur[0], rq[blk], lo, hi),
+                                       quantize_bits((float)cur[1], rq[blk], lo, hi),
+                                       quantize_bits((float)cur[2], rq[blk], lo, hi),
+                                       quantize_bits((float)cur[3], rq[blk], lo, hi));
     const int tl = wave * 4 + (gi >> 2);
     if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
     cur = nxt;

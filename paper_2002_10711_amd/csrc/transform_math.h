@@ -75,6 +75,14 @@ __device__ __forceinline__ float quantize_f(float v, float r, float qmax) {
   return __uint_as_float(quantize_bits(v, r, kMagic - qmax, kMagic + qmax)) - kMagic;
 }
 
+// The low bytes of four such bit patterns as one dword, b0 lowest (v_perm_b32: selector
+// values 0..3 pick bytes of the second operand, 4..7 bytes of the first, 0x0c is zero).
+__device__ __forceinline__ uint32_t pack_codes(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3) {
+  const uint32_t lo2 = __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u);
+  const uint32_t hi2 = __builtin_amdgcn_perm(b3, b2, 0x04000c0cu);
+  return __builtin_amdgcn_perm(hi2, lo2, 0x07060100u);
+}
+
 // out with byte `e` replaced by the low byte of `bits` (v_perm_b32: selector
 // values 0..3 pick bytes of the second operand, 4..7 bytes of the first).
 template <int e>
