@@ -99,7 +99,7 @@ def roofline_entry(name, alg, us, dtype, traffic):
     ent.update(kernel=name, frac=ent["achieved"] / ent["peak"], avg_us=us,
                algorithmic_bytes=alg["bytes"], algorithmic_ops=alg["ops"],
                algorithmic_alu_ops=alg["alu"], hbm_frac=alg["bytes"] / sec / 1e9 / HBM_PEAK_GBS,
-               traffic=traffic)
+               mfma_frac=alg["ops"] / sec / 1e12 / mf, traffic=traffic)
     return ent
 
 
@@ -285,6 +285,74 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
                 BT=BT, AT=AT)
 
 
+def ref_only_leg(L, steps, warmup):
+    """ms per forward of the im2row baseline on a layer (stride 1 or 2), weights packed once."""
+    import torch
+    from paper_2002_10711_amd import binding as wb
+    dev = torch.device("cuda:0")
+    sc = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[L.name]
+    X, g = workloads.make_inputs(L)
+    xh = np.clip(np.rint(X / np.float32(sc["s_x"])), -127, 127).astype(np.int8)
+    wq = np.clip(np.rint(g / np.float32(sc["s_w"])), -127, 127).astype(np.int8)
+    x, wdev = torch.from_numpy(xh).to(dev), torch.from_numpy(wq).to(dev)
+    y = torch.empty((L.N, L.K, L.Ho, L.Wo), dtype=torch.int8, device=dev)
+    wp = torch.empty(wb.conv2d_ref_packed_weights_bytes(L.C, L.K, wb.WINO_I8), dtype=torch.uint8, device=dev)
+    rws = torch.empty(wb.conv2d_ref_workspace_bytes(L.N, L.C, L.K, L.H, L.W, L.stride, L.pad, wb.WINO_I8),
+                      dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        wb.conv2d_ref_pack_weights(L.C, L.K, wb.WINO_I8, wdev, wp, stream=stream)
+
+        def fn():
+            wb.conv2d_ref_gpu(L.N, L.C, L.K, L.H, L.W, L.stride, L.pad, wb.WINO_I8, x, wp, y,
+                              sc["s_x"], sc["s_w"], sc["s_y"], 127, rws, stream=stream)
+        for _ in range(3):
+            fn()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for _ in range(5):
+                fn()
+        for _ in range(max(1, warmup // 5)):
+            graph.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        n = max(1, steps // 5)
+        for _ in range(n):
+            graph.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (n * 5)
+
+
+def stack_line(steps, warmup):
+    """The 16 3x3 convolutions of CIFAR ResNet-18 (batch 256, int8) one after the other:
+    stride-1 layers on their Winograd tile, stride-2 layers on the im2row baseline; forward
+    only, weights prepared beforehand (the paper's deployment setting, Sec. 5.3)."""
+    layers = workloads.config5()
+    rows, t_wino, t_ref, ops = [], 0.0, 0.0, 0
+    for L in layers:
+        if L.stride == 1:
+            r = gpu_leg(L, steps, warmup, True)
+            fwd, ref = r["ms_fwd"], r["ms_ref"]
+        else:
+            fwd = ref = ref_only_leg(L, steps, warmup)
+        rows.append(dict(layer=L.name, fwd_us=fwd * 1e3, im2row_us=ref * 1e3))
+        t_wino += fwd
+        t_ref += ref
+        ops += L.direct_ops
+    return {
+        "metric": "direct-conv-equiv TOPS, CIFAR ResNet-18 3x3 conv stack forward (13 Winograd + 3 im2row layers)",
+        "value": ops / (t_wino * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": t_wino, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "cfg5 stack: 16 layers, N=256, 64/128/256/512 channels at 32/16/8/4, "
+                               "per-layer m from the seed", "launch": "hip-graph replay per layer"},
+        "im2row_stack_ms": t_ref, "speedup_vs_im2row": t_ref / t_wino, "layers": rows,
+    }
+
+
 def cpu_leg(L):
     """The oracle as it stands, on the host cores, whole quantized forward
     (weight stage included) on the first images of the same workload."""
@@ -327,6 +395,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host "
                     "instead of replaying a captured HIP graph of one step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stack", action="store_true", help="time the whole CIFAR ResNet-18 conv "
+                    "stack (config 5: 16 layers, batch 256, int8) layer by layer, forward only, "
+                    "and print its total instead of one workload's line")
     ap.add_argument("--flex", type=float, default=0.0, help="perturb the Cook-Toom matrices by "
                     "seeded N(0, FLEX) noise (dense 'learned' transforms, paper Sec. 3.2): a timing "
                     "option, the stored scales are not recalibrated")
@@ -343,6 +414,9 @@ def main():
         raise SystemExit("bench.py: this build runs on ONE GPU only (the path needs no exchange "
                          "step: tiles are independent, so more GPUs would each take a share of the batch); "
                          "got --gpus %d" % a.gpus)
+    if a.stack:
+        print(json.dumps(stack_line(max(20, a.steps // 5), max(5, a.warmup // 5))))
+        return
     L = pick_workload(a.workload)
     if a.flex > 0:
         from dataclasses import replace
