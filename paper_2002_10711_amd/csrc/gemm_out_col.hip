@@ -34,7 +34,7 @@ constexpr int ring_depth(int sj) {
 }
 
 template <int M, int NCH, bool kSparse, int kTW>
-__global__ __launch_bounds__(256) void gemm_out_col_kernel(Geom g, MatAT at,
+__global__ __launch_bounds__(256, M == 6 ? 2 : 1) void gemm_out_col_kernel(Geom g, MatAT at,
                                                            const int8_t* __restrict__ V,
                                                            const int8_t* __restrict__ U,
                                                            int8_t* __restrict__ y, PosScale w,
@@ -42,10 +42,12 @@ __global__ __launch_bounds__(256) void gemm_out_col_kernel(Geom g, MatAT at,
                                                            int fast) {
   constexpr int n = M + 2;
   constexpr int SJ = n * NCH;                          // steps (64 channels each) per column
-  constexpr int kDepth = ring_depth(SJ);               // U ring, in steps
+  // U ring, in steps (m = 6: shorter, so that two workgroups fit a CU -- its layers have
+  // few tiles, and one workgroup per CU leaves a second, mostly empty round)
+  constexpr int kDepth = M == 6 ? 8 : ring_depth(SJ);
   constexpr int kBlocks = NCH * kTW;                   // 1 KB operand blocks of V per position
   constexpr int kLd = (kBlocks + 3) / 4;               // 16-byte loads per thread and position
-  constexpr int kPos = kLd > 1 ? 2 : NCH >= 4 ? n / 2 : n;        // positions ahead
+  constexpr int kPos = kLd > 1 ? 2 : (NCH >= 4 || M == 6) ? n / 2 : n;        // positions ahead
   static_assert(n % kPos == 0 && n % 2 == 0 && kPos + 1 <= n + 1, "static ring slots");
   constexpr int kBufPieces = kBlocks * 64;             // 16-byte pieces of one position
   __shared__ v4u vlds[2 * kBufPieces];

@@ -3,6 +3,8 @@
 // position, and the NCHW store of one m x m tile (Eq. 1, Sec. 3.1; quantizer of
 // Sec. 3.2).
 #pragma once
+#include <type_traits>
+
 #include "transform_math.h"
 
 namespace wino {
@@ -53,6 +55,17 @@ __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv,
                 (uint16_t)__builtin_amdgcn_perm(q[a][b + 1], q[a][b], 0x0c0c0400u);
         }
       }
+    } else if ((g.Wo & 1) == 0) {
+      // ragged tile, even row pitch: a pair of codes is inside the image or outside it as
+      // a whole (w0 is even), so the rows go out in 2-byte stores -- the L1 pays per lane
+      // and store, not per byte
+#pragma unroll
+      for (int a = 0; a < M; ++a)
+#pragma unroll
+        for (int b = 0; b < M; b += 2)
+          if (h0 + a < g.Ho && w0 + b < g.Wo)
+            *(uint16_t*)(y + (size_t)(h0 + a) * g.Wo + w0 + b) =
+                (uint16_t)__builtin_amdgcn_perm(q[a][b + 1], q[a][b], 0x0c0c0400u);
     } else {
 #pragma unroll
       for (int a = 0; a < M; ++a)
@@ -157,6 +170,20 @@ __device__ __forceinline__ void store_codes(YT* __restrict__ plane, const Geom& 
         }
       }
     }
+  } else if ((g.Wo & 1) == 0 && ((uintptr_t)plane & (2 * sizeof(YT) - 1)) == 0) {
+    // ragged tile, even row pitch: a pair of codes is inside the image or outside it as a
+    // whole (w0 is even): one store per pair -- the L1 pays per lane and store, not per byte
+    typedef typename std::conditional<sizeof(YT) == 2, uint32_t, uint16_t>::type pair_t;
+#pragma unroll
+    for (int a = 0; a < M; ++a)
+#pragma unroll
+      for (int b = 0; b < M; b += 2)
+        if (h0 + a < g.Ho && w0 + b < g.Wo) {
+          constexpr int EB = 8 * (int)sizeof(YT);
+          const uint32_t mask = (1u << EB) - 1u;
+          *(pair_t*)(plane + (size_t)(h0 + a) * g.Wo + w0 + b) =
+              (pair_t)(((uint32_t)q[a][b] & mask) | ((uint32_t)q[a][b + 1] << EB));
+        }
   } else {
 #pragma unroll
     for (int a = 0; a < M; ++a)
