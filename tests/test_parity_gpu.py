@@ -77,6 +77,12 @@ SMALL = [
     Layer("s_f2_c128_k72_32px", 1, 128, 72, 32, 32, m=2, seed=148),
     Layer("s_f2_c100_k128_6px", 7, 100, 128, 6, 6, m=2, seed=149),
     Layer("s_f4_c128_k128_64px", 1, 128, 128, 64, 64, m=4, seed=150),
+    # long reductions: GEMM fused with the column-by-column output transform
+    Layer("s_f2_c200_k300_ragged", 2, 200, 300, 9, 11, m=2, seed=151),
+    Layer("s_f4_c256_k64_pad0", 2, 256, 64, 14, 10, m=4, pad=0, seed=152),
+    Layer("s_f2_c512_k70_5px", 3, 512, 70, 5, 5, m=2, seed=153),
+    Layer("s_f6_c128_k96_13px", 2, 128, 96, 13, 13, m=6, seed=154),
+    Layer("s_f4_c450_k130_12px", 1, 450, 130, 12, 12, m=4, seed=155),   # 512 padded: tiled GEMM
 ]
 
 
@@ -153,6 +159,8 @@ def test_many_tiles_ragged_flex_and_m_quantizer(oracle, m):
     Layer("pos_f2_ragged", 2, 20, 24, 9, 11, m=2, seed=132),      # vector-ALU input stage
     Layer("pos_f6", 2, 12, 33, 14, 14, m=6, seed=133),
     Layer("pos_f4_flex", 2, 24, 40, 10, 10, m=4, flex_sigma=0.05, seed=134),
+    Layer("pos_f2_c256", 2, 256, 40, 8, 8, m=2, seed=135),        # long reduction, fused GEMM + output
+    Layer("pos_f6_c128", 1, 128, 70, 16, 16, m=6, seed=136),
 ], ids=lambda l: l.name)
 def test_per_position_scales_all_taps(oracle, layer):
     """One quantizer scale per Winograd position for V and U (Sec. 6), calibrated by the
