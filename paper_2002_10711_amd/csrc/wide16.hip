@@ -667,12 +667,16 @@ hipError_t gemm_out_mys(const Geom& g, const MatAT& at, const void* V, const voi
   const bool two = w16_two_groups(g);
 #define WINO_W16_GO(NCHV)                                                                     \
   do {                                                                                        \
-    if (two)                                                                                  \
-      gemm_out_w16_kernel<M, YT, NCHV, kSparse, 2><<<dim3(g.Tp / 32, g.Kp / 64), 512, 0, s>>>( \
-          g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast);                             \
-    else                                                                                      \
-      gemm_out_w16_kernel<M, YT, NCHV, kSparse, 1><<<dim3(g.Tp / 16, g.Kp / 64), 256, 0, s>>>( \
-          g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast);                             \
+    if constexpr (M != 6 && NCHV <= 8) { /* (the shapes w16_two_groups can select) */         \
+      if (two) {                                                                              \
+        gemm_out_w16_kernel<M, YT, NCHV, kSparse, 2>                                          \
+            <<<dim3(g.Tp / 32, g.Kp / 64), 512, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y,      \
+                                                        qmax_m, qmax_y, fast);                \
+        break;                                                                                \
+      }                                                                                       \
+    }                                                                                         \
+    gemm_out_w16_kernel<M, YT, NCHV, kSparse, 1><<<dim3(g.Tp / 16, g.Kp / 64), 256, 0, s>>>(  \
+        g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast);                               \
   } while (0)
   switch (g.Cp) {
     case 64: WINO_W16_GO(2); break;
