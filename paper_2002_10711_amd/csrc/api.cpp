@@ -59,10 +59,11 @@ wino_status make_geom(const wino_desc* d, Geom* g) {
 }
 
 size_t align256(size_t b) { return (b + 255) / 256 * 256; }
-// (wide modes: two fp16 digit planes per element of U and V, int64 M)
-size_t v_bytes(const Geom& g) { return align256((size_t)g.P * g.Tp * g.Cp * (g.i8 ? 1 : 4)); }
+// (wide modes: two int8 digit planes per element of U and V, int64 M)
+size_t elem_bytes(const Geom& g) { return g.i8 ? 1 : g.w16 ? 2 : 4; }
+size_t v_bytes(const Geom& g) { return align256((size_t)g.P * g.Tp * g.Cp * elem_bytes(g)); }
 size_t m_bytes(const Geom& g) { return align256((size_t)g.P * g.Tp * g.Kp * (g.w16 ? 8 : 4)); }
-size_t u_bytes(const Geom& g) { return align256((size_t)g.P * g.Kp * g.Cp * (g.i8 ? 1 : 4)); }
+size_t u_bytes(const Geom& g) { return align256((size_t)g.P * g.Kp * g.Cp * elem_bytes(g)); }
 
 // Code range of one stage: its own field, else the common qmax.
 int stage_qmax(int own, int common) { return own ? own : common; }

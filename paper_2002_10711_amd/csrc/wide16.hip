@@ -3,24 +3,30 @@
 // bit-width; Sec. 5.1 runs INT8, INT10 and INT16; Sec. 6 names wider intermediate stages as
 // the way to recover F4/F6 accuracy).
 //
-// The matrix cores have no 16-bit integer instruction.  A code v in [-32767, 32767] is
-// split into two balanced base-256 digits, v = 256 a + b with |a| <= 128 and |b| <= 128,
-// both exact in fp16, and the per-position GEMM of Sec. 5.3 becomes four
-// fp16 MFMAs per 32 channels,
+// The matrix cores have no 16-bit integer instruction, but int8 at twice the fp16 rate.  A
+// code v in [-32767, 32767] is stored as two int8 digits of v - 128,
 //
-//     sum_c u v = 2^16 sum a_u a_v + 2^8 (sum a_u b_v + sum b_u a_v) + sum b_u b_v .
+//     v = 256 a + b + 128,   a = floor(v / 256),  b = v mod 256 - 128,   a, b in [-128, 127]
 //
-// Every product is an integer of magnitude <= 2^14 and every partial sum stays an integer
-// below 2^24 for up to 1024 channels (512 where the two middle sums share one
-// accumulator), so the fp32 accumulators of the MFMA hold them exactly; the four sums are
-// recombined in 64-bit integers.  The result is the exact integer M of the int16 pipeline.
+// (the offset makes both digits fit: a plain balanced split needs a = 128 for the largest
+// codes).  With u~ = u - 128, v~ = v - 128 the per-position GEMM of Sec. 5.3 becomes
 //
-// Device layouts of this mode (fp16 digit planes, digit 0 = a, digit 1 = b):
+//     sum_c u v = sum u~ v~ + 128 sum u~ + 128 sum v~ + 16384 Cp,
+//     sum u~ v~ = 2^16 sum a_u a_v + 2^8 (sum a_u b_v + sum b_u a_v) + sum b_u b_v,
+//
+// all sums over the Cp padded channels (padding encodes v = 0 like any other code): four
+// v_mfma_i32_16x16x64_i8 per 64 channels for the digit pairs, and four more against an
+// operand of ones for sum u~ (per output channel) and sum v~ (per tile), which land in the
+// same lanes as the accumulators they correct.  Every partial sum is an exact int32
+// (|.| <= 2^15 Cp); the recombination runs in 64-bit integers or in fp64 below 2^53.  The
+// result is the exact integer M of the int16 pipeline.
+//
+// Device layouts of this mode (int8 digit planes, plane 0 = a, plane 1 = b):
 //   V [P][2][Tp][Cp]   plain rows, channel fastest
-//   U [P][Kp/16][Cp/32][2][64 lanes][8]  blocks in the order an MFMA wavefront loads its "A"
-//                      operand: lane = (c % 32 / 8) * 16 + k % 16 holds channels c % 8
+//   U [P][Kp/16][Cp/64][2][64 lanes][16]  1 KB blocks in the order an MFMA wavefront loads
+//                      its "A" operand: lane = (c % 64 / 16) * 16 + k % 16 holds 16 channels
 //   M [P][Tp][Kp]      int64
-// with Tp, Kp, Cp rounded up to 64; padding channels hold zero.
+// with Tp, Kp, Cp rounded up to 64.
 #include <type_traits>
 
 #include "output_stage.h"
@@ -28,27 +34,32 @@
 namespace wino {
 namespace {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
-__host__ __device__ inline size_t u16_index(int Kp, int Cp, int p, int digit, int k, int c) {
-  const size_t blk = ((size_t)p * (Kp >> 4) + (k >> 4)) * (Cp >> 5) + (c >> 5);
-  return ((blk * 2 + digit) * 64 + (size_t)(((c & 31) >> 3) * 16 + (k & 15))) * 8 + (c & 7);
+__host__ __device__ inline size_t u8w_index(int Kp, int Cp, int p, int plane, int k, int c) {
+  const size_t blk = ((size_t)p * (Kp >> 4) + (k >> 4)) * (Cp >> 6) + (c >> 6);
+  return ((blk * 2 + plane) * 64 + (size_t)(((c & 63) >> 4) * 16 + (k & 15))) * 16 + (c & 15);
 }
-__host__ __device__ inline size_t v16_index(int Tp, int Cp, int p, int digit, int t, int c) {
-  return (((size_t)p * 2 + digit) * Tp + t) * Cp + c;
-}
-
-// v = 256 a + b with |a|, |b| <= 128, on the code as a float (an integer, |v| <= 32767):
-// a = v / 256 rounded to the nearest integer (ties to even), b the exact remainder.
-__device__ __forceinline__ void split_code(float v, _Float16& a, _Float16& b) {
-  const float hi = __builtin_rintf(v * 0.00390625f);
-  a = (_Float16)hi;
-  b = (_Float16)__builtin_fmaf(hi, -256.0f, v);
+__host__ __device__ inline size_t v8w_index(int Tp, int Cp, int p, int plane, int t, int c) {
+  return (((size_t)p * 2 + plane) * Tp + t) * Cp + c;
 }
 
-__device__ __forceinline__ int join_code(_Float16 a, _Float16 b) {
-  return (int)(float)a * 256 + (int)(float)b;
+// v = 256 a + b + 128 on the code as a float (an integer, |v| <= 32767); a, b in [-128, 127]
+__device__ __forceinline__ void split_code(float v, int& a, int& b) {
+  const float hi = __builtin_floorf(v * 0.00390625f);
+  a = (int)hi;
+  b = (int)(__builtin_fmaf(hi, -256.0f, v) - 128.0f);
+}
+__device__ __forceinline__ int join_code(int8_t a, int8_t b) { return (int)a * 256 + (int)b + 128; }
+
+constexpr int kOnes = 0x01010101;                      // sixteen int8 ones: v4i{kOnes, ...}
+
+// M from the seven int32 sums of one (tile, output channel): digit pairs hh, mid
+// (= a_u b_v + b_u a_v), ll; digit sums of v~ (sva, svb) and of u~ (sua, sub).
+__device__ __forceinline__ long long combine_i64(int hh, int mid, int ll, int sva, int svb,
+                                                 int sua, int sub, int Cp) {
+  return (long long)hh * 65536 + ((long long)mid + 128ll * ((long long)sva + sua)) * 256 +
+         (long long)ll + 128ll * ((long long)svb + sub) + 16384ll * Cp;
 }
 
 // Weight stage (Eq. 1: U = G g G^T; quantizer of Sec. 3.2): one thread per (k, c) of the
@@ -56,7 +67,7 @@ __device__ __forceinline__ int join_code(_Float16 a, _Float16 b) {
 template <int M>
 __global__ __launch_bounds__(256) void weight_transform_w16(Geom g, MatG mg,
                                                             const float* __restrict__ w,
-                                                            _Float16* __restrict__ U, PosScale ru,
+                                                            int8_t* __restrict__ U, PosScale ru,
                                                             float qmax) {
   constexpr int n = M + 2;
   const int idx = blockIdx.x * 256 + threadIdx.x;
@@ -81,18 +92,18 @@ __global__ __launch_bounds__(256) void weight_transform_w16(Geom g, MatG mg,
 #pragma unroll
     for (int j = 0; j < n; ++j) {
       const int p = i * n + j;
-      _Float16 a, b;
+      int a, b;
       split_code(quantize_f(Uf[i][j], ru.r[p], qmax), a, b);
-      U[u16_index(g.Kp, g.Cp, p, 0, k, c)] = a;
-      U[u16_index(g.Kp, g.Cp, p, 1, k, c)] = b;
+      U[u8w_index(g.Kp, g.Cp, p, 0, k, c)] = (int8_t)a;
+      U[u8w_index(g.Kp, g.Cp, p, 1, k, c)] = (int8_t)b;
     }
 }
 
 // Input stage (Eq. 1: V = B^T d B on every patch, Sec. 3.2): a workgroup owns 8
 // consecutive tiles x 32 channels, one (tile, channel) per thread with the tiles along the
 // lanes: neighbouring patches overlap, so the eight lanes of a channel read one run of an
-// image row (one cache access instead of eight).  The codes go through LDS so that the
-// rows of V are written in pieces of 64 bytes.
+// image row (one cache access instead of eight).  The digits go through LDS so that the
+// rows of V are written in pieces of 32 bytes.
 // kRow: every image row holds at least one load window (W >= 8 elements): a
 // lane fetches each of its n patch rows with ONE load of a window clamped into the row and
 // shifts the patch out of it, instead of n loads of one element -- the L1 spends its
@@ -100,11 +111,11 @@ __global__ __launch_bounds__(256) void weight_transform_w16(Geom g, MatG mg,
 template <int M, typename XT, bool kSparse, bool kRow>
 __global__ __launch_bounds__(256) void input_transform_w16(Geom g, MatBT bt,
                                                            const XT* __restrict__ x,
-                                                           _Float16* __restrict__ V, PosScale rv,
+                                                           int8_t* __restrict__ V, PosScale rv,
                                                            float qmax) {
   constexpr int n = M + 2, P = n * n;
-  constexpr int kPitch = 40;                           // halfs per staged row (32 used)
-  __shared__ __attribute__((aligned(16))) _Float16 sm[P * 8 * kPitch];
+  constexpr int kPitch = 48;                           // bytes per staged row (32 used)
+  __shared__ __attribute__((aligned(16))) int8_t sm[P * 8 * kPitch];
   const int tid = threadIdx.x, r = tid & 7, cc = tid >> 3;
   const int t = blockIdx.x * 8 + r, c = blockIdx.y * 32 + cc;
   float d[n][n];
@@ -197,53 +208,53 @@ __global__ __launch_bounds__(256) void input_transform_w16(Geom g, MatBT bt,
     if (digit) __syncthreads();                        // the first plane has left LDS
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-      _Float16 a, b;
+      int a, b;
       split_code(code[p], a, b);
-      sm[(p * 8 + r) * kPitch + cc] = digit ? b : a;
+      sm[(p * 8 + r) * kPitch + cc] = (int8_t)(digit ? b : a);
     }
     __syncthreads();
-    // P * 8 rows of 32 channels = P * 32 pieces of 16 bytes
-    for (int idx = tid; idx < P * 32; idx += 256) {
-      const int p = idx >> 5, row = (idx & 31) >> 2, piece = idx & 3;
-      *(v4u*)(V + v16_index(g.Tp, g.Cp, p, digit, blockIdx.x * 8 + row,
-                            blockIdx.y * 32 + piece * 8)) =
-          *(const v4u*)&sm[(p * 8 + row) * kPitch + piece * 8];
+    // P * 8 rows of 32 channels = P * 16 pieces of 16 bytes
+    for (int idx = tid; idx < P * 16; idx += 256) {
+      const int p = idx >> 4, row = (idx & 15) >> 1, piece = idx & 1;
+      *(v4u*)(V + v8w_index(g.Tp, g.Cp, p, digit, blockIdx.x * 8 + row,
+                            blockIdx.y * 32 + piece * 16)) =
+          *(const v4u*)&sm[(p * 8 + row) * kPitch + piece * 16];
     }
   }
 }
 
 // Hadamard/GEMM stage (Sec. 5.3: one GEMM per Winograd position, channels summed in the
 // Winograd domain), exact in 64-bit integers.  Workgroup = 64 tiles x 64 output channels
-// of one position; wavefront = 32 x 32 = 2 x 2 MFMA tiles with four accumulators each
-// (the digit pairs).  Operands go straight from global memory into the MFMA, one 32-channel
-// step ahead of their use.
+// of one position; wavefront = 32 x 32 = 2 x 2 MFMA tiles with three accumulators each
+// (the digit pairs) plus the digit sums of its two tile blocks and two channel blocks.
+// Operands go straight from global memory into the MFMA, one 64-channel step ahead.
 __global__ __launch_bounds__(256) void gemm_w16_kernel(int Tp, int Kp, int Cp,
-                                                       const _Float16* __restrict__ V,
-                                                       const _Float16* __restrict__ U,
+                                                       const int8_t* __restrict__ V,
+                                                       const int8_t* __restrict__ U,
                                                        long long* __restrict__ Mo) {
   const int p = blockIdx.z, tb = blockIdx.x * 64, kb = blockIdx.y * 64;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
   const int wave = tid >> 6, wt = wave & 1, wk = wave >> 1;
-  const int nch = Cp >> 5;
-  const half8* ua[2][2];
-  const half8* vb[2][2];
+  const int nch = Cp >> 6;
+  const v4i* ua[2][2];
+  const v4i* vb[2][2];
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
     const int kt = kb + wk * 32 + a * 16;
-    const size_t blk = ((size_t)p * (Kp >> 4) + (kt >> 4)) * (Cp >> 5);
+    const size_t blk = ((size_t)p * (Kp >> 4) + (kt >> 4)) * (Cp >> 6);
 #pragma unroll
-    for (int dg = 0; dg < 2; ++dg) ua[a][dg] = (const half8*)(U + (blk * 2 + dg) * 512) + lane;
+    for (int dg = 0; dg < 2; ++dg) ua[a][dg] = (const v4i*)(U + (blk * 2 + dg) * 1024) + lane;
   }
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     const int t = tb + wt * 32 + b * 16 + r;
 #pragma unroll
     for (int dg = 0; dg < 2; ++dg)
-      vb[b][dg] = (const half8*)(V + v16_index(Tp, Cp, p, dg, t, grp * 8));
+      vb[b][dg] = (const v4i*)(V + v8w_index(Tp, Cp, p, dg, t, grp * 16));
   }
-  // per 32-channel step: U advances by one block pair (2 * 512 halfs = 128 pieces), V by
-  // 32 halfs = 4 pieces
-  half8 A[2][2], B[2][2];
+  // per 64-channel step: U advances by one block pair (2 KB = 128 pieces of 16 bytes), V by
+  // 64 bytes = 4 pieces
+  v4i A[2][2], B[2][2];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -251,14 +262,15 @@ __global__ __launch_bounds__(256) void gemm_w16_kernel(int Tp, int Kp, int Cp,
       A[a][dg] = ua[a][dg][0];
       B[a][dg] = vb[a][dg][0];
     }
-  v4f hh[2][2], hl[2][2], lh[2][2], ll[2][2];
+  const v4i zero = v4i{0, 0, 0, 0}, ones = v4i{kOnes, kOnes, kOnes, kOnes};
+  v4i hh[2][2], mid[2][2], ll[2][2], sv[2][2], su[2][2];       // sv[b][dg], su[a][dg]
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b) hh[a][b] = hl[a][b] = lh[a][b] = ll[a][b] = v4f{0, 0, 0, 0};
+    for (int b = 0; b < 2; ++b) hh[a][b] = mid[a][b] = ll[a][b] = sv[a][b] = su[a][b] = zero;
   for (int ch = 0; ch < nch; ++ch) {
     const int nx = ch + 1 < nch ? ch + 1 : ch;         // (the last step reloads itself)
-    half8 nA[2][2], nB[2][2];
+    v4i nA[2][2], nB[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -270,10 +282,17 @@ __global__ __launch_bounds__(256) void gemm_w16_kernel(int Tp, int Kp, int Cp,
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        hh[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[a][0], B[b][0], hh[a][b], 0, 0, 0);
-        hl[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[a][0], B[b][1], hl[a][b], 0, 0, 0);
-        lh[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[a][1], B[b][0], lh[a][b], 0, 0, 0);
-        ll[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[a][1], B[b][1], ll[a][b], 0, 0, 0);
+        hh[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[a][0], B[b][0], hh[a][b], 0, 0, 0);
+        mid[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[a][0], B[b][1], mid[a][b], 0, 0, 0);
+        mid[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[a][1], B[b][0], mid[a][b], 0, 0, 0);
+        ll[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[a][1], B[b][1], ll[a][b], 0, 0, 0);
+      }
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int dg = 0; dg < 2; ++dg) {
+        sv[x][dg] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, B[x][dg], sv[x][dg], 0, 0, 0);
+        su[x][dg] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[x][dg], ones, su[x][dg], 0, 0, 0);
       }
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -283,7 +302,8 @@ __global__ __launch_bounds__(256) void gemm_w16_kernel(int Tp, int Kp, int Cp,
         B[a][dg] = nB[a][dg];
       }
   }
-  // lane: tile t (column), output channels k0 .. k0 + 3 (rows grp*4 + rr)
+  // lane: tile t (column), output channels k0 .. k0 + 3 (rows grp*4 + rr); the digit sums
+  // of v~ are the same in every row, those of u~ the same in every column
   typedef long long v2ll __attribute__((ext_vector_type(2)));
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -293,9 +313,8 @@ __global__ __launch_bounds__(256) void gemm_w16_kernel(int Tp, int Kp, int Cp,
       long long m[4];
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr)
-        m[rr] = ((long long)(int)hh[a][b][rr] << 16) +
-                (((long long)(int)hl[a][b][rr] + (long long)(int)lh[a][b][rr]) << 8) +
-                (long long)(int)ll[a][b][rr];
+        m[rr] = combine_i64(hh[a][b][rr], mid[a][b][rr], ll[a][b][rr], sv[b][0][rr], sv[b][1][rr],
+                            su[a][0][rr], su[a][1][rr], Cp);
       long long* dst = Mo + ((size_t)p * Tp + t) * Kp + k0;
       *(v2ll*)dst = v2ll{m[0], m[1]};
       *(v2ll*)(dst + 2) = v2ll{m[2], m[3]};
@@ -342,86 +361,84 @@ __global__ __launch_bounds__(256) void output_transform_w16(Geom g, MatAT at,
 // exactly the pinned order: z[a] = fma(A^T[a][i], M[i][j], z[a]) as the accumulators of
 // column j arrive (ascending i), then Y[a][b] = fma(z[a], A^T[b][j], Y[a][b]) once the
 // column is complete (ascending j).  A lane therefore keeps m + m*m floats per channel
-// instead of all n*n accumulators, which leaves room for the three digit-pair accumulators
-// and a ring of operands loaded kDepth steps ahead.  The column loop is a real loop (it
-// bounds how far the compiler may hoist loads); inside it everything is unrolled, so
-// NCH = Cp / 32 is a compile-time constant and the ring slots are static.  At most 512
-// channels, so the two middle digit sums may share an accumulator.  kSparse: entries of
-// A^T that are zero in the Cook-Toom pattern are skipped along i (compile time); along j
-// they are multiplied out (fma(z, 0, Y) == Y).
-// kTG: groups of 16 tiles per workgroup (four wavefronts each).  The groups read the same
-// blocks of U at about the same time, so the second group finds them in the CU's L1 and
-// the stream of U through the L2 -- what bounds this kernel -- is halved.
-template <int M, typename YT, int NCH, bool kSparse, int kTG>
-__global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT at,
-                                                           const half8* __restrict__ V,
-                                                           const half8* __restrict__ U,
+// instead of all n*n accumulators, which leaves room for the seven integer sums of a
+// position and a ring of U operands loaded kDepth steps ahead.  The column loop is a real
+// loop (it bounds how far the compiler may hoist loads); inside it everything is unrolled,
+// so NCH = Cp / 64 is a compile-time constant and the ring slots are static.  kSparse:
+// entries of A^T that are zero in the Cook-Toom pattern are skipped along i (compile
+// time); along j they are multiplied out (fma(z, 0, Y) == Y).
+// V reaches the four wavefronts through LDS: the workgroup loads each position's operands
+// once (16 tiles x Cp channels x 2 planes, 16 bytes per thread and load) instead of once
+// per wavefront -- the L1's access rate, about 44 cycles per 16-byte-per-lane wavefront
+// load, is what bounds such a kernel.  The loads run kPos positions ahead in registers;
+// two LDS buffers alternate, one barrier per position.
+template <int M, typename YT, int NCH, bool kSparse>
+__global__ __launch_bounds__(256) void gemm_out_w16_kernel(Geom g, MatAT at,
+                                                           const int8_t* __restrict__ V,
+                                                           const int8_t* __restrict__ U,
                                                            YT* __restrict__ y, PosScale w,
                                                            float r_m, float r_y, float qmax_m,
                                                            float qmax_y, int fast) {
   constexpr int n = M + 2;
-  constexpr int SJ = n * NCH;                          // steps per column
-  constexpr int kDepth = M == 4 ? (kTG == 1 ? 12 : 6) : 8;       // U ring, in steps
+  constexpr int SJ = n * NCH;                          // steps (64 channels each) per column
+  constexpr int kDepth = SJ % 8 == 0 ? 8 : SJ % 6 == 0 ? 6 : 4;  // U ring, in steps
   static_assert(SJ % kDepth == 0 && kDepth <= SJ, "ring depth must divide a column's steps");
-  // V reaches the four wavefronts of a tile group through LDS: the group loads each
-  // position's operands once (16 tiles x Cp channels x 2 digits = NCH * 2 KB, 16 bytes per
-  // thread and 256 bytes of the row) instead of once per wavefront -- the L1's access
-  // rate, about 44 cycles per 16-byte-per-lane wavefront load, is what bounds this kernel.
-  // The loads run kPos positions ahead in registers; two LDS buffers alternate.
-  constexpr int kLd = NCH / 2;                          // 16-byte loads per thread and position
-  constexpr int kPos = NCH == 2 ? n : NCH == 4 ? n / 2 : NCH == 8 ? 2 : 1;
+  constexpr int kBlocks = NCH * 2;                     // 1 KB operand blocks of V per position
+  constexpr int kLd = (kBlocks + 3) / 4;               // 16-byte loads per thread and position
+  constexpr int kPos = kLd > 1 ? 2 : NCH >= 2 ? n / 2 : n;        // positions ahead
   static_assert(n % kPos == 0 && n % 2 == 0, "position ring and buffer parity must be static");
-  constexpr int kBufPieces = NCH * 128;                 // 16-byte pieces of one position
-  __shared__ v4u vlds[kTG * 2 * kBufPieces];
-  const int lane = threadIdx.x & 63, r = lane & 15, grp = lane >> 4;
-  const int wave_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wave = wave_id & 3;                        // block of 16 output channels
-  const int group = wave_id >> 2;                      // tile group of the workgroup
-  const int tb = (blockIdx.x * kTG + group) * 16, kb = blockIdx.y * 64;
+  constexpr int kBufPieces = kBlocks * 64;             // 16-byte pieces of one position
+  __shared__ v4u vlds[2 * kBufPieces];
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tb = blockIdx.x * 16, kb = blockIdx.y * 64;
   const int t = tb + r;
-  const int tidg = threadIdx.x & 255;                  // thread of the tile group
   // Addresses = uniform byte offset (position, channel step: scalar registers, recomputed
   // per load and hidden from the optimiser, which would otherwise keep one 64-bit vector
   // pointer per load site of the unrolled column) + one 32-bit per-lane offset per tensor.
-  // U: block pair of (position, 16 channels k, 32 channels c) = 2 KB, digit planes 1 KB
+  // U: block pair of (position, 16 channels k, 64 channels c) = 2 KB, the planes 1 KB
   // apart, the lane's piece at lane * 16.
   const char* Ub = (const char*)U;
   const char* Vb = (const char*)V;
   const size_t ublock = (size_t)((kb + wave * 16) >> 4) * NCH * 2048;
   const size_t ustep_p = (size_t)(g.Kp >> 4) * NCH * 2048;
-  const size_t vplane = (size_t)g.Tp * g.Cp * 2;       // bytes of one digit plane of a position
+  const size_t vplane = (size_t)g.Tp * g.Cp;           // bytes of one digit plane of a position
   const uint32_t ulane = (uint32_t)lane * 16u;
-  // V piece e = tidg + 256 k of a position, in operand order [channel step][digit][tile
-  // row][8 channels]: e & 3 = piece of the row, (e >> 2) & 15 = tile, (e >> 6) & 1 = digit,
-  // e >> 7 = channel step (its low bit from the thread, the rest from k)
-  const uint32_t vthr = (uint32_t)((tidg >> 6) & 1) * (uint32_t)vplane +
-                        (uint32_t)(tb + ((tidg >> 2) & 15)) * (uint32_t)(g.Cp * 2) +
-                        (uint32_t)(tidg >> 7) * 64u + (uint32_t)(tidg & 3) * 16u;
-  v4u* vbuf = vlds + group * 2 * kBufPieces;
+  // V piece e = tid + 256 k of a position, in operand order [channel step][plane][tile
+  // row][16 bytes]: e & 3 = piece of the 64-byte row, (e >> 2) & 15 = tile, e >> 6 =
+  // channel step * 2 + plane (wave + 4 k: the plane and the low bit of the step come from
+  // the wavefront, the rest of the step from k)
+  const uint32_t vthr = (uint32_t)(wave & 1) * (uint32_t)vplane +
+                        (uint32_t)(tb + ((tid >> 2) & 15)) * (uint32_t)g.Cp +
+                        (uint32_t)(wave >> 1) * 64u + (uint32_t)(tid & 3) * 16u;
 
-  half8 ruh[kDepth], rul[kDepth];
+  v4i rua[kDepth], rub[kDepth];
   v4u vst[kPos][kLd];
   // step sj of column j: position p = (sj / NCH) * n + j, channel step sj % NCH
   auto fetch = [&](int sj, int j, int slot) {
     const int p = (sj / NCH) * n + j, ch = sj % NCH;
     size_t uo = ublock + (size_t)p * ustep_p + (size_t)ch * 2048;
     asm volatile("" : "+s"(uo));
-    ruh[slot] = *(const half8*)(Ub + uo + ulane);
-    rul[slot] = *(const half8*)(Ub + uo + 1024 + ulane);
+    rua[slot] = *(const v4i*)(Ub + uo + ulane);
+    rub[slot] = *(const v4i*)(Ub + uo + 1024 + ulane);
   };
-  // the group's share of position (i, j) into ring slot `slot`
+  // the workgroup's share of position (i, j) into ring slot `slot` (wavefronts beyond the
+  // last operand block of a short reduction load nothing)
   auto vfetch = [&](int i, int j, int slot) {
     const int p = i * n + j;
 #pragma unroll
     for (int k = 0; k < kLd; ++k) {
-      size_t vo = (size_t)(2 * p) * vplane + (size_t)k * 128;
-      asm volatile("" : "+s"(vo));
-      vst[slot][k] = *(const v4u*)(Vb + vo + vthr);
+      if (wave + 4 * k < kBlocks) {
+        size_t vo = (size_t)(2 * p) * vplane + (size_t)k * 128;
+        asm volatile("" : "+s"(vo));
+        vst[slot][k] = *(const v4u*)(Vb + vo + vthr);
+      }
     }
   };
   auto vstore = [&](int slot, int buf) {
 #pragma unroll
-    for (int k = 0; k < kLd; ++k) vbuf[buf * kBufPieces + tidg + 256 * k] = vst[slot][k];
+    for (int k = 0; k < kLd; ++k)
+      if (wave + 4 * k < kBlocks) vlds[buf * kBufPieces + tid + 256 * k] = vst[slot][k];
   };
   // position 0 straight into buffer 0, positions 1 .. kPos into the ring (position x in
   // slot x % kPos), the first kDepth steps of U into theirs
@@ -439,6 +456,8 @@ __global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT a
     for (int b = 0; b < M; ++b)
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) Y[a][b][rr] = 0.0f;
+  const v4i zero = v4i{0, 0, 0, 0}, ones = v4i{kOnes, kOnes, kOnes, kOnes};
+  const int cbias = 16384 * g.Cp;
 
   // (one copy of the loop per setting of the Hadamard-stage quantizer: a test per
   // accumulator would cut the loop body into pieces the scheduler cannot overlap)
@@ -446,8 +465,7 @@ __global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT a
     constexpr bool kMQ = decltype(mq_tag)::value;
 #pragma unroll 1
     for (int j = 0; j < n; ++j) {
-      // (the last column prefetches the steps of column n - 1 again instead of branching
-      // around the loads)
+      // (columns past the last: the loads repeat valid addresses, their data is never used)
       const int jn = j + 1 < n ? j + 1 : j, jnn = j + 2 < n ? j + 2 : n - 1;
 #pragma unroll
       for (int i = 0; i < n; ++i) {
@@ -455,23 +473,25 @@ __global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT a
         // position's operands may now overwrite; this position's buffer is complete.
         __syncthreads();
         vstore((i + 1) % kPos, (i + 1) & 1);
-        // position kPos + 1 ahead: in this column, the next one or the one after
-        // (columns past the last: any valid address, the data is never used)
         constexpr int kAhead = 1 + kPos;
         static_assert(kAhead <= n + 1, "at most two columns ahead");
         vfetch((i + kAhead) % n, (i + kAhead) / n == 0 ? j : (i + kAhead) / n == 1 ? jn : jnn,
                (i + 1) % kPos);
-        const half8* vops = (const half8*)(vbuf + (i & 1) * kBufPieces) + (r * 4 + grp);
-        v4f hh = v4f{0, 0, 0, 0}, mid = hh, ll = hh;
+        const v4i* vops = (const v4i*)(vlds + (i & 1) * kBufPieces) + (r * 4 + grp);
+        v4i hh = zero, mid = zero, ll = zero, sva = zero, svb = zero, sua = zero, sub = zero;
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
           const int sj = i * NCH + ch, slot = sj % kDepth;
-          const half8 uh = ruh[slot], ul = rul[slot];
-          const half8 vh = vops[(ch * 2) * 64], vl = vops[(ch * 2 + 1) * 64];
-          hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vh, hh, 0, 0, 0);
-          mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(uh, vl, mid, 0, 0, 0);
-          mid = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vh, mid, 0, 0, 0);
-          ll = __builtin_amdgcn_mfma_f32_16x16x32_f16(ul, vl, ll, 0, 0, 0);
+          const v4i ua = rua[slot], ub = rub[slot];
+          const v4i va = vops[(ch * 2) * 64], vb = vops[(ch * 2 + 1) * 64];
+          hh = __builtin_amdgcn_mfma_i32_16x16x64_i8(ua, va, hh, 0, 0, 0);
+          mid = __builtin_amdgcn_mfma_i32_16x16x64_i8(ua, vb, mid, 0, 0, 0);
+          mid = __builtin_amdgcn_mfma_i32_16x16x64_i8(ub, va, mid, 0, 0, 0);
+          ll = __builtin_amdgcn_mfma_i32_16x16x64_i8(ub, vb, ll, 0, 0, 0);
+          sva = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, va, sva, 0, 0, 0);
+          svb = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, vb, svb, 0, 0, 0);
+          sua = __builtin_amdgcn_mfma_i32_16x16x64_i8(ua, ones, sua, 0, 0, 0);
+          sub = __builtin_amdgcn_mfma_i32_16x16x64_i8(ub, ones, sub, 0, 0, 0);
           // refill the slot once its operands have been issued (the loads may then land in
           // the same registers); the compiler-level fence keeps later steps' loads behind
           // this one, so that the ring, not the scheduler, decides what is in flight
@@ -482,9 +502,13 @@ __global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT a
         const float wp = w.r[i * n + j];               // 1 with per-tensor scales: exact
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-          // exact in fp64 (below 2^53), one rounding to fp32: the conversion of the integer M
+          // M = 2^16 hh + 2^8 (mid + 128 (sva + sua)) + (ll + 128 (svb + sub) + 16384 Cp):
+          // the brackets fit int32 (|.| <= 2^16 Cp), the sum is exact in fp64 (below
+          // 2^53), and one rounding to fp32 is the conversion of the integer M
+          const int m1 = mid[rr] + (sva[rr] + sua[rr]) * 128;
+          const int m0 = ll[rr] + (svb[rr] + sub[rr]) * 128 + cbias;
           const double dm = __builtin_fma((double)hh[rr], 65536.0,
-                                          __builtin_fma((double)mid[rr], 256.0, (double)ll[rr]));
+                                          __builtin_fma((double)m1, 256.0, (double)m0));
           float f = (float)dm * wp;
           if constexpr (kMQ) f = quantize_f(f, r_m, qmax_m);
 #pragma unroll
@@ -524,21 +548,21 @@ __global__ __launch_bounds__(256 * kTG) void gemm_out_w16_kernel(Geom g, MatAT a
 }
 
 // Taps: canonical dense order, int16 codes (U, V) or the int64 accumulators (M).
-__global__ __launch_bounds__(256) void export_u_w16(const _Float16* __restrict__ U,
+__global__ __launch_bounds__(256) void export_u_w16(const int8_t* __restrict__ U,
                                                     int16_t* __restrict__ out, Geom g) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= (size_t)g.P * g.K * g.C) return;
   const int c = (int)(i % g.C), k = (int)((i / g.C) % g.K), p = (int)(i / ((size_t)g.C * g.K));
-  out[i] = (int16_t)join_code(U[u16_index(g.Kp, g.Cp, p, 0, k, c)],
-                              U[u16_index(g.Kp, g.Cp, p, 1, k, c)]);
+  out[i] = (int16_t)join_code(U[u8w_index(g.Kp, g.Cp, p, 0, k, c)],
+                              U[u8w_index(g.Kp, g.Cp, p, 1, k, c)]);
 }
-__global__ __launch_bounds__(256) void export_v_w16(const _Float16* __restrict__ V,
+__global__ __launch_bounds__(256) void export_v_w16(const int8_t* __restrict__ V,
                                                     int16_t* __restrict__ out, Geom g) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= (size_t)g.P * g.T * g.C) return;
   const int c = (int)(i % g.C), t = (int)((i / g.C) % g.T), p = (int)(i / ((size_t)g.C * g.T));
-  out[i] = (int16_t)join_code(V[v16_index(g.Tp, g.Cp, p, 0, t, c)],
-                              V[v16_index(g.Tp, g.Cp, p, 1, t, c)]);
+  out[i] = (int16_t)join_code(V[v8w_index(g.Tp, g.Cp, p, 0, t, c)],
+                              V[v8w_index(g.Tp, g.Cp, p, 1, t, c)]);
 }
 __global__ __launch_bounds__(256) void export_m_w16(const long long* __restrict__ Mi,
                                                     long long* __restrict__ out, Geom g) {
@@ -554,7 +578,7 @@ hipError_t input_m(const Geom& g, const MatBT& bt, const void* x, void* V, const
   dim3 grid(g.Tp / 8, g.Cp / 32);
   const bool sparse = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt);
   const bool row = g.W >= 8;
-  _Float16* Vh = (_Float16*)V;
+  int8_t* Vh = (int8_t*)V;
 #define WINO_W16_IN(XT, SP, RW) \
   input_transform_w16<M, XT, SP, RW><<<grid, 256, 0, s>>>(g, bt, (const XT*)x, Vh, rv, qmax)
 #define WINO_W16_IN2(XT, SP) do { if (row) WINO_W16_IN(XT, SP, true); else WINO_W16_IN(XT, SP, false); } while (0)
@@ -600,7 +624,7 @@ hipError_t output_m(const Geom& g, const MatAT& at, const void* Mi, void* y, con
 hipError_t launch_w16_weights(const Geom& g, const MatG& mg, const float* w, void* U,
                               const PosScale& ru, float qmax, hipStream_t s) {
   const unsigned nb = (unsigned)(((size_t)g.Kp * g.Cp + 255) / 256);
-  _Float16* Uh = (_Float16*)U;
+  int8_t* Uh = (int8_t*)U;
   switch (g.m) {
     case 2: weight_transform_w16<2><<<nb, 256, 0, s>>>(g, mg, w, Uh, ru, qmax); break;
     case 4: weight_transform_w16<4><<<nb, 256, 0, s>>>(g, mg, w, Uh, ru, qmax); break;
@@ -621,7 +645,7 @@ hipError_t launch_w16_input(const Geom& g, const MatBT& bt, const void* x, void*
 hipError_t launch_w16_gemm(const Geom& g, const void* V, const void* U, void* M, hipStream_t s) {
   if (g.Kp / 64 > 65535 || g.Cp > 1024) return hipErrorInvalidValue;
   dim3 grid(g.Tp / 64, g.Kp / 64, g.P);
-  gemm_w16_kernel<<<grid, 256, 0, s>>>(g.Tp, g.Kp, g.Cp, (const _Float16*)V, (const _Float16*)U,
+  gemm_w16_kernel<<<grid, 256, 0, s>>>(g.Tp, g.Kp, g.Cp, (const int8_t*)V, (const int8_t*)U,
                                        (long long*)M);
   return hipGetLastError();
 }
@@ -642,16 +666,10 @@ hipError_t launch_w16_output(const Geom& g, const MatAT& at, const void* M, void
 bool w16_gemm_out_supported(const Geom& g, const MatAT&) {
   const bool nch_ok = g.Cp == 64 || g.Cp == 128 || g.Cp == 256 || g.Cp == 512;
   // (the per-thread part of a V address, up to two digit planes, must fit 32 bits)
-  return nch_ok && g.Kp / 64 <= 65535 && (size_t)g.Tp * g.Cp * 4 < 0xffffffffull;
+  return nch_ok && g.Kp / 64 <= 65535 && (size_t)g.Tp * g.Cp * 2 < 0xffffffffull;
 }
 
 namespace {
-// Two tile groups per workgroup pay (about 12 % on 64-channel layers of 16 k tiles) once
-// that still leaves two workgroups for every CU; not for m = 6, whose ring would shrink
-// to two steps.
-inline bool w16_two_groups(const Geom& g) {
-  return g.m != 6 && g.Cp <= 256 && (long long)(g.Tp / 32) * (g.Kp / 64) >= 512;
-}
 template <int M, typename YT, bool kSparse>
 hipError_t gemm_out_mys(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                         const PosScale* w, float r_m, float r_y, float qmax_m, float qmax_y,
@@ -659,30 +677,19 @@ hipError_t gemm_out_mys(const Geom& g, const MatAT& at, const void* V, const voi
   PosScale one;
   for (int p = 0; p < 64; ++p) one.r[p] = 1.0f;
   const PosScale& ws = w ? *w : one;
-  const half8* Vh = (const half8*)V;
-  const half8* Uh = (const half8*)U;
+  const int8_t* Vi = (const int8_t*)V;
+  const int8_t* Ui = (const int8_t*)U;
   YT* yo = (YT*)y;
   const int fast = g.Ho % M == 0 && g.Wo % M == 0 && ((uintptr_t)y & 7) == 0;
-  // (Tp is a multiple of 64, so of 32)
-  const bool two = w16_two_groups(g);
-#define WINO_W16_GO(NCHV)                                                                     \
-  do {                                                                                        \
-    if constexpr (M != 6 && NCHV <= 8) { /* (the shapes w16_two_groups can select) */         \
-      if (two) {                                                                              \
-        gemm_out_w16_kernel<M, YT, NCHV, kSparse, 2>                                          \
-            <<<dim3(g.Tp / 32, g.Kp / 64), 512, 0, s>>>(g, at, Vh, Uh, yo, ws, r_m, r_y,      \
-                                                        qmax_m, qmax_y, fast);                \
-        break;                                                                                \
-      }                                                                                       \
-    }                                                                                         \
-    gemm_out_w16_kernel<M, YT, NCHV, kSparse, 1><<<dim3(g.Tp / 16, g.Kp / 64), 256, 0, s>>>(  \
-        g, at, Vh, Uh, yo, ws, r_m, r_y, qmax_m, qmax_y, fast);                               \
-  } while (0)
+  const dim3 grid(g.Tp / 16, g.Kp / 64);
+#define WINO_W16_GO(NCHV)                                                                  \
+  gemm_out_w16_kernel<M, YT, NCHV, kSparse><<<grid, 256, 0, s>>>(g, at, Vi, Ui, yo, ws, r_m, \
+                                                                  r_y, qmax_m, qmax_y, fast)
   switch (g.Cp) {
-    case 64: WINO_W16_GO(2); break;
-    case 128: WINO_W16_GO(4); break;
-    case 256: WINO_W16_GO(8); break;
-    default: WINO_W16_GO(16); break;
+    case 64: WINO_W16_GO(1); break;
+    case 128: WINO_W16_GO(2); break;
+    case 256: WINO_W16_GO(4); break;
+    default: WINO_W16_GO(8); break;
   }
 #undef WINO_W16_GO
   return hipGetLastError();
@@ -714,10 +721,10 @@ hipError_t launch_w16_gemm_out(const Geom& g, const MatAT& at, const void* V, co
 hipError_t launch_w16_export(const Geom& g, int which, const void* src, void* out, hipStream_t s) {
   if (which == WINO_TAP_U) {
     const size_t tot = (size_t)g.P * g.K * g.C;
-    export_u_w16<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const _Float16*)src, (int16_t*)out, g);
+    export_u_w16<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const int8_t*)src, (int16_t*)out, g);
   } else if (which == WINO_TAP_V) {
     const size_t tot = (size_t)g.P * g.T * g.C;
-    export_v_w16<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const _Float16*)src, (int16_t*)out, g);
+    export_v_w16<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const int8_t*)src, (int16_t*)out, g);
   } else {
     const size_t tot = (size_t)g.P * g.T * g.K;
     export_m_w16<<<(unsigned)((tot + 255) / 256), 256, 0, s>>>((const long long*)src, (long long*)out, g);

@@ -195,13 +195,13 @@ def test_per_position_scale_argument_checks(L):
 
 
 def test_wide_mode_sizes_and_argument_checks(L):
-    """The modes with 16-bit codes in the Winograd domain: buffer sizes (two fp16 digit planes
+    """The modes with 16-bit codes in the Winograd domain: buffer sizes (two int8 digit planes
     per code of U and V, int64 M), the channel limit of the exact digit arithmetic, one code
     range per quantizer with the limit of its container -- all checked before any HIP call."""
     d = _desc(N=64, C=64, K=64, H=32, W=32, m=4, dtype=wb.WINO_I16)
-    assert wb.wino_weights_bytes(d) == 36 * 64 * 64 * 4
-    assert wb.wino_workspace_bytes(d) == 36 * 4096 * 64 * 4 + 36 * 4096 * 64 * 8
-    assert wb.wino_workspace_bytes(_desc(C=3, dtype=wb.WINO_I8W16)) == 16 * 64 * 64 * 4 + 16 * 64 * 64 * 8
+    assert wb.wino_weights_bytes(d) == 36 * 64 * 64 * 2
+    assert wb.wino_workspace_bytes(d) == 36 * 4096 * 64 * 2 + 36 * 4096 * 64 * 8
+    assert wb.wino_workspace_bytes(_desc(C=3, dtype=wb.WINO_I8W16)) == 16 * 64 * 64 * 2 + 16 * 64 * 64 * 8
     assert wb.wino_weights_bytes(_desc(C=1024, dtype=wb.WINO_I16)) > 0
     assert wb.wino_weights_bytes(_desc(C=1025, dtype=wb.WINO_I16)) == 0
     assert _fwd(L, _desc(C=1025, dtype=wb.WINO_I8W16), wb.make_quant(1, 1, 1, 1)) == -3
