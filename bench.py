@@ -64,7 +64,7 @@ def algorithmic(L, BT, AT):
     nzb, nza = int(np.count_nonzero(BT)), int(np.count_nonzero(AT))
     x_b, y_b = L.N * L.C * L.H * L.W * e, L.N * L.K * L.Ho * L.Wo * e
     v_b, u_b, m_b = P * T * L.C * ew, P * L.C * L.K * ew, (8 if wide else 4) * P * T * L.K
-    # wide modes: a 16-bit product is four fp16 digit products on the matrix cores
+    # wide modes: a 16-bit product is four int8 digit products on the matrix cores
     mm = 2 * P * T * L.C * L.K * (4 if wide else 1)
     alu_in = T * L.C * (2 * 2 * n * nzb + qops * P)
     alu_out = T * L.K * (2 * (n + L.m) * nza + (P if quantized else 0) + qops * L.m * L.m)
@@ -84,7 +84,7 @@ def algorithmic(L, BT, AT):
 def roofline_entry(name, alg, us, dtype, traffic):
     """The bound is whichever of HBM, MFMA and vector-ALU peak needs the longest time
     for the kernel's algorithmic bytes / GEMM operations / transform operations."""
-    mf = MFMA_PEAK["int8" if dtype == "i8" else "f16" if dtype in WIDE else "f32"]
+    mf = MFMA_PEAK["int8" if dtype == "i8" or dtype in WIDE else "f32"]
     t = {"hbm": alg["bytes"] / (HBM_PEAK_GBS * 1e9), "mfma": alg["ops"] / (mf * 1e12),
          "alu": alg["alu"] / (ALU_PEAK_TFLOPS * 1e12)}
     bound = max(t, key=t.get)
