@@ -35,7 +35,8 @@ wino_status make_geom(const wino_desc* d, Geom* g) {
   g->i8 = d->dtype == WINO_I8;
   g->w16 = d->dtype == WINO_I16 || d->dtype == WINO_I8W16;
   g->x16 = d->dtype == WINO_I16;
-  // (wide modes: partial sums of the digit products stay exact in fp32 up to 1024 channels)
+  // (wide modes: the int32 sums of digit products and their recombination are sized for
+  // reductions of at most 1024 channels)
   if (g->w16 && d->C > 1024) return WINO_E_BAD_SHAPE;
   const long long T = (long long)d->N * g->TH * g->TW;
   const long long limit = 0x7fffffffLL;

@@ -113,7 +113,7 @@ hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& a
 hipError_t launch_export(const Geom& g, int which, const void* src, void* out, hipStream_t s);
 
 // The path with up to 16-bit codes after every stage (g.w16): weight stage, input stage,
-// exact int64 GEMM on fp16 digit planes, output stage; layouts private to these kernels.
+// exact int64 GEMM on int8 digit planes, output stage; layouts private to these kernels.
 hipError_t launch_w16_weights(const Geom& g, const MatG& mg, const float* w, void* U,
                               const PosScale& ru, float qmax, hipStream_t s);
 hipError_t launch_w16_input(const Geom& g, const MatBT& bt, const void* x, void* V,

@@ -134,7 +134,7 @@ def test_wide_stages_per_position_scales(oracle, layer, qm):
 
 def test_every_code_saturated_over_1024_channels(oracle):
     """The worst case of the digit arithmetic: all codes at +-32767 (digits +-128, -+1) and
-    the longest supported reduction, where the partial sums reach 2^24 exactly."""
+    the longest supported reduction, where the sums of digit products reach 2^24."""
     layer = Layer("w_sat", 1, 1024, 16, 4, 4, m=2, seed=308)
     case = make_case(oracle, layer, with_oracle=False)
     sc = dict(s_x=1.0, s_v=1e-6, s_u=1e-9, s_y=1.0, s_m=0.0)
