@@ -170,7 +170,7 @@ bool fused_fwd_supported(const Geom& g) {
   // int8, F2 or F4 (F6 needs 256 accumulator registers per lane on top of the input
   // transform's working set), and few enough output-channel blocks that repeating the
   // input transform per block stays cheaper than a round trip of V through memory.
-  return g.i8 && (g.m == 2 || g.m == 4) && g.Kp <= 128 && g.W >= 8;
+  return g.i8 && (g.m == 2 || g.m == 4) && g.Kp <= 128;
 }
 
 hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,

@@ -651,16 +651,18 @@ bool input_exact_supported(const Geom& g, const MatBT& bt) {
          (unsigned long long)g.Tp * g.Cp < 0x100000000ull && exact_input_shift(g, bt) >= 0;
 }
 
+// Images narrower than a dword (W < 4) are staged byte by byte, which exists for the
+// two-tile workgroup shape only (W < 4 and pad <= 1 give at most two tiles per row).
+static bool narrow_ok(const Geom& g) { return g.W >= 4 || g.TW <= 2; }
+
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
-  // (W < 4 would need byte-wise staging: such images take the unfused path)
-  return g.Kp <= 128 && g.W >= 4 && input_exact_supported(g, bt);
+  return g.Kp <= 128 && narrow_ok(g) && input_exact_supported(g, bt);
 }
 
-// As a stand-alone input stage: wherever the staging can load dwords (W >= 4); only
-// narrower images go to the vector-ALU kernel.
+// As a stand-alone input stage: wherever the matrix B^T allows it.
 bool input_exact_preferred(const Geom& g, const MatBT& bt, const void* x) {
   (void)x;
-  return g.W >= 4 && input_exact_supported(g, bt);
+  return narrow_ok(g) && input_exact_supported(g, bt);
 }
 
 namespace {
@@ -750,11 +752,13 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
 #define WINO_LAUNCH_IN(LOAD, TWBC)                                                         \
   input_transform_exact_kernel<M, LOAD, TWBC><<<grid, 256, xl.lds_bytes, s>>>(               \
       xi, Vi, rvs, qmax, g, xl.pl, xl.kw)
-  if (xl.load < 1) return hipErrorInvalidValue;          // see input_exact_preferred
 #define WINO_LAUNCH_IN2(TWBC) \
   do { if (xl.load == 3) WINO_LAUNCH_IN(3, TWBC); else if (xl.load == 2) WINO_LAUNCH_IN(2, TWBC); \
        else WINO_LAUNCH_IN(1, TWBC); } while (0)
-  if (TWB == 16) WINO_LAUNCH_IN2(16);
+  if (xl.load == 0) {                                    // byte-wise staging: see narrow_ok
+    if (TWB != 2) return hipErrorInvalidValue;
+    WINO_LAUNCH_IN(0, 2);
+  } else if (TWB == 16) WINO_LAUNCH_IN2(16);
   else if (TWB == 8) WINO_LAUNCH_IN2(8);
   else if (TWB == 4) WINO_LAUNCH_IN2(4);
   else WINO_LAUNCH_IN2(2);
@@ -848,8 +852,17 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   do { if (mq) WINO_LAUNCH_G1(SA, LOAD, true); else WINO_LAUNCH_G1(SA, LOAD, false); } while (0)
 #define WINO_LAUNCH_G3(SA)                                                                 \
   do { if (load >= 2) WINO_LAUNCH_G2(SA, 2); else WINO_LAUNCH_G2(SA, 1); } while (0)
-  if (load == 0) return hipErrorInvalidValue;            // W < 4: see fused_fwd_exact_supported
-  if (sa) WINO_LAUNCH_G3(true); else WINO_LAUNCH_G3(false);
+  // (byte-wise staging, W < 4: the dense-A^T variants serve every A^T; the two-tile shape
+  // at compile time, so that the staging issues no loads for channel quads beyond 16)
+  if (load == 0) {
+    if (TWB != 2) return hipErrorInvalidValue;
+    if (mq) { if (one) WINO_LAUNCH_XK(false, 0, true, true, 2, false);
+              else WINO_LAUNCH_XK(false, 0, true, false, 2, false); }
+    else    { if (one) WINO_LAUNCH_XK(false, 0, false, true, 2, false);
+              else WINO_LAUNCH_XK(false, 0, false, false, 2, false); }
+  }
+  else if (sa) WINO_LAUNCH_G3(true);
+  else WINO_LAUNCH_G3(false);
 #undef WINO_LAUNCH_G3
 #undef WINO_LAUNCH_G2
 #undef WINO_LAUNCH_G1

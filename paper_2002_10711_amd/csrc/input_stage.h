@@ -39,12 +39,16 @@ __host__ __device__ inline int stage_dwords(int RB, int TWB) {
 struct __attribute__((packed)) UnalignedU32 { uint32_t v; };   // dword at any byte address
 
 __device__ __forceinline__ uint32_t load_quad_guarded(const int8_t* row, int w, int W) {
-  // four pixels of one channel row starting at column w; zero outside [0, W)
+  // four pixels of one channel row starting at column w; zero outside [0, W).  Branch-free:
+  // every byte is loaded from a column clamped into the row and masked afterwards, so all
+  // loads of a batch are in flight together.  `row` must point at a row that exists.
   uint32_t v = 0;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int ww = w + e;
-    if (ww >= 0 && ww < W) v |= (uint32_t)(uint8_t)row[ww] << (8 * e);
+    const int wc = ww < 0 ? 0 : (ww >= W ? W - 1 : ww);
+    const uint32_t b = (uint32_t)(uint8_t)row[wc];
+    v |= (b & (0u - (uint32_t)(ww == wc))) << (8 * e);
   }
   return v;
 }

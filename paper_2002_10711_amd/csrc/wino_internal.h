@@ -88,7 +88,7 @@ hipError_t launch_gemm_out_col(const Geom& g, const MatAT& at, const void* V, co
 bool fused_fwd_supported(const Geom& g);
 // ... and worth it with the vector-ALU input transform, which a second block of output
 // channels would have to repeat in full.
-inline bool fused_fwd_generic_preferred(const Geom& g) { return g.Kp <= 64; }
+inline bool fused_fwd_generic_preferred(const Geom& g) { return g.Kp <= 64 && g.W >= 8; }
 hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                             const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
                             hipStream_t s);

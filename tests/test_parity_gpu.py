@@ -83,6 +83,13 @@ SMALL = [
     Layer("s_f2_c512_k70_5px", 3, 512, 70, 5, 5, m=2, seed=153),
     Layer("s_f6_c128_k96_13px", 2, 128, 96, 13, 13, m=6, seed=154),
     Layer("s_f4_c450_k130_12px", 1, 450, 130, 12, 12, m=4, seed=155),   # 512 padded: tiled GEMM
+    # images narrower than a dword: byte-wise staging in the one-kernel forward
+    Layer("s_f2_2px", 33, 64, 64, 2, 2, m=2, seed=156),
+    Layer("s_f4_2px_c70_k100", 9, 70, 100, 2, 2, m=4, seed=157),
+    Layer("s_f2_3px_k128", 5, 128, 128, 3, 3, m=2, seed=158),
+    Layer("s_f4_1px_wide", 3, 20, 40, 9, 1, m=4, seed=159),             # a single column
+    Layer("s_f2_3px_k300", 4, 64, 300, 6, 3, m=2, seed=160),            # narrow, unfused
+    Layer("s_f6_2px", 6, 64, 64, 2, 2, m=6, seed=161),
 ]
 
 
