@@ -213,17 +213,34 @@ hipError_t launch_ms(const Geom& g, const MatAT& at, const void* V, const void* 
   const int8_t* Ui = (const int8_t*)U;
   int8_t* yo = (int8_t*)y;
   const int fast = g.Ho % M == 0 && g.Wo % M == 0 && ((uintptr_t)y & 3) == 0;
-  // (kTW = 2, two tile blocks per wavefront, measured no faster on layers of up to 4 k
-  // tiles and is not instantiated)
+  // Two tile blocks per wavefront halve the operand loads of U per MFMA and the number of
+  // workgroups: measured faster only where the layer has many tiles and U is what the L1
+  // is busy with (F2 at 256 channels from 8 k tiles, F4 at 512 channels from 2 k tiles).
 #define WINO_COL_GO(NCHV)                                                                \
   gemm_out_col_kernel<M, NCHV, kSparse, 1><<<dim3(g.Tp / 16, g.Kp / 64), 256, 0, s>>>(   \
       g, at, Vi, Ui, yo, ws, r_m, r_y, qmax, fast)
+#define WINO_COL_GO2(NCHV)                                                               \
+  gemm_out_col_kernel<M, NCHV, kSparse, 2><<<dim3(g.Tp / 32, g.Kp / 64), 256, 0, s>>>(   \
+      g, at, Vi, Ui, yo, ws, r_m, r_y, qmax, fast)
+  if constexpr (M == 2) {
+    if (g.Cp == 256 && g.T >= 8192) {
+      WINO_COL_GO2(4);
+      return hipGetLastError();
+    }
+  }
+  if constexpr (M == 4) {
+    if (g.Cp == 512 && g.T >= 2048) {
+      WINO_COL_GO2(8);
+      return hipGetLastError();
+    }
+  }
   switch (g.Cp) {
     case 64: WINO_COL_GO(1); break;
     case 128: WINO_COL_GO(2); break;
     case 256: WINO_COL_GO(4); break;
     default: WINO_COL_GO(8); break;
   }
+#undef WINO_COL_GO2
 #undef WINO_COL_GO
   return hipGetLastError();
 }

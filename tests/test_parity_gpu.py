@@ -90,6 +90,10 @@ SMALL = [
     Layer("s_f4_1px_wide", 3, 20, 40, 9, 1, m=4, seed=159),             # a single column
     Layer("s_f2_3px_k300", 4, 64, 300, 6, 3, m=2, seed=160),            # narrow, unfused
     Layer("s_f6_2px", 6, 64, 64, 2, 2, m=6, seed=161),
+    # many tiles and long reductions: two tile blocks per wavefront in the GEMM + output kernel
+    Layer("s_f2_c200_k40_8649tiles", 9, 200, 40, 62, 62, m=2, seed=162),
+    Layer("s_f4_c450_k40_2048tiles", 2, 450, 40, 126, 126, m=4, seed=163),
+    Layer("s_f4_c500_k70_600tiles", 6, 500, 70, 38, 40, m=4, seed=164),   # F4, 512 channels, one block
 ]
 
 
