@@ -656,7 +656,8 @@ bool input_exact_supported(const Geom& g, const MatBT& bt) {
 static bool narrow_ok(const Geom& g) { return g.W >= 4 || g.TW <= 2; }
 
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
-  return g.Kp <= 128 && narrow_ok(g) && input_exact_supported(g, bt);
+  // (byte-wise staging is slow enough that only a single channel block is worth fusing)
+  return g.Kp <= 128 && narrow_ok(g) && (g.W >= 4 || g.Cp == 64) && input_exact_supported(g, bt);
 }
 
 // As a stand-alone input stage: wherever the matrix B^T allows it.
