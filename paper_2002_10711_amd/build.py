@@ -30,7 +30,8 @@ FLAGS = [
 # accumulators are consumed by VALU code right away, and the AGPR form costs an extra
 # v_accvgpr_read / v_accvgpr_write per value.
 EXTRA_FLAGS = {
-    "fused_fwd_exact.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "fused_fwd_exact_m2.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "fused_fwd_exact_m4.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "fused_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "wide16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "gemm_out_col.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],

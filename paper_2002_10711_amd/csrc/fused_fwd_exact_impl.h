@@ -29,15 +29,20 @@
 //      windows as the "A" operand so that a lane receives four consecutive channels
 //      of one position: quantize, pack into a dword, store into Vl[p][tile][channel];
 //   4. barrier; wave w: one MFMA per position against U[p][16 k of w][64 c].
+#pragma once
 #include <string.h>
+
+#ifndef WINO_EXACT_M
+#error "define WINO_EXACT_M (2 or 4): the tile size this translation unit instantiates"
+#endif
 
 #include "fastdiv.h"
 #include "input_stage.h"
 #include "output_stage.h"
 
-// Development aid, compiled only with -DWINO_PROFILE_PHASES: every wavefront records the
-// shader clock at its phase boundaries; wino_debug_read_phases() copies them out.
-#ifdef WINO_PROFILE_PHASES
+// Development aid, compiled only with -DWINO_PROFILE_PHASES (F4 kernels): every wavefront
+// records the shader clock at its phase boundaries; wino_debug_read_phases() copies them out.
+#if defined(WINO_PROFILE_PHASES) && WINO_EXACT_M == 4
 __device__ unsigned long long wino_phase_ts[4096 * 16];
 #define WINO_TS(slot)                                                                     \
   if ((threadIdx.x & 63) == 0 && blockIdx.y == 0 && blockIdx.x < 1024)                      \
@@ -74,6 +79,12 @@ constexpr int kVlPitch = 16 * 16 + 4;
 // (j, l) = (2*(lane/16) + b/8, b%8), b = 0..15, of row p = blk*16 + lane%16 (zero for
 // p >= 36 and for j, l >= 6).
 struct KronW { uint32_t v[3 * 64 * 4]; };
+
+// Per-position factors of the two quantizer sites of the fused kernels (n*n <= 36
+// positions): rv[p] multiplies the transformed input before rounding (every entry the
+// per-tensor factor when there is one scale), w[p] brings accumulator p to real units
+// (used only with per-position scales).
+struct PosPair { float rv[36]; float w[36]; };
 
 struct __attribute__((packed, aligned(4))) U64A4 { uint32_t lo, hi; };   // 8 bytes, dword aligned
 
@@ -244,10 +255,11 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
 // first per-position MFMA (zero "C" operand) instead of occupying 144 registers during
 // staging and transform.
 // kFast: whole tiles, K % 4 == 0 (see output_stage.h).
-template <int M, bool kSparseA, int kLoad, bool kMQ, bool kOneBlock, int kTWB, bool kFast>
+template <int M, bool kSparseA, int kLoad, bool kOneBlock, int kTWB, bool kFast>
 __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
-    const int8_t* __restrict__ x, const int8_t* __restrict__ U, void* __restrict__ y, float r_vs,
-    float r_m, float r_y, float qmax, Geom g, XPlan pl, MatAT at, KronW kw) {
+    const int8_t* __restrict__ x, const int8_t* __restrict__ U, void* __restrict__ y, int pos,
+    float r_vs, float r_m, float r_y, float qmax, Geom g, XPlan pl, MatAT at, KronW kw,
+    PosPair pp) {
   // (pointers and scalars first: they sit next to the geometry in the argument block,
   // so one batch of scalar loads at kernel start brings in everything staging needs)
   constexpr int n = M + 2, P = n * n;
@@ -275,6 +287,15 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
   if constexpr (!kOneBlock) {
 #pragma unroll
     for (int p = 0; p < P; ++p) acc[p] = v4i{0, 0, 0, 0};
+  }
+
+  // quantizer factor of the positions this lane produces in the transform (p = blk*16 + r)
+  float rq[NBLK];
+#pragma unroll
+  for (int blk = 0; blk < NBLK; ++blk) rq[blk] = r_vs;
+  if (pos) {
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) rq[blk] = pp.rv[blk * 16 + r < P ? blk * 16 + r : P - 1];
   }
 
   const int nblk = kOneBlock ? 1 : (g.Cp >> 6);
@@ -347,10 +368,10 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
         nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
                                                     v4i{0, 0, 0, 0}, 0, 0, 0);
       // four codes into one dword with three byte permutes
-      const uint32_t packed = pack_codes(quantize_bits((float)cur[0], r_vs, lo, hi),
-                                         quantize_bits((float)cur[1], r_vs, lo, hi),
-                                         quantize_bits((float)cur[2], r_vs, lo, hi),
-                                         quantize_bits((float)cur[3], r_vs, lo, hi));
+      const uint32_t packed = pack_codes(quantize_bits((float)cur[0], rq[blk], lo, hi),
+                                         quantize_bits((float)cur[1], rq[blk], lo, hi),
+                                         quantize_bits((float)cur[2], rq[blk], lo, hi),
+                                         quantize_bits((float)cur[3], rq[blk], lo, hi));
       const int tl = wave * 4 + (gi >> 2);
       if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
       cur = nxt;
@@ -377,7 +398,8 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
   // per-channel guard inside finish_lane is compiled out when kFast)
   if (rs < RB && rr_ < R && tw < g.TW && k0 < g.K) {
     const int img = (int)fast_div(rr_, pl.inv_th), th = rr_ - img * g.TH;
-    finish_lane<M, true, kSparseA, kMQ, kFast>(g, at, acc, y, img, th, tw, k0, r_m, r_y, qmax);
+    finish_lane_any<M, kSparseA, kFast>(g, at, acc, y, img, th, tw, k0, r_m, r_y, qmax, pos != 0,
+                                        pp.w);
   }
   WINO_TS(6);
 }
@@ -394,8 +416,9 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 // output channels.
 template <int M, int kLoad, int kTWB, int kRegions, bool kFast>
 __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
-    const int8_t* __restrict__ x, const int8_t* __restrict__ U, void* __restrict__ y, float r_vs,
-    float r_y, float qmax, Geom g, XPlan pl, MatAT at, KronW kw) {
+    const int8_t* __restrict__ x, const int8_t* __restrict__ U, void* __restrict__ y, int pos,
+    float r_vs, float r_m, float r_y, float qmax, Geom g, XPlan pl, MatAT at, KronW kw,
+    PosPair pp) {
   static_assert(kTWB > 0, "compile-time workgroup shape");
   constexpr int n = M + 2, P = n * n;
   constexpr int NBLK = (P + 15) / 16;
@@ -418,8 +441,16 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
   const uint32_t up = (uint32_t)g.Kp * (uint32_t)g.Cp;
 
   v4i Wb[NBLK];
+  float rq[NBLK];                                      // see fused_fwd_exact_kernel
 #pragma unroll
-  for (int blk = 0; blk < NBLK; ++blk) Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
+  for (int blk = 0; blk < NBLK; ++blk) {
+    Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
+    rq[blk] = r_vs;
+  }
+  if (pos) {
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) rq[blk] = pp.rv[blk * 16 + r < P ? blk * 16 + r : P - 1];
+  }
 
   // U operands of the per-position MFMAs, in the order (position, channel block), through
   // a register ring; the first ring-full is fetched during the last transform phase
@@ -475,10 +506,10 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
         nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
                                                     v4i{0, 0, 0, 0}, 0, 0, 0);
       // four codes into one dword with three byte permutes
-      const uint32_t packed = pack_codes(quantize_bits((float)cur[0], r_vs, lo, hi),
-                                         quantize_bits((float)cur[1], r_vs, lo, hi),
-                                         quantize_bits((float)cur[2], r_vs, lo, hi),
-                                         quantize_bits((float)cur[3], r_vs, lo, hi));
+      const uint32_t packed = pack_codes(quantize_bits((float)cur[0], rq[blk], lo, hi),
+                                         quantize_bits((float)cur[1], rq[blk], lo, hi),
+                                         quantize_bits((float)cur[2], rq[blk], lo, hi),
+                                         quantize_bits((float)cur[3], rq[blk], lo, hi));
       const int tl = wave * 2 + (gi >> 2);
       if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
       cur = nxt;
@@ -506,7 +537,7 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
   const int rr_ = r0 + rs, tw = tw0 + twl, k0 = kw16 + grp * 4;
   if (rr_ < R && tw < g.TW && k0 < g.K) {
     const int img = (int)fast_div(rr_, pl.inv_th), th = rr_ - img * g.TH;
-    finish_lane<M, true, true, false, kFast>(g, at, acc, y, img, th, tw, k0, 0.0f, r_y, qmax);
+    finish_lane_any<M, true, kFast>(g, at, acc, y, img, th, tw, k0, r_m, r_y, qmax, pos != 0, pp.w);
   }
 }
 
@@ -614,6 +645,11 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
 
 }  // namespace
 
+#if WINO_EXACT_M == 2   // the shape predicates are defined once
+// Images narrower than a dword (W < 4) are staged byte by byte, which exists for the
+// two-tile workgroup shape only (W < 4 and pad <= 1 give at most two tiles per row).
+static bool narrow_ok(const Geom& g) { return g.W >= 4 || g.TW <= 2; }
+
 // Host: smallest s <= 3 with 2^s B^T integral, all pairwise products within int8, and
 // every intermediate of the fp32 evaluation exactly representable (so that integer and
 // float evaluation agree bit for bit); -1 if there is none.
@@ -651,10 +687,6 @@ bool input_exact_supported(const Geom& g, const MatBT& bt) {
          (unsigned long long)g.Tp * g.Cp < 0x100000000ull && exact_input_shift(g, bt) >= 0;
 }
 
-// Images narrower than a dword (W < 4) are staged byte by byte, which exists for the
-// two-tile workgroup shape only (W < 4 and pad <= 1 give at most two tiles per row).
-static bool narrow_ok(const Geom& g) { return g.W >= 4 || g.TW <= 2; }
-
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
   // (byte-wise staging is slow enough that only a single channel block is worth fusing)
   return g.Kp <= 128 && narrow_ok(g) && (g.W >= 4 || g.Cp == 64) && input_exact_supported(g, bt);
@@ -665,6 +697,7 @@ bool input_exact_preferred(const Geom& g, const MatBT& bt, const void* x) {
   (void)x;
   return narrow_ok(g) && input_exact_supported(g, bt);
 }
+#endif
 
 namespace {
 
@@ -771,30 +804,43 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
 template <int M>
 hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                           const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
-                          hipStream_t s) {
+                          const PosScale* rv_pos, const PosScale* w_pos, hipStream_t s) {
+  constexpr int P = (M + 2) * (M + 2);
   XLaunch xl;
   if (!fused_fwd_exact_supported(g, bt) || !make_xlaunch<M>(g, bt, x, r_v, &xl))
     return hipErrorInvalidValue;
+  if ((rv_pos == nullptr) != (w_pos == nullptr)) return hipErrorInvalidValue;
+  // quantizer factors per position, each scaled by 4^-s like the per-tensor one (exact, or
+  // refuse), and the accumulators' factors
+  PosPair pp;
+  memset(&pp, 0, sizeof pp);
+  const float sc = r_v / xl.r_vs;                        // 4^s, exactly
+  for (int p = 0; p < P; ++p) {
+    pp.rv[p] = rv_pos ? rv_pos->r[p] / sc : xl.r_vs;
+    if (rv_pos && !(pp.rv[p] * sc == rv_pos->r[p])) return hipErrorInvalidValue;
+    pp.w[p] = w_pos ? w_pos->r[p] : 1.0f;
+  }
+  const int pos = w_pos != nullptr;
   dim3 grid((unsigned)xl.nrb, (unsigned)xl.ntwb, (unsigned)(g.Kp / 64));
   const XPlan& pl = xl.pl;
   const KronW& kw = xl.kw;
-  const float r_vs = xl.r_vs;
   const size_t lb = xl.lds_bytes;
   const int TWB = pl.TWB, load = xl.load;
   const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
   const int8_t* xi = (const int8_t*)x;
   const int8_t* Ui = (const int8_t*)U;
-  const bool mq = r_m > 0.0f, one = g.Cp == 64;
-#define WINO_LAUNCH_XK(SA, LOAD, MQ, ONE, TWBC, FAST)                                      \
-  fused_fwd_exact_kernel<M, SA, LOAD, MQ, ONE, TWBC, FAST><<<grid, 256, lb, s>>>(            \
-      xi, Ui, y, r_vs, r_m, r_y, qmax, g, pl, at, kw)
-  // The common case -- Cook-Toom A^T pattern, no quantizer on M, aligned staging loads --
-  // gets the compile-time workgroup shapes and, with whole tiles and K % 4 == 0, a
-  // branch-free output side.
+  const bool one = g.Cp == 64;
+#define WINO_LAUNCH_XK(SA, LOAD, ONE, TWBC, FAST)                                          \
+  fused_fwd_exact_kernel<M, SA, LOAD, ONE, TWBC, FAST><<<grid, 256, lb, s>>>(                \
+      xi, Ui, y, pos, xl.r_vs, r_m, r_y, qmax, g, pl, at, kw, pp)
+  // The common case -- Cook-Toom A^T pattern, dword staging loads -- gets the compile-time
+  // workgroup shapes and, with whole tiles and K % 4 == 0, a branch-free output side.  The
+  // quantizer after the Hadamard stage and per-position scales are run-time options of
+  // every kernel.
   const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
   // 128 output channels and at most 128 input channels: eight wavefronts share one
   // transform (fused_fwd_exact_wide_kernel)
-  if (sa && load >= 2 && !mq && g.Kp == 128 && g.Cp <= 128) {
+  if (sa && load >= 2 && g.Kp == 128 && g.Cp <= 128) {
     constexpr int n_ = M + 2, P_ = n_ * n_;
     const int plane_ = xs_plane_dw(M, TWB);
     const size_t xs_dw = (size_t)(16 / TWB) * 64 * plane_ + 20, vl_dw = (size_t)P_ * kVlPitch;
@@ -809,7 +855,7 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
           (const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lbw);        \
       if (e != hipSuccess) return e;                                                       \
     }                                                                                      \
-    kern<<<gridw, 512, lbw, s>>>(xi, Ui, y, r_vs, r_y, qmax, g, pl, at, kw);                \
+    kern<<<gridw, 512, lbw, s>>>(xi, Ui, y, pos, xl.r_vs, r_m, r_y, qmax, g, pl, at, kw, pp);        \
   } while (0)
 #define WINO_LAUNCH_W1(LOAD, TWBC, REG) \
   do { if (fast) WINO_LAUNCH_W(LOAD, TWBC, REG, true); else WINO_LAUNCH_W(LOAD, TWBC, REG, false); } while (0)
@@ -827,10 +873,10 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
 #undef WINO_LAUNCH_W
     return hipGetLastError();
   }
-  if (sa && load >= 1 && !mq) {
+  if (sa && load >= 1) {
 #define WINO_LAUNCH_C1(LOAD, TWBC, FAST) \
-  do { if (one) WINO_LAUNCH_XK(true, LOAD, false, true, TWBC, FAST);  \
-       else WINO_LAUNCH_XK(true, LOAD, false, false, TWBC, FAST); } while (0)
+  do { if (one) WINO_LAUNCH_XK(true, LOAD, true, TWBC, FAST);  \
+       else WINO_LAUNCH_XK(true, LOAD, false, TWBC, FAST); } while (0)
 #define WINO_LAUNCH_C2(LOAD, TWBC) \
   do { if (fast) WINO_LAUNCH_C1(LOAD, TWBC, true); else WINO_LAUNCH_C1(LOAD, TWBC, false); } while (0)
 #define WINO_LAUNCH_C3(TWBC) \
@@ -845,47 +891,61 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
 #undef WINO_LAUNCH_C1
     return hipGetLastError();
   }
-  // everything else: the same kernel with the shape read from the plan
-#define WINO_LAUNCH_G1(SA, LOAD, MQ) \
-  do { if (one) WINO_LAUNCH_XK(SA, LOAD, MQ, true, 0, false);      \
-       else WINO_LAUNCH_XK(SA, LOAD, MQ, false, 0, false); } while (0)
-#define WINO_LAUNCH_G2(SA, LOAD) \
-  do { if (mq) WINO_LAUNCH_G1(SA, LOAD, true); else WINO_LAUNCH_G1(SA, LOAD, false); } while (0)
-#define WINO_LAUNCH_G3(SA)                                                                 \
-  do { if (load >= 2) WINO_LAUNCH_G2(SA, 2); else WINO_LAUNCH_G2(SA, 1); } while (0)
-  // (byte-wise staging, W < 4: the dense-A^T variants serve every A^T; the two-tile shape
-  // at compile time, so that the staging issues no loads for channel quads beyond 16)
+  // everything else (a dense A^T; byte-wise staging): the dense-A^T kernel, its shape read
+  // from the plan -- except for byte-wise staging (W < 4), which takes the two-tile shape
+  // at compile time, so that it issues no loads for channel quads beyond 16
   if (load == 0) {
     if (TWB != 2) return hipErrorInvalidValue;
-    if (mq) { if (one) WINO_LAUNCH_XK(false, 0, true, true, 2, false);
-              else WINO_LAUNCH_XK(false, 0, true, false, 2, false); }
-    else    { if (one) WINO_LAUNCH_XK(false, 0, false, true, 2, false);
-              else WINO_LAUNCH_XK(false, 0, false, false, 2, false); }
+    if (one) WINO_LAUNCH_XK(false, 0, true, 2, false);
+    else WINO_LAUNCH_XK(false, 0, false, 2, false);
+  } else if (load >= 2) {
+    if (one) WINO_LAUNCH_XK(false, 2, true, 0, false);
+    else WINO_LAUNCH_XK(false, 2, false, 0, false);
+  } else {
+    if (one) WINO_LAUNCH_XK(false, 1, true, 0, false);
+    else WINO_LAUNCH_XK(false, 1, false, 0, false);
   }
-  else if (sa) WINO_LAUNCH_G3(true);
-  else WINO_LAUNCH_G3(false);
-#undef WINO_LAUNCH_G3
-#undef WINO_LAUNCH_G2
-#undef WINO_LAUNCH_G1
 #undef WINO_LAUNCH_XK
   return hipGetLastError();
 }
 
 }  // namespace
 
+#if WINO_EXACT_M == 2
+hipError_t launch_input_exact_m2(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
+                                 float qmax, hipStream_t s, const PosScale* rv_pos) {
+  return launch_input_m<2>(g, bt, x, V, r_v, qmax, s, rv_pos);
+}
+hipError_t launch_fused_fwd_exact_m2(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                                     const void* U, void* y, float r_v, float r_m, float r_y,
+                                     float qmax, const PosScale* rv_pos, const PosScale* w_pos,
+                                     hipStream_t s) {
+  return launch_exact_m<2>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, rv_pos, w_pos, s);
+}
+#else
+hipError_t launch_input_exact_m2(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
+                                 float qmax, hipStream_t s, const PosScale* rv_pos);
+hipError_t launch_fused_fwd_exact_m2(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                                     const void* U, void* y, float r_v, float r_m, float r_y,
+                                     float qmax, const PosScale* rv_pos, const PosScale* w_pos,
+                                     hipStream_t s);
+
 hipError_t launch_input_exact(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
                               float qmax, hipStream_t s, const PosScale* rv_pos) {
-  if (g.m == 2) return launch_input_m<2>(g, bt, x, V, r_v, qmax, s, rv_pos);
+  if (g.m == 2) return launch_input_exact_m2(g, bt, x, V, r_v, qmax, s, rv_pos);
   if (g.m == 4) return launch_input_m<4>(g, bt, x, V, r_v, qmax, s, rv_pos);
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                                   const void* U, void* y, float r_v, float r_m, float r_y,
-                                  float qmax, hipStream_t s) {
-  if (g.m == 2) return launch_exact_m<2>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, s);
-  if (g.m == 4) return launch_exact_m<4>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, s);
+                                  float qmax, const PosScale* rv_pos, const PosScale* w_pos,
+                                  hipStream_t s) {
+  if (g.m == 2)
+    return launch_fused_fwd_exact_m2(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, rv_pos, w_pos, s);
+  if (g.m == 4) return launch_exact_m<4>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, rv_pos, w_pos, s);
   return hipErrorInvalidValue;
 }
+#endif
 
 }  // namespace wino

@@ -106,11 +106,14 @@ __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv,
 // kMQ: the optional quantizer after the Hadamard stage is on (r_m > 0).
 // kFast: whole tiles only (see store_tile), K a multiple of 4 and k0 < K checked by the
 // caller (no channel guard here).
-template <int M, bool I8, bool kSparse, bool kMQ, bool kFast = false>
+// kPos: per-position scales -- every accumulator is first multiplied by the factor of its
+// position (wpos[p], real units per unit of the integer product).
+template <int M, bool I8, bool kSparse, bool kMQ, bool kFast = false, bool kPos = false>
 __device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
                                             const typename Acc<I8>::type (&acc)[(M + 2) * (M + 2)],
                                             void* __restrict__ yv, int img, int th, int tw, int k0,
-                                            float r_m, float r_y, float qmax) {
+                                            float r_m, float r_y, float qmax,
+                                            const float* wpos = nullptr) {
   constexpr int n = M + 2;
   const float lo = kMagic - qmax, hi = kMagic + qmax;
 #pragma unroll
@@ -124,6 +127,7 @@ __device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
       for (int j = 0; j < n; ++j) {
         if constexpr (I8) {
           float f = (float)acc[i * n + j][rr];
+          if constexpr (kPos) f *= wpos[i * n + j];
           if constexpr (kMQ) f = quantize_f(f, r_m, qmax);
           Mt[i][j] = f;
         } else {
@@ -133,6 +137,28 @@ __device__ __forceinline__ void finish_lane(const Geom& g, const MatAT& at,
     transform_result<M, kSparse>(Mt, at, Y);
     store_tile<M, I8, kFast>(g, yv, ((size_t)img * g.K + k) * g.Ho * g.Wo, th * M, tw * M, Y, r_y,
                              lo, hi);
+  }
+}
+
+// The int8 output side with the quantizer options decided at run time (both uniform):
+// r_m > 0 turns the Hadamard-stage quantizer on, `pos` the per-position factors w[p].
+// One copy of the code per combination, so that none pays for the others' instructions.
+template <int M, bool kSparse, bool kFast>
+__device__ __forceinline__ void finish_lane_any(const Geom& g, const MatAT& at,
+                                                const v4i (&acc)[(M + 2) * (M + 2)],
+                                                void* __restrict__ yv, int img, int th, int tw,
+                                                int k0, float r_m, float r_y, float qmax,
+                                                bool pos, const float* wpos) {
+  if (pos) {
+    if (r_m > 0.0f)
+      finish_lane<M, true, kSparse, true, kFast, true>(g, at, acc, yv, img, th, tw, k0, r_m, r_y, qmax, wpos);
+    else
+      finish_lane<M, true, kSparse, false, kFast, true>(g, at, acc, yv, img, th, tw, k0, r_m, r_y, qmax, wpos);
+  } else {
+    if (r_m > 0.0f)
+      finish_lane<M, true, kSparse, true, kFast>(g, at, acc, yv, img, th, tw, k0, r_m, r_y, qmax);
+    else
+      finish_lane<M, true, kSparse, false, kFast>(g, at, acc, yv, img, th, tw, k0, r_m, r_y, qmax);
   }
 }
 

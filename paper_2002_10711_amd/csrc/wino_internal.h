@@ -107,12 +107,17 @@ hipError_t launch_input_f32_staged(const Geom& g, const MatBT& bt, const void* x
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt);
 // The input stage alone with the same exact transform (any number of output channels).
 bool input_exact_supported(const Geom& g, const MatBT& bt);
+// (smallest s <= 3 with 2^s B^T integral and int8 products; -1 if none)
+int exact_input_shift(const Geom& g, const MatBT& bt);
 bool input_exact_preferred(const Geom& g, const MatBT& bt, const void* x);
 hipError_t launch_input_exact(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
                               float qmax, hipStream_t s, const PosScale* rv_pos = nullptr);
+// (rv_pos, w_pos: per-position quantizer factors of V and factors of the accumulators,
+// both or neither; nullptr = per-tensor scales)
 hipError_t launch_fused_fwd_exact(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                                   const void* U, void* y, float r_v, float r_m, float r_y,
-                                  float qmax, hipStream_t s);
+                                  float qmax, const PosScale* rv_pos, const PosScale* w_pos,
+                                  hipStream_t s);
 hipError_t launch_export(const Geom& g, int which, const void* src, void* out, hipStream_t s);
 
 // The path with up to 16-bit codes after every stage (g.w16): weight stage, input stage,

@@ -172,6 +172,13 @@ def test_many_tiles_ragged_flex_and_m_quantizer(oracle, m):
     Layer("pos_f4_flex", 2, 24, 40, 10, 10, m=4, flex_sigma=0.05, seed=134),
     Layer("pos_f2_c256", 2, 256, 40, 8, 8, m=2, seed=135),        # long reduction, fused GEMM + output
     Layer("pos_f6_c128", 1, 128, 70, 16, 16, m=6, seed=136),
+    # the one-kernel forward with per-position factors: eight-wavefront form (one and two
+    # LDS regions), two channel blocks, ragged tiles, byte-wise staging
+    Layer("pos_f4_c100_k128", 3, 100, 128, 16, 16, m=4, seed=137),
+    Layer("pos_f2_k72_8px", 2, 64, 72, 8, 8, m=2, seed=138),
+    Layer("pos_f2_c128_k64", 2, 128, 64, 12, 12, m=2, seed=139),
+    Layer("pos_f4_7px", 5, 24, 20, 7, 7, m=4, seed=140),
+    Layer("pos_f2_2px", 9, 64, 40, 2, 2, m=2, seed=165),
 ], ids=lambda l: l.name)
 def test_per_position_scales_all_taps(oracle, layer):
     """One quantizer scale per Winograd position for V and U (Sec. 6), calibrated by the
@@ -186,6 +193,32 @@ def test_per_position_scales_all_taps(oracle, layer):
     sc = dict(sc, s_m=float(np.abs(case["ref"]["M"] * case["ref"]["scalars"]["w"][:, None, None]).max()) / 100.0)
     case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc,
                                     pad=layer.pad)
+    _check_i8(case, run_gpu(case, scales=sc))
+
+
+@pytest.mark.parametrize("layer", [
+    Layer("denseA_f4", 3, 64, 64, 16, 16, m=4, seed=166),
+    Layer("denseA_f2_c70_k100", 2, 70, 100, 9, 11, m=2, seed=167),
+], ids=lambda l: l.name)
+def test_learned_output_matrix_with_exact_input_matrix(oracle, layer):
+    """A^T and G learned (dense), B^T left at its Cook-Toom values: the matrix-core input
+    transform feeds the one-kernel forward with a dense output transform; per-tensor scales,
+    then per-position scales with the Hadamard-stage quantizer."""
+    case = make_case(oracle, layer, with_oracle=False)
+    _, G, AT = workloads.perturb_transforms(case["BT"], case["G"], case["AT"], 0.05, layer.seed)
+    case["G"], case["AT"] = G, AT
+    BT = case["BT"]
+    assert np.count_nonzero(AT) == AT.size
+    sc = oracle.calibrate(case["X"], case["g"], BT, G, AT, pad=layer.pad)
+    case["scales"] = sc
+    case["xq"] = oracle.quantize_tensor(case["X"], sc["s_x"]).astype(np.int8)
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], BT, G, AT, sc, pad=layer.pad)
+    _check_i8(case, run_gpu(case))
+    sc = oracle.calibrate_pos(case["X"], case["g"], BT, G, AT, pad=layer.pad)
+    case["xq"] = oracle.quantize_tensor(case["X"], sc["s_x"]).astype(np.int8)
+    ref = oracle.winograd_q(case["xq"], case["g"], BT, G, AT, sc, pad=layer.pad)
+    sc = dict(sc, s_m=float(np.abs(ref["M"] * ref["scalars"]["w"][:, None, None]).max()) / 100.0)
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], BT, G, AT, sc, pad=layer.pad)
     _check_i8(case, run_gpu(case, scales=sc))
 
 
