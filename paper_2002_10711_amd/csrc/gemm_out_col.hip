@@ -33,8 +33,10 @@ constexpr int ring_depth(int sj) {
   return 1;
 }
 
-template <int M, int NCH, bool kSparse, int kTW>
-__global__ __launch_bounds__(256, M == 6 ? 2 : 1) void gemm_out_col_kernel(Geom g, MatAT at,
+// kTwoWG (m = 6 only): held to 128 registers so that two workgroups fit a CU -- it spills a
+// little, which pays when the grid would otherwise need a second, mostly empty round.
+template <int M, int NCH, bool kSparse, int kTW, bool kTwoWG = false>
+__global__ __launch_bounds__(256, kTwoWG ? 2 : 1) void gemm_out_col_kernel(Geom g, MatAT at,
                                                            const int8_t* __restrict__ V,
                                                            const int8_t* __restrict__ U,
                                                            int8_t* __restrict__ y, PosScale w,
@@ -42,9 +44,8 @@ __global__ __launch_bounds__(256, M == 6 ? 2 : 1) void gemm_out_col_kernel(Geom 
                                                            int fast) {
   constexpr int n = M + 2;
   constexpr int SJ = n * NCH;                          // steps (64 channels each) per column
-  // U ring, in steps (m = 6: shorter, so that two workgroups fit a CU -- its layers have
-  // few tiles, and one workgroup per CU leaves a second, mostly empty round)
-  constexpr int kDepth = M == 6 ? 8 : ring_depth(SJ);
+  // U ring, in steps (shorter where two workgroups share a CU's registers)
+  constexpr int kDepth = (kTwoWG || M == 6) ? 8 : ring_depth(SJ);
   constexpr int kBlocks = NCH * kTW;                   // 1 KB operand blocks of V per position
   constexpr int kLd = (kBlocks + 3) / 4;               // 16-byte loads per thread and position
   constexpr int kPos = kLd > 1 ? 2 : (NCH >= 4 || M == 6) ? n / 2 : n;        // positions ahead
@@ -231,6 +232,23 @@ hipError_t launch_ms(const Geom& g, const MatAT& at, const void* V, const void* 
   if constexpr (M == 4) {
     if (g.Cp == 512 && g.T >= 2048) {
       WINO_COL_GO2(8);
+      return hipGetLastError();
+    }
+  }
+  if constexpr (M == 6) {
+    // more workgroups than CUs, but not many more: two per CU finish in one round
+    const long long wgs = (long long)(g.Tp / 16) * (g.Kp / 64);
+    if (wgs > 256) {
+#define WINO_COL_GO6(NCHV)                                                               \
+  gemm_out_col_kernel<M, NCHV, kSparse, 1, true><<<dim3(g.Tp / 16, g.Kp / 64), 256, 0, s>>>( \
+      g, at, Vi, Ui, yo, ws, r_m, r_y, qmax, fast)
+      switch (g.Cp) {
+        case 64: WINO_COL_GO6(1); break;
+        case 128: WINO_COL_GO6(2); break;
+        case 256: WINO_COL_GO6(4); break;
+        default: WINO_COL_GO6(8); break;
+      }
+#undef WINO_COL_GO6
       return hipGetLastError();
     }
   }

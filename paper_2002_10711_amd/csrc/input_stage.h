@@ -17,6 +17,8 @@
 // transformed one after the other and their int8 results packed into one dword per
 // Winograd position.
 #pragma once
+#include <type_traits>
+
 #include "transform_math.h"
 
 namespace wino {
@@ -55,9 +57,10 @@ __device__ __forceinline__ uint32_t load_quad_guarded(const int8_t* row, int w, 
 
 // Phase 1.  A "strip" is the n rows x WQ column quads one channel quad needs for one
 // tile row.  Lane -> (slot, row j, column quad lq), fixed for the whole call (one
-// division per thread); a pass stages `slots` channel quads.  All loads of up to kBatch
-// passes are issued before the first is used (a workgroup has few wavefronts and
-// nothing else hides the memory latency), and they are branch-free: every lane loads a
+// division per thread); a pass stages `slots` channel quads.  All loads of a batch of
+// passes (8, 4, 2 or 1, as many as remain) are issued before the first is used (a
+// workgroup has few wavefronts and nothing else hides the memory latency), and they are
+// branch-free: every lane loads a
 // dword from an address clamped into its image row, shifts out the bytes that fell
 // outside the row and masks rows / channels / tile rows that do not exist.  (Branches
 // around the loads or the LDS stores make the compiler sink the loads into them and
@@ -86,7 +89,6 @@ __device__ __forceinline__ void stage_strips(const Geom& g, const int8_t* __rest
   const int sh = 24 + 8 * (overlap ? dw : 0);
   const int chs = g.H * g.W;
   const int npass = (16 + slots - 1) / slots;
-  constexpr int kBatch = 8;
   uint32_t* dump = lds + RB * n * Wc * CBQ;      // 4*CBQ dwords nobody reads
   for (int rs = 0; rs < RB; ++rs) {
     const int r = r0 + rs;
@@ -97,7 +99,11 @@ __device__ __forceinline__ void stage_strips(const Geom& g, const int8_t* __rest
     const bool rowok = lane_on && r < R && h == hc && overlap;
     const int8_t* base = x + ((size_t)img * g.C + c0) * chs + (size_t)hc * g.W + wl;
     uint32_t* ldsrow = lds + ((rs * n + j) * Wc + lq * 4) * CBQ;
-    for (int ps0 = 0; ps0 < npass; ps0 += kBatch) {
+    // One batch of kB passes: all its loads are issued before the first is used.  (The
+    // batch size follows the number of passes, so that a workgroup shape with many slots
+    // issues no loads for channel quads beyond the block.)
+    auto batch = [&](auto kb_tag, int ps0) {
+      constexpr int kBatch = decltype(kb_tag)::value;
       uint32_t q[kBatch][4];
       int off[kBatch][4];                    // byte offset from base; 0 for masked lanes
       uint32_t msk[kBatch][4];
@@ -142,7 +148,12 @@ __device__ __forceinline__ void stage_strips(const Geom& g, const int8_t* __rest
         dst[2 * CBQ] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
         dst[3 * CBQ] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
       }
-    }
+    };
+    int ps0 = 0;
+    for (; ps0 + 8 <= npass; ps0 += 8) batch(std::integral_constant<int, 8>{}, ps0);
+    if (npass - ps0 >= 4) { batch(std::integral_constant<int, 4>{}, ps0); ps0 += 4; }
+    if (npass - ps0 >= 2) { batch(std::integral_constant<int, 2>{}, ps0); ps0 += 2; }
+    if (npass - ps0 >= 1) batch(std::integral_constant<int, 1>{}, ps0);
   }
 }
 

@@ -56,6 +56,83 @@ __global__ __launch_bounds__(256) void input_transform_i8(Geom g, MatBT bt,
   }
 }
 
+// The same for layers with few tiles (less than a wavefront per SIMD): (M + 2) / 2 wavefronts
+// share an item, each producing two rows i of V -- w = (B^T d)[i][.] and V[i][.] = w B need
+// no other rows -- so the chain of dependent fmas a lane runs is (M + 2) / 2 times shorter.
+// blockDim.x = 64 * (M + 2) / 2; wavefront s owns rows 2s, 2s + 1 of every item.  The row
+// index is uniform but not a constant, so the left product runs over all of B^T's entries
+// (zeros included: fma(0, x, acc) == acc).
+template <int M, bool kSparse, bool kWide, bool kPos>
+__global__ __launch_bounds__(256) void input_transform_i8_rows(Geom g, MatBT bt,
+                                                               const int8_t* __restrict__ x,
+                                                               uint32_t* __restrict__ V, float r_v,
+                                                               float qmax, int RB, int TWB,
+                                                               PosScale rvp) {
+  constexpr int n = M + 2, CBQ = InCfg<M>::kCBQ;
+  extern __shared__ uint32_t lds[];
+  const int Wc = stage_cols(M, TWB);
+  const int ntwb = (g.TW + TWB - 1) / TWB;
+  const int twb = blockIdx.x % ntwb, rb = blockIdx.x / ntwb;
+  const int r0 = rb * RB, tw0 = twb * TWB, c0 = blockIdx.y * 64;
+  const int R = g.N * g.TH;
+  stage_strips<M, kWide>(g, x, lds, c0, r0, tw0, RB, TWB);
+  __syncthreads();
+  const float lo = kMagic - qmax, hi = kMagic + qmax;
+  const int cq_per = g.Cp >> 2;
+  const size_t pstride = (size_t)g.Tp * cq_per;
+  const int nitem = RB * TWB * 16;
+  const int i0 = 2 * __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  for (int it = threadIdx.x & 63; it < nitem; it += 64) {
+    const int cq = it & 15, twl = (it >> 4) % TWB, rs = (it >> 4) / TWB;
+    const int r = r0 + rs, tw = tw0 + twl;
+    if (r >= R || tw >= g.TW) continue;
+    uint32_t raw[n][n];
+    load_quad_patch<M>(lds + ((size_t)rs * n * Wc + twl * M) * CBQ + cq, Wc, raw);
+    uint32_t out[2][n];
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int k = 0; k < n; ++k) out[ii][k] = 0u;
+#pragma unroll 1
+    for (int e = 0; e < 4; ++e) {
+      float d[n][n];
+#pragma unroll
+      for (int j = 0; j < n; ++j)
+#pragma unroll
+        for (int l = 0; l < n; ++l) {
+          d[j][l] = (float)(int)(int8_t)(raw[j][l] & 0xff);
+          raw[j][l] >>= 8;
+        }
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii) {
+        float w[n];
+#pragma unroll
+        for (int l = 0; l < n; ++l) {
+          float acc = 0.0f;
+#pragma unroll
+          for (int j = 0; j < n; ++j) acc = __builtin_fmaf(bt.v[(i0 + ii) * n + j], d[j][l], acc);
+          w[l] = acc;
+        }
+#pragma unroll
+        for (int k = 0; k < n; ++k) {
+          float acc = 0.0f;
+#pragma unroll
+          for (int l = 0; l < n; ++l)
+            if (bt_nonzero<M, kSparse>(k, l)) acc = __builtin_fmaf(w[l], bt.v[k * n + l], acc);
+          const uint32_t bits =
+              quantize_bits(acc, kPos ? rvp.r[(i0 + ii) * n + k] : r_v, lo, hi);
+          out[ii][k] = __builtin_amdgcn_perm(bits, out[ii][k], 0x04030201u);
+        }
+      }
+    }
+    uint32_t* vp = V + ((size_t)r * g.TW + tw) * cq_per + (c0 >> 2) + cq;
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int k = 0; k < n; ++k) vp[(size_t)((i0 + ii) * n + k) * pstride] = out[ii][k];
+  }
+}
+
 // fp32: one thread per (tile, channel), patch gathered straight from global memory.
 template <int M, bool kSparse>
 __global__ __launch_bounds__(256) void input_transform_f32(Geom g, MatBT bt,
@@ -272,6 +349,20 @@ hipError_t launch_input_i8(const Geom& g, const MatBT& bt, const int8_t* x, uint
   const size_t lb = lds_bytes(RB, TWB);
   PosScale none;
   memset(&none, 0, sizeof none);
+  // few tiles (one wavefront per workgroup, less than a wavefront per SIMD): split the
+  // rows of V over (M + 2) / 2 wavefronts
+  if (threads == 64 && (long long)ntwb * nrb * (g.Cp / 64) < 1024) {
+#define WINO_LAUNCH_INR(WIDE, POS)                                                         \
+  input_transform_i8_rows<M, kSparse, WIDE, POS><<<grid, 32 * n, lb, s>>>(                  \
+      g, bt, x, V, r_v, qmax, RB, TWB, POS ? *rv_pos : none)
+    if (g.W >= 4) {
+      if (rv_pos) WINO_LAUNCH_INR(true, true); else WINO_LAUNCH_INR(true, false);
+    } else {
+      if (rv_pos) WINO_LAUNCH_INR(false, true); else WINO_LAUNCH_INR(false, false);
+    }
+#undef WINO_LAUNCH_INR
+    return hipGetLastError();
+  }
 #define WINO_LAUNCH_IN(WIDE, POS)                                                          \
   input_transform_i8<M, kSparse, WIDE, POS><<<grid, threads, lb, s>>>(g, bt, x, V, r_v, qmax, RB, \
                                                                        TWB, POS ? *rv_pos : none)
