@@ -59,9 +59,9 @@ __global__ __launch_bounds__(256) void input_transform_i8(Geom g, MatBT bt,
 // The same for layers with few tiles (less than a wavefront per SIMD): (M + 2) / 2 wavefronts
 // share an item, each producing two rows i of V -- w = (B^T d)[i][.] and V[i][.] = w B need
 // no other rows -- so the chain of dependent fmas a lane runs is (M + 2) / 2 times shorter.
-// blockDim.x = 64 * (M + 2) / 2; wavefront s owns rows 2s, 2s + 1 of every item.  The row
-// index is uniform but not a constant, so the left product runs over all of B^T's entries
-// (zeros included: fma(0, x, acc) == acc).
+// blockDim.x = 64 * (M + 2) / 2; wavefront s owns rows 2s, 2s + 1 of every item (one copy
+// of the arithmetic per s, so that the rows are compile-time constants and the zero
+// pattern of B^T can be skipped in both products).
 template <int M, bool kSparse, bool kWide, bool kPos>
 __global__ __launch_bounds__(256) void input_transform_i8_rows(Geom g, MatBT bt,
                                                                const int8_t* __restrict__ x,
@@ -81,7 +81,9 @@ __global__ __launch_bounds__(256) void input_transform_i8_rows(Geom g, MatBT bt,
   const int cq_per = g.Cp >> 2;
   const size_t pstride = (size_t)g.Tp * cq_per;
   const int nitem = RB * TWB * 16;
-  const int i0 = 2 * __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int sub = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  auto rows = [&](auto i0_tag) {
+  constexpr int i0 = decltype(i0_tag)::value;
   for (int it = threadIdx.x & 63; it < nitem; it += 64) {
     const int cq = it & 15, twl = (it >> 4) % TWB, rs = (it >> 4) / TWB;
     const int r = r0 + rs, tw = tw0 + twl;
@@ -110,7 +112,9 @@ __global__ __launch_bounds__(256) void input_transform_i8_rows(Geom g, MatBT bt,
         for (int l = 0; l < n; ++l) {
           float acc = 0.0f;
 #pragma unroll
-          for (int j = 0; j < n; ++j) acc = __builtin_fmaf(bt.v[(i0 + ii) * n + j], d[j][l], acc);
+          for (int j = 0; j < n; ++j)
+            if (bt_nonzero<M, kSparse>(i0 + ii, j))
+              acc = __builtin_fmaf(bt.v[(i0 + ii) * n + j], d[j][l], acc);
           w[l] = acc;
         }
 #pragma unroll
@@ -130,6 +134,13 @@ __global__ __launch_bounds__(256) void input_transform_i8_rows(Geom g, MatBT bt,
     for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
       for (int k = 0; k < n; ++k) vp[(size_t)((i0 + ii) * n + k) * pstride] = out[ii][k];
+  }
+  };
+  switch (sub) {
+    case 0: rows(std::integral_constant<int, 0>{}); break;
+    case 1: rows(std::integral_constant<int, 2>{}); break;
+    case 2: if constexpr (n > 4) rows(std::integral_constant<int, 4>{}); break;
+    default: if constexpr (n > 6) rows(std::integral_constant<int, 6>{}); break;
   }
 }
 
@@ -349,8 +360,9 @@ hipError_t launch_input_i8(const Geom& g, const MatBT& bt, const int8_t* x, uint
   const size_t lb = lds_bytes(RB, TWB);
   PosScale none;
   memset(&none, 0, sizeof none);
-  // few tiles (one wavefront per workgroup, less than a wavefront per SIMD): split the
-  // rows of V over (M + 2) / 2 wavefronts
+  // few tiles (one wavefront per workgroup, less than one per SIMD): split the rows of V
+  // over (M + 2) / 2 wavefronts (with more wavefronts the kernel is bound by its
+  // instruction count, which the split raises: every wavefront unpacks the whole patch)
   if (threads == 64 && (long long)ntwb * nrb * (g.Cp / 64) < 1024) {
 #define WINO_LAUNCH_INR(WIDE, POS)                                                         \
   input_transform_i8_rows<M, kSparse, WIDE, POS><<<grid, 32 * n, lb, s>>>(                  \
