@@ -223,3 +223,36 @@ def test_wide_mode_sizes_and_argument_checks(L):
     q = wb.make_quant(**kw, qmax=32767)
     assert _fwd(L, _desc(dtype=wb.WINO_I16), q, x=0x1001) == -8
     assert _fwd(L, _desc(dtype=wb.WINO_I16), q, y=0x1001) == -8
+
+
+def test_bench_algorithmic_work_of_config2():
+    """The bytes and operations the benchmark prices its kernels with, for the headline layer
+    (N=64, 64->64, 32x32, F(4x4,3x3), int8), against values worked out by hand from Eq. 1 and
+    the GEMM formulation of Sec. 5.3: 4096 tiles, 36 positions; X and Y 64*64*32*32 bytes,
+    V 36*4096*64, U 36*64*64, M 4*36*4096*64; GEMM 2*36*4096*64*64 operations; direct
+    convolution 2*64*64*32*32*64*9."""
+    import os
+    import sys
+    import numpy as np
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    from paper_2002_10711_amd import binding as wb, workloads
+    L = workloads.config2("i8")[0]
+    BT, G, AT = wb.wino_cook_toom(4)
+    a = bench.algorithmic(L, np.asarray(BT), np.asarray(AT))
+    x = y = 4194304
+    v, u, m = 9437184, 147456, 37748736
+    assert a["input_transform"]["bytes"] == x + v
+    assert a["gemm"]["bytes"] == v + u + m and a["gemm"]["ops"] == 1207959552
+    assert a["output_transform"]["bytes"] == m + y
+    assert a["gemm_output"]["bytes"] == v + u + y
+    assert a["fused_forward"]["bytes"] == x + u + y and a["fused_forward"]["ops"] == 1207959552
+    assert a["weight_transform"]["bytes"] == 9 * 64 * 64 * 4 + u
+    assert 2 * L.N * L.K * L.Ho * L.Wo * L.C * 9 == 4831838208
+    # the 16-bit-stage workload: two bytes per code of X, Y, U, V, eight per accumulator
+    # taken to memory, four int8 digit products per 16-bit product
+    Lw = workloads.config2("i16")[0]
+    w = bench.algorithmic(Lw, np.asarray(BT), np.asarray(AT))
+    assert w["gemm_output"]["bytes"] == 2 * (v + u + y) and w["gemm"]["bytes"] == 2 * (v + u) + 2 * m
+    assert w["gemm"]["ops"] == 4 * 1207959552
