@@ -294,13 +294,15 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
   }
   if (stages == WINO_STAGE_ALL && fused_fwd_supported(g)) {
     // the whole forward in one kernel: V and M stay on chip, the workspace is untouched
-    // (per-position scales: in the matrix-core variant only)
     const bool exact = fused_fwd_exact_supported(g, bt);
-    if (exact || (!s.pos && fused_fwd_generic_preferred(g))) {
+    if (exact || fused_fwd_generic_preferred(g)) {
+      const PosScale* rvq = s.pos ? &s.rv_pos : nullptr;
+      const PosScale* wq = s.pos ? &s.w_pos : nullptr;
       const hipError_t e =
           exact ? launch_fused_fwd_exact(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax,
-                                         s.pos ? &s.rv_pos : nullptr, s.pos ? &s.w_pos : nullptr, hs)
-                : launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, hs);
+                                         rvq, wq, hs)
+                : launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, rvq,
+                                   wq, hs);
       return e == hipSuccess ? WINO_OK : WINO_E_HIP;
     }
   }

@@ -33,10 +33,14 @@ namespace {
 // MFMAs (zero "C" operand) instead of occupying registers during staging and transform.
 // That variant is held to 256 registers per lane, i.e. at least two workgroups per compute
 // unit: one's memory and LDS latencies hide behind the other's arithmetic.
-template <int M, bool kSparseB, bool kSparseA, bool kWide, bool kMQ, bool kFast, bool kOneBlock>
+// pos != 0: per-position scales -- rv[p] is the quantizer factor of V at position p (else
+// r_v everywhere) and w[p] brings accumulator p to real units.  The quantizer
+// after the Hadamard stage (r_m > 0) and `pos` are run-time options (output_stage.h).
+template <int M, bool kSparseB, bool kSparseA, bool kWide, bool kFast, bool kOneBlock>
 __global__ __launch_bounds__(256, kOneBlock ? 2 : 1) void fused_fwd_i8_kernel(
     Geom g, MatBT bt, MatAT at, const int8_t* __restrict__ x, const int8_t* __restrict__ U,
-    void* __restrict__ y, float r_v, float r_m, float r_y, float qmax, int RB, int TWB) {
+    void* __restrict__ y, float r_v, float r_m, float r_y, float qmax, int RB, int TWB, int pos,
+    PosScale rv, PosScale w) {
   constexpr int n = M + 2, P = n * n, CBQ = InCfg<M>::kCBQ;
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   uint32_t* Vl = lds;                                 // [P][16 tiles][16 dwords], aliases staging
@@ -82,7 +86,10 @@ __global__ __launch_bounds__(256, kOneBlock ? 2 : 1) void fused_fwd_i8_kernel(
     __syncthreads();                                   // staging area is free: Vl may overwrite it
     {
       uint32_t out[P];
-      transform_raw<M, kSparseB>(raw, bt, r_v, lo, hi, out);
+      // (one copy per kind of scale: 36 factors in scalar registers would crowd out the
+      // per-tensor path's matrix entries)
+      if (pos) transform_raw<M, kSparseB, true>(raw, bt, 0.0f, lo, hi, out, &rv);
+      else transform_raw<M, kSparseB, false>(raw, bt, r_v, lo, hi, out);
 #pragma unroll
       for (int p = 0; p < P; ++p) Vl[(p * 16 + tl) * 16 + cq] = out[p];
     }
@@ -113,13 +120,13 @@ __global__ __launch_bounds__(256, kOneBlock ? 2 : 1) void fused_fwd_i8_kernel(
   const int k0 = kb + wave * 16 + grp * 4;
   if (rs >= RB || rr_ >= R || tw >= g.TW || k0 >= g.K) return;
   const int img = rr_ / g.TH, th = rr_ - img * g.TH;
-  finish_lane<M, true, kSparseA, kMQ, kFast>(g, at, acc, y, img, th, tw, k0, r_m, r_y, qmax);
+  finish_lane_any<M, kSparseA, kFast>(g, at, acc, y, img, th, tw, k0, r_m, r_y, qmax, pos != 0, w.r);
 }
 
 template <int M, bool kSparseB, bool kSparseA>
 hipError_t launch_k(const Geom& g, const MatBT& bt, const MatAT& at, const int8_t* x,
                     const int8_t* U, void* y, float r_v, float r_m, float r_y, float qmax,
-                    hipStream_t s) {
+                    const PosScale* rv_pos, const PosScale* w_pos, hipStream_t s) {
   constexpr int n = M + 2, P = n * n;
   const int R = g.N * g.TH;
   int TWB = g.TW < 16 ? g.TW : 16;
@@ -129,23 +136,27 @@ hipError_t launch_k(const Geom& g, const MatBT& bt, const MatAT& at, const int8_
   const size_t lb = stage_b > vl_b ? stage_b : vl_b;
   const int ntwb = (g.TW + TWB - 1) / TWB, nrb = (R + RB - 1) / RB;
   if (lb > 65536 || (long long)ntwb * nrb > 0x7fffffffLL || g.Kp / 64 > 65535 ||
-      n * (stage_cols(M, TWB) / 4) > 256)
+      n * (stage_cols(M, TWB) / 4) > 256 || (rv_pos == nullptr) != (w_pos == nullptr))
     return hipErrorInvalidValue;
+  PosScale rv, w;
+  for (int p = 0; p < 64; ++p) {
+    rv.r[p] = rv_pos ? rv_pos->r[p] : r_v;
+    w.r[p] = w_pos ? w_pos->r[p] : 1.0f;
+  }
+  const int pos = w_pos != nullptr;
   dim3 grid((unsigned)(ntwb * nrb), (unsigned)(g.Kp / 64));
-#define WINO_LAUNCH_FUSED1(WIDE, MQ, FAST, ONE)                                       \
-  fused_fwd_i8_kernel<M, kSparseB, kSparseA, WIDE, MQ, FAST, ONE><<<grid, 256, lb, s>>>( \
-      g, bt, at, x, U, y, r_v, r_m, r_y, qmax, RB, TWB)
-#define WINO_LAUNCH_FUSED(WIDE, MQ, FAST)                                             \
-  do { if (g.Cp == 64) WINO_LAUNCH_FUSED1(WIDE, MQ, FAST, true);                      \
-       else WINO_LAUNCH_FUSED1(WIDE, MQ, FAST, false); } while (0)
-  // whole tiles and K % 4 == 0 (and no quantizer on M): no guards on the output side
-  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && !(r_m > 0.0f);
+#define WINO_LAUNCH_FUSED1(WIDE, FAST, ONE)                                           \
+  fused_fwd_i8_kernel<M, kSparseB, kSparseA, WIDE, FAST, ONE><<<grid, 256, lb, s>>>(   \
+      g, bt, at, x, U, y, r_v, r_m, r_y, qmax, RB, TWB, pos, rv, w)
+#define WINO_LAUNCH_FUSED(WIDE, FAST)                                                 \
+  do { if (g.Cp == 64) WINO_LAUNCH_FUSED1(WIDE, FAST, true);                          \
+       else WINO_LAUNCH_FUSED1(WIDE, FAST, false); } while (0)
+  // whole tiles and K % 4 == 0: no guards on the output side
+  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
   if (g.W >= 4) {
-    if (fast) WINO_LAUNCH_FUSED(true, false, true);
-    else if (r_m > 0.0f) WINO_LAUNCH_FUSED(true, true, false);
-    else WINO_LAUNCH_FUSED(true, false, false);
+    if (fast) WINO_LAUNCH_FUSED(true, true); else WINO_LAUNCH_FUSED(true, false);
   } else {
-    if (r_m > 0.0f) WINO_LAUNCH_FUSED(false, true, false); else WINO_LAUNCH_FUSED(false, false, false);
+    WINO_LAUNCH_FUSED(false, false);
   }
 #undef WINO_LAUNCH_FUSED
 #undef WINO_LAUNCH_FUSED1
@@ -155,13 +166,15 @@ hipError_t launch_k(const Geom& g, const MatBT& bt, const MatAT& at, const int8_
 template <int M>
 hipError_t launch_m(const Geom& g, const MatBT& bt, const MatAT& at, const int8_t* x,
                     const int8_t* U, void* y, float r_v, float r_m, float r_y, float qmax,
-                    hipStream_t s) {
+                    const PosScale* rv_pos, const PosScale* w_pos, hipStream_t s) {
   const bool sb = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt);
   const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
-  if (sb && sa) return launch_k<M, true, true>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, s);
-  if (sb) return launch_k<M, true, false>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, s);
-  if (sa) return launch_k<M, false, true>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, s);
-  return launch_k<M, false, false>(g, bt, at, x, U, y, r_v, r_m, r_y, qmax, s);
+#define WINO_ARGS g, bt, at, x, U, y, r_v, r_m, r_y, qmax, rv_pos, w_pos, s
+  if (sb && sa) return launch_k<M, true, true>(WINO_ARGS);
+  if (sb) return launch_k<M, true, false>(WINO_ARGS);
+  if (sa) return launch_k<M, false, true>(WINO_ARGS);
+  return launch_k<M, false, false>(WINO_ARGS);
+#undef WINO_ARGS
 }
 
 }  // namespace
@@ -175,11 +188,13 @@ bool fused_fwd_supported(const Geom& g) {
 
 hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                             const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
-                            hipStream_t s) {
+                            const PosScale* rv_pos, const PosScale* w_pos, hipStream_t s) {
   if (!fused_fwd_supported(g)) return hipErrorInvalidValue;
   if (g.m == 2)
-    return launch_m<2>(g, bt, at, (const int8_t*)x, (const int8_t*)U, y, r_v, r_m, r_y, qmax, s);
-  return launch_m<4>(g, bt, at, (const int8_t*)x, (const int8_t*)U, y, r_v, r_m, r_y, qmax, s);
+    return launch_m<2>(g, bt, at, (const int8_t*)x, (const int8_t*)U, y, r_v, r_m, r_y, qmax,
+                       rv_pos, w_pos, s);
+  return launch_m<4>(g, bt, at, (const int8_t*)x, (const int8_t*)U, y, r_v, r_m, r_y, qmax, rv_pos,
+                     w_pos, s);
 }
 
 }  // namespace wino

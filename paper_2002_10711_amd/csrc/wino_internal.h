@@ -95,7 +95,7 @@ bool fused_fwd_supported(const Geom& g);
 inline bool fused_fwd_generic_preferred(const Geom& g) { return g.Kp <= 64 && g.W >= 8; }
 hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                             const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
-                            hipStream_t s);
+                            const PosScale* rv_pos, const PosScale* w_pos, hipStream_t s);
 // Whole fp32 forward in one kernel; only where supported.
 bool fused_fwd_f32_supported(const Geom& g);
 hipError_t launch_fused_fwd_f32(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
