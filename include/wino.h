@@ -100,7 +100,8 @@ typedef struct {
    * Uq[p] = sat(rne(U[p] / s_u_pos[p])), and every accumulator is brought to real units
    * before the output transform, Mf[p] = (float)M[p] * (s_u_pos[p] * s_v_pos[p]), so that
    * y_q = sat(rne(Yt / s_y)) (with the Hadamard-stage quantizer: Mq = sat(rne(Mf / s_m)),
-   * y_q = sat(rne(Yt * s_m / s_y))).  The forward then runs as two or three kernels. */
+   * y_q = sat(rne(Yt * s_m / s_y))).  The kernel sequence is the same as with per-tensor
+   * scales. */
   const float* s_v_pos;
   const float* s_u_pos;
   /* One code range per quantizer (Sec. 3.2: each stage may be quantized to its own number
@@ -140,14 +141,13 @@ wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void*
                             const void* U_dev, void* y_dev, void* workspace_dev,
                             size_t workspace_bytes, void* stream);
 
-/* How many kernels wino_conv2d_fwd launches for this problem with per-tensor scales (0 if
- * the descriptor is invalid): 1 = input transform, GEMM and output transform in one
+/* How many kernels wino_conv2d_fwd launches for this problem (0 if the descriptor is
+ * invalid): 1 = input transform, GEMM and output transform in one
  * kernel (small layers; V and M never reach memory), 2 = input transform, then GEMM fused
  * with the output transform (M never reaches memory), 3 = input transform, tiled GEMM,
  * output transform (F(6x6,3x3) and F(4x4,3x3) with long reductions, channel counts whose
- * padding is not 64/128/256/512).  Per-position scales and the wide modes run as 2 or 3
- * kernels.  Reads d->BT / d->AT (HOST) if they are not NULL: which variant applies can
- * depend on them. */
+ * padding is not 64/128/256/512).  The wide modes run as 2 or 3 kernels.  Reads d->BT /
+ * d->AT (HOST) if they are not NULL: which variant applies can depend on them. */
 int wino_fwd_num_kernels(const wino_desc* d);
 
 /* The same forward, restricted to the stages named in `stages` (a mask of
