@@ -100,8 +100,8 @@ typedef struct {
    * Uq[p] = sat(rne(U[p] / s_u_pos[p])), and every accumulator is brought to real units
    * before the output transform, Mf[p] = (float)M[p] * (s_u_pos[p] * s_v_pos[p]), so that
    * y_q = sat(rne(Yt / s_y)) (with the Hadamard-stage quantizer: Mq = sat(rne(Mf / s_m)),
-   * y_q = sat(rne(Yt * s_m / s_y))).  The kernel sequence is the same as with per-tensor
-   * scales. */
+   * y_q = sat(rne(Yt * s_m / s_y))).  The kernel sequence is that of per-tensor
+   * scales, except that F(6x6,3x3) with at most 64 channels takes three kernels. */
   const float* s_v_pos;
   const float* s_u_pos;
   /* One code range per quantizer (Sec. 3.2: each stage may be quantized to its own number
