@@ -185,50 +185,64 @@ __global__ __launch_bounds__(256) void weight_transform_i8(Geom g, MatG mg,
                                                            const float* __restrict__ w,
                                                            uint32_t* __restrict__ U, PosScale ru,
                                                            float qmax) {
-  // One thread per (row i of U, k, channel quad); i is uniform per block (blockIdx.y)
-  // so the matrix entries stay in scalar registers.  Splitting the rows over threads
-  // gives this small, latency-bound kernel n times more wavefronts.
+  // One thread per (k, channel quad) and rows i = blockIdx.y, blockIdx.y + gridDim.y, ... of
+  // U; i is uniform per block, so the matrix entries stay in scalar registers.  Small layers
+  // are launched with one row per block (n times more wavefronts for a latency-bound
+  // kernel), large ones with all rows in one thread (the filters are read once).
+  // Lanes run over (channel quad & 3, k & 15, the rest): a wavefront's 64 dwords of one
+  // position are then 256 consecutive bytes of the blocked layout (see u_byte_index).
   constexpr int n = M + 2;
   const int cq_per = g.Cp >> 2;
-  const int i = blockIdx.y;
   const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
-  const int k = (int)(item / cq_per), cq = (int)(item % cq_per);
+  const int lo6 = (int)(item & 63);
+  const long long hi = item >> 6;                      // (k >> 4, cq >> 2), cq >> 2 fastest
+  const int cqh = (int)(hi % (cq_per >> 2)), kh = (int)(hi / (cq_per >> 2));
+  const int k = kh * 16 + (lo6 >> 2), cq = cqh * 4 + (lo6 & 3);
   if (k >= g.Kp) return;
-  uint32_t out[n];
+  float wv[4][9];
 #pragma unroll
-  for (int j = 0; j < n; ++j) out[j] = 0u;
-  if (k < g.K) {
-    const float gi0 = mg.v[i * 3 + 0], gi1 = mg.v[i * 3 + 1], gi2 = mg.v[i * 3 + 2];
+  for (int e = 0; e < 4; ++e) {
+    const int c = cq * 4 + e;
+    const bool ok = k < g.K && c < g.C;               // padding: zero filters give zero codes
+    const float* wp = w + ((size_t)(ok ? k : 0) * g.C + (ok ? c : 0)) * 9;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int c = cq * 4 + e;
-      if (c < g.C) {
-        const float* wp = w + ((size_t)k * g.C + c) * 9;
-        float t[3];
-#pragma unroll
-        for (int b = 0; b < 3; ++b) {        // t[b] = (G g)[i][b]
-          float acc = 0.0f;
-          acc = __builtin_fmaf(gi0, wp[0 * 3 + b], acc);
-          acc = __builtin_fmaf(gi1, wp[1 * 3 + b], acc);
-          acc = __builtin_fmaf(gi2, wp[2 * 3 + b], acc);
-          t[b] = acc;
-        }
-#pragma unroll
-        for (int j = 0; j < n; ++j) {        // U[i][j] = sum_b t[b] G[j][b]
-          float acc = 0.0f;
-#pragma unroll
-          for (int b = 0; b < 3; ++b) acc = __builtin_fmaf(t[b], mg.v[j * 3 + b], acc);
-          const int q = quantize(acc, ru.r[i * n + j], qmax);   // one factor per position
-          out[j] |= (uint32_t)(q & 0xff) << (8 * e);
-        }
-      }
+    for (int a = 0; a < 9; ++a) {
+      const float v = wp[a];
+      wv[e][a] = ok ? v : 0.0f;
     }
   }
-  // blocked layout (see u_byte_index): same place in every position's slab
   const size_t pstride = (size_t)g.Kp * cq_per;        // dwords per position
-  uint32_t* up = U + (size_t)i * n * pstride + u_byte_index(g.Kp, g.Cp, 1, 0, k, cq * 4) / 4;
+  uint32_t* ub = U + u_byte_index(g.Kp, g.Cp, 1, 0, k, cq * 4) / 4;
+  for (int i = blockIdx.y; i < n; i += gridDim.y) {
+    const float gi0 = mg.v[i * 3 + 0], gi1 = mg.v[i * 3 + 1], gi2 = mg.v[i * 3 + 2];
+    uint32_t out[n];
 #pragma unroll
-  for (int j = 0; j < n; ++j) up[j * pstride] = out[j];
+    for (int j = 0; j < n; ++j) out[j] = 0u;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float t[3];
+#pragma unroll
+      for (int b = 0; b < 3; ++b) {        // t[b] = (G g)[i][b]
+        float acc = 0.0f;
+        acc = __builtin_fmaf(gi0, wv[e][0 * 3 + b], acc);
+        acc = __builtin_fmaf(gi1, wv[e][1 * 3 + b], acc);
+        acc = __builtin_fmaf(gi2, wv[e][2 * 3 + b], acc);
+        t[b] = acc;
+      }
+#pragma unroll
+      for (int j = 0; j < n; ++j) {        // U[i][j] = sum_b t[b] G[j][b]
+        float acc = 0.0f;
+#pragma unroll
+        for (int b = 0; b < 3; ++b) acc = __builtin_fmaf(t[b], mg.v[j * 3 + b], acc);
+        const int q = quantize(acc, ru.r[i * n + j], qmax);   // one factor per position
+        out[j] |= (uint32_t)(q & 0xff) << (8 * e);
+      }
+    }
+    // blocked layout: same place in every position's slab
+    uint32_t* up = ub + (size_t)i * n * pstride;
+#pragma unroll
+    for (int j = 0; j < n; ++j) up[j * pstride] = out[j];
+  }
 }
 
 template <int M>
@@ -423,10 +437,12 @@ hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w
     for (int p = 0; p < 64; ++p) ru.r[p] = ru_pos ? ru_pos->r[p] : r_u;
     const unsigned nb = blocks_for((long long)g.Kp * (g.Cp / 4));
     uint32_t* Uo = (uint32_t*)U;
+    // rows per block: one for small layers; with many blocks, all rows in one thread
+    const unsigned ny = nb >= 1024 ? 1u : nb >= 256 ? 2u : (unsigned)g.n;
     switch (g.m) {
-      case 2: weight_transform_i8<2><<<dim3(nb, 4), 256, 0, s>>>(g, mg, w, Uo, ru, qmax); break;
-      case 4: weight_transform_i8<4><<<dim3(nb, 6), 256, 0, s>>>(g, mg, w, Uo, ru, qmax); break;
-      default: weight_transform_i8<6><<<dim3(nb, 8), 256, 0, s>>>(g, mg, w, Uo, ru, qmax); break;
+      case 2: weight_transform_i8<2><<<dim3(nb, ny), 256, 0, s>>>(g, mg, w, Uo, ru, qmax); break;
+      case 4: weight_transform_i8<4><<<dim3(nb, ny), 256, 0, s>>>(g, mg, w, Uo, ru, qmax); break;
+      default: weight_transform_i8<6><<<dim3(nb, ny), 256, 0, s>>>(g, mg, w, Uo, ru, qmax); break;
     }
   } else {
     const unsigned nb = blocks_for((long long)g.Kp * g.Cp);
