@@ -249,6 +249,23 @@ def test_random_shapes_int8_and_fp32(oracle, layer):
     _check_f32(oracle, case, run_gpu(case))
 
 
+@pytest.mark.parametrize("layer", _random_layers(24, 11), ids=lambda l: "%s_%dx%dx%dx%dx%d_m%d_p%d%s" % (
+    l.name, l.N, l.C, l.K, l.H, l.W, l.m, l.pad, "_flex" if l.flex_sigma else ""))
+def test_random_shapes_per_position_scales_and_m_quantizer(oracle, layer):
+    """Seeded random shapes with one scale per Winograd position and the Hadamard-stage
+    quantizer on: every int8 tap bit-exact on whichever kernel sequence the shape takes."""
+    case = make_case(oracle, layer, with_oracle=False)
+    sc = oracle.calibrate_pos(case["X"], case["g"], case["BT"], case["G"], case["AT"], pad=layer.pad)
+    case["xq"] = oracle.quantize_tensor(case["X"], sc["s_x"]).astype(np.int8)
+    ref = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc,
+                            pad=layer.pad)
+    peak = float(np.abs(ref["M"] * ref["scalars"]["w"][:, None, None]).max())
+    sc = dict(sc, s_m=max(peak, 1e-20) / 100.0)
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc,
+                                    pad=layer.pad)
+    _check_i8(case, run_gpu(case, scales=sc))
+
+
 def test_input_at_an_odd_address(oracle):
     """x need not be aligned: the staging falls back to unaligned dword loads."""
     import torch
