@@ -189,7 +189,8 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
     else:
         stages = [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
                   ("gemm_output", wb.WINO_STAGE_GEMM | wb.WINO_STAGE_OUTPUT)]
-    ksteps = max(20, min(steps, 200))
+    ksteps = max(20, min(steps, 2000))
+    kwarm = max(10, min(warmup, 500))
     # (the forward once, so that every stage finds its predecessor's output)
     wb.wino_transform_weights(desc, quant, gd, U, stream=stream)
     for _, mask in stages[1:]:
@@ -208,7 +209,7 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
             else:
                 fn = lambda mask=mask: wb.wino_conv2d_fwd_stages(desc, quant, x, U, y, ws, mask,
                                                                  stream=stream)
-            acc[name] = timed(fn, ksteps - ksteps % 10, 10) * 1e3
+            acc[name] = timed(fn, ksteps - ksteps % 10, kwarm) * 1e3
         return acc
 
     acc = time_stages(stages)
@@ -392,8 +393,8 @@ def cpu_leg(L):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=5000)
+    ap.add_argument("--warmup", type=int, default=2000)
     ap.add_argument("--workload", default="cfg2_i8")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host "
                     "instead of replaying a captured HIP graph of one step")
