@@ -198,20 +198,21 @@ __global__ __launch_bounds__(256) void input_transform_w16(Geom g, MatBT bt,
   }
   float Vf[n][n];
   transform_patch<M, kSparse>(d, bt, Vf);
-  float code[P];
+  // The code c sits in the low 16 bits of the quantizer's bit pattern (two's complement);
+  // its digits as bytes: a = floor(c / 256) is byte 1, b = c mod 256 - 128 is byte 0 with
+  // its top bit flipped.
+  uint32_t code[P];
+  const float qlo = kMagic - qmax, qhi = kMagic + qmax;
 #pragma unroll
   for (int i = 0; i < n; ++i)
 #pragma unroll
-    for (int k = 0; k < n; ++k) code[i * n + k] = quantize_f(Vf[i][k], rv.r[i * n + k], qmax);
+    for (int k = 0; k < n; ++k) code[i * n + k] = quantize_bits(Vf[i][k], rv.r[i * n + k], qlo, qhi);
 #pragma unroll
   for (int digit = 0; digit < 2; ++digit) {
     if (digit) __syncthreads();                        // the first plane has left LDS
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
-      int a, b;
-      split_code(code[p], a, b);
-      sm[(p * 8 + r) * kPitch + cc] = (int8_t)(digit ? b : a);
-    }
+    for (int p = 0; p < P; ++p)
+      sm[(p * 8 + r) * kPitch + cc] = (int8_t)(digit ? (code[p] ^ 0x80u) : (code[p] >> 8));
     __syncthreads();
     // P * 8 rows of 32 channels = P * 16 pieces of 16 bytes
     for (int idx = tid; idx < P * 16; idx += 256) {
