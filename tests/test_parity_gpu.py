@@ -316,6 +316,27 @@ def test_config4_flex_int8_full(oracle):
     _check_i8(case, run_gpu(case))
 
 
+@pytest.mark.parametrize("layer", [l for l in workloads.config5() if l.stride == 1],
+                         ids=lambda l: l.name)
+def test_config5_full_batch_first_and_last_images(oracle, layer):
+    """The stack's Winograd layers at the benchmarked batch of 256, so that every kernel runs
+    in the launch configuration that is timed; the oracle computes the first and the last
+    eight images (tiles do not interact across the batch), scales calibrated on the first
+    eight."""
+    X, g = workloads.make_inputs(layer)
+    BT, G, AT = oracle.cook_toom(layer.m, dtype=np.float32)
+    sc = oracle.calibrate(X[:8], g, BT, G, AT, pad=layer.pad)
+    xq = oracle.quantize_tensor(X, sc["s_x"]).astype(np.int8)
+    case = dict(layer=layer, X=X, g=g, BT=BT, G=G, AT=AT, scales=sc, xq=xq)
+    out = run_gpu(case, taps=False)
+    for sl in (slice(0, 8), slice(layer.N - 8, layer.N)):
+        ref = oracle.winograd_q(xq[sl], g, BT, G, AT, sc, pad=layer.pad)
+        for key in ("Y", "Y_staged"):
+            bad = int((out[key][sl] != ref["Yq"]).sum())
+            assert bad == 0, "%s images %s: %d codes differ" % (key, sl, bad)
+    assert np.abs(out["Y"]).max() >= 100
+
+
 def test_determinism(oracle):
     case = make_case(oracle, Layer("det", 4, 64, 64, 16, 16, m=4, seed=111), with_oracle=False)
     a, b = run_gpu(case), run_gpu(case)
