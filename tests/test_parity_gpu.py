@@ -94,6 +94,8 @@ SMALL = [
     Layer("s_f2_c200_k40_8649tiles", 9, 200, 40, 62, 62, m=2, seed=162),
     Layer("s_f4_c450_k40_2048tiles", 2, 450, 40, 126, 126, m=4, seed=163),
     Layer("s_f4_c500_k70_600tiles", 6, 500, 70, 38, 40, m=4, seed=164),   # F4, 512 channels, one block
+    Layer("s_f6_c200_k40_1100tiles", 11, 200, 40, 60, 58, m=6, seed=168),  # F6, long reduction, many tiles
+    Layer("s_f6_c400_k70_1024tiles", 16, 400, 70, 48, 48, m=6, seed=169),
 ]
 
 
