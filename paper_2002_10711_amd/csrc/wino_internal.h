@@ -93,7 +93,12 @@ hipError_t launch_gemm_out_col(const Geom& g, const MatAT& at, const void* V, co
 bool fused_fwd_supported(const Geom& g);
 // ... and worth it with the vector-ALU input transform, which a second block of output
 // channels would have to repeat in full.
-inline bool fused_fwd_generic_preferred(const Geom& g) { return g.Kp <= 64 && g.W >= 8; }
+// Measured against the separate input stage plus GEMM + output kernel: a single block of
+// input channels always wins; two blocks only for F2 with few tiles (12.5 vs 16.9 us at 4 k
+// tiles, 44 vs 37 at 16 k); longer reductions lose (F4, 256 channels: 44.5 vs 28.6 us).
+inline bool fused_fwd_generic_preferred(const Geom& g) {
+  return g.Kp <= 64 && g.W >= 8 && (g.Cp == 64 || (g.m == 2 && g.Cp == 128 && g.T < 8192));
+}
 hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                             const void* U, void* y, float r_v, float r_m, float r_y, float qmax,
                             const PosScale* rv_pos, const PosScale* w_pos, hipStream_t s);
