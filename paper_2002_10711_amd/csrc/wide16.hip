@@ -663,11 +663,14 @@ hipError_t launch_w16_output(const Geom& g, const MatAT& at, const void* M, void
 }
 
 // GEMM + output in one kernel: 64..512 padded channels in powers of two, every offset in
-// 32 bits.
+// 32 bits -- and enough tiles: with few, its long workgroups leave most of the chip idle and
+// the two separate kernels measure faster (64 tiles: 18.0 vs 12.7 us at 64 channels, 28.8 vs
+// 18.3 at 256; F6 at 288 tiles 51.6 vs 33.7; from 512 tiles on the fused kernel wins).
 bool w16_gemm_out_supported(const Geom& g, const MatAT&) {
   const bool nch_ok = g.Cp == 64 || g.Cp == 128 || g.Cp == 256 || g.Cp == 512;
   // (the per-thread part of a V address, up to two digit planes, must fit 32 bits)
-  return nch_ok && g.Kp / 64 <= 65535 && (size_t)g.Tp * g.Cp * 2 < 0xffffffffull;
+  return nch_ok && g.T >= (g.m == 6 ? 1024 : 512) && g.Kp / 64 <= 65535 &&
+         (size_t)g.Tp * g.Cp * 2 < 0xffffffffull;
 }
 
 namespace {

@@ -102,7 +102,13 @@ LAYERS = [
     Layer("w_f4_c600", 1, 600, 40, 8, 8, m=4, seed=306),          # beyond 512 channels
     Layer("w_f2_1px", 5, 3, 5, 1, 1, m=2, seed=307),              # a single output pixel
     Layer("w_f2_16k_tiles", 64, 16, 24, 32, 32, m=2, seed=309),   # two tile groups per workgroup
+    # enough tiles for the GEMM + output kernel (512; 1024 for F6), every reduction length
+    Layer("w_f4_600tiles_ragged", 6, 37, 70, 38, 40, m=4, seed=310),
+    Layer("w_f6_c100_1100tiles", 11, 100, 40, 60, 58, m=6, seed=311),
+    Layer("w_f2_c200_630tiles", 3, 200, 40, 28, 30, m=2, seed=312),
+    Layer("w_f4_c450_512tiles_flex", 2, 450, 24, 64, 64, m=4, flex_sigma=0.03, seed=313),
 ]
+FUSED = LAYERS[-4:]
 
 
 @pytest.mark.parametrize("layer", LAYERS, ids=lambda l: l.name)
@@ -113,7 +119,7 @@ def test_wide_stages_all_taps(oracle, layer, qm):
     check(ref, run_wide(case, qm, sc))
 
 
-@pytest.mark.parametrize("layer", LAYERS[:5], ids=lambda l: l.name)
+@pytest.mark.parametrize("layer", LAYERS[:5] + FUSED[1:3], ids=lambda l: l.name)
 @pytest.mark.parametrize("qm", [INT16, MIXED], ids=["int16", "mixed"])
 def test_wide_stages_with_hadamard_quantizer(oracle, layer, qm):
     case, sc, ref = wide_case(oracle, layer, qm, with_m=True)
@@ -121,7 +127,7 @@ def test_wide_stages_with_hadamard_quantizer(oracle, layer, qm):
     check(ref, run_wide(case, qm, sc))
 
 
-@pytest.mark.parametrize("layer", LAYERS[:4], ids=lambda l: l.name)
+@pytest.mark.parametrize("layer", LAYERS[:4] + FUSED[:2], ids=lambda l: l.name)
 @pytest.mark.parametrize("qm", [INT16, W16], ids=["int16", "i8w16"])
 def test_wide_stages_per_position_scales(oracle, layer, qm):
     case, sc, ref = wide_case(oracle, layer, qm, pos=True)
