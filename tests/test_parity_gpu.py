@@ -122,6 +122,10 @@ def test_flex_small_int8_and_fp32(oracle):
     L4 = Layer("flex_small4", 2, 24, 40, 10, 10, m=4, flex_sigma=0.05, seed=109)
     case = make_case(oracle, L4)
     _check_i8(case, run_gpu(case))
+    # two blocks of input channels through the vector-ALU one-kernel forward (F2, few tiles)
+    L2 = Layer("flex_f2_c100", 2, 100, 40, 12, 12, m=2, flex_sigma=0.03, seed=170)
+    case = make_case(oracle, L2)
+    _check_i8(case, run_gpu(case))
 
 
 def test_saturation_and_m_quantizer(oracle):
