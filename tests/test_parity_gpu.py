@@ -95,7 +95,13 @@ SMALL = [
     Layer("s_f4_c450_k40_2048tiles", 2, 450, 40, 126, 126, m=4, seed=163),
     Layer("s_f4_c500_k70_600tiles", 6, 500, 70, 38, 40, m=4, seed=164),   # F4, 512 channels, one block
     Layer("s_f6_c200_k40_1100tiles", 11, 200, 40, 60, 58, m=6, seed=168),  # F6, long reduction, many tiles
-    Layer("s_f6_c400_k70_1024tiles", 16, 400, 70, 48, 48, m=6, seed=169),
+    Layer("s_f6_c500_k70_1024tiles", 16, 500, 70, 48, 48, m=6, seed=169),
+    Layer("s_f2_c200_k130_8649tiles", 9, 200, 130, 62, 62, m=2, seed=171),   # K > 128: two kernels
+    # learned (dense) matrices with long reductions: the dense variants of the GEMM + output kernel
+    Layer("s_flex_f4_c200_k70", 8, 200, 70, 16, 16, m=4, flex_sigma=0.02, seed=172),
+    Layer("s_flex_f2_c500_k70", 2, 500, 70, 12, 12, m=2, flex_sigma=0.02, seed=173),
+    Layer("s_flex_f6_c200_k40_1100tiles", 11, 200, 40, 60, 58, m=6, flex_sigma=0.01, seed=174),
+    Layer("s_flex_f4_c450_k40_512tiles", 2, 450, 40, 64, 64, m=4, flex_sigma=0.02, seed=175),
 ]
 
 

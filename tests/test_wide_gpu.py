@@ -107,8 +107,12 @@ LAYERS = [
     Layer("w_f6_c100_1100tiles", 11, 100, 40, 60, 58, m=6, seed=311),
     Layer("w_f2_c200_630tiles", 3, 200, 40, 28, 30, m=2, seed=312),
     Layer("w_f4_c450_512tiles_flex", 2, 450, 24, 64, 64, m=4, flex_sigma=0.03, seed=313),
+    Layer("w_f4_c100_576tiles", 4, 100, 24, 48, 48, m=4, seed=314),
+    Layer("w_f4_c200_576tiles", 4, 200, 24, 48, 48, m=4, seed=315),
+    Layer("w_f2_c100_576tiles", 4, 100, 24, 24, 24, m=2, seed=316),
+    Layer("w_f6_c40_1024tiles", 16, 40, 24, 48, 48, m=6, seed=317),
 ]
-FUSED = LAYERS[-4:]
+FUSED = LAYERS[-8:-4]
 
 
 @pytest.mark.parametrize("layer", LAYERS, ids=lambda l: l.name)
