@@ -148,16 +148,15 @@ hipError_t launch_k(const Geom& g, const MatBT& bt, const MatAT& at, const int8_
 #define WINO_LAUNCH_FUSED1(WIDE, FAST, ONE)                                           \
   fused_fwd_i8_kernel<M, kSparseB, kSparseA, WIDE, FAST, ONE><<<grid, 256, lb, s>>>(   \
       g, bt, at, x, U, y, r_v, r_m, r_y, qmax, RB, TWB, pos, rv, w)
+  // What the dispatch sends here (fused_fwd_generic_preferred): images at least 8 wide, one
+  // block of input channels, or two for F2 -- nothing else is instantiated.
+  if (g.W < 8 || (g.Cp != 64 && !(M == 2 && g.Cp == 128))) return hipErrorInvalidValue;
 #define WINO_LAUNCH_FUSED(WIDE, FAST)                                                 \
   do { if (g.Cp == 64) WINO_LAUNCH_FUSED1(WIDE, FAST, true);                          \
-       else WINO_LAUNCH_FUSED1(WIDE, FAST, false); } while (0)
+       else if constexpr (M == 2) WINO_LAUNCH_FUSED1(WIDE, FAST, false); } while (0)
   // whole tiles and K % 4 == 0: no guards on the output side
   const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
-  if (g.W >= 4) {
-    if (fast) WINO_LAUNCH_FUSED(true, true); else WINO_LAUNCH_FUSED(true, false);
-  } else {
-    WINO_LAUNCH_FUSED(false, false);
-  }
+  if (fast) WINO_LAUNCH_FUSED(true, true); else WINO_LAUNCH_FUSED(true, false);
 #undef WINO_LAUNCH_FUSED
 #undef WINO_LAUNCH_FUSED1
   return hipGetLastError();
