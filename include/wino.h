@@ -71,7 +71,7 @@ typedef enum {
  *            arrays, U, V and the Hadamard-stage quantizer may use up to 16 bits.
  * The two wide modes accept one code range per stage (wino_quant.qmax_*), need C <= 1024,
  * and run as two kernels (input transform; GEMM fused with the output transform) or, for
- * channel counts whose padding is not 64/128/256/512, three. */
+ * layers with few tiles and channel counts whose padding is not 64/128/256/512, three. */
 typedef enum { WINO_F32 = 0, WINO_I8 = 1, WINO_I16 = 2, WINO_I8W16 = 3 } wino_dtype;
 
 /* One layer problem.  BT is n x n, G is n x 3, AT is m x n, row-major, HOST. */
@@ -145,8 +145,8 @@ wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void*
  * invalid): 1 = input transform, GEMM and output transform in one
  * kernel (small layers; V and M never reach memory), 2 = input transform, then GEMM fused
  * with the output transform (M never reaches memory), 3 = input transform, tiled GEMM,
- * output transform (F(6x6,3x3) and F(4x4,3x3) with long reductions, channel counts whose
- * padding is not 64/128/256/512).  The wide modes run as 2 or 3 kernels.  Reads d->BT /
+ * output transform (F(6x6,3x3) and F(4x4,3x3) with long reductions and few tiles, more
+ * than 512 input channels).  The wide modes run as 2 or 3 kernels.  Reads d->BT /
  * d->AT (HOST) if they are not NULL: which variant applies can depend on them. */
 int wino_fwd_num_kernels(const wino_desc* d);
 

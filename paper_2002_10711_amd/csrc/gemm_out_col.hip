@@ -245,7 +245,11 @@ hipError_t launch_ms(const Geom& g, const MatAT& at, const void* V, const void* 
       switch (g.Cp) {
         case 64: WINO_COL_GO6(1); break;
         case 128: WINO_COL_GO6(2); break;
+        case 192: WINO_COL_GO6(3); break;
         case 256: WINO_COL_GO6(4); break;
+        case 320: WINO_COL_GO6(5); break;
+        case 384: WINO_COL_GO6(6); break;
+        case 448: WINO_COL_GO6(7); break;
         default: WINO_COL_GO6(8); break;
       }
 #undef WINO_COL_GO6
@@ -255,7 +259,11 @@ hipError_t launch_ms(const Geom& g, const MatAT& at, const void* V, const void* 
   switch (g.Cp) {
     case 64: WINO_COL_GO(1); break;
     case 128: WINO_COL_GO(2); break;
+    case 192: WINO_COL_GO(3); break;
     case 256: WINO_COL_GO(4); break;
+    case 320: WINO_COL_GO(5); break;
+    case 384: WINO_COL_GO(6); break;
+    case 448: WINO_COL_GO(7); break;
     default: WINO_COL_GO(8); break;
   }
 #undef WINO_COL_GO2
@@ -274,7 +282,7 @@ hipError_t launch_m(const Geom& g, const MatAT& at, const void* V, const void* U
 }  // namespace
 
 bool gemm_out_col_supported(const Geom& g) {
-  const bool nch_ok = g.Cp == 64 || g.Cp == 128 || g.Cp == 256 || g.Cp == 512;
+  const bool nch_ok = g.Cp % 64 == 0 && g.Cp >= 64 && g.Cp <= 512;
   // (the per-thread part of a V address must fit 32 bits)
   return g.i8 && nch_ok && g.Kp / 64 <= 65535 && (size_t)g.Tp * g.Cp < 0xffffffffull;
 }

@@ -70,19 +70,19 @@ inline bool gemm_out_preferred(const Geom& g) {
 }
 hipError_t launch_gemm_out(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                            float r_m, float r_y, float qmax, hipStream_t s);
-// The same for long int8 reductions (64 .. 512 padded channels; per-tensor or per-position
-// scales): column-by-column output transform, V shared through LDS.
+// The same for long int8 reductions (64 .. 512 padded channels in steps of 64; per-tensor
+// or per-position scales): column-by-column output transform, V shared through LDS.
 bool gemm_out_col_supported(const Geom& g);
 // ... and faster than both alternatives (gemm_out_kernel; tiled GEMM + output transform):
-// measured for m = 2 at every supported reduction, for m = 4 up to 128 channels, at 256 from
-// 128 tiles and at 512 from 512 tiles up, for m = 6 at 128 .. 512 channels from 1 k tiles up;
-// elsewhere the few, long workgroups lose to the LDS-tiled GEMM, and gemm_out_kernel keeps
-// m = 6 at 64 channels.
+// measured for m = 2 at every supported reduction, for m = 4 up to 128 channels, up to 256
+// from 128 tiles and beyond from 512 tiles up, for m = 6 at 128 .. 512 channels from 1 k
+// tiles up; elsewhere the few, long workgroups lose to the LDS-tiled GEMM, and
+// gemm_out_kernel keeps m = 6 at 64 channels.
 inline bool gemm_out_col_preferred(const Geom& g) {
   if (!gemm_out_col_supported(g)) return false;
   if (g.m == 2) return true;
   // (F4 with long reductions and few tiles: too few workgroups, the tiled GEMM is faster)
-  if (g.m == 4) return g.Cp <= 128 || (g.Cp == 256 ? g.T >= 128 : g.T >= 512);
+  if (g.m == 4) return g.Cp <= 128 || (g.Cp <= 256 ? g.T >= 128 : g.T >= 512);
   // (m = 6: from 128 channels, and only with enough tiles to fill the machine)
   return g.Cp >= 128 && g.T >= 1024;
 }

@@ -102,6 +102,13 @@ SMALL = [
     Layer("s_flex_f2_c500_k70", 2, 500, 70, 12, 12, m=2, flex_sigma=0.02, seed=173),
     Layer("s_flex_f6_c200_k40_1100tiles", 11, 200, 40, 60, 58, m=6, flex_sigma=0.01, seed=174),
     Layer("s_flex_f4_c450_k40_512tiles", 2, 450, 40, 64, 64, m=4, flex_sigma=0.02, seed=175),
+    # reductions of 3, 5, 6 and 7 blocks of 64 channels
+    Layer("s_f4_c150_k140", 4, 150, 140, 16, 16, m=4, seed=176),
+    Layer("s_f2_c300_k140", 2, 300, 140, 12, 14, m=2, seed=177),
+    Layer("s_f4_c370_k70_576tiles", 4, 370, 70, 48, 48, m=4, seed=178),
+    Layer("s_f2_c420_k130", 3, 420, 130, 9, 11, m=2, seed=179),
+    Layer("s_f6_c300_k40_1100tiles", 11, 300, 40, 60, 58, m=6, seed=180),
+    Layer("s_flex_f2_c170_k40", 3, 170, 40, 10, 10, m=2, flex_sigma=0.02, seed=181),
 ]
 
 
