@@ -256,3 +256,25 @@ def test_bench_algorithmic_work_of_config2():
     w = bench.algorithmic(Lw, np.asarray(BT), np.asarray(AT))
     assert w["gemm_output"]["bytes"] == 2 * (v + u + y) and w["gemm"]["bytes"] == 2 * (v + u) + 2 * m
     assert w["gemm"]["ops"] == 4 * 1207959552
+
+
+def test_kernel_sequences_of_the_named_workloads():
+    """Which kernel sequence the forward takes for the benchmark's workloads (decided on the
+    host from the descriptor alone, so no GPU is needed): one kernel for the 64- and
+    128-channel F2/F4 layers, two (input stage, GEMM + output) for long reductions and for
+    the 16-bit stages, three where few tiles or F(6x6,3x3) leave the tiled GEMM ahead."""
+    from paper_2002_10711_amd import binding as wb, workloads
+    dt = {"i8": wb.WINO_I8, "f32": wb.WINO_F32, "i16": wb.WINO_I16, "i8w16": wb.WINO_I8W16}
+
+    def nk(L):
+        BT, G, AT = wb.wino_cook_toom(L.m)
+        return wb.wino_fwd_num_kernels(wb.Desc(L.N, L.C, L.K, L.H, L.W, L.pad, L.m, dt[L.dtype],
+                                               BT=BT, G=G, AT=AT))
+    assert nk(workloads.config1()[0]) == 1
+    assert nk(workloads.config2("i8")[0]) == 1 and nk(workloads.config2("f32")[0]) == 1
+    assert nk(workloads.config2("i16")[0]) == 2 and nk(workloads.config2("i8w16")[0]) == 2
+    c3 = {L.name: nk(L) for L in workloads.config3()}
+    assert c3 == {"cfg3_c256_s8_F2": 2, "cfg3_c256_s8_F4": 2, "cfg3_c512_s4_F2": 2,
+                  "cfg3_c512_s4_F4": 3}
+    c5 = {L.name: nk(L) for L in workloads.config5() if L.stride == 1}
+    assert [c5[k] for k in sorted(c5)] == [1, 2, 1, 1, 2, 1, 1, 2, 2, 2, 3, 3, 2]
