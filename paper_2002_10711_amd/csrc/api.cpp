@@ -319,7 +319,11 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
     return WINO_E_HIP;
   // (per-position scales: the accumulators need their factors before the output
   // transform, which only the stand-alone output kernel applies)
-  if (s_mm && s_out && gemm_out_col_preferred(g)) {
+  if (s_mm && s_out && gemm_out_lds_preferred(g)) {
+    // F(2x2,3x3), 512 channels, many tiles: the same fusion with squarer workgroup tiles
+    if (launch_gemm_out_lds(g, at, V, U_dev, y_dev, wp, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+      return WINO_E_HIP;
+  } else if (s_mm && s_out && gemm_out_col_preferred(g)) {
     // GEMM and output transform in one kernel for any reduction length (and with
     // per-position scales): M stays in registers
     if (launch_gemm_out_col(g, at, V, U_dev, y_dev, wp, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)

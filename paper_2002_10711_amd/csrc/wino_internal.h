@@ -89,6 +89,16 @@ inline bool gemm_out_col_preferred(const Geom& g) {
 hipError_t launch_gemm_out_col(const Geom& g, const MatAT& at, const void* V, const void* U,
                                void* y, const PosScale* w_pos, float r_m, float r_y, float qmax,
                                hipStream_t s);
+// The same for F(2x2,3x3) with 512 padded input channels: workgroup tiles of 32 tiles x 64
+// channels (fewer operand bytes per compute unit), 32x32x32 MFMAs.  Measured faster than
+// gemm_out_col_kernel from 1 k tiles up (512 -> 512 channels at 4 x 4, batch 256: 20.0 ->
+// 15.8 us); with fewer tiles its 32 x 64 blocks leave compute units idle (512 tiles: 14.0
+// vs 13.1 us).
+bool gemm_out_lds_supported(const Geom& g);
+inline bool gemm_out_lds_preferred(const Geom& g) { return gemm_out_lds_supported(g) && g.T >= 1024; }
+hipError_t launch_gemm_out_lds(const Geom& g, const MatAT& at, const void* V, const void* U,
+                               void* y, const PosScale* w_pos, float r_m, float r_y, float qmax,
+                               hipStream_t s);
 // Whole int8 forward in one kernel (neither V nor M stored); only where supported.
 bool fused_fwd_supported(const Geom& g);
 // ... and worth it with the vector-ALU input transform, which a second block of output

@@ -109,6 +109,11 @@ SMALL = [
     Layer("s_f2_c420_k130", 3, 420, 130, 9, 11, m=2, seed=179),
     Layer("s_f6_c300_k40_1100tiles", 11, 300, 40, 60, 58, m=6, seed=180),
     Layer("s_flex_f2_c170_k40", 3, 170, 40, 10, 10, m=2, flex_sigma=0.02, seed=181),
+    # F2, 512 padded channels, >= 1 k tiles: GEMM + output kernel with 32 x 64 workgroup tiles
+    Layer("s_f2_c500_k72_7px_1024tiles", 64, 500, 72, 7, 7, m=2, seed=182),    # ragged tiles, K = 64 + 8
+    Layer("s_f2_c512_k128_4px_1024tiles", 256, 512, 128, 4, 4, m=2, seed=183),  # whole images: staged stores
+    Layer("s_f2_c450_k64_8px_1040tiles", 65, 450, 64, 8, 8, m=2, seed=184),     # last tile block half empty
+    Layer("s_flex_f2_c512_k70_1024tiles", 16, 512, 70, 16, 16, m=2, flex_sigma=0.02, seed=185),
 ]
 
 
@@ -198,6 +203,7 @@ def test_many_tiles_ragged_flex_and_m_quantizer(oracle, m):
     Layer("pos_f2_c128_k64", 2, 128, 64, 12, 12, m=2, seed=139),
     Layer("pos_f4_7px", 5, 24, 20, 7, 7, m=4, seed=140),
     Layer("pos_f2_2px", 9, 64, 40, 2, 2, m=2, seed=165),
+    Layer("pos_f2_c512_k64_1024tiles", 64, 512, 64, 8, 8, m=2, seed=186),   # 32 x 64 workgroup tiles
 ], ids=lambda l: l.name)
 def test_per_position_scales_all_taps(oracle, layer):
     """One quantizer scale per Winograd position for V and U (Sec. 6), calibrated by the
