@@ -18,7 +18,8 @@
  * Conventions common to all entry points
  *   - Pointers named *_dev are DEVICE pointers, everything else is HOST memory.
  *   - The caller owns all buffers.  The library allocates and frees nothing on
- *     the device and keeps no state between calls.
+ *     the device and keeps no state between calls (the one exception is the
+ *     built-in scratch buffer of wino_conv2d_fwd_noalloc, described there).
  *   - Matrices in a wino_desc are read on the host during the call and passed to
  *     the kernels by value; the caller may change them as soon as the call
  *     returns.
@@ -59,7 +60,9 @@ typedef enum {
                              missing; or a matrix entry is not finite            */
   WINO_E_WORKSPACE = -6,  /* workspace smaller than wino_workspace_bytes()       */
   WINO_E_HIP = -7,        /* a HIP call or kernel launch failed                  */
-  WINO_E_BAD_ARG = -8     /* other invalid argument (stride, tap selector, ...)  */
+  WINO_E_BAD_ARG = -8,    /* other invalid argument (stride, tap selector, ...)  */
+  WINO_E_SCRATCH_LIMIT = -9 /* wino_conv2d_fwd_noalloc: the problem needs more scratch
+                             than WINO_NOALLOC_SCRATCH_BYTES                      */
 } wino_status;
 
 /* WINO_F32   float everywhere, no quantizer.
@@ -140,6 +143,22 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q,
 wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void* x_dev,
                             const void* U_dev, void* y_dev, void* workspace_dev,
                             size_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: wino_conv2d_fwd without the workspace
+ * argument.  V and M live in a buffer of WINO_NOALLOC_SCRATCH_BYTES that is part of the
+ * library's device image (every GPU the library runs on holds one copy until the process
+ * ends); the call allocates and frees nothing.  Same kernels, same results and same
+ * argument checks as wino_conv2d_fwd.  The buffer only has to hold what the problem's
+ * kernel sequence touches (nothing for one kernel, V for two, V and M for three, see
+ * wino_fwd_num_kernels); a problem that needs more returns WINO_E_SCRATCH_LIMIT before
+ * anything is launched.  All calls on one GPU share that GPU's buffer: calls that overlap
+ * in time on one GPU (different streams, or a captured graph replayed next to eager calls)
+ * race on it.  The first call on a device looks the buffer's address up
+ * (hipGetSymbolAddress) and must therefore happen outside stream capture. */
+#define WINO_NOALLOC_SCRATCH_BYTES (32u << 20)
+wino_status wino_conv2d_fwd_noalloc(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                                    const void* U_dev, void* y_dev, void* stream);
 
 /* How many kernels wino_conv2d_fwd launches for this problem (0 if the descriptor is
  * invalid): 1 = input transform, GEMM and output transform in one

@@ -17,7 +17,8 @@ WINO_STAGE_INPUT, WINO_STAGE_GEMM, WINO_STAGE_OUTPUT, WINO_STAGE_ALL = 1, 2, 4, 
 
 EXPORTS = [
     "wino_status_string", "wino_weights_bytes", "wino_workspace_bytes",
-    "wino_transform_weights", "wino_conv2d_fwd", "wino_conv2d_fwd_stages", "wino_fwd_num_kernels",
+    "wino_transform_weights", "wino_conv2d_fwd", "wino_conv2d_fwd_noalloc",
+    "wino_conv2d_fwd_stages", "wino_fwd_num_kernels",
     "wino_debug_export", "wino_debug_mfma_loop", "wino_cook_toom",
     "conv2d_ref_packed_weights_bytes", "conv2d_ref_workspace_bytes",
     "conv2d_ref_pack_weights", "conv2d_ref_gpu",
@@ -69,6 +70,9 @@ def lib():
         L.wino_conv2d_fwd.argtypes = [ctypes.POINTER(WinoDesc), ctypes.POINTER(WinoQuant),
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.wino_conv2d_fwd_noalloc.argtypes = [ctypes.POINTER(WinoDesc), ctypes.POINTER(WinoQuant),
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_void_p]
         L.wino_conv2d_fwd_stages.argtypes = [ctypes.POINTER(WinoDesc), ctypes.POINTER(WinoQuant),
                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                              ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
@@ -171,6 +175,15 @@ def wino_conv2d_fwd(desc, quant, x_dev, U_dev, y_dev, workspace_dev, workspace_b
     _check(lib().wino_conv2d_fwd(desc.ref, q, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev),
                                  _ptr(workspace_dev), workspace_bytes, _stream(stream)),
            "wino_conv2d_fwd")
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def wino_conv2d_fwd_noalloc(desc, quant, x_dev, U_dev, y_dev, stream=None):
+    q = ctypes.byref(quant) if quant is not None else None
+    _check(lib().wino_conv2d_fwd_noalloc(desc.ref, q, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev),
+                                         _stream(stream)), "wino_conv2d_fwd_noalloc")
 
 
 def wino_fwd_num_kernels(desc):

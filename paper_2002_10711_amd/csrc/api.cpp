@@ -175,6 +175,7 @@ const char* wino_status_string(wino_status s) {
     case WINO_E_WORKSPACE: return "workspace too small or misaligned";
     case WINO_E_HIP: return "HIP error";
     case WINO_E_BAD_ARG: return "bad argument";
+    case WINO_E_SCRATCH_LIMIT: return "problem needs more scratch than the built-in buffer holds";
   }
   return "unknown status";
 }
@@ -243,23 +244,56 @@ int wino_fwd_num_kernels(const wino_desc* d) {
   return (gemm_out_col_preferred(g) || gemm_out_preferred(g)) ? 2 : 3;
 }
 
-wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
-                                   const void* U_dev, void* y_dev, void* workspace_dev,
-                                   size_t workspace_bytes, int stages, void* stream) {
+}  // extern "C"
+
+namespace wino {
+
+// Bytes of workspace the kernel sequence of this problem really touches: nothing for the
+// one-kernel forward, V for two kernels, V and M for three.
+size_t fwd_workspace_touched(const wino_desc* d) {
   Geom g;
+  if (make_geom(d, &g) != WINO_OK) return 0;
+  const int nk = wino_fwd_num_kernels(d);
+  return nk <= 1 ? 0 : nk == 2 ? v_bytes(g) : v_bytes(g) + m_bytes(g);
+}
+
+// The forward behind wino_conv2d_fwd_stages.  exact_need: the workspace only has to hold
+// what the kernel sequence touches (fwd_workspace_touched) instead of V and M.
+// Every argument check of the forward that needs no workspace: descriptor, pointers of the
+// selected stages, matrices, quantizer.  Fills the geometry.
+wino_status fwd_check(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                      const void* U_dev, const void* y_dev, int stages, Geom* gp) {
+  Geom& g = *gp;
   wino_status st = make_geom(d, &g);
   if (st != WINO_OK) return st;
   if (stages < 1 || stages > WINO_STAGE_ALL) return WINO_E_BAD_ARG;
   const bool s_in = stages & WINO_STAGE_INPUT, s_mm = stages & WINO_STAGE_GEMM,
              s_out = stages & WINO_STAGE_OUTPUT;
-  if (!workspace_dev || (s_in && (!d->BT || !x_dev)) || (s_mm && !U_dev) ||
-      (s_out && (!d->AT || !y_dev)))
+  if ((s_in && (!d->BT || !x_dev)) || (s_mm && !U_dev) || (s_out && (!d->AT || !y_dev)))
     return WINO_E_NULL;
   if ((s_in && !finite_all(d->BT, g.n * g.n)) || (s_out && !finite_all(d->AT, g.m * g.n)))
     return WINO_E_BAD_SCALE;
   if ((st = check_quant(g, q)) != WINO_OK) return st;
-  if (workspace_bytes < v_bytes(g) + m_bytes(g) || !aligned256(workspace_dev) ||
-      (s_mm && !aligned256(U_dev)))
+  if (g.w16 && g.x16 && ((s_in && ((uintptr_t)x_dev & 1)) || (s_out && ((uintptr_t)y_dev & 1))))
+    return WINO_E_BAD_ARG;
+  return WINO_OK;
+}
+
+wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                       const void* U_dev, void* y_dev, void* workspace_dev,
+                       size_t workspace_bytes, int stages, void* stream, bool exact_need) {
+  Geom g;
+  if (!workspace_dev && d && make_geom(d, &g) == WINO_OK && stages >= 1 &&
+      stages <= WINO_STAGE_ALL)
+    return WINO_E_NULL;
+  wino_status st = fwd_check(d, q, x_dev, U_dev, y_dev, stages, &g);
+  if (st != WINO_OK) return st;
+  const bool s_in = stages & WINO_STAGE_INPUT, s_mm = stages & WINO_STAGE_GEMM,
+             s_out = stages & WINO_STAGE_OUTPUT;
+  if (workspace_bytes < (exact_need && stages == WINO_STAGE_ALL && d->BT && d->AT
+                             ? fwd_workspace_touched(d)
+                             : v_bytes(g) + m_bytes(g)) ||
+      !aligned256(workspace_dev) || (s_mm && !aligned256(U_dev)))
     return WINO_E_WORKSPACE;
   const Scalars s = make_scalars(g, q);
   hipStream_t hs = (hipStream_t)stream;
@@ -276,8 +310,6 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
     memcpy(at.v, d->AT, sizeof(float) * g.m * g.n);
   }
   if (g.w16) {
-    if (s_in && g.x16 && ((uintptr_t)x_dev & 1)) return WINO_E_BAD_ARG;
-    if (s_out && g.x16 && ((uintptr_t)y_dev & 1)) return WINO_E_BAD_ARG;
     if (s_in && launch_w16_input(g, bt, x_dev, V, s.rv_pos, s.qmax_v, hs) != hipSuccess)
       return WINO_E_HIP;
     const PosScale* wpw = s.pos ? &s.w_pos : nullptr;
@@ -343,6 +375,17 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
       return WINO_E_HIP;
   }
   return WINO_OK;
+}
+
+}  // namespace wino
+
+extern "C" {
+
+wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                                   const void* U_dev, void* y_dev, void* workspace_dev,
+                                   size_t workspace_bytes, int stages, void* stream) {
+  return fwd_stages(d, q, x_dev, U_dev, y_dev, workspace_dev, workspace_bytes, stages, stream,
+                    false);
 }
 
 wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void* x_dev,

@@ -43,6 +43,14 @@ __host__ __device__ inline size_t u_byte_index(int Kp, int Cp, int esz, int p, i
   return (blk * 64 + (size_t)(((cb & 63) >> 4) * 16 + (k & 15))) * 16 + (cb & 15);
 }
 
+// Host-side pieces shared by the entry points (api.cpp).
+size_t fwd_workspace_touched(const wino_desc* d);
+wino_status fwd_check(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                      const void* U_dev, const void* y_dev, int stages, Geom* g);
+wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                       const void* U_dev, void* y_dev, void* workspace_dev,
+                       size_t workspace_bytes, int stages, void* stream, bool exact_need);
+
 // Kernel launchers (each enqueues on `s` and returns hipGetLastError()).
 // (the optional PosScale arguments switch a stage to per-position factors: r_v[p], r_u[p],
 // and w[p] = s_u[p] * s_v[p] applied to the accumulators before the output transform)

@@ -97,7 +97,7 @@ def test_error_codes_without_gpu(L):
     assert L.wino_debug_export(_desc().ref, 9, 0x1000, 0x1000, None) == -8
     assert L.wino_debug_export(_desc().ref, 0, None, 0x1000, None) == -1
     assert q.qmax == 127
-    for s in range(-8, 1):
+    for s in range(-9, 1):
         assert len(wb.status_string(s)) > 1
 
 
