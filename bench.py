@@ -8,10 +8,13 @@ CIFAR ResNet-18 stage-1 convolution (batch 64, 32x32, 64->64 channels,
 F(4x4,3x3)); inputs are synthetic (seeded ReLU(N(0,1)) activations, Kaiming
 weights) and resident in HBM before the timed region starts.
 
-Prints ONE JSON line: direct-convolution-equivalent TOPS of the whole step, the
-roofline of the dominant kernel (per-kernel durations measured with events on the
-launch stream), the speedup over the im2row baseline, and the CPU oracle timed on
-the host cores as a reported baseline.
+Prints ONE JSON line: direct-convolution-equivalent TOPS of the whole step; the
+roofline of the dominant kernel -- its algorithmic bytes against the HBM peak or its GEMM
+operations against the matrix-core peak, whichever of the two needs longer (`hbm_frac` and
+`mfma_frac` give both; the vector-ALU figure is an extra) -- with per-kernel durations
+measured with events on the launch stream; the same for the two largest layers of the
+ResNet-18 stack (`largest`); the speedup over the im2row baseline; and the CPU oracle timed
+on the host cores as a reported baseline.
 """
 import argparse
 import json
@@ -46,11 +49,20 @@ def pick_workload(name):
 ALU_PEAK_TFLOPS = 78.6         # fp32 vector without packed ops: 256 CU x 64 lanes x 2 x 2.4 GHz
 
 
+def exact_input_stage(L):
+    """True where the input transform runs on the matrix cores (int8, F2 / F4, Cook-Toom B^T:
+    the kernels with the exact Kronecker form), so that its work is MFMA work, not vector-ALU."""
+    return L.dtype == "i8" and L.m in (2, 4) and L.flex_sigma == 0
+
+
 def algorithmic(L, BT, AT):
     """Bytes / operations the method itself must move / do, per kernel launch.
-    `ops` are the GEMM's multiply-adds (x2); `alu` are the transforms' fp32 operations:
-    one fused multiply-add (2 flops) per nonzero matrix entry and vector element, one
-    int->float conversion per accumulator, four operations per quantized element
+    `ops` are the GEMM's multiply-adds (x2): the figure the matrix-core roofline prices.
+    `mfma_issued` adds the operations the matrix cores are given for the input transform
+    where it runs there (one 16x16x64 MFMA per 16 positions, 16 windows and 64 patch bytes).
+    `alu` are the fp32 operations issued on the vector ALU: one fused multiply-add
+    (2 flops) per nonzero matrix entry and vector element of a transform that runs there,
+    one int->float conversion per accumulator, four operations per quantized element
     (scale, round, saturate, convert)."""
     wide = L.dtype in WIDE
     e = 1 if L.dtype in ("i8", "i8w16") else 2 if L.dtype == "i16" else 4   # X, Y element
@@ -66,44 +78,77 @@ def algorithmic(L, BT, AT):
     v_b, u_b, m_b = P * T * L.C * ew, P * L.C * L.K * ew, (8 if wide else 4) * P * T * L.K
     # wide modes: a 16-bit product is four int8 digit products on the matrix cores
     mm = 2 * P * T * L.C * L.K * (4 if wide else 1)
-    alu_in = T * L.C * (2 * 2 * n * nzb + qops * P)
+    if exact_input_stage(L):
+        kron = T * L.C * (-(-P // 16)) * 16 * 64 * 2       # operations given to the matrix cores
+        alu_in = T * L.C * qops * P                         # only the quantizer is vector-ALU work
+    else:
+        kron = 0
+        alu_in = T * L.C * (2 * 2 * n * nzb + qops * P)
     alu_out = T * L.K * (2 * (n + L.m) * nza + (P if quantized else 0) + qops * L.m * L.m)
     alu_w = L.K * L.C * (2 * (3 * 3 * n + 3 * n * n) + qops * P)
     return {
-        "weight_transform": dict(bytes=9 * L.C * L.K * 4 + u_b, ops=0, alu=alu_w),
-        "input_transform": dict(bytes=x_b + v_b, ops=0, alu=alu_in),
-        "gemm": dict(bytes=v_b + u_b + m_b, ops=mm, alu=0),
-        "output_transform": dict(bytes=m_b + y_b, ops=0, alu=alu_out),
+        "weight_transform": dict(bytes=9 * L.C * L.K * 4 + u_b, ops=0, alu=alu_w, mfma_issued=0),
+        "input_transform": dict(bytes=x_b + v_b, ops=0, alu=alu_in, mfma_issued=kron),
+        "gemm": dict(bytes=v_b + u_b + m_b, ops=mm, alu=0, mfma_issued=mm),
+        "output_transform": dict(bytes=m_b + y_b, ops=0, alu=alu_out, mfma_issued=0),
         # GEMM and output transform in one kernel: M is never stored
-        "gemm_output": dict(bytes=v_b + u_b + y_b, ops=mm, alu=alu_out),
+        "gemm_output": dict(bytes=v_b + u_b + y_b, ops=mm, alu=alu_out, mfma_issued=mm),
         # the whole forward in one kernel: neither V nor M is stored
-        "fused_forward": dict(bytes=x_b + u_b + y_b, ops=mm, alu=alu_in + alu_out),
+        "fused_forward": dict(bytes=x_b + u_b + y_b, ops=mm, alu=alu_in + alu_out,
+                              mfma_issued=mm + kron),
     }
 
 
 def roofline_entry(name, alg, us, dtype, traffic):
-    """The bound is whichever of HBM, MFMA and vector-ALU peak needs the longest time
-    for the kernel's algorithmic bytes / GEMM operations / transform operations."""
+    """The kernel against the roofline that bounds it: its algorithmic bytes at the HBM peak
+    or its GEMM operations at the dense matrix-core peak of its dtype, whichever needs the
+    longer time.  Both fractions are reported (`hbm_frac`, `mfma_frac`); `alu` is an extra:
+    the fp32 operations issued on the vector ALU against its peak (78.6 TFLOP/s without packed
+    instructions, which this build may not use)."""
     mf = MFMA_PEAK["int8" if dtype == "i8" or dtype in WIDE else "f32"]
-    t = {"hbm": alg["bytes"] / (HBM_PEAK_GBS * 1e9), "mfma": alg["ops"] / (mf * 1e12),
-         "alu": alg["alu"] / (ALU_PEAK_TFLOPS * 1e12)}
-    bound = max(t, key=t.get)
     sec = us * 1e-6
-    if bound == "hbm":
-        ent = dict(bound="hbm", achieved=alg["bytes"] / sec / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
-    elif bound == "mfma":
-        ent = dict(bound="mfma", achieved=alg["ops"] / sec / 1e12, peak=mf,
-                   unit="TOP/s" if dtype == "i8" else "TFLOP/s")
+    hbm = alg["bytes"] / sec / 1e9
+    mfma = alg["ops"] / sec / 1e12
+    if alg["bytes"] / (HBM_PEAK_GBS * 1e9) >= alg["ops"] / (mf * 1e12):
+        ent = dict(bound="hbm", achieved=hbm, peak=HBM_PEAK_GBS, unit="GB/s")
     else:
-        # (frac_of_packed_peak: against the 157.3 TFLOP/s the chip reaches with packed fp32
-        # instructions, which this build may not use)
-        ent = dict(bound="alu", achieved=alg["alu"] / sec / 1e12, peak=ALU_PEAK_TFLOPS, unit="TFLOP/s",
-                   frac_of_packed_peak=alg["alu"] / sec / 1e12 / (2 * ALU_PEAK_TFLOPS))
+        ent = dict(bound="mfma", achieved=mfma, peak=mf,
+                   unit="TOP/s" if dtype == "i8" or dtype in WIDE else "TFLOP/s")
+    alu = alg["alu"] / sec / 1e12
     ent.update(kernel=name, frac=ent["achieved"] / ent["peak"], avg_us=us,
+               hbm_frac=hbm / HBM_PEAK_GBS, mfma_frac=mfma / mf,
                algorithmic_bytes=alg["bytes"], algorithmic_ops=alg["ops"],
-               algorithmic_alu_ops=alg["alu"], hbm_frac=alg["bytes"] / sec / 1e9 / HBM_PEAK_GBS,
-               mfma_frac=alg["ops"] / sec / 1e12 / mf, traffic=traffic)
+               mfma_issued_ops=alg["mfma_issued"], mfma_issued_frac=alg["mfma_issued"] / sec / 1e12 / mf,
+               alu=dict(ops=alg["alu"], achieved=alu, peak=ALU_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=alu / ALU_PEAK_TFLOPS),
+               traffic=traffic)
     return ent
+
+
+def csrc_fingerprint():
+    """sha256 over the kernel sources: measured HBM traffic is only quoted for the very
+    sources it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2002_10711_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".h", ".cpp")):
+            h.update(f.encode())
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch and kernel from profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE /
+    WRITE_SIZE, written by paper_2002_10711_amd.profsummary), or {} with a note if the kernel
+    sources have changed since they were measured."""
+    if not os.path.exists(HBM_TRAFFIC_FILE):
+        return {}, "no traffic file"
+    data = json.load(open(HBM_TRAFFIC_FILE))
+    fp = data.get("_meta", {}).get("csrc_sha256_16")
+    if fp != csrc_fingerprint():
+        return {}, "kernel sources changed since the counters were read (measured at %s)" % fp
+    return data.get(workload, {}), "rocprofv3 FETCH_SIZE + WRITE_SIZE, csrc %s" % fp
 
 
 def gpu_leg(L, steps, warmup, use_graph, cold=False):
@@ -130,8 +175,7 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
         quant = wb.make_quant(scales["s_x"], scales["s_v"], scales["s_u"], scales["s_y"], 0.0, qm["y"],
                               qmax_u=qm["u"], qmax_v=qm["v"], qmax_m=qm["m"], qmax_y=qm["y"])
         # input codes of the previous layer's quantizer (input preparation, not the path)
-        xh = np.clip(np.rint(X / np.float32(scales["s_x"])), -qm["x"], qm["x"]).astype(
-            np.int16 if L.dtype == "i16" else np.int8)
+        xh = workloads.input_codes(X, scales["s_x"], qm["x"], np.int16 if L.dtype == "i16" else np.int8)
         ydt = torch.int16 if L.dtype == "i16" else torch.int8
     else:
         xh = X
@@ -227,7 +271,7 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
     ms_ref = None
     if L.dtype != "i16":
         if rdt == wb.WINO_I8:
-            wq = np.clip(np.rint(g / np.float32(s_w)), -127, 127).astype(np.int8)
+            wq = workloads.input_codes(g, s_w)
         else:
             wq = g
         wdev = torch.from_numpy(wq).to(dev)
@@ -296,8 +340,8 @@ def ref_only_leg(L, steps, warmup):
     dev = torch.device("cuda:0")
     sc = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[L.name]
     X, g = workloads.make_inputs(L)
-    xh = np.clip(np.rint(X / np.float32(sc["s_x"])), -127, 127).astype(np.int8)
-    wq = np.clip(np.rint(g / np.float32(sc["s_w"])), -127, 127).astype(np.int8)
+    xh = workloads.input_codes(X, sc["s_x"])
+    wq = workloads.input_codes(g, sc["s_w"])
     x, wdev = torch.from_numpy(xh).to(dev), torch.from_numpy(wq).to(dev)
     y = torch.empty((L.N, L.K, L.Ho, L.Wo), dtype=torch.int8, device=dev)
     wp = torch.empty(wb.conv2d_ref_packed_weights_bytes(L.C, L.K, wb.WINO_I8), dtype=torch.uint8, device=dev)
@@ -357,37 +401,108 @@ def stack_line(steps, warmup):
     }
 
 
+LARGEST = {
+    # the layer with the most bytes through the transforms, and the GEMM-dominated one
+    "transforms": "cfg5_l00_64to64_s32_F4",
+    "gemm": "cfg5_l15_512to512_s4_F2",
+}
+
+
+def largest_block(steps, warmup, use_graph):
+    """The two largest layers of the ResNet-18 stack (batch 256): forward time, and every
+    kernel of the forward and of the same layer as four separate kernels against its
+    roofline."""
+    out = {}
+    for role, name in LARGEST.items():
+        L = pick_workload(name)
+        r = gpu_leg(L, steps, warmup, use_graph)
+        alg = algorithmic(L, r["BT"], r["AT"])
+        traffic, note = measured_traffic(L.name)
+        keys = ("kernel", "avg_us", "bound", "frac", "hbm_frac", "mfma_frac", "mfma_issued_frac",
+                "algorithmic_bytes", "algorithmic_ops", "traffic")
+
+        def rows(us):
+            return [{k: e[k] for k in keys} for e in
+                    (roofline_entry(k, alg[k], t, L.dtype, traffic.get(k)) for k, t in us.items())]
+        out[role] = dict(workload="%s: N=%d C=%d K=%d %dx%d F(%dx%d,3x3) int8" % (
+            L.name, L.N, L.C, L.K, L.H, L.W, L.m, L.m), steps=steps,
+            fwd_us=r["ms_fwd"] * 1e3, fwd_tops=L.direct_ops / (r["ms_fwd"] * 1e-3) / 1e12,
+            im2row_us=r["ms_ref"] * 1e3 if r["ms_ref"] else None,
+            kernels=rows(r["kernel_us"]), staged_kernels=rows(r["staged_us"]), traffic_source=note)
+    return out
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_leg(L):
-    """The oracle as it stands, on the host cores, whole quantized forward
-    (weight stage included) on the first images of the same workload."""
+    """The oracle as it stands, on the host cores, on the first images of the same workload:
+    the quantized pipeline (weight stage included) with OpenMP -- the headline `value` -- and
+    next to it the fp64 direct convolution and the fp64 literal Winograd, each with OpenMP on
+    all cores and on one thread (fewer images, stated)."""
     import oracle
     oracle.build()
-    n_img = min(L.N, 16)
     from dataclasses import replace
-    Ls = replace(L, N=n_img)
     X, g = workloads.make_inputs(L)
-    X = X[:n_img]
     BT, G, AT = oracle.cook_toom(L.m, dtype=np.float32)
     if L.flex_sigma > 0:
         BT, G, AT = workloads.perturb_transforms(BT, G, AT, L.flex_sigma, L.seed)
+    threads = oracle.num_threads()
+
+    def timed(fn, budget):
+        fn()
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < budget or reps < 2:
+            fn()
+            reps += 1
+        return (time.perf_counter() - t0) / reps, reps
+
+    def tops(n_img, dt):
+        return replace(L, N=n_img).direct_ops / dt / 1e12
+
+    n_omp, n_one = min(L.N, 16), min(L.N, 2)
+    runs = {}
     if L.dtype != "f32":
         sc = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[L.name]
         qm = workloads.STAGE_QMAX[L.dtype]
-        xq = oracle.quantize_tensor(X, sc["s_x"], qm["x"])
-        fn = lambda: oracle.winograd_q(xq, g, BT, G, AT, sc, pad=L.pad, qmax=qm)
+        xq = oracle.quantize_tensor(X[:n_omp], sc["s_x"], qm["x"])
+        main_fn = lambda n: (lambda: oracle.winograd_q(xq[:n], g, BT, G, AT, sc, pad=L.pad, qmax=qm))
+        main_name = "quantized_pipeline"
     else:
-        fn = lambda: oracle.winograd_f64(X, g, BT, G, AT, L.pad)
-    fn()
-    t0 = time.perf_counter()
-    reps = 0
-    while time.perf_counter() - t0 < 10.0 or reps < 3:
-        fn()
-        reps += 1
-    dt = (time.perf_counter() - t0) / reps
-    return dict(value=Ls.direct_ops / dt / 1e12, unit="TOPS (direct-conv-equivalent)",
-                cores=oracle.num_threads(), kind="oracle",
-                sample="first %d of %d images of %s, %d repetitions, %.3f s each; quantized "
-                       "pipeline incl. weight stage, OpenMP over tiles" % (n_img, L.N, L.name, reps, dt))
+        main_fn = lambda n: (lambda: oracle.winograd_f64(X[:n], g, BT, G, AT, L.pad))
+        main_name = "winograd_f64"
+    legs = [(main_name, main_fn, 8.0, 3.0),
+            ("direct_f64", lambda n: (lambda: oracle.conv2d_direct_f64(X[:n], g, 1, L.pad)), 3.0, 2.0)]
+    if L.dtype != "f32":
+        legs.append(("winograd_f64", lambda n: (lambda: oracle.winograd_f64(X[:n], g, BT, G, AT, L.pad)),
+                     3.0, 2.0))
+    for name, mk, b_omp, b_one in legs:
+        oracle.set_num_threads(threads)
+        dt, reps = timed(mk(n_omp), b_omp)
+        runs[name + "_openmp"] = dict(tops=tops(n_omp, dt), threads=threads, images=n_omp,
+                                      seconds_per_pass=dt, passes=reps)
+        oracle.set_num_threads(1)
+        dt, reps = timed(mk(n_one), b_one)
+        runs[name + "_1_thread"] = dict(tops=tops(n_one, dt), threads=1, images=n_one,
+                                        seconds_per_pass=dt, passes=reps)
+    oracle.set_num_threads(threads)
+    head = runs[main_name + "_openmp"]
+    return dict(value=head["tops"], unit="TOPS (direct-conv-equivalent)", cores=threads,
+                kind="oracle", cpu_model=cpu_model(),
+                sample="first %d of %d images of %s, %d passes of %.3f s; %s incl. weight stage, "
+                       "OpenMP over tiles; `runs` holds the fp64 direct convolution and the fp64 "
+                       "literal Winograd as well, each with OpenMP and on one thread (first %d images)"
+                       % (n_omp, L.N, L.name, head["passes"], head["seconds_per_pass"],
+                          main_name.replace("_", " "), n_one),
+                runs=runs)
 
 
 def main():
@@ -399,6 +514,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host "
                     "instead of replaying a captured HIP graph of one step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-largest", action="store_true", help="skip the `largest` block (the two "
+                    "largest layers of the ResNet-18 stack, timed next to the default workload)")
     ap.add_argument("--stack", action="store_true", help="time the whole CIFAR ResNet-18 conv "
                     "stack (config 5: 16 layers, batch 256, int8) layer by layer, forward only, "
                     "and print its total instead of one workload's line")
@@ -437,9 +554,7 @@ def main():
         del src, dst
     r = gpu_leg(L, a.steps, a.warmup, not a.no_graph, a.cold)
     alg = algorithmic(L, r["BT"], r["AT"])
-    traffic = {}
-    if os.path.exists(HBM_TRAFFIC_FILE):
-        traffic = json.load(open(HBM_TRAFFIC_FILE)).get(L.name, {})
+    traffic, traffic_note = measured_traffic(L.name)
     kernels = [roofline_entry(k, alg[k], us, L.dtype, traffic.get(k)) for k, us in r["kernel_us"].items()]
     dominant = max(kernels, key=lambda e: e["avg_us"])
     out = {
@@ -458,13 +573,26 @@ def main():
         "fwd_only_ms": r["ms_fwd"],
         "fwd_only_tops": L.direct_ops / (r["ms_fwd"] * 1e-3) / 1e12,
         "im2row_baseline_ms": r["ms_ref"],
+        # (the baseline as built: im2row gather, one GEMM, requantizing epilogue; its own
+        # matrix-core fraction next to the ratio, so that a weak baseline shows)
+        "im2row_baseline_tops": L.direct_ops / (r["ms_ref"] * 1e-3) / 1e12 if r["ms_ref"] else None,
+        "im2row_baseline_mfma_frac": (L.direct_ops / (r["ms_ref"] * 1e-3) / 1e12 /
+                                      MFMA_PEAK["f32" if L.dtype == "f32" else "int8"])
+        if r["ms_ref"] else None,
         "speedup_vs_im2row": r["ms_ref"] / r["ms_fwd"] if r["ms_ref"] else None,
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
                                                "kernel", "avg_us")},
+        "hbm_frac": dominant["hbm_frac"], "mfma_frac": dominant["mfma_frac"],
+        "traffic_source": traffic_note,
         "kernels": kernels,
         "staged_kernels": [roofline_entry(k, alg[k], us, L.dtype, traffic.get(k))
                            for k, us in r["staged_us"].items()],
+        "timing_note": "ms_per_step and fwd_only_ms: HIP graphs of whole steps; per-kernel avg_us: "
+                       "each stage in a graph of its own of ten back-to-back launches, which "
+                       "includes the gap between two launches that a step graph partly hides",
     }
+    if a.workload == "cfg2_i8" and not a.no_largest:
+        out["largest"] = largest_block(max(200, a.steps // 5), max(50, a.warmup // 5), not a.no_graph)
     out.update(r["extra"])
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_leg(L)

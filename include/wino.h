@@ -70,7 +70,7 @@ typedef enum {
  * WINO_I16   up to 16-bit codes after every stage (Sec. 5.1's INT10 and INT16): X and Y are
  *            int16 arrays, U and V hold 16-bit codes, M is the exact int64 sum.
  * WINO_I8W16 8-bit activations with a 16-bit Winograd domain (Sec. 3.2, "quantization
- *            diversity"; Sec. 6, different bit-widths through Eq. 1): X and Y are int8
+ *            diversity"; Sec. 7, different bit-widths through Eq. 1): X and Y are int8
  *            arrays, U, V and the Hadamard-stage quantizer may use up to 16 bits.
  * The two wide modes accept one code range per stage (wino_quant.qmax_*), need C <= 1024,
  * and run as two kernels (input transform; GEMM fused with the output transform) or, for
@@ -96,7 +96,8 @@ typedef struct {
 typedef struct {
   float s_x, s_v, s_u, s_y, s_m;
   int qmax;         /* 1..127 (1..32767 in the wide modes); see qmax_* below */
-  /* Optional finer granularity (Sec. 6: "other types of quantization would likely help"):
+  /* Optional finer granularity (Sec. 7 suggests finer-grained quantization than one scale
+   * per tensor as the way to recover the accuracy of the larger tiles):
    * one scale per Winograd position p = i*n + j for the transformed input and the
    * transformed weights, HOST arrays of n*n floats, both or neither (NULL).  When given,
    * s_v and s_u are ignored, Vq[p] = sat(rne(V[p] * s_x / s_v_pos[p])),
@@ -139,7 +140,11 @@ wino_status wino_transform_weights(const wino_desc* d, const wino_quant* q,
  *   U_dev          in   DEVICE, produced by wino_transform_weights for the same d
  *   y_dev          out  DEVICE Y, int8 / int16 codes or float
  *   workspace_dev       DEVICE scratch, >= wino_workspace_bytes(d), 256-byte
- *                       aligned; holds V and M afterwards (see wino_debug_export) */
+ *                       aligned.  What it holds afterwards depends on the kernel
+ *                       sequence (wino_fwd_num_kernels): nothing new after the
+ *                       one-kernel forward, V after two kernels, V and M after
+ *                       three; the parity taps (wino_debug_export) therefore read it
+ *                       after wino_conv2d_fwd_stages has run the stages separately */
 wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void* x_dev,
                             const void* U_dev, void* y_dev, void* workspace_dev,
                             size_t workspace_bytes, void* stream);

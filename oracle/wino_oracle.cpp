@@ -233,7 +233,7 @@ void oracle_q_scalars(float s_x, float s_v, float s_u, float s_y, float s_m,
 // Weight stage:  t = G g (n x 3), U = t G^T (n x n), Uq = sat(rne(U * r_u)).
 // U_f32 (optional) receives the unscaled fp32 U, Uq (optional) the integers;
 // both in the order [p][k][c].
-// Per-position variant (Sec. 6 names "other types of quantization" as the way to recover
+// Per-position variant (Sec. 7 names other kinds of quantization as the way to recover
 // F4/F6 accuracy; one scale per Winograd position is the smallest step from the paper's
 // one scale per tensor): r_u_pos[p] multiplies position p = i*n + j.  The per-tensor entry
 // point below is this one with all factors equal.

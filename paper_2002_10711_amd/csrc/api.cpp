@@ -324,18 +324,33 @@ wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_de
       return WINO_E_HIP;
     return WINO_OK;
   }
+  bool exact_refused = false;
   if (stages == WINO_STAGE_ALL && fused_fwd_supported(g)) {
     // the whole forward in one kernel: V and M stay on chip, the workspace is untouched
     const bool exact = fused_fwd_exact_supported(g, bt);
     if (exact || fused_fwd_generic_preferred(g)) {
       const PosScale* rvq = s.pos ? &s.rv_pos : nullptr;
       const PosScale* wq = s.pos ? &s.w_pos : nullptr;
-      const hipError_t e =
+      hipError_t e =
           exact ? launch_fused_fwd_exact(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax,
                                          rvq, wq, hs)
                 : launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, rvq,
                                    wq, hs);
-      return e == hipSuccess ? WINO_OK : WINO_E_HIP;
+      // The matrix-core launcher refuses, before launching anything, the few inputs its
+      // exact scaling cannot carry (a quantizer factor that underflows when divided by
+      // 4^s, a tile row count beyond the grid limit): those take the vector-ALU kernels,
+      // which handle them -- as one kernel where that is supported, else stage by stage
+      // (which needs the workspace after all).
+      if (exact && e == hipErrorInvalidValue) {
+        if (fused_fwd_generic_preferred(g))
+          e = launch_fused_fwd(g, bt, at, x_dev, U_dev, y_dev, s.r_v, s.r_m, s.r_y, s.qmax, rvq, wq,
+                               hs);
+        else if (workspace_bytes < v_bytes(g) + m_bytes(g))
+          return WINO_E_WORKSPACE;
+        else
+          exact_refused = true;
+      }
+      if (!exact_refused) return e == hipSuccess ? WINO_OK : WINO_E_HIP;
     }
   }
   if (stages == WINO_STAGE_ALL && fused_fwd_f32_supported(g))
@@ -343,14 +358,20 @@ wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_de
                                                                                   : WINO_E_HIP;
   const PosScale* rvp = s.pos ? &s.rv_pos : nullptr;
   const PosScale* wp = s.pos ? &s.w_pos : nullptr;
-  if (s_in && (input_exact_preferred(g, bt, x_dev)
-                   ? launch_input_exact(g, bt, x_dev, V, s.r_v, s.qmax, hs, rvp)
-               : input_f32_staged_supported(g)
-                   ? launch_input_f32_staged(g, bt, x_dev, V, hs)
-                   : launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs, rvp)) != hipSuccess)
-    return WINO_E_HIP;
-  // (per-position scales: the accumulators need their factors before the output
-  // transform, which only the stand-alone output kernel applies)
+  if (s_in) {
+    hipError_t e = input_exact_preferred(g, bt, x_dev)
+                       ? launch_input_exact(g, bt, x_dev, V, s.r_v, s.qmax, hs, rvp)
+                   : input_f32_staged_supported(g)
+                       ? launch_input_f32_staged(g, bt, x_dev, V, hs)
+                       : launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs, rvp);
+    // (the matrix-core input stage refuses what its exact scaling cannot carry, see above)
+    if (e == hipErrorInvalidValue && input_exact_preferred(g, bt, x_dev))
+      e = launch_input_transform(g, bt, x_dev, V, s.r_v, s.qmax, hs, rvp);
+    if (e != hipSuccess) return WINO_E_HIP;
+  }
+  // (with per-position scales every accumulator is multiplied by its position's factor
+  // before the output transform: the GEMM + output kernels for long reductions and the
+  // stand-alone output kernel do that, gemm_out_kernel does not)
   if (s_mm && s_out && gemm_out_lds_preferred(g)) {
     // F(2x2,3x3), 512 channels, many tiles: the same fusion with squarer workgroup tiles
     if (launch_gemm_out_lds(g, at, V, U_dev, y_dev, wp, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)

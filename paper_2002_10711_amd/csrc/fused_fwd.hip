@@ -155,7 +155,8 @@ hipError_t launch_k(const Geom& g, const MatBT& bt, const MatAT& at, const int8_
   do { if (g.Cp == 64) WINO_LAUNCH_FUSED1(WIDE, FAST, true);                          \
        else if constexpr (M == 2) WINO_LAUNCH_FUSED1(WIDE, FAST, false); } while (0)
   // whole tiles and K % 4 == 0: no guards on the output side
-  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
+  // (the branch-free output side stores 2 or 4 codes at a time: y must be aligned for that)
+  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && ((uintptr_t)y & 3) == 0;
   if (fast) WINO_LAUNCH_FUSED(true, true); else WINO_LAUNCH_FUSED(true, false);
 #undef WINO_LAUNCH_FUSED
 #undef WINO_LAUNCH_FUSED1

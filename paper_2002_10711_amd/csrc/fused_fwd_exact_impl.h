@@ -843,7 +843,8 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   // workgroup shapes and, with whole tiles and K % 4 == 0, a branch-free output side.  The
   // quantizer after the Hadamard stage and per-position scales are run-time options of
   // every kernel.
-  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
+  // (the branch-free output side stores 2 or 4 codes at a time: y must be aligned for that)
+  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && ((uintptr_t)y & 3) == 0;
   // 128 output channels and at most 128 input channels: eight wavefronts share one
   // transform (fused_fwd_exact_wide_kernel)
   if (sa && load >= 2 && g.Kp == 128 && g.Cp <= 128) {

@@ -1,5 +1,5 @@
 // Hadamard stage of Eq. 1 summed over input channels, written as one GEMM per
-// Winograd position (paper, Sec. 5.3: "Winograd convolutions using GEMMs"):
+// Winograd position (the GEMM formulation of Winograd convolutions, paper Sec. 5.3):
 //
 //     M[p][t][k] = sum_c A[p][t][c] * B[p][k][c]
 //

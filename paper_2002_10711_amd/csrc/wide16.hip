@@ -1,6 +1,6 @@
 // Wider Winograd domain: the quantized forward with up to 16-bit codes after every stage
 // (Sec. 3.2, "quantization diversity": each intermediate of Eq. 1 may have its own
-// bit-width; Sec. 5.1 runs INT8, INT10 and INT16; Sec. 6 names wider intermediate stages as
+// bit-width; Sec. 5.1 runs INT8, INT10 and INT16; Sec. 7 names wider intermediate stages as
 // the way to recover F4/F6 accuracy).
 //
 // The matrix cores have no 16-bit integer instruction, but int8 at twice the fp16 rate.  A

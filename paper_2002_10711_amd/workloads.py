@@ -123,6 +123,14 @@ def make_inputs(layer):
     return X, g
 
 
+def input_codes(X, s_x, qmax=127, container=np.int8):
+    """Integer codes a layer receives from the layer before it: round(X / s_x) in fp32, ties
+    to even, clipped to [-qmax, qmax].  Input preparation only (the path starts from these
+    codes); the one place the benchmark takes them from."""
+    v = np.asarray(X, np.float32) / np.float32(s_x)
+    return np.clip(np.rint(v), -qmax, qmax).astype(container)
+
+
 def perturb_transforms(BT, G, AT, sigma, seed):
     """Add seeded N(0, sigma) noise to every entry of the three matrices and round
     to fp32 -- stands in for learned ("flex") transforms, which are dense."""

@@ -250,6 +250,26 @@ def test_bench_algorithmic_work_of_config2():
     assert a["fused_forward"]["bytes"] == x + u + y and a["fused_forward"]["ops"] == 1207959552
     assert a["weight_transform"]["bytes"] == 9 * 64 * 64 * 4 + u
     assert 2 * L.N * L.K * L.Ho * L.Wo * L.C * 9 == 4831838208
+    # the input transform of this layer runs on the matrix cores: three 16x16x64 MFMAs per 16
+    # windows (36 positions in groups of 16) are matrix-core work, only the quantizer's four
+    # operations per element remain vector-ALU work
+    kron = 4096 * 64 * 3 * 16 * 64 * 2
+    assert a["input_transform"]["mfma_issued"] == kron and a["input_transform"]["ops"] == 0
+    assert a["fused_forward"]["mfma_issued"] == 1207959552 + kron
+    assert a["input_transform"]["alu"] == 4096 * 64 * 36 * 4
+    # which roofline bounds a kernel: bytes at 8 TB/s against GEMM operations at 5 POP/s
+    e = bench.roofline_entry("fused_forward", a["fused_forward"], 10.0, "i8", None)
+    assert e["bound"] == "hbm" and abs(e["hbm_frac"] - (x + u + y) / 10e-6 / 8e12) < 1e-12
+    assert abs(e["mfma_frac"] - 1207959552 / 10e-6 / 5e15) < 1e-12 and e["frac"] == e["hbm_frac"]
+    L5 = [l for l in workloads.config5() if l.name == "cfg5_l15_512to512_s4_F2"][0]
+    BT2, _, AT2 = wb.wino_cook_toom(2)
+    a5 = bench.algorithmic(L5, np.asarray(BT2), np.asarray(AT2))
+    e5 = bench.roofline_entry("gemm_output", a5["gemm_output"], 10.0, "i8", None)
+    # (V 16*1024*512 + U 16*512*512 + Y 256*512*16 bytes need 1.835 us at 8 TB/s, the
+    # 8.59 G operations 1.718 us at 5 POP/s: the two roofs of this layer all but coincide)
+    assert a5["gemm_output"]["ops"] == 2 * 16 * 1024 * 512 * 512
+    assert a5["gemm_output"]["bytes"] == 16 * 1024 * 512 + 16 * 512 * 512 + 256 * 512 * 16
+    assert e5["bound"] == "hbm" and 0.9 < e5["mfma_frac"] / e5["hbm_frac"] < 1.0
     # the 16-bit-stage workload: two bytes per code of X, Y, U, V, eight per accumulator
     # taken to memory, four int8 digit products per 16-bit product
     Lw = workloads.config2("i16")[0]

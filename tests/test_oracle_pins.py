@@ -451,7 +451,7 @@ def test_flex_limit_noise_to_zero(oracle):
 def test_per_position_f2_stages_are_exact_integers(oracle):
     """Per-position variant with power-of-two factors on exact F2 data: every stage equals
     integer algebra with the factor applied per Winograd position, and the real-unit
-    output equals the integer direct convolution (Sec. 6: finer quantization granularity
+    output equals the integer direct convolution (Sec. 7: finer quantization granularity
     as the way to recover the larger tiles' accuracy)."""
     rng = np.random.default_rng(31)
     BT, G, AT = oracle.cook_toom(2, dtype=np.float32)
@@ -510,7 +510,7 @@ def test_per_position_equals_per_tensor_when_all_factors_agree(oracle):
 
 
 def test_per_position_scales_reduce_the_static_int8_error(oracle):
-    """The motivation (Sec. 6; Table 1): one scale for all positions wastes most of the
+    """The motivation (Sec. 7; Table 1): one scale for all positions wastes most of the
     int8 range on F4 / F6; one scale per position brings the error against the direct
     convolution down, and converges like the per-tensor pipeline as qmax grows."""
     from paper_2002_10711_amd import workloads
@@ -619,7 +619,7 @@ def test_error_to_direct_convolution_falls_with_the_bit_width(oracle):
     to the direct convolution falls with every added bit, for each tile size, but the
     ordering F2 < F4 < F6 of Table 1 stays at every width -- F6 is still far away with
     16-bit stages (Table 1's 16-bit column), F4 is within 2e-3 for a single layer.  Widening
-    only the Winograd domain (8-bit activations, 16-bit U, V and Hadamard stage; Sec. 6:
+    only the Winograd domain (8-bit activations, 16-bit U, V and Hadamard stage; Sec. 7:
     different bit-widths through Eq. 1) brings F4 down to the floor of its 8-bit output."""
     from paper_2002_10711_amd import workloads
     L = workloads.Layer("t", 2, 32, 16, 12, 12, seed=23)

@@ -206,7 +206,7 @@ def test_many_tiles_ragged_flex_and_m_quantizer(oracle, m):
     Layer("pos_f2_c512_k64_1024tiles", 64, 512, 64, 8, 8, m=2, seed=186),   # 32 x 64 workgroup tiles
 ], ids=lambda l: l.name)
 def test_per_position_scales_all_taps(oracle, layer):
-    """One quantizer scale per Winograd position for V and U (Sec. 6), calibrated by the
+    """One quantizer scale per Winograd position for V and U (Sec. 7), calibrated by the
     oracle; every tap bit-exact; then the same with the Hadamard-stage quantizer on."""
     case = make_case(oracle, layer, with_oracle=False)
     sc = oracle.calibrate_pos(case["X"], case["g"], case["BT"], case["G"], case["AT"], pad=layer.pad)
@@ -318,6 +318,57 @@ def test_input_at_an_odd_address(oracle):
         torch.cuda.synchronize()
         assert np.array_equal(y.cpu().numpy(), case["ref"]["Yq"])
         assert np.array_equal(y2.cpu().numpy(), case["ref"]["Yq"])
+
+
+@pytest.mark.parametrize("flex", [0.0, 0.03], ids=["matrix_core_input", "vector_alu_input"])
+def test_output_at_an_odd_address(oracle, flex):
+    """y need not be aligned either: the one-kernel forwards then leave their branch-free
+    output side (2- and 4-byte stores) for byte stores."""
+    import torch
+    from paper_2002_10711_amd import binding as wb
+    L = Layer("odd_y", 2, 64, 64, 16, 16, m=4, flex_sigma=flex, seed=187)
+    case = make_case(oracle, L)
+    sc = case["scales"]
+    dev = torch.device("cuda:0")
+    desc = wb.Desc(L.N, L.C, L.K, L.H, L.W, L.pad, L.m, wb.WINO_I8, BT=case["BT"], G=case["G"],
+                   AT=case["AT"])
+    assert wb.wino_fwd_num_kernels(desc) == 1
+    quant = wb.make_quant(sc["s_x"], sc["s_v"], sc["s_u"], sc["s_y"])
+    x = torch.from_numpy(case["xq"]).to(dev)
+    U = torch.empty(wb.wino_weights_bytes(desc), dtype=torch.uint8, device=dev)
+    ws = torch.empty(wb.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    wb.wino_transform_weights(desc, quant, torch.from_numpy(case["g"]).to(dev), U)
+    numel = L.N * L.K * 16 * 16
+    buf = torch.full((numel + 3,), 99, dtype=torch.int8, device=dev)
+    for shift in (1, 2, 3):
+        y = buf[shift:shift + numel].view(L.N, L.K, 16, 16)
+        assert y.data_ptr() % 4 == shift
+        buf.fill_(99)
+        wb.wino_conv2d_fwd(desc, quant, x, U, y, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), case["ref"]["Yq"])
+        edge = buf.cpu().numpy()
+        assert (edge[:shift] == 99).all() and (edge[shift + numel:] == 99).all()
+
+
+def test_quantizer_factor_too_small_for_the_exact_scaling(oracle):
+    """The matrix-core input transform divides the quantizer factor s_x / s_v by 4^s, exactly;
+    a factor that underflows there makes its launcher decline, and the call must take the
+    vector-ALU kernels instead of failing (every code of V is then 0, like the oracle's)."""
+    L = Layer("tiny_rv", 2, 64, 64, 16, 16, m=4, seed=188)
+    case = make_case(oracle, L, with_oracle=False)
+    sc = dict(case["scales"])
+    sc["s_x"] = float(np.float32(2.0 ** -148))
+    sc["s_v"] = 1.0
+    assert np.float32(sc["s_x"]) / np.float32(sc["s_v"]) / np.float32(16) == 0
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc)
+    assert not case["ref"]["Vq"].any()
+    _check_i8(case, run_gpu(case, scales=sc))
+    # the same with more output channels than one kernel handles without the exact transform
+    L2 = Layer("tiny_rv_k128", 2, 64, 128, 16, 16, m=4, seed=189)
+    case = make_case(oracle, L2, with_oracle=False)
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc)
+    _check_i8(case, run_gpu(case, scales=sc))
 
 
 def test_config2_int8_full(oracle):
