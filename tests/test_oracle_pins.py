@@ -178,16 +178,71 @@ def test_direct_conv_single_channel_nine_terms(oracle):
 
 
 def test_direct_conv_q_matches_integer_bruteforce(oracle):
+    """The integer direct convolution and its one requantization: the accumulators against
+    brute force, the codes against the exact-product rule -- nearest integer, ties to even,
+    to the exact rational product of the accumulator and the fp32 factor, then saturation --
+    evaluated in rationals (not a second floating-point rounding)."""
     rng = np.random.default_rng(5)
     Xq = rng.integers(-127, 128, (2, 5, 6, 6))
     gq = rng.integers(-127, 128, (3, 5, 3, 3))
+    r_y = np.float32(2e-3)
     for stride in (1, 2):
-        acc, Yq = oracle.conv2d_direct_q(Xq, gq, r_y=np.float32(3e-4), stride=stride, pad=1)
+        acc, Yq = oracle.conv2d_direct_q(Xq, gq, r_y=r_y, stride=stride, pad=1)
         ref = _direct_bruteforce(Xq.astype(np.int64), gq.astype(np.int64), stride, 1)
         assert np.array_equal(acc, ref)
-        exp = np.clip(np.rint(ref.astype(np.float32) * np.float32(3e-4)), -127, 127)
-        assert np.array_equal(Yq, exp.astype(np.int32))
-        assert np.abs(Yq).max() == 127 or np.abs(exp).max() < 127
+        exp = np.array([_rne_sat(Fraction(int(a)) * Fraction(float(r_y)), 127) for a in ref.ravel()])
+        assert np.array_equal(Yq.ravel(), exp)
+        assert np.abs(Yq).max() == 127 and (np.abs(Yq) < 127).sum() > Yq.size // 2
+    # products that the two-step rule (round the product to fp32, then to an integer) gets
+    # wrong: fl(1/6) lies just above 1/6, so 3 fl(1/6) is just above 1/2 and belongs to 1, but
+    # the fp32 product is 0.5 exactly, a tie that would go to 0 (likewise 15 fl(1/6) -> 3, not 2)
+    one_sixth = np.float32(1.0) / np.float32(6.0)
+    assert np.float32(3.0) * one_sixth == np.float32(0.5) and 3 * Fraction(float(one_sixth)) > Fraction(1, 2)
+    assert np.float32(15.0) * one_sixth == np.float32(2.5)
+    X1 = np.zeros((1, 1, 3, 3), np.int64)
+    X1[0, 0, 1, 1] = 1
+    for a, want in ((3, 1), (9, 2), (15, 3), (-3, -1), (-9, -2), (6, 1), (12, 2)):
+        g1 = np.zeros((1, 1, 3, 3), np.int64)
+        g1[0, 0, 1, 1] = a
+        acc, Yq = oracle.conv2d_direct_q(X1, g1, r_y=one_sixth, stride=1, pad=1)
+        assert acc[0, 0, 1, 1] == a
+        assert Yq[0, 0, 1, 1] == want == _rne_sat(Fraction(a) * Fraction(float(one_sixth)), 127)
+    # true ties (factor 1/2 is exact): half to even
+    for a, want in ((1, 0), (3, 2), (5, 2), (7, 4), (-1, 0), (-3, -2), (255, 127), (-999, -127)):
+        g1 = np.zeros((1, 1, 3, 3), np.int64)
+        g1[0, 0, 1, 1] = a
+        _, Yq = oracle.conv2d_direct_q(X1, g1, r_y=np.float32(0.5), stride=1, pad=1)
+        assert Yq[0, 0, 1, 1] == want
+
+
+def test_quantize_tensor_hand_values(oracle):
+    """The input quantizer sat(rne(x / scale)) -- a correctly rounded fp32 division, then the
+    nearest integer, ties to even, then saturation -- on values worked out by hand, and
+    against the same rule in exact rationals on random data."""
+    q = oracle.quantize_tensor
+    x = np.array([0.0, 0.25, 0.75, 1.25, 1.75, -0.25, -0.75, -1.25, 63.5, 64.5, 1000.0, -1000.0,
+                  126.5, 127.5, -127.5], np.float32)
+    want = [0, 0, 2, 2, 4, 0, -2, -2, 127, 127, 127, -127, 127, 127, -127]
+    assert q(x, 0.5).tolist() == want                       # x / 0.5 is exact: .5 ties go to even
+    assert q(np.array([2.5, 3.5, -2.5, 7.49999, 7.5, 8.5], np.float32), 1.0, 7).tolist() == \
+        [2, 4, -2, 7, 7, 7]
+    # the division is rounded to fp32 before the integer is taken: fl(0.35 / 0.1) is 3.5
+    # exactly (the quotient of the two floats lies within half an ulp of it), so it is a tie
+    a, b = np.float32(0.35), np.float32(0.1)
+    assert a / b == np.float32(3.5) and Fraction(float(a)) / Fraction(float(b)) != Fraction(7, 2)
+    assert q(np.array([a]), b).tolist() == [4]
+    rng = np.random.default_rng(41)
+    xs = (rng.standard_normal(400) * 3).astype(np.float32)
+    sc = np.float32(0.0237)
+    got = q(xs, sc)
+    for v, g_ in zip(xs, got):
+        quo = _round32(Fraction(float(v)) / Fraction(float(sc)))        # correctly rounded fp32 division
+        assert g_ == _rne_sat(Fraction(float(quo)), 127)
+    assert got.dtype == np.int32 and np.abs(got).max() == 127
+    # the benchmark's input preparation is the same function of (x, scale)
+    from paper_2002_10711_amd import workloads
+    assert np.array_equal(workloads.input_codes(xs, sc), got.astype(np.int8))
+    assert np.array_equal(workloads.input_codes(x, 0.5), np.array(want, np.int8))
 
 
 # ---------------------------------------------------------------- P1 Winograd == direct in fp64
@@ -295,24 +350,29 @@ def _rne_sat(v, qmax):
     return int(min(max(q, -qmax), qmax))
 
 
-def test_fused_chain_order_on_dense_matrices(oracle):
+@pytest.mark.parametrize("m,H,W,pad", [(2, 4, 4, 1), (4, 5, 7, 1), (6, 7, 6, 1), (4, 9, 6, 0)],
+                         ids=["m2_4x4", "m4_ragged_5x7", "m6_ragged_7x6", "m4_pad0_9x6"])
+def test_fused_chain_order_on_dense_matrices(oracle, m, H, W, pad):
     """The pinned arithmetic (ascending fused chains from +0; the quantizer rounds the
-    exact product with its reciprocal step half to even, then saturates) emulated with exact rationals on a tiny case
-    with dense random matrices, where the evaluation order does change bits."""
-    rng = np.random.default_rng(13)
-    m, n = 2, 4
+    exact product with its reciprocal step half to even, then saturates) emulated with exact
+    rationals on tiny cases with dense random matrices, where the evaluation order does
+    change bits: every tile size, tiles cut by the image edge, with and without padding."""
+    rng = np.random.default_rng(13 + m + H)
+    n = m + 2
+    C, K = (2, 2) if m == 2 else (1, 2)
     BT = rng.standard_normal((n, n)).astype(np.float32)
     G = rng.standard_normal((n, 3)).astype(np.float32)
     AT = rng.standard_normal((m, n)).astype(np.float32)
-    xq = rng.integers(-127, 128, (1, 2, 4, 4))
-    g = rng.standard_normal((2, 2, 3, 3)).astype(np.float32)
-    r_v, r_u, r_y = np.float32(0.37), np.float32(41.3), np.float32(2.1e-3)
+    xq = rng.integers(-127, 128, (1, C, H, W))
+    g = rng.standard_normal((K, C, 3, 3)).astype(np.float32)
+    r_v, r_u = np.float32(0.37 / n), np.float32(41.3)
     f0 = np.float32(0)
-    # input stage, tile (0,0) .. all tiles of a 4x4 image with pad 1 (2x2 tiles)
-    Vf, Vq = oracle.q_input(xq, BT, pad=1, r_v=r_v)
-    d, TH, TW = _patches(xq, m, 1)
+    Ho, Wo = H + 2 * pad - 2, W + 2 * pad - 2
+    Vf, Vq = oracle.q_input(xq, BT, pad=pad, r_v=r_v)
+    d, TH, TW = _patches(xq, m, pad)
+    assert (TH, TW) == (-(-Ho // m), -(-Wo // m)) and d.shape[0] == TH * TW
     for t in range(d.shape[0]):
-        for c in range(2):
+        for c in range(C):
             w = [[f0] * n for _ in range(n)]
             for i in range(n):
                 for l in range(n):
@@ -327,9 +387,10 @@ def test_fused_chain_order_on_dense_matrices(oracle):
                         acc = _fma32(w[i][l], BT[k, l], acc)
                     assert Vf[i * n + k, t, c] == acc
                     assert Vq[i * n + k, t, c] == _rne_sat(Fraction(float(acc)) * Fraction(float(r_v)), 127)
+    assert 0 < np.abs(Vq).max() and np.abs(Vq).mean() > 5
     Uf, Uq = oracle.q_weights(g, G, r_u=r_u)
-    for k in range(2):
-        for c in range(2):
+    for k in range(K):
+        for c in range(C):
             tt = [[f0] * 3 for _ in range(n)]
             for i in range(n):
                 for b in range(3):
@@ -345,10 +406,14 @@ def test_fused_chain_order_on_dense_matrices(oracle):
                     assert Uf[i * n + j, k, c] == acc
                     assert Uq[i * n + j, k, c] == _rne_sat(Fraction(float(acc)) * Fraction(float(r_u)), 127)
     M = oracle.q_hadamard(Vq, Uq)
-    Yf, Yq, _ = oracle.q_output(M, AT, 1, 4, 4, pad=1, r_y=r_y)
-    for t in range(4):
-        th, tw = divmod(t, 2)
-        for k in range(2):
+    Yf, _, _ = oracle.q_output(M, AT, 1, H, W, pad=pad, r_y=1.0)
+    r_y = np.float32(110.0 / np.abs(Yf).max())          # codes spread over the whole range
+    Yf, Yq, _ = oracle.q_output(M, AT, 1, H, W, pad=pad, r_y=r_y)
+    assert Yq.shape == (1, K, Ho, Wo)
+    seen = np.zeros((Ho, Wo), bool)
+    for t in range(TH * TW):
+        th, tw = divmod(t, TW)
+        for k in range(K):
             z = [[f0] * n for _ in range(m)]
             for a in range(m):
                 for j in range(n):
@@ -358,12 +423,16 @@ def test_fused_chain_order_on_dense_matrices(oracle):
                     z[a][j] = acc
             for a in range(m):
                 for b in range(m):
+                    if th * m + a >= Ho or tw * m + b >= Wo:
+                        continue                       # outputs beyond the image are dropped
                     acc = f0
                     for j in range(n):
                         acc = _fma32(z[a][j], AT[b, j], acc)
                     assert Yf[0, k, th * m + a, tw * m + b] == acc
                     assert Yq[0, k, th * m + a, tw * m + b] == _rne_sat(
                         Fraction(float(acc)) * Fraction(float(r_y)), 127)
+                    seen[th * m + a, tw * m + b] = True
+    assert seen.all() and np.abs(Yq).max() >= 100 and np.abs(Yq).mean() > 10
 
 
 def test_q_scalars(oracle):
