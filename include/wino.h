@@ -82,7 +82,7 @@ typedef struct {
   int N, C, K, H, W;
   int pad;          /* 0 or 1 */
   int m;            /* 2, 4 or 6 */
-  wino_dtype dtype;
+  int dtype;        /* a wino_dtype, held as int so that any value can be passed and refused */
   const float* BT;
   const float* G;
   const float* AT;
@@ -201,7 +201,7 @@ wino_status wino_debug_export(const wino_desc* d, int which, const void* src_dev
  *   out_dev         out  DEVICE, workgroups * 256 floats (checksums, ignore)
  *   ops_per_launch  out  HOST, may be NULL: multiply-adds x 2 the launch performs
  * Time it with events on `stream`; ops / time is the achievable matrix rate. */
-wino_status wino_debug_mfma_loop(wino_dtype dtype, int workgroups, int iters, float* out_dev,
+wino_status wino_debug_mfma_loop(int dtype, int workgroups, int iters, float* out_dev,
                                  double* ops_per_launch, void* stream);
 
 /* Cook-Toom matrices for F(m,3) from m+1 distinct finite points (NULL = the
@@ -213,15 +213,15 @@ wino_status wino_cook_toom(int m, const double* points, float* BT, float* G, flo
  * stride 1 or 2: gather rows of 9*C taps, one GEMM, requantize/scatter.
  * Weights are packed once with conv2d_ref_pack_weights.
  * int8 mode: y = sat(rne(acc * (s_x*s_w/s_y))), codes in [-qmax,qmax]. */
-size_t conv2d_ref_packed_weights_bytes(int C, int K, wino_dtype dtype);
+size_t conv2d_ref_packed_weights_bytes(int C, int K, int dtype);
 size_t conv2d_ref_workspace_bytes(int N, int C, int K, int H, int W, int stride, int pad,
-                                  wino_dtype dtype);
+                                  int dtype);
 /*   w_dev   in  DEVICE [K][C][3][3], int8 codes or float
  *   wp_dev  out DEVICE packed weights                                         */
-wino_status conv2d_ref_pack_weights(int C, int K, wino_dtype dtype, const void* w_dev,
+wino_status conv2d_ref_pack_weights(int C, int K, int dtype, const void* w_dev,
                                     void* wp_dev, void* stream);
 wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pad,
-                           wino_dtype dtype, const void* x_dev, const void* wp_dev,
+                           int dtype, const void* x_dev, const void* wp_dev,
                            void* y_dev, float s_x, float s_w, float s_y, int qmax,
                            void* workspace_dev, size_t workspace_bytes, void* stream);
 

@@ -9,7 +9,9 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libwino.so")
+# WINO_LIB names another build of the same library (the sanitizer test loads one whose
+# host code is instrumented); it is still this library, never a substitute path.
+LIB_PATH = os.environ.get("WINO_LIB") or os.path.join(_HERE, "libwino.so")
 
 WINO_F32, WINO_I8, WINO_I16, WINO_I8W16 = 0, 1, 2, 3
 WINO_TAP_U, WINO_TAP_V, WINO_TAP_M = 0, 1, 2

@@ -482,7 +482,7 @@ wino_status wino_cook_toom(int m, const double* points, float* BT, float* G, flo
 
 // ------------------------------------------------------------ im2row baseline
 static wino_status make_ref_geom(int N, int C, int K, int H, int W, int stride, int pad,
-                                 wino_dtype dtype, RefGeom* g) {
+                                 int dtype, RefGeom* g) {
   if (dtype != WINO_F32 && dtype != WINO_I8) return WINO_E_BAD_DTYPE;
   if (N < 1 || C < 1 || K < 1 || H < 1 || W < 1) return WINO_E_BAD_SHAPE;
   if (stride != 1 && stride != 2) return WINO_E_BAD_ARG;
@@ -504,20 +504,20 @@ static wino_status make_ref_geom(int N, int C, int K, int H, int W, int stride, 
   return WINO_OK;
 }
 
-size_t conv2d_ref_packed_weights_bytes(int C, int K, wino_dtype dtype) {
+size_t conv2d_ref_packed_weights_bytes(int C, int K, int dtype) {
   if (C < 1 || K < 1 || (dtype != WINO_F32 && dtype != WINO_I8)) return 0;
   const int i8 = dtype == WINO_I8;
   return align256((size_t)round_up(K, 64) * 9 * round_up(C, i8 ? 64 : 16) * (i8 ? 1 : 4));
 }
 
 size_t conv2d_ref_workspace_bytes(int N, int C, int K, int H, int W, int stride, int pad,
-                                  wino_dtype dtype) {
+                                  int dtype) {
   RefGeom g;
   if (make_ref_geom(N, C, K, H, W, stride, pad, dtype, &g) != WINO_OK) return 0;
   return align256((size_t)g.Tp * 9 * g.Cp * (g.i8 ? 1 : 4)) + align256((size_t)g.Tp * g.Kp * 4);
 }
 
-wino_status conv2d_ref_pack_weights(int C, int K, wino_dtype dtype, const void* w_dev, void* wp_dev,
+wino_status conv2d_ref_pack_weights(int C, int K, int dtype, const void* w_dev, void* wp_dev,
                                     void* stream) {
   if (dtype != WINO_F32 && dtype != WINO_I8) return WINO_E_BAD_DTYPE;
   if (C < 1 || K < 1) return WINO_E_BAD_SHAPE;
@@ -532,7 +532,7 @@ wino_status conv2d_ref_pack_weights(int C, int K, wino_dtype dtype, const void* 
   return WINO_OK;
 }
 
-wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pad, wino_dtype dtype,
+wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pad, int dtype,
                            const void* x_dev, const void* wp_dev, void* y_dev, float s_x, float s_w,
                            float s_y, int qmax, void* workspace_dev, size_t workspace_bytes,
                            void* stream) {

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(int iters, float* __rest
 }  // namespace
 }  // namespace wino
 
-extern "C" wino_status wino_debug_mfma_loop(wino_dtype dtype, int workgroups, int iters,
+extern "C" wino_status wino_debug_mfma_loop(int dtype, int workgroups, int iters,
                                             float* out_dev, double* ops_per_launch,
                                             void* stream) {
   if (!out_dev) return WINO_E_NULL;
