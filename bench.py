@@ -268,7 +268,7 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
     # one, the int16 workload has no baseline)
     s_w = scales.get("s_w", 1.0)
     rdt = wb.WINO_F32 if L.dtype == "f32" else wb.WINO_I8
-    ms_ref = None
+    ms_ref = ms_ref_rows = None
     if L.dtype != "i16":
         if rdt == wb.WINO_I8:
             wq = workloads.input_codes(g, s_w)
@@ -286,6 +286,13 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
                               scales["s_y"], 127, rws, stream=stream)
 
         ms_ref = timed(ref_fwd, max(10, steps // 4), max(2, warmup // 4))
+
+        # the same baseline with the row matrix written out (three kernels)
+        def ref_rows_fwd():
+            wb.conv2d_ref_gpu_rows(L.N, L.C, L.K, L.H, L.W, 1, L.pad, rdt, x, wp, y, scales["s_x"],
+                                   s_w, scales["s_y"], 127, rws, stream=stream)
+
+        ms_ref_rows = timed(ref_rows_fwd, max(10, steps // 8), max(2, warmup // 8))
     extra = {}
     if cold:
         # cold: every call finds neither X, U nor anything else in L2 / Infinity Cache
@@ -329,7 +336,7 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
                 torch.cuda.synchronize()
                 extra[name] = ops / (a.elapsed_time(b) * 1e-3) / 1e12
         del big, dst
-    return dict(extra=extra, ms_step=ms_step, ms_fwd=ms_fwd, ms_ref=ms_ref, kernel_us=acc, staged_us=acc_staged,
+    return dict(extra=extra, ms_step=ms_step, ms_fwd=ms_fwd, ms_ref=ms_ref, ms_ref_rows=ms_ref_rows, kernel_us=acc, staged_us=acc_staged,
                 BT=BT, AT=AT)
 
 
@@ -573,8 +580,10 @@ def main():
         "fwd_only_ms": r["ms_fwd"],
         "fwd_only_tops": L.direct_ops / (r["ms_fwd"] * 1e-3) / 1e12,
         "im2row_baseline_ms": r["ms_ref"],
-        # (the baseline as built: im2row gather, one GEMM, requantizing epilogue; its own
-        # matrix-core fraction next to the ratio, so that a weak baseline shows)
+        # (the baseline as built: for int8 one kernel that gathers the im2row rows in LDS,
+        # multiplies and requantizes; its own matrix-core fraction next to the ratio, so
+        # that a weak baseline shows; `im2row_rows_ms` is the form that writes the row matrix)
+        "im2row_rows_ms": r["ms_ref_rows"],
         "im2row_baseline_tops": L.direct_ops / (r["ms_ref"] * 1e-3) / 1e12 if r["ms_ref"] else None,
         "im2row_baseline_mfma_frac": (L.direct_ops / (r["ms_ref"] * 1e-3) / 1e12 /
                                       MFMA_PEAK["f32" if L.dtype == "f32" else "int8"])

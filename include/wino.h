@@ -209,10 +209,16 @@ wino_status wino_debug_mfma_loop(int dtype, int workgroups, int iters, float* ou
  * (Sec. 3.1).  HOST outputs: BT n*n, G n*3, AT m*n floats. */
 wino_status wino_cook_toom(int m, const double* points, float* BT, float* G, float* AT);
 
-/* Baseline the paper compares against: im2row 3x3 convolution (Sec. 5.3),
- * stride 1 or 2: gather rows of 9*C taps, one GEMM, requantize/scatter.
- * Weights are packed once with conv2d_ref_pack_weights.
- * int8 mode: y = sat(rne(acc * (s_x*s_w/s_y))), codes in [-qmax,qmax]. */
+/* Baseline the paper compares against: im2row 3x3 convolution (Sec. 5.3, Table 3),
+ * stride 1 or 2: every output pixel is a row of 9*C taps, one GEMM with the packed
+ * weights, requantize and scatter to NCHW.  Weights are packed once with
+ * conv2d_ref_pack_weights.
+ * int8 mode: y = sat(rne(acc * (s_x*s_w/s_y))), codes in [-qmax,qmax].
+ * conv2d_ref_gpu runs int8 as ONE kernel that gathers the rows of its pixels in LDS
+ * and never writes the row matrix (the workspace is then left untouched), fp32 as
+ * three kernels (gather to the workspace, GEMM, epilogue); conv2d_ref_gpu_rows always
+ * runs the three kernels.  Both give the same y; both take the same arguments and
+ * need the same workspace size. */
 size_t conv2d_ref_packed_weights_bytes(int C, int K, int dtype);
 size_t conv2d_ref_workspace_bytes(int N, int C, int K, int H, int W, int stride, int pad,
                                   int dtype);
@@ -224,6 +230,10 @@ wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pa
                            int dtype, const void* x_dev, const void* wp_dev,
                            void* y_dev, float s_x, float s_w, float s_y, int qmax,
                            void* workspace_dev, size_t workspace_bytes, void* stream);
+wino_status conv2d_ref_gpu_rows(int N, int C, int K, int H, int W, int stride, int pad,
+                                int dtype, const void* x_dev, const void* wp_dev,
+                                void* y_dev, float s_x, float s_w, float s_y, int qmax,
+                                void* workspace_dev, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

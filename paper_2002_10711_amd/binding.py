@@ -23,7 +23,7 @@ EXPORTS = [
     "wino_conv2d_fwd_stages", "wino_fwd_num_kernels",
     "wino_debug_export", "wino_debug_mfma_loop", "wino_cook_toom",
     "conv2d_ref_packed_weights_bytes", "conv2d_ref_workspace_bytes",
-    "conv2d_ref_pack_weights", "conv2d_ref_gpu",
+    "conv2d_ref_pack_weights", "conv2d_ref_gpu", "conv2d_ref_gpu_rows",
 ]
 
 
@@ -88,9 +88,9 @@ def lib():
         L.conv2d_ref_packed_weights_bytes.argtypes = [ctypes.c_int] * 3
         L.conv2d_ref_workspace_bytes.argtypes = [ctypes.c_int] * 8
         L.conv2d_ref_pack_weights.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 3
-        L.conv2d_ref_gpu.argtypes = ([ctypes.c_int] * 8 + [ctypes.c_void_p] * 3 +
-                                     [ctypes.c_float] * 3 + [ctypes.c_int, ctypes.c_void_p,
-                                                             ctypes.c_size_t, ctypes.c_void_p])
+        for f in (L.conv2d_ref_gpu, L.conv2d_ref_gpu_rows):
+            f.argtypes = ([ctypes.c_int] * 8 + [ctypes.c_void_p] * 3 + [ctypes.c_float] * 3 +
+                          [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p])
         _lib = L
     return _lib
 
@@ -252,3 +252,12 @@ def conv2d_ref_gpu(N, C, K, H, W, stride, pad, dtype, x_dev, wp_dev, y_dev, s_x,
     _check(lib().conv2d_ref_gpu(N, C, K, H, W, stride, pad, dtype, _ptr(x_dev), _ptr(wp_dev),
                                 _ptr(y_dev), s_x, s_w, s_y, qmax, _ptr(workspace_dev),
                                 workspace_bytes, _stream(stream)), "conv2d_ref_gpu")
+
+
+def conv2d_ref_gpu_rows(N, C, K, H, W, stride, pad, dtype, x_dev, wp_dev, y_dev, s_x, s_w, s_y, qmax,
+                   workspace_dev, workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = workspace_dev.numel() * workspace_dev.element_size()
+    _check(lib().conv2d_ref_gpu_rows(N, C, K, H, W, stride, pad, dtype, _ptr(x_dev), _ptr(wp_dev),
+                                _ptr(y_dev), s_x, s_w, s_y, qmax, _ptr(workspace_dev),
+                                workspace_bytes, _stream(stream)), "conv2d_ref_gpu_rows")

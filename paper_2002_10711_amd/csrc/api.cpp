@@ -532,10 +532,11 @@ wino_status conv2d_ref_pack_weights(int C, int K, int dtype, const void* w_dev, 
   return WINO_OK;
 }
 
-wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pad, int dtype,
-                           const void* x_dev, const void* wp_dev, void* y_dev, float s_x, float s_w,
-                           float s_y, int qmax, void* workspace_dev, size_t workspace_bytes,
-                           void* stream) {
+// explicit: always the three-kernel form that writes the row matrix.
+static wino_status ref_conv(int N, int C, int K, int H, int W, int stride, int pad, int dtype,
+                            const void* x_dev, const void* wp_dev, void* y_dev, float s_x, float s_w,
+                            float s_y, int qmax, void* workspace_dev, size_t workspace_bytes,
+                            void* stream, bool explicit_rows) {
   RefGeom g;
   wino_status st = make_ref_geom(N, C, K, H, W, stride, pad, dtype, &g);
   if (st != WINO_OK) return st;
@@ -554,6 +555,11 @@ wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pa
       !aligned256(wp_dev))
     return WINO_E_WORKSPACE;
   hipStream_t hs = (hipStream_t)stream;
+  if (!explicit_rows && conv_implicit_supported(g)) {
+    if (launch_conv_implicit(g, x_dev, wp_dev, y_dev, r_y, (float)qmax, hs) != hipSuccess)
+      return WINO_E_HIP;
+    return WINO_OK;
+  }
   void* rows = workspace_dev;
   void* M = (char*)workspace_dev + rows_b;
   if (launch_im2row(g, x_dev, rows, hs) != hipSuccess) return WINO_E_HIP;
@@ -561,6 +567,22 @@ wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pa
     return WINO_E_HIP;
   if (launch_ref_epilogue(g, M, y_dev, r_y, (float)qmax, hs) != hipSuccess) return WINO_E_HIP;
   return WINO_OK;
+}
+
+wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pad, int dtype,
+                           const void* x_dev, const void* wp_dev, void* y_dev, float s_x, float s_w,
+                           float s_y, int qmax, void* workspace_dev, size_t workspace_bytes,
+                           void* stream) {
+  return ref_conv(N, C, K, H, W, stride, pad, dtype, x_dev, wp_dev, y_dev, s_x, s_w, s_y, qmax,
+                  workspace_dev, workspace_bytes, stream, false);
+}
+
+wino_status conv2d_ref_gpu_rows(int N, int C, int K, int H, int W, int stride, int pad, int dtype,
+                                const void* x_dev, const void* wp_dev, void* y_dev, float s_x,
+                                float s_w, float s_y, int qmax, void* workspace_dev,
+                                size_t workspace_bytes, void* stream) {
+  return ref_conv(N, C, K, H, W, stride, pad, dtype, x_dev, wp_dev, y_dev, s_x, s_w, s_y, qmax,
+                  workspace_dev, workspace_bytes, stream, true);
 }
 
 }  // extern "C"

@@ -171,5 +171,9 @@ hipError_t launch_ref_pack_weights(int C, int K, int Cp, int Kp, int i8, const v
 hipError_t launch_im2row(const RefGeom& g, const void* x, void* rows, hipStream_t s);
 hipError_t launch_ref_epilogue(const RefGeom& g, const void* M, void* y, float r_y, float qmax,
                                hipStream_t s);
+// The same convolution as one kernel that gathers its rows in LDS (int8 only).
+bool conv_implicit_supported(const RefGeom& g);
+hipError_t launch_conv_implicit(const RefGeom& g, const void* x, const void* wp, void* y, float r_y,
+                                float qmax, hipStream_t s);
 
 }  // namespace wino

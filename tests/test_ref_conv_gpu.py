@@ -15,10 +15,20 @@ CASES = [
     Layer("r3", 2, 7, 5, 7, 5, stride=2, seed=203),
     Layer("r4", 1, 130, 70, 6, 10, stride=1, pad=0, seed=204),
     Layer("r5", 8, 64, 64, 32, 32, stride=1, seed=205),
+    # several whole images per workgroup, the last group ragged; two chunks of channels
+    Layer("r6_4x4_out", 5, 100, 128, 8, 8, stride=2, seed=206),
+    Layer("r7_4x4_in", 7, 64, 130, 4, 4, stride=1, seed=207),
+    # more than 64 output columns: two column blocks; rows not a multiple of four wide
+    Layer("r8_wide", 1, 8, 16, 5, 70, stride=1, seed=208),
+    Layer("r9_wide_s2", 1, 8, 16, 7, 141, stride=2, seed=209),
+    # one output pixel per image
+    Layer("r10_1x1", 70, 9, 12, 3, 3, stride=1, pad=0, seed=210),
+    Layer("r11_30", 2, 16, 64, 30, 30, stride=1, seed=211),
 ]
+ENTRY = ["conv2d_ref_gpu", "conv2d_ref_gpu_rows"]
 
 
-def _run(L, x_np, w_np, i8, s=(1.0, 1.0, 1.0)):
+def _run(L, x_np, w_np, i8, s=(1.0, 1.0, 1.0), entry="conv2d_ref_gpu", odd=False):
     import torch
     from paper_2002_10711_amd import binding as wb
     dev = torch.device("cuda:0")
@@ -28,14 +38,25 @@ def _run(L, x_np, w_np, i8, s=(1.0, 1.0, 1.0)):
     ws = torch.empty(wb.conv2d_ref_workspace_bytes(L.N, L.C, L.K, L.H, L.W, L.stride, L.pad, dt),
                      dtype=torch.uint8, device=dev)
     y = torch.full((L.N, L.K, L.Ho, L.Wo), 77, dtype=torch.int8 if i8 else torch.float32, device=dev)
+    if odd:                                  # both tensors one element off their allocation
+        xb = torch.empty(x.numel() + 1, dtype=x.dtype, device=dev)
+        yb = torch.full((y.numel() + 2,), 77, dtype=y.dtype, device=dev)
+        xb[1:].copy_(x.reshape(-1))
+        x, y = xb[1:], yb[1:-1].view(y.shape)
     wb.conv2d_ref_pack_weights(L.C, L.K, dt, w, wp)
-    wb.conv2d_ref_gpu(L.N, L.C, L.K, L.H, L.W, L.stride, L.pad, dt, x, wp, y, s[0], s[1], s[2], 127, ws)
+    getattr(wb, entry)(L.N, L.C, L.K, L.H, L.W, L.stride, L.pad, dt, x, wp, y, s[0], s[1], s[2],
+                       127, ws)
     torch.cuda.synchronize()
+    if odd:
+        assert int(yb[0]) == 77 and int(yb[-1]) == 77        # nothing written outside y
     return y.cpu().numpy()
 
 
+@pytest.mark.parametrize("entry,odd", [("conv2d_ref_gpu", False), ("conv2d_ref_gpu", True),
+                                       ("conv2d_ref_gpu_rows", False)],
+                         ids=["one_kernel", "one_kernel_odd_addresses", "three_kernels"])
 @pytest.mark.parametrize("L", CASES, ids=lambda l: l.name)
-def test_ref_conv_int8(oracle, L):
+def test_ref_conv_int8(oracle, L, entry, odd):
     X, g = make_inputs(L)
     s_x, s_w = np.float32(np.abs(X).max() / 127), np.float32(np.abs(g).max() / 127)
     xq, wq = oracle.quantize_tensor(X, s_x), oracle.quantize_tensor(g, s_w)
@@ -43,7 +64,9 @@ def test_ref_conv_int8(oracle, L):
     s_y = np.float32(s_x * s_w * np.abs(acc).max() / 127 * 0.8)      # a little saturation
     r_y = np.float32(np.float32(s_x * s_w) / s_y)
     _, Yq = oracle.conv2d_direct_q(xq, wq, r_y, stride=L.stride, pad=L.pad)
-    y = _run(L, xq.astype(np.int8), wq.astype(np.int8), True, (float(s_x), float(s_w), float(s_y)))
+    print("case", L.name, entry, "odd" if odd else "aligned", flush=True)
+    y = _run(L, xq.astype(np.int8), wq.astype(np.int8), True, (float(s_x), float(s_w), float(s_y)),
+             entry, odd)
     assert np.abs(Yq).max() == 127
     assert np.array_equal(y.astype(np.int32), Yq)
 
