@@ -33,7 +33,7 @@
 #include <string.h>
 
 #ifndef WINO_EXACT_M
-#error "define WINO_EXACT_M (2 or 4): the tile size this translation unit instantiates"
+#error "define WINO_EXACT_M (2, 4 or 6): the tile size this translation unit instantiates"
 #endif
 
 #include "fastdiv.h"
@@ -58,13 +58,23 @@ namespace wino {
 namespace {
 
 // F(2x2,3x3) and F(4x4,3x3): the n x n patch fits the 8 x 8 window and the products of
-// the usual matrices fit int8; F(6x6,3x3) does not (4 B^T reaches 21, products 441).
+// the usual matrices fit int8.  F(6x6,3x3) fills the window (n = 8) and its products do not
+// fit (4 B^T reaches 21, products 441): there W is split into two int8 digits,
+// W = 16 Wh + Wl with Wl in [-8, 7], two MFMAs per block of 16 positions whose results are
+// recombined in integers (exact), and the digits are built inside the kernel (two 64 x 64
+// byte matrices exceed what kernel arguments can carry): the wavefronts compute one block
+// of 16 positions each and hand it to the others through LDS.  Only the stand-alone input
+// stage exists for F(6x6,3x3): 64 accumulator sets do not fit a one-kernel forward.
 
 // LDS geometry of the staged input: a row holds the image columns from tw0*m - pad on,
 // up to the second dword of the last tile's window (which starts at byte (TWB-1)*m); a
 // channel plane is n rows, made odd so that the 16 channels of a window group fall into
 // 16 different banks.
-__host__ __device__ inline int xs_row_dw(int M, int TWB) { return (((TWB - 1) * M) >> 2) + 2; }
+// (m = 6: all eight window columns are used and a window may start in mid-dword, so it can
+// reach into a third dword)
+__host__ __device__ inline int xs_row_dw(int M, int TWB) {
+  return (((TWB - 1) * M) >> 2) + (M == 6 ? 3 : 2);
+}
 __host__ __device__ inline int xs_plane_dw(int M, int TWB) {
   return ((M + 2) * xs_row_dw(M, TWB)) | 1;
 }
@@ -79,6 +89,10 @@ constexpr int kVlPitch = 16 * 16 + 4;
 // (j, l) = (2*(lane/16) + b/8, b%8), b = 0..15, of row p = blk*16 + lane%16 (zero for
 // p >= 36 and for j, l >= 6).
 struct KronW { uint32_t v[3 * 64 * 4]; };
+// F(6x6,3x3): the integer matrix 2^s B^T itself; the kernel builds W's digits from it.
+struct KronB { int bi[64]; };
+template <int M> struct KronArg { typedef KronW type; };
+template <> struct KronArg<6> { typedef KronB type; };
 
 // Per-position factors of the two quantizer sites of the fused kernels (n*n <= 36
 // positions): rv[p] multiplies the transformed input before rounding (every entry the
@@ -95,6 +109,7 @@ struct XPlan {
   uint32_t inv_twb;          // numerators < 16
   uint32_t inv_strip, inv_wq;   // numerators < 256
   uint32_t inv_th;           // numerators < N * TH
+  int w_off;                 // F(6x6,3x3): dword offset in LDS of the digits of W
 };
 
 // kLoad: 0 = byte loads (W < 4), 1 = one dword per lane at any byte address,
@@ -550,9 +565,11 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
 template <int M, int kLoad, int kTWB>
 __global__ __launch_bounds__(256) void input_transform_exact_kernel(
     const int8_t* __restrict__ x, int8_t* __restrict__ V, PosScale rvs, float qmax, Geom g,
-    XPlan pl, KronW kw) {
+    XPlan pl, typename KronArg<M>::type kw) {
   constexpr int n = M + 2, P = n * n;
   constexpr int NBLK = (P + 15) / 16, NSTEP = 16 * NBLK;
+  constexpr int ND = M == 6 ? 2 : 1;                   // int8 digits of W
+  static_assert(M != 6 || NBLK == 4, "one block of positions per wavefront builds W");
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   uint32_t* Xs = lds;
   uint32_t* Vl = lds;                                  // aliases Xs
@@ -570,10 +587,40 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
   float rq[NBLK];
 #pragma unroll
   for (int blk = 0; blk < NBLK; ++blk) rq[blk] = rvs.r[blk * 16 + r < P ? blk * 16 + r : P - 1];
-  v4i Wb[NBLK];
+  v4i Wb[NBLK * ND];
+  if constexpr (M != 6) {
 #pragma unroll
-  for (int blk = 0; blk < NBLK; ++blk) Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
+    for (int blk = 0; blk < NBLK; ++blk) Wb[blk] = *(const v4i*)&kw.v[(blk * 64 + lane) * 4];
+  }
   __syncthreads();
+
+  if constexpr (M == 6) {
+    // Digits of W, block `wave` (positions p = wave*16 + r: i = p / 8, k = p % 8): the lane's
+    // 16 bytes are the patch entries (j, l) = (2 grp + b / 8, b % 8), W = bi[i][j] * bi[k][l],
+    // Wh = floor((W + 8) / 16), Wl = W - 16 Wh.  Stored as [block][digit][lane] x 16 bytes.
+    const int i = 2 * wave + (r >> 3), k = r & 7;
+    int bk[8];
+#pragma unroll
+    for (int l = 0; l < 8; ++l) bk[l] = kw.bi[k * 8 + l];
+    uint32_t wl[4], wh[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const int bij = kw.bi[i * 8 + 2 * grp + (d >> 1)];
+      uint32_t ql = 0, qh = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int w = bij * bk[(d & 1) * 4 + e];
+        const int h = (w + 8) >> 4;
+        qh |= ((uint32_t)h & 0xffu) << (8 * e);
+        ql |= ((uint32_t)(w - 16 * h) & 0xffu) << (8 * e);
+      }
+      wl[d] = ql;
+      wh[d] = qh;
+    }
+    v4i* Wl = (v4i*)(lds + pl.w_off);
+    Wl[(wave * 2 + 0) * 64 + lane] = v4i{(int)wl[0], (int)wl[1], (int)wl[2], (int)wl[3]};
+    Wl[(wave * 2 + 1) * 64 + lane] = v4i{(int)wh[0], (int)wh[1], (int)wh[2], (int)wh[3]};
+  }
 
   // window operands: see fused_fwd_exact_kernel
   v4i Aw[16];
@@ -594,6 +641,13 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
         const uint32_t* p1 = p0 + cg * 16 * plane;
         if constexpr (M == 4) {
           Aw[t4 * 4 + cg] = v4i{(int)p1[0], (int)p1[1], (int)p1[dj], (int)p1[dj + 1]};
+        } else if constexpr (M == 6) {
+          // all eight columns count: both dwords of a row are shifted into place
+          const uint32_t a0 = __builtin_amdgcn_alignbyte(p1[1], p1[0], sh);
+          const uint32_t a1 = __builtin_amdgcn_alignbyte(p1[2], p1[1], sh);
+          const uint32_t b0 = __builtin_amdgcn_alignbyte(p1[dj + 1], p1[dj], sh);
+          const uint32_t b1 = __builtin_amdgcn_alignbyte(p1[dj + 2], p1[dj + 1], sh);
+          Aw[t4 * 4 + cg] = v4i{(int)a0, (int)a1, (int)b0, (int)b1};
         } else {
           const uint32_t a0 = __builtin_amdgcn_alignbyte(p1[1], p1[0], sh);
           const uint32_t a1 = __builtin_amdgcn_alignbyte(p1[dj + 1], p1[dj], sh);
@@ -603,16 +657,30 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
     }
   }
   __syncthreads();                                     // Xs is free: Vl may overwrite it
+  if constexpr (M == 6) {
+    const v4i* Wl = (const v4i*)(lds + pl.w_off);
+#pragma unroll
+    for (int q = 0; q < NBLK * ND; ++q) Wb[q] = Wl[q * 64 + lane];
+  }
 
   uint32_t* lane_v = Vl + r * kVlPitch + grp;
-  v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], v4i{0, 0, 0, 0}, 0, 0, 0);
+  const v4i zero4 = v4i{0, 0, 0, 0};
+  // (two digits: cur / curh hold 4^s V's low and high parts, recombined when consumed)
+  v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], zero4, 0, 0, 0);
+  v4i curh = zero4;
+  if constexpr (ND == 2) curh = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[1], zero4, 0, 0, 0);
 #pragma unroll
   for (int st = 0; st < NSTEP; ++st) {
     const int gi = st / NBLK, blk = st % NBLK;
-    v4i nxt = cur;
-    if (st + 1 < NSTEP)
-      nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
-                                                  v4i{0, 0, 0, 0}, 0, 0, 0);
+    v4i nxt = cur, nxth = curh;
+    if (st + 1 < NSTEP) {
+      nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[((st + 1) % NBLK) * ND],
+                                                  zero4, 0, 0, 0);
+      if constexpr (ND == 2)
+        nxth = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK],
+                                                     Wb[((st + 1) % NBLK) * ND + 1], zero4, 0, 0, 0);
+    }
+    if constexpr (ND == 2) cur = (curh << 4) + cur;
     const uint32_t packed = pack_codes(quantize_bits((float)cur[0], rq[blk], lo, hi),
                                        quantize_bits((float)cur[1], rq[blk], lo, hi),
                                        quantize_bits((float)cur[2], rq[blk], lo, hi),
@@ -620,6 +688,7 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
     const int tl = wave * 4 + (gi >> 2);
     if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
     cur = nxt;
+    curh = nxth;
   }
   __syncthreads();
 
@@ -654,7 +723,9 @@ static bool narrow_ok(const Geom& g) { return g.W >= 4 || g.TW <= 2; }
 // every intermediate of the fp32 evaluation exactly representable (so that integer and
 // float evaluation agree bit for bit); -1 if there is none.
 int exact_input_shift(const Geom& g, const MatBT& bt) {
-  if (!g.i8 || (g.m != 2 && g.m != 4)) return -1;
+  if (!g.i8 || (g.m != 2 && g.m != 4 && g.m != 6)) return -1;
+  // products of two entries: one int8 digit for m = 2, 4; two digits (base 16) for m = 6
+  const float prodmax = g.m == 6 ? 2031.0f : 127.0f;
   for (int s = 0; s <= 3; ++s) {
     const float sc = (float)(1 << s);
     bool ok = true;
@@ -671,7 +742,7 @@ int exact_input_shift(const Geom& g, const MatBT& bt) {
       rowmax = rowsum > rowmax ? rowsum : rowmax;
     }
     if (!ok) continue;
-    if (amax * amax > 127.0f) return -1;
+    if (amax * amax > prodmax) return -1;
     // |4^s V| <= 128 * rowmax^2 must stay below 2^24 (fp32 exact integers)
     if (128.0f * rowmax * rowmax >= 16777216.0f) return -1;
     return s;
@@ -694,7 +765,8 @@ bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
   // plus the GEMM + output kernel: 256 channels 24.6 vs 20.6 us, 512 channels 46.8 vs 31.7)
   // (and with fewer than 128 workgroups a long reduction leaves most of the chip idle for
   // the whole of it: 512 channels, F2, 1 k tiles: 35 vs 15 us as two kernels)
-  return g.Kp <= 128 && narrow_ok(g) && (g.W >= 4 || g.Cp == 64) && (g.m == 2 || g.Cp <= 192) &&
+  return (g.m == 2 || g.m == 4) && g.Kp <= 128 && narrow_ok(g) && (g.W >= 4 || g.Cp == 64) &&
+         (g.m == 2 || g.Cp <= 192) &&
          (g.Cp <= 128 || g.T >= 2048) && input_exact_supported(g, bt);
 }
 
@@ -711,6 +783,7 @@ namespace {
 // the LDS size and the grid extents along tile rows and row pieces.
 struct XLaunch {
   KronW kw;
+  KronB kb;
   XPlan pl;
   float r_vs;
   size_t lds_bytes;
@@ -731,7 +804,9 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   int bi[8][8] = {};
   for (int i = 0; i < n; ++i)
     for (int j = 0; j < n; ++j) bi[i][j] = (int)(bt.v[i * n + j] * bt_scale);
-  for (int blk = 0; blk < NBLK; ++blk)
+  for (int i = 0; i < 8; ++i)
+    for (int j = 0; j < 8; ++j) xl->kb.bi[i * 8 + j] = bi[i][j];
+  for (int blk = 0; M != 6 && blk < NBLK; ++blk)
     for (int lane = 0; lane < 64; ++lane) {
       const int p = blk * 16 + (lane & 15), kgrp = lane >> 4;
       const int i = p < P ? p / n : 7, k = p < P ? p % n : 7;     // row 7 of bi is zero
@@ -754,11 +829,18 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   // (+ 20 dwords: the dump area of surplus staging lanes, up to one staged row)
   const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(M, TWB) + 20) * 4, vl_b = (size_t)P * kVlPitch * 4;
   xl->lds_bytes = xs_b > vl_b ? xs_b : vl_b;
+  XPlan& pl = xl->pl;
+  pl.w_off = 0;
+  if (M == 6) {
+    // the digits of W behind the staging / V region: [4 blocks][2 digits][64 lanes] x 16 bytes
+    xl->lds_bytes = (xl->lds_bytes + 15) / 16 * 16;
+    pl.w_off = (int)(xl->lds_bytes / 4);
+    xl->lds_bytes += 8192;
+  }
   xl->ntwb = (g.TW + TWB - 1) / TWB;
   xl->nrb = (R + RB - 1) / RB;
   const int strip = n * xs_row_dw(M, TWB);
-  if (xl->lds_bytes > 65536 || xl->ntwb > 65535 || strip > 256) return false;
-  XPlan& pl = xl->pl;
+  if (xl->lds_bytes > (M == 6 ? 81920u : 65536u) || xl->ntwb > 65535 || strip > 256) return false;
   pl.RB = RB;
   pl.TWB = TWB;
   pl.inv_twb = make_inv(TWB);
@@ -767,7 +849,7 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   pl.inv_th = make_inv(g.TH);
   xl->load = g.W < 4 ? 0 : (g.W % 4 == 0 && g.W >= 8 && ((uintptr_t)x & 3) == 0) ? 2 : 1;
   // whole-row staging: the workgroup spans the image width, rows are 8, 16, 32 or 64 bytes
-  if (xl->load == 2 && g.pad == 1 && g.TW == TWB && g.W == TWB * M && g.W >= 8 &&
+  if (M != 6 && xl->load == 2 && g.pad == 1 && g.TW == TWB && g.W == TWB * M && g.W >= 8 &&
       ((uintptr_t)x & (g.W >= 16 ? 15 : 7)) == 0)
     xl->load = 3;
   return true;
@@ -789,12 +871,26 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
   const int8_t* xi = (const int8_t*)x;
   int8_t* Vi = (int8_t*)V;
   const int TWB = xl.pl.TWB;
+  typename KronArg<M>::type karg;
+  if constexpr (M == 6) karg = xl.kb;
+  else karg = xl.kw;
 #define WINO_LAUNCH_IN(LOAD, TWBC)                                                         \
-  input_transform_exact_kernel<M, LOAD, TWBC><<<grid, 256, xl.lds_bytes, s>>>(               \
-      xi, Vi, rvs, qmax, g, xl.pl, xl.kw)
-#define WINO_LAUNCH_IN2(TWBC) \
-  do { if (xl.load == 3) WINO_LAUNCH_IN(3, TWBC); else if (xl.load == 2) WINO_LAUNCH_IN(2, TWBC); \
-       else WINO_LAUNCH_IN(1, TWBC); } while (0)
+  do {                                                                                     \
+    auto kern = input_transform_exact_kernel<M, LOAD, TWBC>;                               \
+    if (xl.lds_bytes > 65536) {                                                            \
+      const hipError_t e = hipFuncSetAttribute(                                            \
+          (const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)xl.lds_bytes); \
+      if (e != hipSuccess) return e;                                                       \
+    }                                                                                      \
+    kern<<<grid, 256, xl.lds_bytes, s>>>(xi, Vi, rvs, qmax, g, xl.pl, karg);               \
+  } while (0)
+#define WINO_LAUNCH_IN2(TWBC)                                                              \
+  do {                                                                                     \
+    if (xl.load == 3) {                                                                    \
+      if constexpr (M != 6) WINO_LAUNCH_IN(3, TWBC);                                       \
+    } else if (xl.load == 2) WINO_LAUNCH_IN(2, TWBC);                                      \
+    else WINO_LAUNCH_IN(1, TWBC);                                                          \
+  } while (0)
   if (xl.load == 0) {                                    // byte-wise staging: see narrow_ok
     if (TWB != 2) return hipErrorInvalidValue;
     WINO_LAUNCH_IN(0, 2);
@@ -918,7 +1014,12 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
 
 }  // namespace
 
-#if WINO_EXACT_M == 2
+#if WINO_EXACT_M == 6
+hipError_t launch_input_exact_m6(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
+                                 float qmax, hipStream_t s, const PosScale* rv_pos) {
+  return launch_input_m<6>(g, bt, x, V, r_v, qmax, s, rv_pos);
+}
+#elif WINO_EXACT_M == 2
 hipError_t launch_input_exact_m2(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
                                  float qmax, hipStream_t s, const PosScale* rv_pos) {
   return launch_input_m<2>(g, bt, x, V, r_v, qmax, s, rv_pos);
@@ -932,6 +1033,8 @@ hipError_t launch_fused_fwd_exact_m2(const Geom& g, const MatBT& bt, const MatAT
 #else
 hipError_t launch_input_exact_m2(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
                                  float qmax, hipStream_t s, const PosScale* rv_pos);
+hipError_t launch_input_exact_m6(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
+                                 float qmax, hipStream_t s, const PosScale* rv_pos);
 hipError_t launch_fused_fwd_exact_m2(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                                      const void* U, void* y, float r_v, float r_m, float r_y,
                                      float qmax, const PosScale* rv_pos, const PosScale* w_pos,
@@ -941,6 +1044,7 @@ hipError_t launch_input_exact(const Geom& g, const MatBT& bt, const void* x, voi
                               float qmax, hipStream_t s, const PosScale* rv_pos) {
   if (g.m == 2) return launch_input_exact_m2(g, bt, x, V, r_v, qmax, s, rv_pos);
   if (g.m == 4) return launch_input_m<4>(g, bt, x, V, r_v, qmax, s, rv_pos);
+  if (g.m == 6) return launch_input_exact_m6(g, bt, x, V, r_v, qmax, s, rv_pos);
   return hipErrorInvalidValue;
 }
 

@@ -133,6 +133,11 @@ SMALL = [
     Layer("s_f2_c500_k72_7px_1024tiles", 64, 500, 72, 7, 7, m=2, seed=182),    # ragged tiles, K = 64 + 8
     Layer("s_f2_c512_k128_4px_1024tiles", 256, 512, 128, 4, 4, m=2, seed=183),  # whole images: staged stores
     Layer("s_f2_c450_k64_8px_1040tiles", 65, 450, 64, 8, 8, m=2, seed=184),     # last tile block half empty
+    # F6 with the Cook-Toom B^T: input transform on the matrix cores (two int8 digits of W)
+    Layer("s_f6_pad0_20px", 2, 70, 33, 20, 20, m=6, pad=0, seed=185),          # 3 x 3 whole tiles, two channel blocks
+    Layer("s_f6_w5_h9", 3, 24, 20, 9, 5, m=6, seed=186),                       # odd width: unaligned dword loads
+    Layer("s_f6_112px", 1, 8, 16, 30, 112, m=6, seed=187),                     # 19 tiles per row: two row pieces of 16
+    Layer("s_f6_24px_c130", 2, 130, 64, 24, 24, m=6, seed=188),                # 4 tiles per row, ragged channel block
     Layer("s_flex_f2_c512_k70_1024tiles", 16, 512, 70, 16, 16, m=2, flex_sigma=0.02, seed=185),
 ]
 
