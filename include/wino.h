@@ -174,6 +174,28 @@ wino_status wino_conv2d_fwd_noalloc(const wino_desc* d, const wino_quant* q, con
  * d->AT (HOST) if they are not NULL: which variant applies can depend on them. */
 int wino_fwd_num_kernels(const wino_desc* d);
 
+/* Kernel sequences of the int8 forward.  wino_conv2d_fwd picks one from a table of times
+ * measured on MI355X over a grid of layer shapes (as the paper picks the algorithm per layer
+ * from measured latencies, Sec. 5.3); the calls below let a tuner or a test name it. */
+#define WINO_SEQ_AUTO 0    /* the table's choice                                          */
+#define WINO_SEQ_FUSED 1   /* one kernel                                                   */
+#define WINO_SEQ_COL 2     /* input stage; GEMM + column-wise output transform             */
+#define WINO_SEQ_COL2 3    /* ... two tile blocks per wavefront                            */
+#define WINO_SEQ_LDS 4     /* input stage; GEMM + output transform, 32 x 64 workgroup tiles */
+#define WINO_SEQ_REGS 5    /* input stage; GEMM + output transform, accumulators in registers */
+#define WINO_SEQ_STAGED 6  /* input stage; GEMM writing M; output transform               */
+#define WINO_SEQ_COUNT 7
+/* seq = WINO_SEQ_AUTO: the sequence wino_conv2d_fwd takes for this problem; any other seq:
+ * seq itself if that sequence can run the problem, else 0.  0 also for an invalid
+ * descriptor and for dtypes other than WINO_I8.  HOST only; reads d->BT if not NULL. */
+int wino_fwd_sequence(const wino_desc* d, int seq);
+/* wino_conv2d_fwd with the kernel sequence named by the caller (same arguments, results
+ * and checks; the workspace must hold wino_workspace_bytes(d)).  WINO_E_BAD_ARG if the
+ * sequence cannot run the problem (wino_fwd_sequence(d, seq) == 0). */
+wino_status wino_conv2d_fwd_seq(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                                const void* U_dev, void* y_dev, void* workspace_dev,
+                                size_t workspace_bytes, int seq, void* stream);
+
 /* The same forward, restricted to the stages named in `stages` (a mask of
  * WINO_STAGE_*), for per-kernel timing and for tests: a stage reads what the
  * previous one left in the workspace.  WINO_STAGE_ALL is wino_conv2d_fwd.

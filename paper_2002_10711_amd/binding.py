@@ -20,7 +20,7 @@ WINO_STAGE_INPUT, WINO_STAGE_GEMM, WINO_STAGE_OUTPUT, WINO_STAGE_ALL = 1, 2, 4, 
 EXPORTS = [
     "wino_status_string", "wino_weights_bytes", "wino_workspace_bytes",
     "wino_transform_weights", "wino_conv2d_fwd", "wino_conv2d_fwd_noalloc",
-    "wino_conv2d_fwd_stages", "wino_fwd_num_kernels",
+    "wino_conv2d_fwd_stages", "wino_fwd_num_kernels", "wino_fwd_sequence", "wino_conv2d_fwd_seq",
     "wino_debug_export", "wino_debug_mfma_loop", "wino_cook_toom",
     "conv2d_ref_packed_weights_bytes", "conv2d_ref_workspace_bytes",
     "conv2d_ref_pack_weights", "conv2d_ref_gpu", "conv2d_ref_gpu_rows",
@@ -72,6 +72,11 @@ def lib():
         L.wino_conv2d_fwd.argtypes = [ctypes.POINTER(WinoDesc), ctypes.POINTER(WinoQuant),
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.wino_conv2d_fwd_seq.argtypes = [ctypes.POINTER(WinoDesc), ctypes.POINTER(WinoQuant),
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
+                                          ctypes.c_void_p]
+        L.wino_fwd_sequence.argtypes = [ctypes.POINTER(WinoDesc), ctypes.c_int]
         L.wino_conv2d_fwd_noalloc.argtypes = [ctypes.POINTER(WinoDesc), ctypes.POINTER(WinoQuant),
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                               ctypes.c_void_p]
@@ -177,6 +182,27 @@ def wino_conv2d_fwd(desc, quant, x_dev, U_dev, y_dev, workspace_dev, workspace_b
     _check(lib().wino_conv2d_fwd(desc.ref, q, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev),
                                  _ptr(workspace_dev), workspace_bytes, _stream(stream)),
            "wino_conv2d_fwd")
+
+
+# kernel sequences of the int8 forward (wino.h)
+(WINO_SEQ_AUTO, WINO_SEQ_FUSED, WINO_SEQ_COL, WINO_SEQ_COL2, WINO_SEQ_LDS, WINO_SEQ_REGS,
+ WINO_SEQ_STAGED) = range(7)
+SEQ_NAMES = {WINO_SEQ_FUSED: "fused", WINO_SEQ_COL: "col", WINO_SEQ_COL2: "col2", WINO_SEQ_LDS: "lds",
+             WINO_SEQ_REGS: "regs", WINO_SEQ_STAGED: "staged"}
+
+
+def wino_fwd_sequence(desc, seq=WINO_SEQ_AUTO):
+    return int(lib().wino_fwd_sequence(desc.ref, seq))
+
+
+def wino_conv2d_fwd_seq(desc, quant, x_dev, U_dev, y_dev, workspace_dev, seq, workspace_bytes=None,
+                        stream=None):
+    q = ctypes.byref(quant) if quant is not None else None
+    if workspace_bytes is None:
+        workspace_bytes = workspace_dev.numel() * workspace_dev.element_size()
+    _check(lib().wino_conv2d_fwd_seq(desc.ref, q, _ptr(x_dev), _ptr(U_dev), _ptr(y_dev),
+                                     _ptr(workspace_dev), workspace_bytes, seq, _stream(stream)),
+           "wino_conv2d_fwd_seq")
 
 
 NOALLOC_SCRATCH_BYTES = 32 << 20

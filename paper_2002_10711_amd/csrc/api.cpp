@@ -229,19 +229,19 @@ int wino_fwd_num_kernels(const wino_desc* d) {
     return 3;
   }
   if (fused_fwd_f32_supported(g)) return 1;
-  if (fused_fwd_supported(g)) {
-    // as in wino_conv2d_fwd: the matrix-core variant whenever B^T allows it, the
-    // vector-ALU one for a single block of output channels
-    bool exact = false;
-    if (d->BT && finite_all(d->BT, g.n * g.n)) {
-      MatBT bt;
+  if (g.i8) {
+    // as in wino_conv2d_fwd: the sequence the table of measured times names
+    MatBT bt;
+    const bool have_bt = d->BT && finite_all(d->BT, g.n * g.n);
+    if (have_bt) {
       memset(&bt, 0, sizeof bt);
       memcpy(bt.v, d->BT, sizeof(float) * g.n * g.n);
-      exact = fused_fwd_exact_supported(g, bt);
     }
-    if (exact || fused_fwd_generic_preferred(g)) return 1;
+    const int seq = fwd_sequence_auto(g, have_bt ? &bt : nullptr, true);
+    return seq == kSeqFused ? 1 : seq == kSeqStaged ? 3 : 2;
   }
-  return (gemm_out_col_preferred(g) || gemm_out_preferred(g)) ? 2 : 3;
+  // fp32: GEMM + output transform in one kernel while the reduction is short
+  return gemm_out_f32_preferred(g) ? 2 : 3;
 }
 
 }  // extern "C"
@@ -281,7 +281,8 @@ wino_status fwd_check(const wino_desc* d, const wino_quant* q, const void* x_dev
 
 wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
                        const void* U_dev, void* y_dev, void* workspace_dev,
-                       size_t workspace_bytes, int stages, void* stream, bool exact_need) {
+                       size_t workspace_bytes, int stages, void* stream, bool exact_need,
+                       int forced_seq) {
   Geom g;
   if (!workspace_dev && d && make_geom(d, &g) == WINO_OK && stages >= 1 &&
       stages <= WINO_STAGE_ALL)
@@ -324,11 +325,23 @@ wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_de
       return WINO_E_HIP;
     return WINO_OK;
   }
+  // int8: which kernel sequence (measured table, or the caller's choice)
+  int seq = kSeqStaged;
+  if (g.i8) {
+    const MatBT* btp = s_in ? &bt : nullptr;
+    if (forced_seq != kSeqAuto) {
+      if (stages != WINO_STAGE_ALL || !fwd_sequence_supported(g, btp, forced_seq))
+        return WINO_E_BAD_ARG;
+      seq = forced_seq;
+    } else {
+      seq = fwd_sequence_auto(g, btp, stages == WINO_STAGE_ALL);
+    }
+  }
   bool exact_refused = false;
-  if (stages == WINO_STAGE_ALL && fused_fwd_supported(g)) {
+  if (stages == WINO_STAGE_ALL && seq == kSeqFused) {
     // the whole forward in one kernel: V and M stay on chip, the workspace is untouched
     const bool exact = fused_fwd_exact_supported(g, bt);
-    if (exact || fused_fwd_generic_preferred(g)) {
+    {
       const PosScale* rvq = s.pos ? &s.rv_pos : nullptr;
       const PosScale* wq = s.pos ? &s.w_pos : nullptr;
       hipError_t e =
@@ -351,6 +364,7 @@ wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_de
           exact_refused = true;
       }
       if (!exact_refused) return e == hipSuccess ? WINO_OK : WINO_E_HIP;
+      seq = fwd_sequence_auto(g, &bt, false);
     }
   }
   if (stages == WINO_STAGE_ALL && fused_fwd_f32_supported(g))
@@ -372,16 +386,20 @@ wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_de
   // (with per-position scales every accumulator is multiplied by its position's factor
   // before the output transform: the GEMM + output kernels for long reductions and the
   // stand-alone output kernel do that, gemm_out_kernel does not)
-  if (s_mm && s_out && gemm_out_lds_preferred(g)) {
+  // (gemm_out_kernel knows no per-position factors: such calls take the column-wise kernel)
+  if (g.i8 && seq == kSeqRegs && s.pos) seq = gemm_out_col_supported(g) ? kSeqCol : kSeqStaged;
+  if (!g.i8) seq = gemm_out_f32_preferred(g) ? kSeqRegs : kSeqStaged;
+  if (s_mm && s_out && seq == kSeqLds) {
     // F(2x2,3x3), 512 channels, many tiles: the same fusion with squarer workgroup tiles
     if (launch_gemm_out_lds(g, at, V, U_dev, y_dev, wp, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;
-  } else if (s_mm && s_out && gemm_out_col_preferred(g)) {
+  } else if (s_mm && s_out && (seq == kSeqCol || seq == kSeqCol2)) {
     // GEMM and output transform in one kernel for any reduction length (and with
     // per-position scales): M stays in registers
-    if (launch_gemm_out_col(g, at, V, U_dev, y_dev, wp, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+    if (launch_gemm_out_col(g, at, V, U_dev, y_dev, wp, s.r_m, s.r_y, s.qmax, hs,
+                            seq == kSeqCol2) != hipSuccess)
       return WINO_E_HIP;
-  } else if (s_mm && s_out && !s.pos && gemm_out_preferred(g)) {
+  } else if (s_mm && s_out && seq == kSeqRegs) {
     // short reductions: GEMM and output transform in one kernel, M stays in registers
     if (launch_gemm_out(g, at, V, U_dev, y_dev, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;
@@ -406,7 +424,28 @@ wino_status wino_conv2d_fwd_stages(const wino_desc* d, const wino_quant* q, cons
                                    const void* U_dev, void* y_dev, void* workspace_dev,
                                    size_t workspace_bytes, int stages, void* stream) {
   return fwd_stages(d, q, x_dev, U_dev, y_dev, workspace_dev, workspace_bytes, stages, stream,
-                    false);
+                    false, kSeqAuto);
+}
+
+wino_status wino_conv2d_fwd_seq(const wino_desc* d, const wino_quant* q, const void* x_dev,
+                                const void* U_dev, void* y_dev, void* workspace_dev,
+                                size_t workspace_bytes, int seq, void* stream) {
+  if (seq < kSeqAuto || seq >= kSeqCount) return WINO_E_BAD_ARG;
+  return fwd_stages(d, q, x_dev, U_dev, y_dev, workspace_dev, workspace_bytes, WINO_STAGE_ALL,
+                    stream, false, seq);
+}
+
+int wino_fwd_sequence(const wino_desc* d, int seq) {
+  Geom g;
+  if (make_geom(d, &g) != WINO_OK || !g.i8 || seq < kSeqAuto || seq >= kSeqCount) return 0;
+  MatBT bt;
+  const bool have_bt = d->BT && finite_all(d->BT, g.n * g.n);
+  if (have_bt) {
+    memset(&bt, 0, sizeof bt);
+    memcpy(bt.v, d->BT, sizeof(float) * g.n * g.n);
+  }
+  if (seq == kSeqAuto) return fwd_sequence_auto(g, have_bt ? &bt : nullptr, true);
+  return fwd_sequence_supported(g, have_bt ? &bt : nullptr, seq) ? seq : 0;
 }
 
 wino_status wino_conv2d_fwd(const wino_desc* d, const wino_quant* q, const void* x_dev,

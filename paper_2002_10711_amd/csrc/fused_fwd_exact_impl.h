@@ -759,15 +759,13 @@ bool input_exact_supported(const Geom& g, const MatBT& bt) {
 }
 
 bool fused_fwd_exact_supported(const Geom& g, const MatBT& bt) {
-  // (byte-wise staging is slow enough that only a single channel block is worth fusing;
-  // F4 with four or more channel blocks keeps 144 accumulator registers alive through
-  // every block's staging and transform and measures slower than the separate input stage
-  // plus the GEMM + output kernel: 256 channels 24.6 vs 20.6 us, 512 channels 46.8 vs 31.7)
-  // (and with fewer than 128 workgroups a long reduction leaves most of the chip idle for
-  // the whole of it: 512 channels, F2, 1 k tiles: 35 vs 15 us as two kernels)
+  // What the one-kernel forward can run (whether it is the fastest sequence for a shape is
+  // measured, not decided here: with long reductions it mostly is not -- F4 keeps 144
+  // accumulator registers alive through every block's staging and transform, and fewer
+  // than 128 workgroups leave most of the chip idle for a whole long reduction).
+  // (byte-wise staging is built for a single channel block only)
   return (g.m == 2 || g.m == 4) && g.Kp <= 128 && narrow_ok(g) && (g.W >= 4 || g.Cp == 64) &&
-         (g.m == 2 || g.Cp <= 192) &&
-         (g.Cp <= 128 || g.T >= 2048) && input_exact_supported(g, bt);
+         input_exact_supported(g, bt);
 }
 
 // As a stand-alone input stage: wherever the matrix B^T allows it.

@@ -206,7 +206,8 @@ __global__ __launch_bounds__(256, kTwoWG ? 2 : 1) void gemm_out_col_kernel(Geom 
 
 template <int M, bool kSparse>
 hipError_t launch_ms(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
-                     const PosScale* w, float r_m, float r_y, float qmax, hipStream_t s) {
+                     const PosScale* w, float r_m, float r_y, float qmax, hipStream_t s,
+                     bool two_blocks) {
   PosScale one;
   for (int p = 0; p < 64; ++p) one.r[p] = 1.0f;
   const PosScale& ws = w ? *w : one;
@@ -214,26 +215,29 @@ hipError_t launch_ms(const Geom& g, const MatAT& at, const void* V, const void* 
   const int8_t* Ui = (const int8_t*)U;
   int8_t* yo = (int8_t*)y;
   const int fast = g.Ho % M == 0 && g.Wo % M == 0 && ((uintptr_t)y & 3) == 0;
-  // Two tile blocks per wavefront halve the operand loads of U per MFMA and the number of
-  // workgroups: measured faster only where the layer has many tiles and U is what the L1
-  // is busy with (F2 at 256 channels from 8 k tiles, F4 at 512 channels from 2 k tiles).
 #define WINO_COL_GO(NCHV)                                                                \
   gemm_out_col_kernel<M, NCHV, kSparse, 1><<<dim3(g.Tp / 16, g.Kp / 64), 256, 0, s>>>(   \
       g, at, Vi, Ui, yo, ws, r_m, r_y, qmax, fast)
 #define WINO_COL_GO2(NCHV)                                                               \
   gemm_out_col_kernel<M, NCHV, kSparse, 2><<<dim3(g.Tp / 32, g.Kp / 64), 256, 0, s>>>(   \
       g, at, Vi, Ui, yo, ws, r_m, r_y, qmax, fast)
-  if constexpr (M == 2) {
-    if (g.Cp == 256 && g.T >= 8192) {
-      WINO_COL_GO2(4);
-      return hipGetLastError();
+  // Two tile blocks per wavefront halve the operand loads of U per MFMA and the number of
+  // workgroups; built where it has measured faster on layers with many tiles (F2 at 256
+  // channels, F4 at 512 channels).
+  if (two_blocks) {
+    if constexpr (M == 2) {
+      if (g.Cp == 256) {
+        WINO_COL_GO2(4);
+        return hipGetLastError();
+      }
     }
-  }
-  if constexpr (M == 4) {
-    if (g.Cp == 512 && g.T >= 2048) {
-      WINO_COL_GO2(8);
-      return hipGetLastError();
+    if constexpr (M == 4) {
+      if (g.Cp == 512) {
+        WINO_COL_GO2(8);
+        return hipGetLastError();
+      }
     }
+    return hipErrorInvalidValue;
   }
   if constexpr (M == 6) {
     // more workgroups than CUs, but not many more: two per CU finish in one round
@@ -273,10 +277,10 @@ hipError_t launch_ms(const Geom& g, const MatAT& at, const void* V, const void* 
 
 template <int M>
 hipError_t launch_m(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
-                    const PosScale* w, float r_m, float r_y, float qmax, hipStream_t s) {
+                    const PosScale* w, float r_m, float r_y, float qmax, hipStream_t s, bool two) {
   return fits_mask(at.v, g.m * g.n, CookToomMask<M>::at)
-             ? launch_ms<M, true>(g, at, V, U, y, w, r_m, r_y, qmax, s)
-             : launch_ms<M, false>(g, at, V, U, y, w, r_m, r_y, qmax, s);
+             ? launch_ms<M, true>(g, at, V, U, y, w, r_m, r_y, qmax, s, two)
+             : launch_ms<M, false>(g, at, V, U, y, w, r_m, r_y, qmax, s, two);
 }
 
 }  // namespace
@@ -287,14 +291,19 @@ bool gemm_out_col_supported(const Geom& g) {
   return g.i8 && nch_ok && g.Kp / 64 <= 65535 && (size_t)g.Tp * g.Cp < 0xffffffffull;
 }
 
+bool gemm_out_col2_supported(const Geom& g) {
+  return gemm_out_col_supported(g) && ((g.m == 2 && g.Cp == 256) || (g.m == 4 && g.Cp == 512));
+}
+
 hipError_t launch_gemm_out_col(const Geom& g, const MatAT& at, const void* V, const void* U,
                                void* y, const PosScale* w_pos, float r_m, float r_y, float qmax,
-                               hipStream_t s) {
-  if (!gemm_out_col_supported(g)) return hipErrorInvalidValue;
+                               hipStream_t s, bool two_blocks) {
+  if (!(two_blocks ? gemm_out_col2_supported(g) : gemm_out_col_supported(g)))
+    return hipErrorInvalidValue;
   switch (g.m) {
-    case 2: return launch_m<2>(g, at, V, U, y, w_pos, r_m, r_y, qmax, s);
-    case 4: return launch_m<4>(g, at, V, U, y, w_pos, r_m, r_y, qmax, s);
-    default: return launch_m<6>(g, at, V, U, y, w_pos, r_m, r_y, qmax, s);
+    case 2: return launch_m<2>(g, at, V, U, y, w_pos, r_m, r_y, qmax, s, two_blocks);
+    case 4: return launch_m<4>(g, at, V, U, y, w_pos, r_m, r_y, qmax, s, two_blocks);
+    default: return launch_m<6>(g, at, V, U, y, w_pos, r_m, r_y, qmax, s, two_blocks);
   }
 }
 

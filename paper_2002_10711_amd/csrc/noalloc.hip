@@ -53,5 +53,5 @@ extern "C" wino_status wino_conv2d_fwd_noalloc(const wino_desc* d, const wino_qu
   // and channels of V are written by the input stage, padding tiles only feed sums that
   // are dropped -- nothing has to be cleared between calls)
   return wino::fwd_stages(d, q, x_dev, U_dev, y_dev, ws, (size_t)WINO_NOALLOC_SCRATCH_BYTES,
-                          WINO_STAGE_ALL, stream, true);
+                          WINO_STAGE_ALL, stream, true, wino::kSeqAuto);
 }

@@ -49,7 +49,8 @@ wino_status fwd_check(const wino_desc* d, const wino_quant* q, const void* x_dev
                       const void* U_dev, const void* y_dev, int stages, Geom* g);
 wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_dev,
                        const void* U_dev, void* y_dev, void* workspace_dev,
-                       size_t workspace_bytes, int stages, void* stream, bool exact_need);
+                       size_t workspace_bytes, int stages, void* stream, bool exact_need,
+                       int forced_seq);
 
 // Kernel launchers (each enqueues on `s` and returns hipGetLastError()).
 // (the optional PosScale arguments switch a stage to per-position factors: r_v[p], r_u[p],
@@ -68,42 +69,46 @@ hipError_t launch_gemm(int P, int Tp, int Kp, int Cp, int i8, int b_blocked, con
 hipError_t launch_output_transform(const Geom& g, const MatAT& at, const void* M, void* y,
                                    float r_m, float r_y, float qmax, hipStream_t s,
                                    const PosScale* w_pos = nullptr);
-// GEMM and output transform in one kernel (M stays in registers, operands straight
-// from global memory): preferred while the reduction is short and the n*n accumulator
-// sets leave room for two wavefronts per SIMD.
-inline bool gemm_out_preferred(const Geom& g) {
-  // (8 x 8 accumulator sets fill the register file: one wavefront per SIMD, so the
-  // operand stream must be short to stay ahead)
-  return g.Cp * (g.i8 ? 1 : 4) <= (g.m == 6 ? 64 : 128);
+// Kernel sequences of the int8 forward (which one runs is looked up in a table of measured
+// times, see fwd_sequence_auto):
+enum FwdSeq {
+  kSeqAuto = 0,
+  kSeqFused = 1,    // one kernel: matrix-core input transform, per-position MFMAs, output transform
+  kSeqCol = 2,      // input stage; GEMM + column-wise output transform (gemm_out_col_kernel)
+  kSeqCol2 = 3,     // ... with two tile blocks per wavefront
+  kSeqLds = 4,      // input stage; GEMM + output transform with 32 x 64 workgroup tiles
+  kSeqRegs = 5,     // input stage; GEMM + output transform, all accumulators in registers
+  kSeqStaged = 6,   // input stage; LDS-tiled GEMM writing M; output transform
+  kSeqCount = 7
+};
+// Can sequence `seq` run this problem at all (shape and matrices only)?
+bool fwd_sequence_supported(const Geom& g, const MatBT* bt, int seq);
+// The sequence wino_conv2d_fwd takes: the fastest supported one at the nearest point of the
+// measured grid (dispatch_table.h, written by paper_2002_10711_amd/tune.py).
+// allow_fused: the call runs the whole forward (a stage-by-stage call cannot fuse it).
+int fwd_sequence_auto(const Geom& g, const MatBT* bt, bool allow_fused);
+// fp32: GEMM + output transform in one kernel (gemm_out_kernel) while the reduction is short
+// enough for the operand stream to stay ahead of the matrix cores.
+inline bool gemm_out_f32_preferred(const Geom& g) {
+  return !g.i8 && !g.w16 && g.Cp * 4 <= (g.m == 6 ? 64 : 128);
 }
+
+// GEMM and output transform in one kernel (M stays in registers, operands straight
+// from global memory).
 hipError_t launch_gemm_out(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                            float r_m, float r_y, float qmax, hipStream_t s);
 // The same for long int8 reductions (64 .. 512 padded channels in steps of 64; per-tensor
 // or per-position scales): column-by-column output transform, V shared through LDS.
+// two_blocks: two tile blocks per wavefront (every U operand feeds two MFMAs, half the
+// workgroups), built for F(2x2,3x3) at 256 and F(4x4,3x3) at 512 padded channels.
 bool gemm_out_col_supported(const Geom& g);
-// ... and faster than both alternatives (gemm_out_kernel; tiled GEMM + output transform):
-// measured for m = 2 at every supported reduction, for m = 4 up to 128 channels, up to 256
-// from 128 tiles and beyond from 512 tiles up, for m = 6 at 128 .. 512 channels from 1 k
-// tiles up; elsewhere the few, long workgroups lose to the LDS-tiled GEMM, and
-// gemm_out_kernel keeps m = 6 at 64 channels.
-inline bool gemm_out_col_preferred(const Geom& g) {
-  if (!gemm_out_col_supported(g)) return false;
-  if (g.m == 2) return true;
-  // (F4 with long reductions and few tiles: too few workgroups, the tiled GEMM is faster)
-  if (g.m == 4) return g.Cp <= 128 || (g.Cp <= 256 ? g.T >= 128 : g.T >= 512);
-  // (m = 6: from 128 channels, and only with enough tiles to fill the machine)
-  return g.Cp >= 128 && g.T >= 1024;
-}
+bool gemm_out_col2_supported(const Geom& g);
 hipError_t launch_gemm_out_col(const Geom& g, const MatAT& at, const void* V, const void* U,
                                void* y, const PosScale* w_pos, float r_m, float r_y, float qmax,
-                               hipStream_t s);
+                               hipStream_t s, bool two_blocks);
 // The same for F(2x2,3x3) with 512 padded input channels: workgroup tiles of 32 tiles x 64
-// channels (fewer operand bytes per compute unit), 32x32x32 MFMAs.  Measured faster than
-// gemm_out_col_kernel from 1 k tiles up (512 -> 512 channels at 4 x 4, batch 256: 20.0 ->
-// 15.8 us); with fewer tiles its 32 x 64 blocks leave compute units idle (512 tiles: 14.0
-// vs 13.1 us).
+// channels (fewer operand bytes per compute unit), 32x32x32 MFMAs.
 bool gemm_out_lds_supported(const Geom& g);
-inline bool gemm_out_lds_preferred(const Geom& g) { return gemm_out_lds_supported(g) && g.T >= 1024; }
 hipError_t launch_gemm_out_lds(const Geom& g, const MatAT& at, const void* V, const void* U,
                                void* y, const PosScale* w_pos, float r_m, float r_y, float qmax,
                                hipStream_t s);

@@ -46,6 +46,17 @@ def run_gpu(case, taps=True, scales=None):
     wb.wino_conv2d_fwd(desc, quant, x, U, y, ws)
     torch.cuda.synchronize()
     out = dict(Y=y.cpu().numpy())
+    # the same forward with every kernel sequence that can run this problem, named explicitly
+    out["Y_seq"] = {}
+    if i8:
+        for seq, name in wb.SEQ_NAMES.items():
+            if wb.wino_fwd_sequence(desc, seq) != seq:
+                continue
+            ys = torch.full_like(y, 33)
+            ws.zero_()
+            wb.wino_conv2d_fwd_seq(desc, quant, x, U, ys, ws, seq)
+            torch.cuda.synchronize()
+            out["Y_seq"][name] = ys.cpu().numpy()
     # stage by stage, which materialises V and M for the taps
     y2 = torch.full_like(y, 55)
     ws.zero_()

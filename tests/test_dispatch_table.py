@@ -1,0 +1,63 @@
+"""The int8 forward picks its kernel sequence from a table of measured times
+(paper_2002_10711_amd/tune.py; the paper picks the algorithm per layer the same way,
+Sec. 5.3).  Host-side checks, no GPU: the generated table matches the stored sweep, and on
+every point of the sweep grid (batch 32 and 256) the dispatch's choice is within 10 % of the
+fastest sequence measured there."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_2002_10711_amd import binding as wb
+from paper_2002_10711_amd import tune
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sweep():
+    return json.load(open(os.path.join(ROOT, "profiles", "dispatch_sweep.json")))
+
+
+def test_table_is_generated_from_the_stored_sweep(sweep):
+    assert open(tune.TABLE_FILE).read() == tune.table_text(sweep)
+
+
+def test_grid_covers_both_batches_and_all_tile_sizes(sweep):
+    pts = sweep["grid"]
+    assert {p["N"] for p in pts} == {32, 256}
+    assert {p["m"] for p in pts} == {2, 4, 6}
+    assert {p["C"] for p in pts} == {64, 128, 256, 512}
+    assert all(p["times_us"] for p in pts)
+
+
+def test_dispatch_within_ten_percent_of_the_fastest_sequence(sweep):
+    names = wb.SEQ_NAMES
+    worst = 1.0
+    for p in sweep["grid"]:
+        BT, G, AT = wb.wino_cook_toom(p["m"])
+        desc = wb.Desc(p["N"], p["C"], p["K"], p["H"], p["H"], 1, p["m"], wb.WINO_I8, BT=BT, G=G, AT=AT)
+        seq = wb.wino_fwd_sequence(desc, wb.WINO_SEQ_AUTO)
+        assert seq in names, (p, seq)
+        t = p["times_us"]
+        # (every sequence the library reports as supported was timed, and vice versa)
+        assert {names[s] for s in names if wb.wino_fwd_sequence(desc, s) == s} == set(t), p
+        ratio = t[names[seq]] / min(t.values())
+        worst = max(worst, ratio)
+        assert ratio <= 1.10, (p, names[seq], ratio)
+    assert worst >= 1.0
+
+
+def test_off_grid_shapes_get_a_supported_sequence():
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        m = int(rng.choice([2, 4, 6]))
+        N, C, K = int(rng.integers(1, 40)), int(rng.integers(1, 700)), int(rng.integers(1, 300))
+        H, W = int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        BT, G, AT = wb.wino_cook_toom(m)
+        desc = wb.Desc(N, C, K, H, W, 1, m, wb.WINO_I8, BT=BT, G=G, AT=AT)
+        seq = wb.wino_fwd_sequence(desc, wb.WINO_SEQ_AUTO)
+        assert seq in wb.SEQ_NAMES and wb.wino_fwd_sequence(desc, seq) == seq
+        nk = wb.wino_fwd_num_kernels(desc)
+        assert nk == (1 if seq == wb.WINO_SEQ_FUSED else 3 if seq == wb.WINO_SEQ_STAGED else 2)

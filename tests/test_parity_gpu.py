@@ -25,6 +25,11 @@ def _check_i8(case, out, inexact_ok=False):
         bad = int((a != b).sum())
         assert bad == 0, "%s: %d of %d differ, first at %s" % (
             tap, bad, a.size, np.argwhere(a != b)[:3].tolist())
+    # every kernel sequence that can run the shape gives the same codes
+    assert out["Y_seq"], "no kernel sequence reported as supported"
+    for name, ys in out["Y_seq"].items():
+        bad = int((ys.astype(np.int64) != ref["Yq"].astype(np.int64)).sum())
+        assert bad == 0, "sequence %s: %d of %d output codes differ" % (name, bad, ys.size)
 
 
 def _check_f32(oracle, case, out):
@@ -470,4 +475,9 @@ def test_determinism(oracle):
     case = make_case(oracle, Layer("det", 4, 64, 64, 16, 16, m=4, seed=111), with_oracle=False)
     a, b = run_gpu(case), run_gpu(case)
     for k in a:
-        assert np.array_equal(a[k], b[k]), k
+        if k == "Y_seq":
+            assert a[k].keys() == b[k].keys()
+            for name in a[k]:
+                assert np.array_equal(a[k][name], b[k][name]), (k, name)
+        else:
+            assert np.array_equal(a[k], b[k]), k

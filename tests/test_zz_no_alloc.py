@@ -54,7 +54,7 @@ def test_two_calls_in_a_row_the_second_smaller():
     assert nk == 3
     assert np.array_equal(a, b)
     # then a smaller one on the same buffer: F2, two kernels (V only), ragged tiles
-    a, b, nk = _both(Layer("na_small", 2, 200, 40, 9, 11, m=2), 2)
+    a, b, nk = _both(Layer("na_small", 3, 200, 140, 13, 11, m=2), 2)
     assert nk == 2
     assert np.array_equal(a, b)
     # one kernel (no scratch at all) and fp32 (bit-identical: same kernels, same order)
