@@ -789,7 +789,8 @@ struct XLaunch {
 };
 
 template <int M>
-bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLaunch* xl) {
+bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLaunch* xl,
+                  bool allow_one_tile_rows = false) {
   constexpr int n = M + 2, P = n * n, NBLK = (P + 15) / 16;
   const int sft = exact_input_shift(g, bt);
   if (sft < 0 || !input_exact_supported(g, bt)) return false;
@@ -822,7 +823,11 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   // that covers the tile row (16 at most).  Tile slots beyond the image (TWB > TW, tile
   // rows beyond N * TH) are masked everywhere, so every shape is one of four, all known
   // at compile time.
-  const int TWB = g.TW > 8 ? 16 : g.TW > 4 ? 8 : g.TW > 2 ? 4 : 2;
+  // (the stand-alone input stage of F2 and F4 also has a 16 x 1 shape for images of one tile
+  // per row -- 4 x 4 pixels with F4 -- where the 8 x 2 shape would waste every other slot;
+  // for F6 sixteen staged tile rows would not fit the LDS)
+  const int TWB = g.TW > 8 ? 16 : g.TW > 4 ? 8 : g.TW > 2 ? 4
+                  : (M != 6 && g.TW == 1 && g.W >= 4 && allow_one_tile_rows) ? 1 : 2;
   const int RB = 16 / TWB;
   // (+ 20 dwords: the dump area of surplus staging lanes, up to one staged row)
   const size_t xs_b = ((size_t)RB * 64 * xs_plane_dw(M, TWB) + 20) * 4, vl_b = (size_t)P * kVlPitch * 4;
@@ -850,6 +855,9 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   if (M != 6 && xl->load == 2 && g.pad == 1 && g.TW == TWB && g.W == TWB * M && g.W >= 8 &&
       ((uintptr_t)x & (g.W >= 16 ? 15 : 7)) == 0)
     xl->load = 3;
+  // ... or 4 bytes: images four pixels wide (two tiles of F2 or one of F4 per row)
+  if (M != 6 && g.W == 4 && g.pad == 1 && g.TW == TWB && TWB * M == 4 && ((uintptr_t)x & 3) == 0)
+    xl->load = 3;
   return true;
 }
 
@@ -857,7 +865,7 @@ template <int M>
 hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V, float r_v,
                           float qmax, hipStream_t s, const PosScale* rv_pos) {
   XLaunch xl;
-  if (!make_xlaunch<M>(g, bt, x, r_v, &xl) || g.Cp / 64 > 65535) return hipErrorInvalidValue;
+  if (!make_xlaunch<M>(g, bt, x, r_v, &xl, true) || g.Cp / 64 > 65535) return hipErrorInvalidValue;
   // per-position factors, each scaled by 4^-s like the per-tensor one (exact, or refuse)
   PosScale rvs;
   const float sc = r_v / xl.r_vs;                        // 4^s, exactly
@@ -882,10 +890,12 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
     }                                                                                      \
     kern<<<grid, 256, xl.lds_bytes, s>>>(xi, Vi, rvs, qmax, g, xl.pl, karg);               \
   } while (0)
+  // (whole-row staging is built for rows of 4, 8, 16, 32 or 64 bytes)
 #define WINO_LAUNCH_IN2(TWBC)                                                              \
   do {                                                                                     \
     if (xl.load == 3) {                                                                    \
-      if constexpr (M != 6) WINO_LAUNCH_IN(3, TWBC);                                       \
+      if constexpr (M != 6 && (TWBC * M) % 4 == 0) WINO_LAUNCH_IN(3, TWBC);                \
+      else return hipErrorInvalidValue;                                                    \
     } else if (xl.load == 2) WINO_LAUNCH_IN(2, TWBC);                                      \
     else WINO_LAUNCH_IN(1, TWBC);                                                          \
   } while (0)
@@ -895,7 +905,8 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
   } else if (TWB == 16) WINO_LAUNCH_IN2(16);
   else if (TWB == 8) WINO_LAUNCH_IN2(8);
   else if (TWB == 4) WINO_LAUNCH_IN2(4);
-  else WINO_LAUNCH_IN2(2);
+  else if (TWB == 2) WINO_LAUNCH_IN2(2);
+  else WINO_LAUNCH_IN2(1);
 #undef WINO_LAUNCH_IN2
 #undef WINO_LAUNCH_IN
   return hipGetLastError();
