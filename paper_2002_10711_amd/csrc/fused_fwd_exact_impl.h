@@ -264,6 +264,29 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
   }
 }
 
+// F(4x4,3x3): P = 36 positions are two full blocks of 16 and a block with 4.  The third
+// block's MFMA results occupy columns 0 .. 3 only (lanes with r < 4); quantizing them one
+// window group at a time would spend a full set of vector instructions on a quarter of the
+// lanes.  The four window groups of one tile (its four blocks of 16 channels) are therefore
+// merged first: group c's columns 0 .. 3 move to columns 4c .. 4c + 3 with row-shift moves
+// (three per register), and one quantize-and-pack serves all four.  Lane r then holds
+// position 32 + r % 4 of channel group r / 4.
+__device__ __forceinline__ v4i merge_tail_groups(const v4i& t0, const v4i& t1, const v4i& t2,
+                                                 const v4i& t3) {
+  v4i m;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    int v = t0[e];
+    // update_dpp(old, src, ctrl, row_mask, bank_mask, bound_ctrl): row_shr:n = 0x110 + n;
+    // bank b = lanes 4b .. 4b + 3 of every row of 16
+    v = __builtin_amdgcn_update_dpp(v, t1[e], 0x114, 0xf, 0x2, false);
+    v = __builtin_amdgcn_update_dpp(v, t2[e], 0x118, 0xf, 0x4, false);
+    v = __builtin_amdgcn_update_dpp(v, t3[e], 0x11c, 0xf, 0x8, false);
+    m[e] = v;
+  }
+  return m;
+}
+
 // Grid: x = blocks of RB tile rows, y = blocks of TWB tiles along a row, z = blocks of 64
 // output channels.
 // kOneBlock: C <= 64, a single channel block; the accumulators then start life at the
@@ -374,6 +397,40 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     uint32_t* lane_v = Vl + r * kVlPitch + grp;
     v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], v4i{0, 0, 0, 0}, 0, 0, 0);
     static_assert(NSTEP >= P, "one U load per step must cover all positions");
+    if constexpr (M == 4) {
+      // two full blocks per window group, the third block once per tile
+      // (merge_tail_groups): 32 + 4 steps, one U load each = the 36 positions
+      uint32_t* lane_v2 = Vl + (32 + (r & 3)) * kVlPitch + (r >> 2) * 4 + grp;
+      const float rq2 = pos ? pp.rv[32 + (r & 3)] : r_vs;
+      const v4i zero4 = v4i{0, 0, 0, 0};
+      v4i tail[4];
+#pragma unroll
+      for (int st = 0; st < 32; ++st) {
+        const int gi = st >> 1, blk = st & 1, q = gi >> 2;
+        bufU[st] = *(const v4i*)(U + (ub + (uint32_t)st * up));
+        v4i nxt = cur;
+        if (st + 1 < 32)
+          nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) >> 1], Wb[(st + 1) & 1], zero4, 0, 0, 0);
+        if ((st & 7) >= 2 && (st & 7) < 6)
+          tail[(st & 7) - 2] =
+              __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[q * 4 + (st & 7) - 2], Wb[2], zero4, 0, 0, 0);
+        const uint32_t packed = pack_codes(quantize_bits((float)cur[0], rq[blk], lo, hi),
+                                           quantize_bits((float)cur[1], rq[blk], lo, hi),
+                                           quantize_bits((float)cur[2], rq[blk], lo, hi),
+                                           quantize_bits((float)cur[3], rq[blk], lo, hi));
+        const int tl = wave * 4 + q;
+        lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
+        cur = nxt;
+        if ((st & 7) == 7) {
+          bufU[32 + q] = *(const v4i*)(U + (ub + (uint32_t)(32 + q) * up));
+          const v4i m4 = merge_tail_groups(tail[0], tail[1], tail[2], tail[3]);
+          lane_v2[tl * 16] = pack_codes(quantize_bits((float)m4[0], rq2, lo, hi),
+                                        quantize_bits((float)m4[1], rq2, lo, hi),
+                                        quantize_bits((float)m4[2], rq2, lo, hi),
+                                        quantize_bits((float)m4[3], rq2, lo, hi));
+        }
+      }
+    } else {
 #pragma unroll
     for (int st = 0; st < NSTEP; ++st) {
       const int gi = st / NBLK, blk = st % NBLK;
@@ -390,6 +447,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
       const int tl = wave * 4 + (gi >> 2);
       if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
       cur = nxt;
+    }
     }
     __syncthreads();
     WINO_TS(4);
@@ -513,6 +571,37 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
     }
     uint32_t* lane_v = Vl + r * kVlPitch + grp;
     v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], v4i{0, 0, 0, 0}, 0, 0, 0);
+    if constexpr (M == 4) {
+      // two full blocks per window group, the third block once per tile (merge_tail_groups)
+      uint32_t* lane_v2 = Vl + (32 + (r & 3)) * kVlPitch + (r >> 2) * 4 + grp;
+      const float rq2 = pos ? pp.rv[32 + (r & 3)] : r_vs;
+      const v4i zero4 = v4i{0, 0, 0, 0};
+      v4i tail[4];
+#pragma unroll
+      for (int st = 0; st < 2 * NG; ++st) {
+        const int gi = st >> 1, blk = st & 1, q = gi >> 2;
+        v4i nxt = cur;
+        if (st + 1 < 2 * NG)
+          nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) >> 1], Wb[(st + 1) & 1], zero4, 0, 0, 0);
+        if ((st & 7) >= 2 && (st & 7) < 6)
+          tail[(st & 7) - 2] =
+              __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[q * 4 + (st & 7) - 2], Wb[2], zero4, 0, 0, 0);
+        const uint32_t packed = pack_codes(quantize_bits((float)cur[0], rq[blk], lo, hi),
+                                           quantize_bits((float)cur[1], rq[blk], lo, hi),
+                                           quantize_bits((float)cur[2], rq[blk], lo, hi),
+                                           quantize_bits((float)cur[3], rq[blk], lo, hi));
+        const int tl = wave * 2 + q;
+        lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
+        cur = nxt;
+        if ((st & 7) == 7) {
+          const v4i m4 = merge_tail_groups(tail[0], tail[1], tail[2], tail[3]);
+          lane_v2[tl * 16] = pack_codes(quantize_bits((float)m4[0], rq2, lo, hi),
+                                        quantize_bits((float)m4[1], rq2, lo, hi),
+                                        quantize_bits((float)m4[2], rq2, lo, hi),
+                                        quantize_bits((float)m4[3], rq2, lo, hi));
+        }
+      }
+    } else {
 #pragma unroll
     for (int st = 0; st < NSTEP; ++st) {
       const int gi = st / NBLK, blk = st % NBLK;
@@ -528,6 +617,7 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
       const int tl = wave * 2 + (gi >> 2);
       if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
       cur = nxt;
+    }
     }
   }
   __syncthreads();
@@ -665,6 +755,38 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
 
   uint32_t* lane_v = Vl + r * kVlPitch + grp;
   const v4i zero4 = v4i{0, 0, 0, 0};
+  if constexpr (M == 4) {
+    // two full blocks per window group, the third block once per tile (merge_tail_groups)
+    uint32_t* lane_v2 = Vl + (32 + (r & 3)) * kVlPitch + (r >> 2) * 4 + grp;
+    const float rq2 = rvs.r[32 + (r & 3)];
+    v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], zero4, 0, 0, 0);
+    v4i tail[4];
+#pragma unroll
+    for (int st = 0; st < 32; ++st) {
+      const int gi = st >> 1, blk = st & 1, q = gi >> 2;
+      v4i nxt = cur;
+      if (st + 1 < 32)
+        nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) >> 1], Wb[(st + 1) & 1], zero4, 0, 0, 0);
+      // the tile's third-block MFMAs, one per step in mid-tile, consumed at its end
+      if ((st & 7) >= 2 && (st & 7) < 6)
+        tail[(st & 7) - 2] =
+            __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[q * 4 + (st & 7) - 2], Wb[2], zero4, 0, 0, 0);
+      const uint32_t packed = pack_codes(quantize_bits((float)cur[0], rq[blk], lo, hi),
+                                         quantize_bits((float)cur[1], rq[blk], lo, hi),
+                                         quantize_bits((float)cur[2], rq[blk], lo, hi),
+                                         quantize_bits((float)cur[3], rq[blk], lo, hi));
+      const int tl = wave * 4 + q;
+      lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
+      cur = nxt;
+      if ((st & 7) == 7) {
+        const v4i m4 = merge_tail_groups(tail[0], tail[1], tail[2], tail[3]);
+        lane_v2[tl * 16] = pack_codes(quantize_bits((float)m4[0], rq2, lo, hi),
+                                      quantize_bits((float)m4[1], rq2, lo, hi),
+                                      quantize_bits((float)m4[2], rq2, lo, hi),
+                                      quantize_bits((float)m4[3], rq2, lo, hi));
+      }
+    }
+  } else {
   // (two digits: cur / curh hold 4^s V's low and high parts, recombined when consumed)
   v4i cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[0], Wb[0], zero4, 0, 0, 0);
   v4i curh = zero4;
@@ -689,6 +811,7 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
     if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
     cur = nxt;
     curh = nxth;
+  }
   }
   __syncthreads();
 
