@@ -30,14 +30,16 @@ sys.path.insert(0, ROOT)
 from paper_2002_10711_amd import workloads  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-MFMA_PEAK = {"int8": 5000.0, "f32": 157.3, "f16": 2500.0}   # dense TOP/s, TFLOP/s
+MFMA_PEAK = {"int8": 5000.0, "f32": 157.3, "bf16": 2500.0}   # dense TOP/s, TFLOP/s
+FLOAT = ("f32", "bf16")     # float activations, no quantizer (bf16: bf16 operands in the GEMM)
 WIDE = ("i16", "i8w16")    # dtypes with 16-bit codes in the Winograd domain
 HBM_TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 
 def pick_workload(name):
     table = {}
-    for L in (workloads.config2("i8") + workloads.config2("f32") + workloads.config2("i16") +
+    for L in (workloads.config2("i8") + workloads.config2("f32") + workloads.config2("bf16") +
+              workloads.config2("i16") +
               workloads.config2("i8w16") + workloads.config3() +
               workloads.config4() + workloads.config5()):
         table[L.name] = L
@@ -66,8 +68,8 @@ def algorithmic(L, BT, AT):
     (scale, round, saturate, convert)."""
     wide = L.dtype in WIDE
     e = 1 if L.dtype in ("i8", "i8w16") else 2 if L.dtype == "i16" else 4   # X, Y element
-    ew = 2 if wide else e                                                   # U, V element
-    quantized = L.dtype != "f32"
+    ew = 2 if wide or L.dtype == "bf16" else e                              # U, V element
+    quantized = L.dtype not in FLOAT
     qops = 4 if quantized else 0
     n = L.m + 2
     P = n * n
@@ -105,7 +107,7 @@ def roofline_entry(name, alg, us, dtype, traffic):
     longer time.  Both fractions are reported (`hbm_frac`, `mfma_frac`); `alu` is an extra:
     the fp32 operations issued on the vector ALU against its peak (78.6 TFLOP/s without packed
     instructions, which this build may not use)."""
-    mf = MFMA_PEAK["int8" if dtype == "i8" or dtype in WIDE else "f32"]
+    mf = MFMA_PEAK["int8" if dtype == "i8" or dtype in WIDE else dtype]
     sec = us * 1e-6
     hbm = alg["bytes"] / sec / 1e9
     mfma = alg["ops"] / sec / 1e12
@@ -162,12 +164,13 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
     wide = L.dtype in WIDE
     qm = workloads.STAGE_QMAX.get(L.dtype)
     scales = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[
-        L.name.replace("_f32", "_i8")]
+        L.name.replace("_f32", "_i8").replace("_bf16", "_i8")]
     X, g = workloads.make_inputs(L)
     BT, G, AT = wb.wino_cook_toom(L.m)
     if L.flex_sigma > 0:
         BT, G, AT = workloads.perturb_transforms(BT, G, AT, L.flex_sigma, L.seed)
-    dt = {"i8": wb.WINO_I8, "f32": wb.WINO_F32, "i16": wb.WINO_I16, "i8w16": wb.WINO_I8W16}[L.dtype]
+    dt = {"i8": wb.WINO_I8, "f32": wb.WINO_F32, "i16": wb.WINO_I16, "i8w16": wb.WINO_I8W16,
+          "bf16": wb.WINO_BF16}[L.dtype]
     desc = wb.Desc(L.N, L.C, L.K, L.H, L.W, L.pad, L.m, dt, BT=BT, G=G, AT=AT)
     quant = None
     ydt = torch.float32
@@ -259,7 +262,8 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
     acc = time_stages(stages)
     # the four kernels of the unfused path, one call each (the paper's kernels a-d as
     # separate launches, V and M through memory), whatever the forward call itself uses
-    acc_staged = acc if nk == 3 else time_stages(
+    # (the bf16 variant exists as one kernel only)
+    acc_staged = acc if nk == 3 else {} if L.dtype == "bf16" else time_stages(
         [("weight_transform", None), ("input_transform", wb.WINO_STAGE_INPUT),
          ("gemm", wb.WINO_STAGE_GEMM), ("output_transform", wb.WINO_STAGE_OUTPUT)])
 
@@ -267,7 +271,7 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
     # (the baseline has int8 and fp32 forms: 8-bit activations are compared with the int8
     # one, the int16 workload has no baseline)
     s_w = scales.get("s_w", 1.0)
-    rdt = wb.WINO_F32 if L.dtype == "f32" else wb.WINO_I8
+    rdt = wb.WINO_F32 if L.dtype in FLOAT else wb.WINO_I8
     ms_ref = ms_ref_rows = None
     if L.dtype != "i16":
         if rdt == wb.WINO_I8:
@@ -477,7 +481,7 @@ def cpu_leg(L):
 
     n_omp, n_one = min(L.N, 16), min(L.N, 2)
     runs = {}
-    if L.dtype != "f32":
+    if L.dtype not in FLOAT:
         sc = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[L.name]
         qm = workloads.STAGE_QMAX[L.dtype]
         xq = oracle.quantize_tensor(X[:n_omp], sc["s_x"], qm["x"])
@@ -488,7 +492,7 @@ def cpu_leg(L):
         main_name = "winograd_f64"
     legs = [(main_name, main_fn, 8.0, 3.0),
             ("direct_f64", lambda n: (lambda: oracle.conv2d_direct_f64(X[:n], g, 1, L.pad)), 3.0, 2.0)]
-    if L.dtype != "f32":
+    if L.dtype not in FLOAT:
         legs.append(("winograd_f64", lambda n: (lambda: oracle.winograd_f64(X[:n], g, BT, G, AT, L.pad)),
                      3.0, 2.0))
     for name, mk, b_omp, b_one in legs:
@@ -572,7 +576,8 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": r["ms_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"i8": "int8", "f32": "f32", "i16": "int16", "i8w16": "int8 data, int16 Winograd domain"}[L.dtype],
+        "dtype": {"i8": "int8", "f32": "f32", "i16": "int16", "i8w16": "int8 data, int16 Winograd domain",
+                  "bf16": "f32 data, bf16 operands in the Winograd-domain GEMM"}[L.dtype],
         "data": "synthetic",
         "config": {"workload": "%s: N=%d C=%d K=%d %dx%d pad=%d F(%dx%d,3x3) %s" % (
             L.name, L.N, L.C, L.K, L.H, L.W, L.pad, L.m, L.m, L.dtype),
@@ -586,7 +591,7 @@ def main():
         "im2row_rows_ms": r["ms_ref_rows"],
         "im2row_baseline_tops": L.direct_ops / (r["ms_ref"] * 1e-3) / 1e12 if r["ms_ref"] else None,
         "im2row_baseline_mfma_frac": (L.direct_ops / (r["ms_ref"] * 1e-3) / 1e12 /
-                                      MFMA_PEAK["f32" if L.dtype == "f32" else "int8"])
+                                      MFMA_PEAK["f32" if L.dtype in FLOAT else "int8"])
         if r["ms_ref"] else None,
         "speedup_vs_im2row": r["ms_ref"] / r["ms_fwd"] if r["ms_ref"] else None,
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",

@@ -74,8 +74,17 @@ typedef enum {
  *            arrays, U, V and the Hadamard-stage quantizer may use up to 16 bits.
  * The two wide modes accept one code range per stage (wino_quant.qmax_*), need C <= 1024,
  * and run as two kernels (input transform; GEMM fused with the output transform) or, for
- * layers with few tiles and channel counts whose padding is not 64/128/256/512, three. */
-typedef enum { WINO_F32 = 0, WINO_I8 = 1, WINO_I16 = 2, WINO_I8W16 = 3 } wino_dtype;
+ * layers with few tiles and channel counts whose padding is not 64/128/256/512, three.
+ * WINO_BF16  the float path with bf16 operands in the Winograd-domain GEMM (the variant
+ *            of the method's GEMM stage for speed): X, g and Y are
+ *            float, the transforms run in fp32 exactly as for WINO_F32, U and V are rounded
+ *            to bf16 (nearest even) where they enter the per-position GEMM, which
+ *            accumulates in fp32 on v_mfma_f32_16x16x16_bf16.  Error against WINO_F32 about
+ *            2^-9 relative per operand: a speed option, outside the float mode's 1e-4.
+ *            Built as a one-kernel forward for m in {2, 4}; other tile sizes, and shapes
+ *            whose staging does not fit the kernel, return WINO_E_BAD_SHAPE / WINO_E_BAD_M.
+ *            No stage-by-stage calls and no taps. */
+typedef enum { WINO_F32 = 0, WINO_I8 = 1, WINO_I16 = 2, WINO_I8W16 = 3, WINO_BF16 = 4 } wino_dtype;
 
 /* One layer problem.  BT is n x n, G is n x 3, AT is m x n, row-major, HOST. */
 typedef struct {

@@ -130,6 +130,74 @@ def winograd_f64(X, g, BT, G, AT, pad=1):
 
 
 # ------------------------------------------------------------------ O3 -----
+def bf16_round(a):
+    """fp32 values rounded to the nearest bf16 (8 significant bits), ties to even, returned
+    as fp32.  Finite inputs only."""
+    bits = np.ascontiguousarray(a, np.float32).view(np.uint32)
+    bits = (bits + np.uint32(0x7FFF) + ((bits >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return bits.view(np.float32)
+
+
+def _fma32(a, b, c):
+    """fp32 fused multiply-add on arrays: the product of two fp32 numbers is exact in fp64,
+    the fp64 sum is then rounded once to fp32 (the fp64 sum itself rounds only when the terms
+    are more than 2^5 apart in magnitude, and a wrong final bit then needs an exact fp32 tie
+    after that rounding: about one case in 2^29)."""
+    return (np.asarray(a, np.float64) * np.asarray(b, np.float64) + np.asarray(c, np.float64)).astype(np.float32)
+
+
+def input_f32(X, BT, pad=1):
+    """V = B^T d B of every tile of a FLOAT input in the pinned fp32 arithmetic (chains
+    acc = +0; acc = fma(B^T[i][j], d[j][l], acc) over ascending j, left product first):
+    what oracle_q_input computes for integer codes, here for any fp32 X.  Returns
+    V [P, T, C] fp32, t = (img*TH + th)*TW + tw."""
+    X = np.asarray(X, np.float32)
+    BT = np.asarray(BT, np.float32)
+    N, C, H, W = X.shape
+    n = BT.shape[0]
+    m = n - 2
+    geo = geometry(N, H, W, pad, m)
+    TH, TW = geo["TH"], geo["TW"]
+    Xp = np.zeros((N, C, pad + TH * m + n, pad + TW * m + n), np.float32)
+    Xp[:, :, pad:pad + H, pad:pad + W] = X
+    d = np.stack([Xp[:, :, th * m:th * m + n, tw * m:tw * m + n]
+                  for th in range(TH) for tw in range(TW)], axis=1)          # [N, TH*TW, C, n, n]
+    d = d.reshape(N * TH * TW, C, n, n)
+    w = np.zeros_like(d)
+    for i in range(n):
+        acc = np.zeros(d[:, :, 0, :].shape, np.float32)
+        for j in range(n):
+            acc = _fma32(BT[i, j], d[:, :, j, :], acc)
+        w[:, :, i, :] = acc
+    V = np.zeros_like(d)
+    for k in range(n):
+        acc = np.zeros(d[:, :, :, 0].shape, np.float32)
+        for l in range(n):
+            acc = _fma32(w[:, :, :, l], BT[k, l], acc)
+        V[:, :, :, k] = acc
+    return np.ascontiguousarray(V.transpose(2, 3, 0, 1).reshape(n * n, N * TH * TW, C))
+
+
+def winograd_bf16(X, g, BT, G, AT, pad=1):
+    """The float path with bf16 operands in the per-position GEMM (the speed variant of the
+    GEMM stage, Sec. 5.3): U = G g G^T and V = B^T d B in the pinned fp32 arithmetic, each
+    rounded to bf16 (nearest even), multiplied and summed over the input channels exactly
+    (fp64), and transformed back with A^T in fp64.  Returns Y [N, K, Ho, Wo] in fp64."""
+    AT = np.asarray(AT, np.float64)
+    N, C, H, W = np.shape(X)
+    K = np.shape(g)[0]
+    m = AT.shape[0]
+    n = m + 2
+    geo = geometry(N, H, W, pad, m)
+    TH, TW, Ho, Wo = geo["TH"], geo["TW"], geo["Ho"], geo["Wo"]
+    Uf, _ = q_weights(g, G, want_q=False)                       # [P, K, C] fp32, pinned chains
+    Ub = bf16_round(Uf).astype(np.float64)
+    Vb = bf16_round(input_f32(X, BT, pad)).astype(np.float64)   # [P, T, C]
+    Mt = np.einsum("ptc,pkc->ptk", Vb, Ub).reshape(n, n, N, TH, TW, K)
+    Yt = np.einsum("ai,ijnhwk,bj->nkhawb", AT, Mt, AT).reshape(N, K, TH * m, TW * m)
+    return np.ascontiguousarray(Yt[:, :, :Ho, :Wo])
+
+
 def q_scalars(s_x, s_v, s_u, s_y, s_m=0.0):
     out = [ctypes.c_float() for _ in range(4)]
     lib().oracle_q_scalars(ctypes.c_float(s_x), ctypes.c_float(s_v), ctypes.c_float(s_u),

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # host code is instrumented); it is still this library, never a substitute path.
 LIB_PATH = os.environ.get("WINO_LIB") or os.path.join(_HERE, "libwino.so")
 
-WINO_F32, WINO_I8, WINO_I16, WINO_I8W16 = 0, 1, 2, 3
+WINO_F32, WINO_I8, WINO_I16, WINO_I8W16, WINO_BF16 = 0, 1, 2, 3, 4
 WINO_TAP_U, WINO_TAP_V, WINO_TAP_M = 0, 1, 2
 WINO_STAGE_INPUT, WINO_STAGE_GEMM, WINO_STAGE_OUTPUT, WINO_STAGE_ALL = 1, 2, 4, 7
 

@@ -21,8 +21,9 @@ wino_status make_geom(const wino_desc* d, Geom* g) {
   if (!d) return WINO_E_NULL;
   if (d->m != 2 && d->m != 4 && d->m != 6) return WINO_E_BAD_M;
   if (d->dtype != WINO_F32 && d->dtype != WINO_I8 && d->dtype != WINO_I16 &&
-      d->dtype != WINO_I8W16)
+      d->dtype != WINO_I8W16 && d->dtype != WINO_BF16)
     return WINO_E_BAD_DTYPE;
+  if (d->dtype == WINO_BF16 && d->m == 6) return WINO_E_BAD_M;
   if (d->N < 1 || d->C < 1 || d->K < 1 || d->H < 1 || d->W < 1) return WINO_E_BAD_SHAPE;
   if (d->pad != 0 && d->pad != 1) return WINO_E_BAD_SHAPE;
   g->N = d->N; g->C = d->C; g->K = d->K; g->H = d->H; g->W = d->W;
@@ -35,6 +36,7 @@ wino_status make_geom(const wino_desc* d, Geom* g) {
   g->i8 = d->dtype == WINO_I8;
   g->w16 = d->dtype == WINO_I16 || d->dtype == WINO_I8W16;
   g->x16 = d->dtype == WINO_I16;
+  g->bf16 = d->dtype == WINO_BF16;
   // (wide modes: the int32 sums of digit products and their recombination are sized for
   // reductions of at most 1024 channels)
   if (g->w16 && d->C > 1024) return WINO_E_BAD_SHAPE;
@@ -56,6 +58,7 @@ wino_status make_geom(const wino_desc* d, Geom* g) {
       (long long)d->N * d->C * d->H * d->W * e > limit * e ||
       (long long)d->N * d->K * g->Ho * g->Wo > limit)
     return WINO_E_BAD_SHAPE;
+  if (g->bf16 && !fused_fwd_bf16_supported(*g)) return WINO_E_BAD_SHAPE;
   return WINO_OK;
 }
 
@@ -228,7 +231,7 @@ int wino_fwd_num_kernels(const wino_desc* d) {
     }
     return 3;
   }
-  if (fused_fwd_f32_supported(g)) return 1;
+  if (g.bf16 || fused_fwd_f32_supported(g)) return 1;
   if (g.i8) {
     // as in wino_conv2d_fwd: the sequence the table of measured times names
     MatBT bt;
@@ -367,6 +370,12 @@ wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_de
       seq = fwd_sequence_auto(g, &bt, false);
     }
   }
+  if (g.bf16) {
+    // bf16 GEMM operands: the one-kernel forward only (make_geom has checked the shape)
+    if (stages != WINO_STAGE_ALL) return WINO_E_BAD_ARG;
+    return launch_fused_fwd_bf16(g, bt, at, x_dev, U_dev, y_dev, hs) == hipSuccess ? WINO_OK
+                                                                                   : WINO_E_HIP;
+  }
   if (stages == WINO_STAGE_ALL && fused_fwd_f32_supported(g))
     return launch_fused_fwd_f32(g, bt, at, x_dev, U_dev, y_dev, hs) == hipSuccess ? WINO_OK
                                                                                   : WINO_E_HIP;
@@ -462,6 +471,7 @@ wino_status wino_debug_export(const wino_desc* d, int which, const void* src_dev
   if (st != WINO_OK) return st;
   if (!src_dev || !out_dev) return WINO_E_NULL;
   if (which != WINO_TAP_U && which != WINO_TAP_V && which != WINO_TAP_M) return WINO_E_BAD_ARG;
+  if (g.bf16) return WINO_E_BAD_DTYPE;                 // no taps in this mode
   const void* src = src_dev;
   if (which == WINO_TAP_M) src = (const char*)src_dev + v_bytes(g);
   if ((g.w16 ? launch_w16_export(g, which, src, out_dev, (hipStream_t)stream)

@@ -62,7 +62,15 @@ __device__ __forceinline__ void lds_barrier() {
 // kSparse: B^T and A^T both have the Cook-Toom zero pattern.
 // kFast: whole tiles, K % 4 == 0, y 16-byte aligned (vector stores, no guards).
 // kIters: staged elements per producer thread and block (>= ceil(total / 256)).
-template <int M, bool kSparse, bool kFast, int kIters>
+// kBF: bf16 operands in the per-position GEMM (WINO_BF16): the producers round V to bf16
+// (nearest even) as they store it, U arrives as bf16 in the layout of ubf_index, and a
+// block of 16 channels is one v_mfma_f32_16x16x16_bf16 per position instead of four fp32
+// MFMAs at an eighth of the rate -- the consumers then wait for the producers, whose loads
+// of the next block of X are no longer covered by a long MFMA phase (running them several
+// blocks ahead was tried and measured slower: the waits the compiler places at the loop's
+// joins drain every block in flight).  Everything else (staging, transforms, barriers,
+// output side) is the fp32 kernel's.
+template <int M, bool kSparse, bool kFast, int kIters, bool kBF = false>
 __global__ __launch_bounds__(512) void fused_fwd_f32_kernel(const float* __restrict__ x,
                                                             const float* __restrict__ U,
                                                             float* __restrict__ y, Geom g, FPlan pl,
@@ -166,9 +174,15 @@ __global__ __launch_bounds__(512) void fused_fwd_f32_kernel(const float* __restr
       {
         float Vt[n][n];
         transform_patch<M, kSparse>(d, bt, Vt);
-        float* vdst = Vl + (nb & 1) * P * 256 + tl * 16 + c2;
+        if constexpr (kBF) {
+          __bf16* vdst = (__bf16*)Vl + (nb & 1) * P * 256 + tl * 16 + c2;
 #pragma unroll
-        for (int p = 0; p < P; ++p) vdst[p * 256] = Vt[p / n][p % n];
+          for (int p = 0; p < P; ++p) vdst[p * 256] = (__bf16)Vt[p / n][p % n];
+        } else {
+          float* vdst = Vl + (nb & 1) * P * 256 + tl * 16 + c2;
+#pragma unroll
+          for (int p = 0; p < P; ++p) vdst[p * 256] = Vt[p / n][p % n];
+        }
       }
       if (nb == 1) WINO_TSF(11);
       lds_barrier();                                   // barrier 2 of step nb - 1
@@ -182,15 +196,69 @@ __global__ __launch_bounds__(512) void fused_fwd_f32_kernel(const float* __restr
 
   // -------------------------------------------------------------------- consumers
   const int lane = tid & 63, r = lane & 15, grp = lane >> 4;
+  v4f acc[P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) acc[p] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+  constexpr int kVRing = 4;                            // V operands: LDS reads 4 positions ahead
+  static_assert(P % kVRing == 0 && P % 2 == 0, "ring depths must divide the number of positions");
+  constexpr int kSplit = (P / 3) & ~1;                 // barrier 1 after this many positions
+  if constexpr (kBF) {
+    // "A" rows = output channels kb + wave*16 + r, four bf16 at channel grp*4: in the layout
+    // of ubf_index the wavefront's 16 x 16 block of a channel block is 512 consecutive
+    // bytes, this lane's piece at (grp*16 + r) * 8
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    const uint32_t uoff = (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)(g.Cp >> 4) * 512u +
+                          (uint32_t)(grp * 16 + r) * 8u;
+    const size_t up = (size_t)g.Kp * g.Cp * 2;
+    constexpr int kDepth = M == 4 ? 12 : 8;
+    static_assert(P % kDepth == 0, "ring depth must divide the number of positions");
+    v4s bufU[kDepth];
+    const char* Ub = (const char*)U;
+    size_t ublk = 0, uld = 0;
+#pragma unroll
+    for (int p = 0; p < kDepth; ++p) {
+      bufU[p] = *(const v4s*)(Ub + uld + uoff);
+      uld += up;
+      asm volatile("" : "+s"(uld));
+    }
+    lds_barrier();                                     // step -1: the producers prepare block 0
+    lds_barrier();
+    for (int s = 0; s < nblk; ++s) {
+      const __bf16* vb = (const __bf16*)Vl + (s & 1) * P * 256 + r * 16 + grp * 4;
+      v4s bufV[kVRing];
+#pragma unroll
+      for (int p = 0; p < kVRing; ++p) bufV[p] = *(const v4s*)(vb + p * 256);
+#pragma unroll
+      for (int p0 = 0; p0 < P; p0 += 2) {
+        if (p0 == kSplit) lds_barrier();               // barrier 1 of step s
+        v4s au[2], bv[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int p = p0 + q;
+          au[q] = bufU[p % kDepth];
+          bv[q] = bufV[p % kVRing];
+          if (p + kVRing < P) bufV[p % kVRing] = *(const v4s*)(vb + (p + kVRing) * 256);
+          if (p + kDepth < P || s + 1 < nblk) bufU[p % kDepth] = *(const v4s*)(Ub + uld + uoff);
+          if (p + kDepth + 1 == P) {
+            ublk += 512;                               // next 16-channel block of U
+            uld = ublk;
+          } else {
+            uld += up;
+          }
+          asm volatile("" : "+s"(uld));
+        }
+        acc[p0] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(au[0], bv[0], acc[p0], 0, 0, 0);
+        acc[p0 + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(au[1], bv[1], acc[p0 + 1], 0, 0, 0);
+      }
+      lds_barrier();                                   // barrier 2 of step s
+    }
+  } else {
   // "A" rows = output channels kb + wave*16 + r, 4 floats at channel grp*4: in the blocked
   // layout of the fp32 weights (u_byte_index) the wavefront's 16 x 16 block of a channel
   // block is 1 KB of consecutive bytes, this lane's piece at (grp*16 + r) * 16
   const uint32_t uoff = (uint32_t)((kb + wave * 16) >> 4) * (uint32_t)(g.Cp >> 4) * 1024u +
                         (uint32_t)(grp * 16 + r) * 16u;
   const size_t up = (size_t)g.Kp * g.Cp * 4;
-  v4f acc[P];
-#pragma unroll
-  for (int p = 0; p < P; ++p) acc[p] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
   // U through a register ring kDepth positions deep that runs on across the channel
   // blocks (uniform running byte offset, one position per step; the empty statement keeps
@@ -212,9 +280,6 @@ __global__ __launch_bounds__(512) void fused_fwd_f32_kernel(const float* __restr
   lds_barrier();
   WINO_TSF(1);
 
-  constexpr int kVRing = 4;                            // V operands: LDS reads 4 positions ahead
-  static_assert(P % kVRing == 0 && P % 2 == 0, "ring depths must divide the number of positions");
-  constexpr int kSplit = (P / 3) & ~1;                 // barrier 1 after this many positions
   for (int s = 0; s < nblk; ++s) {
     const float* vb = Vl + (s & 1) * P * 256 + r * 16 + grp * 4;
     v4f bufV[kVRing];
@@ -267,6 +332,7 @@ __global__ __launch_bounds__(512) void fused_fwd_f32_kernel(const float* __restr
     lds_barrier();                                     // barrier 2 of step s
     if (s == 0) WINO_TSF(2);
     if (s == 1) WINO_TSF(3);
+  }
   }
   WINO_TSF(4);
 
@@ -388,18 +454,43 @@ hipError_t launch_input_staged_m(const Geom& g, const MatBT& bt, const float* x,
   return hipGetLastError();
 }
 
-template <int M, bool kSparse, bool kFast, int kIters>
+template <int M, bool kSparse, bool kFast, int kIters, bool kBF = false>
 hipError_t launch_k(const Geom& g, const FPlan& pl, size_t lb, dim3 grid, const MatBT& bt,
                     const MatAT& at, const float* x, const float* U, float* y, hipStream_t s) {
   if (lb > 65536) {
     // more dynamic LDS than the default limit: raise it for this kernel (cheap, idempotent)
     const hipError_t e =
-        hipFuncSetAttribute((const void*)fused_fwd_f32_kernel<M, kSparse, kFast, kIters>,
+        hipFuncSetAttribute((const void*)fused_fwd_f32_kernel<M, kSparse, kFast, kIters, kBF>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lb);
     if (e != hipSuccess) return e;
   }
-  fused_fwd_f32_kernel<M, kSparse, kFast, kIters><<<grid, 512, lb, s>>>(x, U, y, g, pl, bt, at);
+  fused_fwd_f32_kernel<M, kSparse, kFast, kIters, kBF><<<grid, 512, lb, s>>>(x, U, y, g, pl, bt, at);
   return hipGetLastError();
+}
+
+// WINO_BF16: the same launch with bf16 GEMM operands (fewer staging-loop sizes are built)
+template <int M>
+hipError_t launch_m_bf16(const Geom& g, const MatBT& bt, const MatAT& at, const float* x,
+                         const float* U, float* y, hipStream_t s) {
+  FPlan pl;
+  size_t lb;
+  int nrb, ntwb;
+  if (!make_fplan(g, &pl, &lb, &nrb, &ntwb)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)nrb, (unsigned)ntwb, (unsigned)(g.Kp / 64));
+  const bool sparse = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt) &&
+                      fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && ((uintptr_t)y & 15) == 0;
+#define WINO_LAUNCH_BF(SP, FA, IT) \
+  return launch_k<M, SP, FA, IT, true>(g, pl, lb, grid, bt, at, x, U, y, s)
+  if (sparse && fast) {
+    if (pl.iters <= 8) WINO_LAUNCH_BF(true, true, 8);
+    if (pl.iters <= 16) WINO_LAUNCH_BF(true, true, 16);
+    WINO_LAUNCH_BF(true, true, 32);
+  }
+  if (sparse) WINO_LAUNCH_BF(true, false, 32);
+  if (fast) WINO_LAUNCH_BF(false, true, 32);
+  WINO_LAUNCH_BF(false, false, 32);
+#undef WINO_LAUNCH_BF
 }
 
 template <int M>
@@ -453,6 +544,24 @@ bool fused_fwd_f32_supported(const Geom& g) {
   return !g.i8 && (g.m == 2 || g.m == 4) && g.Kp <= 128 && make_fplan(g, &pl, &lb, &nrb, &ntwb) &&
          (unsigned long long)g.N * g.C * g.H * g.W < 0x7fffffffull &&
          (unsigned long long)g.Kp * g.Cp * 4 < 0xffffffffull && R * g.TH < 0x100000000ull;
+}
+
+bool fused_fwd_bf16_supported(const Geom& g) {
+  // what the kernel can run: F2 or F4, the staging plan within its limits, 32-bit offsets
+  const unsigned long long R = (unsigned long long)g.N * g.TH;
+  FPlan pl;
+  size_t lb;
+  int nrb, ntwb;
+  return g.bf16 && (g.m == 2 || g.m == 4) && make_fplan(g, &pl, &lb, &nrb, &ntwb) &&
+         (unsigned long long)g.N * g.C * g.H * g.W < 0x7fffffffull &&
+         (unsigned long long)g.Kp * g.Cp * 2 < 0xffffffffull && R * g.TH < 0x100000000ull;
+}
+
+hipError_t launch_fused_fwd_bf16(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                                 const void* U, void* y, hipStream_t s) {
+  if (!fused_fwd_bf16_supported(g)) return hipErrorInvalidValue;
+  if (g.m == 2) return launch_m_bf16<2>(g, bt, at, (const float*)x, (const float*)U, (float*)y, s);
+  return launch_m_bf16<4>(g, bt, at, (const float*)x, (const float*)U, (float*)y, s);
 }
 
 bool input_f32_staged_supported(const Geom& g) {

@@ -245,7 +245,8 @@ __global__ __launch_bounds__(256) void weight_transform_i8(Geom g, MatG mg,
   }
 }
 
-template <int M>
+// kBF: results rounded to bf16 (nearest even) and stored in the layout of ubf_index.
+template <int M, bool kBF = false>
 __global__ __launch_bounds__(256) void weight_transform_f32(Geom g, MatG mg,
                                                             const float* __restrict__ w,
                                                             float* __restrict__ U) {
@@ -267,11 +268,17 @@ __global__ __launch_bounds__(256) void weight_transform_f32(Geom g, MatG mg,
       for (int b = 0; b < 3; ++b) gk[a][b] = wp[a * 3 + b];
     transform_filter<n>(gk, mg, Ut);
   }
-  // blocked layout (see u_byte_index): same place in every position's slab
+  // blocked layout (see u_byte_index / ubf_index): same place in every position's slab
   const size_t pstride = (size_t)g.Kp * g.Cp;
-  float* up = U + u_byte_index(g.Kp, g.Cp, 4, 0, k, c) / 4;
+  if constexpr (kBF) {
+    __bf16* up = (__bf16*)U + ubf_index(g.Kp, g.Cp, 0, k, c);
 #pragma unroll
-  for (int p = 0; p < P; ++p) up[p * pstride] = Ut[p / n][p % n];
+    for (int p = 0; p < P; ++p) up[p * pstride] = (__bf16)Ut[p / n][p % n];
+  } else {
+    float* up = U + u_byte_index(g.Kp, g.Cp, 4, 0, k, c) / 4;
+#pragma unroll
+    for (int p = 0; p < P; ++p) up[p * pstride] = Ut[p / n][p % n];
+  }
 }
 
 // ------------------------------------------------------------------ output --
@@ -447,6 +454,12 @@ hipError_t launch_weight_transform(const Geom& g, const MatG& mg, const float* w
   } else {
     const unsigned nb = blocks_for((long long)g.Kp * g.Cp);
     float* Uo = (float*)U;
+    if (g.bf16) {
+      if (g.m == 2) weight_transform_f32<2, true><<<nb, 256, 0, s>>>(g, mg, w, Uo);
+      else if (g.m == 4) weight_transform_f32<4, true><<<nb, 256, 0, s>>>(g, mg, w, Uo);
+      else return hipErrorInvalidValue;
+      return hipGetLastError();
+    }
     switch (g.m) {
       case 2: weight_transform_f32<2><<<nb, 256, 0, s>>>(g, mg, w, Uo); break;
       case 4: weight_transform_f32<4><<<nb, 256, 0, s>>>(g, mg, w, Uo); break;

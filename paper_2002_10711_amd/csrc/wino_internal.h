@@ -21,6 +21,7 @@ struct Geom {
   int i8;
   int w16;   // 16-bit codes in the Winograd domain (WINO_I16, WINO_I8W16): own kernels, own layouts
   int x16;   // ... and int16 containers for X and Y (WINO_I16)
+  int bf16;  // float path with bf16 GEMM operands (WINO_BF16): own U layout, one-kernel forward only
 };
 
 struct MatBT { float v[64]; };   // n x n, row-major, n <= 8
@@ -129,6 +130,19 @@ hipError_t launch_fused_fwd(const Geom& g, const MatBT& bt, const MatAT& at, con
 bool fused_fwd_f32_supported(const Geom& g);
 hipError_t launch_fused_fwd_f32(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
                                 const void* U, void* y, hipStream_t s);
+// The same with bf16 operands in the per-position GEMM (WINO_BF16): U in the layout of
+// ubf_index, written by launch_weight_transform when g.bf16 is set.
+bool fused_fwd_bf16_supported(const Geom& g);
+hipError_t launch_fused_fwd_bf16(const Geom& g, const MatBT& bt, const MatAT& at, const void* x,
+                                 const void* U, void* y, hipStream_t s);
+// Element index of U[p][k][c] in the bf16 layout: per position, blocks of 16 output channels
+// x 16 input channels (512 bytes), each in the order in which an MFMA wavefront loads it --
+// lane (k % 16, c % 16 / 4) takes the four consecutive channels c % 4 = 0 .. 3 as one 8-byte
+// piece at piece index (c % 16 / 4) * 16 + k % 16.
+__host__ __device__ inline size_t ubf_index(int Kp, int Cp, int p, int k, int c) {
+  const size_t blk = ((size_t)p * (Kp >> 4) + (k >> 4)) * (Cp >> 4) + (c >> 4);
+  return blk * 256 + (size_t)((((c & 15) >> 2) * 16 + (k & 15)) * 4 + (c & 3));
+}
 // The fp32 input stage alone, LDS-staged (coalesced row loads); only where supported.
 bool input_f32_staged_supported(const Geom& g);
 hipError_t launch_input_f32_staged(const Geom& g, const MatBT& bt, const void* x, void* V,

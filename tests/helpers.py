@@ -27,7 +27,9 @@ def run_gpu(case, taps=True, scales=None):
     L = case["layer"]
     dev = torch.device("cuda:0")
     i8 = L.dtype == "i8"
-    desc = wb.Desc(L.N, L.C, L.K, L.H, L.W, L.pad, L.m, wb.WINO_I8 if i8 else wb.WINO_F32,
+    bf = L.dtype == "bf16"
+    desc = wb.Desc(L.N, L.C, L.K, L.H, L.W, L.pad, L.m,
+                   wb.WINO_I8 if i8 else wb.WINO_BF16 if bf else wb.WINO_F32,
                    BT=case["BT"], G=case["G"], AT=case["AT"])
     quant = None
     if i8:
@@ -57,6 +59,8 @@ def run_gpu(case, taps=True, scales=None):
             wb.wino_conv2d_fwd_seq(desc, quant, x, U, ys, ws, seq)
             torch.cuda.synchronize()
             out["Y_seq"][name] = ys.cpu().numpy()
+    if bf:
+        return out                                  # one kernel only: no stages, no taps
     # stage by stage, which materialises V and M for the taps
     y2 = torch.full_like(y, 55)
     ws.zero_()

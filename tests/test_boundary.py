@@ -298,3 +298,23 @@ def test_kernel_sequences_of_the_named_workloads():
                   "cfg3_c512_s4_F4": 3}
     c5 = {L.name: nk(L) for L in workloads.config5() if L.stride == 1}
     assert [c5[k] for k in sorted(c5)] == [1, 2, 1, 1, 2, 1, 1, 2, 2, 2, 3, 3, 2]
+
+
+def test_bf16_mode_is_limited_to_the_one_kernel_forward():
+    """WINO_BF16 (float path, bf16 GEMM operands) is built for m in {2, 4}: m = 6 is an error
+    of the descriptor, stage-by-stage calls and taps are refused, all before any HIP call."""
+    import ctypes
+    BT, G, AT = wb.wino_cook_toom(6)
+    d6 = wb.Desc(1, 16, 16, 12, 12, 1, 6, wb.WINO_BF16, BT=BT, G=G, AT=AT)
+    assert wb.wino_fwd_num_kernels(d6) == 0 and wb.wino_weights_bytes(d6) == 0
+    lib = wb.lib()
+    assert lib.wino_transform_weights(d6.ref, None, 0x1000, 0x1000, None) == -2
+    BT, G, AT = wb.wino_cook_toom(4)
+    d4 = wb.Desc(2, 16, 16, 12, 12, 1, 4, wb.WINO_BF16, BT=BT, G=G, AT=AT)
+    assert wb.wino_fwd_num_kernels(d4) == 1
+    assert wb.wino_weights_bytes(d4) > 0 and wb.wino_workspace_bytes(d4) > 0
+    ws = wb.wino_workspace_bytes(d4)
+    for stage in (wb.WINO_STAGE_INPUT, wb.WINO_STAGE_GEMM, wb.WINO_STAGE_OUTPUT):
+        assert lib.wino_conv2d_fwd_stages(d4.ref, None, 0x1000, 0x1000, 0x1000, 0x1000, ws, stage, None) == -8
+    assert lib.wino_debug_export(d4.ref, wb.WINO_TAP_U, 0x1000, 0x1000, None) == -4
+    assert wb.wino_fwd_sequence(d4, wb.WINO_SEQ_AUTO) == 0

@@ -727,3 +727,37 @@ def test_quantizer_rounds_the_exact_product_once(oracle):
     for r, want in ((r_up, [1, -1, 1, 127]), (r_dn, [0, 0, 1, 127]), (np.float32(0.5), [2, -2, 2, 127])):
         _, Yq, _ = oracle.q_output(M, AT, 1, 2, 2, pad=1, r_y=r)
         assert [int(v) for v in Yq[0, :, 0, 0]] == want, (r, Yq[0, :, 0, 0])
+
+
+def test_bf16_variant_rounding_and_exact_case(oracle):
+    """The bf16 variant of the GEMM stage: round-to-nearest-even at 8 significant bits (hand
+    values around ties), nothing lost when every transformed value is representable (F2 with
+    small integers: the result then is the direct convolution, exactly), and a visible error
+    otherwise."""
+    vals = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20, -1 - 2.0 ** -8,
+                     255.0, 257.0, 0.0, -3.140625], np.float32)
+    want = np.array([1.0, 1 + 2.0 ** -6, 1 + 2.0 ** -7, -1.0, 255.0, 256.0, 0.0, -3.140625], np.float32)
+    assert np.array_equal(oracle.bf16_round(vals), want)
+    rng = np.random.default_rng(77)
+    BT, G, AT = oracle.cook_toom(2, dtype=np.float32)
+    X = rng.integers(-3, 4, (2, 5, 7, 6)).astype(np.float32)
+    g = (4 * rng.integers(-1, 2, (4, 5, 3, 3))).astype(np.float32)
+    Y = oracle.winograd_bf16(X, g, BT, G, AT, 1)
+    assert np.array_equal(Y, oracle.conv2d_direct_f64(X, g, 1, 1))
+    # the float input transform in the pinned arithmetic: bit-equal to the integer-input one
+    # (C++ oracle) on integer-valued data, for every tile size and a ragged shape
+    xi = rng.integers(-127, 128, (2, 3, 9, 7))
+    for m in (2, 4, 6):
+        BT, G, AT = oracle.cook_toom(m, dtype=np.float32)
+        Vf, _ = oracle.q_input(xi, BT, pad=1, want_q=False)
+        assert np.array_equal(oracle.input_f32(xi.astype(np.float32), BT, 1), Vf)
+        BTd = (BT + 0.01 * rng.standard_normal(BT.shape)).astype(np.float32)     # dense matrix
+        Vf, _ = oracle.q_input(xi, BTd, pad=0, want_q=False)
+        assert np.array_equal(oracle.input_f32(xi.astype(np.float32), BTd, 0), Vf)
+    X = rng.standard_normal((2, 5, 7, 6)).astype(np.float32)
+    g = rng.standard_normal((4, 5, 3, 3)).astype(np.float32)
+    for m, lo, hi in ((2, 1e-4, 2e-2), (4, 1e-3, 2e-1)):
+        BT, G, AT = oracle.cook_toom(m, dtype=np.float32)
+        ref = oracle.conv2d_direct_f64(X, g, 1, 1)
+        e = np.abs(oracle.winograd_bf16(X, g, BT, G, AT, 1) - ref).max() / np.abs(ref).max()
+        assert lo < e < hi, (m, e)
