@@ -133,14 +133,17 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
   const int R = g.N * g.TH;
   if constexpr (kLoad == 3) {
     static_assert(kLoad != 3 || kTWB > 0, "whole-row staging needs a compile-time shape");
-    constexpr int RW = (kTWB ? kTWB : 1) * M;          // bytes per image row
-    constexpr int ND = RW / 4;                         // dwords per image row; WQ == ND + 1
+    // bytes per image row: the tiles of a row cover it exactly (m = 2, 4), or, for m = 6,
+    // rows of 16, 32, 64 bytes under 4, 8, 16 tile slots (3, 6, 11 tiles and idle slots)
+    constexpr int RW = (kTWB ? kTWB : 1) * (M == 6 ? 4 : M);
+    constexpr int ND = RW / 4;                         // dwords per image row; WQ >= ND + 1
+    constexpr int WQc = (((kTWB ? kTWB : 1) - 1) * M >> 2) + (M == 6 ? 3 : 2);   // = WQ
     constexpr int RBc = 16 / (kTWB ? kTWB : 1);
     constexpr int nrows = RBc * n * 64;                // rows to stage: (rs, channel, j), j fastest
     constexpr int per = (nrows + kThreads - 1) / kThreads;
     uint32_t rw[per][ND];
     uint32_t* dst[per];
-    uint32_t* dump = Xs + RB * 64 * plane;             // WQ dwords nobody reads
+    uint32_t* dump = Xs + RB * 64 * plane;             // WQ dwords nobody reads (see make_xlaunch)
 #pragma unroll
     for (int i = 0; i < per; ++i) {
       const int id = (int)threadIdx.x + i * kThreads;
@@ -180,9 +183,9 @@ __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
     for (int i = 0; i < per; ++i) {
       // staged dword k = image bytes 4k-1 .. 4k+2 (zero outside the row)
 #pragma unroll
-      for (int k = 0; k <= ND; ++k) {
-        const uint32_t hi = k < ND ? rw[i][k] : 0u, lo = k > 0 ? rw[i][k - 1] : 0u;
-        dst[i][k] = __builtin_amdgcn_alignbyte(hi, lo, 3);
+      for (int k = 0; k < WQc; ++k) {
+        const uint32_t hi = k < ND ? rw[i][k] : 0u, lo = (k > 0 && k <= ND) ? rw[i][k - 1] : 0u;
+        dst[i][k] = k <= ND ? __builtin_amdgcn_alignbyte(hi, lo, 3) : 0u;
       }
     }
     return;
@@ -978,6 +981,10 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   if (M != 6 && xl->load == 2 && g.pad == 1 && g.TW == TWB && g.W == TWB * M && g.W >= 8 &&
       ((uintptr_t)x & (g.W >= 16 ? 15 : 7)) == 0)
     xl->load = 3;
+  // ... F(6x6,3x3): rows of 16, 32 or 64 bytes under 4, 8 or 16 tile slots
+  if (M == 6 && xl->load == 2 && g.pad == 1 && g.W == 4 * TWB && g.TW <= TWB && g.W >= 16 &&
+      ((uintptr_t)x & 15) == 0)
+    xl->load = 3;
   // ... or 4 bytes: images four pixels wide (two tiles of F2 or one of F4 per row)
   if (M != 6 && g.W == 4 && g.pad == 1 && g.TW == TWB && TWB * M == 4 && ((uintptr_t)x & 3) == 0)
     xl->load = 3;
@@ -1013,11 +1020,11 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
     }                                                                                      \
     kern<<<grid, 256, xl.lds_bytes, s>>>(xi, Vi, rvs, qmax, g, xl.pl, karg);               \
   } while (0)
-  // (whole-row staging is built for rows of 4, 8, 16, 32 or 64 bytes)
+  // (whole-row staging is built for rows of 4, 8, 16, 32 or 64 bytes; for m = 6: 16, 32, 64)
 #define WINO_LAUNCH_IN2(TWBC)                                                              \
   do {                                                                                     \
     if (xl.load == 3) {                                                                    \
-      if constexpr (M != 6 && (TWBC * M) % 4 == 0) WINO_LAUNCH_IN(3, TWBC);                \
+      if constexpr (M == 6 ? TWBC >= 4 : (TWBC * M) % 4 == 0) WINO_LAUNCH_IN(3, TWBC);     \
       else return hipErrorInvalidValue;                                                    \
     } else if (xl.load == 2) WINO_LAUNCH_IN(2, TWBC);                                      \
     else WINO_LAUNCH_IN(1, TWBC);                                                          \
