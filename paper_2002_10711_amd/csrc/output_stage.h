@@ -17,6 +17,23 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 template <bool I8> struct Acc { typedef v4i type; };
 template <> struct Acc<false> { typedef v4f type; };
 
+// One row of six output codes of F(6x6,3x3) as a dword and a pair instead of three pairs:
+// tile columns start at w0 = 6 tw, so a row begins on a dword boundary (even tw: dword at
+// w0, pair at w0 + 4) or in mid-dword (odd tw: pair at w0, dword at w0 + 2).  For row
+// pitches that are multiples of 4 and planes that start dword-aligned: then a dword, like a
+// pair, is inside the image or outside it as a whole.  b0 .. b5: the codes in the low bytes.
+__device__ __forceinline__ void store_row6(int8_t* row, int w0, int Wo, uint32_t b0, uint32_t b1,
+                                           uint32_t b2, uint32_t b3, uint32_t b4, uint32_t b5) {
+  const uint32_t lo4 = pack_codes(b0, b1, b2, b3);
+  const uint32_t hi2 = __builtin_amdgcn_perm(b5, b4, 0x0c0c0400u);
+  const bool odd = (w0 & 3) != 0;
+  const uint32_t dv = odd ? __builtin_amdgcn_alignbit(hi2, lo4, 16) : lo4;
+  const uint32_t sv = odd ? lo4 : hi2;
+  const int doff = odd ? 2 : 0, soff = odd ? 0 : 4;
+  if (w0 + doff + 4 <= Wo) *(uint32_t*)(row + doff) = dv;
+  if (w0 + soff + 2 <= Wo) *(uint16_t*)(row + soff) = (uint16_t)sv;
+}
+
 // Stores one m x m output tile of channel k; (h0, w0) is its top-left corner.
 // kFast: the host has checked that m divides Ho and Wo (every tile is whole and every
 // row keeps the alignment of the vector stores; for fp32 also that y itself is 16-byte
@@ -54,6 +71,15 @@ __device__ __forceinline__ void store_tile(const Geom& g, void* __restrict__ yv,
             *(uint16_t*)(row + b) =
                 (uint16_t)__builtin_amdgcn_perm(q[a][b + 1], q[a][b], 0x0c0c0400u);
         }
+      }
+    } else if (M == 6 && (g.Wo & 3) == 0 && (((uintptr_t)yv + plane) & 3) == 0) {
+      // six codes per row as a dword and a pair (store_row6)
+      if constexpr (M == 6) {
+#pragma unroll
+        for (int a = 0; a < M; ++a)
+          if (h0 + a < g.Ho)
+            store_row6(y + (size_t)(h0 + a) * g.Wo + w0, w0, g.Wo, q[a][0], q[a][1], q[a][2], q[a][3],
+                       q[a][4], q[a][5]);
       }
     } else if ((g.Wo & 1) == 0) {
       // ragged tile, even row pitch: a pair of codes is inside the image or outside it as
@@ -195,6 +221,16 @@ __device__ __forceinline__ void store_codes(YT* __restrict__ plane, const Geom& 
                 (uint16_t)(((uint32_t)q[a][2 * e] & 0xffu) | (((uint32_t)q[a][2 * e + 1] & 0xffu) << 8));
         }
       }
+    }
+  } else if (M == 6 && sizeof(YT) == 1 && (g.Wo & 3) == 0 && ((uintptr_t)plane & 3) == 0) {
+    // six codes per row as a dword and a pair (store_row6)
+    if constexpr (M == 6 && sizeof(YT) == 1) {
+#pragma unroll
+      for (int a = 0; a < M; ++a)
+        if (h0 + a < g.Ho)
+          store_row6((int8_t*)plane + (size_t)(h0 + a) * g.Wo + w0, w0, g.Wo, (uint32_t)q[a][0],
+                     (uint32_t)q[a][1], (uint32_t)q[a][2], (uint32_t)q[a][3], (uint32_t)q[a][4],
+                     (uint32_t)q[a][5]);
     }
   } else if ((g.Wo & 1) == 0 && ((uintptr_t)plane & (2 * sizeof(YT) - 1)) == 0) {
     // ragged tile, even row pitch: a pair of codes is inside the image or outside it as a
