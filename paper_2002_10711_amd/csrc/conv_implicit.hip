@@ -107,6 +107,46 @@ __global__ __launch_bounds__(256) void conv_implicit_i8_kernel(RefGeom g, Tiling
     if (ch) __syncthreads();                           // the previous chunk has been read
     // Transpose the chunk's patch into LDS.  A task: four channels x four input columns
     // of one patch row; 16 consecutive lanes take the 16 channel groups of one place.
+    // (fast_ld == 2: four channels x SIXTEEN columns per task, one 16-byte load per channel
+    // row -- the 4-byte loads of the other form fetch a 32-byte sector each for four bytes,
+    // which made the gather, not the matrix cores, the bound of this kernel)
+    if (fast_ld == 2) {
+      typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+      const int qlo16 = w0 < 0 ? -1 : w0 / 16;
+      const int NQ16 = (w0 + tl.PW - 1) / 16 - qlo16 + 1;
+      const int ntasks16 = tl.NI * tl.IR * NQ16 * 16;
+      const uint32_t inv_NQ16 = make_inv((uint32_t)NQ16);
+      for (int task = tid; task < ntasks16; task += 256) {
+        const int cg = task & 15, v = task >> 4;
+        const int prow = (int)fast_div((uint32_t)v, inv_NQ16), q = v - prow * NQ16;
+        const int il = (int)fast_div((uint32_t)prow, tl.inv_IR), hr = prow - il * tl.IR;
+        const int img = ig * tl.NI + il, h = h0 + hr, wb = 16 * (qlo16 + q);
+        const int c0 = ch * 64 + 4 * cg;
+        // an aligned group of sixteen columns is inside the image or outside it as a whole
+        const bool in = img < g.N && h >= 0 && h < g.H && wb >= 0 && wb < g.W;
+        const uint32_t rbase = (((uint32_t)img * g.C + c0) * g.H + h) * g.W;
+        v4u d4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool ok = in && c0 + j < g.C;
+          const v4u t = *(const v4u*)(x + (ok ? rbase + j * plane + wb : 0u));
+          d4[j] = ok ? t : v4u{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int sq = 0; sq < 4; ++sq) {
+          uint32_t d[4], e[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) d[j] = d4[j][sq];
+          transpose4x4(d, e);
+          unsigned char* dst = Xs + (prow * tl.PW + (wb + 4 * sq - w0)) * kCS + 4 * cg;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int col = wb + 4 * sq + i - w0;
+            if (col >= 0 && col < tl.PW) *(uint32_t*)(dst + i * kCS) = e[i];
+          }
+        }
+      }
+    } else
     for (int task = tid; task < ntasks; task += 256) {
       const int cg = task & 15, v = task >> 4;
       const int prow = (int)fast_div((uint32_t)v, inv_NQ), q = v - prow * NQ;
@@ -233,7 +273,9 @@ hipError_t launch_conv_implicit(const RefGeom& g, const void* x, const void* wp,
   const size_t lds = (size_t)t.NI * t.IR * t.PW * kCS;
   // dword loads along the image rows / dword stores of four pixels: every row start and
   // every group of four must be 4-byte aligned
-  const int fast_ld = ((uintptr_t)x & 3) == 0 && g.W % 4 == 0;
+  const int fast_ld = (((uintptr_t)x & 15) == 0 && g.W % 16 == 0)  ? 2
+                      : (((uintptr_t)x & 3) == 0 && g.W % 4 == 0) ? 1
+                                                                   : 0;
   const int fast_st = ((uintptr_t)y & 3) == 0 && g.Wo % 4 == 0 && t.CB % 4 == 0;
   const bool two = g.Kp % 128 == 0;
   dim3 grid((unsigned)(t.nCB * t.nRB * t.nIG), (unsigned)(g.Kp / (two ? 128 : 64)));
