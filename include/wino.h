@@ -193,7 +193,8 @@ int wino_fwd_num_kernels(const wino_desc* d);
 #define WINO_SEQ_LDS 4     /* input stage; GEMM + output transform, 32 x 64 workgroup tiles */
 #define WINO_SEQ_REGS 5    /* input stage; GEMM + output transform, accumulators in registers */
 #define WINO_SEQ_STAGED 6  /* input stage; GEMM writing M; output transform               */
-#define WINO_SEQ_COUNT 7
+#define WINO_SEQ_TROW 7    /* input stage; GEMM + output transform on whole rows of tiles  */
+#define WINO_SEQ_COUNT 8
 /* seq = WINO_SEQ_AUTO: the sequence wino_conv2d_fwd takes for this problem; any other seq:
  * seq itself if that sequence can run the problem, else 0.  0 also for an invalid
  * descriptor and for dtypes other than WINO_I8.  HOST only; reads d->BT if not NULL. */

@@ -186,9 +186,9 @@ def wino_conv2d_fwd(desc, quant, x_dev, U_dev, y_dev, workspace_dev, workspace_b
 
 # kernel sequences of the int8 forward (wino.h)
 (WINO_SEQ_AUTO, WINO_SEQ_FUSED, WINO_SEQ_COL, WINO_SEQ_COL2, WINO_SEQ_LDS, WINO_SEQ_REGS,
- WINO_SEQ_STAGED) = range(7)
+ WINO_SEQ_STAGED, WINO_SEQ_TROW) = range(8)
 SEQ_NAMES = {WINO_SEQ_FUSED: "fused", WINO_SEQ_COL: "col", WINO_SEQ_COL2: "col2", WINO_SEQ_LDS: "lds",
-             WINO_SEQ_REGS: "regs", WINO_SEQ_STAGED: "staged"}
+             WINO_SEQ_REGS: "regs", WINO_SEQ_STAGED: "staged", WINO_SEQ_TROW: "trow"}
 
 
 def wino_fwd_sequence(desc, seq=WINO_SEQ_AUTO):

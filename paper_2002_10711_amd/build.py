@@ -35,6 +35,7 @@ EXTRA_FLAGS = {
     "fused_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "wide16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "gemm_out_col.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "gemm_out_trow.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "conv_implicit.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 

@@ -398,7 +398,14 @@ wino_status fwd_stages(const wino_desc* d, const wino_quant* q, const void* x_de
   // (gemm_out_kernel knows no per-position factors: such calls take the column-wise kernel)
   if (g.i8 && seq == kSeqRegs && s.pos) seq = gemm_out_col_supported(g) ? kSeqCol : kSeqStaged;
   if (!g.i8) seq = gemm_out_f32_preferred(g) ? kSeqRegs : kSeqStaged;
-  if (s_mm && s_out && seq == kSeqLds) {
+  // (the row-of-tiles kernel stores 16-byte pieces: other alignments of y take the
+  // column-wise kernel, which supports every shape that one does)
+  if (g.i8 && seq == kSeqTrow && ((uintptr_t)y_dev & 15) != 0) seq = kSeqCol;
+  if (s_mm && s_out && seq == kSeqTrow) {
+    // F(6x6,3x3), short reductions: the same fusion on whole rows of tiles
+    if (launch_gemm_out_trow(g, at, V, U_dev, y_dev, wp, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
+      return WINO_E_HIP;
+  } else if (s_mm && s_out && seq == kSeqLds) {
     // F(2x2,3x3), 512 channels, many tiles: the same fusion with squarer workgroup tiles
     if (launch_gemm_out_lds(g, at, V, U_dev, y_dev, wp, s.r_m, s.r_y, s.qmax, hs) != hipSuccess)
       return WINO_E_HIP;

@@ -26,6 +26,7 @@ void fallback_rank(const Geom& g, unsigned char* rank) {
   int n = 0;
   if (g.Kp <= 128 && (g.m == 2 || g.Cp <= 192) && (g.Cp <= 128 || g.T >= 2048)) rank[n++] = kSeqFused;
   if (g.T >= 1024) rank[n++] = kSeqLds;
+  if (g.T >= 1024) rank[n++] = kSeqTrow;
   if (g.m == 2 || (g.m == 4 && (g.Cp <= 128 || (g.Cp <= 256 ? g.T >= 128 : g.T >= 512))) ||
       (g.m == 6 && g.Cp >= 128 && g.T >= 1024))
     rank[n++] = kSeqCol;
@@ -45,6 +46,7 @@ bool fwd_sequence_supported(const Geom& g, const MatBT* bt, int seq) {
     case kSeqCol: return gemm_out_col_supported(g);
     case kSeqCol2: return gemm_out_col2_supported(g);
     case kSeqLds: return gemm_out_lds_supported(g);
+    case kSeqTrow: return gemm_out_trow_supported(g);
     case kSeqRegs:
       // (32-bit per-lane offsets; reductions beyond 256 channels are not worth 64
       // accumulator sets waiting for them)

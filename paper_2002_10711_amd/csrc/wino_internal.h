@@ -80,7 +80,8 @@ enum FwdSeq {
   kSeqLds = 4,      // input stage; GEMM + output transform with 32 x 64 workgroup tiles
   kSeqRegs = 5,     // input stage; GEMM + output transform, all accumulators in registers
   kSeqStaged = 6,   // input stage; LDS-tiled GEMM writing M; output transform
-  kSeqCount = 7
+  kSeqTrow = 7,     // input stage; GEMM + output transform on whole rows of tiles (F6)
+  kSeqCount = 8
 };
 // Can sequence `seq` run this problem at all (shape and matrices only)?
 bool fwd_sequence_supported(const Geom& g, const MatBT* bt, int seq);
@@ -113,6 +114,14 @@ bool gemm_out_lds_supported(const Geom& g);
 hipError_t launch_gemm_out_lds(const Geom& g, const MatAT& at, const void* V, const void* U,
                                void* y, const PosScale* w_pos, float r_m, float r_y, float qmax,
                                hipStream_t s);
+// The same for F(6x6,3x3) with 64, 128 or 256 padded input channels and output rows of a
+// multiple of 16 pixels: workgroups of 32 tiles x 32 channels that own whole rows of tiles,
+// both operands staged through LDS, output codes stored as 16-byte pieces of plane rows.
+// (y must be 16-byte aligned: the launcher returns hipErrorInvalidValue otherwise.)
+bool gemm_out_trow_supported(const Geom& g);
+hipError_t launch_gemm_out_trow(const Geom& g, const MatAT& at, const void* V, const void* U,
+                                void* y, const PosScale* w_pos, float r_m, float r_y, float qmax,
+                                hipStream_t s);
 // Whole int8 forward in one kernel (neither V nor M stored); only where supported.
 bool fused_fwd_supported(const Geom& g);
 // ... and worth it with the vector-ALU input transform, which a second block of output

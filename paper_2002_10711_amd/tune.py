@@ -24,7 +24,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SWEEP_FILE = os.path.join(ROOT, "profiles", "dispatch_sweep.json")
 TABLE_FILE = os.path.join(ROOT, "paper_2002_10711_amd", "csrc", "dispatch_table.h")
-SEQ_IDS = {"fused": 1, "col": 2, "col2": 3, "lds": 4, "regs": 5, "staged": 6}
+SEQ_IDS = {"fused": 1, "col": 2, "col2": 3, "lds": 4, "regs": 5, "staged": 6, "trow": 7}
 MAX_WORKSPACE = 3 << 30
 
 

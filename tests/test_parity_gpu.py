@@ -381,6 +381,70 @@ def test_output_at_an_odd_address(oracle, flex):
         assert (edge[:shift] == 99).all() and (edge[shift + numel:] == 99).all()
 
 
+TROW = [
+    # F(6x6,3x3) GEMM + output kernel on whole rows of tiles (sequence "trow"): several
+    # workgroups with a partly filled last one, output channels that do not fill a block of
+    # 32, every reduction length it is built for, images whose last row of tiles is cut
+    Layer("tr_32px", 3, 64, 64, 32, 32, m=6, seed=190),                 # 18 rows of 6 tiles, 5 per workgroup
+    Layer("tr_16px_c128_k40", 7, 128, 40, 16, 16, m=6, seed=191),       # 21 rows of 3 tiles, 10 per workgroup
+    Layer("tr_48x20_c200_k70", 2, 200, 70, 20, 48, m=6, seed=192),      # 8 tiles per row, 256 padded channels
+    Layer("tr_pad0_34px_k33", 2, 40, 33, 34, 34, m=6, pad=0, seed=193),
+    Layer("tr_flex_16px_c100", 5, 100, 64, 16, 16, m=6, flex_sigma=0.01, seed=194),   # dense A^T
+]
+
+
+@pytest.mark.parametrize("layer", TROW, ids=lambda l: l.name)
+def test_rows_of_tiles_kernel_all_taps(oracle, layer):
+    case = make_case(oracle, layer)
+    out = run_gpu(case)
+    assert "trow" in out["Y_seq"]
+    _check_i8(case, out)
+    # ... with one scale per position and the Hadamard-stage quantizer on
+    case = make_case(oracle, layer, with_oracle=False)
+    sc = oracle.calibrate_pos(case["X"], case["g"], case["BT"], case["G"], case["AT"], pad=layer.pad)
+    case["xq"] = oracle.quantize_tensor(case["X"], sc["s_x"]).astype(np.int8)
+    ref = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc,
+                            pad=layer.pad)
+    peak = float(np.abs(ref["M"] * ref["scalars"]["w"][:, None, None]).max())
+    sc = dict(sc, s_m=max(peak, 1e-20) / 100.0)
+    case["ref"] = oracle.winograd_q(case["xq"], case["g"], case["BT"], case["G"], case["AT"], sc,
+                                    pad=layer.pad)
+    out = run_gpu(case, scales=sc)
+    assert "trow" in out["Y_seq"]
+    _check_i8(case, out)
+
+
+def test_rows_of_tiles_kernel_needs_16_byte_aligned_output(oracle):
+    """The kernel stores 16-byte pieces; an output at any other address takes the
+    column-wise kernel instead, named or not."""
+    import torch
+    from paper_2002_10711_amd import binding as wb
+    L = TROW[0]
+    case = make_case(oracle, L)
+    sc = case["scales"]
+    dev = torch.device("cuda:0")
+    desc = wb.Desc(L.N, L.C, L.K, L.H, L.W, L.pad, L.m, wb.WINO_I8, BT=case["BT"], G=case["G"],
+                   AT=case["AT"])
+    assert wb.wino_fwd_sequence(desc, wb.WINO_SEQ_TROW) == wb.WINO_SEQ_TROW
+    quant = wb.make_quant(sc["s_x"], sc["s_v"], sc["s_u"], sc["s_y"])
+    x = torch.from_numpy(case["xq"]).to(dev)
+    U = torch.empty(wb.wino_weights_bytes(desc), dtype=torch.uint8, device=dev)
+    ws = torch.empty(wb.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    wb.wino_transform_weights(desc, quant, torch.from_numpy(case["g"]).to(dev), U)
+    numel = case["ref"]["Yq"].size
+    buf = torch.full((numel + 16,), 99, dtype=torch.int8, device=dev)
+    for shift in (0, 4, 9):
+        base = (-buf.data_ptr()) % 16 + shift
+        y = buf[base:base + numel].view(case["ref"]["Yq"].shape)
+        assert y.data_ptr() % 16 == shift
+        buf.fill_(99)
+        wb.wino_conv2d_fwd_seq(desc, quant, x, U, y, ws, wb.WINO_SEQ_TROW)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), case["ref"]["Yq"]), shift
+        got = buf.cpu().numpy()
+        assert (got[:base] == 99).all() and (got[base + numel:] == 99).all(), shift
+
+
 def test_quantizer_factor_too_small_for_the_exact_scaling(oracle):
     """The matrix-core input transform divides the quantizer factor s_x / s_v by 4^s, exactly;
     a factor that underflows there makes its launcher decline, and the call must take the
