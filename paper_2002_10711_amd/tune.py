@@ -6,6 +6,9 @@ algorithm).
     python -m paper_2002_10711_amd.tune --sweep [--out profiles/dispatch_sweep.json]
         on the MI355X: times wino_conv2d_fwd_seq for every sequence that can run each grid
         point (HIP-graph replays, events on the launch stream) and stores all times
+    python -m paper_2002_10711_amd.tune --sweep --only trow [--m 6]
+        the same for the named sequences only (and one tile size only): their times replace
+        or join the ones the stored sweep holds for every grid point, the rest stays
     python -m paper_2002_10711_amd.tune --emit [--sweep-file profiles/dispatch_sweep.json]
         anywhere: writes paper_2002_10711_amd/csrc/dispatch_table.h from the stored times
         (rebuild the library afterwards)
@@ -47,17 +50,32 @@ def derived(pt):
     return dict(T=pt["N"] * th * th, Cp=-(-pt["C"] // 64) * 64, Kp=-(-pt["K"] // 64) * 64)
 
 
-def sweep(out_path, budget_ms):
+def sweep(out_path, budget_ms, only=None, only_m=None, base_path=None):
     import torch
     from paper_2002_10711_amd import binding as wb
     dev = torch.device("cuda:0")
     stream = torch.cuda.Stream()
     rng = np.random.default_rng(7)
     rows = []
+    old = {}
+    if only:
+        # (a partial sweep: start from the stored rows and time the named sequences again)
+        for r in json.load(open(base_path or out_path))["grid"]:
+            old[(r["m"], r["C"], r["K"], r["H"], r["N"])] = r
     for pt in grid():
         m, C, K, H, N = pt["m"], pt["C"], pt["K"], pt["H"], pt["N"]
+        key = (m, C, K, H, N)
+        if only and (key not in old or (only_m and m != only_m)):
+            if key in old:
+                rows.append(old[key])
+            continue
         BT, G, AT = wb.wino_cook_toom(m)
         desc = wb.Desc(N, C, K, H, H, 1, m, wb.WINO_I8, BT=BT, G=G, AT=AT)
+        if only and not any(wb.wino_fwd_sequence(desc, SEQ_IDS[nm]) == SEQ_IDS[nm] for nm in only):
+            r = dict(old[key])
+            r["times_us"] = {k: v for k, v in r["times_us"].items() if k not in only}
+            rows.append(r)
+            continue
         ws_bytes = wb.wino_workspace_bytes(desc)
         if ws_bytes > MAX_WORKSPACE:
             continue
@@ -70,9 +88,12 @@ def sweep(out_path, budget_ms):
         with torch.cuda.stream(stream):
             wb.wino_transform_weights(desc, quant, g, U, stream=stream)
         stream.synchronize()
-        times = {}
+        times = dict(old[key]["times_us"]) if only else {}
         for name, sid in SEQ_IDS.items():
+            if only and name not in only:
+                continue
             if wb.wino_fwd_sequence(desc, sid) != sid:
+                times.pop(name, None)
                 continue
 
             def fn():
@@ -136,9 +157,11 @@ def main():
     ap.add_argument("--out", default=SWEEP_FILE)
     ap.add_argument("--sweep-file", default=SWEEP_FILE)
     ap.add_argument("--budget-ms", type=float, default=12.0, help="timed GPU work per sequence and run")
+    ap.add_argument("--only", default="", help="comma-separated sequence names: time only these, keep the rest")
+    ap.add_argument("--m", type=int, default=0, help="with --only: grid points of this tile size only")
     a = ap.parse_args()
     if a.sweep:
-        sweep(a.out, a.budget_ms)
+        sweep(a.out, a.budget_ms, [x for x in a.only.split(",") if x] or None, a.m or None, a.sweep_file)
     if a.emit:
         open(TABLE_FILE, "w").write(table_text(json.load(open(a.sweep_file))))
         print("wrote", TABLE_FILE)
