@@ -7,15 +7,23 @@
 // i inner), each position's channel reduction is finished before the next one starts,
 // z[a] = fma(A^T[a][i], M[i][j], z[a]) in ascending i, then
 // Y[a][b] = fma(z[a], A^T[b][j], Y[a][b]) in ascending j -- the pinned order of the two-sided
-// transform.  A wavefront owns 16 tiles x 16 output channels (one MFMA result per position).
+// transform.
 //
 // What differs:
-//  * A workgroup is 2 x 2 wavefronts = 32 tiles x 32 output channels, and both operands go
-//    through LDS in stages of four 64-channel steps (4, 2 or 1 positions), two buffers, ONE
-//    barrier per stage instead of one per position: 16 bytes per thread and step, loaded a
-//    stage ahead into registers.  Every operand byte is fetched once per workgroup.
-//  * The MFMAs of the next position are issued before the chains of the current one, also
-//    across a stage's barrier, so the chains never wait for the matrix cores.
+//  * A workgroup is 32 tiles x 32 output channels, and both operands go through LDS in
+//    stages of four 64-channel steps (4, 2 or 1 positions), two buffers, ONE barrier per
+//    stage instead of one per position; every operand byte is fetched once per workgroup,
+//    16 bytes per thread and step, a stage ahead in registers.
+//  * Each 16 x 16 MFMA result is shared by TWO wavefronts: a lane of an MFMA result holds
+//    four output channels of a tile, and each wavefront transforms two of them (both issue
+//    the MFMA; it costs a fiftieth of the chains).  That halves the transform state per lane
+//    (84 floats), so four wavefronts fit a SIMD instead of two, and halves the time a
+//    wavefront lives: a grid that does not fill the chip evenly ends with a shorter tail.
+//    The second wavefront reads the rows of U in an order that puts its two channels where
+//    the first one's are, so both run the same code.
+//  * A position's operand reads are issued two positions ahead and its MFMAs one position
+//    ahead of the chains that consume them, also across a stage's barrier, so the chains
+//    wait neither for LDS nor for the matrix cores.
 //  * The 32 tiles are whole rows of tiles (R = 32 / TW rows; the rest of the 32 is idle):
 //    a row of tiles is M consecutive rows of an output plane, i.e. one run of consecutive
 //    bytes.  The codes are assembled in LDS and leave as 16-byte stores of those runs
@@ -48,7 +56,9 @@ struct TrowPlan {
 };
 
 // Six codes (low bytes of b0 .. b5) to LDS as a dword and a pair: tile columns start at
-// 6 tw, on a dword boundary for even tw and in mid-dword for odd tw.
+// 6 tw, on a dword boundary for even tw and in mid-dword for odd tw.  (Three pairs would
+// save the selects and measured 7 % slower on the whole kernel: what the LDS charges for
+// is the number of sub-dword writes.)
 __device__ __forceinline__ void lds_row6(char* row, bool odd, uint32_t b0, uint32_t b1, uint32_t b2,
                                          uint32_t b3, uint32_t b4, uint32_t b5) {
   const uint32_t lo4 = pack_codes(b0, b1, b2, b3);
@@ -59,8 +69,9 @@ __device__ __forceinline__ void lds_row6(char* row, bool odd, uint32_t b0, uint3
   *(uint16_t*)(row + (odd ? 0 : 4)) = (uint16_t)sv;
 }
 
+// (second launch bound: four wavefronts per SIMD, i.e. 128 registers)
 template <int M, int NCH, bool kSparse>
-__global__ __launch_bounds__(256, 2) void gemm_out_trow_kernel(
+__global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
     Geom g, MatAT at, const int8_t* __restrict__ V, const int8_t* __restrict__ U,
     int8_t* __restrict__ y, PosScale w, float r_m, float r_y, float qmax, int plain, TrowPlan pl) {
   constexpr int n = M + 2;
@@ -80,109 +91,144 @@ __global__ __launch_bounds__(256, 2) void gemm_out_trow_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int tb2 = wave & 1, kb2 = wave >> 1;     // which 16 tiles, which 16 output channels
+  // which 16 tiles, which 16 output channels, which two of a lane's four channels
+  const int tb2 = wave & 1, kb2 = (wave >> 1) & 1, hf = wave >> 2;
   const int t0 = tbi * pl.R * g.TW;              // first tile of the block
 
-  // ---- loader side: wavefronts 0, 1 fetch V, wavefronts 2, 3 fetch U ----
+  // ---- loader side: of every four wavefronts, two fetch V and two fetch U; wavefronts
+  // 0 .. 3 take steps 0 and 2 of a stage, wavefronts 4 .. 7 steps 1 and 3 ----
   // Step block in LDS: [32 tile rows x 64 bytes of V][2 x 1 KB of U in operand order].  The
   // 16-byte pieces of a row of V are stored at piece ^ (row / 4 % 4): the operand reads
   // (16 consecutive rows, one piece index) then touch every bank group once.
-  const bool ldv = wave < 2;
+  const int wl = wave & 3, sp = wave >> 2;
+  const bool ldv = wl < 2;
   const char* const lbase = ldv ? (const char*)V : (const char*)U;
   const size_t pstep = ldv ? (size_t)g.Tp * g.Cp : (size_t)(g.Kp >> 4) * NCH * 1024;
   const uint32_t cstep = ldv ? 64u : 1024u;
   uint32_t loff, ldst;
   {
-    const int e = (wave & 1) * 64 + lane;        // piece of the wavefront pair's 2 KB
+    const int e = (wl & 1) * 64 + lane;          // piece of the wavefront pair's 2 KB
     const int row = e >> 2, piece = e & 3;
     int tr = t0 + row;
     tr = tr < g.Tp ? tr : g.Tp - 1;              // (idle rows past the end: any valid row)
     const uint32_t voff = (uint32_t)tr * (uint32_t)g.Cp + (uint32_t)piece * 16u;
     const uint32_t vdst = (uint32_t)row * 64u + (uint32_t)(piece ^ ((row >> 2) & 3)) * 16u;
-    const uint32_t uoff = (uint32_t)((kbi * 2 + (wave & 1)) * NCH) * 1024u + (uint32_t)lane * 16u;
+    const uint32_t uoff = (uint32_t)((kbi * 2 + (wl & 1)) * NCH) * 1024u + (uint32_t)lane * 16u;
     const uint32_t udst = 2048u + (uint32_t)e * 16u;
     loff = ldv ? voff : uoff;
-    ldst = ldv ? vdst : udst;
+    ldst = (ldv ? vdst : udst) + (uint32_t)sp * kStepBytes;
   }
-  v4u R[4];
-  // the four steps of stage sc of column jj into registers
+  v4u R[2];
+  // this wavefront's two steps of stage sc of column jj into registers
   auto load_stage = [&](int sc, int jj) {
 #pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      const int i = sc * G + st / NCH, ch = st % NCH;
+    for (int h = 0; h < 2; ++h) {
+      // step st = 2 h + sp of the stage: position st / NCH, channel step st % NCH (uniform)
+      const int st = 2 * h + sp;
+      const int i = sc * G + (NCH == 4 ? 0 : NCH == 2 ? h : st);
+      const int ch = NCH == 1 ? 0 : NCH == 2 ? sp : st;
       size_t off = (size_t)(i * n + jj) * pstep + (size_t)ch * cstep;
       asm volatile("" : "+s"(off));
-      R[st] = *(const v4u*)(lbase + off + loff);
+      R[h] = *(const v4u*)(lbase + off + loff);
     }
   };
   auto write_stage = [&](int buf) {
 #pragma unroll
-    for (int st = 0; st < 4; ++st) *(v4u*)(lds + buf * kStageBytes + st * kStepBytes + ldst) = R[st];
+    for (int h = 0; h < 2; ++h) *(v4u*)(lds + buf * kStageBytes + 2 * h * kStepBytes + ldst) = R[h];
   };
 
   // ---- multiplying side ----
   const int vrow = tb2 * 16 + r;
   const uint32_t vrd = (uint32_t)vrow * 64u + (uint32_t)(grp ^ ((vrow >> 2) & 3)) * 16u;
-  const uint32_t urd = 2048u + (uint32_t)kb2 * 1024u + (uint32_t)lane * 16u;
-  // the accumulators of position q of the stage in buffer buf
-  auto mfma_pos = [&](int buf, int q) {
-    v4i acc = v4i{0, 0, 0, 0};
+  // (wavefronts with hf = 1 take row r ^ 2 of U as row r of the MFMA: the lane's components
+  // 0 and 1 of the result are then the channels the others find in components 2 and 3)
+  const uint32_t urd = 2048u + (uint32_t)kb2 * 1024u + (uint32_t)(grp * 16 + (r ^ (hf << 1))) * 16u;
+  // The operands of position q of the stage in buffer buf, and their product.  The reads of
+  // a position are issued two positions before its accumulators are needed and its MFMAs
+  // one position before: a wavefront that has its SIMD to itself (a small layer, the tail
+  // of a grid) then waits for neither.
+  struct Ops {
+    v4i u[NCH], v[NCH];
+  };
+  auto read_ops = [&](Ops& o, int buf, int q) {
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
       const char* sb = lds + buf * kStageBytes + (q * NCH + ch) * kStepBytes;
-      const v4i u = *(const v4i*)(sb + urd);
-      const v4i v = *(const v4i*)(sb + vrd);
-      acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(u, v, acc, 0, 0, 0);
+      o.u[ch] = *(const v4i*)(sb + urd);
+      o.v[ch] = *(const v4i*)(sb + vrd);
     }
+  };
+  auto mfma_ops = [&](const Ops& o) {
+    v4i acc = v4i{0, 0, 0, 0};
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch)
+      acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(o.u[ch], o.v[ch], acc, 0, 0, 0);
     return acc;
   };
+  // The operands of position i2 (0 .. 2 n - 1: positions past n - 1 belong to the next
+  // column) of column j.  A position that opens a stage first publishes it: the stage waits
+  // in R; it goes into the buffer that held the stage before the current one (everybody
+  // passed the current stage's barrier after their last read of it), the stage after it
+  // into R, then the barrier.  Past the last stage the same is done with clamped addresses
+  // and nobody uses the result: the loop body stays one straight line (a branch here lets
+  // the compiler sink the chains behind both stages of a column).
+  Ops ops;
+  auto fetch_ops = [&](int i2, int j) {
+    const int ii = i2 % n, jj = j + i2 / n;
+    const int sc = ii / G, q = ii % G;
+    if (q == 0) {
+      write_stage(sc & 1);
+      const int jn = jj + (sc + 1) / SC;
+      load_stage((sc + 1) % SC, jn < n ? jn : n - 1);
+      __syncthreads();
+    }
+    read_ops(ops, sc & 1, q);
+  };
 
-  // A lane owns, for tile vrow of the block, the output channels kb2*16 + grp*4 + rr.
-  float z[M][4], Y[M][M][4];
+  // A lane owns, for tile vrow of the block, the output channels kb2*16 + grp*4 + 2 hf + rr.
+  float z[M][2], Y[M][M][2];
 #pragma unroll
   for (int a = 0; a < M; ++a)
 #pragma unroll
     for (int b = 0; b < M; ++b)
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) Y[a][b][rr] = 0.0f;
+      for (int rr = 0; rr < 2; ++rr) Y[a][b][rr] = 0.0f;
 
   load_stage(0, 0);
   write_stage(0);
-  load_stage(1, 0);
+  load_stage(1 % SC, 1 / SC);
   __syncthreads();
-  v4i acc_nx = mfma_pos(0, 0);
+  // (with 256 channels the operands of a position are 32 registers: there the reads stay
+  // next to their MFMAs, one position ahead)
+  constexpr bool kDeep = NCH <= 2;
+  read_ops(ops, 0, 0);
+  v4i acc_cur = mfma_ops(ops);
+  if (kDeep) fetch_ops(1, 0);
 
   // (one copy of the loop without per-position factors and Hadamard-stage quantizer, one
   // with: multiplying by a factor of 1 is exact, but costs an instruction per accumulator)
   auto columns = [&](auto plain_tag) {
     constexpr bool kPlain = decltype(plain_tag)::value;
     const bool mq = r_m > 0.0f;
-#pragma unroll 1
-    for (int j = 0; j < n; ++j) {
+    // One column of positions.  The first and the last column are compiled with j known:
+    // A^T has a single nonzero entry there (Cook-Toom pattern), and 5 of the 6 row updates
+    // of the second product drop out; the columns between run as a loop.
+    auto column = [&](auto jt) {
+      constexpr bool kStaticJ = !std::is_same<decltype(jt), int>::value;
+      const int j = jt;
 #pragma unroll
       for (int i = 0; i < n; ++i) {
-        const int q = i % G, sc = i / G;
-        const v4i acc = acc_nx;
-        if (q == G - 1) {
-          // The next position opens a stage.  Its operands wait in R: into the buffer that
-          // held the stage before this one (everybody passed this stage's barrier after
-          // their last read of it), then the stage after it into R, then the barrier that
-          // publishes the buffer.  Past the last stage the same is done with clamped
-          // addresses and nobody reads the result: the loop body stays one straight line
-          // (a branch here lets the compiler sink the chains behind both stages of a column).
-          // The scheduler may not move a stage's memory operations up past the chains of the
-          // positions before it: those chains are what the loads' latency hides behind.
-          __builtin_amdgcn_sched_barrier(0);
-          write_stage((sc + 1) & 1);
-          const int jn = j + (sc + 2) / SC;
-          load_stage((sc + 2) % SC, jn < n ? jn : n - 1);
-          __syncthreads();
-        }
-        acc_nx = i < n - 1 ? mfma_pos(((i + 1) / G) & 1, (i + 1) % G) : mfma_pos(0, 0);
+        // position i + 1 to the matrix cores, the operands of position i + 2 on their way,
+        // then the chains of position i.  (The scheduler may not move anything across the
+        // end of this step: it would undo the distance between issue and use.)
+        if (!kDeep) fetch_ops(i + 1, j);
+        const v4i acc_nx = mfma_ops(ops);
+        if (kDeep) fetch_ops(i + 2, j);
+        const v4i acc = acc_cur;
         float wp = 1.0f;
         if constexpr (!kPlain) wp = w.r[i * n + j];
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
+        for (int rr = 0; rr < 2; ++rr) {
           float f = (float)acc[rr];
           if constexpr (!kPlain) {
             f *= wp;
@@ -195,16 +241,25 @@ __global__ __launch_bounds__(256, 2) void gemm_out_trow_kernel(
             if (at_nonzero<M, kSparse>(a, i)) z[a][rr] = __builtin_fmaf(at.v[a * n + i], f, z[a][rr]);
           }
         }
+        acc_cur = acc_nx;
+        __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int b = 0; b < M; ++b) {
+        if constexpr (kStaticJ) {
+          if (!at_nonzero<M, kSparse>(b, decltype(jt)::value)) continue;
+        }
         const float abj = at.v[b * n + j];
 #pragma unroll
         for (int a = 0; a < M; ++a)
 #pragma unroll
-          for (int rr = 0; rr < 4; ++rr) Y[a][b][rr] = __builtin_fmaf(z[a][rr], abj, Y[a][b][rr]);
+          for (int rr = 0; rr < 2; ++rr) Y[a][b][rr] = __builtin_fmaf(z[a][rr], abj, Y[a][b][rr]);
       }
-    }
+    };
+    column(std::integral_constant<int, 0>{});
+#pragma unroll 1
+    for (int j = 1; j < n - 1; ++j) column(j);
+    column(std::integral_constant<int, n - 1>{});
   };
   if (plain) columns(std::true_type{});
   else columns(std::false_type{});
@@ -217,8 +272,9 @@ __global__ __launch_bounds__(256, 2) void gemm_out_trow_kernel(
     if ((int)trow < pl.R) {
       const float lo = kMagic - qmax, hi = kMagic + qmax;
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        char* tp = lds + (kb2 * 16 + grp * 4 + rr) * pl.plane_b + (int)trow * M * pl.pitch + tw * M;
+      for (int rr = 0; rr < 2; ++rr) {
+        char* tp = lds + (kb2 * 16 + grp * 4 + 2 * hf + rr) * pl.plane_b +
+                   (int)trow * M * pl.pitch + tw * M;
 #pragma unroll
         for (int a = 0; a < M; ++a) {
           uint32_t b[M];
@@ -252,14 +308,14 @@ __global__ __launch_bounds__(256, 2) void gemm_out_trow_kernel(
     }
     const size_t plane = (size_t)g.Ho * g.Wo;
 #pragma unroll 1
-    for (int kk = wave; kk < 32; kk += 4) {
+    for (int kk = wave; kk < 32; kk += 8) {
       const int k = kbi * 32 + kk;
       if (k >= g.K) break;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         if (ok[h]) {
-          const uint32_t* sp = (const uint32_t*)(lds + kk * pl.plane_b + src[h]);
-          *(v4u*)(y + dst[h] + (size_t)k * plane) = v4u{sp[0], sp[1], sp[2], sp[3]};
+          const uint32_t* sp4 = (const uint32_t*)(lds + kk * pl.plane_b + src[h]);
+          *(v4u*)(y + dst[h] + (size_t)k * plane) = v4u{sp4[0], sp4[1], sp4[2], sp4[3]};
         }
       }
     }
@@ -304,7 +360,7 @@ hipError_t go(const Geom& g, const MatAT& at, const void* V, const void* U, void
   for (int p = 0; p < 64; ++p) one.r[p] = 1.0f;
   const int plain = !w && !(r_m > 0.0f);
   const unsigned grid = (unsigned)((pl.nTB + 7) / 8 * 8 * pl.nKB);
-  gemm_out_trow_kernel<6, NCH, kSparse><<<dim3(grid), 256, 0, s>>>(
+  gemm_out_trow_kernel<6, NCH, kSparse><<<dim3(grid), 512, 0, s>>>(
       g, at, (const int8_t*)V, (const int8_t*)U, (int8_t*)y, w ? *w : one, r_m, r_y, qmax, plain, pl);
   return hipGetLastError();
 }
