@@ -69,14 +69,23 @@ __device__ __forceinline__ void lds_row6(char* row, bool odd, uint32_t b0, uint3
   *(uint16_t*)(row + (odd ? 0 : 4)) = (uint16_t)sv;
 }
 
-// (second launch bound: four wavefronts per SIMD, i.e. 128 registers)
-template <int M, int NCH, bool kSparse>
-__global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
+// kHalf: two wavefronts per MFMA result (eight wavefronts, two channels per lane, four
+// wavefronts per SIMD at 128 registers) -- for 64 input channels; with longer reductions the
+// operand registers of a position no longer fit next to that, and a wavefront keeps all
+// four channels of its lanes (four wavefronts, two per SIMD).
+// (second launch bound: wavefronts per SIMD)
+template <int M, int NCH, bool kSparse, bool kHalf>
+__global__ __launch_bounds__(kHalf ? 512 : 256, kHalf ? 4 : 2) void gemm_out_trow_kernel(
     Geom g, MatAT at, const int8_t* __restrict__ V, const int8_t* __restrict__ U,
     int8_t* __restrict__ y, PosScale w, float r_m, float r_y, float qmax, int plain, TrowPlan pl) {
   constexpr int n = M + 2;
   constexpr int G = 4 / NCH;                     // positions per stage
   constexpr int SC = n / G;                      // stages per column
+  constexpr int RR = kHalf ? 2 : 4;              // output channels per lane
+  constexpr int LPS = kHalf ? 2 : 4;             // 16-byte loads per thread and stage
+  constexpr int NW = kHalf ? 8 : 4;              // wavefronts
+  // operand reads two positions ahead of their use (else next to their MFMAs, one ahead)
+  constexpr bool kDeep = kHalf && NCH <= 2;
   static_assert(M == 6, "the row stores are written for six codes per tile row");
   static_assert(NCH == 1 || NCH == 2 || NCH == 4, "a stage is four steps");
   static_assert(n % G == 0 && SC % 2 == 0, "a column is a whole, even number of stages");
@@ -92,7 +101,7 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // which 16 tiles, which 16 output channels, which two of a lane's four channels
-  const int tb2 = wave & 1, kb2 = (wave >> 1) & 1, hf = wave >> 2;
+  const int tb2 = wave & 1, kb2 = (wave >> 1) & 1, hf = kHalf ? wave >> 2 : 0;
   const int t0 = tbi * pl.R * g.TW;              // first tile of the block
 
   // ---- loader side: of every four wavefronts, two fetch V and two fetch U; wavefronts
@@ -100,7 +109,7 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
   // Step block in LDS: [32 tile rows x 64 bytes of V][2 x 1 KB of U in operand order].  The
   // 16-byte pieces of a row of V are stored at piece ^ (row / 4 % 4): the operand reads
   // (16 consecutive rows, one piece index) then touch every bank group once.
-  const int wl = wave & 3, sp = wave >> 2;
+  const int wl = wave & 3, sp = kHalf ? wave >> 2 : 0;
   const bool ldv = wl < 2;
   const char* const lbase = ldv ? (const char*)V : (const char*)U;
   const size_t pstep = ldv ? (size_t)g.Tp * g.Cp : (size_t)(g.Kp >> 4) * NCH * 1024;
@@ -118,15 +127,14 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
     loff = ldv ? voff : uoff;
     ldst = (ldv ? vdst : udst) + (uint32_t)sp * kStepBytes;
   }
-  v4u R[2];
-  // this wavefront's two steps of stage sc of column jj into registers
+  v4u R[LPS];
+  // this wavefront's steps of stage sc of column jj into registers
   auto load_stage = [&](int sc, int jj) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      // step st = 2 h + sp of the stage: position st / NCH, channel step st % NCH (uniform)
-      const int st = 2 * h + sp;
-      const int i = sc * G + (NCH == 4 ? 0 : NCH == 2 ? h : st);
-      const int ch = NCH == 1 ? 0 : NCH == 2 ? sp : st;
+    for (int h = 0; h < LPS; ++h) {
+      // step st of the stage: position st / NCH, channel step st % NCH (uniform)
+      const int st = kHalf ? 2 * h + sp : h;
+      const int i = sc * G + st / NCH, ch = st % NCH;
       size_t off = (size_t)(i * n + jj) * pstep + (size_t)ch * cstep;
       asm volatile("" : "+s"(off));
       R[h] = *(const v4u*)(lbase + off + loff);
@@ -134,7 +142,8 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
   };
   auto write_stage = [&](int buf) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) *(v4u*)(lds + buf * kStageBytes + 2 * h * kStepBytes + ldst) = R[h];
+    for (int h = 0; h < LPS; ++h)
+      *(v4u*)(lds + buf * kStageBytes + (kHalf ? 2 : 1) * h * kStepBytes + ldst) = R[h];
   };
 
   // ---- multiplying side ----
@@ -177,6 +186,9 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
     const int ii = i2 % n, jj = j + i2 / n;
     const int sc = ii / G, q = ii % G;
     if (q == 0) {
+      // (nothing of the stage may move up past the chains before it: they are what the
+      // loads' latency hides behind)
+      if (!kDeep) __builtin_amdgcn_sched_barrier(0);
       write_stage(sc & 1);
       const int jn = jj + (sc + 1) / SC;
       load_stage((sc + 1) % SC, jn < n ? jn : n - 1);
@@ -186,21 +198,18 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
   };
 
   // A lane owns, for tile vrow of the block, the output channels kb2*16 + grp*4 + 2 hf + rr.
-  float z[M][2], Y[M][M][2];
+  float z[M][RR], Y[M][M][RR];
 #pragma unroll
   for (int a = 0; a < M; ++a)
 #pragma unroll
     for (int b = 0; b < M; ++b)
 #pragma unroll
-      for (int rr = 0; rr < 2; ++rr) Y[a][b][rr] = 0.0f;
+      for (int rr = 0; rr < RR; ++rr) Y[a][b][rr] = 0.0f;
 
   load_stage(0, 0);
   write_stage(0);
   load_stage(1 % SC, 1 / SC);
   __syncthreads();
-  // (with 256 channels the operands of a position are 32 registers: there the reads stay
-  // next to their MFMAs, one position ahead)
-  constexpr bool kDeep = NCH <= 2;
   read_ops(ops, 0, 0);
   v4i acc_cur = mfma_ops(ops);
   if (kDeep) fetch_ops(1, 0);
@@ -228,7 +237,7 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
         float wp = 1.0f;
         if constexpr (!kPlain) wp = w.r[i * n + j];
 #pragma unroll
-        for (int rr = 0; rr < 2; ++rr) {
+        for (int rr = 0; rr < RR; ++rr) {
           float f = (float)acc[rr];
           if constexpr (!kPlain) {
             f *= wp;
@@ -242,7 +251,7 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
           }
         }
         acc_cur = acc_nx;
-        __builtin_amdgcn_sched_barrier(0);
+        if (kDeep) __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int b = 0; b < M; ++b) {
@@ -253,7 +262,7 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
 #pragma unroll
         for (int a = 0; a < M; ++a)
 #pragma unroll
-          for (int rr = 0; rr < 2; ++rr) Y[a][b][rr] = __builtin_fmaf(z[a][rr], abj, Y[a][b][rr]);
+          for (int rr = 0; rr < RR; ++rr) Y[a][b][rr] = __builtin_fmaf(z[a][rr], abj, Y[a][b][rr]);
       }
     };
     column(std::integral_constant<int, 0>{});
@@ -272,7 +281,7 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
     if ((int)trow < pl.R) {
       const float lo = kMagic - qmax, hi = kMagic + qmax;
 #pragma unroll
-      for (int rr = 0; rr < 2; ++rr) {
+      for (int rr = 0; rr < RR; ++rr) {
         char* tp = lds + (kb2 * 16 + grp * 4 + 2 * hf + rr) * pl.plane_b +
                    (int)trow * M * pl.pitch + tw * M;
 #pragma unroll
@@ -308,7 +317,7 @@ __global__ __launch_bounds__(512, 4) void gemm_out_trow_kernel(
     }
     const size_t plane = (size_t)g.Ho * g.Wo;
 #pragma unroll 1
-    for (int kk = wave; kk < 32; kk += 8) {
+    for (int kk = wave; kk < 32; kk += NW) {
       const int k = kbi * 32 + kk;
       if (k >= g.K) break;
 #pragma unroll
@@ -352,7 +361,7 @@ bool make_plan(const Geom& g, TrowPlan* pl) {
   return true;
 }
 
-template <int NCH, bool kSparse>
+template <int NCH, bool kSparse, bool kHalf>
 hipError_t go(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
               const PosScale* w, float r_m, float r_y, float qmax, const TrowPlan& pl,
               hipStream_t s) {
@@ -360,7 +369,7 @@ hipError_t go(const Geom& g, const MatAT& at, const void* V, const void* U, void
   for (int p = 0; p < 64; ++p) one.r[p] = 1.0f;
   const int plain = !w && !(r_m > 0.0f);
   const unsigned grid = (unsigned)((pl.nTB + 7) / 8 * 8 * pl.nKB);
-  gemm_out_trow_kernel<6, NCH, kSparse><<<dim3(grid), 512, 0, s>>>(
+  gemm_out_trow_kernel<6, NCH, kSparse, kHalf><<<dim3(grid), kHalf ? 512 : 256, 0, s>>>(
       g, at, (const int8_t*)V, (const int8_t*)U, (int8_t*)y, w ? *w : one, r_m, r_y, qmax, plain, pl);
   return hipGetLastError();
 }
@@ -378,13 +387,13 @@ hipError_t launch_gemm_out_trow(const Geom& g, const MatAT& at, const void* V, c
   TrowPlan pl;
   if (!make_plan(g, &pl) || ((uintptr_t)y & 15) != 0) return hipErrorInvalidValue;
   const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<6>::at);
-#define WINO_TROW_GO(NCHV)                                                               \
-  (sparse ? go<NCHV, true>(g, at, V, U, y, w_pos, r_m, r_y, qmax, pl, s)                 \
-          : go<NCHV, false>(g, at, V, U, y, w_pos, r_m, r_y, qmax, pl, s))
+#define WINO_TROW_GO(NCHV, HALF)                                                         \
+  (sparse ? go<NCHV, true, HALF>(g, at, V, U, y, w_pos, r_m, r_y, qmax, pl, s)           \
+          : go<NCHV, false, HALF>(g, at, V, U, y, w_pos, r_m, r_y, qmax, pl, s))
   switch (g.Cp) {
-    case 64: return WINO_TROW_GO(1);
-    case 128: return WINO_TROW_GO(2);
-    default: return WINO_TROW_GO(4);
+    case 64: return WINO_TROW_GO(1, true);
+    case 128: return WINO_TROW_GO(2, false);   // (the other form measures 9 % slower here)
+    default: return WINO_TROW_GO(4, false);
   }
 #undef WINO_TROW_GO
 }
