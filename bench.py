@@ -43,9 +43,29 @@ def pick_workload(name):
               workloads.config2("i8w16") + workloads.config3() +
               workloads.config4() + workloads.config5()):
         table[L.name] = L
+    if name.startswith("layer:"):
+        # an ad-hoc int8 layer "layer:N,C,K,H,m" (square image, stride 1, pad 1): for scaling
+        # studies of one kernel beyond the sizes the named configurations hold
+        try:
+            N, C, K, H, m = (int(v) for v in name[6:].split(","))
+        except ValueError:
+            raise SystemExit("ad-hoc layers are written layer:N,C,K,H,m")
+        return workloads.Layer("layer_%d_%dto%d_s%d_F%d" % (N, C, K, H, m), N, C, K, H, H, m=m, seed=7)
     if name not in table:
-        raise SystemExit("unknown workload %r; choose from %s" % (name, sorted(table)))
+        raise SystemExit("unknown workload %r; choose from %s (or layer:N,C,K,H,m)" % (name, sorted(table)))
     return table[name]
+
+
+def bench_scales(name):
+    """Quantizer scales of a named workload (calibrated by the oracle, stored by
+    tests/golden/make_bench_scales.py).  Ad-hoc layers get fixed, uncalibrated ones: the
+    kernels' run time does not depend on the values."""
+    table = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))
+    if name in table:
+        return table[name]
+    if name.startswith("layer_"):
+        return {"s_x": 0.03, "s_w": 0.002, "s_v": 0.25, "s_u": 0.01, "s_y": 0.1}
+    raise SystemExit("no stored scales for workload %r" % name)
 
 
 ALU_PEAK_TFLOPS = 78.6         # fp32 vector without packed ops: 256 CU x 64 lanes x 2 x 2.4 GHz
@@ -163,8 +183,7 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
     i8 = L.dtype == "i8"
     wide = L.dtype in WIDE
     qm = workloads.STAGE_QMAX.get(L.dtype)
-    scales = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[
-        L.name.replace("_f32", "_i8").replace("_bf16", "_i8")]
+    scales = bench_scales(L.name.replace("_f32", "_i8").replace("_bf16", "_i8"))
     X, g = workloads.make_inputs(L)
     BT, G, AT = wb.wino_cook_toom(L.m)
     if L.flex_sigma > 0:
@@ -349,7 +368,7 @@ def ref_only_leg(L, steps, warmup):
     import torch
     from paper_2002_10711_amd import binding as wb
     dev = torch.device("cuda:0")
-    sc = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[L.name]
+    sc = bench_scales(L.name)
     X, g = workloads.make_inputs(L)
     xh = workloads.input_codes(X, sc["s_x"])
     wq = workloads.input_codes(g, sc["s_w"])
@@ -482,7 +501,7 @@ def cpu_leg(L):
     n_omp, n_one = min(L.N, 16), min(L.N, 2)
     runs = {}
     if L.dtype not in FLOAT:
-        sc = json.load(open(os.path.join(ROOT, "tests", "golden", "bench_scales.json")))[L.name]
+        sc = bench_scales(L.name)
         qm = workloads.STAGE_QMAX[L.dtype]
         xq = oracle.quantize_tensor(X[:n_omp], sc["s_x"], qm["x"])
         main_fn = lambda n: (lambda: oracle.winograd_q(xq[:n], g, BT, G, AT, sc, pad=L.pad, qmax=qm))

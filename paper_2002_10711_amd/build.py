@@ -32,6 +32,7 @@ FLAGS = [
 EXTRA_FLAGS = {
     "fused_fwd_exact_m2.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "fused_fwd_exact_m4.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "fused_fwd_exact_m6.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "fused_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "wide16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "gemm_out_col.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],

@@ -685,12 +685,19 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
 // Grid: x = blocks of RB tile rows, y = blocks of TWB tiles along a row, z = blocks of 64
 // input channels.  Tiles of a workgroup that lie beyond the image are not written; the
 // rows of V between T and Tp are never read by anything that reaches the output.
-template <int M, int kLoad, int kTWB>
+// kTPW: tiles per wavefront, 4 or 3.  The workgroup shapes are powers of two, so a row of 3
+// or 6 tiles (F(6x6,3x3) on 16 or 32 pixels) leaves 4 of the 16 tile slots empty, and with
+// four slots per wavefront the empty ones cost as much as the others.  With kTPW = 3 the at
+// most 12 real tiles of the workgroup are dealt out three to a wavefront (the host checks
+// that one workgroup spans the tile row and that RB * TW <= 12); V in LDS keeps the slot
+// order, so the stores do not change.
+template <int M, int kLoad, int kTWB, int kTPW = 4>
 __global__ __launch_bounds__(256) void input_transform_exact_kernel(
     const int8_t* __restrict__ x, int8_t* __restrict__ V, PosScale rvs, float qmax, Geom g,
     XPlan pl, typename KronArg<M>::type kw) {
   constexpr int n = M + 2, P = n * n;
-  constexpr int NBLK = (P + 15) / 16, NSTEP = 16 * NBLK;
+  constexpr int NBLK = (P + 15) / 16, NSTEP = 4 * kTPW * NBLK;
+  static_assert(kTPW == 4 || (kTPW == 3 && M == 6), "three tiles per wavefront: F(6x6,3x3) only");
   constexpr int ND = M == 6 ? 2 : 1;                   // int8 digits of W
   static_assert(M != 6 || NBLK == 4, "one block of positions per wavefront builds W");
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
@@ -746,14 +753,22 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
   }
 
   // window operands: see fused_fwd_exact_kernel
-  v4i Aw[16];
+  v4i Aw[4 * kTPW];
+  int slot[kTPW];                                      // tile slot (rs * TWB + twl) of the wave's tiles
   {
     const int j0 = 2 * grp < n ? 2 * grp : 0, j1 = 2 * grp + 1 < n ? 2 * grp + 1 : 0;
     const uint32_t* lane_x = Xs + r * plane + j0 * WQ;
     const int dj = (j1 - j0) * WQ;
 #pragma unroll
-    for (int t4 = 0; t4 < 4; ++t4) {
-      const int tl = wave * 4 + t4;
+    for (int t4 = 0; t4 < kTPW; ++t4) {
+      int tl = wave * kTPW + t4;
+      if constexpr (kTPW != 4) {
+        // real tile number v -> slot; v / TW by comparison (at most four tile rows)
+        const int v = tl;
+        const int vr = (v >= g.TW) + (v >= 2 * g.TW) + (v >= 3 * g.TW);
+        tl = vr < RB ? vr * TWB + (v - vr * g.TW) : RB * TWB - 1;   // (past the last: an empty slot)
+      }
+      slot[t4] = tl;
       int rs = kTWB ? tl / (kTWB ? kTWB : 1) : (int)fast_div(tl, pl.inv_twb);
       const int twl = tl - rs * TWB;
       rs = rs < RB ? rs : 0;
@@ -840,7 +855,7 @@ __global__ __launch_bounds__(256) void input_transform_exact_kernel(
                                        quantize_bits((float)cur[1], rq[blk], lo, hi),
                                        quantize_bits((float)cur[2], rq[blk], lo, hi),
                                        quantize_bits((float)cur[3], rq[blk], lo, hi));
-    const int tl = wave * 4 + (gi >> 2);
+    const int tl = slot[gi >> 2];
     if (blk * 16 + r < P) lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
     cur = nxt;
     curh = nxth;
@@ -1041,9 +1056,15 @@ hipError_t launch_input_m(const Geom& g, const MatBT& bt, const void* x, void* V
   typename KronArg<M>::type karg;
   if constexpr (M == 6) karg = xl.kb;
   else karg = xl.kw;
+  // (F(6x6,3x3): at most 12 real tiles in a workgroup that spans the tile row: three tiles
+  // per wavefront instead of four slots)
+  const bool three = M == 6 && xl.ntwb == 1 && xl.pl.RB * g.TW <= 12 && g.TW < TWB;
 #define WINO_LAUNCH_IN(LOAD, TWBC)                                                         \
   do {                                                                                     \
     auto kern = input_transform_exact_kernel<M, LOAD, TWBC>;                               \
+    if constexpr (M == 6 && TWBC >= 4) {                                                   \
+      if (three) kern = input_transform_exact_kernel<M, LOAD, TWBC, 3>;                    \
+    }                                                                                      \
     if (xl.lds_bytes > 65536) {                                                            \
       const hipError_t e = hipFuncSetAttribute(                                            \
           (const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)xl.lds_bytes); \
