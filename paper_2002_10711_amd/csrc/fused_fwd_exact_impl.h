@@ -110,7 +110,6 @@ struct XPlan {
   uint32_t inv_strip, inv_wq;   // numerators < 256
   uint32_t inv_th;           // numerators < N * TH
   int w_off;                 // F(6x6,3x3): dword offset in LDS of the digits of W
-  int iters;                 // persistent one-kernel forward: blocks of tile rows per workgroup
 };
 
 // kLoad: 0 = byte loads (W < 4), 1 = one dword per lane at any byte address,
@@ -122,12 +121,6 @@ struct XPlan {
 // kTWB > 0: the workgroup shape (TWB, RB) = (kTWB, 16 / kTWB) is a compile-time constant,
 // which folds the index arithmetic; 0 = taken from the plan at run time.
 // kThreads: threads of the workgroup (256, or 512 for the 128-output-channel kernel).
-template <bool kFirst, class A, class B>
-__device__ __forceinline__ auto& pick_ref(A& a, B& b) {
-  if constexpr (kFirst) return a;
-  else return b;
-}
-
 template <int M, int kLoad, int kTWB, int kThreads = 256>
 __device__ __forceinline__ void stage_planes(const Geom& g, const XPlan& pl,
                                              const int8_t* __restrict__ x, uint32_t* Xs, int c0,
@@ -303,13 +296,7 @@ __device__ __forceinline__ v4i merge_tail_groups(const v4i& t0, const v4i& t1, c
 // first per-position MFMA (zero "C" operand) instead of occupying 144 registers during
 // staging and transform.
 // kFast: whole tiles, K % 4 == 0 (see output_stage.h).
-// kPersist (one block of input channels, all P weight operands fit the registers next to
-// everything else: F(2x2,3x3)): a workgroup takes pl.iters consecutive blocks of tile rows
-// and loads its 64 output channels of U ONCE, before the first, instead of streaming all of
-// U[.][64][64] through its compute unit's L1 for every 16 tiles.  Worth 3 % on layers with
-// many tiles (64 -> 64 at 32 x 32, batch 256: 31.6 -> 30.7 us): the kernel is bound by its
-// vector-ALU instructions (counters: 74 % of the wavefronts' lifetime), not by that stream.
-template <int M, bool kSparseA, int kLoad, bool kOneBlock, int kTWB, bool kFast, bool kPersist = false>
+template <int M, bool kSparseA, int kLoad, bool kOneBlock, int kTWB, bool kFast>
 __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     const int8_t* __restrict__ x, const int8_t* __restrict__ U, void* __restrict__ y, int pos,
     float r_vs, float r_m, float r_y, float qmax, Geom g, XPlan pl, MatAT at, KronW kw,
@@ -324,10 +311,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
   uint32_t* Vl = lds;                                  // aliases Xs
   const int RB = kTWB ? 16 / (kTWB ? kTWB : 1) : pl.RB, TWB = kTWB ? kTWB : pl.TWB;
   const int WQ = xs_row_dw(M, TWB), plane = xs_plane_dw(M, TWB);
-  static_assert(!kPersist || kOneBlock, "the persistent form keeps one block of U");
-  const int iters = kPersist ? pl.iters : 1;
-  int r0 = blockIdx.x * iters * RB;
-  const int tw0 = blockIdx.y * TWB, kb = blockIdx.z * 64;
+  const int r0 = blockIdx.x * RB, tw0 = blockIdx.y * TWB, kb = blockIdx.z * 64;
   const int R = g.N * g.TH;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, grp = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps tile math scalar
@@ -355,18 +339,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     for (int blk = 0; blk < NBLK; ++blk) rq[blk] = pp.rv[blk * 16 + r < P ? blk * 16 + r : P - 1];
   }
 
-  v4i bufU_keep[kPersist ? P : 1];
-  if constexpr (kPersist) {
-#pragma unroll
-    for (int p = 0; p < P; ++p) bufU_keep[p] = *(const v4i*)(U + (uoff + (uint32_t)p * up));
-  }
   const int nblk = kOneBlock ? 1 : (g.Cp >> 6);
-#pragma unroll 1
-  for (int it = 0; it < iters; ++it, r0 += RB) {
-  if (kPersist && it) {
-    if (r0 >= R) break;                                // (uniform)
-    __syncthreads();                                   // the block before has been multiplied
-  }
   for (int cb = 0; cb < nblk; ++cb) {
     if (cb) __syncthreads();                           // previous block's Vl fully consumed
     WINO_TS(1);
@@ -415,8 +388,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     // otherwise stall the MFMA loop.
     constexpr int kDepth = P;
     const uint32_t ub = uoff + (uint32_t)cb * 1024u;
-    v4i bufU_ring[kPersist ? 1 : kDepth];
-    auto& bufU = pick_ref<kPersist>(bufU_keep, bufU_ring);
+    v4i bufU[kDepth];
     __syncthreads();                                   // Xs is free: Vl may overwrite it
     WINO_TS(3);
 
@@ -438,7 +410,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 #pragma unroll
       for (int st = 0; st < 32; ++st) {
         const int gi = st >> 1, blk = st & 1, q = gi >> 2;
-        if constexpr (!kPersist) bufU[st] = *(const v4i*)(U + (ub + (uint32_t)st * up));
+        bufU[st] = *(const v4i*)(U + (ub + (uint32_t)st * up));
         v4i nxt = cur;
         if (st + 1 < 32)
           nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) >> 1], Wb[(st + 1) & 1], zero4, 0, 0, 0);
@@ -453,7 +425,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
         lane_v[blk * 16 * kVlPitch + tl * 16 + (gi & 3) * 4] = packed;
         cur = nxt;
         if ((st & 7) == 7) {
-          if constexpr (!kPersist) bufU[32 + q] = *(const v4i*)(U + (ub + (uint32_t)(32 + q) * up));
+          bufU[32 + q] = *(const v4i*)(U + (ub + (uint32_t)(32 + q) * up));
           const v4i m4 = merge_tail_groups(tail[0], tail[1], tail[2], tail[3]);
           lane_v2[tl * 16] = pack_codes(quantize_bits((float)m4[0], rq2, lo, hi),
                                         quantize_bits((float)m4[1], rq2, lo, hi),
@@ -465,8 +437,7 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
 #pragma unroll
     for (int st = 0; st < NSTEP; ++st) {
       const int gi = st / NBLK, blk = st % NBLK;
-      if constexpr (!kPersist)
-        if (st < kDepth) bufU[st] = *(const v4i*)(U + (ub + (uint32_t)st * up));
+      if (st < kDepth) bufU[st] = *(const v4i*)(U + (ub + (uint32_t)st * up));
       v4i nxt = cur;
       if (st + 1 < NSTEP)   // every lane takes part in the MFMA; only the stores are predicated
         nxt = __builtin_amdgcn_mfma_i32_16x16x64_i8(Aw[(st + 1) / NBLK], Wb[(st + 1) % NBLK],
@@ -505,7 +476,6 @@ __global__ __launch_bounds__(256) void fused_fwd_exact_kernel(
     const int img = (int)fast_div(rr_, pl.inv_th), th = rr_ - img * g.TH;
     finish_lane_any<M, kSparseA, kFast>(g, at, acc, y, img, th, tw, k0, r_m, r_y, qmax, pos != 0,
                                         pp.w);
-  }
   }
   WINO_TS(6);
 }
@@ -1005,7 +975,6 @@ bool make_xlaunch(const Geom& g, const MatBT& bt, const void* x, float r_v, XLau
   xl->lds_bytes = xs_b > vl_b ? xs_b : vl_b;
   XPlan& pl = xl->pl;
   pl.w_off = 0;
-  pl.iters = 1;
   if (M == 6) {
     // the digits of W behind the staging / V region: [4 blocks][2 digits][64 lanes] x 16 bytes
     xl->lds_bytes = (xl->lds_bytes + 15) / 16 * 16;
@@ -1115,15 +1084,6 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   }
   const int pos = w_pos != nullptr;
   dim3 grid((unsigned)xl.nrb, (unsigned)xl.ntwb, (unsigned)(g.Kp / 64));
-  // F(2x2,3x3), one block of input channels, more than two workgroups per compute unit:
-  // persistent workgroups, two per compute unit, that load their weights once
-  const long long wgs = (long long)xl.nrb * xl.ntwb * (g.Kp / 64);
-  const bool persist = M == 2 && g.Cp == 64 && wgs > 1024;
-  dim3 gridp = grid;
-  if (persist) {
-    xl.pl.iters = (int)((wgs + 511) / 512);
-    gridp.x = (unsigned)((xl.nrb + xl.pl.iters - 1) / xl.pl.iters);
-  }
   const XPlan& pl = xl.pl;
   const KronW& kw = xl.kw;
   const size_t lb = xl.lds_bytes;
@@ -1178,11 +1138,7 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   }
   if (sa && load >= 1) {
 #define WINO_LAUNCH_C1(LOAD, TWBC, FAST) \
-  do { if (persist) {                                                                      \
-         if constexpr (M == 2)                                                             \
-           fused_fwd_exact_kernel<M, true, LOAD, true, TWBC, FAST, true><<<gridp, 256, lb, s>>>( \
-               xi, Ui, y, pos, xl.r_vs, r_m, r_y, qmax, g, pl, at, kw, pp);                 \
-       } else if (one) WINO_LAUNCH_XK(true, LOAD, true, TWBC, FAST);  \
+  do { if (one) WINO_LAUNCH_XK(true, LOAD, true, TWBC, FAST);  \
        else WINO_LAUNCH_XK(true, LOAD, false, TWBC, FAST); } while (0)
 #define WINO_LAUNCH_C2(LOAD, TWBC) \
   do { if (fast) WINO_LAUNCH_C1(LOAD, TWBC, true); else WINO_LAUNCH_C1(LOAD, TWBC, false); } while (0)

@@ -381,20 +381,19 @@ def test_output_at_an_odd_address(oracle, flex):
         assert (edge[:shift] == 99).all() and (edge[shift + numel:] == 99).all()
 
 
-# the persistent one-kernel F(2x2,3x3) forward (more than 1024 workgroups of 16 tiles x 64
-# output channels): a last workgroup whose blocks of tile rows run past the end, and several
+# the one-kernel F(2x2,3x3) forward on grids of more than a thousand workgroups, with several
 # blocks of output channels; the F(6x6,3x3) input stage with three tiles per wavefront where
 # the tile rows leave tile slots of the workgroup empty (5 of 8, 11 of 16)
 EXTRA = [
-    Layer("persist_f2_ragged", 70, 64, 64, 32, 32, m=2, seed=195),
-    Layer("persist_f2_k200", 20, 40, 200, 32, 32, m=2, seed=196),
+    Layer("f2_1120_workgroups", 70, 64, 64, 32, 32, m=2, seed=195),
+    Layer("f2_k200_1280_workgroups", 20, 40, 200, 32, 32, m=2, seed=196),
     Layer("f6_tw5", 3, 64, 32, 20, 28, m=6, seed=197),
     Layer("f6_tw11", 1, 64, 32, 12, 64, m=6, seed=198),
 ]
 
 
 @pytest.mark.parametrize("layer", EXTRA, ids=lambda l: l.name)
-def test_persistent_forward_and_three_tile_input_stage(oracle, layer):
+def test_large_grids_and_three_tile_input_stage(oracle, layer):
     case = make_case(oracle, layer)
     _check_i8(case, run_gpu(case))
 
