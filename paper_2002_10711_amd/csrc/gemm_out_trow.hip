@@ -338,6 +338,9 @@ bool make_plan(const Geom& g, TrowPlan* pl) {
   const int M = 6;
   TrowPlan p;
   p.R = 32 / g.TW;
+  // (whole rows of tiles must fill at least three quarters of the 32 MFMA rows: 19 tiles per
+  // row -- 112 pixels -- would leave 13 idle, and the column-wise kernel is faster there)
+  if (p.R * g.TW < 24) return false;
   const long long rows_all = (long long)g.N * g.TH;
   p.rows_all = (int)rows_all;
   p.nTB = (int)((rows_all + p.R - 1) / p.R);

@@ -15,7 +15,7 @@ algorithm).
 
 Grid: m in {2, 4, 6}; C in {64, 128, 256, 512}; K in {64, 128, max(256, C)} (the three classes
 of output channels the dispatch distinguishes); square images of 4, 8, 16, 32, 56 pixels;
-batch 32 and 256.  Inputs are random codes: the kernels' run time does not depend on values.
+batch 32, 64, 128 and 256.  Inputs are random codes: the kernels' run time does not depend on values.
 """
 import argparse
 import json
@@ -36,7 +36,7 @@ def grid():
         for C in (64, 128, 256, 512):
             for K in (64, 128, max(256, C)):
                 for hw in (4, 8, 16, 32, 56):
-                    for N in (32, 256):
+                    for N in (32, 64, 128, 256):
                         yield dict(m=m, C=C, K=K, H=hw, N=N)
 
 
