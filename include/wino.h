@@ -193,7 +193,9 @@ int wino_fwd_num_kernels(const wino_desc* d);
 #define WINO_SEQ_LDS 4     /* input stage; GEMM + output transform, 32 x 64 workgroup tiles */
 #define WINO_SEQ_REGS 5    /* input stage; GEMM + output transform, accumulators in registers */
 #define WINO_SEQ_STAGED 6  /* input stage; GEMM writing M; output transform               */
-#define WINO_SEQ_TROW 7    /* input stage; GEMM + output transform on whole rows of tiles  */
+#define WINO_SEQ_TROW 7    /* input stage; GEMM + output transform on whole rows of tiles
+                            * (F(6x6,3x3); a y_dev that is not 16-byte aligned runs
+                            * WINO_SEQ_COL instead, named or not)                        */
 #define WINO_SEQ_COUNT 8
 /* seq = WINO_SEQ_AUTO: the sequence wino_conv2d_fwd takes for this problem; any other seq:
  * seq itself if that sequence can run the problem, else 0.  0 also for an invalid

@@ -70,9 +70,10 @@ __device__ __forceinline__ void lds_row6(char* row, bool odd, uint32_t b0, uint3
 }
 
 // kHalf: two wavefronts per MFMA result (eight wavefronts, two channels per lane, four
-// wavefronts per SIMD at 128 registers) -- for 64 input channels; with longer reductions the
-// operand registers of a position no longer fit next to that, and a wavefront keeps all
-// four channels of its lanes (four wavefronts, two per SIMD).
+// wavefronts per SIMD at 128 registers) -- for 64 input channels, and for 128 while the grid
+// gives a compute unit at most one workgroup; otherwise a wavefront keeps all four channels
+// of its lanes (four wavefronts, two per SIMD): with longer reductions the operand
+// registers of a position press on the 128, and at 256 channels they no longer fit.
 // (second launch bound: wavefronts per SIMD)
 template <int M, int NCH, bool kSparse, bool kHalf>
 __global__ __launch_bounds__(kHalf ? 512 : 256, kHalf ? 4 : 2) void gemm_out_trow_kernel(
@@ -206,19 +207,21 @@ __global__ __launch_bounds__(kHalf ? 512 : 256, kHalf ? 4 : 2) void gemm_out_tro
 #pragma unroll
       for (int rr = 0; rr < RR; ++rr) Y[a][b][rr] = 0.0f;
 
-  load_stage(0, 0);
-  write_stage(0);
-  load_stage(1 % SC, 1 / SC);
-  __syncthreads();
-  read_ops(ops, 0, 0);
-  v4i acc_cur = mfma_ops(ops);
-  if (kDeep) fetch_ops(1, 0);
-
   // (one copy of the loop without per-position factors and Hadamard-stage quantizer, one
   // with: multiplying by a factor of 1 is exact, but costs an instruction per accumulator)
   auto columns = [&](auto plain_tag) {
     constexpr bool kPlain = decltype(plain_tag)::value;
     const bool mq = r_m > 0.0f;
+    // (the first stage is loaded inside each copy: a value that lives across the branch
+    // between the copies is spilled at 128 registers, and a spill here is 64 lanes x 4 bytes
+    // per wavefront of memory traffic -- as much as the layer's output for a few registers)
+    load_stage(0, 0);
+    write_stage(0);
+    load_stage(1 % SC, 1 / SC);
+    __syncthreads();
+    read_ops(ops, 0, 0);
+    v4i acc_cur = mfma_ops(ops);
+    if (kDeep) fetch_ops(1, 0);
     // One column of positions.  The first and the last column are compiled with j known:
     // A^T has a single nonzero entry there (Cook-Toom pattern), and 5 of the 6 row updates
     // of the second product drop out; the columns between run as a loop.
@@ -275,14 +278,20 @@ __global__ __launch_bounds__(kHalf ? 512 : 256, kHalf ? 4 : 2) void gemm_out_tro
 
   // ---- output codes: to LDS as [channel of the block][row of tiles][M rows][pitch] ----
   __syncthreads();                               // every operand read is done: LDS is free
+  // (the lane's coordinates are derived again from the thread id, hidden from the
+  // optimiser: kept alive through the loop they would be spilled, see above)
+  int tid_e = threadIdx.x;
+  asm volatile("" : "+v"(tid_e));
+  const int lane_e = tid_e & 63, r_e = lane_e & 15, grp_e = lane_e >> 4;
+  const int vrow_e = tb2 * 16 + r_e;
   {
-    const uint32_t trow = fast_div((uint32_t)vrow, pl.inv_TW);
-    const int tw = vrow - (int)trow * g.TW;
+    const uint32_t trow = fast_div((uint32_t)vrow_e, pl.inv_TW);
+    const int tw = vrow_e - (int)trow * g.TW;
     if ((int)trow < pl.R) {
       const float lo = kMagic - qmax, hi = kMagic + qmax;
 #pragma unroll
       for (int rr = 0; rr < RR; ++rr) {
-        char* tp = lds + (kb2 * 16 + grp * 4 + 2 * hf + rr) * pl.plane_b +
+        char* tp = lds + (kb2 * 16 + grp_e * 4 + 2 * hf + rr) * pl.plane_b +
                    (int)trow * M * pl.pitch + tw * M;
 #pragma unroll
         for (int a = 0; a < M; ++a) {
@@ -304,7 +313,7 @@ __global__ __launch_bounds__(kHalf ? 512 : 256, kHalf ? 4 : 2) void gemm_out_tro
     bool ok[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const uint32_t s = (uint32_t)(lane + 64 * h);
+      const uint32_t s = (uint32_t)(lane_e + 64 * h);
       const uint32_t trow = fast_div(s, pl.inv_ppt);
       const uint32_t rem = s - trow * (uint32_t)pl.ppt;
       const uint32_t yr = fast_div(rem, pl.inv_ppr), x16 = rem - yr * (uint32_t)pl.ppr;
@@ -395,7 +404,11 @@ hipError_t launch_gemm_out_trow(const Geom& g, const MatAT& at, const void* V, c
           : go<NCHV, false, HALF>(g, at, V, U, y, w_pos, r_m, r_y, qmax, pl, s))
   switch (g.Cp) {
     case 64: return WINO_TROW_GO(1, true);
-    case 128: return WINO_TROW_GO(2, false);   // (the other form measures 9 % slower here)
+    case 128:
+      // (measured on 128 -> 128 at 16 x 16 and 32 x 32: with at most one workgroup per
+      // compute unit the eight-wavefront form is 2 us faster -- two wavefronts per SIMD
+      // instead of one --, with more the four-wavefront form is 1 us faster)
+      return pl.nTB * pl.nKB <= 256 ? WINO_TROW_GO(2, true) : WINO_TROW_GO(2, false);
     default: return WINO_TROW_GO(4, false);
   }
 #undef WINO_TROW_GO
