@@ -96,14 +96,21 @@ __global__ __launch_bounds__(256) void conv_implicit_i8_kernel(RefGeom g, Tiling
   const size_t wrow = (size_t)9 * g.Cp;
   const int nch = g.Cp >> 6;
   for (int ch = 0; ch < nch; ++ch) {
-    // this chunk's weight operands: issued first, they arrive during the staging
+    // this chunk's weight operands: the first kEarly taps are issued before the staging and
+    // arrive during it; the rest is issued right after it and arrives while the first taps
+    // are multiplied.  (All nine up front keep 72 registers alive through the staging, which
+    // holds the kernel with 128 output channels per workgroup to three wavefronts per SIMD;
+    // this way it fits four.)
+    constexpr int kEarly = KW == 2 ? 4 : 9;
     v4i b[9][KW];
-#pragma unroll
-    for (int tap = 0; tap < 9; ++tap)
+    auto load_b = [&](int tap) {
 #pragma unroll
       for (int j = 0; j < KW; ++j)
         b[tap][j] = *(const v4i*)(wp + (size_t)(k0 + 16 * j + r16) * wrow + (size_t)tap * g.Cp +
                                   ch * 64 + grp * 16);
+    };
+#pragma unroll
+    for (int tap = 0; tap < kEarly; ++tap) load_b(tap);
     if (ch) __syncthreads();                           // the previous chunk has been read
     // Transpose the chunk's patch into LDS.  A task: four channels x four input columns
     // of one patch row; 16 consecutive lanes take the 16 channel groups of one place.
@@ -191,6 +198,8 @@ __global__ __launch_bounds__(256) void conv_implicit_i8_kernel(RefGeom g, Tiling
       }
     }
     __syncthreads();
+#pragma unroll
+    for (int tap = kEarly; tap < 9; ++tap) load_b(tap);
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
       const int toff = ((tap / 3) * tl.PW + tap % 3) * kCS;
