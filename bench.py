@@ -363,6 +363,40 @@ def gpu_leg(L, steps, warmup, use_graph, cold=False):
                 BT=BT, AT=AT)
 
 
+def load_probe():
+    """Bytes per cycle and compute unit (at the 2.1 GHz the chip sustains, 256 compute units)
+    that the vector memory path delivers, per load form, wavefronts per workgroup and
+    footprint: 16 KB per workgroup stays in the L1, 64 KB in the XCD's L2 (16 MB in all), 256 KB
+    (64 MB in all) in neither."""
+    import torch
+    from paper_2002_10711_amd import binding as wb
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream()
+    wgs = 256
+    buf = torch.ones(wgs * (256 << 10), dtype=torch.uint8, device=dev)
+    out = torch.empty(wgs * 1024, dtype=torch.float32, device=dev)
+    names = {0: "16 B/lane", 1: "8 B/lane", 2: "4 B/lane", 3: "16 B/lane into LDS"}
+    rows = []
+    with torch.cuda.stream(stream):
+        for kb in (16, 64, 256):
+            for waves in (4, 8, 16):
+                for mode in (0, 1, 2, 3):
+                    if mode in (1, 2) and waves != 4:
+                        continue
+                    iters = 400
+                    wb.wino_debug_load_loop(mode, waves, wgs, kb << 10, 50, buf, out, stream=stream)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    nbytes = wb.wino_debug_load_loop(mode, waves, wgs, kb << 10, iters, buf, out, stream=stream)
+                    e1.record(stream)
+                    stream.synchronize()
+                    tbs = nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e12
+                    rows.append({"load": names[mode], "waves_per_workgroup": waves, "workgroups": wgs,
+                                 "footprint_kb_per_workgroup": kb, "TB_per_s": round(tbs, 2),
+                                 "bytes_per_clk_per_cu": round(tbs * 1e12 / 2.1e9 / 256, 1)})
+    print(json.dumps({"probe": "vector memory path (wino_debug_load_loop)", "rows": rows}))
+
+
 def ref_only_leg(L, steps, warmup):
     """ms per forward of the im2row baseline on a layer (stride 1 or 2), weights packed once."""
     import torch
@@ -552,6 +586,9 @@ def main():
     ap.add_argument("--flex", type=float, default=0.0, help="perturb the Cook-Toom matrices by "
                     "seeded N(0, FLEX) noise (dense 'learned' transforms, paper Sec. 3.2): a timing "
                     "option, the stored scales are not recalibrated")
+    ap.add_argument("--load-probe", action="store_true", help="only measure what the vector memory "
+                    "path of a compute unit delivers (wino_debug_load_loop) for footprints that fit "
+                    "the L1, the L2 and neither, and print the table as one JSON line")
     ap.add_argument("--cold", action="store_true", help="also time the forward with L2 and "
                     "Infinity Cache evicted before every call (a 1 GiB buffer is overwritten in "
                     "between) and measure the plain-copy HBM rate; adds cold_fwd_ms, "
@@ -565,6 +602,9 @@ def main():
         raise SystemExit("bench.py: this build runs on ONE GPU only (the path needs no exchange "
                          "step: tiles are independent, so more GPUs would each take a share of the batch); "
                          "got --gpus %d" % a.gpus)
+    if a.load_probe:
+        load_probe()
+        return
     if a.stack:
         print(json.dumps(stack_line(max(20, a.steps // 5), max(5, a.warmup // 5))))
         return

@@ -238,6 +238,20 @@ wino_status wino_debug_export(const wino_desc* d, int which, const void* src_dev
 wino_status wino_debug_mfma_loop(int dtype, int workgroups, int iters, float* out_dev,
                                  double* ops_per_launch, void* stream);
 
+/* Vector-memory-path probe (not the paper's): `workgroups` workgroups of `waves` (4, 8 or 16)
+ * wavefronts; every wavefront walks its own slice (workgroup_bytes / waves) of its
+ * workgroup's part of buf_dev round and round, eight loads in flight, `iters` rounds of
+ * eight loads.  mode 0: 16 bytes per lane into registers, 1: 8 bytes, 2: 4 bytes, 3: 16 bytes
+ * per lane straight into LDS.  A slice that fits the L1 measures the L1, a workgroup part
+ * that fits its XCD's share of the L2 the L2 -> L1 path, a larger one what lies behind.
+ *   buf_dev           in   DEVICE, workgroups * workgroup_bytes bytes (any contents)
+ *   out_dev           out  DEVICE, workgroups * waves * 64 floats (checksums, ignore)
+ *   bytes_per_launch  out  HOST, may be NULL: bytes one launch loads
+ * workgroup_bytes: a multiple of waves * 1024.  Time it with events on `stream`. */
+wino_status wino_debug_load_loop(int mode, int waves, int workgroups, size_t workgroup_bytes,
+                                 int iters, const void* buf_dev, float* out_dev,
+                                 double* bytes_per_launch, void* stream);
+
 /* Cook-Toom matrices for F(m,3) from m+1 distinct finite points (NULL = the
  * usual 0, 1, -1, 1/2, -1/2, 2, -2 prefix) plus the point at infinity
  * (Sec. 3.1).  HOST outputs: BT n*n, G n*3, AT m*n floats. */

@@ -21,7 +21,7 @@ EXPORTS = [
     "wino_status_string", "wino_weights_bytes", "wino_workspace_bytes",
     "wino_transform_weights", "wino_conv2d_fwd", "wino_conv2d_fwd_noalloc",
     "wino_conv2d_fwd_stages", "wino_fwd_num_kernels", "wino_fwd_sequence", "wino_conv2d_fwd_seq",
-    "wino_debug_export", "wino_debug_mfma_loop", "wino_cook_toom",
+    "wino_debug_export", "wino_debug_mfma_loop", "wino_debug_load_loop", "wino_cook_toom",
     "conv2d_ref_packed_weights_bytes", "conv2d_ref_workspace_bytes",
     "conv2d_ref_pack_weights", "conv2d_ref_gpu", "conv2d_ref_gpu_rows",
 ]
@@ -87,6 +87,9 @@ def lib():
         L.wino_debug_export.argtypes = [ctypes.POINTER(WinoDesc), ctypes.c_int, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_void_p]
         L.wino_debug_mfma_loop.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                           ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+        L.wino_debug_load_loop.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
+                                           ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
         L.wino_cook_toom.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_void_p]
@@ -239,6 +242,15 @@ def wino_debug_mfma_loop(dtype, workgroups, iters, out_dev, stream=None):
     _check(lib().wino_debug_mfma_loop(dtype, workgroups, iters, _ptr(out_dev), ctypes.byref(ops),
                                       _stream(stream)), "wino_debug_mfma_loop")
     return ops.value
+
+
+def wino_debug_load_loop(mode, waves, workgroups, workgroup_bytes, iters, buf_dev, out_dev, stream=None):
+    """Launches the vector-memory-path probe; returns the bytes one launch loads."""
+    nbytes = ctypes.c_double(0.0)
+    _check(lib().wino_debug_load_loop(mode, waves, workgroups, ctypes.c_size_t(workgroup_bytes), iters,
+                                      _ptr(buf_dev), _ptr(out_dev), ctypes.byref(nbytes),
+                                      _stream(stream)), "wino_debug_load_loop")
+    return nbytes.value
 
 
 def wino_cook_toom(m, points=None):

@@ -14,9 +14,10 @@
 // workgroup share the tiles.  V reaches them through LDS (loaded once per workgroup,
 // positions ahead in registers, two buffers, one barrier per position); U comes straight
 // from global memory in its blocked layout through a register ring.  What bounds such a
-// kernel is the number of wavefront loads the L1 has to process (about 44 cycles per
-// 16-byte-per-lane load), so every operand is fetched once per workgroup (V) or serves
-// kTW MFMAs (U).
+// kernel is the number of wavefront loads its compute unit has to take in (about 44 cycles
+// per 16-byte-per-lane load as measured in this kernel, first touches from beyond the L2
+// included; 15 - 19 from the L2 alone), so every operand is fetched once per workgroup (V)
+// or serves kTW MFMAs (U).
 #include <type_traits>
 
 #include "output_stage.h"

@@ -4,6 +4,8 @@
         per-kernel table of a ``--kernel-trace --stats`` run (calls, total, average us)
     python -m paper_2002_10711_amd.profsummary pmc    RESULTS.db [RESULTS.db ...]
         per-kernel averages of every counter of ``--pmc`` runs
+    python -m paper_2002_10711_amd.profsummary dispatches RESULTS.db [--match NAME]
+        the counters of a ``--pmc`` run dispatch by dispatch, in dispatch order
     python -m paper_2002_10711_amd.profsummary traffic --workload NAME --fetch FETCH.db
             --write WRITE.db [--out profiles/hbm_traffic.json]
         HBM bytes per launch of the workload's kernels from a FETCH_SIZE and a WRITE_SIZE run
@@ -63,6 +65,22 @@ def pmc_averages(db_path):
         a[0] += v
         a[1] += 1
     return {kc: (v / n, n) for kc, (v, n) in agg.items()}
+
+
+def dispatch_table(db_path, match):
+    """One row per dispatch, in dispatch order, of the kernels whose name contains `match`:
+    every collected counter summed over its hardware instances."""
+    cur = sqlite3.connect(db_path).cursor()
+    cols = [d[0] for d in cur.execute("select * from counters_collection limit 1").description]
+    ki, ci, vi, di = (cols.index(c) for c in ("kernel_name", "counter_name", "value", "dispatch_id"))
+    per = collections.OrderedDict()
+    for row in cur.execute("select * from counters_collection order by dispatch_id"):
+        if match in row[ki]:
+            key = (row[di], short(row[ki]), row[ci])
+            per[key] = per.get(key, 0.0) + row[vi]
+    lines = ["| dispatch | kernel | counter | value |", "|---|---|---|---|"]
+    lines += ["| %d | %s | %s | %.1f |" % (d, k, c, v) for (d, k, c), v in per.items()]
+    return "\n".join(lines)
 
 
 def pmc_table(db_paths):
@@ -135,6 +153,9 @@ def main():
     t.add_argument("db")
     p = sub.add_parser("pmc")
     p.add_argument("db", nargs="+")
+    dd = sub.add_parser("dispatches")
+    dd.add_argument("db")
+    dd.add_argument("--match", default="")
     h = sub.add_parser("traffic")
     h.add_argument("--workload", required=True)
     h.add_argument("--fetch", required=True)
@@ -145,6 +166,8 @@ def main():
         print(trace_table(a.db))
     elif a.cmd == "pmc":
         print(pmc_table(a.db))
+    elif a.cmd == "dispatches":
+        print(dispatch_table(a.db, a.match))
     else:
         print(traffic(a.workload, a.fetch, a.write, a.out))
 

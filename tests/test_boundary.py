@@ -157,6 +157,12 @@ def test_mfma_probe_argument_checks():
     assert L.wino_debug_mfma_loop(wb.WINO_I8, 0, 10, p, None, None) == -3           # bad shape
     assert L.wino_debug_mfma_loop(wb.WINO_I8, 8, 0, p, None, None) == -3
     assert L.wino_debug_mfma_loop(7, 8, 10, p, None, None) == -4                    # bad dtype
+    # the memory-path probe: pointers, then mode / wavefronts, then sizes
+    assert L.wino_debug_load_loop(0, 4, 8, 4096, 10, None, p, None, None) == -1
+    assert L.wino_debug_load_loop(4, 4, 8, 4096, 10, p, p, None, None) == -8
+    assert L.wino_debug_load_loop(0, 5, 8, 4096, 10, p, p, None, None) == -8
+    assert L.wino_debug_load_loop(0, 4, 8, 4000, 10, p, p, None, None) == -3          # not whole chunks
+    assert L.wino_debug_load_loop(0, 4, 0, 4096, 10, p, p, None, None) == -3
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -91,3 +91,18 @@ def test_mfma_probe_runs_and_counts_its_operations():
     torch.cuda.synchronize()
     assert ops == 2.0 * 16 * 16 * 4 * 8 * 10 * 4 * 64
     assert torch.isfinite(out).all()
+
+
+@pytest.mark.gpu
+def test_memory_path_probe_runs_and_counts_its_bytes():
+    import torch
+    from paper_2002_10711_amd import binding as wb
+    wgs, kb = 32, 64
+    buf = torch.ones(wgs * (kb << 10), dtype=torch.uint8, device="cuda:0")
+    out = torch.zeros(wgs * 1024, dtype=torch.float32, device="cuda:0")
+    for mode, bpl in ((0, 16), (1, 8), (2, 4), (3, 16)):
+        for waves in (4, 8, 16):
+            nbytes = wb.wino_debug_load_loop(mode, waves, wgs, kb << 10, 5, buf, out)
+            torch.cuda.synchronize()
+            assert nbytes == wgs * waves * 64 * bpl * 8 * 5
+    assert torch.isfinite(out).all()
