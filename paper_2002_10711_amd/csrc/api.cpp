@@ -563,7 +563,8 @@ static wino_status make_ref_geom(int N, int C, int K, int H, int W, int stride, 
 size_t conv2d_ref_packed_weights_bytes(int C, int K, int dtype) {
   if (C < 1 || K < 1 || (dtype != WINO_F32 && dtype != WINO_I8)) return 0;
   const int i8 = dtype == WINO_I8;
-  return align256((size_t)round_up(K, 64) * 9 * round_up(C, i8 ? 64 : 16) * (i8 ? 1 : 4));
+  // (int8: the tap-major rows and the copy in operand order, one after the other)
+  return align256((size_t)round_up(K, 64) * 9 * round_up(C, i8 ? 64 : 16) * (i8 ? 2 : 4));
 }
 
 size_t conv2d_ref_workspace_bytes(int N, int C, int K, int H, int W, int stride, int pad,

@@ -11,8 +11,12 @@
 // tap (r, s) of the 3x3 filter then reads, for every output pixel, the 64 bytes at a fixed
 // offset from the pixel's corner: one v_mfma_i32_16x16x64_i8 operand per 16 pixels.
 // A wavefront owns 16*KW output channels and takes its weight operands straight from the
-// packed weights (rows of 9*Cp bytes, tap-major, the layout ref_pack_weights_kernel
-// writes), 16 bytes per lane.
+// packed weights' second copy (1 KB blocks in operand order, [k/16][c/64][tap], written by
+// ref_pack_weights_operand_kernel): one contiguous kilobyte per load.  (From the tap-major
+// rows a load touched 16 half cache lines: 256 -> 256 channels at 8 x 8, batch 256, took
+// 29.7 us instead of 20.8.)
+#include <type_traits>
+
 #include "fastdiv.h"
 #include "transform_math.h"
 
@@ -56,13 +60,16 @@ __device__ __forceinline__ PixelAt pixel_at(const Tiling& tl, int p) {
   return a;
 }
 
-template <int KW>
+// (kLd: how the patch is gathered, see below; a template parameter so that every form gets
+// its own register allocation -- as a run-time switch the widest form cost the others a
+// wavefront per SIMD)
+template <int KW, int kLd>
 __global__ __launch_bounds__(256) void conv_implicit_i8_kernel(RefGeom g, Tiling tl,
                                                                const int8_t* __restrict__ x,
                                                                const int8_t* __restrict__ wp,
                                                                int8_t* __restrict__ y, float r_y,
-                                                               float qmax, int fast_ld,
-                                                               int fast_st) {
+                                                               float qmax, int fast_st) {
+  constexpr int fast_ld = kLd;
   extern __shared__ __attribute__((aligned(16))) unsigned char Xs[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, grp = lane >> 4;
   int bx = blockIdx.x;
@@ -93,8 +100,16 @@ __global__ __launch_bounds__(256) void conv_implicit_i8_kernel(RefGeom g, Tiling
 #pragma unroll
     for (int j = 0; j < KW; ++j) acc[mt][j] = v4i{0, 0, 0, 0};
 
-  const size_t wrow = (size_t)9 * g.Cp;
+  const int8_t* wo = wp + ref_operand_weights_offset(g.Cp, g.Kp);
   const int nch = g.Cp >> 6;
+  if constexpr (fast_ld == 3) {
+    // the whole-plane form below writes the pixels inside the image only: the zero border of
+    // the patch is written once, here
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    const int nbytes = tl.NI * tl.IR * tl.PW * kCS;               // a multiple of 16
+    for (int i = tid * 16; i < nbytes; i += 256 * 16) *(v4u*)(Xs + i) = v4u{0u, 0u, 0u, 0u};
+    __syncthreads();
+  }
   for (int ch = 0; ch < nch; ++ch) {
     // this chunk's weight operands: the first kEarly taps are issued before the staging and
     // arrive during it; the rest is issued right after it and arrives while the first taps
@@ -106,8 +121,8 @@ __global__ __launch_bounds__(256) void conv_implicit_i8_kernel(RefGeom g, Tiling
     auto load_b = [&](int tap) {
 #pragma unroll
       for (int j = 0; j < KW; ++j)
-        b[tap][j] = *(const v4i*)(wp + (size_t)(k0 + 16 * j + r16) * wrow + (size_t)tap * g.Cp +
-                                  ch * 64 + grp * 16);
+        b[tap][j] = *(const v4i*)(wo + (((size_t)((k0 >> 4) + j) * nch + ch) * 9 + tap) * 1024 +
+                                  lane * 16);
     };
 #pragma unroll
     for (int tap = 0; tap < kEarly; ++tap) load_b(tap);
@@ -117,7 +132,45 @@ __global__ __launch_bounds__(256) void conv_implicit_i8_kernel(RefGeom g, Tiling
     // (fast_ld == 2: four channels x SIXTEEN columns per task, one 16-byte load per channel
     // row -- the 4-byte loads of the other form fetch a 32-byte sector each for four bytes,
     // which made the gather, not the matrix cores, the bound of this kernel)
-    if (fast_ld == 2) {
+    if constexpr (fast_ld == 3) {
+      // Whole images of 4 or 8 columns: a task is four channels x 16 consecutive bytes of
+      // their planes (two or four image rows), so a lane's load is 16 bytes of one cache line
+      // and 16 lanes cover a whole 8 x 8 plane -- with 4-byte loads along the rows every lane
+      // touched a cache line of its own for four bytes, and the L1's one line per clock, not
+      // the matrix cores, set the pace of these layers.
+      typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+      const int ppp = (int)plane >> 4;                              // 16-byte pieces per plane
+      const uint32_t inv_ppp = make_inv((uint32_t)ppp);
+      const int wsh = g.W == 8 ? 3 : 2;
+      const int ntasks3 = tl.NI * ppp * 16;
+      for (int task = tid; task < ntasks3; task += 256) {
+        const int cg = task & 15, v = task >> 4;
+        const int il = (int)fast_div((uint32_t)v, inv_ppp), q = v - il * ppp;
+        const int img = ig * tl.NI + il, c0 = ch * 64 + 4 * cg;
+        const uint32_t pbase = ((uint32_t)img * g.C + c0) * plane + 16 * q;
+        v4u d4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool ok = img < g.N && c0 + j < g.C;
+          const v4u t = *(const v4u*)(x + (ok ? pbase + j * plane : 0u));
+          d4[j] = ok ? t : v4u{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int sq = 0; sq < 4; ++sq) {
+          uint32_t d[4], e[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) d[j] = d4[j][sq];
+          transpose4x4(d, e);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int l = 16 * q + 4 * sq + i;
+            const int hr = (l >> wsh) - h0, col = (l & (g.W - 1)) - w0;
+            if (hr >= 0 && hr < tl.IR && col >= 0 && col < tl.PW)
+              *(uint32_t*)(Xs + ((il * tl.IR + hr) * tl.PW + col) * kCS + 4 * cg) = e[i];
+          }
+        }
+      }
+    } else if constexpr (fast_ld == 2) {
       typedef uint32_t v4u __attribute__((ext_vector_type(4)));
       const int qlo16 = w0 < 0 ? -1 : w0 / 16;
       const int NQ16 = (w0 + tl.PW - 1) / 16 - qlo16 + 1;
@@ -282,18 +335,30 @@ hipError_t launch_conv_implicit(const RefGeom& g, const void* x, const void* wp,
   const size_t lds = (size_t)t.NI * t.IR * t.PW * kCS;
   // dword loads along the image rows / dword stores of four pixels: every row start and
   // every group of four must be 4-byte aligned
-  const int fast_ld = (((uintptr_t)x & 15) == 0 && g.W % 16 == 0)  ? 2
+  // whole images per workgroup, 4 or 8 columns, planes that are multiples of 16 bytes
+  const bool planes = ((uintptr_t)x & 15) == 0 && (g.W == 4 || g.W == 8) && (g.H * g.W) % 16 == 0 &&
+                      t.CB == g.Wo && t.RB == g.Ho;
+  const int fast_ld = planes                                        ? 3
+                      : (((uintptr_t)x & 15) == 0 && g.W % 16 == 0) ? 2
                       : (((uintptr_t)x & 3) == 0 && g.W % 4 == 0) ? 1
                                                                    : 0;
   const int fast_st = ((uintptr_t)y & 3) == 0 && g.Wo % 4 == 0 && t.CB % 4 == 0;
   const bool two = g.Kp % 128 == 0;
   dim3 grid((unsigned)(t.nCB * t.nRB * t.nIG), (unsigned)(g.Kp / (two ? 128 : 64)));
-  if (two)
-    conv_implicit_i8_kernel<2><<<grid, 256, lds, s>>>(g, t, (const int8_t*)x, (const int8_t*)wp,
-                                                      (int8_t*)y, r_y, qmax, fast_ld, fast_st);
-  else
-    conv_implicit_i8_kernel<1><<<grid, 256, lds, s>>>(g, t, (const int8_t*)x, (const int8_t*)wp,
-                                                      (int8_t*)y, r_y, qmax, fast_ld, fast_st);
+  auto go = [&](auto kw, auto ld) {
+    conv_implicit_i8_kernel<decltype(kw)::value, decltype(ld)::value><<<grid, 256, lds, s>>>(
+        g, t, (const int8_t*)x, (const int8_t*)wp, (int8_t*)y, r_y, qmax, fast_st);
+  };
+  auto with_ld = [&](auto kw) {
+    switch (fast_ld) {
+      case 3: go(kw, std::integral_constant<int, 3>{}); break;
+      case 2: go(kw, std::integral_constant<int, 2>{}); break;
+      case 1: go(kw, std::integral_constant<int, 1>{}); break;
+      default: go(kw, std::integral_constant<int, 0>{}); break;
+    }
+  };
+  if (two) with_ld(std::integral_constant<int, 2>{});
+  else with_ld(std::integral_constant<int, 1>{});
   return hipGetLastError();
 }
 

@@ -22,6 +22,28 @@ __global__ __launch_bounds__(256) void ref_pack_weights_kernel(const T* __restri
   wp[i] = v;
 }
 
+// The same int8 weights once more in the order the one-kernel form reads them: 1 KB blocks,
+// one per (16 output channels, 64 input channels, tap), [k/16][c/64][tap]; inside a block
+// lane (c % 64 / 16) * 16 + k % 16 owns the 16 bytes c % 16 = 0..15 -- the B operand of
+// v_mfma_i32_16x16x64_i8, so that a wavefront's load is one contiguous kilobyte (rows of
+// 9*Cp bytes made it 16 half cache lines).
+__global__ __launch_bounds__(256) void ref_pack_weights_operand_kernel(const int8_t* __restrict__ w,
+                                                                       int8_t* __restrict__ wo,
+                                                                       int C, int K, int Cp,
+                                                                       int Kp) {
+  const long long total = (long long)Kp * 9 * Cp;
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int nch = Cp >> 6;
+  const int byte = (int)(i & 15), lane = (int)((i >> 4) & 63);
+  const long long blk = i >> 10;
+  const int tap = (int)(blk % 9), ch = (int)((blk / 9) % nch), kb = (int)(blk / (9LL * nch));
+  const int k = kb * 16 + (lane & 15), c = ch * 64 + (lane >> 4) * 16 + byte;
+  int8_t v = 0;
+  if (k < K && c < C) v = w[((size_t)k * C + c) * 9 + tap];
+  wo[i] = v;
+}
+
 // rows[t][rs*Cp + c] <- x[img][c][ho*stride + r - pad][wo*stride + s - pad].
 // VEC channels per thread (4 int8 packed into a dword, or 1 float).
 template <typename T, int VEC>
@@ -170,9 +192,11 @@ unsigned blocks_for(long long items) { return (unsigned)((items + 255) / 256); }
 hipError_t launch_ref_pack_weights(int C, int K, int Cp, int Kp, int i8, const void* w, void* wp,
                                    hipStream_t s) {
   const unsigned nb = blocks_for((long long)Kp * 9 * Cp);
-  if (i8)
+  if (i8) {
     ref_pack_weights_kernel<int8_t><<<nb, 256, 0, s>>>((const int8_t*)w, (int8_t*)wp, C, K, Cp, Kp);
-  else
+    ref_pack_weights_operand_kernel<<<nb, 256, 0, s>>>(
+        (const int8_t*)w, (int8_t*)wp + ref_operand_weights_offset(Cp, Kp), C, K, Cp, Kp);
+  } else
     ref_pack_weights_kernel<float><<<nb, 256, 0, s>>>((const float*)w, (float*)wp, C, K, Cp, Kp);
   return hipGetLastError();
 }

@@ -194,6 +194,9 @@ hipError_t launch_w16_export(const Geom& g, int which, const void* src, void* ou
 struct RefGeom {
   int N, C, K, H, W, stride, pad, Ho, Wo, T, Tp, Cp, Kp, i8;
 };
+// Packed weights: rows of 9*Cp values per output channel (tap-major); for int8 a second copy
+// in MFMA operand order follows at this byte offset (a multiple of 256).
+__host__ __device__ inline size_t ref_operand_weights_offset(int Cp, int Kp) { return (size_t)Kp * 9 * Cp; }
 hipError_t launch_ref_pack_weights(int C, int K, int Cp, int Kp, int i8, const void* w, void* wp,
                                    hipStream_t s);
 hipError_t launch_im2row(const RefGeom& g, const void* x, void* rows, hipStream_t s);

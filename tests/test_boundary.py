@@ -118,7 +118,8 @@ def test_ref_conv_error_codes_without_gpu(L):
     assert f(nbytes=10) == -6
     assert wb.conv2d_ref_workspace_bytes(1, 8, 8, 8, 8, 1, 1, wb.WINO_I8) == 64 * 9 * 64 + 64 * 64 * 4
     assert wb.conv2d_ref_workspace_bytes(1, 8, 8, 8, 8, 2, 1, wb.WINO_F32) == 64 * 9 * 16 * 4 + 64 * 64 * 4
-    assert wb.conv2d_ref_packed_weights_bytes(8, 8, wb.WINO_I8) == 64 * 9 * 64
+    # int8: the tap-major rows and the copy in MFMA operand order
+    assert wb.conv2d_ref_packed_weights_bytes(8, 8, wb.WINO_I8) == 2 * 64 * 9 * 64
     assert wb.conv2d_ref_packed_weights_bytes(0, 8, wb.WINO_I8) == 0
     assert L.conv2d_ref_pack_weights(8, 8, wb.WINO_I8, None, 0x1000, None) == -1
     assert L.conv2d_ref_pack_weights(8, 8, 9, 0x1000, 0x1000, None) == -4

@@ -24,6 +24,12 @@ CASES = [
     # one output pixel per image
     Layer("r10_1x1", 70, 9, 12, 3, 3, stride=1, pad=0, seed=210),
     Layer("r11_30", 2, 16, 64, 30, 30, stride=1, seed=211),
+    # whole images of 4 or 8 columns (gathered plane by plane): one image per workgroup, no
+    # padding with an odd row count of pieces, 48 pixels per image, stride 2 on 4 columns
+    Layer("r12_8x8", 3, 70, 64, 8, 8, stride=1, seed=212),
+    Layer("r13_6x8_pad0", 6, 64, 128, 6, 8, stride=1, pad=0, seed=213),
+    Layer("r14_12x4", 3, 130, 64, 12, 4, stride=1, seed=214),
+    Layer("r15_8x4_s2", 9, 64, 192, 8, 4, stride=2, seed=215),
 ]
 ENTRY = ["conv2d_ref_gpu", "conv2d_ref_gpu_rows"]
 
