@@ -461,7 +461,11 @@ def stack_line(steps, warmup):
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "cfg5 stack: 16 layers, N=256, 64/128/256/512 channels at 32/16/8/4, "
                                "per-layer m from the seed", "launch": "hip-graph replay per layer"},
-        "im2row_stack_ms": t_ref, "speedup_vs_im2row": t_ref / t_wino, "layers": rows,
+        "im2row_stack_ms": t_ref, "speedup_vs_im2row": t_ref / t_wino,
+        # the faster of the two per layer: what a latency-aware choice of the algorithm per
+        # layer (the paper's search, Sec. 4) would run on this machine
+        "best_per_layer_ms": sum(min(r["fwd_us"], r["im2row_us"]) for r in rows) * 1e-3,
+        "layers": rows,
     }
 
 

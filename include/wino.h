@@ -271,7 +271,10 @@ size_t conv2d_ref_packed_weights_bytes(int C, int K, int dtype);
 size_t conv2d_ref_workspace_bytes(int N, int C, int K, int H, int W, int stride, int pad,
                                   int dtype);
 /*   w_dev   in  DEVICE [K][C][3][3], int8 codes or float
- *   wp_dev  out DEVICE packed weights                                         */
+ *   wp_dev  out DEVICE packed weights, conv2d_ref_packed_weights_bytes bytes, aligned to
+ *           256: one row of 9*Cp values per output channel, tap-major, zero padded; for
+ *           int8 the same weights follow once more in matrix-core operand order (what
+ *           the one-kernel form reads)                                             */
 wino_status conv2d_ref_pack_weights(int C, int K, int dtype, const void* w_dev,
                                     void* wp_dev, void* stream);
 wino_status conv2d_ref_gpu(int N, int C, int K, int H, int W, int stride, int pad,
