@@ -168,7 +168,7 @@ hipError_t launch_m(const Geom& g, const MatBT& bt, const MatAT& at, const int8_
                     const int8_t* U, void* y, float r_v, float r_m, float r_y, float qmax,
                     const PosScale* rv_pos, const PosScale* w_pos, hipStream_t s) {
   const bool sb = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt);
-  const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool sa = sparse_at<M>(at.v);
 #define WINO_ARGS g, bt, at, x, U, y, r_v, r_m, r_y, qmax, rv_pos, w_pos, s
   if (sb && sa) return launch_k<M, true, true>(WINO_ARGS);
   if (sb) return launch_k<M, true, false>(WINO_ARGS);

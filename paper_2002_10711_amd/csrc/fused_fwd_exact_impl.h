@@ -1088,7 +1088,7 @@ hipError_t launch_exact_m(const Geom& g, const MatBT& bt, const MatAT& at, const
   const KronW& kw = xl.kw;
   const size_t lb = xl.lds_bytes;
   const int TWB = pl.TWB, load = xl.load;
-  const bool sa = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool sa = sparse_at<M>(at.v);
   const int8_t* xi = (const int8_t*)x;
   const int8_t* Ui = (const int8_t*)U;
   const bool one = g.Cp == 64;

@@ -478,7 +478,7 @@ hipError_t launch_m_bf16(const Geom& g, const MatBT& bt, const MatAT& at, const 
   if (!make_fplan(g, &pl, &lb, &nrb, &ntwb)) return hipErrorInvalidValue;
   dim3 grid((unsigned)nrb, (unsigned)ntwb, (unsigned)(g.Kp / 64));
   const bool sparse = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt) &&
-                      fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+                      sparse_at<M>(at.v);
   const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && ((uintptr_t)y & 15) == 0;
 #define WINO_LAUNCH_BF(SP, FA, IT) \
   return launch_k<M, SP, FA, IT, true>(g, pl, lb, grid, bt, at, x, U, y, s)
@@ -502,7 +502,7 @@ hipError_t launch_m(const Geom& g, const MatBT& bt, const MatAT& at, const float
   if (!make_fplan(g, &pl, &lb, &nrb, &ntwb)) return hipErrorInvalidValue;
   dim3 grid((unsigned)nrb, (unsigned)ntwb, (unsigned)(g.Kp / 64));
   const bool sparse = fits_mask(bt.v, g.n * g.n, CookToomMask<M>::bt) &&
-                      fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+                      sparse_at<M>(at.v);
   const bool fast = g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0 && ((uintptr_t)y & 15) == 0;
   // The common case (Cook-Toom pattern, whole tiles) gets the staging loop sized to the
   // shape, in steps of 4 elements per thread; everything else the full 32.

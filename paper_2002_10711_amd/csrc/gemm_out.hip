@@ -119,7 +119,7 @@ hipError_t launch_m(const Geom& g, const MatAT& at, const void* V, const void* U
       (size_t)g.Kp * g.Cp * esz >= 0xffffffffull)
     return hipErrorInvalidValue;
   dim3 grid(g.Tp / 16, g.Kp / 64);
-  const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool sparse = sparse_at<M>(at.v);
   if (I8 && r_m > 0.0f) {
     if (sparse)
       gemm_out_kernel<M, I8, true, I8><<<grid, 256, 0, s>>>(g, at, V, U, y, r_m, r_y, qmax);

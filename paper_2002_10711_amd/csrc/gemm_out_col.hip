@@ -163,9 +163,7 @@ __global__ __launch_bounds__(256, kTwoWG ? 2 : 1) void gemm_out_col_kernel(Geom 
             if constexpr (kMQ) f = quantize_f(f, r_m, qmax);
 #pragma unroll
             for (int a = 0; a < M; ++a) {
-              if (i == 0) z[tk][a][rr] = 0.0f;
-              if (at_nonzero<M, kSparse>(a, i))
-                z[tk][a][rr] = __builtin_fmaf(at.v[a * n + i], f, z[tk][a][rr]);
+              z[tk][a][rr] = at_step<M, kSparse>(at, a, i, f, z[tk][a][rr]);
             }
           }
       }
@@ -279,7 +277,7 @@ hipError_t launch_ms(const Geom& g, const MatAT& at, const void* V, const void* 
 template <int M>
 hipError_t launch_m(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                     const PosScale* w, float r_m, float r_y, float qmax, hipStream_t s, bool two) {
-  return fits_mask(at.v, g.m * g.n, CookToomMask<M>::at)
+  return sparse_at<M>(at.v)
              ? launch_ms<M, true>(g, at, V, U, y, w, r_m, r_y, qmax, s, two)
              : launch_ms<M, false>(g, at, V, U, y, w, r_m, r_y, qmax, s, two);
 }

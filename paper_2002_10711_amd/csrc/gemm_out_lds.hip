@@ -227,8 +227,7 @@ __global__ __launch_bounds__(576, 1) void gemm_out_lds_kernel(
         if constexpr (kMQ) f = quantize_f(f, r_m, qmax);
 #pragma unroll
         for (int a = 0; a < M; ++a) {
-          if (i == 0) z[e][a] = 0.0f;
-          if (at_nonzero<M, kSparse>(a, i)) z[e][a] = __builtin_fmaf(at.v[a * n + i], f, z[e][a]);
+          z[e][a] = at_step<M, kSparse>(at, a, i, f, z[e][a]);
         }
       }
       if (i == n - 1) {
@@ -408,7 +407,7 @@ hipError_t launch_gemm_out_lds(const Geom& g, const MatAT& at, const void* V, co
                                hipStream_t s) {
   if (!gemm_out_lds_supported(g)) return hipErrorInvalidValue;
   // 256 input channels per chunk, a ring of 6 chunks of V in LDS, 2 chunks of U in flight
-  return fits_mask(at.v, g.m * g.n, CookToomMask<2>::at)
+  return sparse_at<2>(at.v)
              ? go<2, 8, 4, true, 6, 2>(g, at, V, U, y, w_pos, r_m, r_y, qmax, s)
              : go<2, 8, 4, false, 6, 2>(g, at, V, U, y, w_pos, r_m, r_y, qmax, s);
 }

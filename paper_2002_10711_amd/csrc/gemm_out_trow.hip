@@ -249,8 +249,7 @@ __global__ __launch_bounds__(kHalf ? 512 : 256, kHalf ? 4 : 2) void gemm_out_tro
           }
 #pragma unroll
           for (int a = 0; a < M; ++a) {
-            if (i == 0) z[a][rr] = 0.0f;
-            if (at_nonzero<M, kSparse>(a, i)) z[a][rr] = __builtin_fmaf(at.v[a * n + i], f, z[a][rr]);
+            z[a][rr] = at_step<M, kSparse>(at, a, i, f, z[a][rr]);
           }
         }
         acc_cur = acc_nx;
@@ -398,7 +397,7 @@ hipError_t launch_gemm_out_trow(const Geom& g, const MatAT& at, const void* V, c
                                 hipStream_t s) {
   TrowPlan pl;
   if (!make_plan(g, &pl) || ((uintptr_t)y & 15) != 0) return hipErrorInvalidValue;
-  const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<6>::at);
+  const bool sparse = sparse_at<6>(at.v);
 #define WINO_TROW_GO(NCHV, HALF)                                                         \
   (sparse ? go<NCHV, true, HALF>(g, at, V, U, y, w_pos, r_m, r_y, qmax, pl, s)           \
           : go<NCHV, false, HALF>(g, at, V, U, y, w_pos, r_m, r_y, qmax, pl, s))

@@ -50,6 +50,28 @@ inline bool fits_mask(const float* mat, int count, uint64_t mask) {
   return true;
 }
 
+// First column of row a of A^T that the Cook-Toom pattern leaves nonzero (column 0 for the
+// first row, the first nonzero point's column for the others).
+template <int M>
+__host__ __device__ constexpr int at_lead(int a) {
+  for (int i = 0; i < M + 2; ++i)
+    if ((CookToomMask<M>::at >> (a * (M + 2) + i)) & 1ull) return i;
+  return 0;
+}
+
+// Host: A^T has the pattern's zeros AND a leading 1 in every row (x^a at the point x = 1, and
+// the row of ones: true of every point list that starts 0, 1, -1).  The kSparse forms of the
+// output transform rely on both: a chain's first term fma(1, x, +0) is x itself, so they
+// start the chain with x instead of issuing it (at most the sign of a zero differs, which
+// no result shows, see above).  Any other A^T takes the dense forms.
+template <int M>
+inline bool sparse_at(const float* at) {
+  if (!fits_mask(at, M * (M + 2), CookToomMask<M>::at)) return false;
+  for (int a = 0; a < M; ++a)
+    if (at[a * (M + 2) + at_lead<M>(a)] != 1.0f) return false;
+  return true;
+}
+
 #if defined(__HIPCC__)
 
 // The stage quantizer q = sat(rne(v * r)), product taken exactly and rounded once: the
@@ -90,6 +112,21 @@ __device__ __forceinline__ uint32_t insert_byte(uint32_t out, uint32_t bits) {
   constexpr uint32_t sel = e == 0 ? 0x03020104u : e == 1 ? 0x03020400u
                          : e == 2 ? 0x03040100u : 0x04020100u;
   return __builtin_amdgcn_perm(bits, out, sel);
+}
+
+// One step of a chain z = sum_i A^T[a][i] * f_i in ascending i: z after the term i.  kSparse:
+// skipped zeros and the unit leading entry (sparse_at); before the leading entry z is unused.
+template <int M, bool kSparse>
+__device__ __forceinline__ float at_step(const MatAT& at, int a, int i, float f, float z) {
+  constexpr int n = M + 2;
+  if constexpr (kSparse) {
+    if (i < at_lead<M>(a)) return 0.0f;
+    if (i == at_lead<M>(a)) return f;
+    if (!at_nonzero<M, true>(a, i)) return z;
+    return __builtin_fmaf(at.v[a * n + i], f, z);
+  } else {
+    return __builtin_fmaf(at.v[a * n + i], f, i == 0 ? 0.0f : z);
+  }
 }
 
 // V = B^T d B for one n x n patch in registers.
@@ -157,8 +194,7 @@ __device__ __forceinline__ void transform_result(const float (&Mt)[M + 2][M + 2]
     for (int j = 0; j < n; ++j) {
       float acc = 0.0f;
 #pragma unroll
-      for (int i = 0; i < n; ++i)
-        if (at_nonzero<M, kSparse>(a, i)) acc = __builtin_fmaf(at.v[a * n + i], Mt[i][j], acc);
+      for (int i = 0; i < n; ++i) acc = at_step<M, kSparse>(at, a, i, Mt[i][j], acc);
       z[a][j] = acc;
     }
 #pragma unroll
@@ -167,8 +203,7 @@ __device__ __forceinline__ void transform_result(const float (&Mt)[M + 2][M + 2]
     for (int b = 0; b < M; ++b) {
       float acc = 0.0f;
 #pragma unroll
-      for (int j = 0; j < n; ++j)
-        if (at_nonzero<M, kSparse>(b, j)) acc = __builtin_fmaf(z[a][j], at.v[b * n + j], acc);
+      for (int j = 0; j < n; ++j) acc = at_step<M, kSparse>(at, b, j, z[a][j], acc);
       Y[a][b] = acc;
     }
 }

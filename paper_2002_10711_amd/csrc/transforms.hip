@@ -504,7 +504,7 @@ hipError_t launch_output_quad(const Geom& g, const MatAT& at, const void* Mv, vo
                               float r_y, float qmax, hipStream_t s) {
   if (g.Kp / 64 > 65535) return hipErrorInvalidValue;
   dim3 grid(g.Tp / 16, g.Kp / 64);
-  const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool sparse = sparse_at<M>(at.v);
   const bool mq = I8 && r_m > 0.0f;
   const bool fast = I8 && !mq && sparse && g.Ho % M == 0 && g.Wo % M == 0 && g.K % 4 == 0;
   if (fast)
@@ -526,7 +526,7 @@ template <int M, bool I8>
 hipError_t launch_output_m(const Geom& g, const MatAT& at, const void* Mv, void* y, float r_m,
                            float r_y, float qmax, hipStream_t s, const PosScale* w_pos) {
   const unsigned nb = blocks_for((long long)g.T * g.Kp);
-  const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool sparse = sparse_at<M>(at.v);
   const bool mq = I8 && r_m > 0.0f;
   PosScale none;
   memset(&none, 0, sizeof none);

@@ -597,7 +597,7 @@ template <int M, typename YT>
 hipError_t output_my(const Geom& g, const MatAT& at, const void* Mi, void* y, const PosScale* w,
                      float r_m, float r_y, float qmax_m, float qmax_y, hipStream_t s) {
   dim3 grid(g.Tp / 4, g.Kp / 64);
-  const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool sparse = sparse_at<M>(at.v);
   PosScale one;
   for (int p = 0; p < 64; ++p) one.r[p] = 1.0f;
   const long long* Ml = (const long long*)Mi;
@@ -702,7 +702,7 @@ template <int M>
 hipError_t gemm_out_m(const Geom& g, const MatAT& at, const void* V, const void* U, void* y,
                       const PosScale* w, float r_m, float r_y, float qmax_m, float qmax_y,
                       hipStream_t s) {
-  const bool sparse = fits_mask(at.v, g.m * g.n, CookToomMask<M>::at);
+  const bool sparse = sparse_at<M>(at.v);
   if (g.x16)
     return sparse ? gemm_out_mys<M, int16_t, true>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s)
                   : gemm_out_mys<M, int16_t, false>(g, at, V, U, y, w, r_m, r_y, qmax_m, qmax_y, s);

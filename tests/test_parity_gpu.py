@@ -398,6 +398,32 @@ def test_large_grids_and_three_tile_input_stage(oracle, layer):
     _check_i8(case, run_gpu(case))
 
 
+NONUNIT = [
+    # Cook-Toom matrices from point lists that keep A^T's zero pattern but not its leading
+    # ones (first nonzero point 2 or 1/2 instead of 1): the kernels whose chains start with
+    # the term itself must not be taken; every sequence still has to give the oracle's codes
+    (Layer("nonunit_f2", 3, 40, 70, 12, 12, m=2, seed=230), (0, 2, -2)),
+    (Layer("nonunit_f4", 2, 64, 64, 16, 16, m=4, seed=231), (0, "1/2", "-1/2", 1, -1)),
+    (Layer("nonunit_f4_c256", 2, 256, 64, 8, 8, m=4, seed=232), (0, 2, -2, 1, -1)),
+    (Layer("nonunit_f6", 2, 64, 40, 16, 16, m=6, seed=233), (0, 2, -2, 1, -1, "1/2", "-1/2")),
+]
+
+
+@pytest.mark.parametrize("layer,points", NONUNIT, ids=lambda v: v.name if hasattr(v, "name") else "pts")
+def test_sparse_matrices_without_unit_leading_entries(oracle, layer, points):
+    from fractions import Fraction
+    X, g = workloads.make_inputs(layer)
+    BT, G, AT = oracle.cook_toom(layer.m, points=[Fraction(p) for p in points], dtype=np.float32)
+    n = layer.m + 2
+    assert AT[1, 1] != 1.0 and np.count_nonzero(AT) == np.count_nonzero(oracle.cook_toom(layer.m)[2])
+    case = dict(layer=layer, X=X, g=g, BT=BT, G=G, AT=AT)
+    sc = oracle.calibrate(X, g, BT, G, AT, pad=layer.pad)
+    case["scales"] = sc
+    case["xq"] = oracle.quantize_tensor(X, sc["s_x"]).astype(np.int8)
+    case["ref"] = oracle.winograd_q(case["xq"], g, BT, G, AT, sc, pad=layer.pad)
+    _check_i8(case, run_gpu(case), inexact_ok=True)
+
+
 TROW = [
     # F(6x6,3x3) GEMM + output kernel on whole rows of tiles (sequence "trow"): several
     # workgroups with a partly filled last one, output channels that do not fill a block of
