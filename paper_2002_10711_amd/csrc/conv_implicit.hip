@@ -63,7 +63,9 @@ __device__ __forceinline__ PixelAt pixel_at(const Tiling& tl, int p) {
 // (kLd: how the patch is gathered, see below; a template parameter so that every form gets
 // its own register allocation -- as a run-time switch the widest form cost the others a
 // wavefront per SIMD)
-template <int KW, int kLd>
+// kAhead: the pixel operands of the next tap are read from LDS before this tap's MFMAs (see
+// below); 34 registers more with KW = 2, i.e. three wavefronts per SIMD instead of four.
+template <int KW, int kLd, bool kAhead>
 __global__ __launch_bounds__(256) void conv_implicit_i8_kernel(RefGeom g, Tiling tl,
                                                                const int8_t* __restrict__ x,
                                                                const int8_t* __restrict__ wp,
@@ -253,17 +255,45 @@ __global__ __launch_bounds__(256) void conv_implicit_i8_kernel(RefGeom g, Tiling
     __syncthreads();
 #pragma unroll
     for (int tap = kEarly; tap < 9; ++tap) load_b(tap);
+    // kAhead: the pixel operands of tap t + 1 are read from LDS before the MFMAs of tap t are
+    // issued, and held there (left to itself the compiler reads two operands, waits for them,
+    // and multiplies: some twenty LDS round trips per chunk, which a workgroup that has its
+    // compute unit to itself or shares it with one other sits out; with four workgroups per
+    // compute unit the others fill the gaps and the registers this takes cost more: 128 -> 128
+    // at 16 x 16, batch 256: 20.4 -> 24.5 us with it, 256 -> 256 at 8 x 8: 20.1 -> 19.2).
+    // All four row blocks always: a block beyond PIX multiplies pixel 0 again and is dropped
+    // at the end, which costs less than branches around the MFMAs.
+    if constexpr (kAhead) {
+      v4i a[2][4];
+      auto read_a = [&](int tap, int buf) {
+        const int toff = ((tap / 3) * tl.PW + tap % 3) * kCS;
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) {
-      const int toff = ((tap / 3) * tl.PW + tap % 3) * kCS;
+        for (int mt = 0; mt < 4; ++mt) a[buf][mt] = *(const v4i*)(Xs + corner[mt] + toff);
+      };
+      read_a(0, 0);
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        // (all four row blocks always: a block beyond PIX multiplies pixel 0 again and is
-        // dropped at the end, which costs less than branches around the MFMAs)
-        const v4i a = *(const v4i*)(Xs + corner[mt] + toff);
+      for (int tap = 0; tap < 9; ++tap) {
+        if (tap + 1 < 9) read_a(tap + 1, (tap + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < KW; ++j)
-          acc[mt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[tap][j], acc[mt][j], 0, 0, 0);
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+          for (int j = 0; j < KW; ++j)
+            acc[mt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[tap & 1][mt], b[tap][j],
+                                                               acc[mt][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        const int toff = ((tap / 3) * tl.PW + tap % 3) * kCS;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const v4i a = *(const v4i*)(Xs + corner[mt] + toff);
+#pragma unroll
+          for (int j = 0; j < KW; ++j)
+            acc[mt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[tap][j], acc[mt][j], 0, 0, 0);
+        }
       }
     }
   }
@@ -345,9 +375,18 @@ hipError_t launch_conv_implicit(const RefGeom& g, const void* x, const void* wp,
   const int fast_st = ((uintptr_t)y & 3) == 0 && g.Wo % 4 == 0 && t.CB % 4 == 0;
   const bool two = g.Kp % 128 == 0;
   dim3 grid((unsigned)(t.nCB * t.nRB * t.nIG), (unsigned)(g.Kp / (two ? 128 : 64)));
+  // (operands read a tap ahead: 64 output channels per workgroup, or at most two workgroups
+  // per compute unit)
+  const bool ahead = !two || (long long)grid.x * grid.y <= 512;
   auto go = [&](auto kw, auto ld) {
-    conv_implicit_i8_kernel<decltype(kw)::value, decltype(ld)::value><<<grid, 256, lds, s>>>(
-        g, t, (const int8_t*)x, (const int8_t*)wp, (int8_t*)y, r_y, qmax, fast_st);
+    if (ahead)
+      conv_implicit_i8_kernel<decltype(kw)::value, decltype(ld)::value, true>
+          <<<grid, 256, lds, s>>>(g, t, (const int8_t*)x, (const int8_t*)wp, (int8_t*)y, r_y, qmax,
+                                  fast_st);
+    else
+      conv_implicit_i8_kernel<decltype(kw)::value, decltype(ld)::value, false>
+          <<<grid, 256, lds, s>>>(g, t, (const int8_t*)x, (const int8_t*)wp, (int8_t*)y, r_y, qmax,
+                                  fast_st);
   };
   auto with_ld = [&](auto kw) {
     switch (fast_ld) {

@@ -120,53 +120,29 @@ __global__ __launch_bounds__(256, kTwoWG ? 2 : 1) void gemm_out_col_kernel(Geom 
 
   // (one copy of the loop per setting of the Hadamard-stage quantizer: a test per
   // accumulator would cut the loop body into pieces the scheduler cannot overlap)
+  // Two things a lone wavefront per SIMD needs here.  A position's operands of V are all read
+  // from LDS right after the barrier, before the first MFMA (read step by step between the
+  // loads of U, each read's latency was waited for in full).  And the output work of a
+  // position (conversion, chains) is issued one position late, right after the next
+  // position's MFMAs, and pinned there: the wavefront then has it to do while the matrix
+  // cores work through that chain of dependent MFMAs (left to itself the compiler collects a
+  // whole column's output work behind the column's last MFMA).
   auto columns = [&](auto mq_tag) {
     constexpr bool kMQ = decltype(mq_tag)::value;
-#pragma unroll 1
-    for (int j = 0; j < n; ++j) {
-      // (columns past the last: the loads repeat valid addresses, their data is never used)
-      const int jn = j + 1 < n ? j + 1 : j, jnn = j + 2 < n ? j + 2 : n - 1;
+    // position (i, j) into the chains z; i is a compile-time value at every call
+    auto out_step = [&](int i, float wp, const v4i (&acc)[kTW]) {
 #pragma unroll
-      for (int i = 0; i < n; ++i) {
-        // Every wavefront has finished the previous position, whose buffer the next
-        // position's operands may now overwrite; this position's buffer is complete.
-        __syncthreads();
-        vstore((i + 1) % kPos, (i + 1) & 1);
-        constexpr int kAhead = 1 + kPos;
-        vfetch((i + kAhead) % n, (i + kAhead) / n == 0 ? j : (i + kAhead) / n == 1 ? jn : jnn,
-               (i + 1) % kPos);
-        const v4i* vops = (const v4i*)(vlds + (i & 1) * kBufPieces) + (r * 4 + grp);
-        v4i acc[kTW];
+      for (int tk = 0; tk < kTW; ++tk)
 #pragma unroll
-        for (int tk = 0; tk < kTW; ++tk) acc[tk] = v4i{0, 0, 0, 0};
+        for (int rr = 0; rr < 4; ++rr) {
+          float f = (float)acc[tk][rr] * wp;
+          if constexpr (kMQ) f = quantize_f(f, r_m, qmax);
 #pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) {
-          const int sj = i * NCH + ch, slot = sj % kDepth;
-          const v4i u = ru[slot];
-#pragma unroll
-          for (int tk = 0; tk < kTW; ++tk)
-            acc[tk] = __builtin_amdgcn_mfma_i32_16x16x64_i8(u, vops[(ch * kTW + tk) * 64], acc[tk],
-                                                            0, 0, 0);
-          // refill the slot once its operand has been issued; the compiler-level fence
-          // keeps later steps' loads behind this one, so that the ring, not the
-          // scheduler, decides what is in flight
-          if (sj + kDepth < SJ) fetch(sj + kDepth, j, slot);
-          else fetch(sj + kDepth - SJ, jn, slot);
-          asm volatile("" ::: "memory");
+          for (int a = 0; a < M; ++a) z[tk][a][rr] = at_step<M, kSparse>(at, a, i, f, z[tk][a][rr]);
         }
-        const float wp = w.r[i * n + j];               // 1 with per-tensor scales: exact
-#pragma unroll
-        for (int tk = 0; tk < kTW; ++tk)
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr) {
-            float f = (float)acc[tk][rr] * wp;
-            if constexpr (kMQ) f = quantize_f(f, r_m, qmax);
-#pragma unroll
-            for (int a = 0; a < M; ++a) {
-              z[tk][a][rr] = at_step<M, kSparse>(at, a, i, f, z[tk][a][rr]);
-            }
-          }
-      }
+    };
+    // column j, complete in z, into Y
+    auto y_step = [&](int j) {
 #pragma unroll
       for (int b = 0; b < M; ++b) {
         const float abj = at.v[b * n + j];
@@ -178,7 +154,77 @@ __global__ __launch_bounds__(256, kTwoWG ? 2 : 1) void gemm_out_col_kernel(Geom 
             for (int rr = 0; rr < 4; ++rr)
               Y[tk][a][b][rr] = __builtin_fmaf(z[tk][a][rr], abj, Y[tk][a][b][rr]);
       }
+    };
+    v4i prev[kTW];                                     // sums of the position before this one
+#pragma unroll
+    for (int tk = 0; tk < kTW; ++tk) prev[tk] = v4i{0, 0, 0, 0};
+#pragma unroll 1
+    for (int j = 0; j < n; ++j) {
+      // (columns past the last: the loads repeat valid addresses, their data is never used)
+      const int jn = j + 1 < n ? j + 1 : j, jnn = j + 2 < n ? j + 2 : n - 1;
+#pragma unroll
+      for (int i = 0; i < n; ++i) {
+        // Every wavefront has finished the previous position, whose buffer the next
+        // position's operands may now overwrite; this position's buffer is complete.
+        __syncthreads();
+        // factor of the position whose output work follows this position's MFMAs (1 with
+        // per-tensor scales: exact); a scalar load, requested here so that it is not waited
+        // for there
+        const float wp = i > 0 ? w.r[(i - 1) * n + j] : w.r[(n - 1) * n + (j > 0 ? j - 1 : 0)];
+        const v4i* vops = (const v4i*)(vlds + (i & 1) * kBufPieces) + (r * 4 + grp);
+        // (with two tile blocks per wavefront the 2 NCH operands up front would push the
+        // F(2x2,3x3) form past 256 registers, which costs it its second resident workgroup)
+        constexpr bool kHoist = kTW == 1;
+        v4i vr[kHoist ? NCH : 1][kTW];
+        if constexpr (kHoist) {
+#pragma unroll
+          for (int ch = 0; ch < NCH; ++ch)
+#pragma unroll
+            for (int tk = 0; tk < kTW; ++tk) vr[ch][tk] = vops[(ch * kTW + tk) * 64];
+        }
+        vstore((i + 1) % kPos, (i + 1) & 1);
+        constexpr int kAhead = 1 + kPos;
+        vfetch((i + kAhead) % n, (i + kAhead) / n == 0 ? j : (i + kAhead) / n == 1 ? jn : jnn,
+               (i + 1) % kPos);
+        v4i acc[kTW];
+#pragma unroll
+        for (int tk = 0; tk < kTW; ++tk) acc[tk] = v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+          const int sj = i * NCH + ch, slot = sj % kDepth;
+          const v4i u = ru[slot];
+#pragma unroll
+          for (int tk = 0; tk < kTW; ++tk)
+            acc[tk] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                u, kHoist ? vr[kHoist ? ch : 0][tk] : vops[(ch * kTW + tk) * 64], acc[tk], 0, 0, 0);
+          // refill the slot once its operand has been issued; the compiler-level fence
+          // keeps later steps' loads behind this one, so that the ring, not the
+          // scheduler, decides what is in flight
+          if (sj + kDepth < SJ) fetch(sj + kDepth, j, slot);
+          else fetch(sj + kDepth - SJ, jn, slot);
+          asm volatile("" ::: "memory");
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (i > 0) {
+          out_step(i - 1, wp, prev);
+        } else if (j > 0) {
+          out_step(n - 1, wp, prev);
+          y_step(j - 1);
+        }
+        // (the chains' values are claimed here, so that their instructions stay here)
+#pragma unroll
+        for (int tk = 0; tk < kTW; ++tk)
+#pragma unroll
+          for (int a = 0; a < M; ++a)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) asm volatile("" : "+v"(z[tk][a][rr]));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int tk = 0; tk < kTW; ++tk) prev[tk] = acc[tk];
+      }
     }
+    out_step(n - 1, w.r[n * n - 1], prev);
+    y_step(n - 1);
   };
   if (r_m > 0.0f) columns(std::true_type{});
   else columns(std::false_type{});
