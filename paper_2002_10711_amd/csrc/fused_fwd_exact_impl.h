@@ -646,10 +646,10 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
 
   v4i acc[P];
   // (the operands of V are read from LDS kAheadV steps ahead of their MFMAs, as in the
-  // four-wavefront kernel)
+  // four-wavefront kernel, and like there not for F(2x2,3x3))
   const uint32_t* lane_b = lds + r * 16 + grp * 4;
-  constexpr int kAheadV = 4;
-  v4i bvr[kAheadV];
+  constexpr int kAheadV = M == 2 ? 0 : 4;
+  v4i bvr[kAheadV ? kAheadV : 1];
 #pragma unroll
   for (int q = 0; q < kAheadV && q < Q; ++q)
     bvr[q] = *(const v4i*)(lane_b + (q % kRegions) * kRegionDw + (q / kRegions) * kVlPitch);
@@ -660,16 +660,22 @@ __global__ __launch_bounds__(512) void fused_fwd_exact_wide_kernel(
     if (q + kDepth < Q)
       bufU[q % kDepth] = *(const v4i*)(U + (uoff + (uint32_t)((q + kDepth) % kRegions) * 1024u +
                                             (uint32_t)((q + kDepth) / kRegions) * up));
-    const v4i bv = bvr[q % kAheadV];
-    if (q + kAheadV < Q)
-      bvr[q % kAheadV] = *(const v4i*)(lane_b + ((q + kAheadV) % kRegions) * kRegionDw +
-                                       ((q + kAheadV) / kRegions) * kVlPitch);
-    __builtin_amdgcn_sched_barrier(0);
+    v4i bv;
+    if constexpr (kAheadV > 0) {
+      bv = bvr[q % (kAheadV ? kAheadV : 1)];
+      if (q + kAheadV < Q)
+        bvr[q % (kAheadV ? kAheadV : 1)] =
+            *(const v4i*)(lane_b + ((q + kAheadV) % kRegions) * kRegionDw +
+                          ((q + kAheadV) / kRegions) * kVlPitch);
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
+      bv = *(const v4i*)(lane_b + cb * kRegionDw + p * kVlPitch);
+    }
     if (cb == 0)
       acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, v4i{0, 0, 0, 0}, 0, 0, 0);
     else
       acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(au, bv, acc[p], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (kAheadV > 0) __builtin_amdgcn_sched_barrier(0);
   }
 
   const int rs = r / kTWB, twl = r - rs * kTWB;

@@ -155,6 +155,11 @@ __global__ __launch_bounds__(256, kTwoWG ? 2 : 1) void gemm_out_col_kernel(Geom 
               Y[tk][a][b][rr] = __builtin_fmaf(z[tk][a][rr], abj, Y[tk][a][b][rr]);
       }
     };
+    // (Where it pays: F(4x4,3x3), and F(2x2,3x3) up to 256 channels.  F(6x6,3x3) and
+    // F(2x2,3x3) at 512 channels pass 256 registers with it and lose their second resident
+    // workgroup: up to 2.3 times slower on 512 -> 512 at 32 x 32 with F6.  They keep the
+    // plain order: operands read step by step, output work right behind the MFMAs.)
+    constexpr bool kLate = M == 4 || (M == 2 && NCH <= 4);
     v4i prev[kTW];                                     // sums of the position before this one
 #pragma unroll
     for (int tk = 0; tk < kTW; ++tk) prev[tk] = v4i{0, 0, 0, 0};
@@ -170,11 +175,13 @@ __global__ __launch_bounds__(256, kTwoWG ? 2 : 1) void gemm_out_col_kernel(Geom 
         // factor of the position whose output work follows this position's MFMAs (1 with
         // per-tensor scales: exact); a scalar load, requested here so that it is not waited
         // for there
-        const float wp = i > 0 ? w.r[(i - 1) * n + j] : w.r[(n - 1) * n + (j > 0 ? j - 1 : 0)];
+        float wp = 1.0f;
+        if constexpr (kLate)
+          wp = i > 0 ? w.r[(i - 1) * n + j] : w.r[(n - 1) * n + (j > 0 ? j - 1 : 0)];
         const v4i* vops = (const v4i*)(vlds + (i & 1) * kBufPieces) + (r * 4 + grp);
         // (with two tile blocks per wavefront the 2 NCH operands up front would push the
         // F(2x2,3x3) form past 256 registers, which costs it its second resident workgroup)
-        constexpr bool kHoist = kTW == 1;
+        constexpr bool kHoist = kLate && kTW == 1;
         v4i vr[kHoist ? NCH : 1][kTW];
         if constexpr (kHoist) {
 #pragma unroll
@@ -204,27 +211,34 @@ __global__ __launch_bounds__(256, kTwoWG ? 2 : 1) void gemm_out_col_kernel(Geom 
           else fetch(sj + kDepth - SJ, jn, slot);
           asm volatile("" ::: "memory");
         }
-        __builtin_amdgcn_sched_barrier(0);
-        if (i > 0) {
-          out_step(i - 1, wp, prev);
-        } else if (j > 0) {
-          out_step(n - 1, wp, prev);
-          y_step(j - 1);
+        if constexpr (kLate) {
+          __builtin_amdgcn_sched_barrier(0);
+          if (i > 0) {
+            out_step(i - 1, wp, prev);
+          } else if (j > 0) {
+            out_step(n - 1, wp, prev);
+            y_step(j - 1);
+          }
+          // (the chains' values are claimed here, so that their instructions stay here)
+#pragma unroll
+          for (int tk = 0; tk < kTW; ++tk)
+#pragma unroll
+            for (int a = 0; a < M; ++a)
+#pragma unroll
+              for (int rr = 0; rr < 4; ++rr) asm volatile("" : "+v"(z[tk][a][rr]));
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int tk = 0; tk < kTW; ++tk) prev[tk] = acc[tk];
+        } else {
+          out_step(i, w.r[i * n + j], acc);
         }
-        // (the chains' values are claimed here, so that their instructions stay here)
-#pragma unroll
-        for (int tk = 0; tk < kTW; ++tk)
-#pragma unroll
-          for (int a = 0; a < M; ++a)
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) asm volatile("" : "+v"(z[tk][a][rr]));
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int tk = 0; tk < kTW; ++tk) prev[tk] = acc[tk];
       }
+      if constexpr (!kLate) y_step(j);
     }
-    out_step(n - 1, w.r[n * n - 1], prev);
-    y_step(n - 1);
+    if constexpr (kLate) {
+      out_step(n - 1, w.r[n * n - 1], prev);
+      y_step(n - 1);
+    }
   };
   if (r_m > 0.0f) columns(std::true_type{});
   else columns(std::false_type{});
