@@ -59,6 +59,10 @@ def lib():
             raise RuntimeError(
                 "libwino.so is missing: build it with `python -m paper_2002_10711_amd.build` "
                 "(or __graft_entry__.build()); there is no fallback path")
+        # PyTorch first: it brings its own copy of the HIP runtime, and the device pointers the
+        # callers pass come from it -- loaded the other way round, the library would bind to a
+        # second runtime and its first kernel launch fails (hipErrorInvalidDeviceFunction)
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         L.wino_status_string.restype = ctypes.c_char_p
         for f in ("wino_weights_bytes", "wino_workspace_bytes",
